@@ -1,0 +1,137 @@
+"""Integer tile/halo maps of fused tile partitioning, written out from Sec. 4.2.
+
+TEST INFRASTRUCTURE ONLY (second, independent implementation of the maps the
+GPU library's planner produces; compared bit-exactly in the tests).
+
+Notation follows the paper: a tile (i, j) of an N x M grid (i = row, j = column)
+spans, at the input of layer l ("boundary" l), the inclusive rectangle
+(x1, y1)-(x2, y2); layer l has kernel K_l and stride S_l; a group (s, e) starts at
+the input of layer s and ends at the input of layer e.
+
+Four families per group, all clamped to the map after every step:
+  OWN  O_l : O_e is the equal split of the group's output map (tile index t of n parts
+             over a length W owns [floor(t*W/n), floor((t+1)*W/n) - 1]); O_{l-1} is O_l
+             scaled by the stride only (no kernel term).  A disjoint cover of every map.
+  FWD  F_l : F_e = O_e, then Eq. (1a-d) walked from e down to s.
+  BWD  B_l : B_s = O_s, then Eq. (2a-d) walked from s up to e.
+  HELD H_l : what the forward pass computes and keeps so that back-propagation finds the
+             activation signs / pool winners on B_l without communication inside the
+             group: H_e = O_e; H_l = Eq1(H_{l+1}) united with B_l at every interior
+             boundary that is materialised (a pool directly behind a convolution of the
+             same group is evaluated inside that convolution's epilogue, so the
+             boundary between them is not).
+For a 2x2/2 pool the exact dependence is used in both directions (Eq. (1) and (2) are
+stated for convolutions): back a' = 2a, b' = 2b + 1; forth a' = floor(a/2), b' = floor(b/2).
+"""
+
+CONV, MAXPOOL = 0, 1
+OWN, FWD, BWD, HELD = 0, 1, 2, 3
+
+
+def map_sizes(layers, in_h, in_w):
+    """[(H_l, W_l)] for boundaries 0..L."""
+    out = [(in_h, in_w)]
+    h, w = in_h, in_w
+    for ly in layers:
+        h = (h + 2 * ly.pad - ly.k) // ly.stride + 1
+        w = (w + 2 * ly.pad - ly.k) // ly.stride + 1
+        out.append((h, w))
+    return out
+
+
+def _clamp(r, hw):
+    h, w = hw
+    x1, y1, x2, y2 = r
+    return (max(x1, 0), max(y1, 0), min(x2, w - 1), min(y2, h - 1))
+
+
+def _union(a, b):
+    return (min(a[0], b[0]), min(a[1], b[1]), max(a[2], b[2]), max(a[3], b[3]))
+
+
+def equal_split(length, parts, t):
+    return (t * length) // parts, ((t + 1) * length) // parts - 1
+
+
+def eq1_back(r, ly):
+    """Region at the input of layer `ly` needed for region r of its output (Eq. 1a-d)."""
+    x1, y1, x2, y2 = r
+    if ly.kind == CONV:
+        S, h = ly.stride, ly.k // 2
+        return (x1 * S - h, y1 * S - h, x2 * S + h + (S - 1), y2 * S + h + (S - 1))
+    return (2 * x1, 2 * y1, 2 * x2 + 1, 2 * y2 + 1)
+
+
+def stride_back(r, ly):
+    """Eq. 1 with the kernel term dropped: the input pixels a tile's outputs sit on."""
+    x1, y1, x2, y2 = r
+    S = ly.stride
+    return (x1 * S, y1 * S, x2 * S + (S - 1), y2 * S + (S - 1))
+
+
+def _ceil_div(a, b):
+    return -((-a) // b)
+
+
+def eq2_forth(r, ly):
+    """Delta region at the output of layer `ly` needed for delta region r at its input (Eq. 2a-d)."""
+    x1, y1, x2, y2 = r
+    if ly.kind == CONV:
+        S, h = ly.stride, ly.k // 2
+        return (_ceil_div(x1 - h, S), _ceil_div(y1 - h, S), (x2 + h) // S, (y2 + h) // S)
+    return (x1 // 2, y1 // 2, x2 // 2, y2 // 2)
+
+
+def materialised(layers, s, l):
+    """False where boundary l lies between a convolution and the pool fused behind it."""
+    if l >= len(layers) or l <= s:
+        return True
+    return not (layers[l].kind == MAXPOOL and layers[l - 1].kind == CONV)
+
+
+def group_rects(layers, sizes, s, e, N, M, i, j):
+    """{kind: {l: (x1,y1,x2,y2)}} for tile (i,j) of group (s,e), boundaries s..e."""
+    He, We = sizes[e]
+    ya, yb = equal_split(He, N, i)
+    xa, xb = equal_split(We, M, j)
+    O = {e: (xa, ya, xb, yb)}
+    F = {e: O[e]}
+    for l in range(e, s, -1):
+        O[l - 1] = _clamp(stride_back(O[l], layers[l - 1]), sizes[l - 1])
+        F[l - 1] = _clamp(eq1_back(F[l], layers[l - 1]), sizes[l - 1])
+    B = {s: O[s]}
+    for l in range(s, e):
+        B[l + 1] = _clamp(eq2_forth(B[l], layers[l]), sizes[l + 1])
+    Hd = {e: O[e]}
+    for l in range(e - 1, s - 1, -1):
+        r = _clamp(eq1_back(Hd[l + 1], layers[l]), sizes[l])
+        if s < l < e and materialised(layers, s, l):
+            r = _union(r, B[l])
+        Hd[l] = r
+    return {OWN: O, FWD: F, BWD: B, HELD: Hd}
+
+
+def groups_from_ends(group_ends):
+    out, s = [], 0
+    for e in group_ends:
+        out.append((s, e))
+        s = e
+    return out
+
+
+def plan(layers, in_h, in_w, N, M, group_ends):
+    """rects[g][(i,j)][kind][l]."""
+    sizes = map_sizes(layers, in_h, in_w)
+    res = []
+    for (s, e) in groups_from_ends(group_ends):
+        res.append({(i, j): group_rects(layers, sizes, s, e, N, M, i, j)
+                    for i in range(N) for j in range(M)})
+    return sizes, res
+
+
+def area(r):
+    return max(0, r[2] - r[0] + 1) * max(0, r[3] - r[1] + 1)
+
+
+def contains(outer, inner):
+    return outer[0] <= inner[0] and outer[1] <= inner[1] and outer[2] >= inner[2] and outer[3] >= inner[3]

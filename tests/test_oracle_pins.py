@@ -1,0 +1,225 @@
+"""Pins of the CPU oracle against things other than itself: finite differences, adjoint
+identities, closed forms, library routines (numpy matmul, scipy correlate, torch CPU autograd)."""
+import numpy as np
+import pytest
+
+from ftp_synth.configs import Layer, conv, pool, CONV, MAXPOOL
+
+
+def _rand(rs, shape, dtype=np.float64):
+    return rs.standard_normal(shape).astype(dtype)
+
+
+def _net_small():
+    return [conv(3, 4), pool(4), conv(4, 5, 1), conv(5, 2)]
+
+
+def _weights(rs, layers, dtype=np.float64):
+    return [None if ly.kind != CONV else _rand(rs, (ly.cout, ly.cin, ly.k, ly.k), dtype) * 0.5 for ly in layers]
+
+
+def _loss(oracle, layers, x, ws, bs, g):
+    acts, _ = oracle.forward(layers, x, ws, bs)
+    return float(np.sum(acts[-1] * g))
+
+
+def test_finite_differences_fp64(oracle):
+    """Central differences of L = <G, f(X, W, b)> reproduce dX, dW and db (fp64 everywhere)."""
+    rs = np.random.RandomState(7)
+    layers = _net_small()
+    x = _rand(rs, (2, 3, 8, 8))
+    ws = _weights(rs, layers)
+    bs = [None if w is None else _rand(rs, (w.shape[0],)) * 0.1 for w in ws]
+    acts, args = oracle.forward(layers, x, ws, bs)
+    g = _rand(rs, acts[-1].shape)
+    # keep clear of the kinks: every pre-activation and every pool top-2 gap is well away from 0
+    for l, ly in enumerate(layers):
+        if ly.kind == CONV:
+            assert np.abs(acts[l + 1]).min() > 1e-5
+    dx, dws, dbs = oracle.backward(layers, acts, args, ws, g)
+    eps = 1e-6
+    checked = 0
+    for (arr, grad) in [(x, dx)] + [(ws[l], dws[l]) for l in range(len(layers)) if ws[l] is not None] \
+            + [(bs[l], dbs[l]) for l in range(len(layers)) if bs[l] is not None]:
+        flat, gflat = arr.reshape(-1), grad.reshape(-1)
+        for idx in rs.choice(flat.size, size=min(25, flat.size), replace=False):
+            old = flat[idx]
+            flat[idx] = old + eps
+            lp = _loss(oracle, layers, x, ws, bs, g)
+            flat[idx] = old - eps
+            lm = _loss(oracle, layers, x, ws, bs, g)
+            flat[idx] = old
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - gflat[idx]) <= 1e-6 * max(1.0, abs(fd)), (idx, fd, gflat[idx])
+            checked += 1
+    assert checked > 100
+
+
+def test_adjoint_identities_fp64(oracle):
+    """slope = 1, no pool: the layer is linear, so <G, A x> == <A^T G, x> and <dW, W> == <G, Y>."""
+    rs = np.random.RandomState(3)
+    for k in (1, 3):
+        ly = Layer(CONV, k, 1, k // 2, 3, 5, 1.0)
+        x = _rand(rs, (2, 3, 7, 9))
+        w = _rand(rs, (5, 3, k, k))
+        acts, args = oracle.forward([ly], x, [w], None)
+        g = _rand(rs, acts[-1].shape)
+        dx, dws, _ = oracle.backward([ly], acts, args, [w], g)
+        lhs = np.sum(g * acts[-1])
+        assert abs(lhs - np.sum(dx * x)) <= 1e-12 * abs(lhs)
+        assert abs(lhs - np.sum(dws[0] * w)) <= 1e-12 * abs(lhs)
+
+
+def test_all_ones_closed_form(oracle):
+    """All-ones input and 3x3 filters, pad 1: Z = 9 Cin inside, 6 Cin on edges, 4 Cin in corners."""
+    cin = 3
+    x = np.ones((1, cin, 6, 7))
+    w = np.ones((2, cin, 3, 3))
+    z = oracle.conv_fwd(x, w, None, 1, 1)
+    exp = np.full((6, 7), 9.0 * cin)
+    exp[0, :] = exp[-1, :] = 6.0 * cin
+    exp[:, 0] = exp[:, -1] = 6.0 * cin
+    exp[0, 0] = exp[0, -1] = exp[-1, 0] = exp[-1, -1] = 4.0 * cin
+    for co in range(2):
+        assert np.array_equal(z[0, co], exp)
+
+
+def test_conv1x1_is_matmul(oracle):
+    rs = np.random.RandomState(5)
+    x = _rand(rs, (2, 6, 5, 4))
+    w = _rand(rs, (3, 6, 1, 1))
+    z = oracle.conv_fwd(x, w, None, 1, 0)
+    W2 = w[:, :, 0, 0]
+    ref = np.einsum("oc,nchw->nohw", W2, x)
+    assert np.allclose(z, ref, rtol=1e-13, atol=1e-13)
+    g = _rand(rs, z.shape)
+    dx = oracle.conv_bwd_data(g, w, (5, 4), 1, 0)
+    assert np.allclose(dx, np.einsum("oc,nohw->nchw", W2, g), rtol=1e-13, atol=1e-13)
+    dw, db = oracle.conv_bwd_weight(x, g, 1, 1, 0)
+    assert np.allclose(dw[:, :, 0, 0], np.einsum("nohw,nchw->oc", g, x), rtol=1e-13, atol=1e-13)
+    assert np.allclose(db, g.sum(axis=(0, 2, 3)), rtol=1e-13, atol=1e-13)
+
+
+def test_conv3x3_is_scipy_correlate(oracle):
+    from scipy.signal import correlate2d, convolve2d
+    rs = np.random.RandomState(11)
+    x = _rand(rs, (1, 2, 9, 8))
+    w = _rand(rs, (3, 2, 3, 3))
+    z = oracle.conv_fwd(x, w, None, 1, 1)
+    for co in range(3):
+        ref = sum(correlate2d(x[0, ci], w[co, ci], mode="same") for ci in range(2))
+        assert np.allclose(z[0, co], ref, rtol=1e-13, atol=1e-13)
+    # delta back-propagation is the correlation with the 180-degree rotated filter = a true convolution
+    g = _rand(rs, z.shape)
+    dx = oracle.conv_bwd_data(g, w, (9, 8), 1, 1)
+    for ci in range(2):
+        ref = sum(convolve2d(g[0, co], w[co, ci], mode="same") for co in range(3))
+        assert np.allclose(dx[0, ci], ref, rtol=1e-13, atol=1e-13)
+        ref2 = sum(correlate2d(g[0, co], w[co, ci, ::-1, ::-1], mode="same") for co in range(3))
+        assert np.allclose(dx[0, ci], ref2, rtol=1e-13, atol=1e-13)
+
+
+def test_pool_and_leaky_pointwise(oracle):
+    rs = np.random.RandomState(2)
+    x = _rand(rs, (2, 3, 6, 8))
+    y, arg = oracle.pool_fwd(x)
+    ref = x.reshape(2, 3, 3, 2, 4, 2).transpose(0, 1, 2, 4, 3, 5).reshape(2, 3, 3, 4, 4)
+    assert np.array_equal(y, ref.max(axis=-1))
+    assert np.array_equal(arg, ref.argmax(axis=-1))       # numpy argmax = first maximum
+    g = _rand(rs, y.shape)
+    dx = oracle.pool_bwd(g, arg, (6, 8))
+    win = dx.reshape(2, 3, 3, 2, 4, 2).transpose(0, 1, 2, 4, 3, 5).reshape(2, 3, 3, 4, 4)
+    assert np.array_equal((win != 0).sum(axis=-1), np.ones_like(arg))
+    assert np.array_equal(win.sum(axis=-1), g)
+    # ties: the first maximum in window order wins
+    t = np.zeros((1, 1, 2, 2))
+    _, a = oracle.pool_fwd(t)
+    assert a[0, 0, 0, 0] == 0
+    t[0, 0, 0, 1] = t[0, 0, 1, 0] = 1.0
+    _, a = oracle.pool_fwd(t)
+    assert a[0, 0, 0, 0] == 1
+    z = np.array([-2.0, -0.0, 0.0, 3.0])
+    yv = oracle.leaky_fwd(z, 0.1)
+    assert np.allclose(yv, [-0.2, 0.0, 0.0, 3.0])
+    assert np.allclose(oracle.leaky_bwd(np.ones(4), yv, 0.1), [0.1, 0.1, 0.1, 1.0])
+
+
+def test_against_torch_cpu_autograd(oracle):
+    """Library pin: torch's CPU conv2d / leaky_relu / max_pool2d and its autograd, in fp64."""
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    rs = np.random.RandomState(13)
+    layers = [conv(3, 6), pool(6), conv(6, 8), conv(8, 4, 1), pool(4), conv(4, 5)]
+    x = _rand(rs, (2, 3, 16, 12))
+    ws = _weights(rs, layers)
+    bs = [None if w is None else _rand(rs, (w.shape[0],)) * 0.1 for w in ws]
+    acts, args = oracle.forward(layers, x, ws, bs)
+    g = _rand(rs, acts[-1].shape)
+    dx, dws, dbs, deltas = oracle.backward(layers, acts, args, ws, g, keep_deltas=True)
+
+    tx = torch.tensor(x, requires_grad=True)
+    tws = [None if w is None else torch.tensor(w, requires_grad=True) for w in ws]
+    tbs = [None if b is None else torch.tensor(b, requires_grad=True) for b in bs]
+    t = tx
+    tacts = [t]
+    for l, ly in enumerate(layers):
+        if ly.kind == CONV:
+            t = F.leaky_relu(F.conv2d(t, tws[l], tbs[l], stride=1, padding=ly.pad), ly.slope)
+        else:
+            t = F.max_pool2d(t, 2, 2)
+        t.retain_grad()
+        tacts.append(t)
+    (t * torch.tensor(g)).sum().backward()
+    for l in range(len(layers) + 1):
+        assert np.allclose(acts[l], tacts[l].detach().numpy(), rtol=1e-12, atol=1e-12), l
+    assert np.allclose(dx, tx.grad.numpy(), rtol=1e-11, atol=1e-12)
+    for l in range(1, len(layers) + 1):
+        assert np.allclose(deltas[l], tacts[l].grad.numpy(), rtol=1e-11, atol=1e-12), l
+    for l, ly in enumerate(layers):
+        if ly.kind == CONV:
+            assert np.allclose(dws[l], tws[l].grad.numpy(), rtol=1e-11, atol=1e-12), l
+            assert np.allclose(dbs[l], tbs[l].grad.numpy(), rtol=1e-11, atol=1e-12), l
+
+
+def test_fp32_mode_rounds_fp64_result_once(oracle):
+    """fp32 tensors + fp64 accumulators: each op equals the fp64 op on the same values, rounded once."""
+    rs = np.random.RandomState(17)
+    x = _rand(rs, (2, 3, 9, 10), np.float32)
+    w = (_rand(rs, (4, 3, 3, 3), np.float32) * 0.3).astype(np.float32)
+    b = _rand(rs, (4,), np.float32)
+    z32 = oracle.conv_fwd(x, w, b, 1, 1)
+    z64 = oracle.conv_fwd(x.astype(np.float64), w.astype(np.float64), b.astype(np.float64), 1, 1)
+    assert z32.dtype == np.float32 and np.array_equal(z32, z64.astype(np.float32))
+    g = _rand(rs, z32.shape, np.float32)
+    d32 = oracle.conv_bwd_data(g, w, (9, 10), 1, 1)
+    d64 = oracle.conv_bwd_data(g.astype(np.float64), w.astype(np.float64), (9, 10), 1, 1)
+    assert np.array_equal(d32, d64.astype(np.float32))
+    w32, b32 = oracle.conv_bwd_weight(x, g, 3, 1, 1)
+    w64, b64 = oracle.conv_bwd_weight(x.astype(np.float64), g.astype(np.float64), 3, 1, 1)
+    assert np.array_equal(w32, w64.astype(np.float32)) and np.array_equal(b32, b64.astype(np.float32))
+
+
+def test_batch_sum_and_tile_partial_sums(oracle):
+    """dW of a batch = sum of per-image dW (one update per batch); the filter-gradient partial sums of
+    a disjoint cover of the output pixels add up to the whole gradient (Sec. 4.1)."""
+    rs = np.random.RandomState(19)
+    x = _rand(rs, (3, 2, 8, 10))
+    g = _rand(rs, (3, 4, 8, 10))
+    full, fullb = oracle.conv_bwd_weight(x, g, 3, 1, 1)
+    per = sum(oracle.conv_bwd_weight(x[n:n + 1].copy(), g[n:n + 1].copy(), 3, 1, 1)[0] for n in range(3))
+    assert np.allclose(full, per, rtol=1e-12, atol=1e-12)
+    parts, partb = 0.0, 0.0
+    for (y0, y1) in ((0, 2), (3, 7)):
+        for (x0, x1) in ((0, 3), (4, 4), (5, 9)):
+            dw, db = oracle.conv_bwd_weight(x, g, 3, 1, 1, rect=(x0, y0, x1, y1))
+            parts, partb = parts + dw, partb + db
+    assert np.allclose(full, parts, rtol=1e-12, atol=1e-12)
+    assert np.allclose(fullb, partb, rtol=1e-12, atol=1e-12)
+
+
+def test_bf16_rounding(oracle):
+    from ftp_synth import rng
+    a = np.array([1.0, 1.00390625, 1.01171875, 3.14159, -2.71828, 1e-30, 65504.0], dtype=np.float32)
+    r = oracle.round_bf16(a.copy())
+    assert np.array_equal(r, rng.to_bf16_rne(a))
+    assert r[1] == 1.0 and r[2] == np.float32(1.015625)     # ties go to the even mantissa
