@@ -1,0 +1,129 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-tile forward + backward + gradient-sum pass on one MI355X.
+
+One step = ftp_forward, ftp_backward, ftp_reduce_wgrad over one batch of synthetic input that is
+already resident in HBM.  Prints ONE JSON line: whole-job images/s, the roofline of the dominant
+kernel (timed live with HIP events inside the timed region) and the CPU oracle timed on the host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+PEAK_ALU_TFLOPS = 157.3          # fp32 vector FMA, 256 CUs x 4 SIMD x 64 lanes x 2 x 2.4 GHz
+
+
+def pick_config(name, group_size):
+    from ftp_synth import configs as C
+    if name == "cfg5":
+        return C.config5(group_size)
+    return C.ALL[name]()
+
+
+def cpu_baseline(cfg, budget_images):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    from ftp_synth import configs as C
+    from oracle import reference as O
+    n = min(cfg.batch, budget_images)
+    x, ws, bs, dy = C.make_tensors(cfg, images=list(range(n)))
+    bf = cfg.dtype == "bf16"
+    t0 = time.perf_counter()
+    acts, args = O.forward(cfg.layers, x, ws, None, bf16_store=bf)
+    O.backward(cfg.layers, acts, args, ws, dy, bf16_store=bf, want_db=False)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "images/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": "%d of %d images of the same workload, forward + backward, %.1f s" % (n, cfg.batch, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg4", choices=["tiny", "cfg2_perblock", "cfg2_fused", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--group-size", type=int, default=4, help="layers per group (cfg5 sweep)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-images", type=int, default=0, help="images for the oracle timing (0 = automatic)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from ftp_synth import configs as C
+    import paper_2409_09083_amd as F
+    from paper_2409_09083_amd.harness import Session
+
+    cfg = pick_config(args.config, args.group_size)
+    x, ws, bs, dy = C.make_tensors(cfg)
+    s = Session(cfg.layers, cfg.batch, cfg.in_c, cfg.in_h, cfg.in_w, cfg.grid, cfg.group_ends, cfg.dtype)
+    s.load(x=x, weights=ws, dy=dy)
+    del x, dy
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        s.step()
+    torch.cuda.synchronize()
+    F.ftp_profile(s.plan, True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        s.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    F.ftp_profile(s.plan, False)
+    recs = F.ftp_profile_read(s.plan)
+
+    ms_per_step = dt * 1e3 / args.steps
+    images_per_s = cfg.batch * args.steps / dt
+
+    # roofline of the dominant kernel (largest share of the timed region)
+    dom = max(recs, key=lambda r: r["total_ms"])
+    avg_ms = dom["total_ms"] / dom["launches"]
+    ai = dom["flops_per_launch"] / max(dom["bytes_per_launch"], 1.0)
+    ly = cfg.layers[dom["layer"]] if dom["layer"] >= 0 else None
+    ridge = PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if ly is not None and ly.kind == C.CONV and ai >= ridge:
+        peak = PEAK_MFMA_TFLOPS[cfg.dtype]
+        roof = {"bound": "mfma", "achieved": dom["flops_per_launch"] / (avg_ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["bytes_per_launch"] / (avg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = "%s layer %d" % (dom["pass"], dom["layer"])
+    roof["avg_launch_ms"] = avg_ms
+    roof["share_of_step"] = dom["total_ms"] / (dt * 1e3)
+
+    phases = {}
+    for r in recs:
+        phases[r["pass"]] = phases.get(r["pass"], 0.0) + r["total_ms"] / args.steps
+    work = s.work
+    useful_flops = 2.0 * work["useful_macs"]
+    out = {
+        "metric": "train images/sec (fwd+bwd, fused-tile early layers)",
+        "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.batch, "input": [cfg.in_c, cfg.in_h, cfg.in_w],
+                   "primitive_layers": cfg.n_layers, "grid": list(cfg.grid), "group_ends": list(cfg.group_ends)},
+        "roofline": roof,
+        "useful_tflops": useful_flops / (ms_per_step * 1e-3) / 1e12,
+        "executed_over_useful_macs": work["executed_macs"] / work["useful_macs"],
+        "halo_bytes_per_step": [work["halo_bytes_fwd"], work["halo_bytes_bwd"]],
+        "phases_ms_per_step": phases,
+    }
+    if not args.no_cpu_baseline:
+        n_img = args.cpu_images or (1 if cfg.name.startswith(("cfg4", "cfg5")) else cfg.batch)
+        out["cpu_baseline"] = cpu_baseline(cfg, n_img)
+    s.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

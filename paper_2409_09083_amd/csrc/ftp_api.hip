@@ -1,0 +1,364 @@
+// C ABI of libftp: plan queries and the three device passes (forward, backward, gradient sum).
+#include "ftp.h"
+#include "ftp_plan.h"
+#include "ftp_launch.h"
+
+#include <cstring>
+
+using namespace ftp;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+struct UserBufs {
+    const void* x = nullptr; void* y = nullptr; const void* dy = nullptr; void* dx = nullptr; void* ws = nullptr;
+};
+
+View make_view(const Plan& p, const BufRef& b, int group, int boundary, const UserBufs& ub)
+{
+    View v;
+    std::memset(&v, 0, sizeof(v));
+    switch (b.kind) {
+        case BUF_X: v.p = const_cast<void*>(ub.x); break;
+        case BUF_Y: v.p = ub.y; break;
+        case BUF_DY: v.p = const_cast<void*>(ub.dy); break;
+        case BUF_DX: v.p = ub.dx; break;
+        case BUF_WS: v.p = (char*)ub.ws + b.offset; break;
+        default: v.p = nullptr; break;
+    }
+    v.pitch = b.slot_w;
+    v.cs = (long long)b.slot_w * b.slot_h;
+    v.ns = v.cs * b.channels;
+    if (b.per_stack) {
+        v.ss = v.ns * p.batch;
+        const GroupRects& g = p.groups[group];
+        for (int t = 0; t < p.M; ++t) v.x0[t] = g.at(b.rect_kind, boundary, 0, t).a;
+        for (int t = 0; t < p.N; ++t) v.y0[t] = g.at(b.rect_kind, boundary, 1, t).a;
+    }
+    return v;
+}
+
+RectTab make_rect(const Plan& p, int group, int kind, int boundary)
+{
+    RectTab r;
+    std::memset(&r, 0, sizeof(r));
+    const GroupRects& g = p.groups[group];
+    for (int t = 0; t < p.M; ++t) { r.x0[t] = g.at(kind, boundary, 0, t).a; r.x1[t] = g.at(kind, boundary, 0, t).b; }
+    for (int t = 0; t < p.N; ++t) { r.y0[t] = g.at(kind, boundary, 1, t).a; r.y1[t] = g.at(kind, boundary, 1, t).b; }
+    return r;
+}
+
+ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void* const* weights, const void* const* biases)
+{
+    ConvArgs a;
+    const ftp_layer& ly = p.layers[u.layer];
+    a.in = make_view(p, u.in_act, u.group, u.bi, ub);
+    a.out = make_view(p, u.out_act, u.group, u.bo, ub);
+    a.arg = make_view(p, u.out_arg, u.group, u.bo, ub);
+    a.din = make_view(p, u.in_delta, u.group, u.bo, ub);
+    a.dout = make_view(p, u.out_delta, u.group, u.bi, ub);
+    a.w = weights[u.layer];
+    a.bias = (biases && ly.has_bias) ? biases[u.layer] : nullptr;
+    a.n_params = (long long)p.n_params; a.w_off = (long long)u.param_offset; a.b_off = (long long)u.bias_offset;
+    a.has_bias = ly.has_bias;
+    a.K = ly.k; a.Cin = ly.cin; a.Cout = ly.cout;
+    a.Hc = p.H[u.layer]; a.Wc = p.W[u.layer];
+    a.pooled = u.pooled ? 1 : 0;
+    a.slope = ly.leaky_slope;
+    a.N = p.N; a.M = p.M; a.batch = p.batch;
+    a.bf16 = p.dtype == FTP_BF16;
+    return a;
+}
+
+PoolArgs pool_args(const Plan& p, const Unit& u, const UserBufs& ub)
+{
+    PoolArgs a;
+    a.in = make_view(p, u.in_act, u.group, u.bi, ub);
+    a.out = make_view(p, u.out_act, u.group, u.bo, ub);
+    a.arg = make_view(p, u.out_arg, u.group, u.bo, ub);
+    a.din = make_view(p, u.in_delta, u.group, u.bo, ub);
+    a.dout = make_view(p, u.out_delta, u.group, u.bi, ub);
+    a.C = p.C[u.bi]; a.N = p.N; a.M = p.M; a.batch = p.batch;
+    a.bf16 = p.dtype == FTP_BF16;
+    return a;
+}
+
+template <class Fn>
+int timed(const ftp_plan_s* plan, int pass, int layer, hipStream_t s, Fn&& launch);
+
+int check_hip()
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { g_last_hip = (int)e; return FTP_EHIP; }
+    return FTP_OK;
+}
+
+// Runs one kernel launch; while profiling is on, brackets it with two HIP events on the same stream.
+template <class Fn>
+int timed(const ftp_plan_s* plan, int pass, int layer, hipStream_t s, Fn&& launch)
+{
+    Profiler& pr = plan->prof;
+    if (!pr.on) { launch(); return check_hip(); }
+    hipEvent_t a = (hipEvent_t)pr.get(), b = (hipEvent_t)pr.get();
+    if (!a || !b) { g_last_hip = (int)hipGetLastError(); return FTP_EHIP; }
+    (void)hipEventRecord(a, s);
+    launch();
+    (void)hipEventRecord(b, s);
+    pr.pending.push_back(Profiler::Rec{pass, layer, a, b});
+    return check_hip();
+}
+
+int check_weights(const Plan& p, const void* const* weights, const void* const* biases)
+{
+    if (!weights) return FTP_EINVAL;
+    for (int l = 0; l < p.n_layers; ++l) {
+        if (p.layers[l].kind != FTP_CONV) continue;
+        if (!weights[l]) return FTP_EINVAL;
+        if (p.layers[l].has_bias && biases && !biases[l]) return FTP_EINVAL;
+    }
+    return FTP_OK;
+}
+
+bool any_bias(const Plan& p)
+{
+    for (const ftp_layer& ly : p.layers) if (ly.kind == FTP_CONV && ly.has_bias) return true;
+    return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ftp_plan(const ftp_layer* layers, int32_t n_layers, int32_t batch, int32_t in_c, int32_t in_h, int32_t in_w,
+             int32_t grid_rows, int32_t grid_cols, const int32_t* group_ends, int32_t n_groups,
+             ftp_dtype dtype, ftp_plan_t** out_plan)
+{
+    return build_plan(layers, n_layers, batch, in_c, in_h, in_w, grid_rows, grid_cols, group_ends, n_groups, dtype, out_plan);
+}
+
+void ftp_plan_destroy(ftp_plan_t* plan) { delete plan; }
+
+int ftp_plan_rect(const ftp_plan_t* plan, int32_t group, int32_t boundary, int32_t ti, int32_t tj,
+                  ftp_rect_kind kind, int32_t out[4])
+{
+    if (!plan || !out) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    if (group < 0 || group >= (int)p.groups.size() || ti < 0 || ti >= p.N || tj < 0 || tj >= p.M) return FTP_EINVAL;
+    if ((int)kind < 0 || (int)kind > FTP_RECT_HELD) return FTP_EINVAL;
+    const GroupRects& g = p.groups[group];
+    if (boundary < g.s || boundary > g.e) return FTP_EINVAL;
+    const Seg sx = g.at(kind, boundary, 0, tj), sy = g.at(kind, boundary, 1, ti);
+    out[0] = sx.a; out[1] = sy.a; out[2] = sx.b; out[3] = sy.b;
+    return FTP_OK;
+}
+
+int ftp_plan_map_shape(const ftp_plan_t* plan, int32_t boundary, int32_t out_chw[3])
+{
+    if (!plan || !out_chw) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    if (boundary < 0 || boundary > p.n_layers) return FTP_EINVAL;
+    out_chw[0] = p.C[boundary]; out_chw[1] = p.H[boundary]; out_chw[2] = p.W[boundary];
+    return FTP_OK;
+}
+
+int ftp_plan_sizes(const ftp_plan_t* plan, size_t* workspace_bytes, size_t* wgrad_partial_bytes, size_t* n_params,
+                   size_t per_stack_split[4])
+{
+    if (!plan) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    if (workspace_bytes) *workspace_bytes = p.workspace_bytes;
+    if (wgrad_partial_bytes) *wgrad_partial_bytes = (size_t)p.N * p.M * p.n_params * sizeof(float);
+    if (n_params) *n_params = p.n_params;
+    if (per_stack_split) for (int i = 0; i < 4; ++i) per_stack_split[i] = p.split[i];
+    return FTP_OK;
+}
+
+int ftp_plan_work(const ftp_plan_t* plan, double* useful_macs, double* executed_macs, double halo_bytes[2])
+{
+    if (!plan) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    if (useful_macs) *useful_macs = p.useful_macs;
+    if (executed_macs) *executed_macs = p.executed_macs;
+    if (halo_bytes) { halo_bytes[0] = p.halo_bytes[0]; halo_bytes[1] = p.halo_bytes[1]; }
+    return FTP_OK;
+}
+
+int ftp_plan_buffer(const ftp_plan_t* plan, int32_t boundary, ftp_buf_kind which, int64_t out[8])
+{
+    if (!plan || !out) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    if (boundary < 0 || boundary > p.n_layers) return FTP_EINVAL;
+    const BufRef* b = nullptr;
+    switch (which) {
+        case FTP_BUF_ACT: b = &p.act[boundary]; break;
+        case FTP_BUF_ARG: b = &p.arg[boundary]; break;
+        case FTP_BUF_DELTA: b = &p.delta[boundary]; break;
+        default: return FTP_EINVAL;
+    }
+    out[0] = b->kind; out[1] = (int64_t)b->offset; out[2] = b->per_stack ? 1 : 0;
+    out[3] = b->slot_w; out[4] = b->slot_h; out[5] = b->channels; out[6] = b->rect_kind; out[7] = p.home_group[boundary];
+    return FTP_OK;
+}
+
+int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weights, const void* const* biases,
+                void* workspace, void* y, void* stream)
+{
+    if (!plan || !x || !workspace || !y) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    int rc = check_weights(p, weights, biases);
+    if (rc != FTP_OK) return rc;
+    if (any_bias(p) && !biases) return FTP_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    UserBufs ub; ub.x = x; ub.y = y; ub.ws = workspace;
+    for (const Unit& u : p.units) {
+        if (u.kind == UNIT_CONV) {
+            ConvArgs a = conv_args(p, u, ub, weights, biases);
+            a.rect = make_rect(p, u.group, FTP_RECT_HELD, u.bo);
+            rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { direct_conv_fwd(a, s); });
+        } else {
+            PoolArgs a = pool_args(p, u, ub);
+            a.rect = make_rect(p, u.group, FTP_RECT_HELD, u.bo);
+            rc = timed(plan, FTP_PASS_POOL_FWD, u.layer, s, [&] { pool_fwd(a, s); });
+        }
+        if (rc != FTP_OK) return rc;
+    }
+    return FTP_OK;
+}
+
+int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const void* y, const void* const* weights,
+                 void* workspace, void* dx, float* wgrad_partials, void* stream)
+{
+    if (!plan || !dy || !x || !y || !workspace || !dx || !wgrad_partials) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    int rc = check_weights(p, weights, nullptr);
+    if (rc != FTP_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    UserBufs ub; ub.x = x; ub.y = const_cast<void*>(y); ub.dy = dy; ub.dx = dx; ub.ws = workspace;
+    for (int i = (int)p.units.size() - 1; i >= 0; --i) {
+        const Unit& u = p.units[i];
+        if (u.kind == UNIT_CONV) {
+            ConvArgs a = conv_args(p, u, ub, weights, nullptr);
+            a.partial = wgrad_partials;
+            a.rect = make_rect(p, u.group, FTP_RECT_OWN, u.layer + 1);
+            rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { direct_wgrad(a, s); });
+            if (rc != FTP_OK) return rc;
+            a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
+            rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { direct_conv_bwd_data(a, s); });
+        } else {
+            PoolArgs a = pool_args(p, u, ub);
+            a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
+            rc = timed(plan, FTP_PASS_POOL_BWD, u.layer, s, [&] { pool_bwd(a, s); });
+        }
+        if (rc != FTP_OK) return rc;
+    }
+    return FTP_OK;
+}
+
+int ftp_reduce_wgrad(const ftp_plan_t* plan, const float* wgrad_partials, float* wgrad, void* stream)
+{
+    if (!plan || !wgrad_partials || !wgrad) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    if (p.n_params == 0) return FTP_OK;
+    hipStream_t s = (hipStream_t)stream;
+    return timed(plan, FTP_PASS_REDUCE, -1, s, [&] { reduce_wgrad(wgrad_partials, wgrad, (long long)p.n_params, p.N * p.M, s); });
+}
+
+int ftp_profile(ftp_plan_t* plan, int32_t enable)
+{
+    if (!plan) return FTP_EINVAL;
+    Profiler& pr = plan->prof;
+    if (enable) { pr.recycle(); pr.agg.clear(); }
+    pr.on = enable != 0;
+    return FTP_OK;
+}
+
+int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, int32_t* count)
+{
+    if (!plan || !count || (capacity > 0 && !out)) return FTP_EINVAL;
+    Profiler& pr = plan->prof;
+    const Plan& p = plan->p;
+    for (const Profiler::Rec& r : pr.pending) {
+        if (hipEventSynchronize((hipEvent_t)r.b) != hipSuccess) { g_last_hip = (int)hipGetLastError(); return FTP_EHIP; }
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, (hipEvent_t)r.a, (hipEvent_t)r.b) != hipSuccess) { g_last_hip = (int)hipGetLastError(); return FTP_EHIP; }
+        Profiler::Agg* hit = nullptr;
+        for (Profiler::Agg& g : pr.agg) if (g.pass == r.pass && g.layer == r.layer) { hit = &g; break; }
+        if (!hit) { pr.agg.push_back(Profiler::Agg{r.pass, r.layer, 0, 0.0}); hit = &pr.agg.back(); }
+        hit->launches += 1; hit->ms += ms;
+    }
+    pr.recycle();
+    *count = (int32_t)pr.agg.size();
+    const double es = (double)p.esize, B = p.batch, stacks = (double)p.N * p.M;
+    for (int i = 0; i < (int)pr.agg.size() && i < capacity; ++i) {
+        const Profiler::Agg& g = pr.agg[i];
+        ftp_kernel_time t;
+        t.pass = g.pass; t.layer = g.layer; t.launches = g.launches; t.reserved = 0; t.total_ms = g.ms;
+        t.flops_per_launch = 0; t.bytes_per_launch = 0;
+        if (g.pass == FTP_PASS_REDUCE) {
+            t.bytes_per_launch = (stacks + 1.0) * (double)p.n_params * 4.0;
+            t.flops_per_launch = (stacks - 1.0) * (double)p.n_params;
+        } else {
+            const ftp_layer& ly = p.layers[g.layer];
+            const Unit* u = nullptr;
+            for (const Unit& q : p.units) if (q.layer == g.layer) { u = &q; break; }
+            const double in_el = B * p.C[u->bi] * p.H[u->bi] * p.W[u->bi];
+            const double out_el = B * p.C[u->bo] * p.H[u->bo] * p.W[u->bo];
+            const double has_arg = (u->pooled || u->kind == UNIT_POOL) ? 1.0 : 0.0;
+            if (u->kind == UNIT_CONV) {
+                const double wel = (double)ly.cout * ly.cin * ly.k * ly.k;
+                t.flops_per_launch = 2.0 * wel * B * p.H[g.layer] * p.W[g.layer];
+                if (g.pass == FTP_PASS_CONV_FWD) t.bytes_per_launch = (in_el + out_el + wel) * es + out_el * has_arg;
+                else if (g.pass == FTP_PASS_CONV_BWD_DATA) t.bytes_per_launch = (in_el + 2.0 * out_el + wel) * es + out_el * has_arg;
+                else t.bytes_per_launch = (in_el + 2.0 * out_el) * es + out_el * has_arg + stacks * wel * 4.0;
+            } else {
+                t.bytes_per_launch = (in_el + out_el) * es + out_el;
+            }
+        }
+        out[i] = t;
+    }
+    return FTP_OK;
+}
+
+const char* ftp_strerror(int code)
+{
+    switch (code) {
+        case FTP_OK: return "ok";
+        case FTP_EINVAL: return "invalid argument";
+        case FTP_EUNSUPPORTED: return "unsupported layer (conv needs stride 1, K in {1,3}, pad K/2, slope >= 0; pool needs 2x2 stride 2)";
+        case FTP_EGRID: return "tile grid does not fit the maps (empty tile, odd map before a pool, or more than 16 tiles per side)";
+        case FTP_EGROUPS: return "group ends must be strictly increasing and end at the number of layers";
+        case FTP_ENOMEM: return "host allocation failed";
+        case FTP_EHIP: return "HIP call failed";
+        case FTP_ECHANNELS: return "channel counts of consecutive layers do not match";
+        default: return "unknown error";
+    }
+}
+
+int ftp_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"
+
+namespace ftp {
+
+Profiler::event_t Profiler::get()
+{
+    if (!free_list.empty()) { event_t e = free_list.back(); free_list.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void Profiler::recycle()
+{
+    for (const Rec& r : pending) { free_list.push_back(r.a); free_list.push_back(r.b); }
+    pending.clear();
+}
+
+Profiler::~Profiler()
+{
+    recycle();
+    for (event_t e : free_list) (void)hipEventDestroy((hipEvent_t)e);
+}
+
+}  // namespace ftp

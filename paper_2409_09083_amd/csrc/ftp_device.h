@@ -1,0 +1,54 @@
+// Device-side addressing shared by the kernels of libftp (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ftp {
+
+constexpr int kTabGrid = 16;
+
+// Where the map of one boundary lives and how a stack addresses it.  A whole (group-boundary) map
+// has stack stride 0 and origin (0,0); a per-stack slot starts at the stack's own rectangle.
+struct View {
+    void* p;
+    long long ss, ns, cs;         // element strides: stack, image, channel
+    int pitch;                    // elements per row
+    int x0[kTabGrid], y0[kTabGrid];   // map coordinate of the slot origin, per tile column / row
+};
+
+// Rectangle each stack works on: x interval per tile column, y interval per tile row (inclusive).
+struct RectTab {
+    int x0[kTabGrid], x1[kTabGrid], y0[kTabGrid], y1[kTabGrid];
+};
+
+typedef uint16_t bf16_t;          // raw bfloat16 bits
+
+__device__ __forceinline__ float ld(const float* p) { return *p; }
+__device__ __forceinline__ float ld(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
+__device__ __forceinline__ void st(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st(bf16_t* p, float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);   // nearest, ties to even
+    *p = (bf16_t)(u >> 16);
+}
+
+// Value a map element holds after being stored with element type T (identity for fp32).
+__device__ __forceinline__ float stored(float v, const float*) { return v; }
+__device__ __forceinline__ float stored(float v, const bf16_t*)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);
+    return __uint_as_float(u & 0xFFFF0000u);
+}
+
+template <typename T>
+__device__ __forceinline__ T* at(const View& v, int stack, int ti, int tj, int n, int c, int y, int x)
+{
+    return (T*)v.p + (long long)stack * v.ss + (long long)n * v.ns + (long long)c * v.cs +
+           (long long)(y - v.y0[ti]) * v.pitch + (x - v.x0[tj]);
+}
+
+__device__ __forceinline__ float leaky(float z, float slope) { return z > 0.0f ? z : slope * z; }
+
+}  // namespace ftp

@@ -1,0 +1,311 @@
+// Direct (non-matrix-core) kernels of libftp for gfx950: the generic path for every layer shape,
+// and the path of choice for thin layers (3 input channels) and lone pools.
+// One workgroup serves one (stack, image); stacks only read the rectangles the plan entitles them to.
+#include "ftp_device.h"
+#include "ftp_launch.h"
+
+namespace ftp {
+
+// ---- delta at the convolution output ---------------------------------------------------------------
+// dZ(q) = delta * leaky'(Y); with a pool behind the convolution the delta sits at pooled resolution
+// and reaches only the window's recorded winner (Sec. 4.1, back-propagation of the delta).
+template <typename T, bool POOL>
+__device__ __forceinline__ float delta_z(const View& din, const View& yv, const View& arg, int stack, int ti, int tj,
+                                         int n, int co, int qy, int qx, float slope)
+{
+    int sy = qy, sx = qx;
+    if (POOL) {
+        sy = qy >> 1; sx = qx >> 1;
+        const uint8_t a = *at<uint8_t>(arg, stack, ti, tj, n, co, sy, sx);
+        if (a != (uint8_t)(((qy & 1) << 1) | (qx & 1))) return 0.0f;
+    }
+    const float g = ld(at<T>(din, stack, ti, tj, n, co, sy, sx));
+    const float y = ld(at<T>(yv, stack, ti, tj, n, co, sy, sx));
+    return y > 0.0f ? g : slope * g;
+}
+
+// ---- forward: convolution + leaky ReLU (+ 2x2 max-pool) ------------------------------------------------
+template <typename T, int K, bool POOL, int COB>
+__global__ void __launch_bounds__(64)
+k_conv_fwd_direct(View in, View out, View arg, RectTab rt, const T* __restrict__ w, const T* __restrict__ bias,
+                  int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
+{
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    const int rw = rt.x1[tj] - rt.x0[tj] + 1, rh = rt.y1[ti] - rt.y0[ti] + 1;
+    const int pid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (pid >= rw * rh) return;
+    const int oy = rt.y0[ti] + pid / rw, ox = rt.x0[tj] + pid % rw;
+    const int co0 = blockIdx.y * COB;
+    constexpr int NP = POOL ? 2 : 1, P = K / 2, R = NP + K - 1;
+    float acc[COB][NP * NP];
+#pragma unroll
+    for (int j = 0; j < COB; ++j)
+#pragma unroll
+        for (int d = 0; d < NP * NP; ++d) acc[j][d] = 0.0f;
+    const int by = oy * NP - P, bx = ox * NP - P;
+    for (int ci = 0; ci < Cin; ++ci) {
+        float patch[R * R];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < R; ++c) {
+                const int y = by + r, x = bx + c;
+                patch[r * R + c] = (y >= 0 && y < Hc && x >= 0 && x < Wc) ? ld(at<T>(in, stack, ti, tj, n, ci, y, x)) : 0.0f;
+            }
+#pragma unroll
+        for (int j = 0; j < COB; ++j) {
+            const int co = co0 + j;
+            if (co >= Cout) break;
+            const T* wp = w + ((size_t)co * Cin + ci) * K * K;
+#pragma unroll
+            for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+                for (int kx = 0; kx < K; ++kx) {
+                    const float wv = ld(wp + ky * K + kx);
+#pragma unroll
+                    for (int dy = 0; dy < NP; ++dy)
+#pragma unroll
+                        for (int dx = 0; dx < NP; ++dx)
+                            acc[j][dy * NP + dx] = fmaf(wv, patch[(dy + ky) * R + dx + kx], acc[j][dy * NP + dx]);
+                }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < COB; ++j) {
+        const int co = co0 + j;
+        if (co >= Cout) break;
+        const float b = bias ? ld(bias + co) : 0.0f;
+        // the pool compares activations as the map would hold them (rounded to the storage type), so the
+        // winner does not depend on whether the pool is evaluated here or as a layer of its own
+        float best = stored(leaky(acc[j][0] + b, slope), (const T*)nullptr);
+        int bi = 0;
+        if (POOL) {
+#pragma unroll
+            for (int d = 1; d < NP * NP; ++d) {
+                const float v = stored(leaky(acc[j][d] + b, slope), (const T*)nullptr);
+                if (v > best) { best = v; bi = d; }        // first maximum in window order wins
+            }
+            *at<uint8_t>(arg, stack, ti, tj, n, co, oy, ox) = (uint8_t)bi;
+        }
+        st(at<T>(out, stack, ti, tj, n, co, oy, ox), best);
+    }
+}
+
+// ---- backward: delta at the convolution input -------------------------------------------------------
+template <typename T, int K, bool POOL, int CIB>
+__global__ void __launch_bounds__(64)
+k_conv_bwd_data_direct(View din, View yv, View arg, View dout, RectTab rt, const T* __restrict__ w,
+                       int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
+{
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    const int rw = rt.x1[tj] - rt.x0[tj] + 1, rh = rt.y1[ti] - rt.y0[ti] + 1;
+    const int pid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (pid >= rw * rh) return;
+    const int iy = rt.y0[ti] + pid / rw, ix = rt.x0[tj] + pid % rw;
+    const int ci0 = blockIdx.y * CIB;
+    constexpr int P = K / 2;
+    float acc[CIB];
+#pragma unroll
+    for (int j = 0; j < CIB; ++j) acc[j] = 0.0f;
+    for (int co = 0; co < Cout; ++co) {
+#pragma unroll
+        for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < K; ++kx) {
+                const int qy = iy + P - ky, qx = ix + P - kx;
+                if (qy < 0 || qy >= Hc || qx < 0 || qx >= Wc) continue;
+                const float dz = delta_z<T, POOL>(din, yv, arg, stack, ti, tj, n, co, qy, qx, slope);
+#pragma unroll
+                for (int j = 0; j < CIB; ++j) {
+                    const int ci = ci0 + j;
+                    if (ci < Cin) acc[j] = fmaf(ld(w + (((size_t)co * Cin + ci) * K + ky) * K + kx), dz, acc[j]);
+                }
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < CIB; ++j)
+        if (ci0 + j < Cin) st(at<T>(dout, stack, ti, tj, n, ci0 + j, iy, ix), acc[j]);
+}
+
+// ---- backward: per-stack partial filter gradient -----------------------------------------------------
+// One workgroup per (ci, co, stack) sums dZ * X over the batch and the stack's owned output pixels.
+// Lanes are combined with wavefront shuffles, waves through LDS in a fixed order: deterministic.
+template <typename T, int K, bool POOL>
+__global__ void __launch_bounds__(256)
+k_wgrad_direct(View xin, View din, View yv, View arg, RectTab own, float* __restrict__ partial, long long n_params,
+               long long w_off, long long b_off, int has_bias, int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
+{
+    const int ci = blockIdx.x, co = blockIdx.y, stack = blockIdx.z;
+    const int ti = stack / M, tj = stack % M;
+    const int rw = own.x1[tj] - own.x0[tj] + 1, rh = own.y1[ti] - own.y0[ti] + 1;
+    const int px = rw * rh, items = px * batch;
+    constexpr int P = K / 2, KK = K * K;
+    float acc[KK + 1];
+#pragma unroll
+    for (int t = 0; t <= KK; ++t) acc[t] = 0.0f;
+    for (int it = threadIdx.x; it < items; it += 256) {
+        const int n = it / px, r = it - n * px;
+        const int qy = own.y0[ti] + r / rw, qx = own.x0[tj] + r % rw;
+        const float dz = delta_z<T, POOL>(din, yv, arg, stack, ti, tj, n, co, qy, qx, slope);
+        acc[KK] += dz;
+#pragma unroll
+        for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < K; ++kx) {
+                const int y = qy - P + ky, x = qx - P + kx;
+                if (y >= 0 && y < Hc && x >= 0 && x < Wc)
+                    acc[ky * K + kx] = fmaf(dz, ld(at<T>(xin, stack, ti, tj, n, ci, y, x)), acc[ky * K + kx]);
+            }
+    }
+    __shared__ float red[4][KK + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int t = 0; t <= KK; ++t) {
+        float v = acc[t];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+        if (lane == 0) red[wave][t] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x <= KK) {
+        const int t = threadIdx.x;
+        const float v = (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]);
+        float* base = partial + (long long)stack * n_params;
+        if (t < KK) base[w_off + ((long long)co * Cin + ci) * KK + t] = v;
+        else if (has_bias && ci == 0) base[b_off + co] = v;
+    }
+}
+
+// ---- lone 2x2 max-pool ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(64)
+k_pool_fwd(View in, View out, View arg, RectTab rt, int C, int M, int batch)
+{
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    const int rw = rt.x1[tj] - rt.x0[tj] + 1, rh = rt.y1[ti] - rt.y0[ti] + 1;
+    const int pid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (pid >= rw * rh) return;
+    const int oy = rt.y0[ti] + pid / rw, ox = rt.x0[tj] + pid % rw;
+    const int c = blockIdx.y;
+    float best = ld(at<T>(in, stack, ti, tj, n, c, 2 * oy, 2 * ox));
+    int bi = 0;
+#pragma unroll
+    for (int d = 1; d < 4; ++d) {
+        const float v = ld(at<T>(in, stack, ti, tj, n, c, 2 * oy + (d >> 1), 2 * ox + (d & 1)));
+        if (v > best) { best = v; bi = d; }
+    }
+    st(at<T>(out, stack, ti, tj, n, c, oy, ox), best);
+    *at<uint8_t>(arg, stack, ti, tj, n, c, oy, ox) = (uint8_t)bi;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(64)
+k_pool_bwd(View din, View arg, View dout, RectTab rt, int C, int M, int batch)
+{
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    const int rw = rt.x1[tj] - rt.x0[tj] + 1, rh = rt.y1[ti] - rt.y0[ti] + 1;
+    const int pid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (pid >= rw * rh) return;
+    const int iy = rt.y0[ti] + pid / rw, ix = rt.x0[tj] + pid % rw;
+    const int c = blockIdx.y;
+    const uint8_t a = *at<uint8_t>(arg, stack, ti, tj, n, c, iy >> 1, ix >> 1);
+    const float g = (a == (uint8_t)(((iy & 1) << 1) | (ix & 1))) ? ld(at<T>(din, stack, ti, tj, n, c, iy >> 1, ix >> 1)) : 0.0f;
+    st(at<T>(dout, stack, ti, tj, n, c, iy, ix), g);
+}
+
+// ---- sum of the per-stack partial gradients ------------------------------------------------------------
+// Balanced pairwise order over the stack index (pairs (2k, 2k+1) at each level, an odd tail is carried
+// up), evaluated with a binary-counter stack so that one pass over the partials suffices.
+__global__ void __launch_bounds__(256)
+k_reduce_wgrad(const float* __restrict__ partial, float* __restrict__ wgrad, long long n_params, int stacks)
+{
+    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n_params) return;
+    float stk[10];
+    int top = 0;
+    for (int s = 0; s < stacks; ++s) {
+        float v = partial[(long long)s * n_params + p];
+        for (int k = s; k & 1; k >>= 1) v = stk[--top] + v;
+        stk[top++] = v;
+    }
+    float v = stk[--top];
+    while (top > 0) v = stk[--top] + v;
+    wgrad[p] = v;
+}
+
+// ---- launchers ---------------------------------------------------------------------------------------------
+namespace {
+
+inline int rect_max_px(const RectTab& rt, int N, int M)
+{
+    int mw = 0, mh = 0;
+    for (int t = 0; t < M; ++t) mw = mw > rt.x1[t] - rt.x0[t] + 1 ? mw : rt.x1[t] - rt.x0[t] + 1;
+    for (int t = 0; t < N; ++t) mh = mh > rt.y1[t] - rt.y0[t] + 1 ? mh : rt.y1[t] - rt.y0[t] + 1;
+    return mw * mh;
+}
+
+template <typename T>
+void conv_fwd_t(const ConvArgs& a, hipStream_t s)
+{
+    constexpr int COB = 8;
+    dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cout + COB - 1) / COB, a.N * a.M * a.batch), block(64);
+    const T* w = (const T*)a.w; const T* b = (const T*)a.bias;
+#define FTP_FWD(KK, PL) hipLaunchKernelGGL((k_conv_fwd_direct<T, KK, PL, COB>), grid, block, 0, s, a.in, a.out, a.arg, a.rect, w, b, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+    if (a.K == 3) { if (a.pooled) FTP_FWD(3, true); else FTP_FWD(3, false); }
+    else          { if (a.pooled) FTP_FWD(1, true); else FTP_FWD(1, false); }
+#undef FTP_FWD
+}
+
+template <typename T>
+void conv_bwd_data_t(const ConvArgs& a, hipStream_t s)
+{
+    constexpr int CIB = 8;
+    dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cin + CIB - 1) / CIB, a.N * a.M * a.batch), block(64);
+    const T* w = (const T*)a.w;
+#define FTP_BWD(KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, PL, CIB>), grid, block, 0, s, a.din, a.out, a.arg, a.dout, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+    if (a.K == 3) { if (a.pooled) FTP_BWD(3, true); else FTP_BWD(3, false); }
+    else          { if (a.pooled) FTP_BWD(1, true); else FTP_BWD(1, false); }
+#undef FTP_BWD
+}
+
+template <typename T>
+void wgrad_t(const ConvArgs& a, hipStream_t s)
+{
+    dim3 grid(a.Cin, a.Cout, a.N * a.M), block(256);
+#define FTP_WG(KK, PL) hipLaunchKernelGGL((k_wgrad_direct<T, KK, PL>), grid, block, 0, s, a.in, a.din, a.out, a.arg, a.rect, a.partial, a.n_params, a.w_off, a.b_off, a.has_bias, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+    if (a.K == 3) { if (a.pooled) FTP_WG(3, true); else FTP_WG(3, false); }
+    else          { if (a.pooled) FTP_WG(1, true); else FTP_WG(1, false); }
+#undef FTP_WG
+}
+
+}  // namespace
+
+void direct_conv_fwd(const ConvArgs& a, hipStream_t s) { if (a.bf16) conv_fwd_t<bf16_t>(a, s); else conv_fwd_t<float>(a, s); }
+void direct_conv_bwd_data(const ConvArgs& a, hipStream_t s) { if (a.bf16) conv_bwd_data_t<bf16_t>(a, s); else conv_bwd_data_t<float>(a, s); }
+void direct_wgrad(const ConvArgs& a, hipStream_t s) { if (a.bf16) wgrad_t<bf16_t>(a, s); else wgrad_t<float>(a, s); }
+
+void pool_fwd(const PoolArgs& a, hipStream_t s)
+{
+    dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
+    if (a.bf16) hipLaunchKernelGGL(k_pool_fwd<bf16_t>, grid, block, 0, s, a.in, a.out, a.arg, a.rect, a.C, a.M, a.batch);
+    else        hipLaunchKernelGGL(k_pool_fwd<float>, grid, block, 0, s, a.in, a.out, a.arg, a.rect, a.C, a.M, a.batch);
+}
+
+void pool_bwd(const PoolArgs& a, hipStream_t s)
+{
+    dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
+    if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.arg, a.dout, a.rect, a.C, a.M, a.batch);
+    else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.arg, a.dout, a.rect, a.C, a.M, a.batch);
+}
+
+void reduce_wgrad(const float* partial, float* wgrad, long long n_params, int stacks, hipStream_t s)
+{
+    dim3 grid((unsigned)((n_params + 255) / 256)), block(256);
+    hipLaunchKernelGGL(k_reduce_wgrad, grid, block, 0, s, partial, wgrad, n_params, stacks);
+}
+
+}  // namespace ftp

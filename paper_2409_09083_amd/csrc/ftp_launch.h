@@ -1,0 +1,44 @@
+// Host-side launch descriptors of libftp's kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "ftp_device.h"
+
+namespace ftp {
+
+// One convolution unit (convolution + leaky ReLU, optionally with the 2x2 pool behind it).
+// Which fields a pass reads:
+//   forward        in (activation at the input), out (activation at the output), arg (pool winners), rect = held
+//                  rectangle at the output boundary
+//   backward data  din (delta at the output boundary), out (activation there: sign), arg, dout (delta at the input),
+//                  rect = backward rectangle at the input boundary
+//   filter grad    in, din, out, arg, rect = owned rectangle at the convolution output (before the pool)
+struct ConvArgs {
+    View in, out, arg, din, dout;
+    RectTab rect;
+    const void* w = nullptr;        // filter, OIHW
+    const void* bias = nullptr;
+    float* partial = nullptr;       // [stacks][n_params]
+    long long n_params = 0, w_off = 0, b_off = 0;
+    int has_bias = 0;
+    int K = 3, Cin = 0, Cout = 0;
+    int Hc = 0, Wc = 0;             // map extent at the convolution (input = output, stride 1)
+    int pooled = 0;
+    float slope = 0.1f;
+    int N = 1, M = 1, batch = 1;
+    int bf16 = 0;
+};
+
+struct PoolArgs {
+    View in, out, arg, din, dout;
+    RectTab rect;
+    int C = 0, N = 1, M = 1, batch = 1, bf16 = 0;
+};
+
+void direct_conv_fwd(const ConvArgs& a, hipStream_t s);
+void direct_conv_bwd_data(const ConvArgs& a, hipStream_t s);
+void direct_wgrad(const ConvArgs& a, hipStream_t s);
+void pool_fwd(const PoolArgs& a, hipStream_t s);
+void pool_bwd(const PoolArgs& a, hipStream_t s);
+void reduce_wgrad(const float* partial, float* wgrad, long long n_params, int stacks, hipStream_t s);
+
+}  // namespace ftp

@@ -1,0 +1,98 @@
+// Internal plan structures of libftp (host side, integers only).
+#pragma once
+#include <cstdint>
+#include <cstddef>
+#include <vector>
+#include "ftp.h"
+
+struct ftp_plan_s;
+
+namespace ftp {
+
+constexpr int kMaxGrid = 16;   // tiles per dimension
+
+struct Seg { int a, b; };      // inclusive 1-D interval; a rectangle is (x-seg, y-seg)
+
+inline int seg_len(Seg s) { return s.b - s.a + 1; }
+inline bool seg_contains(Seg o, Seg i) { return o.a <= i.a && o.b >= i.b; }
+
+// Rectangles are separable: the x interval of tile (ti, tj) depends on tj only, the y interval on ti only.
+struct GroupRects {
+    int s = 0, e = 0;
+    // seg[kind][boundary - s][dim][tile index]; dim 0 = x (columns, M tiles), dim 1 = y (rows, N tiles)
+    std::vector<Seg> seg;
+    Seg& at(int kind, int l, int dim, int t) { return seg[(((size_t)kind * (e - s + 1) + (l - s)) * 2 + dim) * kMaxGrid + t]; }
+    const Seg& at(int kind, int l, int dim, int t) const { return seg[(((size_t)kind * (e - s + 1) + (l - s)) * 2 + dim) * kMaxGrid + t]; }
+};
+
+// Where a map (activation, pool winner or delta) of one boundary lives.
+enum BufKind : int { BUF_NONE = 0, BUF_X, BUF_Y, BUF_DY, BUF_DX, BUF_WS };
+
+struct BufRef {
+    int kind = BUF_NONE;      // user buffer or workspace
+    size_t offset = 0;        // byte offset inside the workspace (BUF_WS)
+    bool per_stack = false;   // per-stack slots over a held / delta rectangle, else one whole map
+    int slot_w = 0, slot_h = 0;   // slot extent (per-stack) or map extent
+    int channels = 0;
+    int rect_kind = 0;        // rectangle family giving each stack's slot origin (per-stack only)
+    size_t bytes = 0;
+};
+
+enum UnitKind : int { UNIT_CONV = 0, UNIT_POOL = 1 };
+
+// One kernel-level step: a convolution with its leaky ReLU and, if a pool follows inside the same
+// group, that pool evaluated in the epilogue; or a pool on its own.
+struct Unit {
+    int kind = UNIT_CONV;
+    int group = 0;
+    int layer = 0;            // primitive layer of the convolution (or of the lone pool)
+    bool pooled = false;
+    int bi = 0, bo = 0;       // input / output boundary
+    BufRef in_act, out_act, out_arg;          // forward
+    BufRef in_delta, out_delta;               // backward (in_delta lives at bo, out_delta at bi)
+    size_t param_offset = 0;                  // first filter element in the parameter vector
+    size_t bias_offset = 0;
+};
+
+struct Plan {
+    std::vector<ftp_layer> layers;
+    int n_layers = 0, batch = 0, N = 0, M = 0;
+    ftp_dtype dtype = FTP_F32;
+    size_t esize = 4;
+    std::vector<int> C, H, W;                 // per boundary
+    std::vector<GroupRects> groups;
+    std::vector<int> group_of_layer;
+    std::vector<Unit> units;
+    std::vector<BufRef> act, arg, delta;      // home of each boundary's activation / pool winners / delta
+    std::vector<int> home_group;              // group whose rectangles address a per-stack boundary
+    size_t workspace_bytes = 0, n_params = 0;
+    size_t split[4] = {0, 0, 0, 0};
+    double useful_macs = 0, executed_macs = 0, halo_bytes[2] = {0, 0};
+};
+
+int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int in_h, int in_w,
+               int N, int M, const int32_t* group_ends, int n_groups, ftp_dtype dtype, ftp_plan_s** out);
+
+}  // namespace ftp
+
+// Optional per-kernel timing (benchmarks): HIP events around every launch of the three passes.
+// Host objects only; created on first use and owned by the plan.
+namespace ftp {
+struct Profiler {
+    typedef void* event_t;              // hipEvent_t, kept opaque so that this header needs no HIP
+    struct Rec { int pass, layer; event_t a, b; };
+    struct Agg { int pass, layer, launches; double ms; };
+    bool on = false;
+    std::vector<Rec> pending;
+    std::vector<event_t> free_list;
+    std::vector<Agg> agg;
+    event_t get();
+    void recycle();
+    ~Profiler();
+};
+}  // namespace ftp
+
+struct ftp_plan_s {
+    ftp::Plan p;
+    mutable ftp::Profiler prof;
+};

@@ -1,0 +1,256 @@
+"""Helpers of the GPU parity tests: run libftp and the CPU oracle on the same seeded tensors.
+
+Bars (max |a-b| / max |b| per tensor): activations 1e-5 and gradients 1e-4 in fp32, 2e-2 with bf16
+storage.  Gradients are compared twice:
+  * "given state": the oracle's forward maps are copied into the plan's workspace (oracle -> GPU, never
+    the other way), so both sides back-propagate through identical leaky signs and pool winners.  This
+    is the strict elementwise check of back-propagation.
+  * "chain": ftp_forward followed by ftp_backward.  A rounding difference in a forward value that sits on
+    a kink (a pre-activation within rounding of 0, two pool candidates within rounding of each other)
+    legitimately flips a decision and changes a few gradient entries by O(1); the chain check is strict
+    only where the oracle shows every decision is clear of its kink, else it is held to a norm-wise bound.
+"""
+import numpy as np
+
+from ftp_synth import configs as C
+from ftp_synth.configs import CONV
+
+TOL_ACT_F32 = 1e-5     # activations, fp32
+TOL_GRAD_F32 = 1e-4    # dX and dW, fp32
+TOL_BF16 = 2e-2        # everything, bf16 storage
+
+
+def rel_inf(a, b):
+    """max |a - b| / max |b| over one tensor (the 'relative' of the parity bars)."""
+    d = float(np.max(np.abs(a.astype(np.float64) - b.astype(np.float64))))
+    s = float(np.max(np.abs(b)))
+    return d / s if s > 0 else d
+
+
+def rel_l2(a, b):
+    d = float(np.linalg.norm((a.astype(np.float64) - b.astype(np.float64)).ravel()))
+    s = float(np.linalg.norm(b.astype(np.float64).ravel()))
+    return d / s if s > 0 else d
+
+
+def oracle_run(oracle, cfg, x, ws, bs, dy, want_db=False):
+    bf = cfg.dtype == "bf16"
+    acts, args = oracle.forward(cfg.layers, x, ws, bs, bf16_store=bf)
+    dx, dws, dbs = oracle.backward(cfg.layers, acts, args, ws, dy, bf16_store=bf, want_db=want_db)
+    return acts, args, dx, dws, dbs
+
+
+def pool_gap(a):
+    """Top-2 gap of every 2x2 window of a map (n, c, h, w) -> (n, c, h/2, w/2)."""
+    n, c, h, w = a.shape
+    win = a.reshape(n, c, h // 2, 2, w // 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(n, c, h // 2, w // 2, 4)
+    srt = np.sort(win, axis=-1)
+    return srt[..., 3] - srt[..., 2]
+
+
+def min_decision_margin(layers, acts):
+    """Smallest distance of any forward decision from its kink, relative to the map's max magnitude:
+    |Y| for the leaky signs that back-propagation reads (pooled outputs where a pool follows), and the
+    top-2 gap of every pool window."""
+    m = np.inf
+    L = len(layers)
+    for l, ly in enumerate(layers):
+        out = acts[l + 1]
+        scale = float(np.max(np.abs(out))) or 1.0
+        if ly.kind == CONV:
+            if not (l + 1 < L and layers[l + 1].kind != CONV):
+                m = min(m, float(np.min(np.abs(out))) / scale)
+        else:
+            m = min(m, float(np.min(pool_gap(acts[l]))) / scale)
+            if l > 0 and layers[l - 1].kind == CONV:
+                m = min(m, float(np.min(np.abs(out))) / scale)
+    return m
+
+
+class _BiasLayer:
+    def __init__(self, ly):
+        self.kind, self.k, self.stride, self.pad, self.cin, self.cout, self.slope = \
+            ly.kind, ly.k, ly.stride, ly.pad, ly.cin, ly.cout, ly.slope
+        self.has_bias = 1
+
+
+def make_session(cfg, batch, has_bias=False):
+    from paper_2409_09083_amd.harness import Session
+    layers = cfg.layers
+    if has_bias:
+        layers = [_BiasLayer(ly) if ly.kind == CONV else ly for ly in layers]
+    return Session(layers, batch, cfg.in_c, cfg.in_h, cfg.in_w, cfg.grid, cfg.group_ends, cfg.dtype)
+
+
+def gpu_run(cfg, x, ws, bs, dy, has_bias=False):
+    import torch
+    s = make_session(cfg, x.shape[0], has_bias)
+    s.load(x=x, weights=ws, dy=dy, biases=bs if has_bias else None)
+    s.step()
+    torch.cuda.synchronize()
+    return {"y": s.to_np(s.y), "dx": s.to_np(s.dx), "wgrad": s.to_np(s.wgrad), "partials": s.to_np(s.partials),
+            "session": s}
+
+
+def flat_grad(cfg, dws, dbs=None, has_bias=False):
+    parts = []
+    for l, ly in enumerate(cfg.layers):
+        if ly.kind == CONV:
+            parts.append(dws[l].ravel())
+            if has_bias:
+                parts.append(dbs[l].ravel())
+    return np.concatenate(parts)
+
+
+def param_slices(cfg, has_bias=False):
+    """[(layer, start, stop)] of each convolution's filter inside the parameter vector."""
+    out, off = [], 0
+    for l, ly in enumerate(cfg.layers):
+        if ly.kind == CONV:
+            n = ly.cout * ly.cin * ly.k * ly.k
+            out.append((l, off, off + n))
+            off += n + (ly.cout if has_bias else 0)
+    return out
+
+
+def groups_of(cfg):
+    out, s = [], 0
+    for e in cfg.group_ends:
+        out.append((s, e))
+        s = e
+    return out
+
+
+def check_forward_state(s, cfg, acts, args, tol_a):
+    """Every map the plan keeps equals the oracle's: the assembled owned tiles, and each stack's whole
+    held rectangle (recomputed halo included).  Pool winners may differ only where the oracle's top-2
+    gap is within the activation tolerance."""
+    import paper_2409_09083_amd as F
+    worst = 0.0
+    for b in range(1, len(cfg.layers) + 1):
+        got = s.get_boundary(b)
+        if got is None:
+            continue
+        e = rel_inf(got, acts[b])
+        worst = max(worst, e)
+        assert e <= tol_a, ("activation at boundary", b, e)
+        scale = float(np.max(np.abs(acts[b])))
+        for (r, slot) in s.get_slots(b):
+            ref = acts[b][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]
+            assert np.max(np.abs(slot - ref)) <= tol_a * scale, ("held rectangle", b, r)
+        ga = s.get_boundary(b, F.FTP_BUF_ARG)
+        if ga is not None:
+            bad = ga != args[b - 1]
+            if bad.any():
+                gap = pool_gap(_prepool(cfg, acts, b))
+                assert float(gap[bad].max()) <= 2 * tol_a * float(np.max(np.abs(acts[b]))), ("pool winners", b, int(bad.sum()))
+    return worst
+
+
+def decisions_agree(s, cfg, acts, args):
+    """True if every leaky sign and pool winner the GPU's forward state holds equals the oracle's."""
+    import paper_2409_09083_amd as F
+    for b in range(1, len(cfg.layers) + 1):
+        got = s.get_boundary(b)
+        if got is None:
+            continue
+        if ((got > 0) != (acts[b] > 0)).any():
+            return False
+        for (r, slot) in s.get_slots(b):
+            if ((slot > 0) != (acts[b][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1] > 0)).any():
+                return False
+        ga = s.get_boundary(b, F.FTP_BUF_ARG)
+        if ga is not None and (ga != args[b - 1]).any():
+            return False
+        for (r, slot) in s.get_slots(b, F.FTP_BUF_ARG):
+            if (slot != args[b - 1][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]).any():
+                return False
+    return True
+
+
+def _prepool(cfg, acts, b):
+    return acts[b - 1]
+
+
+def import_forward_state(s, cfg, acts, args):
+    """oracle -> GPU: the plan's workspace and y receive the oracle's forward maps."""
+    import paper_2409_09083_amd as F
+    L = len(cfg.layers)
+    for b in range(1, L + 1):
+        s.set_boundary(b, acts[b])
+        if args[b - 1] is not None:
+            s.set_boundary(b, args[b - 1], F.FTP_BUF_ARG)
+
+
+def check_grads(cfg, got_dx, got_wgrad, dx, dws, dbs, has_bias, tol_g, label):
+    e = rel_inf(got_dx, dx)
+    assert e <= tol_g, (label, "dx", e)
+    ref = flat_grad(cfg, dws, dbs, has_bias)
+    assert got_wgrad.shape == ref.shape
+    for (l, a, b) in param_slices(cfg, has_bias):
+        e = rel_inf(got_wgrad[a:b], ref[a:b])
+        assert e <= tol_g, (label, "dW", l, e)
+        if has_bias:
+            eb = rel_inf(got_wgrad[b:b + cfg.layers[l].cout], dbs[l])
+            assert eb <= tol_g, (label, "db", l, eb)
+
+
+def check_case(oracle, cfg, seed=C.rng.MASTER_SEED, has_bias=False, strict_chain=None, partial_check=True):
+    import torch
+    import paper_2409_09083_amd as F
+    x, ws, bs, dy = C.make_tensors(cfg, master_seed=seed)
+    bf = cfg.dtype == "bf16"
+    if has_bias:
+        bs = [None if b is None else C.rng.normal("b/%d" % l, b.shape, 0.2, seed) for l, b in enumerate(bs)]
+        if bf:
+            bs = [None if b is None else C.rng.to_bf16_rne(b) for b in bs]
+    acts, args, dx, dws, dbs = oracle_run(oracle, cfg, x, ws, bs if has_bias else None, dy, want_db=has_bias)
+    tol_a, tol_g = (TOL_BF16, TOL_BF16) if bf else (TOL_ACT_F32, TOL_GRAD_F32)
+    ref = flat_grad(cfg, dws, dbs, has_bias)
+
+    s = make_session(cfg, x.shape[0], has_bias)
+    s.load(x=x, weights=ws, dy=dy, biases=bs if has_bias else None)
+    s.forward()
+    torch.cuda.synchronize()
+    assert rel_inf(s.to_np(s.y), acts[-1]) <= tol_a
+    check_forward_state(s, cfg, acts, args, tol_a)
+
+    # chain: back-propagation through the GPU's own forward state
+    s.backward()
+    s.reduce()
+    torch.cuda.synchronize()
+    chain_dx, chain_w, chain_p = s.to_np(s.dx), s.to_np(s.wgrad), s.to_np(s.partials)
+    agree = decisions_agree(s, cfg, acts, args)
+    if strict_chain is None:
+        strict_chain = agree
+    if strict_chain:
+        # both sides took the same decisions (leaky signs, pool winners): elementwise comparison is well posed
+        assert agree
+        check_grads(cfg, chain_dx, chain_w, dx, dws, dbs, has_bias, tol_g, "chain")
+    else:
+        # some decisions sit on their kink and flipped: each flip moves a few gradient entries by O(1), so
+        # only a norm-wise bound is meaningful here; the elementwise bars are enforced below on given state
+        assert rel_l2(chain_dx, dx) <= (1e-1 if bf else 2e-2), ("chain dx", rel_l2(chain_dx, dx))
+        assert rel_l2(chain_w, ref) <= (1e-1 if bf else 2e-2), ("chain dW", rel_l2(chain_w, ref))
+    assert np.allclose(chain_p.astype(np.float64).sum(axis=0), chain_w, rtol=1e-5, atol=1e-6 * np.abs(ref).max())
+
+    # given state: identical decisions on both sides, strict elementwise bars
+    import_forward_state(s, cfg, acts, args)
+    s.y.copy_(torch.from_numpy(acts[-1]).cuda().to(s.y.dtype))
+    s.backward()
+    s.reduce()
+    torch.cuda.synchronize()
+    got_dx, got_w, got_p = s.to_np(s.dx), s.to_np(s.wgrad), s.to_np(s.partials)
+    check_grads(cfg, got_dx, got_w, dx, dws, dbs, has_bias, tol_g, "given state")
+    if partial_check:
+        # one stack's partial = the oracle's filter-gradient sum restricted to that stack's owned pixels
+        ti, tj = cfg.grid[0] - 1, cfg.grid[1] // 2
+        stack = ti * cfg.grid[1] + tj
+        groups = groups_of(cfg)
+        for (l, a, b) in param_slices(cfg, has_bias):
+            g = [k for k, (s0, e0) in enumerate(groups) if s0 <= l < e0][0]
+            own = F.ftp_plan_rect(s.plan, g, l + 1, ti, tj, F.FTP_RECT_OWN)
+            _, dres, _ = oracle.backward(cfg.layers, acts, args, ws, dy, rect_of_layer=lambda q: own if q == l else None,
+                                         bf16_store=bf, want_db=False)
+            assert rel_inf(got_p[stack, a:b], dres[l].ravel()) <= tol_g, ("partial", l)
+    s.close()

@@ -1,0 +1,69 @@
+"""GPU parity, small cases: libftp through the C ABI against the CPU oracle, element by element,
+on shapes that span several tiles, ragged tails, every grouping and both storage types."""
+import numpy as np
+import pytest
+
+from ftp_synth import configs as C
+from ftp_synth.configs import Config, conv, pool
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def test_tiny_config(oracle):
+    P.check_case(oracle, C.tiny())
+
+
+_NETS = {
+    "convs": ((conv(3, 8), conv(8, 16), conv(16, 8, 1), conv(8, 12)), 40, 36),
+    "pools": ((conv(3, 8), pool(8), conv(8, 16), conv(16, 8, 1), pool(8), conv(8, 12)), 48, 40),
+    "poolfirst": ((pool(3), conv(3, 6), pool(6), pool(6), conv(6, 10), conv(10, 4, 1)), 64, 48),
+    "wide": ((conv(3, 20), pool(20), conv(20, 40), conv(40, 24, 1), conv(24, 33)), 28, 36),
+}
+
+
+def _mk(net, grid, grouping, dtype="f32", batch=2):
+    layers, h, w = _NETS[net]
+    L = len(layers)
+    ends = {"whole": (L,), "each": tuple(range(1, L + 1)), "split": (L // 2, L)}[grouping]
+    return Config("%s_%s" % (net, grouping), batch, layers[0].cin, h, w, layers, grid, ends, dtype)
+
+
+@pytest.mark.parametrize("net", sorted(_NETS))
+@pytest.mark.parametrize("grouping", ["whole", "each", "split"])
+@pytest.mark.parametrize("grid", [(1, 1), (3, 2), (2, 4)])
+def test_small_nets_f32(oracle, net, grouping, grid):
+    P.check_case(oracle, _mk(net, grid, grouping))
+
+
+@pytest.mark.parametrize("net", ["pools", "wide", "poolfirst"])
+@pytest.mark.parametrize("grouping", ["whole", "each"])
+def test_small_nets_bf16(oracle, net, grouping):
+    P.check_case(oracle, _mk(net, (3, 2), grouping, "bf16"))
+
+
+@pytest.mark.parametrize("grouping", ["whole", "split"])
+def test_bias(oracle, grouping):
+    P.check_case(oracle, _mk("pools", (2, 3), grouping), has_bias=True)
+
+
+def test_batch_one_and_odd_batch(oracle):
+    P.check_case(oracle, _mk("pools", (2, 2), "split", batch=1))
+    P.check_case(oracle, _mk("convs", (2, 2), "whole", batch=3))
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_config2(oracle, fused):
+    P.check_case(oracle, C.config2(fused), strict_chain=False)
+
+
+def test_deterministic_bitwise(oracle):
+    """Two runs give bitwise identical y, dx and reduced gradients (no float atomics anywhere)."""
+    cfg = _mk("pools", (3, 2), "split")
+    x, ws, bs, dy = C.make_tensors(cfg)
+    a = P.gpu_run(cfg, x, ws, bs, dy)
+    b = P.gpu_run(cfg, x, ws, bs, dy)
+    for k in ("y", "dx", "wgrad", "partials"):
+        assert np.array_equal(a[k], b[k]), k
+    a["session"].close()
+    b["session"].close()

@@ -1,0 +1,153 @@
+"""Host-only checks of libftp: the library loads without a GPU, exports every symbol the header
+declares, its integer maps equal the oracle's bit for bit, and bad plans are rejected with codes."""
+import ctypes
+import os
+import random
+import re
+
+import pytest
+
+from ftp_synth import configs as C
+from ftp_synth.configs import Layer, conv, pool, CONV, MAXPOOL
+from oracle import rects as R
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def F():
+    import paper_2409_09083_amd as F
+    return F
+
+
+def test_exports_match_header(F):
+    hdr = open(os.path.join(ROOT, "include", "ftp.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ftp_[a-z_]+)\s*\(", hdr))
+    assert declared == set(F.binding.EXPORTS)
+    lib = ctypes.CDLL(F.binding.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def _compare(F, layers, h, w, N, M, ends, batch=1):
+    plan = F.ftp_plan(layers, batch, layers[0].cin, h, w, N, M, list(ends))
+    try:
+        sizes, oplan = R.plan(layers, h, w, N, M, ends)
+        for l, (hh, ww) in enumerate(sizes):
+            c = layers[0].cin if l == 0 else layers[l - 1].cout
+            assert F.ftp_plan_map_shape(plan, l) == (c, hh, ww)
+        for g, (s, e) in enumerate(R.groups_from_ends(ends)):
+            for (i, j), rk in oplan[g].items():
+                for kind, fk in ((R.OWN, F.FTP_RECT_OWN), (R.FWD, F.FTP_RECT_FWD), (R.BWD, F.FTP_RECT_BWD), (R.HELD, F.FTP_RECT_HELD)):
+                    for l in range(s, e + 1):
+                        assert F.ftp_plan_rect(plan, g, l, i, j, fk) == tuple(rk[kind][l]), (g, l, i, j, kind)
+    finally:
+        F.ftp_plan_destroy(plan)
+
+
+def _all_configs():
+    out = [C.tiny(), C.config2(False), C.config2(True), C.config3(), C.config4()]
+    out += [C.config5(g) for g in (1, 2, 4, 8, 16)]
+    return out
+
+
+@pytest.mark.parametrize("cfg", _all_configs(), ids=lambda c: c.name)
+def test_rects_bit_exact_on_configs(F, cfg):
+    _compare(F, cfg.layers, cfg.in_h, cfg.in_w, cfg.grid[0], cfg.grid[1], cfg.group_ends, cfg.batch)
+
+
+def test_rects_bit_exact_random_sweep(F):
+    rnd = random.Random(1234)
+    done = 0
+    while done < 150:
+        L = rnd.randint(1, 9)
+        in_h, in_w = rnd.choice([16, 24, 32, 40, 48, 64, 96]), rnd.choice([16, 24, 32, 48, 56, 64, 80])
+        layers, c, h, w = [], rnd.randint(1, 4), in_h, in_w
+        for _ in range(L):
+            if rnd.random() < 0.3 and h % 2 == 0 and w % 2 == 0 and h >= 8 and w >= 8:
+                layers.append(pool(c))
+                h //= 2
+                w //= 2
+            else:
+                co = rnd.randint(1, 5)
+                layers.append(conv(c, co, rnd.choice([1, 3])))
+                c = co
+        N, M = rnd.randint(1, 4), rnd.randint(1, 4)
+        if h < N or w < M:
+            continue
+        cuts = sorted(rnd.sample(range(1, L), rnd.randint(0, L - 1))) if L > 1 else []
+        _compare(F, layers, in_h, in_w, N, M, tuple(cuts + [L]))
+        done += 1
+
+
+def test_plan_sizes_and_work(F):
+    cfg = C.config4()
+    plan = F.ftp_plan(cfg.layers, cfg.batch, 3, 608, 608, 6, 6, list(cfg.group_ends))
+    sz = F.ftp_plan_sizes(plan)
+    assert sz["n_params"] == 3418976
+    assert sz["wgrad_partial_bytes"] == 36 * 3418976 * 4
+    wk = F.ftp_plan_work(plan)
+    # untiled work: 3 x forward MACs (forward, delta, filter gradient), 26.0 GFLOP forward per image
+    macs_fwd = sum(ly.cin * ly.cout * ly.k ** 2 * h * w for ly, (h, w) in
+                   zip(cfg.layers, R.map_sizes(cfg.layers, 608, 608)[1:]) if ly.kind == CONV)
+    assert wk["useful_macs"] == 3.0 * macs_fwd * cfg.batch
+    assert 1.0 <= wk["executed_macs"] / wk["useful_macs"] < 1.5
+    F.ftp_plan_destroy(plan)
+    # one layer per group: nothing is recomputed
+    c5 = C.config5(1)
+    plan = F.ftp_plan(c5.layers, c5.batch, 3, 608, 608, 8, 8, list(c5.group_ends), F.FTP_BF16)
+    wk = F.ftp_plan_work(plan)
+    assert wk["executed_macs"] == wk["useful_macs"]
+    F.ftp_plan_destroy(plan)
+
+
+def test_plan_rejections(F):
+    ok = [conv(3, 4), pool(4), conv(4, 4)]
+
+    def code(layers, h=16, w=16, N=2, M=2, ends=None, batch=1, c=3, dtype=0):
+        try:
+            p = F.ftp_plan(layers, batch, c, h, w, N, M, list(ends if ends is not None else [len(layers)]), dtype)
+        except F.binding.FtpError as e:
+            return e.code
+        F.ftp_plan_destroy(p)
+        return 0
+
+    assert code(ok) == 0
+    assert code([Layer(CONV, 3, 2, 1, 3, 4)]) == F.FTP_EUNSUPPORTED          # strided convolution
+    assert code([Layer(CONV, 5, 1, 2, 3, 4)]) == F.FTP_EUNSUPPORTED          # 5x5
+    assert code([Layer(CONV, 3, 1, 0, 3, 4)]) == F.FTP_EUNSUPPORTED          # pad != K/2
+    assert code([Layer(CONV, 3, 1, 1, 3, 4, -0.1)]) == F.FTP_EUNSUPPORTED    # negative slope
+    assert code([Layer(MAXPOOL, 3, 2, 0, 3, 3)]) == F.FTP_EUNSUPPORTED
+    assert code([conv(4, 4)]) == F.FTP_ECHANNELS
+    assert code([conv(3, 4), pool(5)]) == F.FTP_ECHANNELS
+    assert code([conv(3, 4), pool(4)], h=15, w=16) == F.FTP_EGRID            # odd map meets a pool
+    assert code(ok, N=9, M=2) == F.FTP_EGRID                                 # 8 rows after the pool, 9 tiles
+    assert code(ok, N=17, M=1, h=64, w=64) == F.FTP_EGRID
+    assert code(ok, ends=[2, 2, 3]) == F.FTP_EGROUPS
+    assert code(ok, ends=[1, 2]) == F.FTP_EGROUPS
+    assert code(ok, ends=[0, 3]) == F.FTP_EGROUPS
+    assert code(ok, ends=[4]) == F.FTP_EGROUPS
+    assert code(ok, batch=0) == F.FTP_EINVAL
+    assert code(ok, N=0) == F.FTP_EINVAL
+    assert code(ok, dtype=7) == F.FTP_EINVAL
+    assert code([], ends=[0]) == F.FTP_EINVAL
+    assert code(ok, N=16, M=16, h=64, w=64, batch=300) == F.FTP_EUNSUPPORTED
+    assert "grid" in F.ftp_strerror(F.FTP_EGRID)
+
+
+def test_null_arguments_rejected_without_gpu(F):
+    cfg = C.tiny()
+    plan = F.ftp_plan(cfg.layers, 1, 3, 32, 32, 2, 2, [2])
+    with pytest.raises(F.binding.FtpError) as e:
+        F.ftp_forward(plan, 0, [0, 0], None, 0, 0, 0)
+    assert e.value.code == F.FTP_EINVAL
+    with pytest.raises(F.binding.FtpError):
+        F.ftp_backward(plan, 0, 0, 0, [0, 0], 0, 0, 0, 0)
+    with pytest.raises(F.binding.FtpError):
+        F.ftp_reduce_wgrad(plan, 0, 0, 0)
+    with pytest.raises(F.binding.FtpError):
+        F.ftp_plan_rect(plan, 0, 3, 0, 0, F.FTP_RECT_OWN)
+    with pytest.raises(F.binding.FtpError):
+        F.ftp_plan_rect(plan, 1, 0, 0, 0, F.FTP_RECT_OWN)
+    F.ftp_plan_destroy(plan)
