@@ -110,30 +110,33 @@ class Session:
     def _rect(self, info, boundary, stack, kind):
         return B.ftp_plan_rect(self.plan, info["group"], boundary, stack // self.grid[1], stack % self.grid[1], kind)
 
-    def get_boundary(self, boundary, which=B.FTP_BUF_ACT):
-        """Whole map at a boundary, assembled from what each stack owns.  None if the plan keeps none."""
+    def get_boundary(self, boundary, which=B.FTP_BUF_ACT, images=None):
+        """Whole map at a boundary, assembled from what each stack owns.  None if the plan keeps none.
+        images: optional list of image indices to fetch (default: the whole batch)."""
         t, info = self._buffer(boundary, which)
         if t is None:
             return None
+        idx = list(range(self.batch)) if images is None else list(images)
         if not info["per_stack"]:
-            return self.to_np(t)
+            return self.to_np(t[idx])
         c, h, w = B.ftp_plan_map_shape(self.plan, boundary)
-        out = torch.zeros((self.batch, c, h, w), dtype=t.dtype, device=t.device)
+        out = torch.zeros((len(idx), c, h, w), dtype=t.dtype, device=t.device)
         for s in range(self.stacks):
             o = self._rect(info, boundary, s, B.FTP_RECT_OWN)
             r = self._rect(info, boundary, s, info["rect_kind"])
-            out[:, :, o[1]:o[3] + 1, o[0]:o[2] + 1] = t[s, :, :, o[1] - r[1]:o[3] - r[1] + 1, o[0] - r[0]:o[2] - r[0] + 1]
+            out[:, :, o[1]:o[3] + 1, o[0]:o[2] + 1] = t[s][idx][:, :, o[1] - r[1]:o[3] - r[1] + 1, o[0] - r[0]:o[2] - r[0] + 1]
         return self.to_np(out)
 
-    def get_slots(self, boundary, which=B.FTP_BUF_ACT):
+    def get_slots(self, boundary, which=B.FTP_BUF_ACT, images=None):
         """[(rect, array)] per stack: everything a stack holds at an interior boundary (own tile + halo)."""
         t, info = self._buffer(boundary, which)
         if t is None or not info["per_stack"]:
             return []
+        idx = list(range(self.batch)) if images is None else list(images)
         out = []
         for s in range(self.stacks):
             r = self._rect(info, boundary, s, info["rect_kind"])
-            out.append((r, self.to_np(t[s, :, :, :r[3] - r[1] + 1, :r[2] - r[0] + 1])))
+            out.append((r, self.to_np(t[s][idx][:, :, :r[3] - r[1] + 1, :r[2] - r[0] + 1])))
         return out
 
     def set_boundary(self, boundary, full_map, which=B.FTP_BUF_ACT):
