@@ -3,6 +3,7 @@
 #include "ftp_plan.h"
 #include "ftp_launch.h"
 
+#include <cstdlib>
 #include <cstring>
 
 using namespace ftp;
@@ -47,6 +48,23 @@ RectTab make_rect(const Plan& p, int group, int kind, int boundary)
     for (int t = 0; t < p.M; ++t) { r.x0[t] = g.at(kind, boundary, 0, t).a; r.x1[t] = g.at(kind, boundary, 0, t).b; }
     for (int t = 0; t < p.N; ++t) { r.y0[t] = g.at(kind, boundary, 1, t).a; r.y1[t] = g.at(kind, boundary, 1, t).b; }
     return r;
+}
+
+// Extent of a view per tile column / row: the stack's rectangle for per-stack slots, else the whole map.
+RectTab view_extent(const Plan& p, const BufRef& b, int group, int boundary)
+{
+    if (b.per_stack) return make_rect(p, group, b.rect_kind, boundary);
+    RectTab r;
+    std::memset(&r, 0, sizeof(r));
+    for (int t = 0; t < kTabGrid; ++t) { r.x1[t] = b.slot_w - 1; r.y1[t] = b.slot_h - 1; }
+    return r;
+}
+
+// FTP_KERNELS=direct keeps every layer on the direct kernels (debugging aid).
+bool use_mfma()
+{
+    static const bool on = [] { const char* e = std::getenv("FTP_KERNELS"); return !(e && std::strcmp(e, "direct") == 0); }();
+    return on;
 }
 
 ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void* const* weights, const void* const* biases)
@@ -215,7 +233,16 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
         if (u.kind == UNIT_CONV) {
             ConvArgs a = conv_args(p, u, ub, weights, biases);
             a.rect = make_rect(p, u.group, FTP_RECT_HELD, u.bo);
-            rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { direct_conv_fwd(a, s); });
+            if (use_mfma() && mfma_conv_eligible(a, false)) {
+                float* wt = (float*)((char*)workspace + u.wt_fwd_offset);
+                const RectTab ext = view_extent(p, u.in_act, u.group, u.bi);
+                rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] {
+                    prep_filter((const float*)a.w, wt, nullptr, a.Cout, a.Cin, a.K, s);
+                    mfma_conv_fwd(a, ext, wt, s);
+                });
+            } else {
+                rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { direct_conv_fwd(a, s); });
+            }
         } else {
             PoolArgs a = pool_args(p, u, ub);
             a.rect = make_rect(p, u.group, FTP_RECT_HELD, u.bo);
@@ -244,7 +271,16 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { direct_wgrad(a, s); });
             if (rc != FTP_OK) return rc;
             a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
-            rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { direct_conv_bwd_data(a, s); });
+            if (use_mfma() && mfma_conv_eligible(a, true)) {
+                float* wt = (float*)((char*)workspace + u.wt_bwd_offset);
+                const RectTab ext = view_extent(p, u.in_delta, u.group, u.bo);
+                rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] {
+                    prep_filter((const float*)a.w, nullptr, wt, a.Cout, a.Cin, a.K, s);
+                    mfma_conv_bwd_data(a, ext, wt, s);
+                });
+            } else {
+                rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { direct_conv_bwd_data(a, s); });
+            }
         } else {
             PoolArgs a = pool_args(p, u, ub);
             a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);

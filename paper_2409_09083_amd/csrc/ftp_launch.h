@@ -34,6 +34,26 @@ struct PoolArgs {
     int C = 0, N = 1, M = 1, batch = 1, bf16 = 0;
 };
 
+// Kernel argument block of the matrix-core convolution (forward and delta back-propagation).
+struct MfmaConvArgs {
+    View in, out, arg, din, dout;
+    RectTab rect;                                   // output rectangle each stack computes
+    int ix0[kTabGrid], ix1[kTabGrid], iy0[kTabGrid], iy1[kTabGrid];   // extent of the input view per tile column / row
+    const float* wt;                                // relaid filter [tap][reduction channel][output channel]
+    const float* bias;
+    int C, Mtot;                                    // reduction channels, output channels
+    int Hc, Wc;                                     // map extent at the convolution
+    int TI, TR, TC, tiles_x, tiles_y, tiles_i;      // tile: images x rows x columns, and tile counts
+    int cs_pad;
+    float slope;
+    int M, batch;
+};
+
+bool mfma_conv_eligible(const ConvArgs& a, bool backward);
+void prep_filter(const float* w, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s);
+void mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
+void mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
+
 void direct_conv_fwd(const ConvArgs& a, hipStream_t s);
 void direct_conv_bwd_data(const ConvArgs& a, hipStream_t s);
 void direct_wgrad(const ConvArgs& a, hipStream_t s);

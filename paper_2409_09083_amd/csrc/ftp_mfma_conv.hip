@@ -1,0 +1,321 @@
+// fp32 matrix-core (MFMA) implicit-GEMM convolution for gfx950, used for the forward pass and for the
+// delta back-propagation (which is the same convolution with the 180-degree rotated, transposed
+// filter applied to dZ).  D[m][pixel] = sum_k Wt[k][m] * patch[k][pixel], k = (tap, channel).
+//
+// One workgroup (4 wavefronts) produces BM = 32*WAVES_M output channels for a tile of 256 pixels of
+// one stack: TI images x TR rows x TC columns of the stack's rectangle (pooled layers: 64 windows of
+// 4 pixels).  The input patch (tile + filter halo, zero outside the real map) and the filter slice
+// of 8 channels x K*K taps are staged in LDS; v_mfma_f32_32x32x2_f32 reads both from there.
+// MFMA lane layout (64 lanes): A[m = lane%32][k = lane/32], B[k = lane/32][n = lane%32],
+// D[m = 8*(i/4) + 4*(lane/32) + i%4][n = lane%32] for accumulator register i of 16.
+#include "ftp_device.h"
+#include "ftp_launch.h"
+
+namespace ftp {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kBN = 256;        // pixels per workgroup tile
+
+// Filter relayout: OIHW -> [tap][reduction channel][output channel], so that a stage's slice is a set of
+// contiguous rows.  fwd: Wt[t][ci][co] = W[co][ci][t].  bwd: Wt[t][co][ci] = W[co][ci][K*K-1-t] (rotated).
+__global__ void __launch_bounds__(256)
+k_prep_filter(const float* __restrict__ w, float* __restrict__ wt_fwd, float* __restrict__ wt_bwd, int Cout, int Cin, int KK)
+{
+    const long long n = (long long)Cout * Cin * KK;
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int t = (int)(i % KK);
+    const int ci = (int)((i / KK) % Cin);
+    const int co = (int)(i / ((long long)KK * Cin));
+    const float v = w[i];
+    if (wt_fwd) wt_fwd[((long long)t * Cin + ci) * Cout + co] = v;
+    if (wt_bwd) wt_bwd[((long long)(KK - 1 - t) * Cout + co) * Cin + ci] = v;
+}
+
+template <int K, int WAVES_M, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+__global__ void __launch_bounds__(256)
+k_conv_mfma(MfmaConvArgs a)
+{
+    constexpr int kCK = K == 1 ? 32 : 8;             // reduction channels per LDS stage
+    constexpr int WAVES_N = 4 / WAVES_M;
+    constexpr int NT = kBN / 32 / WAVES_N;           // 32-pixel MFMA tiles per wavefront
+    constexpr int BM = 32 * WAVES_M;
+    constexpr int KK = K * K, P = K / 2;
+    constexpr int S = POOL_OUT ? 2 : 1;
+
+    extern __shared__ float lds[];
+    float* Wl = lds;                                   // [KK][kCK][BM]
+    float* Xl = lds + KK * kCK * BM;                   // [kCK][TI][PH][PW] (+ pad)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
+    const int hi = lane >> 5, l32 = lane & 31;
+    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
+    const int x0 = a.rect.x0[tj], x1 = a.rect.x1[tj], y0 = a.rect.y0[ti], y1 = a.rect.y1[ti];
+    const int bx = blockIdx.x;
+    const int tx = bx % a.tiles_x, ty = (bx / a.tiles_x) % a.tiles_y, tb = bx / (a.tiles_x * a.tiles_y);
+    const int ox0 = x0 + tx * a.TC, oy0 = y0 + ty * a.TR, n0 = tb * a.TI;
+    if (ox0 > x1 || oy0 > y1) return;                 // this stack's rectangle is smaller than the largest one
+    const int m0 = blockIdx.y * BM;
+    const int PW = a.TC * S + 2 * P, PH = a.TR * S + 2 * P;
+    const int IS = PH * PW, CS = a.TI * IS + a.cs_pad;
+    const int px0 = ox0 * S - P, py0 = oy0 * S - P;   // patch origin in the coordinates of the convolution input
+
+    // ---- per-lane pixel of each 32-pixel tile --------------------------------------------------------
+    int baseB[NT];
+    int pn[NT], py[NT], pxx[NT];                      // image, output row, output column (pooled coordinates if POOL_OUT)
+    bool pvalid[NT];
+    const int per_img = a.TR * a.TC;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int q = (wave_n * NT + t) * 32 + l32;
+        const int wq = POOL_OUT ? (q >> 2) : q, pos = POOL_OUT ? (q & 3) : 0;
+        const int il = wq / per_img, rem = wq - il * per_img;
+        const int yl = rem / a.TC, xl = rem - yl * a.TC;
+        const bool v = il < a.TI && n0 + il < a.batch && oy0 + yl <= y1 && ox0 + xl <= x1;
+        pvalid[t] = v; pn[t] = n0 + il; py[t] = oy0 + yl; pxx[t] = ox0 + xl;
+        const int base = v ? il * IS + (yl * S + (pos >> 1)) * PW + xl * S + (pos & 1) : 0;
+        baseB[t] = base + hi * CS;
+    }
+    const int baseA = hi * BM + wave_m * 32 + l32;
+
+    // ---- per-thread patch positions (fixed over the channel loop) ---------------------------------------
+    constexpr int MAXPOS = 3;
+    const int npos = a.TI * IS;
+    long long goff[MAXPOS];        // element offset in the input view (channel 0); -1: zero padding / outside
+    long long goff2[MAXPOS];       // DELTA_IN: offset in the activation view
+    long long goff3[MAXPOS];       // DELTA_IN && POOL_IN: offset in the winner view
+    int pcode[MAXPOS];
+#pragma unroll
+    for (int j = 0; j < MAXPOS; ++j) {
+        const int s = tid + j * 256;
+        goff[j] = -1; goff2[j] = 0; goff3[j] = 0; pcode[j] = 0;
+        if (s < npos) {
+            const int il = s / IS, rem = s - il * IS;
+            const int r = rem / PW, c = rem - r * PW;
+            const int gy = py0 + r, gx = px0 + c, n = n0 + il;
+            if (n < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc) {
+                if (!DELTA_IN) {
+                    // only positions some valid output pixel of this stack reads are inside the view
+                    if (gy >= a.iy0[ti] && gy <= a.iy1[ti] && gx >= a.ix0[tj] && gx <= a.ix1[tj])
+                        goff[j] = (long long)stack * a.in.ss + (long long)n * a.in.ns + (long long)(gy - a.in.y0[ti]) * a.in.pitch + (gx - a.in.x0[tj]);
+                } else {
+                    const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
+                    if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
+                        goff[j] = (long long)stack * a.din.ss + (long long)n * a.din.ns + (long long)(sy - a.din.y0[ti]) * a.din.pitch + (sx - a.din.x0[tj]);
+                        goff2[j] = (long long)stack * a.out.ss + (long long)n * a.out.ns + (long long)(sy - a.out.y0[ti]) * a.out.pitch + (sx - a.out.x0[tj]);
+                        if (POOL_IN) {
+                            goff3[j] = (long long)stack * a.arg.ss + (long long)n * a.arg.ns + (long long)(sy - a.arg.y0[ti]) * a.arg.pitch + (sx - a.arg.x0[tj]);
+                            pcode[j] = ((gy & 1) << 1) | (gx & 1);
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    v16f acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
+
+    const float* __restrict__ wt = a.wt;
+    for (int c0 = 0; c0 < a.C; c0 += kCK) {
+        __syncthreads();
+        // filter slice: KK*kCK rows of BM contiguous floats
+        for (int idx = tid; idx < KK * kCK * (BM / 4); idx += 256) {
+            const int row = idx / (BM / 4), c4 = idx - row * (BM / 4);
+            const int tap = row / kCK, cl = row - tap * kCK;
+            const int ci = c0 + cl, m = m0 + c4 * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ci < a.C && m < a.Mtot) v = *(const float4*)(wt + ((long long)tap * a.C + ci) * a.Mtot + m);
+            *(float4*)(Wl + row * BM + c4 * 4) = v;
+        }
+        // input patch
+#pragma unroll
+        for (int j = 0; j < MAXPOS; ++j) {
+            const int s = tid + j * 256;
+            if (s < npos) {
+#pragma unroll
+                for (int cl = 0; cl < kCK; ++cl) {
+                    const int ci = c0 + cl;
+                    float v = 0.0f;
+                    if (goff[j] >= 0 && ci < a.C) {
+                        if (!DELTA_IN) {
+                            v = ((const float*)a.in.p)[goff[j] + (long long)ci * a.in.cs];
+                        } else {
+                            bool take = true;
+                            if (POOL_IN) take = ((const uint8_t*)a.arg.p)[goff3[j] + (long long)ci * a.arg.cs] == (uint8_t)pcode[j];
+                            if (take) {
+                                const float g = ((const float*)a.din.p)[goff[j] + (long long)ci * a.din.cs];
+                                const float y = ((const float*)a.out.p)[goff2[j] + (long long)ci * a.out.cs];
+                                v = y > 0.0f ? g : a.slope * g;
+                            }
+                        }
+                    }
+                    Xl[cl * CS + s] = v;
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int tap = 0; tap < KK; ++tap) {
+            const int toff = (tap / K) * PW + (tap % K);
+#pragma unroll
+            for (int i = 0; i < kCK / 2; ++i) {
+                const float av = Wl[(tap * kCK + 2 * i) * BM + baseA];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const float bv = Xl[baseB[t] + 2 * i * CS + toff];
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue ------------------------------------------------------------------------------------------
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = m0 + wave_m * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
+            float v = acc[t][i];
+            if (DELTA_IN) {
+                if (pvalid[t] && m < a.Mtot) *at<float>(a.dout, stack, ti, tj, pn[t], m, py[t], pxx[t]) = v;
+            } else {
+                const float b = (a.bias && m < a.Mtot) ? a.bias[m] : 0.0f;
+                v = leaky(v + b, a.slope);
+                if (POOL_OUT) {
+                    // the 4 pixels of a window sit in 4 adjacent lanes; every lane rebuilds the window in order
+                    const float o1 = __shfl_xor(v, 1, 64), o2 = __shfl_xor(v, 2, 64), o3 = __shfl_xor(v, 3, 64);
+                    const int pos = lane & 3;
+                    const float w0 = pos == 0 ? v : pos == 1 ? o1 : pos == 2 ? o2 : o3;
+                    const float w1 = pos == 1 ? v : pos == 0 ? o1 : pos == 3 ? o2 : o3;
+                    const float w2 = pos == 2 ? v : pos == 3 ? o1 : pos == 0 ? o2 : o3;
+                    const float w3 = pos == 3 ? v : pos == 2 ? o1 : pos == 1 ? o2 : o3;
+                    float best = w0; int bi = 0;
+                    if (w1 > best) { best = w1; bi = 1; }
+                    if (w2 > best) { best = w2; bi = 2; }
+                    if (w3 > best) { best = w3; bi = 3; }
+                    if (pos == 0 && pvalid[t] && m < a.Mtot) {
+                        *at<float>(a.out, stack, ti, tj, pn[t], m, py[t], pxx[t]) = best;
+                        *at<uint8_t>(a.arg, stack, ti, tj, pn[t], m, py[t], pxx[t]) = (uint8_t)bi;
+                    }
+                } else {
+                    if (pvalid[t] && m < a.Mtot) *at<float>(a.out, stack, ti, tj, pn[t], m, py[t], pxx[t]) = v;
+                }
+            }
+        }
+    }
+}
+
+// ---- host side ------------------------------------------------------------------------------------------------
+namespace {
+
+struct TileChoice { int TI, TR, TC, tiles_x, tiles_y, tiles_i, npos; };
+
+// Largest rectangle of any stack decides the tile shape: whole rectangles of several images when they are
+// small, bands of rows otherwise, column blocks only for rectangles wider than a tile.
+TileChoice choose_tile(int rw, int rh, int batch, int cap /* pixels (or windows) per tile */, int S, int P)
+{
+    TileChoice c;
+    c.TC = rw <= cap ? rw : cap;
+    if (c.TC > 64) c.TC = 64;
+    c.tiles_x = (rw + c.TC - 1) / c.TC;
+    c.TC = (rw + c.tiles_x - 1) / c.tiles_x;
+    int rows = cap / c.TC; if (rows < 1) rows = 1;
+    if (rows >= rh) {
+        c.TR = rh; c.tiles_y = 1;
+        c.TI = cap / (c.TC * c.TR); if (c.TI < 1) c.TI = 1; if (c.TI > batch) c.TI = batch;
+    } else {
+        c.tiles_y = (rh + rows - 1) / rows;
+        c.TR = (rh + c.tiles_y - 1) / c.tiles_y;
+        c.TI = 1;
+    }
+    c.tiles_i = (batch + c.TI - 1) / c.TI;
+    c.npos = c.TI * (c.TR * S + 2 * P) * (c.TC * S + 2 * P);
+    // the staging loop handles at most 3*256 patch positions per workgroup
+    while (c.npos > 768) {
+        if (c.TI > 1) { --c.TI; c.tiles_i = (batch + c.TI - 1) / c.TI; }
+        else { ++c.tiles_y; c.TR = (rh + c.tiles_y - 1) / c.tiles_y; }
+        c.npos = c.TI * (c.TR * S + 2 * P) * (c.TC * S + 2 * P);
+    }
+    return c;
+}
+
+template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+void launch_m(MfmaConvArgs& a, int stacks, hipStream_t s)
+{
+    const int KK = K * K;
+    constexpr int kCK = K == 1 ? 32 : 8;
+    const int waves_m = a.Mtot >= 128 ? 4 : a.Mtot >= 64 ? 2 : 1;
+    const int BM = 32 * waves_m;
+    const int CS = a.TI * (a.TR * (POOL_OUT ? 2 : 1) + 2 * (K / 2)) * (a.TC * (POOL_OUT ? 2 : 1) + 2 * (K / 2)) + a.cs_pad;
+    const size_t lds = (size_t)(KK * kCK * BM + kCK * CS) * sizeof(float);
+    dim3 grid(a.tiles_x * a.tiles_y * a.tiles_i, (a.Mtot + BM - 1) / BM, stacks), block(256);
+    if (waves_m == 4) hipLaunchKernelGGL((k_conv_mfma<K, 4, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    else if (waves_m == 2) hipLaunchKernelGGL((k_conv_mfma<K, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((k_conv_mfma<K, 1, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+}
+
+void rect_max(const RectTab& rt, int N, int M, int& mw, int& mh)
+{
+    mw = 0; mh = 0;
+    for (int t = 0; t < M; ++t) mw = mw > rt.x1[t] - rt.x0[t] + 1 ? mw : rt.x1[t] - rt.x0[t] + 1;
+    for (int t = 0; t < N; ++t) mh = mh > rt.y1[t] - rt.y0[t] + 1 ? mh : rt.y1[t] - rt.y0[t] + 1;
+}
+
+}  // namespace
+
+bool mfma_conv_eligible(const ConvArgs& a, bool backward)
+{
+    if (a.bf16) return false;
+    const int Mtot = backward ? a.Cin : a.Cout, C = backward ? a.Cout : a.Cin;
+    return Mtot >= 16 && Mtot % 4 == 0 && C >= 8;
+}
+
+void prep_filter(const float* w, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s)
+{
+    const long long n = (long long)Cout * Cin * K * K;
+    hipLaunchKernelGGL(k_prep_filter, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w, wt_fwd, wt_bwd, Cout, Cin, K * K);
+}
+
+// Forward: a.rect = held rectangle at the unit's output boundary; a.inrect = extent of the input view per stack.
+void mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
+{
+    MfmaConvArgs a;
+    a.in = c.in; a.out = c.out; a.arg = c.arg; a.din = c.din; a.dout = c.dout; a.rect = c.rect;
+    for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
+    a.wt = wt; a.bias = (const float*)c.bias;
+    a.C = c.Cin; a.Mtot = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
+    int mw, mh; rect_max(c.rect, c.N, c.M, mw, mh);
+    const int S = c.pooled ? 2 : 1, P = c.K / 2;
+    const TileChoice tc = choose_tile(mw, mh, c.batch, c.pooled ? kBN / 4 : kBN, S, P);
+    a.TI = tc.TI; a.TR = tc.TR; a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_y = tc.tiles_y; a.tiles_i = tc.tiles_i;
+    a.cs_pad = 0;
+    const int stacks = c.N * c.M;
+    if (c.K == 3) { if (c.pooled) launch_m<3, true, false, false>(a, stacks, s); else launch_m<3, false, false, false>(a, stacks, s); }
+    else          { if (c.pooled) launch_m<1, true, false, false>(a, stacks, s); else launch_m<1, false, false, false>(a, stacks, s); }
+}
+
+// Backward data: a.rect = backward rectangle at the unit's input boundary; inrect = extent of the delta view
+// (at the unit's output boundary, pooled coordinates if the unit has a pool).
+void mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
+{
+    MfmaConvArgs a;
+    a.in = c.in; a.out = c.out; a.arg = c.arg; a.din = c.din; a.dout = c.dout; a.rect = c.rect;
+    for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
+    a.wt = wt; a.bias = nullptr;
+    a.C = c.Cout; a.Mtot = c.Cin; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
+    int mw, mh; rect_max(c.rect, c.N, c.M, mw, mh);
+    const TileChoice tc = choose_tile(mw, mh, c.batch, kBN, 1, c.K / 2);
+    a.TI = tc.TI; a.TR = tc.TR; a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_y = tc.tiles_y; a.tiles_i = tc.tiles_i;
+    a.cs_pad = 0;
+    const int stacks = c.N * c.M;
+    if (c.K == 3) { if (c.pooled) launch_m<3, false, true, true>(a, stacks, s); else launch_m<3, false, true, false>(a, stacks, s); }
+    else          { if (c.pooled) launch_m<1, false, true, true>(a, stacks, s); else launch_m<1, false, true, false>(a, stacks, s); }
+}
+
+}  // namespace ftp

@@ -239,6 +239,14 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
     const size_t pp0 = alloc(pp_bytes), pp1 = alloc(pp_bytes);
     for (int b = 1; b <= L; ++b)
         if (delta[b].kind == BUF_WS && delta[b].per_stack) delta[b].offset = delta[b].offset ? pp1 : pp0;
+    // relaid filters for the matrix-core kernels (fp32, two orders per convolution: forward and rotated)
+    for (Unit& u : p.units) {
+        if (u.kind != UNIT_CONV) continue;
+        const ftp_layer& ly = p.layers[u.layer];
+        const size_t bytes = (size_t)ly.cout * ly.cin * ly.k * ly.k * sizeof(float);
+        u.wt_fwd_offset = alloc(bytes);
+        u.wt_bwd_offset = alloc(bytes);
+    }
     p.workspace_bytes = std::max<size_t>(ws, 256);
 
     size_t poff = 0;

@@ -52,6 +52,7 @@ struct Unit {
     BufRef in_delta, out_delta;               // backward (in_delta lives at bo, out_delta at bi)
     size_t param_offset = 0;                  // first filter element in the parameter vector
     size_t bias_offset = 0;
+    size_t wt_fwd_offset = 0, wt_bwd_offset = 0;   // relaid filter copies in the workspace (bytes)
 };
 
 struct Plan {
