@@ -268,7 +268,12 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             ConvArgs a = conv_args(p, u, ub, weights, nullptr);
             a.partial = wgrad_partials;
             a.rect = make_rect(p, u.group, FTP_RECT_OWN, u.layer + 1);
-            rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { direct_wgrad(a, s); });
+            if (use_mfma() && mfma_wgrad_eligible(a)) {
+                float* scratch = (float*)((char*)workspace + p.wgrad_scratch_offset);
+                rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { mfma_wgrad(a, scratch, s); });
+            } else {
+                rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { direct_wgrad(a, s); });
+            }
             if (rc != FTP_OK) return rc;
             a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
             if (use_mfma() && mfma_conv_eligible(a, true)) {

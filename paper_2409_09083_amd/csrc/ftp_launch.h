@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include "ftp_device.h"
+#include "ftp_plan.h"
 
 namespace ftp {
 
@@ -53,6 +54,23 @@ bool mfma_conv_eligible(const ConvArgs& a, bool backward);
 void prep_filter(const float* w, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s);
 void mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
 void mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
+
+// Kernel argument block of the matrix-core filter gradient.
+struct MfmaWgradArgs {
+    View in, din, out, arg;
+    RectTab own;                                    // owned rectangle at the convolution output (before the pool)
+    float* partial;                                 // [stacks][n_params]
+    float* scratch;                                 // [stacks][splits][Cout*Cin*K*K] when splits > 1
+    long long n_params, w_off;
+    int Cin, Cout, Hc, Wc;
+    int splits;                                     // batch shares per stack
+    int PK;                                         // pixels staged per step
+    float slope;
+    int M, batch;
+};
+
+bool mfma_wgrad_eligible(const ConvArgs& a);
+void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s);
 
 void direct_conv_fwd(const ConvArgs& a, hipStream_t s);
 void direct_conv_bwd_data(const ConvArgs& a, hipStream_t s);

@@ -247,6 +247,16 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
         u.wt_fwd_offset = alloc(bytes);
         u.wt_bwd_offset = alloc(bytes);
     }
+    {
+        size_t scratch = 0;
+        for (const Unit& u : p.units) {
+            if (u.kind != UNIT_CONV) continue;
+            const ftp_layer& ly = p.layers[u.layer];
+            const int shares = wgrad_batch_shares(ly.cout, ly.cin, N * M, batch);
+            if (shares > 1) scratch = std::max(scratch, stacks * shares * (size_t)ly.cout * ly.cin * ly.k * ly.k * sizeof(float));
+        }
+        p.wgrad_scratch_offset = alloc(scratch);
+    }
     p.workspace_bytes = std::max<size_t>(ws, 256);
 
     size_t poff = 0;

@@ -67,9 +67,20 @@ struct Plan {
     std::vector<BufRef> act, arg, delta;      // home of each boundary's activation / pool winners / delta
     std::vector<int> home_group;              // group whose rectangles address a per-stack boundary
     size_t workspace_bytes = 0, n_params = 0;
+    size_t wgrad_scratch_offset = 0;          // batch shares of one layer's partial gradients (bytes)
     size_t split[4] = {0, 0, 0, 0};
     double useful_macs = 0, executed_macs = 0, halo_bytes[2] = {0, 0};
 };
+
+// Number of batch shares the matrix-core filter-gradient kernel splits one stack's reduction into, so
+// that layers with few (co, ci) blocks still fill the chip; the shares are summed in a fixed order.
+inline int wgrad_batch_shares(int cout, int cin, int stacks, int batch)
+{
+    const int blocks = ((cout + 63) / 64) * ((cin + 63) / 64) * stacks;
+    int shares = (1024 + blocks - 1) / blocks;
+    if (shares > batch) shares = batch;
+    return shares < 1 ? 1 : shares;
+}
 
 int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int in_h, int in_w,
                int N, int M, const int32_t* group_ends, int n_groups, ftp_dtype dtype, ftp_plan_s** out);
