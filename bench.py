@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--config", default="cfg4", choices=["tiny", "cfg2_perblock", "cfg2_fused", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--group-size", type=int, default=4, help="layers per group (cfg5 sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-kernel", action="store_true", help="print the per-kernel timing table to stderr")
     ap.add_argument("--cpu-images", type=int, default=0, help="images for the oracle timing (0 = automatic)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -80,6 +81,11 @@ def main():
     F.ftp_profile(s.plan, False)
     recs = F.ftp_profile_read(s.plan)
 
+    if args.per_kernel:
+        for r in sorted(recs, key=lambda r: (r["layer"], r["pass"])):
+            ms = r["total_ms"] / r["launches"]
+            print("%-14s layer %2d  %8.3f ms  %7.2f TFLOP/s  %7.1f GB/s" % (
+                r["pass"], r["layer"], ms, r["flops_per_launch"] / ms / 1e9, r["bytes_per_launch"] / ms / 1e6), file=sys.stderr)
     ms_per_step = dt * 1e3 / args.steps
     images_per_s = cfg.batch * args.steps / dt
 

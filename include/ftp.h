@@ -37,7 +37,7 @@ typedef struct ftp_plan_s ftp_plan_t;
 
 typedef enum { FTP_CONV = 0, FTP_MAXPOOL = 1 } ftp_layer_kind;
 typedef enum { FTP_F32 = 0, FTP_BF16 = 1 } ftp_dtype;
-typedef enum { FTP_RECT_OWN = 0, FTP_RECT_FWD = 1, FTP_RECT_BWD = 2, FTP_RECT_HELD = 3 } ftp_rect_kind;
+typedef enum { FTP_RECT_OWN = 0, FTP_RECT_FWD = 1, FTP_RECT_BWD = 2 } ftp_rect_kind;
 
 typedef enum {
     FTP_OK = 0,
@@ -61,9 +61,9 @@ typedef struct {
 
 /* Builds the partition plan (Sec. 4.2): map sizes, and per group and tile the owned rectangle
  * (equal split of the group's output map, projected back through the strides), the forward
- * rectangles of Eq. (1) walked from e to s, the backward (delta) rectangles of Eq. (2) walked
- * from s to e, and the held rectangles the forward pass keeps for back-propagation; all clamped
- * to the map.  Host only, integer only; touches no GPU.
+ * rectangles of Eq. (1) walked from e to s (what a stack computes and keeps), and the backward
+ * (delta) rectangles of Eq. (2) walked from s to e; all clamped to the map.
+ * Host only, integer only; touches no GPU.
  *   layers[n_layers]         primitive layers, in order
  *   batch, in_c, in_h, in_w  shape of the input map x
  *   grid_rows N, grid_cols M tile grid (1..16 each)
@@ -107,9 +107,11 @@ int ftp_plan_work(const ftp_plan_t* plan, double* useful_macs, double* executed_
  *   [6] rectangle kind whose top-left corner is the origin of each stack's slot (per-stack only)
  *   [7] group whose rectangles apply (per-stack only)
  * A per-stack buffer is laid out [stack][image][channel][slot height][slot width]; a stack's
- * rectangle occupies the top-left part of its slot.  Winners are one byte per element (index
- * 2*dy+dx of the first maximum in the window); activations and deltas have the plan's type. */
-typedef enum { FTP_BUF_ACT = 0, FTP_BUF_ARG = 1, FTP_BUF_DELTA = 2 } ftp_buf_kind;
+ * rectangle occupies the top-left part of its slot.  Activations and deltas have the plan's type.
+ * FTP_BUF_MASK is the decision code back-propagation reads, one byte per element of a whole map,
+ * written by the owning stack: bit 0 = activation > 0, bits 1-2 = index 2*dy+dx of the first
+ * maximum of the 2x2 window (pooled boundaries only). */
+typedef enum { FTP_BUF_ACT = 0, FTP_BUF_MASK = 1, FTP_BUF_DELTA = 2 } ftp_buf_kind;
 int ftp_plan_buffer(const ftp_plan_t* plan, int32_t boundary, ftp_buf_kind which, int64_t out[8]);
 
 /* Forward pass of all groups (Sec. 4.1 forward, Sec. 4.2 fusing and grouping).
@@ -123,11 +125,11 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
 
 /* Back-propagation of all groups in reverse (Sec. 4.1 delta and filter gradients).
  *   dy        device, dLoss/dy, shape of y
- *   x, y      device, the input and output of the preceding ftp_forward on the same workspace
+ *   x         device, the input of the preceding ftp_forward on the same workspace
  *   dx        device, receives dLoss/dx, shape of x
  *   wgrad_partials device, fp32 [N*M][n_params]: one partial parameter gradient per stack, summed
  *             over the batch and over the output pixels the stack owns; overwritten, not accumulated */
-int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const void* y,
+int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x,
                  const void* const* weights, void* workspace, void* dx,
                  float* wgrad_partials, void* stream);
 

@@ -8,24 +8,23 @@ spans, at the input of layer l ("boundary" l), the inclusive rectangle
 (x1, y1)-(x2, y2); layer l has kernel K_l and stride S_l; a group (s, e) starts at
 the input of layer s and ends at the input of layer e.
 
-Four families per group, all clamped to the map after every step:
+Three families per group, all clamped to the map after every step:
   OWN  O_l : O_e is the equal split of the group's output map (tile index t of n parts
              over a length W owns [floor(t*W/n), floor((t+1)*W/n) - 1]); O_{l-1} is O_l
              scaled by the stride only (no kernel term).  A disjoint cover of every map.
-  FWD  F_l : F_e = O_e, then Eq. (1a-d) walked from e down to s.
-  BWD  B_l : B_s = O_s, then Eq. (2a-d) walked from s up to e.
-  HELD H_l : what the forward pass computes and keeps so that back-propagation finds the
-             activation signs / pool winners on B_l without communication inside the
-             group: H_e = O_e; H_l = Eq1(H_{l+1}) united with B_l at every interior
-             boundary that is materialised (a pool directly behind a convolution of the
-             same group is evaluated inside that convolution's epilogue, so the
-             boundary between them is not).
+  FWD  F_l : F_e = O_e, then Eq. (1a-d) walked from e down to s: what the forward pass of
+             the tile computes and keeps.
+  BWD  B_l : B_s = O_s, then Eq. (2a-d) walked from s up to e: where the tile holds deltas.
+B_l can stick out of F_l (second half of a group).  The activation signs and pool winners
+back-propagation needs there are one small code per element; like the delta halo they are
+collected from the owning neighbours at the synchronisation point where the backward pass
+enters the group, so nothing is exchanged inside a group.
 For a 2x2/2 pool the exact dependence is used in both directions (Eq. (1) and (2) are
 stated for convolutions): back a' = 2a, b' = 2b + 1; forth a' = floor(a/2), b' = floor(b/2).
 """
 
 CONV, MAXPOOL = 0, 1
-OWN, FWD, BWD, HELD = 0, 1, 2, 3
+OWN, FWD, BWD = 0, 1, 2
 
 
 def map_sizes(layers, in_h, in_w):
@@ -82,13 +81,6 @@ def eq2_forth(r, ly):
     return (x1 // 2, y1 // 2, x2 // 2, y2 // 2)
 
 
-def materialised(layers, s, l):
-    """False where boundary l lies between a convolution and the pool fused behind it."""
-    if l >= len(layers) or l <= s:
-        return True
-    return not (layers[l].kind == MAXPOOL and layers[l - 1].kind == CONV)
-
-
 def group_rects(layers, sizes, s, e, N, M, i, j):
     """{kind: {l: (x1,y1,x2,y2)}} for tile (i,j) of group (s,e), boundaries s..e."""
     He, We = sizes[e]
@@ -102,13 +94,7 @@ def group_rects(layers, sizes, s, e, N, M, i, j):
     B = {s: O[s]}
     for l in range(s, e):
         B[l + 1] = _clamp(eq2_forth(B[l], layers[l]), sizes[l + 1])
-    Hd = {e: O[e]}
-    for l in range(e - 1, s - 1, -1):
-        r = _clamp(eq1_back(Hd[l + 1], layers[l]), sizes[l])
-        if s < l < e and materialised(layers, s, l):
-            r = _union(r, B[l])
-        Hd[l] = r
-    return {OWN: O, FWD: F, BWD: B, HELD: Hd}
+    return {OWN: O, FWD: F, BWD: B}
 
 
 def groups_from_ends(group_ends):

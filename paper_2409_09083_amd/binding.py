@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libftp.so")
 
 FTP_CONV, FTP_MAXPOOL = 0, 1
 FTP_F32, FTP_BF16 = 0, 1
-FTP_RECT_OWN, FTP_RECT_FWD, FTP_RECT_BWD, FTP_RECT_HELD = 0, 1, 2, 3
+FTP_RECT_OWN, FTP_RECT_FWD, FTP_RECT_BWD = 0, 1, 2
 FTP_OK, FTP_EINVAL, FTP_EUNSUPPORTED, FTP_EGRID, FTP_EGROUPS, FTP_ENOMEM, FTP_EHIP, FTP_ECHANNELS = 0, -1, -2, -3, -4, -5, -6, -7
 
 
@@ -71,7 +71,7 @@ def _load():
                                   ctypes.POINTER(ctypes.c_double)]
     lib.ftp_plan_buffer.argtypes = [vp, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
     lib.ftp_forward.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp]
-    lib.ftp_backward.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp, vp, vp]
+    lib.ftp_backward.argtypes = [vp, vp, vp, ctypes.POINTER(vp), vp, vp, vp, vp]
     lib.ftp_reduce_wgrad.argtypes = [vp, vp, vp, vp]
     lib.ftp_profile.argtypes = [vp, i32]
     lib.ftp_profile_read.argtypes = [vp, ctypes.POINTER(ftp_kernel_time), i32, ctypes.POINTER(i32)]
@@ -154,7 +154,7 @@ def ftp_plan_work(plan):
     return {"useful_macs": u.value, "executed_macs": e.value, "halo_bytes_fwd": halo[0], "halo_bytes_bwd": halo[1]}
 
 
-FTP_BUF_ACT, FTP_BUF_ARG, FTP_BUF_DELTA = 0, 1, 2
+FTP_BUF_ACT, FTP_BUF_MASK, FTP_BUF_DELTA = 0, 1, 2
 
 
 def ftp_plan_buffer(plan, boundary, which):
@@ -169,9 +169,9 @@ def ftp_forward(plan, x, weights, biases, workspace, y, stream=0):
     _check(_lib.ftp_forward(plan, x, _ptr_array(weights, n), _ptr_array(biases, n), workspace, y, stream), "ftp_forward")
 
 
-def ftp_backward(plan, dy, x, y, weights, workspace, dx, wgrad_partials, stream=0):
+def ftp_backward(plan, dy, x, weights, workspace, dx, wgrad_partials, stream=0):
     n = len(weights)
-    _check(_lib.ftp_backward(plan, dy, x, y, _ptr_array(weights, n), workspace, dx, wgrad_partials, stream), "ftp_backward")
+    _check(_lib.ftp_backward(plan, dy, x, _ptr_array(weights, n), workspace, dx, wgrad_partials, stream), "ftp_backward")
 
 
 def ftp_reduce_wgrad(plan, wgrad_partials, wgrad, stream=0):

@@ -73,7 +73,7 @@ ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void*
     const ftp_layer& ly = p.layers[u.layer];
     a.in = make_view(p, u.in_act, u.group, u.bi, ub);
     a.out = make_view(p, u.out_act, u.group, u.bo, ub);
-    a.arg = make_view(p, u.out_arg, u.group, u.bo, ub);
+    a.mask = make_view(p, u.out_mask, u.group, u.bo, ub);
     a.din = make_view(p, u.in_delta, u.group, u.bo, ub);
     a.dout = make_view(p, u.out_delta, u.group, u.bi, ub);
     a.w = weights[u.layer];
@@ -94,7 +94,7 @@ PoolArgs pool_args(const Plan& p, const Unit& u, const UserBufs& ub)
     PoolArgs a;
     a.in = make_view(p, u.in_act, u.group, u.bi, ub);
     a.out = make_view(p, u.out_act, u.group, u.bo, ub);
-    a.arg = make_view(p, u.out_arg, u.group, u.bo, ub);
+    a.mask = make_view(p, u.out_mask, u.group, u.bo, ub);
     a.din = make_view(p, u.in_delta, u.group, u.bo, ub);
     a.dout = make_view(p, u.out_delta, u.group, u.bi, ub);
     a.C = p.C[u.bi]; a.N = p.N; a.M = p.M; a.batch = p.batch;
@@ -163,7 +163,7 @@ int ftp_plan_rect(const ftp_plan_t* plan, int32_t group, int32_t boundary, int32
     if (!plan || !out) return FTP_EINVAL;
     const Plan& p = plan->p;
     if (group < 0 || group >= (int)p.groups.size() || ti < 0 || ti >= p.N || tj < 0 || tj >= p.M) return FTP_EINVAL;
-    if ((int)kind < 0 || (int)kind > FTP_RECT_HELD) return FTP_EINVAL;
+    if ((int)kind < 0 || (int)kind > FTP_RECT_BWD) return FTP_EINVAL;
     const GroupRects& g = p.groups[group];
     if (boundary < g.s || boundary > g.e) return FTP_EINVAL;
     const Seg sx = g.at(kind, boundary, 0, tj), sy = g.at(kind, boundary, 1, ti);
@@ -210,7 +210,7 @@ int ftp_plan_buffer(const ftp_plan_t* plan, int32_t boundary, ftp_buf_kind which
     const BufRef* b = nullptr;
     switch (which) {
         case FTP_BUF_ACT: b = &p.act[boundary]; break;
-        case FTP_BUF_ARG: b = &p.arg[boundary]; break;
+        case FTP_BUF_MASK: b = &p.mask[boundary]; break;
         case FTP_BUF_DELTA: b = &p.delta[boundary]; break;
         default: return FTP_EINVAL;
     }
@@ -232,7 +232,8 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
     for (const Unit& u : p.units) {
         if (u.kind == UNIT_CONV) {
             ConvArgs a = conv_args(p, u, ub, weights, biases);
-            a.rect = make_rect(p, u.group, FTP_RECT_HELD, u.bo);
+            a.rect = make_rect(p, u.group, FTP_RECT_FWD, u.bo);
+            a.own = make_rect(p, u.group, FTP_RECT_OWN, u.bo);
             if (use_mfma() && mfma_conv_eligible(a, false)) {
                 float* wt = (float*)((char*)workspace + u.wt_fwd_offset);
                 const RectTab ext = view_extent(p, u.in_act, u.group, u.bi);
@@ -245,7 +246,8 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
             }
         } else {
             PoolArgs a = pool_args(p, u, ub);
-            a.rect = make_rect(p, u.group, FTP_RECT_HELD, u.bo);
+            a.rect = make_rect(p, u.group, FTP_RECT_FWD, u.bo);
+            a.own = make_rect(p, u.group, FTP_RECT_OWN, u.bo);
             rc = timed(plan, FTP_PASS_POOL_FWD, u.layer, s, [&] { pool_fwd(a, s); });
         }
         if (rc != FTP_OK) return rc;
@@ -253,15 +255,15 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
     return FTP_OK;
 }
 
-int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const void* y, const void* const* weights,
+int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const void* const* weights,
                  void* workspace, void* dx, float* wgrad_partials, void* stream)
 {
-    if (!plan || !dy || !x || !y || !workspace || !dx || !wgrad_partials) return FTP_EINVAL;
+    if (!plan || !dy || !x || !workspace || !dx || !wgrad_partials) return FTP_EINVAL;
     const Plan& p = plan->p;
     int rc = check_weights(p, weights, nullptr);
     if (rc != FTP_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
-    UserBufs ub; ub.x = x; ub.y = const_cast<void*>(y); ub.dy = dy; ub.dx = dx; ub.ws = workspace;
+    UserBufs ub; ub.x = x; ub.dy = dy; ub.dx = dx; ub.ws = workspace;
     for (int i = (int)p.units.size() - 1; i >= 0; --i) {
         const Unit& u = p.units[i];
         if (u.kind == UNIT_CONV) {

@@ -8,26 +8,28 @@ namespace ftp {
 
 // ---- delta at the convolution output ---------------------------------------------------------------
 // dZ(q) = delta * leaky'(Y); with a pool behind the convolution the delta sits at pooled resolution
-// and reaches only the window's recorded winner (Sec. 4.1, back-propagation of the delta).
+// and reaches only the window's recorded winner (Sec. 4.1, back-propagation of the delta).  Sign and
+// winner come from the decision code the owning stack wrote in the forward pass.
 template <typename T, bool POOL>
-__device__ __forceinline__ float delta_z(const View& din, const View& yv, const View& arg, int stack, int ti, int tj,
+__device__ __forceinline__ float delta_z(const View& din, const View& mask, int stack, int ti, int tj,
                                          int n, int co, int qy, int qx, float slope)
 {
-    int sy = qy, sx = qx;
-    if (POOL) {
-        sy = qy >> 1; sx = qx >> 1;
-        const uint8_t a = *at<uint8_t>(arg, stack, ti, tj, n, co, sy, sx);
-        if (a != (uint8_t)(((qy & 1) << 1) | (qx & 1))) return 0.0f;
-    }
+    const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
+    const uint8_t m = *at<uint8_t>(mask, stack, ti, tj, n, co, sy, sx);
+    if (POOL && ((m >> 1) & 3) != (((qy & 1) << 1) | (qx & 1))) return 0.0f;
     const float g = ld(at<T>(din, stack, ti, tj, n, co, sy, sx));
-    const float y = ld(at<T>(yv, stack, ti, tj, n, co, sy, sx));
-    return y > 0.0f ? g : slope * g;
+    return (m & 1) ? g : slope * g;
+}
+
+__device__ __forceinline__ bool in_rect(const RectTab& r, int ti, int tj, int y, int x)
+{
+    return y >= r.y0[ti] && y <= r.y1[ti] && x >= r.x0[tj] && x <= r.x1[tj];
 }
 
 // ---- forward: convolution + leaky ReLU (+ 2x2 max-pool) ------------------------------------------------
 template <typename T, int K, bool POOL, int COB>
 __global__ void __launch_bounds__(64)
-k_conv_fwd_direct(View in, View out, View arg, RectTab rt, const T* __restrict__ w, const T* __restrict__ bias,
+k_conv_fwd_direct(View in, View out, View mask, RectTab rt, RectTab own, const T* __restrict__ w, const T* __restrict__ bias,
                   int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
@@ -86,16 +88,16 @@ k_conv_fwd_direct(View in, View out, View arg, RectTab rt, const T* __restrict__
                 const float v = stored(leaky(acc[j][d] + b, slope), (const T*)nullptr);
                 if (v > best) { best = v; bi = d; }        // first maximum in window order wins
             }
-            *at<uint8_t>(arg, stack, ti, tj, n, co, oy, ox) = (uint8_t)bi;
         }
         st(at<T>(out, stack, ti, tj, n, co, oy, ox), best);
+        if (in_rect(own, ti, tj, oy, ox)) *at<uint8_t>(mask, stack, ti, tj, n, co, oy, ox) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
     }
 }
 
 // ---- backward: delta at the convolution input -------------------------------------------------------
 template <typename T, int K, bool POOL, int CIB>
 __global__ void __launch_bounds__(64)
-k_conv_bwd_data_direct(View din, View yv, View arg, View dout, RectTab rt, const T* __restrict__ w,
+k_conv_bwd_data_direct(View din, View mask, View dout, RectTab rt, const T* __restrict__ w,
                        int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
@@ -116,7 +118,7 @@ k_conv_bwd_data_direct(View din, View yv, View arg, View dout, RectTab rt, const
             for (int kx = 0; kx < K; ++kx) {
                 const int qy = iy + P - ky, qx = ix + P - kx;
                 if (qy < 0 || qy >= Hc || qx < 0 || qx >= Wc) continue;
-                const float dz = delta_z<T, POOL>(din, yv, arg, stack, ti, tj, n, co, qy, qx, slope);
+                const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx, slope);
 #pragma unroll
                 for (int j = 0; j < CIB; ++j) {
                     const int ci = ci0 + j;
@@ -134,7 +136,7 @@ k_conv_bwd_data_direct(View din, View yv, View arg, View dout, RectTab rt, const
 // Lanes are combined with wavefront shuffles, waves through LDS in a fixed order: deterministic.
 template <typename T, int K, bool POOL>
 __global__ void __launch_bounds__(256)
-k_wgrad_direct(View xin, View din, View yv, View arg, RectTab own, float* __restrict__ partial, long long n_params,
+k_wgrad_direct(View xin, View din, View mask, RectTab own, float* __restrict__ partial, long long n_params,
                long long w_off, long long b_off, int has_bias, int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
 {
     const int ci = blockIdx.x, co = blockIdx.y, stack = blockIdx.z;
@@ -148,7 +150,7 @@ k_wgrad_direct(View xin, View din, View yv, View arg, RectTab own, float* __rest
     for (int it = threadIdx.x; it < items; it += 256) {
         const int n = it / px, r = it - n * px;
         const int qy = own.y0[ti] + r / rw, qx = own.x0[tj] + r % rw;
-        const float dz = delta_z<T, POOL>(din, yv, arg, stack, ti, tj, n, co, qy, qx, slope);
+        const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx, slope);
         acc[KK] += dz;
 #pragma unroll
         for (int ky = 0; ky < K; ++ky)
@@ -181,7 +183,7 @@ k_wgrad_direct(View xin, View din, View yv, View arg, RectTab own, float* __rest
 // ---- lone 2x2 max-pool ---------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(64)
-k_pool_fwd(View in, View out, View arg, RectTab rt, int C, int M, int batch)
+k_pool_fwd(View in, View out, View mask, RectTab rt, RectTab own, int C, int M, int batch)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
@@ -198,12 +200,12 @@ k_pool_fwd(View in, View out, View arg, RectTab rt, int C, int M, int batch)
         if (v > best) { best = v; bi = d; }
     }
     st(at<T>(out, stack, ti, tj, n, c, oy, ox), best);
-    *at<uint8_t>(arg, stack, ti, tj, n, c, oy, ox) = (uint8_t)bi;
+    if (in_rect(own, ti, tj, oy, ox)) *at<uint8_t>(mask, stack, ti, tj, n, c, oy, ox) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
 }
 
 template <typename T>
 __global__ void __launch_bounds__(64)
-k_pool_bwd(View din, View arg, View dout, RectTab rt, int C, int M, int batch)
+k_pool_bwd(View din, View mask, View dout, RectTab rt, int C, int M, int batch)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
@@ -212,7 +214,7 @@ k_pool_bwd(View din, View arg, View dout, RectTab rt, int C, int M, int batch)
     if (pid >= rw * rh) return;
     const int iy = rt.y0[ti] + pid / rw, ix = rt.x0[tj] + pid % rw;
     const int c = blockIdx.y;
-    const uint8_t a = *at<uint8_t>(arg, stack, ti, tj, n, c, iy >> 1, ix >> 1);
+    const uint8_t a = (*at<uint8_t>(mask, stack, ti, tj, n, c, iy >> 1, ix >> 1) >> 1) & 3;
     const float g = (a == (uint8_t)(((iy & 1) << 1) | (ix & 1))) ? ld(at<T>(din, stack, ti, tj, n, c, iy >> 1, ix >> 1)) : 0.0f;
     st(at<T>(dout, stack, ti, tj, n, c, iy, ix), g);
 }
@@ -254,7 +256,7 @@ void conv_fwd_t(const ConvArgs& a, hipStream_t s)
     constexpr int COB = 8;
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cout + COB - 1) / COB, a.N * a.M * a.batch), block(64);
     const T* w = (const T*)a.w; const T* b = (const T*)a.bias;
-#define FTP_FWD(KK, PL) hipLaunchKernelGGL((k_conv_fwd_direct<T, KK, PL, COB>), grid, block, 0, s, a.in, a.out, a.arg, a.rect, w, b, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+#define FTP_FWD(KK, PL) hipLaunchKernelGGL((k_conv_fwd_direct<T, KK, PL, COB>), grid, block, 0, s, a.in, a.out, a.mask, a.rect, a.own, w, b, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
     if (a.K == 3) { if (a.pooled) FTP_FWD(3, true); else FTP_FWD(3, false); }
     else          { if (a.pooled) FTP_FWD(1, true); else FTP_FWD(1, false); }
 #undef FTP_FWD
@@ -266,7 +268,7 @@ void conv_bwd_data_t(const ConvArgs& a, hipStream_t s)
     constexpr int CIB = 8;
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cin + CIB - 1) / CIB, a.N * a.M * a.batch), block(64);
     const T* w = (const T*)a.w;
-#define FTP_BWD(KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, PL, CIB>), grid, block, 0, s, a.din, a.out, a.arg, a.dout, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+#define FTP_BWD(KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, PL, CIB>), grid, block, 0, s, a.din, a.mask, a.dout, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
     if (a.K == 3) { if (a.pooled) FTP_BWD(3, true); else FTP_BWD(3, false); }
     else          { if (a.pooled) FTP_BWD(1, true); else FTP_BWD(1, false); }
 #undef FTP_BWD
@@ -276,7 +278,7 @@ template <typename T>
 void wgrad_t(const ConvArgs& a, hipStream_t s)
 {
     dim3 grid(a.Cin, a.Cout, a.N * a.M), block(256);
-#define FTP_WG(KK, PL) hipLaunchKernelGGL((k_wgrad_direct<T, KK, PL>), grid, block, 0, s, a.in, a.din, a.out, a.arg, a.rect, a.partial, a.n_params, a.w_off, a.b_off, a.has_bias, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+#define FTP_WG(KK, PL) hipLaunchKernelGGL((k_wgrad_direct<T, KK, PL>), grid, block, 0, s, a.in, a.din, a.mask, a.rect, a.partial, a.n_params, a.w_off, a.b_off, a.has_bias, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
     if (a.K == 3) { if (a.pooled) FTP_WG(3, true); else FTP_WG(3, false); }
     else          { if (a.pooled) FTP_WG(1, true); else FTP_WG(1, false); }
 #undef FTP_WG
@@ -291,15 +293,15 @@ void direct_wgrad(const ConvArgs& a, hipStream_t s) { if (a.bf16) wgrad_t<bf16_t
 void pool_fwd(const PoolArgs& a, hipStream_t s)
 {
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
-    if (a.bf16) hipLaunchKernelGGL(k_pool_fwd<bf16_t>, grid, block, 0, s, a.in, a.out, a.arg, a.rect, a.C, a.M, a.batch);
-    else        hipLaunchKernelGGL(k_pool_fwd<float>, grid, block, 0, s, a.in, a.out, a.arg, a.rect, a.C, a.M, a.batch);
+    if (a.bf16) hipLaunchKernelGGL(k_pool_fwd<bf16_t>, grid, block, 0, s, a.in, a.out, a.mask, a.rect, a.own, a.C, a.M, a.batch);
+    else        hipLaunchKernelGGL(k_pool_fwd<float>, grid, block, 0, s, a.in, a.out, a.mask, a.rect, a.own, a.C, a.M, a.batch);
 }
 
 void pool_bwd(const PoolArgs& a, hipStream_t s)
 {
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
-    if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.arg, a.dout, a.rect, a.C, a.M, a.batch);
-    else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.arg, a.dout, a.rect, a.C, a.M, a.batch);
+    if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.mask, a.dout, a.rect, a.C, a.M, a.batch);
+    else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.mask, a.dout, a.rect, a.C, a.M, a.batch);
 }
 
 void reduce_wgrad(const float* partial, float* wgrad, long long n_params, int stacks, hipStream_t s)

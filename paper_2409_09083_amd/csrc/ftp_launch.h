@@ -8,14 +8,16 @@ namespace ftp {
 
 // One convolution unit (convolution + leaky ReLU, optionally with the 2x2 pool behind it).
 // Which fields a pass reads:
-//   forward        in (activation at the input), out (activation at the output), arg (pool winners), rect = held
-//                  rectangle at the output boundary
-//   backward data  din (delta at the output boundary), out (activation there: sign), arg, dout (delta at the input),
+//   forward        in (activation at the input), out (activation at the output), mask (decision codes at the
+//                  output boundary, written for owned pixels), rect = forward rectangle at the output boundary,
+//                  own = owned rectangle there
+//   backward data  din (delta at the output boundary), mask, dout (delta at the input),
 //                  rect = backward rectangle at the input boundary
-//   filter grad    in, din, out, arg, rect = owned rectangle at the convolution output (before the pool)
+//   filter grad    in, din, mask, rect = owned rectangle at the convolution output (before the pool)
+// Decision code: bit 0 = activation > 0, bits 1-2 = winner 2*dy+dx of the 2x2 window (pooled units).
 struct ConvArgs {
-    View in, out, arg, din, dout;
-    RectTab rect;
+    View in, out, mask, din, dout;
+    RectTab rect, own;
     const void* w = nullptr;        // filter, OIHW
     const void* bias = nullptr;
     float* partial = nullptr;       // [stacks][n_params]
@@ -30,15 +32,16 @@ struct ConvArgs {
 };
 
 struct PoolArgs {
-    View in, out, arg, din, dout;
-    RectTab rect;
+    View in, out, mask, din, dout;
+    RectTab rect, own;
     int C = 0, N = 1, M = 1, batch = 1, bf16 = 0;
 };
 
 // Kernel argument block of the matrix-core convolution (forward and delta back-propagation).
 struct MfmaConvArgs {
-    View in, out, arg, din, dout;
+    View in, out, mask, din, dout;
     RectTab rect;                                   // output rectangle each stack computes
+    RectTab own;                                    // forward: owned part of it (decision codes are written there)
     int ix0[kTabGrid], ix1[kTabGrid], iy0[kTabGrid], iy1[kTabGrid];   // extent of the input view per tile column / row
     const float* wt;                                // relaid filter [tap][reduction channel][output channel]
     const float* bias;
@@ -57,7 +60,7 @@ void mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* w
 
 // Kernel argument block of the matrix-core filter gradient.
 struct MfmaWgradArgs {
-    View in, din, out, arg;
+    View in, din, mask;
     RectTab own;                                    // owned rectangle at the convolution output (before the pool)
     float* partial;                                 // [stacks][n_params]
     float* scratch;                                 // [stacks][splits][Cout*Cin*K*K] when splits > 1

@@ -65,7 +65,7 @@ k_conv_mfma(MfmaConvArgs a)
     // ---- per-lane pixel of each 32-pixel tile --------------------------------------------------------
     int baseB[NT];
     int pn[NT], py[NT], pxx[NT];                      // image, output row, output column (pooled coordinates if POOL_OUT)
-    bool pvalid[NT];
+    bool pvalid[NT], powned[NT];                      // inside the stack's rectangle / inside its owned part
     const int per_img = a.TR * a.TC;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -75,6 +75,7 @@ k_conv_mfma(MfmaConvArgs a)
         const int yl = rem / a.TC, xl = rem - yl * a.TC;
         const bool v = il < a.TI && n0 + il < a.batch && oy0 + yl <= y1 && ox0 + xl <= x1;
         pvalid[t] = v; pn[t] = n0 + il; py[t] = oy0 + yl; pxx[t] = ox0 + xl;
+        powned[t] = v && !DELTA_IN && py[t] >= a.own.y0[ti] && py[t] <= a.own.y1[ti] && pxx[t] >= a.own.x0[tj] && pxx[t] <= a.own.x1[tj];
         const int base = v ? il * IS + (yl * S + (pos >> 1)) * PW + xl * S + (pos & 1) : 0;
         baseB[t] = base + hi * CS;
     }
@@ -84,13 +85,12 @@ k_conv_mfma(MfmaConvArgs a)
     constexpr int MAXPOS = 3;
     const int npos = a.TI * IS;
     long long goff[MAXPOS];        // element offset in the input view (channel 0); -1: zero padding / outside
-    long long goff2[MAXPOS];       // DELTA_IN: offset in the activation view
-    long long goff3[MAXPOS];       // DELTA_IN && POOL_IN: offset in the winner view
+    long long goff2[MAXPOS];       // DELTA_IN: offset in the decision-code map
     int pcode[MAXPOS];
 #pragma unroll
     for (int j = 0; j < MAXPOS; ++j) {
         const int s = tid + j * 256;
-        goff[j] = -1; goff2[j] = 0; goff3[j] = 0; pcode[j] = 0;
+        goff[j] = -1; goff2[j] = 0; pcode[j] = 0;
         if (s < npos) {
             const int il = s / IS, rem = s - il * IS;
             const int r = rem / PW, c = rem - r * PW;
@@ -104,11 +104,8 @@ k_conv_mfma(MfmaConvArgs a)
                     const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
                     if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
                         goff[j] = (long long)stack * a.din.ss + (long long)n * a.din.ns + (long long)(sy - a.din.y0[ti]) * a.din.pitch + (sx - a.din.x0[tj]);
-                        goff2[j] = (long long)stack * a.out.ss + (long long)n * a.out.ns + (long long)(sy - a.out.y0[ti]) * a.out.pitch + (sx - a.out.x0[tj]);
-                        if (POOL_IN) {
-                            goff3[j] = (long long)stack * a.arg.ss + (long long)n * a.arg.ns + (long long)(sy - a.arg.y0[ti]) * a.arg.pitch + (sx - a.arg.x0[tj]);
-                            pcode[j] = ((gy & 1) << 1) | (gx & 1);
-                        }
+                        goff2[j] = (long long)stack * a.mask.ss + (long long)n * a.mask.ns + (long long)(sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]);
+                        if (POOL_IN) pcode[j] = ((gy & 1) << 1) | (gx & 1);
                     }
                 }
             }
@@ -146,12 +143,10 @@ k_conv_mfma(MfmaConvArgs a)
                         if (!DELTA_IN) {
                             v = ((const float*)a.in.p)[goff[j] + (long long)ci * a.in.cs];
                         } else {
-                            bool take = true;
-                            if (POOL_IN) take = ((const uint8_t*)a.arg.p)[goff3[j] + (long long)ci * a.arg.cs] == (uint8_t)pcode[j];
-                            if (take) {
+                            const uint8_t m = ((const uint8_t*)a.mask.p)[goff2[j] + (long long)ci * a.mask.cs];
+                            if (!POOL_IN || ((m >> 1) & 3) == pcode[j]) {
                                 const float g = ((const float*)a.din.p)[goff[j] + (long long)ci * a.din.cs];
-                                const float y = ((const float*)a.out.p)[goff2[j] + (long long)ci * a.out.cs];
-                                v = y > 0.0f ? g : a.slope * g;
+                                v = (m & 1) ? g : a.slope * g;
                             }
                         }
                     }
@@ -201,10 +196,13 @@ k_conv_mfma(MfmaConvArgs a)
                     if (w3 > best) { best = w3; bi = 3; }
                     if (pos == 0 && pvalid[t] && m < a.Mtot) {
                         *at<float>(a.out, stack, ti, tj, pn[t], m, py[t], pxx[t]) = best;
-                        *at<uint8_t>(a.arg, stack, ti, tj, pn[t], m, py[t], pxx[t]) = (uint8_t)bi;
+                        if (powned[t]) *at<uint8_t>(a.mask, stack, ti, tj, pn[t], m, py[t], pxx[t]) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
                     }
                 } else {
-                    if (pvalid[t] && m < a.Mtot) *at<float>(a.out, stack, ti, tj, pn[t], m, py[t], pxx[t]) = v;
+                    if (pvalid[t] && m < a.Mtot) {
+                        *at<float>(a.out, stack, ti, tj, pn[t], m, py[t], pxx[t]) = v;
+                        if (powned[t]) *at<uint8_t>(a.mask, stack, ti, tj, pn[t], m, py[t], pxx[t]) = (uint8_t)(v > 0.0f ? 1 : 0);
+                    }
                 }
             }
         }
@@ -286,7 +284,7 @@ void prep_filter(const float* w, float* wt_fwd, float* wt_bwd, int Cout, int Cin
 void mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
 {
     MfmaConvArgs a;
-    a.in = c.in; a.out = c.out; a.arg = c.arg; a.din = c.din; a.dout = c.dout; a.rect = c.rect;
+    a.in = c.in; a.out = c.out; a.mask = c.mask; a.din = c.din; a.dout = c.dout; a.rect = c.rect; a.own = c.own;
     for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
     a.wt = wt; a.bias = (const float*)c.bias;
     a.C = c.Cin; a.Mtot = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
@@ -305,7 +303,7 @@ void mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hi
 void mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
 {
     MfmaConvArgs a;
-    a.in = c.in; a.out = c.out; a.arg = c.arg; a.din = c.din; a.dout = c.dout; a.rect = c.rect;
+    a.in = c.in; a.out = c.out; a.mask = c.mask; a.din = c.din; a.dout = c.dout; a.rect = c.rect; a.own = c.own;
     for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
     a.wt = wt; a.bias = nullptr;
     a.C = c.Cout; a.Mtot = c.Cin; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;

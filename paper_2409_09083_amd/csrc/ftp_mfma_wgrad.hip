@@ -68,16 +68,11 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     const int co = co0 + c, qy = yb + r, qx = x0 + col, n = n0 + il;
                     float v = 0.0f;
                     if (col < rw && co < a.Cout) {
-                        int sy = qy, sx = qx;
-                        bool take = true;
-                        if (POOL) {
-                            sy = qy >> 1; sx = qx >> 1;
-                            take = *at<uint8_t>(a.arg, stack, ti, tj, n, co, sy, sx) == (uint8_t)(((qy & 1) << 1) | (qx & 1));
-                        }
-                        if (take) {
+                        const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
+                        const uint8_t m = *at<uint8_t>(a.mask, stack, ti, tj, n, co, sy, sx);
+                        if (!POOL || ((m >> 1) & 3) == (((qy & 1) << 1) | (qx & 1))) {
                             const float g = *at<float>(a.din, stack, ti, tj, n, co, sy, sx);
-                            const float y = *at<float>(a.out, stack, ti, tj, n, co, sy, sx);
-                            v = y > 0.0f ? g : a.slope * g;
+                            v = (m & 1) ? g : a.slope * g;
                         }
                     }
                     Zl[((il * nr + r) * TCp + col) * ZP + c] = v;
@@ -209,7 +204,7 @@ int mfma_wgrad_splits(const ConvArgs& c)
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
 {
     MfmaWgradArgs a;
-    a.in = c.in; a.din = c.din; a.out = c.out; a.arg = c.arg; a.own = c.rect;
+    a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.rect;
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
     a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
     a.splits = mfma_wgrad_splits(c);

@@ -44,16 +44,10 @@ inline Seg dep_forth(Seg i, const ftp_layer& ly)
     return Seg{floordiv(i.a, 2), floordiv(i.b, 2)};
 }
 
-bool fused_away(const std::vector<ftp_layer>& layers, int s, int l)
-{
-    // boundary l sits between a convolution and the pool evaluated in that convolution's epilogue
-    return l > s && l < (int)layers.size() && layers[l].kind == FTP_MAXPOOL && layers[l - 1].kind == FTP_CONV;
-}
-
 int fill_group(const Plan& p, GroupRects& g)
 {
     const int nb = g.e - g.s + 1;
-    g.seg.assign((size_t)4 * nb * 2 * kMaxGrid, Seg{0, -1});
+    g.seg.assign((size_t)3 * nb * 2 * kMaxGrid, Seg{0, -1});
     for (int dim = 0; dim < 2; ++dim) {
         const int parts = dim == 0 ? p.M : p.N;
         auto len = [&](int l) { return dim == 0 ? p.W[l] : p.H[l]; };
@@ -64,7 +58,6 @@ int fill_group(const Plan& p, GroupRects& g)
             if (o.b < o.a) return FTP_EGRID;
             g.at(FTP_RECT_OWN, g.e, dim, t) = o;
             g.at(FTP_RECT_FWD, g.e, dim, t) = o;
-            g.at(FTP_RECT_HELD, g.e, dim, t) = o;
             for (int l = g.e; l > g.s; --l) {
                 g.at(FTP_RECT_OWN, l - 1, dim, t) = clampseg(own_back(g.at(FTP_RECT_OWN, l, dim, t), p.layers[l - 1]), len(l - 1));
                 g.at(FTP_RECT_FWD, l - 1, dim, t) = clampseg(dep_back(g.at(FTP_RECT_FWD, l, dim, t), p.layers[l - 1]), len(l - 1));
@@ -72,13 +65,6 @@ int fill_group(const Plan& p, GroupRects& g)
             g.at(FTP_RECT_BWD, g.s, dim, t) = g.at(FTP_RECT_OWN, g.s, dim, t);
             for (int l = g.s; l < g.e; ++l)
                 g.at(FTP_RECT_BWD, l + 1, dim, t) = clampseg(dep_forth(g.at(FTP_RECT_BWD, l, dim, t), p.layers[l]), len(l + 1));
-            // held: forward rectangles widened so that every materialised interior boundary also
-            // covers the backward rectangle there (signs and pool winners for back-propagation)
-            for (int l = g.e - 1; l >= g.s; --l) {
-                Seg h = clampseg(dep_back(g.at(FTP_RECT_HELD, l + 1, dim, t), p.layers[l]), len(l));
-                if (l > g.s && !fused_away(p.layers, g.s, l)) h = hull(h, g.at(FTP_RECT_BWD, l, dim, t));
-                g.at(FTP_RECT_HELD, l, dim, t) = h;
-            }
         }
         // invariants the kernels rely on
         for (int l = g.s; l <= g.e; ++l) {
@@ -87,11 +73,12 @@ int fill_group(const Plan& p, GroupRects& g)
                 const Seg o = g.at(FTP_RECT_OWN, l, dim, t);
                 if (o.a != next || o.b < o.a) return FTP_EGRID;      // disjoint cover, in order
                 next = o.b + 1;
-                const Seg f = g.at(FTP_RECT_FWD, l, dim, t), b = g.at(FTP_RECT_BWD, l, dim, t), h = g.at(FTP_RECT_HELD, l, dim, t);
-                if (!seg_contains(f, o) || !seg_contains(b, o) || !seg_contains(h, f)) return FTP_EGRID;
-                if (l > g.s && l < g.e && !fused_away(p.layers, g.s, l) && !seg_contains(h, b)) return FTP_EGRID;
+                const Seg f = g.at(FTP_RECT_FWD, l, dim, t), b = g.at(FTP_RECT_BWD, l, dim, t);
+                if (!seg_contains(f, o) || !seg_contains(b, o)) return FTP_EGRID;
                 if (l < g.e) {
-                    if (!seg_contains(h, clampseg(dep_back(g.at(FTP_RECT_HELD, l + 1, dim, t), p.layers[l]), len(l)))) return FTP_EGRID;
+                    // forward reads stay inside what the stack holds; the filter-gradient ring too
+                    if (!seg_contains(f, clampseg(dep_back(g.at(FTP_RECT_FWD, l + 1, dim, t), p.layers[l]), len(l)))) return FTP_EGRID;
+                    if (!seg_contains(f, clampseg(dep_back(g.at(FTP_RECT_OWN, l + 1, dim, t), p.layers[l]), len(l)))) return FTP_EGRID;
                     if (!seg_contains(g.at(FTP_RECT_BWD, l + 1, dim, t), clampseg(dep_forth(b, p.layers[l]), len(l + 1)))) return FTP_EGRID;
                 }
             }
@@ -179,8 +166,8 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
     size_t ws = 0;
     auto alloc = [&](size_t bytes) { const size_t off = ws; ws = align256(ws + bytes); return off; };
 
-    std::vector<BufRef>& act = p.act; std::vector<BufRef>& arg = p.arg; std::vector<BufRef>& delta = p.delta;
-    act.assign(L + 1, BufRef()); arg.assign(L + 1, BufRef()); delta.assign(L + 1, BufRef());
+    std::vector<BufRef>& act = p.act; std::vector<BufRef>& mask = p.mask; std::vector<BufRef>& delta = p.delta;
+    act.assign(L + 1, BufRef()); mask.assign(L + 1, BufRef()); delta.assign(L + 1, BufRef());
     p.home_group.assign(L + 1, 0);
     size_t pp_bytes = 0;                       // size of one ping-pong slot set for interior deltas
     for (int g = 0; g < (int)p.groups.size(); ++g) {
@@ -196,38 +183,36 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
             } else {
                 u.kind = UNIT_POOL; u.pooled = false; u.bo = l + 1;
             }
-            const bool has_arg = u.pooled || u.kind == UNIT_POOL;
             const int b = u.bo;
-            // activation / winner / delta homes of boundary b (boundary 0 handled below)
+            // homes of boundary b: activation, decision codes, delta (boundary 0 handled below)
             if (act[b].kind == BUF_NONE) {
                 BufRef a, w, d;
                 a.channels = w.channels = d.channels = p.C[b];
+                const size_t map_elems = (size_t)batch * p.C[b] * p.H[b] * p.W[b];
+                // decision codes: one byte per element of the whole map, written by the owners
+                w.kind = BUF_WS; w.slot_w = p.W[b]; w.slot_h = p.H[b]; w.bytes = map_elems; w.offset = alloc(w.bytes);
                 if (is_group_edge[b]) {
-                    a.slot_w = w.slot_w = d.slot_w = p.W[b];
-                    a.slot_h = w.slot_h = d.slot_h = p.H[b];
-                    const size_t elems = (size_t)batch * p.C[b] * p.H[b] * p.W[b];
+                    a.slot_w = d.slot_w = p.W[b];
+                    a.slot_h = d.slot_h = p.H[b];
                     if (b == L) { a.kind = BUF_Y; d.kind = BUF_DY; }
                     else {
-                        a.kind = BUF_WS; a.bytes = elems * p.esize; a.offset = alloc(a.bytes);
-                        d.kind = BUF_WS; d.bytes = elems * p.esize; d.offset = alloc(d.bytes);
+                        a.kind = BUF_WS; a.bytes = map_elems * p.esize; a.offset = alloc(a.bytes);
+                        d.kind = BUF_WS; d.bytes = map_elems * p.esize; d.offset = alloc(d.bytes);
                     }
-                    if (has_arg) { w.kind = BUF_WS; w.bytes = elems; w.offset = alloc(w.bytes); }
                 } else {
-                    a.per_stack = w.per_stack = d.per_stack = true;
-                    a.rect_kind = w.rect_kind = FTP_RECT_HELD; d.rect_kind = FTP_RECT_BWD;
-                    a.slot_w = w.slot_w = max_len(gr, FTP_RECT_HELD, b, 0, M);
-                    a.slot_h = w.slot_h = max_len(gr, FTP_RECT_HELD, b, 1, N);
+                    a.per_stack = d.per_stack = true;
+                    a.rect_kind = FTP_RECT_FWD; d.rect_kind = FTP_RECT_BWD;
+                    a.slot_w = max_len(gr, FTP_RECT_FWD, b, 0, M);
+                    a.slot_h = max_len(gr, FTP_RECT_FWD, b, 1, N);
                     d.slot_w = max_len(gr, FTP_RECT_BWD, b, 0, M);
                     d.slot_h = max_len(gr, FTP_RECT_BWD, b, 1, N);
-                    const size_t ae = stacks * batch * p.C[b] * a.slot_w * a.slot_h;
-                    a.kind = BUF_WS; a.bytes = ae * p.esize; a.offset = alloc(a.bytes);
-                    if (has_arg) { w.kind = BUF_WS; w.bytes = ae; w.offset = alloc(w.bytes); }
+                    a.kind = BUF_WS; a.bytes = stacks * batch * p.C[b] * a.slot_w * a.slot_h * p.esize; a.offset = alloc(a.bytes);
                     d.kind = BUF_WS; d.bytes = stacks * batch * p.C[b] * d.slot_w * d.slot_h * p.esize;
                     d.offset = (size_t)(ordinal & 1);       // ping-pong index, resolved below
                     pp_bytes = std::max(pp_bytes, d.bytes);
                     ++ordinal;
                 }
-                act[b] = a; arg[b] = w; delta[b] = d;
+                act[b] = a; mask[b] = w; delta[b] = d;
                 p.home_group[b] = g;
             }
             p.units.push_back(u);
@@ -261,7 +246,7 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
 
     size_t poff = 0;
     for (Unit& u : p.units) {
-        u.in_act = act[u.bi]; u.out_act = act[u.bo]; u.out_arg = arg[u.bo];
+        u.in_act = act[u.bi]; u.out_act = act[u.bo]; u.out_mask = mask[u.bo];
         u.in_delta = delta[u.bo]; u.out_delta = delta[u.bi];
     }
     std::vector<size_t> layer_poff(L, 0), layer_boff(L, 0);
@@ -293,22 +278,24 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
             const double kk = (double)ly.k * ly.k * ly.cin * ly.cout * batch;
             const double full = (double)p.H[u.layer + 1] * p.W[u.layer + 1];
             p.useful_macs += 3.0 * kk * full;
-            p.executed_macs += kk * (area_sum(gr, FTP_RECT_HELD, u.layer + 1) + area_sum(gr, FTP_RECT_BWD, u.layer) + full);
+            p.executed_macs += kk * (area_sum(gr, FTP_RECT_FWD, u.layer + 1) + area_sum(gr, FTP_RECT_BWD, u.layer) + full);
         }
         if (u.bi == gr.s) {
-            p.halo_bytes[0] += (area_sum(gr, FTP_RECT_HELD, u.bi) - (double)p.H[u.bi] * p.W[u.bi]) * p.C[u.bi] * batch * p.esize;
+            p.halo_bytes[0] += (area_sum(gr, FTP_RECT_FWD, u.bi) - (double)p.H[u.bi] * p.W[u.bi]) * p.C[u.bi] * batch * p.esize;
         }
         if (u.bo == gr.e) {
             const double halo_px = area_sum(gr, FTP_RECT_BWD, u.bo) - (double)p.H[u.bo] * p.W[u.bo];
-            const bool has_arg = u.pooled || u.kind == UNIT_POOL;
-            p.halo_bytes[1] += halo_px * p.C[u.bo] * batch * ((u.kind == UNIT_CONV ? 2.0 : 1.0) * p.esize + (has_arg ? 1.0 : 0.0));
+            p.halo_bytes[1] += halo_px * p.C[u.bo] * batch * (p.esize + 1.0);      // delta + decision code
+        } else {
+            // interior boundary: only decision codes cross tiles (collected when the backward pass enters the group)
+            p.halo_bytes[1] += (area_sum(gr, FTP_RECT_BWD, u.bo) - (double)p.H[u.bo] * p.W[u.bo]) * p.C[u.bo] * batch;
         }
-        const int kind_out = u.bo == gr.e ? FTP_RECT_OWN : FTP_RECT_HELD;
+        const int kind_out = u.bo == gr.e ? FTP_RECT_OWN : FTP_RECT_FWD;
         fmap += area_max(gr, kind_out, u.bo) * p.C[u.bo] * batch * p.esize;
-        if (u.pooled || u.kind == UNIT_POOL) other += area_max(gr, kind_out, u.bo) * p.C[u.bo] * batch;
+        other += area_max(gr, FTP_RECT_OWN, u.bo) * p.C[u.bo] * batch;                // decision codes of the own tile
         dmap = std::max(dmap, (area_max(gr, FTP_RECT_BWD, u.bo) * p.C[u.bo] + area_max(gr, FTP_RECT_BWD, u.bi) * p.C[u.bi]) * batch * p.esize);
     }
-    fmap += area_max(p.groups[0], FTP_RECT_HELD, 0) * p.C[0] * batch * p.esize;
+    fmap += area_max(p.groups[0], FTP_RECT_FWD, 0) * p.C[0] * batch * p.esize;
     p.split[0] = (size_t)fmap; p.split[1] = (size_t)dmap;
     p.split[2] = p.n_params * (p.esize + 4);      // own copy of all filters + own partial gradient set
     p.split[3] = (size_t)other;

@@ -48,7 +48,7 @@ struct Unit {
     int layer = 0;            // primitive layer of the convolution (or of the lone pool)
     bool pooled = false;
     int bi = 0, bo = 0;       // input / output boundary
-    BufRef in_act, out_act, out_arg;          // forward
+    BufRef in_act, out_act, out_mask;         // forward (out_mask: decision codes at the output boundary)
     BufRef in_delta, out_delta;               // backward (in_delta lives at bo, out_delta at bi)
     size_t param_offset = 0;                  // first filter element in the parameter vector
     size_t bias_offset = 0;
@@ -64,7 +64,7 @@ struct Plan {
     std::vector<GroupRects> groups;
     std::vector<int> group_of_layer;
     std::vector<Unit> units;
-    std::vector<BufRef> act, arg, delta;      // home of each boundary's activation / pool winners / delta
+    std::vector<BufRef> act, mask, delta;     // home of each boundary's activation / decision codes / delta
     std::vector<int> home_group;              // group whose rectangles address a per-stack boundary
     size_t workspace_bytes = 0, n_params = 0;
     size_t wgrad_scratch_offset = 0;          // batch shares of one layer's partial gradients (bytes)

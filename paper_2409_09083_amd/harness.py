@@ -78,7 +78,7 @@ class Session:
                       self.y.data_ptr(), self._stream())
 
     def backward(self):
-        B.ftp_backward(self.plan, self.dy.data_ptr(), self.x.data_ptr(), self.y.data_ptr(), self._wptrs(),
+        B.ftp_backward(self.plan, self.dy.data_ptr(), self.x.data_ptr(), self._wptrs(),
                        self.workspace.data_ptr(), self.dx.data_ptr(), self.partials.data_ptr(), self._stream())
 
     def reduce(self):
@@ -97,8 +97,8 @@ class Session:
             return None, info
         if loc in (1, 2, 3, 4):
             return {1: self.x, 2: self.y, 3: self.dy, 4: self.dx}[loc], info
-        dt = torch.uint8 if which == B.FTP_BUF_ARG else self.tdtype
-        esz = 1 if which == B.FTP_BUF_ARG else (2 if self.bf16 else 4)
+        dt = torch.uint8 if which == B.FTP_BUF_MASK else self.tdtype
+        esz = 1 if which == B.FTP_BUF_MASK else (2 if self.bf16 else 4)
         lead = (self.stacks,) if info["per_stack"] else ()
         shape = lead + (self.batch, info["channels"], info["slot_h"], info["slot_w"])
         n = 1
@@ -145,7 +145,7 @@ class Session:
         if t is None:
             return
         src = torch.from_numpy(np.ascontiguousarray(full_map))
-        src = src.cuda() if which == B.FTP_BUF_ARG else src.float().cuda().to(t.dtype)
+        src = src.cuda() if which == B.FTP_BUF_MASK else src.float().cuda().to(t.dtype)
         if not info["per_stack"]:
             t.copy_(src)
             return

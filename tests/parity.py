@@ -121,65 +121,61 @@ def groups_of(cfg):
     return out
 
 
+def oracle_mask(acts, args, b):
+    """Decision code of boundary b as the library defines it: bit 0 = value > 0, bits 1-2 = pool winner."""
+    m = (acts[b] > 0).astype(np.uint8)
+    if args[b - 1] is not None:
+        m |= (args[b - 1].astype(np.uint8) << 1)
+    return m
+
+
 def check_forward_state(s, cfg, acts, args, tol_a):
     """Every map the plan keeps equals the oracle's: the assembled owned tiles, and each stack's whole
-    held rectangle (recomputed halo included).  Pool winners may differ only where the oracle's top-2
-    gap is within the activation tolerance."""
+    forward rectangle (recomputed halo included).  Decision codes may differ from the oracle's only where
+    the oracle's own value is within the activation tolerance of the kink (|Y| small, top-2 gap small)."""
     import paper_2409_09083_amd as F
-    worst = 0.0
     for b in range(1, len(cfg.layers) + 1):
         got = s.get_boundary(b)
-        if got is None:
-            continue
-        e = rel_inf(got, acts[b])
-        worst = max(worst, e)
-        assert e <= tol_a, ("activation at boundary", b, e)
         scale = float(np.max(np.abs(acts[b])))
-        for (r, slot) in s.get_slots(b):
-            ref = acts[b][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]
-            assert np.max(np.abs(slot - ref)) <= tol_a * scale, ("held rectangle", b, r)
-        ga = s.get_boundary(b, F.FTP_BUF_ARG)
-        if ga is not None:
-            bad = ga != args[b - 1]
+        if got is not None:
+            e = rel_inf(got, acts[b])
+            assert e <= tol_a, ("activation at boundary", b, e)
+            for (r, slot) in s.get_slots(b):
+                ref = acts[b][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]
+                assert np.max(np.abs(slot - ref)) <= tol_a * scale, ("held rectangle", b, r)
+        gm = s.get_boundary(b, F.FTP_BUF_MASK)
+        if gm is None:
+            continue
+        bad = (gm & 1) != (acts[b] > 0)
+        if bad.any():
+            assert float(np.abs(acts[b][bad]).max()) <= tol_a * scale, ("activation signs", b, int(bad.sum()))
+        if args[b - 1] is not None:
+            bad = ((gm >> 1) & 3) != args[b - 1]
             if bad.any():
-                gap = pool_gap(_prepool(cfg, acts, b))
-                assert float(gap[bad].max()) <= 2 * tol_a * float(np.max(np.abs(acts[b]))), ("pool winners", b, int(bad.sum()))
-    return worst
+                gap = pool_gap(acts[b - 1])
+                assert float(gap[bad].max()) <= 2 * tol_a * scale, ("pool winners", b, int(bad.sum()))
 
 
 def decisions_agree(s, cfg, acts, args):
-    """True if every leaky sign and pool winner the GPU's forward state holds equals the oracle's."""
+    """True if every leaky sign and pool winner the GPU's forward pass recorded equals the oracle's."""
     import paper_2409_09083_amd as F
     for b in range(1, len(cfg.layers) + 1):
-        got = s.get_boundary(b)
-        if got is None:
+        gm = s.get_boundary(b, F.FTP_BUF_MASK)
+        if gm is None:
             continue
-        if ((got > 0) != (acts[b] > 0)).any():
+        want = oracle_mask(acts, args, b)
+        keep = 0x7 if args[b - 1] is not None else 0x1
+        if ((gm & keep) != (want & keep)).any():
             return False
-        for (r, slot) in s.get_slots(b):
-            if ((slot > 0) != (acts[b][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1] > 0)).any():
-                return False
-        ga = s.get_boundary(b, F.FTP_BUF_ARG)
-        if ga is not None and (ga != args[b - 1]).any():
-            return False
-        for (r, slot) in s.get_slots(b, F.FTP_BUF_ARG):
-            if (slot != args[b - 1][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]).any():
-                return False
     return True
 
 
-def _prepool(cfg, acts, b):
-    return acts[b - 1]
-
-
 def import_forward_state(s, cfg, acts, args):
-    """oracle -> GPU: the plan's workspace and y receive the oracle's forward maps."""
+    """oracle -> GPU: the plan's workspace receives the oracle's forward maps and decision codes."""
     import paper_2409_09083_amd as F
-    L = len(cfg.layers)
-    for b in range(1, L + 1):
+    for b in range(1, len(cfg.layers) + 1):
         s.set_boundary(b, acts[b])
-        if args[b - 1] is not None:
-            s.set_boundary(b, args[b - 1], F.FTP_BUF_ARG)
+        s.set_boundary(b, oracle_mask(acts, args, b), F.FTP_BUF_MASK)
 
 
 def check_grads(cfg, got_dx, got_wgrad, dx, dws, dbs, has_bias, tol_g, label):
@@ -237,7 +233,6 @@ def check_case(oracle, cfg, seed=C.rng.MASTER_SEED, has_bias=False, strict_chain
 
     # given state: identical decisions on both sides, strict elementwise bars
     import_forward_state(s, cfg, acts, args)
-    s.y.copy_(torch.from_numpy(acts[-1]).cuda().to(s.y.dtype))
     s.backward()
     s.reduce()
     torch.cuda.synchronize()

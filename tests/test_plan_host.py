@@ -39,7 +39,7 @@ def _compare(F, layers, h, w, N, M, ends, batch=1):
             assert F.ftp_plan_map_shape(plan, l) == (c, hh, ww)
         for g, (s, e) in enumerate(R.groups_from_ends(ends)):
             for (i, j), rk in oplan[g].items():
-                for kind, fk in ((R.OWN, F.FTP_RECT_OWN), (R.FWD, F.FTP_RECT_FWD), (R.BWD, F.FTP_RECT_BWD), (R.HELD, F.FTP_RECT_HELD)):
+                for kind, fk in ((R.OWN, F.FTP_RECT_OWN), (R.FWD, F.FTP_RECT_FWD), (R.BWD, F.FTP_RECT_BWD)):
                     for l in range(s, e + 1):
                         assert F.ftp_plan_rect(plan, g, l, i, j, fk) == tuple(rk[kind][l]), (g, l, i, j, kind)
     finally:
@@ -92,7 +92,7 @@ def test_plan_sizes_and_work(F):
     macs_fwd = sum(ly.cin * ly.cout * ly.k ** 2 * h * w for ly, (h, w) in
                    zip(cfg.layers, R.map_sizes(cfg.layers, 608, 608)[1:]) if ly.kind == CONV)
     assert wk["useful_macs"] == 3.0 * macs_fwd * cfg.batch
-    assert 1.0 <= wk["executed_macs"] / wk["useful_macs"] < 1.5
+    assert 1.0 <= wk["executed_macs"] / wk["useful_macs"] < 1.2
     F.ftp_plan_destroy(plan)
     # one layer per group: nothing is recomputed
     c5 = C.config5(1)
@@ -143,7 +143,7 @@ def test_null_arguments_rejected_without_gpu(F):
         F.ftp_forward(plan, 0, [0, 0], None, 0, 0, 0)
     assert e.value.code == F.FTP_EINVAL
     with pytest.raises(F.binding.FtpError):
-        F.ftp_backward(plan, 0, 0, 0, [0, 0], 0, 0, 0, 0)
+        F.ftp_backward(plan, 0, 0, [0, 0], 0, 0, 0, 0)
     with pytest.raises(F.binding.FtpError):
         F.ftp_reduce_wgrad(plan, 0, 0, 0)
     with pytest.raises(F.binding.FtpError):

@@ -26,8 +26,6 @@ def test_tiny_hand_derived():
     t = plan[0][(1, 0)]                          # row 1, column 0
     assert [t[R.FWD][l] for l in (0, 1, 2)] == [(0, 14, 17, 31), (0, 15, 16, 31), (0, 16, 15, 31)]
     assert [t[R.BWD][l] for l in (0, 1, 2)] == [(0, 16, 15, 31), (0, 15, 16, 31), (0, 14, 17, 31)]
-    # held: boundary 1 must also carry the signs for the backward region there
-    assert t[R.HELD][1] == (0, 15, 16, 31) and t[R.HELD][2] == (0, 16, 15, 31)
 
 
 @pytest.mark.parametrize("n_conv", [1, 2, 3, 5])
@@ -71,12 +69,10 @@ def test_invariants_on_configs(cfg):
             h, w = sizes[l]
             cover = np.zeros((h, w), dtype=np.int32)
             for (i, j), rk in plan[g].items():
-                o, f, b, hd = rk[R.OWN][l], rk[R.FWD][l], rk[R.BWD][l], rk[R.HELD][l]
+                o, f, b = rk[R.OWN][l], rk[R.FWD][l], rk[R.BWD][l]
                 assert R.area(o) > 0
                 cover[o[1]:o[3] + 1, o[0]:o[2] + 1] += 1
-                assert R.contains(f, o) and R.contains(b, o) and R.contains(hd, f)
-                if s < l < e and R.materialised(cfg.layers, s, l):
-                    assert R.contains(hd, b)
+                assert R.contains(f, o) and R.contains(b, o)
                 if l < e:
                     ly = cfg.layers[l]
                     # Eq. 1 after Eq. 2 covers the rectangle it started from

@@ -1,10 +1,12 @@
 """CPU emulation of fused-tile execution built from oracle ops only (test helper).
 
-Every tile of every group evaluates its layers on nothing but (a) the rectangle of the
-group-input map it is entitled to read at the group boundary and (b) what it computed
-itself; any read outside those rectangles raises.  Reproducing the untiled oracle this way
-shows that the integer maps of oracle/rects.py are sufficient (Sec. 4.2: within a group
-all intermediate data is computed locally from data collected at the group input).
+Every tile of every group evaluates its layers on nothing but (a) what it is entitled to collect at a
+group boundary: the forward rectangle F_s of the group-input map, the backward rectangle B_e of the
+delta map, and the decision codes (activation sign, pool winner) on its backward rectangles, which the
+owning tiles publish when the backward pass enters the group; and (b) what it computed itself.  Any
+read outside those rectangles raises.  Reproducing the untiled oracle this way shows that the integer
+maps of oracle/rects.py are sufficient (Sec. 4.2: within a group all intermediate data is computed
+locally from data collected at the group input).
 """
 import numpy as np
 
@@ -51,34 +53,33 @@ def run(layers, x, weights, dy, N, M, group_ends):
     chans = [x.shape[1]] + [ly.cout for ly in layers]
     nb = x.shape[0]
     glob = {0: x}
-    globarg = {}
-    held = [dict() for _ in groups]      # held[g][(i,j)] = {l: Held}, args likewise
-    heldarg = [dict() for _ in groups]
+    # decision codes published by the owners: sign[l] = (map at boundary l > 0), win[l] = pool winners of layer l-1
+    sign = {l: np.zeros((nb, chans[l]) + sizes[l], dtype=bool) for l in range(1, L + 1)}
+    win = {l: np.zeros((nb, chans[l]) + sizes[l], dtype=np.uint8) for l in range(1, L + 1) if layers[l - 1].kind == MAXPOOL}
+    held = [dict() for _ in groups]
     for g, (s, e) in enumerate(groups):
         out = np.full((nb, chans[e]) + sizes[e], np.nan)
-        outarg = np.zeros((nb, chans[e]) + sizes[e], dtype=np.uint8)
         for tile, rk in plan[g].items():
-            Hd = rk[R.HELD]
-            h = {s: Held(Hd[s], full(glob[s]).crop(Hd[s]))}     # group-boundary read: tile + halo
-            ha = {}
+            F, Ow = rk[R.FWD], rk[R.OWN]
+            h = {s: Held(F[s], full(glob[s]).crop(F[s]))}        # group-boundary read: tile + halo
             for l in range(s, e):
                 ly = layers[l]
                 if ly.kind == CONV:
-                    src = h[l].crop_zero_padded(R.eq1_back(Hd[l + 1], ly), sizes[l])
+                    src = h[l].crop_zero_padded(R.eq1_back(F[l + 1], ly), sizes[l])
                     y = O.leaky_fwd(O.conv_fwd(src, weights[l], None, ly.stride, 0), ly.slope)
                 else:
-                    y, a = O.pool_fwd(h[l].crop(R.eq1_back(Hd[l + 1], ly)))
-                    ha[l + 1] = Held(Hd[l + 1], a)
-                h[l + 1] = Held(Hd[l + 1], y)
-            r = Hd[e]
-            assert r == rk[R.OWN][e]
+                    y, a = O.pool_fwd(h[l].crop(R.eq1_back(F[l + 1], ly)))
+                    o = Ow[l + 1]
+                    win[l + 1][:, :, o[1]:o[3] + 1, o[0]:o[2] + 1] = Held(F[l + 1], a).crop(o)
+                h[l + 1] = Held(F[l + 1], y)
+                o = Ow[l + 1]
+                sign[l + 1][:, :, o[1]:o[3] + 1, o[0]:o[2] + 1] = h[l + 1].crop(o) > 0
+            r = F[e]
+            assert r == Ow[e]
             out[:, :, r[1]:r[3] + 1, r[0]:r[2] + 1] = h[e].data
-            if e in ha:
-                outarg[:, :, r[1]:r[3] + 1, r[0]:r[2] + 1] = ha[e].data
-            held[g][tile], heldarg[g][tile] = h, ha
+            held[g][tile] = h
         assert not np.isnan(out).any()
         glob[e] = out
-        globarg[e] = outarg
 
     tiles = [(i, j) for i in range(N) for j in range(M)]
     partial = {t: [None] * L for t in tiles}
@@ -88,44 +89,28 @@ def run(layers, x, weights, dy, N, M, group_ends):
         out = np.full((nb, chans[s]) + sizes[s], np.nan)
         for tile, rk in plan[g].items():
             B, Ow = rk[R.BWD], rk[R.OWN]
-            h, ha = held[g][tile], heldarg[g][tile]
-            d = Held(B[e], full(gdelta[e]).crop(B[e]))           # group-boundary read of the delta map
-            l = e - 1
-            while l >= s:
+            h = held[g][tile]
+            # collected when the backward pass enters the group: delta on B_e, decision codes on B_l
+            d = Held(B[e], full(gdelta[e]).crop(B[e]))
+            sg = {l: Held(B[l], full(sign[l]).crop(B[l])) for l in range(s + 1, e + 1)}
+            wn = {l: Held(B[l], full(win[l]).crop(B[l])) for l in range(s + 1, e + 1) if l in win}
+            for l in range(e - 1, s - 1, -1):
                 ly = layers[l]
-                ysrc = full(glob[e]) if l + 1 == e else h[l + 1]
-                if ly.kind == MAXPOOL and l > s and layers[l - 1].kind == CONV and l + 1 == e:
-                    # pool closing the group behind a convolution: sign and winner come with the
-                    # group-boundary maps; leaky is monotone, so the winner's sign is the pooled sign
-                    lc = layers[l - 1]
-                    pm = O.leaky_bwd(d.data, ysrc.crop(B[l + 1]), lc.slope)
-                    dzfull = Held(R.eq1_back(B[l + 1], ly), O.pool_bwd(pm, full(globarg[e]).crop(B[l + 1]),
-                                  (2 * pm.shape[2], 2 * pm.shape[3])))
-                    dz = Held(B[l], dzfull.crop(B[l]))
-                    l -= 1
-                    ly = lc
-                    d = _conv_backward(ly, l, dz, h, glob, s, sizes, weights, B, Ow, partial[tile], premasked=True)
-                elif ly.kind == MAXPOOL:
-                    asrc = full(globarg[e]) if l + 1 == e else ha[l + 1]
-                    dxf = O.pool_bwd(d.data, asrc.crop(B[l + 1]), (2 * d.data.shape[2], 2 * d.data.shape[3]))
+                if ly.kind == MAXPOOL:
+                    dxf = O.pool_bwd(d.data, wn[l + 1].data, (2 * d.data.shape[2], 2 * d.data.shape[3]))
                     d = Held(B[l], Held(R.eq1_back(B[l + 1], ly), dxf).crop(B[l]))
                 else:
-                    dz = Held(B[l + 1], O.leaky_bwd(d.data, ysrc.crop(B[l + 1]), ly.slope))
-                    d = _conv_backward(ly, l, dz, h, glob, s, sizes, weights, B, Ow, partial[tile], premasked=True)
-                l -= 1
+                    # leaky'(Y) from the sign code: slope where the sign is not positive
+                    yy = np.where(sg[l + 1].data, 1.0, -1.0)
+                    dz = Held(B[l + 1], O.leaky_bwd(d.data, yy, ly.slope))
+                    own = Ow[l + 1]
+                    xin = h[l].crop_zero_padded(grow(own, ly.pad), sizes[l])
+                    partial[tile][l], _ = O.conv_bwd_weight(xin, dz.crop(own), ly.k, ly.stride, 0, want_db=False)
+                    wrot = np.ascontiguousarray(weights[l][:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+                    dzp = dz.crop_zero_padded(grow(B[l], ly.pad), sizes[l + 1])
+                    d = Held(B[l], O.conv_fwd(dzp, wrot, None, 1, 0))
             r = B[s]
             out[:, :, r[1]:r[3] + 1, r[0]:r[2] + 1] = d.data
         assert not np.isnan(out).any()
         gdelta[s] = out
     return glob[L], gdelta[0], [partial[t] for t in tiles]
-
-
-def _conv_backward(ly, l, dz, h, glob, s, sizes, weights, B, Ow, partial, premasked):
-    """dz: Held over B[l+1] (already multiplied by the activation derivative)."""
-    xsrc = h[l]
-    own = Ow[l + 1]
-    xin = xsrc.crop_zero_padded(grow(own, ly.pad), sizes[l])
-    partial[l], _ = O.conv_bwd_weight(xin, dz.crop(own), ly.k, ly.stride, 0, want_db=False)
-    wrot = np.ascontiguousarray(weights[l][:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
-    dzp = dz.crop_zero_padded(grow(B[l], ly.pad), sizes[l + 1])
-    return Held(B[l], O.conv_fwd(dzp, wrot, None, 1, 0))
