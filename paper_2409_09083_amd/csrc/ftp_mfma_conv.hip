@@ -19,7 +19,7 @@ constexpr int kBN = 256;        // pixels per workgroup tile
 
 // Filter relayout: OIHW -> [tap][reduction channel][output channel], so that a stage's slice is a set of
 // contiguous rows.  fwd: Wt[t][ci][co] = W[co][ci][t].  bwd: Wt[t][co][ci] = W[co][ci][K*K-1-t] (rotated).
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 k_prep_filter(const float* __restrict__ w, float* __restrict__ wt_fwd, float* __restrict__ wt_bwd, int Cout, int Cin, int KK)
 {
     const long long n = (long long)Cout * Cin * KK;
@@ -33,20 +33,33 @@ k_prep_filter(const float* __restrict__ w, float* __restrict__ wt_fwd, float* __
     if (wt_bwd) wt_bwd[((long long)(KK - 1 - t) * Cout + co) * Cin + ci] = v;
 }
 
-template <int K, int WAVES_M, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
-__global__ void __launch_bounds__(256)
+// Pixel (or pool window) q of a tile -> image, row, column inside the tile.
+struct TilePix { int il, yl, xl; };
+__device__ __forceinline__ TilePix tile_pix(int wq, int per_img, int TC)
+{
+    TilePix t;
+    t.il = wq / per_img;
+    const int rem = wq - t.il * per_img;
+    t.yl = rem / TC;
+    t.xl = rem - t.yl * TC;
+    return t;
+}
+
+// WAVES_M x WAVES_N wavefronts; each computes MT x NT tiles of 32 channels x 32 pixels.
+template <int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+__global__ void __launch_bounds__(256, 2)
 k_conv_mfma(MfmaConvArgs a)
 {
     constexpr int kCK = K == 1 ? 32 : 8;             // reduction channels per LDS stage
     constexpr int WAVES_N = 4 / WAVES_M;
     constexpr int NT = kBN / 32 / WAVES_N;           // 32-pixel MFMA tiles per wavefront
-    constexpr int BM = 32 * WAVES_M;
+    constexpr int BM = 32 * MT * WAVES_M;
     constexpr int KK = K * K, P = K / 2;
     constexpr int S = POOL_OUT ? 2 : 1;
 
     extern __shared__ float lds[];
     float* Wl = lds;                                   // [KK][kCK][BM]
-    float* Xl = lds + KK * kCK * BM;                   // [kCK][TI][PH][PW] (+ pad)
+    float* Xl = lds + KK * kCK * BM;                   // [kCK][TI][PH][PW]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
@@ -59,69 +72,65 @@ k_conv_mfma(MfmaConvArgs a)
     if (ox0 > x1 || oy0 > y1) return;                 // this stack's rectangle is smaller than the largest one
     const int m0 = blockIdx.y * BM;
     const int PW = a.TC * S + 2 * P, PH = a.TR * S + 2 * P;
-    const int IS = PH * PW, CS = a.TI * IS + a.cs_pad;
+    const int IS = PH * PW, CS = a.TI * IS;
     const int px0 = ox0 * S - P, py0 = oy0 * S - P;   // patch origin in the coordinates of the convolution input
-
-    // ---- per-lane pixel of each 32-pixel tile --------------------------------------------------------
-    int baseB[NT];
-    int pn[NT], py[NT], pxx[NT];                      // image, output row, output column (pooled coordinates if POOL_OUT)
-    bool pvalid[NT], powned[NT];                      // inside the stack's rectangle / inside its owned part
     const int per_img = a.TR * a.TC;
+
+    // ---- LDS offset of each lane's pixel, per 32-pixel tile ---------------------------------------------
+    int baseB[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int q = (wave_n * NT + t) * 32 + l32;
-        const int wq = POOL_OUT ? (q >> 2) : q, pos = POOL_OUT ? (q & 3) : 0;
-        const int il = wq / per_img, rem = wq - il * per_img;
-        const int yl = rem / a.TC, xl = rem - yl * a.TC;
-        const bool v = il < a.TI && n0 + il < a.batch && oy0 + yl <= y1 && ox0 + xl <= x1;
-        pvalid[t] = v; pn[t] = n0 + il; py[t] = oy0 + yl; pxx[t] = ox0 + xl;
-        powned[t] = v && !DELTA_IN && py[t] >= a.own.y0[ti] && py[t] <= a.own.y1[ti] && pxx[t] >= a.own.x0[tj] && pxx[t] <= a.own.x1[tj];
-        const int base = v ? il * IS + (yl * S + (pos >> 1)) * PW + xl * S + (pos & 1) : 0;
-        baseB[t] = base + hi * CS;
+        const TilePix tp = tile_pix(POOL_OUT ? (q >> 2) : q, per_img, a.TC);
+        const int pos = POOL_OUT ? (q & 3) : 0;
+        const bool v = tp.il < a.TI && n0 + tp.il < a.batch && oy0 + tp.yl <= y1 && ox0 + tp.xl <= x1;
+        baseB[t] = (v ? tp.il * IS + (tp.yl * S + (pos >> 1)) * PW + tp.xl * S + (pos & 1) : 0) + hi * CS;
     }
-    const int baseA = hi * BM + wave_m * 32 + l32;
+    const int baseA = hi * BM + wave_m * (32 * MT) + l32;
 
-    // ---- per-thread patch positions (fixed over the channel loop) ---------------------------------------
+    // ---- per-thread patch positions (fixed over the channel loop): 32-bit offsets from per-workgroup bases ------
     constexpr int MAXPOS = 3;
     const int npos = a.TI * IS;
-    long long goff[MAXPOS];        // element offset in the input view (channel 0); -1: zero padding / outside
-    long long goff2[MAXPOS];       // DELTA_IN: offset in the decision-code map
-    int pcode[MAXPOS];
+    const View& sv = DELTA_IN ? a.din : a.in;          // source of the patch values
+    const float* __restrict__ src = (const float*)sv.p + (long long)stack * sv.ss + (long long)n0 * sv.ns;
+    const uint8_t* __restrict__ msk = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)n0 * a.mask.ns;
+    int goff[MAXPOS];               // source element offset (channel 0); -1: zero padding / outside the view
+    int moff[MAXPOS];               // DELTA_IN: offset in the decision-code map, winner code in the top bits
 #pragma unroll
     for (int j = 0; j < MAXPOS; ++j) {
         const int s = tid + j * 256;
-        goff[j] = -1; goff2[j] = 0; pcode[j] = 0;
+        goff[j] = -1; moff[j] = 0;
         if (s < npos) {
             const int il = s / IS, rem = s - il * IS;
             const int r = rem / PW, c = rem - r * PW;
-            const int gy = py0 + r, gx = px0 + c, n = n0 + il;
-            if (n < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc) {
-                if (!DELTA_IN) {
-                    // only positions some valid output pixel of this stack reads are inside the view
-                    if (gy >= a.iy0[ti] && gy <= a.iy1[ti] && gx >= a.ix0[tj] && gx <= a.ix1[tj])
-                        goff[j] = (long long)stack * a.in.ss + (long long)n * a.in.ns + (long long)(gy - a.in.y0[ti]) * a.in.pitch + (gx - a.in.x0[tj]);
-                } else {
-                    const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
-                    if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
-                        goff[j] = (long long)stack * a.din.ss + (long long)n * a.din.ns + (long long)(sy - a.din.y0[ti]) * a.din.pitch + (sx - a.din.x0[tj]);
-                        goff2[j] = (long long)stack * a.mask.ss + (long long)n * a.mask.ns + (long long)(sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]);
-                        if (POOL_IN) pcode[j] = ((gy & 1) << 1) | (gx & 1);
+            const int gy = py0 + r, gx = px0 + c;
+            if (n0 + il < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc) {
+                const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
+                // positions no valid output pixel of this stack reads may lie outside the view
+                if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
+                    goff[j] = il * (int)sv.ns + (sy - sv.y0[ti]) * sv.pitch + (sx - sv.x0[tj]);
+                    if (DELTA_IN) {
+                        moff[j] = il * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]);
+                        if (POOL_IN) moff[j] |= (((gy & 1) << 1) | (gx & 1)) << 29;
                     }
                 }
             }
         }
     }
 
-    v16f acc[NT];
+    v16f acc[MT][NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mt][t][i] = 0.0f;
 
     const float* __restrict__ wt = a.wt;
     for (int c0 = 0; c0 < a.C; c0 += kCK) {
         __syncthreads();
         // filter slice: KK*kCK rows of BM contiguous floats
+#pragma unroll 3
         for (int idx = tid; idx < KK * kCK * (BM / 4); idx += 256) {
             const int row = idx / (BM / 4), c4 = idx - row * (BM / 4);
             const int tap = row / kCK, cl = row - tap * kCK;
@@ -135,17 +144,17 @@ k_conv_mfma(MfmaConvArgs a)
         for (int j = 0; j < MAXPOS; ++j) {
             const int s = tid + j * 256;
             if (s < npos) {
-#pragma unroll
+#pragma unroll 4
                 for (int cl = 0; cl < kCK; ++cl) {
                     const int ci = c0 + cl;
                     float v = 0.0f;
                     if (goff[j] >= 0 && ci < a.C) {
                         if (!DELTA_IN) {
-                            v = ((const float*)a.in.p)[goff[j] + (long long)ci * a.in.cs];
+                            v = src[goff[j] + (long long)ci * sv.cs];
                         } else {
-                            const uint8_t m = ((const uint8_t*)a.mask.p)[goff2[j] + (long long)ci * a.mask.cs];
-                            if (!POOL_IN || ((m >> 1) & 3) == pcode[j]) {
-                                const float g = ((const float*)a.din.p)[goff[j] + (long long)ci * a.din.cs];
+                            const uint8_t m = msk[(moff[j] & 0x1FFFFFFF) + (long long)ci * a.mask.cs];
+                            if (!POOL_IN || ((m >> 1) & 3) == ((unsigned)moff[j] >> 29)) {
+                                const float g = src[goff[j] + (long long)ci * sv.cs];
                                 v = (m & 1) ? g : a.slope * g;
                             }
                         }
@@ -160,48 +169,55 @@ k_conv_mfma(MfmaConvArgs a)
             const int toff = (tap / K) * PW + (tap % K);
 #pragma unroll
             for (int i = 0; i < kCK / 2; ++i) {
-                const float av = Wl[(tap * kCK + 2 * i) * BM + baseA];
+                float av[MT], bv[NT];
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const float bv = Xl[baseB[t] + 2 * i * CS + toff];
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t], 0, 0, 0);
-                }
+                for (int mt = 0; mt < MT; ++mt) av[mt] = Wl[(tap * kCK + 2 * i) * BM + baseA + 32 * mt];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) bv[t] = Xl[baseB[t] + 2 * i * CS + toff];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt], bv[t], acc[mt][t], 0, 0, 0);
             }
         }
     }
 
     // ---- epilogue ------------------------------------------------------------------------------------------
+    // A lane holds, per 32x32 tile, 16 channels (8*(i/4) + 4*hi + i%4) of one pixel.
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
+        const int q = (wave_n * NT + t) * 32 + l32;
+        const TilePix tp = tile_pix(POOL_OUT ? (q >> 2) : q, per_img, a.TC);
+        const int pn = n0 + tp.il, py = oy0 + tp.yl, pxx = ox0 + tp.xl;
+        bool pvalid = tp.il < a.TI && pn < a.batch && py <= y1 && pxx <= x1;
+        if (POOL_OUT) pvalid = pvalid && (lane & 3) == 0;       // the window's first lane stores
+        const bool powned = pvalid && !DELTA_IN && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
+        const View& ov = DELTA_IN ? a.dout : a.out;
+        float* __restrict__ optr = at<float>(ov, stack, ti, tj, pn, 0, py, pxx);
+        uint8_t* __restrict__ mptr = at<uint8_t>(a.mask, stack, ti, tj, pn, 0, py, pxx);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int m = m0 + wave_m * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
-            float v = acc[t][i];
-            if (DELTA_IN) {
-                if (pvalid[t] && m < a.Mtot) *at<float>(a.dout, stack, ti, tj, pn[t], m, py[t], pxx[t]) = v;
-            } else {
-                const float b = (a.bias && m < a.Mtot) ? a.bias[m] : 0.0f;
-                v = leaky(v + b, a.slope);
-                if (POOL_OUT) {
-                    // the 4 pixels of a window sit in 4 adjacent lanes; every lane rebuilds the window in order
-                    const float o1 = __shfl_xor(v, 1, 64), o2 = __shfl_xor(v, 2, 64), o3 = __shfl_xor(v, 3, 64);
-                    const int pos = lane & 3;
-                    const float w0 = pos == 0 ? v : pos == 1 ? o1 : pos == 2 ? o2 : o3;
-                    const float w1 = pos == 1 ? v : pos == 0 ? o1 : pos == 3 ? o2 : o3;
-                    const float w2 = pos == 2 ? v : pos == 3 ? o1 : pos == 0 ? o2 : o3;
-                    const float w3 = pos == 3 ? v : pos == 2 ? o1 : pos == 1 ? o2 : o3;
-                    float best = w0; int bi = 0;
-                    if (w1 > best) { best = w1; bi = 1; }
-                    if (w2 > best) { best = w2; bi = 2; }
-                    if (w3 > best) { best = w3; bi = 3; }
-                    if (pos == 0 && pvalid[t] && m < a.Mtot) {
-                        *at<float>(a.out, stack, ti, tj, pn[t], m, py[t], pxx[t]) = best;
-                        if (powned[t]) *at<uint8_t>(a.mask, stack, ti, tj, pn[t], m, py[t], pxx[t]) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
-                    }
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = m0 + (wave_m * MT + mt) * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
+                float v = acc[mt][t][i];
+                if (DELTA_IN) {
+                    if (pvalid && m < a.Mtot) optr[(long long)m * ov.cs] = v;
                 } else {
-                    if (pvalid[t] && m < a.Mtot) {
-                        *at<float>(a.out, stack, ti, tj, pn[t], m, py[t], pxx[t]) = v;
-                        if (powned[t]) *at<uint8_t>(a.mask, stack, ti, tj, pn[t], m, py[t], pxx[t]) = (uint8_t)(v > 0.0f ? 1 : 0);
+                    const float b = (a.bias && m < a.Mtot) ? a.bias[m] : 0.0f;
+                    v = leaky(v + b, a.slope);
+                    int bi = 0;
+                    if (POOL_OUT) {
+                        // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
+                        const float o1 = __shfl_xor(v, 1, 64), o2 = __shfl_xor(v, 2, 64), o3 = __shfl_xor(v, 3, 64);
+                        if (o1 > v) { v = o1; bi = 1; }
+                        if (o2 > v) { v = o2; bi = 2; }
+                        if (o3 > v) { v = o3; bi = 3; }
+                    }
+                    if (pvalid && m < a.Mtot) {
+                        optr[(long long)m * ov.cs] = v;
+                        if (powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
                     }
                 }
             }
@@ -248,14 +264,14 @@ void launch_m(MfmaConvArgs& a, int stacks, hipStream_t s)
 {
     const int KK = K * K;
     constexpr int kCK = K == 1 ? 32 : 8;
-    const int waves_m = a.Mtot >= 128 ? 4 : a.Mtot >= 64 ? 2 : 1;
-    const int BM = 32 * waves_m;
-    const int CS = a.TI * (a.TR * (POOL_OUT ? 2 : 1) + 2 * (K / 2)) * (a.TC * (POOL_OUT ? 2 : 1) + 2 * (K / 2)) + a.cs_pad;
+    // output channels per workgroup: 128 (2x2 wavefronts of 64 x 128 pixels), 64 (1x4 of 64 x 64) or 32 (1x4 of 32 x 64)
+    const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
+    const int CS = a.TI * (a.TR * (POOL_OUT ? 2 : 1) + 2 * (K / 2)) * (a.TC * (POOL_OUT ? 2 : 1) + 2 * (K / 2));
     const size_t lds = (size_t)(KK * kCK * BM + kCK * CS) * sizeof(float);
     dim3 grid(a.tiles_x * a.tiles_y * a.tiles_i, (a.Mtot + BM - 1) / BM, stacks), block(256);
-    if (waves_m == 4) hipLaunchKernelGGL((k_conv_mfma<K, 4, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
-    else if (waves_m == 2) hipLaunchKernelGGL((k_conv_mfma<K, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((k_conv_mfma<K, 1, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    if (BM == 128) hipLaunchKernelGGL((k_conv_mfma<K, 2, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    else if (BM == 64) hipLaunchKernelGGL((k_conv_mfma<K, 1, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((k_conv_mfma<K, 1, 1, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
 }
 
 void rect_max(const RectTab& rt, int N, int M, int& mw, int& mh)
@@ -292,7 +308,6 @@ void mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hi
     const int S = c.pooled ? 2 : 1, P = c.K / 2;
     const TileChoice tc = choose_tile(mw, mh, c.batch, c.pooled ? kBN / 4 : kBN, S, P);
     a.TI = tc.TI; a.TR = tc.TR; a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_y = tc.tiles_y; a.tiles_i = tc.tiles_i;
-    a.cs_pad = 0;
     const int stacks = c.N * c.M;
     if (c.K == 3) { if (c.pooled) launch_m<3, true, false, false>(a, stacks, s); else launch_m<3, false, false, false>(a, stacks, s); }
     else          { if (c.pooled) launch_m<1, true, false, false>(a, stacks, s); else launch_m<1, false, false, false>(a, stacks, s); }
@@ -310,7 +325,6 @@ void mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* w
     int mw, mh; rect_max(c.rect, c.N, c.M, mw, mh);
     const TileChoice tc = choose_tile(mw, mh, c.batch, kBN, 1, c.K / 2);
     a.TI = tc.TI; a.TR = tc.TR; a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_y = tc.tiles_y; a.tiles_i = tc.tiles_i;
-    a.cs_pad = 0;
     const int stacks = c.N * c.M;
     if (c.K == 3) { if (c.pooled) launch_m<3, false, true, true>(a, stacks, s); else launch_m<3, false, true, false>(a, stacks, s); }
     else          { if (c.pooled) launch_m<1, false, true, true>(a, stacks, s); else launch_m<1, false, true, false>(a, stacks, s); }
