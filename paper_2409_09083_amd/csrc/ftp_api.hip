@@ -270,8 +270,10 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             ConvArgs a = conv_args(p, u, ub, weights, nullptr);
             a.partial = wgrad_partials;
             a.rect = make_rect(p, u.group, FTP_RECT_OWN, u.layer + 1);
-            if (use_mfma() && mfma_wgrad_eligible(a)) {
-                float* scratch = (float*)((char*)workspace + p.wgrad_scratch_offset);
+            float* scratch = (float*)((char*)workspace + p.wgrad_scratch_offset);
+            if (use_mfma() && thin_wgrad_eligible(a)) {
+                rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { thin_wgrad(a, scratch, s); });
+            } else if (use_mfma() && mfma_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { mfma_wgrad(a, scratch, s); });
             } else {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { direct_wgrad(a, s); });
@@ -285,6 +287,8 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
                     prep_filter((const float*)a.w, nullptr, wt, a.Cout, a.Cin, a.K, s);
                     mfma_conv_bwd_data(a, ext, wt, s);
                 });
+            } else if (use_mfma() && thin_bwd_data_eligible(a)) {
+                rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { thin_conv_bwd_data(a, s); });
             } else {
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { direct_conv_bwd_data(a, s); });
             }

@@ -48,7 +48,6 @@ struct MfmaConvArgs {
     int C, Mtot;                                    // reduction channels, output channels
     int Hc, Wc;                                     // map extent at the convolution
     int TI, TR, TC, tiles_x, tiles_y, tiles_i;      // tile: images x rows x columns, and tile counts
-    int cs_pad;
     float slope;
     int M, batch;
 };
@@ -74,6 +73,11 @@ struct MfmaWgradArgs {
 
 bool mfma_wgrad_eligible(const ConvArgs& a);
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s);
+
+bool thin_bwd_data_eligible(const ConvArgs& a);
+void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s);
+bool thin_wgrad_eligible(const ConvArgs& c);
+void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s);
 
 void direct_conv_fwd(const ConvArgs& a, hipStream_t s);
 void direct_conv_bwd_data(const ConvArgs& a, hipStream_t s);

@@ -51,6 +51,9 @@ k_wgrad_mfma(MfmaWgradArgs a)
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
 
     const int co_l = wave_co * 32 + l32, ci_l = wave_ci * 32 + l32;
+    // staging: lane -> (row within a pass, column)
+    const int zrows = 64 / TCp > 0 ? 64 / TCp : 1, zsub = lane / TCp, zcol = lane - zsub * TCp;
+    const int xrows = 64 / PW > 0 ? 64 / PW : 1, xsub = lane / PW, xcol = lane - xsub * PW;
 
     for (int n0 = nb0; n0 < nb1; n0 += TI) {
         const int ni = (nb1 - n0) < TI ? (nb1 - n0) : TI;
@@ -59,38 +62,72 @@ k_wgrad_mfma(MfmaWgradArgs a)
             const int nr = (y1 - yb + 1) < TR ? (y1 - yb + 1) : TR;
             __syncthreads();
             // ---- stage dZ: [image][row][padded column][co] -------------------------------------------------
+            // A wavefront covers `zrows` rows of TCp columns at once (lane -> row, column) and walks its share
+            // of the channels 8 at a time, so that 16 independent loads are in flight.
             {
-                const int npx = ni * nr * TCp;
-                for (int e = tid; e < npx * BCO; e += 256) {
-                    const int col = e % TCp, t1 = e / TCp;
-                    const int r = t1 % nr, t2 = t1 / nr;
-                    const int il = t2 % ni, c = t2 / ni;          // consecutive threads: consecutive columns
-                    const int co = co0 + c, qy = yb + r, qx = x0 + col, n = n0 + il;
-                    float v = 0.0f;
-                    if (col < rw && co < a.Cout) {
-                        const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
-                        const uint8_t m = *at<uint8_t>(a.mask, stack, ti, tj, n, co, sy, sx);
-                        if (!POOL || ((m >> 1) & 3) == (((qy & 1) << 1) | (qx & 1))) {
-                            const float g = *at<float>(a.din, stack, ti, tj, n, co, sy, sx);
-                            v = (m & 1) ? g : a.slope * g;
+                const int nrows = ni * nr;
+                for (int rbase = 0; rbase < nrows; rbase += zrows)
+                for (int cofs = 0; cofs < TCp; cofs += 64) {             // rows wider than a wavefront take several passes
+                    const int row = rbase + zsub, zc = zcol + cofs;
+                    const bool rok = zsub < zrows && row < nrows && zc < TCp;
+                    const int rowc = rok ? row : 0;
+                    const int il = rowc / nr, r = rowc - il * nr;
+                    const int qy = yb + r, qx = x0 + (zc < rw ? zc : rw - 1);
+                    const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
+                    const int code = ((qy & 1) << 1) | (qx & 1);
+                    const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, n0 + il, 0, sy, sx);
+                    const float* gp = at<float>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
+                    float* zdst = Zl + (rowc * TCp + (rok ? zc : 0)) * ZP;
+#pragma unroll
+                    for (int cb = 0; cb < BCO / 4; cb += 8) {
+                        uint8_t m[8]; float g[8];
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const int c = wave + 4 * (cb + k);
+                            const int co = co0 + c < a.Cout ? co0 + c : a.Cout - 1;
+                            m[k] = mp[(long long)co * a.mask.cs];
+                            g[k] = gp[(long long)co * a.din.cs];
+                        }
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const int c = wave + 4 * (cb + k);
+                            float v = (m[k] & 1) ? g[k] : a.slope * g[k];
+                            if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
+                            if (zc >= rw || co0 + c >= a.Cout) v = 0.0f;
+                            if (rok) zdst[c] = v;
                         }
                     }
-                    Zl[((il * nr + r) * TCp + col) * ZP + c] = v;
                 }
             }
             // ---- stage X: [image][patch row][patch column][ci] --------------------------------------------
             {
                 const int nph = nr + 2 * P;
-                const int npos = ni * nph * PW;
-                for (int e = tid; e < npos * BCI; e += 256) {
-                    const int col = e % PW, t1 = e / PW;
-                    const int r = t1 % nph, t2 = t1 / nph;
-                    const int il = t2 % ni, c = t2 / ni;
-                    const int ci = ci0 + c, gy = yb - P + r, gx = x0 - P + col, n = n0 + il;
-                    float v = 0.0f;
-                    if (ci < a.Cin && col < rw + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc)
-                        v = *at<float>(a.in, stack, ti, tj, n, ci, gy, gx);
-                    Xl[((il * PH + r) * PW + col) * XP + c] = v;
+                const int nprow = ni * nph;
+                for (int rbase = 0; rbase < nprow; rbase += xrows)
+                for (int cofs = 0; cofs < PW; cofs += 64) {
+                    const int prow = rbase + xsub, xc = xcol + cofs;
+                    const bool rok = xsub < xrows && prow < nprow && xc < PW;
+                    const int prc = rok ? prow : 0;
+                    const int il = prc / nph, r = prc - il * nph;
+                    const int gy = yb - P + r, gx = x0 - P + xc;
+                    const bool inside = xc < rw + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
+                    const float* xp = at<float>(a.in, stack, ti, tj, n0 + il, 0, inside ? gy : y0, inside ? gx : x0);
+                    float* xdst = Xl + ((il * PH + r) * PW + (rok ? xc : 0)) * XP;
+#pragma unroll
+                    for (int cb = 0; cb < BCI / 4; cb += 8) {
+                        float g[8];
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const int c = wave + 4 * (cb + k);
+                            const int ci = ci0 + c < a.Cin ? ci0 + c : a.Cin - 1;
+                            g[k] = xp[(long long)ci * a.in.cs];
+                        }
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const int c = wave + 4 * (cb + k);
+                            if (rok) xdst[c] = (inside && ci0 + c < a.Cin) ? g[k] : 0.0f;
+                        }
+                    }
                 }
             }
             __syncthreads();

@@ -1,0 +1,316 @@
+// Kernels for the thin first layer (a handful of input channels, e.g. the 3-channel image), gfx950.
+// The layer is far from a dense contraction in its input-channel dimension, so
+//  * the delta towards the image (3 output channels) is a coalesced, LDS-tiled direct convolution:
+//    the dZ patch of 16 channels is staged once and every thread produces all input channels of a pixel;
+//  * the filter gradient puts (input channel, tap) - 27 columns - on the N side of one 32x32 MFMA tile
+//    and reduces over pixels, so the matrix cores are used without padding the 3 channels to 32.
+#include "ftp_device.h"
+#include "ftp_launch.h"
+
+namespace ftp {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// dZ of one element from the delta and the owner's decision code (see ftp_direct.hip: delta_z).
+template <typename T, bool POOL>
+__device__ __forceinline__ float thin_delta_z(const View& din, const View& mask, int stack, int ti, int tj,
+                                              int n, int co, int qy, int qx, float slope)
+{
+    const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
+    const uint8_t m = *at<uint8_t>(mask, stack, ti, tj, n, co, sy, sx);
+    if (POOL && ((m >> 1) & 3) != (((qy & 1) << 1) | (qx & 1))) return 0.0f;
+    const float g = ld(at<T>(din, stack, ti, tj, n, co, sy, sx));
+    return (m & 1) ? g : slope * g;
+}
+
+// ---- delta at the input of a convolution with at most CIT input channels ------------------------------------
+// Workgroup = 16 x 16 pixels of one (stack, image); LDS = dZ patch of COC channels with the filter halo.
+template <typename T, int K, bool POOL, int CIT>
+__global__ void __launch_bounds__(256)
+k_conv_bwd_data_thin(View din, View mask, View dout, RectTab rt, const T* __restrict__ w,
+                     int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch, int tiles_x)
+{
+    constexpr int P = K / 2, TS = 16, PS = TS + 2 * P, PP = PS + 1, COC = 16;
+    __shared__ float dz[COC][PS][PP];
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    const int bx = blockIdx.x % tiles_x, by = blockIdx.x / tiles_x;
+    const int ox0 = rt.x0[tj] + bx * TS, oy0 = rt.y0[ti] + by * TS;
+    if (ox0 > rt.x1[tj] || oy0 > rt.y1[ti]) return;
+    const int tx = threadIdx.x % TS, ty = threadIdx.x / TS;
+    const int ix = ox0 + tx, iy = oy0 + ty;
+    float acc[CIT];
+#pragma unroll
+    for (int j = 0; j < CIT; ++j) acc[j] = 0.0f;
+    for (int c0 = 0; c0 < Cout; c0 += COC) {
+        __syncthreads();
+        // every thread owns fixed patch positions and walks the channels, 4 loads in flight at a time
+        for (int sp = threadIdx.x; sp < PS * PS; sp += 256) {
+            const int r = sp / PS, q = sp - r * PS;
+            const int qy = oy0 - P + r, qx = ox0 - P + q;
+            // dZ positions that only out-of-rectangle pixels of the tile would read may lie outside the delta view
+            const bool ok = qy >= 0 && qy < Hc && qx >= 0 && qx < Wc && qy <= rt.y1[ti] + P && qx <= rt.x1[tj] + P;
+            const int cy = ok ? qy : rt.y0[ti], cx = ok ? qx : rt.x0[tj];
+            const int sy = POOL ? (cy >> 1) : cy, sx = POOL ? (cx >> 1) : cx;
+            const int code = ((cy & 1) << 1) | (cx & 1);
+            const uint8_t* mp = at<uint8_t>(mask, stack, ti, tj, n, 0, sy, sx);
+            const T* gp = at<T>(din, stack, ti, tj, n, 0, sy, sx);
+#pragma unroll
+            for (int cb = 0; cb < COC; cb += 4) {
+                uint8_t m[4]; float g[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int co = c0 + cb + k < Cout ? c0 + cb + k : Cout - 1;
+                    m[k] = mp[(long long)co * mask.cs];
+                    g[k] = ld(gp + (long long)co * din.cs);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float v = (m[k] & 1) ? g[k] : slope * g[k];
+                    if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
+                    if (!ok || c0 + cb + k >= Cout) v = 0.0f;
+                    dz[cb + k][r][q] = v;
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int c = 0; c < COC; ++c) {
+            const int co = c0 + c;
+            if (co >= Cout) break;
+#pragma unroll
+            for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+                for (int kx = 0; kx < K; ++kx) {
+                    const float d = dz[c][ty + 2 * P - ky][tx + 2 * P - kx];
+#pragma unroll
+                    for (int j = 0; j < CIT; ++j)
+                        if (j < Cin) acc[j] = fmaf(ld(w + (((size_t)co * Cin + j) * K + ky) * K + kx), d, acc[j]);
+                }
+        }
+    }
+    if (ix <= rt.x1[tj] && iy <= rt.y1[ti]) {
+#pragma unroll
+        for (int j = 0; j < CIT; ++j)
+            if (j < Cin) st(at<T>(dout, stack, ti, tj, n, j, iy, ix), acc[j]);
+    }
+}
+
+bool thin_bwd_data_eligible(const ConvArgs& a) { return a.Cin <= 4; }
+
+void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
+{
+    int mw = 0, mh = 0;
+    for (int t = 0; t < a.M; ++t) mw = mw > a.rect.x1[t] - a.rect.x0[t] + 1 ? mw : a.rect.x1[t] - a.rect.x0[t] + 1;
+    for (int t = 0; t < a.N; ++t) mh = mh > a.rect.y1[t] - a.rect.y0[t] + 1 ? mh : a.rect.y1[t] - a.rect.y0[t] + 1;
+    const int tiles_x = (mw + 15) / 16, tiles_y = (mh + 15) / 16;
+    dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
+#define FTP_TB(T, KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_thin<T, KK, PL, 4>), grid, block, 0, s, a.din, a.mask, a.dout, a.rect, (const T*)a.w, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch, tiles_x)
+    if (a.bf16) {
+        if (a.K == 3) { if (a.pooled) FTP_TB(bf16_t, 3, true); else FTP_TB(bf16_t, 3, false); }
+        else          { if (a.pooled) FTP_TB(bf16_t, 1, true); else FTP_TB(bf16_t, 1, false); }
+    } else {
+        if (a.K == 3) { if (a.pooled) FTP_TB(float, 3, true); else FTP_TB(float, 3, false); }
+        else          { if (a.pooled) FTP_TB(float, 1, true); else FTP_TB(float, 1, false); }
+    }
+#undef FTP_TB
+}
+
+// ---- per-stack filter gradient with Cin*K*K <= 32 --------------------------------------------------------------
+// D[m = co][n = (ci, tap)] += sum over pixel pairs of dZ[co][pixel] * X[ci][pixel + tap - P].
+// Workgroup = 32 output channels of one stack and one batch share; its 4 wavefronts take alternate pixel
+// rows of each staged block and are summed in wavefront order at the end.
+template <int K, bool POOL>
+__global__ void __launch_bounds__(256)
+k_wgrad_mfma_thin(MfmaWgradArgs a)
+{
+    constexpr int KK = K * K, P = K / 2, ZP = 33;
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hi = lane >> 5, l32 = lane & 31;
+    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
+    const int x0 = a.own.x0[tj], x1 = a.own.x1[tj], y0 = a.own.y0[ti], y1 = a.own.y1[ti];
+    const int rw = x1 - x0 + 1, rh = y1 - y0 + 1;
+    const int co0 = blockIdx.x * 32;
+    const int split = blockIdx.y;
+    const int nb0 = (int)((long long)split * a.batch / a.splits), nb1 = (int)((long long)(split + 1) * a.batch / a.splits);
+
+    const int TCp = (rw + 1) & ~1;
+    int TR = a.PK / TCp; if (TR < 1) TR = 1; if (TR > rh) TR = rh;
+    int TI = 1;
+    if (TR == rh) { TI = a.PK / (TCp * rh); if (TI < 1) TI = 1; }
+    const int PW = TCp + 2 * P, PH = TR + 2 * P;
+    const int XCS = TI * PH * PW;                      // channel stride of the X patch
+    float* Zl = lds;                                   // [TI*TR*TCp][ZP]
+    float* Xl = lds + a.PK * ZP;                       // [Cin][TI][PH][PW]
+    const int row_blocks = (rh + TR - 1) / TR;
+
+    // B operand of lane n = (ci, tap): fixed offset into the patch
+    const int nn = l32 < a.Cin * KK ? l32 : 0;
+    const int lane_off = (nn / KK) * XCS + ((nn % KK) / K) * PW + (nn % KK) % K + hi;
+
+    v16f acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+
+    for (int n0 = nb0; n0 < nb1; n0 += TI) {
+        const int ni = (nb1 - n0) < TI ? (nb1 - n0) : TI;
+        for (int rb = 0; rb < row_blocks; ++rb) {
+            const int yb = y0 + rb * TR;
+            const int nr = (y1 - yb + 1) < TR ? (y1 - yb + 1) : TR;
+            __syncthreads();
+            // dZ rows: wavefront w takes channels w, w+4, ... (8 of them, loaded together); lanes run along the row
+            for (int row = 0; row < ni * nr; ++row) {
+                const int il = row / nr, r = row - il * nr;
+                const int qy = yb + r, sy = POOL ? (qy >> 1) : qy;
+                for (int col = lane; col < TCp; col += 64) {
+                    const int qx = x0 + (col < rw ? col : rw - 1), sx = POOL ? (qx >> 1) : qx;
+                    const int code = ((qy & 1) << 1) | (qx & 1);
+                    const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, n0 + il, 0, sy, sx);
+                    const float* gp = at<float>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
+                    uint8_t m[8]; float g[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const int co = co0 + wave + 4 * k < a.Cout ? co0 + wave + 4 * k : a.Cout - 1;
+                        m[k] = mp[(long long)co * a.mask.cs];
+                        g[k] = gp[(long long)co * a.din.cs];
+                    }
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        float v = (m[k] & 1) ? g[k] : a.slope * g[k];
+                        if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
+                        if (col >= rw || co0 + wave + 4 * k >= a.Cout) v = 0.0f;
+                        Zl[(row * TCp + col) * ZP + wave + 4 * k] = v;
+                    }
+                }
+            }
+            // X patch rows in natural order [ci][image][row][column]
+            {
+                const int nph = nr + 2 * P;
+                for (int prow = wave; prow < a.Cin * ni * nph; prow += 4) {
+                    const int ci = prow / (ni * nph), rem = prow - ci * (ni * nph);
+                    const int il = rem / nph, r = rem - il * nph;
+                    const int gy = yb - P + r;
+                    for (int col = lane; col < PW; col += 64) {
+                        const int gx = x0 - P + col;
+                        float v = 0.0f;
+                        if (col < rw + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc)
+                            v = *at<float>(a.in, stack, ti, tj, n0 + il, ci, gy, gx);
+                        Xl[ci * XCS + (il * PH + r) * PW + col] = v;
+                    }
+                }
+            }
+            __syncthreads();
+            const int nrows = ni * nr;
+            for (int rr = wave; rr < nrows; rr += 4) {
+                const int il = rr / nr, r = rr - il * nr;
+                const float* zrow = Zl + (rr * TCp + hi) * ZP + l32;
+                const float* xrow = Xl + lane_off + (il * PH + r) * PW;
+                for (int xp = 0; xp < TCp; xp += 2)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(zrow[xp * ZP], xrow[xp], acc, 0, 0, 0);
+            }
+        }
+    }
+
+    // sum the 4 wavefronts in order, then wavefront 0 stores D[co][(ci, tap)]
+    __syncthreads();
+    float* red = lds;                                  // [3][16][64]
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) red[((wave - 1) * 16 + i) * 64 + lane] = acc[i];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const long long layer_params = (long long)a.Cout * a.Cin * KK;
+        float* dst = a.splits > 1 ? a.scratch + ((long long)stack * a.splits + split) * layer_params
+                                  : a.partial + (long long)stack * a.n_params + a.w_off;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float v = ((acc[i] + red[(0 * 16 + i) * 64 + lane]) + red[(1 * 16 + i) * 64 + lane]) + red[(2 * 16 + i) * 64 + lane];
+            const int co = co0 + 8 * (i >> 2) + 4 * hi + (i & 3);
+            if (co < a.Cout && l32 < a.Cin * KK) dst[(long long)co * a.Cin * KK + l32] = v;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_thin_splitk_reduce(const float* __restrict__ scratch, float* __restrict__ partial, long long layer_params, long long n_params,
+                     long long w_off, int splits)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int stack = blockIdx.y;
+    if (i >= layer_params) return;
+    const float* src = scratch + (long long)stack * splits * layer_params + i;
+    float v = src[0];
+    for (int s = 1; s < splits; ++s) v += src[(long long)s * layer_params];
+    partial[(long long)stack * n_params + w_off + i] = v;
+}
+
+namespace {
+
+struct ThinGeom { int PK; size_t lds; };
+
+ThinGeom thin_geom(const ConvArgs& c)
+{
+    ThinGeom g;
+    g.PK = 256;
+    const int P = c.K / 2;
+    int max_pos = 1;
+    for (int t = 0; t < c.M; ++t) { const int w = ((c.rect.x1[t] - c.rect.x0[t] + 2) & ~1); if (w > g.PK) g.PK = w; }
+    for (int i = 0; i < c.N; ++i)
+        for (int j = 0; j < c.M; ++j) {
+            const int rw = c.rect.x1[j] - c.rect.x0[j] + 1, rh = c.rect.y1[i] - c.rect.y0[i] + 1;
+            const int TCp = (rw + 1) & ~1;
+            int TR = g.PK / TCp; if (TR < 1) TR = 1; if (TR > rh) TR = rh;
+            int TI = 1; if (TR == rh) { TI = g.PK / (TCp * rh); if (TI < 1) TI = 1; }
+            const int pos = TI * (TR + 2 * P) * (TCp + 2 * P);
+            if (pos > max_pos) max_pos = pos;
+        }
+    size_t words = (size_t)g.PK * 33 + (size_t)max_pos * c.Cin + 2;     // +2: the second pixel of the last pair
+    if (words < 3 * 16 * 64) words = 3 * 16 * 64;                         // final sum of the wavefronts
+    g.lds = words * sizeof(float);
+    return g;
+}
+
+}  // namespace
+
+int thin_wgrad_splits(int cout, int stacks, int batch)
+{
+    const int blocks = ((cout + 31) / 32) * stacks;
+    int shares = (1024 + blocks - 1) / blocks;
+    if (shares > batch) shares = batch;
+    return shares < 1 ? 1 : shares;
+}
+
+// c.rect must hold the owned rectangles.
+bool thin_wgrad_eligible(const ConvArgs& c)
+{
+    if (c.bf16 || c.has_bias || c.Cin * c.K * c.K > 32) return false;
+    return thin_geom(c).lds <= 64 * 1024;
+}
+
+void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
+{
+    MfmaWgradArgs a;
+    a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.rect;
+    a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
+    a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
+    a.splits = thin_wgrad_splits(c.Cout, c.N * c.M, c.batch);
+    const ThinGeom g = thin_geom(c);
+    a.PK = g.PK;
+    dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
+    if (c.K == 3) {
+        if (c.pooled) hipLaunchKernelGGL((k_wgrad_mfma_thin<3, true>), grid, block, g.lds, s, a);
+        else          hipLaunchKernelGGL((k_wgrad_mfma_thin<3, false>), grid, block, g.lds, s, a);
+    } else {
+        if (c.pooled) hipLaunchKernelGGL((k_wgrad_mfma_thin<1, true>), grid, block, g.lds, s, a);
+        else          hipLaunchKernelGGL((k_wgrad_mfma_thin<1, false>), grid, block, g.lds, s, a);
+    }
+    if (a.splits > 1) {
+        const long long lp = (long long)c.Cout * c.Cin * c.K * c.K;
+        dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);
+        hipLaunchKernelGGL(k_thin_splitk_reduce, g2, dim3(256), 0, s, scratch, c.partial, lp, c.n_params, c.w_off, a.splits);
+    }
+}
+
+}  // namespace ftp
