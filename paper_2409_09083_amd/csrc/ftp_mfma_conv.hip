@@ -139,27 +139,33 @@ k_conv_mfma(MfmaConvArgs a)
             if (ci < a.C && m < a.Mtot) v = *(const float4*)(wt + ((long long)tap * a.C + ci) * a.Mtot + m);
             *(float4*)(Wl + row * BM + c4 * 4) = v;
         }
-        // input patch
+        // input patch: every thread owns fixed positions and walks the stage's channels, 8 loads in flight
 #pragma unroll
         for (int j = 0; j < MAXPOS; ++j) {
             const int s = tid + j * 256;
             if (s < npos) {
-#pragma unroll 4
-                for (int cl = 0; cl < kCK; ++cl) {
-                    const int ci = c0 + cl;
-                    float v = 0.0f;
-                    if (goff[j] >= 0 && ci < a.C) {
-                        if (!DELTA_IN) {
-                            v = src[goff[j] + (long long)ci * sv.cs];
-                        } else {
-                            const uint8_t m = msk[(moff[j] & 0x1FFFFFFF) + (long long)ci * a.mask.cs];
-                            if (!POOL_IN || ((m >> 1) & 3) == ((unsigned)moff[j] >> 29)) {
-                                const float g = src[goff[j] + (long long)ci * sv.cs];
-                                v = (m & 1) ? g : a.slope * g;
-                            }
-                        }
+                const bool inside = goff[j] >= 0;
+                const int go = inside ? goff[j] : 0, mo = moff[j] & 0x1FFFFFFF;
+                const unsigned code = (unsigned)moff[j] >> 29;
+#pragma unroll
+                for (int cb = 0; cb < kCK; cb += 8) {
+                    float g[8]; uint8_t m[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const int ci = c0 + cb + k < a.C ? c0 + cb + k : a.C - 1;
+                        g[k] = src[go + (long long)ci * sv.cs];
+                        if (DELTA_IN) m[k] = msk[mo + (long long)ci * a.mask.cs];
                     }
-                    Xl[cl * CS + s] = v;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        float v = g[k];
+                        if (DELTA_IN) {
+                            v = (m[k] & 1) ? v : a.slope * v;
+                            if (POOL_IN && ((m[k] >> 1) & 3) != code) v = 0.0f;
+                        }
+                        if (!inside || c0 + cb + k >= a.C) v = 0.0f;
+                        Xl[(cb + k) * CS + s] = v;
+                    }
                 }
             }
         }
