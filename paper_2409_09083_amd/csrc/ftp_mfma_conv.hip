@@ -33,6 +33,10 @@ k_prep_filter(const float* __restrict__ w, float* __restrict__ wt_fwd, float* __
     if (wt_bwd) wt_bwd[((long long)(KK - 1 - t) * Cout + co) * Cin + ci] = v;
 }
 
+// Reduction channels staged per step: fewer for the 128-channel tile, whose accumulators leave fewer registers
+// for the prefetched next stage.
+__host__ __device__ constexpr int conv_stage_channels(int K, int BM) { return K == 1 ? (BM == 128 ? 16 : 32) : (BM == 128 ? 4 : 8); }
+
 // Pixel (or pool window) q of a tile -> image, row, column inside the tile.
 struct TilePix { int il, yl, xl; };
 __device__ __forceinline__ TilePix tile_pix(int wq, int per_img, int TC)
@@ -50,7 +54,7 @@ template <int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, bool POOL_IN
 __global__ void __launch_bounds__(256, 2)
 k_conv_mfma(MfmaConvArgs a)
 {
-    constexpr int kCK = K == 1 ? 32 : 8;             // reduction channels per LDS stage
+    constexpr int kCK = conv_stage_channels(K, 32 * MT * WAVES_M);   // reduction channels per LDS stage
     constexpr int WAVES_N = 4 / WAVES_M;
     constexpr int NT = kBN / 32 / WAVES_N;           // 32-pixel MFMA tiles per wavefront
     constexpr int BM = 32 * MT * WAVES_M;
@@ -89,7 +93,7 @@ k_conv_mfma(MfmaConvArgs a)
     const int baseA = hi * BM + wave_m * (32 * MT) + l32;
 
     // ---- per-thread patch positions (fixed over the channel loop): 32-bit offsets from per-workgroup bases ------
-    constexpr int MAXPOS = 3;
+    constexpr int MAXPOS = K == 1 ? 1 : 2;
     const int npos = a.TI * IS;
     const View& sv = DELTA_IN ? a.din : a.in;          // source of the patch values
     const float* __restrict__ src = (const float*)sv.p + (long long)stack * sv.ss + (long long)n0 * sv.ns;
@@ -127,49 +131,64 @@ k_conv_mfma(MfmaConvArgs a)
             for (int i = 0; i < 16; ++i) acc[mt][t][i] = 0.0f;
 
     const float* __restrict__ wt = a.wt;
-    for (int c0 = 0; c0 < a.C; c0 += kCK) {
-        __syncthreads();
-        // filter slice: KK*kCK rows of BM contiguous floats
-#pragma unroll 3
-        for (int idx = tid; idx < KK * kCK * (BM / 4); idx += 256) {
+    // Software pipeline: the next stage's filter slice and patch are fetched into registers while the matrix
+    // cores work on the current stage, and written to LDS between two barriers.
+    constexpr int WREG = (KK * kCK * (BM / 4) + 255) / 256;
+    float4 wreg[WREG];
+    float greg[MAXPOS][kCK];
+    uint8_t mreg[MAXPOS][kCK];
+    auto prefetch = [&](int c0) {
+#pragma unroll
+        for (int u = 0; u < WREG; ++u) {
+            const int idx = tid + u * 256;
             const int row = idx / (BM / 4), c4 = idx - row * (BM / 4);
             const int tap = row / kCK, cl = row - tap * kCK;
             const int ci = c0 + cl, m = m0 + c4 * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ci < a.C && m < a.Mtot) v = *(const float4*)(wt + ((long long)tap * a.C + ci) * a.Mtot + m);
-            *(float4*)(Wl + row * BM + c4 * 4) = v;
+            wreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < KK * kCK * (BM / 4) && ci < a.C && m < a.Mtot) wreg[u] = *(const float4*)(wt + ((long long)tap * a.C + ci) * a.Mtot + m);
         }
-        // input patch: every thread owns fixed positions and walks the stage's channels, 8 loads in flight
+#pragma unroll
+        for (int j = 0; j < MAXPOS; ++j) {
+            const int go = goff[j] >= 0 ? goff[j] : 0, mo = moff[j] & 0x1FFFFFFF;
+#pragma unroll
+            for (int k = 0; k < kCK; ++k) {
+                const int ci = c0 + k < a.C ? c0 + k : a.C - 1;
+                greg[j][k] = src[go + (long long)ci * sv.cs];
+                if (DELTA_IN) mreg[j][k] = msk[mo + (long long)ci * a.mask.cs];
+            }
+        }
+    };
+    auto commit = [&](int c0) {
+#pragma unroll
+        for (int u = 0; u < WREG; ++u) {
+            const int idx = tid + u * 256;
+            if (idx < KK * kCK * (BM / 4)) *(float4*)(Wl + idx * 4) = wreg[u];
+        }
 #pragma unroll
         for (int j = 0; j < MAXPOS; ++j) {
             const int s = tid + j * 256;
             if (s < npos) {
                 const bool inside = goff[j] >= 0;
-                const int go = inside ? goff[j] : 0, mo = moff[j] & 0x1FFFFFFF;
                 const unsigned code = (unsigned)moff[j] >> 29;
 #pragma unroll
-                for (int cb = 0; cb < kCK; cb += 8) {
-                    float g[8]; uint8_t m[8];
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        const int ci = c0 + cb + k < a.C ? c0 + cb + k : a.C - 1;
-                        g[k] = src[go + (long long)ci * sv.cs];
-                        if (DELTA_IN) m[k] = msk[mo + (long long)ci * a.mask.cs];
+                for (int k = 0; k < kCK; ++k) {
+                    float v = greg[j][k];
+                    if (DELTA_IN) {
+                        v = (mreg[j][k] & 1) ? v : a.slope * v;
+                        if (POOL_IN && ((mreg[j][k] >> 1) & 3) != code) v = 0.0f;
                     }
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        float v = g[k];
-                        if (DELTA_IN) {
-                            v = (m[k] & 1) ? v : a.slope * v;
-                            if (POOL_IN && ((m[k] >> 1) & 3) != code) v = 0.0f;
-                        }
-                        if (!inside || c0 + cb + k >= a.C) v = 0.0f;
-                        Xl[(cb + k) * CS + s] = v;
-                    }
+                    if (!inside || c0 + k >= a.C) v = 0.0f;
+                    Xl[k * CS + s] = v;
                 }
             }
         }
+    };
+    prefetch(0);
+    for (int c0 = 0; c0 < a.C; c0 += kCK) {
         __syncthreads();
+        commit(c0);
+        __syncthreads();
+        if (c0 + kCK < a.C) prefetch(c0 + kCK);
 #pragma unroll
         for (int tap = 0; tap < KK; ++tap) {
             const int toff = (tap / K) * PW + (tap % K);
@@ -256,8 +275,8 @@ TileChoice choose_tile(int rw, int rh, int batch, int cap /* pixels (or windows)
     }
     c.tiles_i = (batch + c.TI - 1) / c.TI;
     c.npos = c.TI * (c.TR * S + 2 * P) * (c.TC * S + 2 * P);
-    // the staging loop handles at most 3*256 patch positions per workgroup
-    while (c.npos > 768) {
+    // the staging registers hold at most 2*256 patch positions per workgroup (256 without a filter halo)
+    while (c.npos > (P > 0 ? 512 : 256)) {
         if (c.TI > 1) { --c.TI; c.tiles_i = (batch + c.TI - 1) / c.TI; }
         else { ++c.tiles_y; c.TR = (rh + c.tiles_y - 1) / c.tiles_y; }
         c.npos = c.TI * (c.TR * S + 2 * P) * (c.TC * S + 2 * P);
@@ -269,10 +288,10 @@ template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 void launch_m(MfmaConvArgs& a, int stacks, hipStream_t s)
 {
     const int KK = K * K;
-    constexpr int kCK = K == 1 ? 32 : 8;
     // output channels per workgroup: 128 (2x2 wavefronts of 64 x 128 pixels), 64 (1x4 of 64 x 64) or 32 (1x4 of 32 x 64)
     const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
     const int CS = a.TI * (a.TR * (POOL_OUT ? 2 : 1) + 2 * (K / 2)) * (a.TC * (POOL_OUT ? 2 : 1) + 2 * (K / 2));
+    const int kCK = conv_stage_channels(K, BM);
     const size_t lds = (size_t)(KK * kCK * BM + kCK * CS) * sizeof(float);
     dim3 grid(a.tiles_x * a.tiles_y * a.tiles_i, (a.Mtot + BM - 1) / BM, stacks), block(256);
     if (BM == 128) hipLaunchKernelGGL((k_conv_mfma<K, 2, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
