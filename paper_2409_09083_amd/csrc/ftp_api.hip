@@ -239,7 +239,7 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
                 const RectTab ext = view_extent(p, u.in_act, u.group, u.bi);
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] {
                     prep_filter((const float*)a.w, wt, nullptr, a.Cout, a.Cin, a.K, s);
-                    mfma_conv_fwd(a, ext, wt, s);
+                    if (mfma_conv_fwd(a, ext, wt, s)) direct_conv_fwd(a, s);
                 });
             } else {
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { direct_conv_fwd(a, s); });
@@ -285,7 +285,7 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
                 const RectTab ext = view_extent(p, u.in_delta, u.group, u.bo);
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] {
                     prep_filter((const float*)a.w, nullptr, wt, a.Cout, a.Cin, a.K, s);
-                    mfma_conv_bwd_data(a, ext, wt, s);
+                    if (mfma_conv_bwd_data(a, ext, wt, s)) direct_conv_bwd_data(a, s);
                 });
             } else if (use_mfma() && thin_bwd_data_eligible(a)) {
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { thin_conv_bwd_data(a, s); });

@@ -47,15 +47,17 @@ struct MfmaConvArgs {
     const float* bias;
     int C, Mtot;                                    // reduction channels, output channels
     int Hc, Wc;                                     // map extent at the convolution
-    int TI, TR, TC, tiles_x, tiles_y, tiles_i;      // tile: images x rows x columns, and tile counts
+    int TC, tiles_x, tiles_r;                       // column block (when tiles_x > 1), column / row-run tile counts
+    int cap;                                        // pixels (pool windows) per tile
+    int cs;                                         // LDS channel stride of the patch = largest patch of any stack
     float slope;
     int M, batch;
 };
 
 bool mfma_conv_eligible(const ConvArgs& a, bool backward);
 void prep_filter(const float* w, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s);
-void mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
-void mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
+int mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);       // non-zero: does not fit
+int mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
 
 // Kernel argument block of the matrix-core filter gradient.
 struct MfmaWgradArgs {

@@ -2,10 +2,13 @@
 // delta back-propagation (which is the same convolution with the 180-degree rotated, transposed
 // filter applied to dZ).  D[m][pixel] = sum_k Wt[k][m] * patch[k][pixel], k = (tap, channel).
 //
-// One workgroup (4 wavefronts) produces BM = 32*WAVES_M output channels for a tile of 256 pixels of
-// one stack: TI images x TR rows x TC columns of the stack's rectangle (pooled layers: 64 windows of
-// 4 pixels).  The input patch (tile + filter halo, zero outside the real map) and the filter slice
-// of 8 channels x K*K taps are staged in LDS; v_mfma_f32_32x32x2_f32 reads both from there.
+// One workgroup (4 wavefronts) produces BM = 32/64/128 output channels for a tile of up to 256 pixels of
+// one stack (pooled layers: 64 windows of 4 pixels).  A tile is a run of consecutive rows of the
+// stack's rectangle, counted through the batch (row index R = image * rows + row), times a block of
+// columns, so that small rectangles of several images fill one tile and medium ones leave no ragged
+// last tile per image.  The input patch (tile rows + filter halo per image, zero outside the real map)
+// and the filter slice of a few channels x K*K taps are staged in LDS; v_mfma_f32_32x32x2_f32 reads both
+// from there.  The next stage is prefetched into registers while the matrix cores work.
 // MFMA lane layout (64 lanes): A[m = lane%32][k = lane/32], B[k = lane/32][n = lane%32],
 // D[m = 8*(i/4) + 4*(lane/32) + i%4][n = lane%32] for accumulator register i of 16.
 #include "ftp_device.h"
@@ -19,7 +22,7 @@ constexpr int kBN = 256;        // pixels per workgroup tile
 
 // Filter relayout: OIHW -> [tap][reduction channel][output channel], so that a stage's slice is a set of
 // contiguous rows.  fwd: Wt[t][ci][co] = W[co][ci][t].  bwd: Wt[t][co][ci] = W[co][ci][K*K-1-t] (rotated).
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256)
 k_prep_filter(const float* __restrict__ w, float* __restrict__ wt_fwd, float* __restrict__ wt_bwd, int Cout, int Cin, int KK)
 {
     const long long n = (long long)Cout * Cin * KK;
@@ -36,16 +39,56 @@ k_prep_filter(const float* __restrict__ w, float* __restrict__ wt_fwd, float* __
 // Reduction channels staged per step: fewer for the 128-channel tile, whose accumulators leave fewer registers
 // for the prefetched next stage.
 __host__ __device__ constexpr int conv_stage_channels(int K, int BM) { return K == 1 ? (BM == 128 ? 16 : 32) : (BM == 128 ? 4 : 8); }
+__host__ __device__ constexpr int conv_max_positions(int K) { return K == 1 ? 256 : 512; }   // patch positions held in registers
 
-// Pixel (or pool window) q of a tile -> image, row, column inside the tile.
-struct TilePix { int il, yl, xl; };
-__device__ __forceinline__ TilePix tile_pix(int wq, int per_img, int TC)
+// Geometry of one tile: rows R0 .. R0+nrows-1 of the batch-flattened row index, columns ox0 .. ox0+TC-1.
+struct TileGeom {
+    int rw, rh;            // the stack's rectangle
+    int TC, ox0;           // column block
+    int R0, nrows;         // flattened rows
+    int n_a, y_a;          // first image and its first row
+    int PW;                // patch row length
+    int first_cnt, per_cnt;// patch rows of the first image / of every further image
+    int npos;              // patch positions
+    bool empty;
+};
+
+template <int S, int P>
+__device__ __forceinline__ TileGeom tile_geom(const MfmaConvArgs& a, int x0, int x1, int y0, int y1, int bx)
+{
+    TileGeom g;
+    g.rw = x1 - x0 + 1; g.rh = y1 - y0 + 1;
+    const int tx = bx % a.tiles_x, tb = bx / a.tiles_x;
+    g.TC = a.tiles_x == 1 ? g.rw : a.TC;
+    g.ox0 = x0 + tx * g.TC;
+    int trf = a.cap / g.TC; if (trf < 1) trf = 1;
+    const int rtot = a.batch * g.rh;
+    g.R0 = tb * trf;
+    g.empty = g.ox0 > x1 || g.R0 >= rtot;
+    g.nrows = rtot - g.R0 < trf ? rtot - g.R0 : trf;
+    g.n_a = g.R0 / g.rh; g.y_a = g.R0 - g.n_a * g.rh;
+    const int n_l = (g.R0 + g.nrows - 1) / g.rh;
+    g.PW = g.TC * S + 2 * P;
+    const int first_rows = g.rh - g.y_a < g.nrows ? g.rh - g.y_a : g.nrows;
+    g.first_cnt = S * first_rows + 2 * P;
+    g.per_cnt = S * g.rh + 2 * P;
+    g.npos = (S * g.nrows + 2 * P * (n_l - g.n_a + 1)) * g.PW;
+    return g;
+}
+
+// Pixel (or pool window) wq of a tile -> image, row (relative to the rectangle), column, and its patch row.
+struct TilePix { int n, y, xl, prow; bool valid; };
+template <int S, int P>
+__device__ __forceinline__ TilePix tile_pix(const TileGeom& g, int wq, int x1)
 {
     TilePix t;
-    t.il = wq / per_img;
-    const int rem = wq - t.il * per_img;
-    t.yl = rem / TC;
-    t.xl = rem - t.yl * TC;
+    const int fr = wq / g.TC;
+    t.xl = wq - fr * g.TC;
+    const int R = g.R0 + fr;
+    t.n = R / g.rh;
+    t.y = R - t.n * g.rh;
+    t.prow = S * fr + 2 * P * (t.n - g.n_a);
+    t.valid = fr < g.nrows && g.ox0 + t.xl <= x1;
     return t;
 }
 
@@ -63,41 +106,35 @@ k_conv_mfma(MfmaConvArgs a)
 
     extern __shared__ float lds[];
     float* Wl = lds;                                   // [KK][kCK][BM]
-    float* Xl = lds + KK * kCK * BM;                   // [kCK][TI][PH][PW]
+    float* Xl = lds + KK * kCK * BM;                   // [kCK][patch positions]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
     const int hi = lane >> 5, l32 = lane & 31;
     const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.rect.x0[tj], x1 = a.rect.x1[tj], y0 = a.rect.y0[ti], y1 = a.rect.y1[ti];
-    const int bx = blockIdx.x;
-    const int tx = bx % a.tiles_x, ty = (bx / a.tiles_x) % a.tiles_y, tb = bx / (a.tiles_x * a.tiles_y);
-    const int ox0 = x0 + tx * a.TC, oy0 = y0 + ty * a.TR, n0 = tb * a.TI;
-    if (ox0 > x1 || oy0 > y1) return;                 // this stack's rectangle is smaller than the largest one
+    const TileGeom g = tile_geom<S, P>(a, x0, x1, y0, y1, blockIdx.x);
+    if (g.empty) return;                              // this stack has fewer tiles than the largest one
     const int m0 = blockIdx.y * BM;
-    const int PW = a.TC * S + 2 * P, PH = a.TR * S + 2 * P;
-    const int IS = PH * PW, CS = a.TI * IS;
-    const int px0 = ox0 * S - P, py0 = oy0 * S - P;   // patch origin in the coordinates of the convolution input
-    const int per_img = a.TR * a.TC;
+    const int PW = g.PW, CS = a.cs;
 
     // ---- LDS offset of each lane's pixel, per 32-pixel tile ---------------------------------------------
     int baseB[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int q = (wave_n * NT + t) * 32 + l32;
-        const TilePix tp = tile_pix(POOL_OUT ? (q >> 2) : q, per_img, a.TC);
+        const TilePix tp = tile_pix<S, P>(g, POOL_OUT ? (q >> 2) : q, x1);
         const int pos = POOL_OUT ? (q & 3) : 0;
-        const bool v = tp.il < a.TI && n0 + tp.il < a.batch && oy0 + tp.yl <= y1 && ox0 + tp.xl <= x1;
-        baseB[t] = (v ? tp.il * IS + (tp.yl * S + (pos >> 1)) * PW + tp.xl * S + (pos & 1) : 0) + hi * CS;
+        baseB[t] = (tp.valid ? (tp.prow + (pos >> 1)) * PW + tp.xl * S + (pos & 1) : 0) + hi * CS;
     }
     const int baseA = hi * BM + wave_m * (32 * MT) + l32;
 
     // ---- per-thread patch positions (fixed over the channel loop): 32-bit offsets from per-workgroup bases ------
-    constexpr int MAXPOS = K == 1 ? 1 : 2;
-    const int npos = a.TI * IS;
+    constexpr int MAXPOS = conv_max_positions(K) / 256;
+    const int npos = g.npos;
     const View& sv = DELTA_IN ? a.din : a.in;          // source of the patch values
-    const float* __restrict__ src = (const float*)sv.p + (long long)stack * sv.ss + (long long)n0 * sv.ns;
-    const uint8_t* __restrict__ msk = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)n0 * a.mask.ns;
+    const float* __restrict__ src = (const float*)sv.p + (long long)stack * sv.ss + (long long)g.n_a * sv.ns;
+    const uint8_t* __restrict__ msk = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)g.n_a * a.mask.ns;
     int goff[MAXPOS];               // source element offset (channel 0); -1: zero padding / outside the view
     int moff[MAXPOS];               // DELTA_IN: offset in the decision-code map, winner code in the top bits
 #pragma unroll
@@ -105,16 +142,20 @@ k_conv_mfma(MfmaConvArgs a)
         const int s = tid + j * 256;
         goff[j] = -1; moff[j] = 0;
         if (s < npos) {
-            const int il = s / IS, rem = s - il * IS;
-            const int r = rem / PW, c = rem - r * PW;
-            const int gy = py0 + r, gx = px0 + c;
-            if (n0 + il < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc) {
+            const int pr = s / PW, c = s - pr * PW;
+            int k = 0, lr = pr, ybase = g.y_a * S;
+            if (pr >= g.first_cnt) {
+                const int t = pr - g.first_cnt;
+                k = 1 + t / g.per_cnt; lr = t - (k - 1) * g.per_cnt; ybase = 0;
+            }
+            const int gy = y0 * S + ybase + lr - P, gx = g.ox0 * S - P + c;   // coordinates at the convolution input
+            if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc) {
                 const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
                 // positions no valid output pixel of this stack reads may lie outside the view
                 if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
-                    goff[j] = il * (int)sv.ns + (sy - sv.y0[ti]) * sv.pitch + (sx - sv.x0[tj]);
+                    goff[j] = k * (int)sv.ns + (sy - sv.y0[ti]) * sv.pitch + (sx - sv.x0[tj]);
                     if (DELTA_IN) {
-                        moff[j] = il * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]);
+                        moff[j] = k * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]);
                         if (POOL_IN) moff[j] |= (((gy & 1) << 1) | (gx & 1)) << 29;
                     }
                 }
@@ -213,14 +254,14 @@ k_conv_mfma(MfmaConvArgs a)
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int q = (wave_n * NT + t) * 32 + l32;
-        const TilePix tp = tile_pix(POOL_OUT ? (q >> 2) : q, per_img, a.TC);
-        const int pn = n0 + tp.il, py = oy0 + tp.yl, pxx = ox0 + tp.xl;
-        bool pvalid = tp.il < a.TI && pn < a.batch && py <= y1 && pxx <= x1;
+        const TilePix tp = tile_pix<S, P>(g, POOL_OUT ? (q >> 2) : q, x1);
+        const int pn = tp.n, py = y0 + tp.y, pxx = g.ox0 + tp.xl;
+        bool pvalid = tp.valid;
         if (POOL_OUT) pvalid = pvalid && (lane & 3) == 0;       // the window's first lane stores
         const bool powned = pvalid && !DELTA_IN && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
         const View& ov = DELTA_IN ? a.dout : a.out;
-        float* __restrict__ optr = at<float>(ov, stack, ti, tj, pn, 0, py, pxx);
-        uint8_t* __restrict__ mptr = at<uint8_t>(a.mask, stack, ti, tj, pn, 0, py, pxx);
+        float* __restrict__ optr = at<float>(ov, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
+        uint8_t* __restrict__ mptr = at<uint8_t>(a.mask, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -253,57 +294,64 @@ k_conv_mfma(MfmaConvArgs a)
 // ---- host side ------------------------------------------------------------------------------------------------
 namespace {
 
-struct TileChoice { int TI, TR, TC, tiles_x, tiles_y, tiles_i, npos; };
+struct TileChoice { int TC, tiles_x, tiles_r, cap, cs; };
 
-// Largest rectangle of any stack decides the tile shape: whole rectangles of several images when they are
-// small, bands of rows otherwise, column blocks only for rectangles wider than a tile.
-TileChoice choose_tile(int rw, int rh, int batch, int cap /* pixels (or windows) per tile */, int S, int P)
+// Tile capacity (pixels or pool windows), column blocking and the worst-case patch size over all stacks.
+TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int S, int P, int max_pos)
 {
     TileChoice c;
-    c.TC = rw <= cap ? rw : cap;
-    if (c.TC > 64) c.TC = 64;
-    c.tiles_x = (rw + c.TC - 1) / c.TC;
-    c.TC = (rw + c.tiles_x - 1) / c.tiles_x;
-    int rows = cap / c.TC; if (rows < 1) rows = 1;
-    if (rows >= rh) {
-        c.TR = rh; c.tiles_y = 1;
-        c.TI = cap / (c.TC * c.TR); if (c.TI < 1) c.TI = 1; if (c.TI > batch) c.TI = batch;
-    } else {
-        c.tiles_y = (rh + rows - 1) / rows;
-        c.TR = (rh + c.tiles_y - 1) / c.tiles_y;
-        c.TI = 1;
-    }
-    c.tiles_i = (batch + c.TI - 1) / c.TI;
-    c.npos = c.TI * (c.TR * S + 2 * P) * (c.TC * S + 2 * P);
-    // the staging registers hold at most 2*256 patch positions per workgroup (256 without a filter halo)
-    while (c.npos > (P > 0 ? 512 : 256)) {
-        if (c.TI > 1) { --c.TI; c.tiles_i = (batch + c.TI - 1) / c.TI; }
-        else { ++c.tiles_y; c.TR = (rh + c.tiles_y - 1) / c.tiles_y; }
-        c.npos = c.TI * (c.TR * S + 2 * P) * (c.TC * S + 2 * P);
+    int mw = 0;
+    for (int t = 0; t < M; ++t) mw = mw > rt.x1[t] - rt.x0[t] + 1 ? mw : rt.x1[t] - rt.x0[t] + 1;
+    const int max_tc = 64 / S;                         // widest column block of a tile
+    c.tiles_x = (mw + max_tc - 1) / max_tc;
+    c.TC = (mw + c.tiles_x - 1) / c.tiles_x;
+    c.cap = cap0;
+    for (;;) {
+        c.tiles_r = 1; c.cs = 1;
+        bool fits = true;
+        for (int i = 0; i < N; ++i)
+            for (int j = 0; j < M; ++j) {
+                const int rw = rt.x1[j] - rt.x0[j] + 1, rh = rt.y1[i] - rt.y0[i] + 1;
+                const int tc = c.tiles_x == 1 ? rw : c.TC;
+                int trf = c.cap / tc; if (trf < 1) trf = 1;
+                const int rtot = batch * rh;
+                const int tiles = (rtot + trf - 1) / trf;
+                if (tiles > c.tiles_r) c.tiles_r = tiles;
+                int nimg = (trf + rh - 2) / rh + 1; if (nimg > batch) nimg = batch;
+                const int rows = trf < rtot ? trf : rtot;
+                const int npos = (S * rows + 2 * P * nimg) * (tc * S + 2 * P);
+                if (npos > c.cs) c.cs = npos;
+                if (npos > max_pos && trf > 1) fits = false;
+            }
+        if (fits || c.cap <= 8) break;
+        c.cap -= c.cap / 8;
     }
     return c;
 }
 
 template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
-void launch_m(MfmaConvArgs& a, int stacks, hipStream_t s)
+int launch_m(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
 {
     const int KK = K * K;
+    const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? kBN / 4 : kBN, POOL_OUT ? 2 : 1, K / 2, conv_max_positions(K));
+    if (tc.cs > conv_max_positions(K)) return 1;       // a single row of some stack does not fit the staging registers
+    a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_r = tc.tiles_r; a.cap = tc.cap; a.cs = tc.cs;
     // output channels per workgroup: 128 (2x2 wavefronts of 64 x 128 pixels), 64 (1x4 of 64 x 64) or 32 (1x4 of 32 x 64)
     const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
-    const int CS = a.TI * (a.TR * (POOL_OUT ? 2 : 1) + 2 * (K / 2)) * (a.TC * (POOL_OUT ? 2 : 1) + 2 * (K / 2));
     const int kCK = conv_stage_channels(K, BM);
-    const size_t lds = (size_t)(KK * kCK * BM + kCK * CS) * sizeof(float);
-    dim3 grid(a.tiles_x * a.tiles_y * a.tiles_i, (a.Mtot + BM - 1) / BM, stacks), block(256);
+    const size_t lds = (size_t)(KK * kCK * BM + kCK * a.cs) * sizeof(float);
+    dim3 grid(a.tiles_x * a.tiles_r, (a.Mtot + BM - 1) / BM, c.N * c.M), block(256);
     if (BM == 128) hipLaunchKernelGGL((k_conv_mfma<K, 2, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
     else if (BM == 64) hipLaunchKernelGGL((k_conv_mfma<K, 1, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
     else hipLaunchKernelGGL((k_conv_mfma<K, 1, 1, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    return 0;
 }
 
-void rect_max(const RectTab& rt, int N, int M, int& mw, int& mh)
+void fill_common(MfmaConvArgs& a, const ConvArgs& c, const RectTab& inrect)
 {
-    mw = 0; mh = 0;
-    for (int t = 0; t < M; ++t) mw = mw > rt.x1[t] - rt.x0[t] + 1 ? mw : rt.x1[t] - rt.x0[t] + 1;
-    for (int t = 0; t < N; ++t) mh = mh > rt.y1[t] - rt.y0[t] + 1 ? mh : rt.y1[t] - rt.y0[t] + 1;
+    a.in = c.in; a.out = c.out; a.mask = c.mask; a.din = c.din; a.dout = c.dout; a.rect = c.rect; a.own = c.own;
+    for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
+    a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
 }
 
 }  // namespace
@@ -321,38 +369,28 @@ void prep_filter(const float* w, float* wt_fwd, float* wt_bwd, int Cout, int Cin
     hipLaunchKernelGGL(k_prep_filter, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w, wt_fwd, wt_bwd, Cout, Cin, K * K);
 }
 
-// Forward: a.rect = held rectangle at the unit's output boundary; a.inrect = extent of the input view per stack.
-void mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
+// Forward: c.rect = forward rectangle at the unit's output boundary; inrect = extent of the input view per stack.
+// Returns non-zero if the layer's geometry does not fit this kernel (the caller then uses the direct kernel).
+int mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
 {
     MfmaConvArgs a;
-    a.in = c.in; a.out = c.out; a.mask = c.mask; a.din = c.din; a.dout = c.dout; a.rect = c.rect; a.own = c.own;
-    for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
+    fill_common(a, c, inrect);
     a.wt = wt; a.bias = (const float*)c.bias;
-    a.C = c.Cin; a.Mtot = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
-    int mw, mh; rect_max(c.rect, c.N, c.M, mw, mh);
-    const int S = c.pooled ? 2 : 1, P = c.K / 2;
-    const TileChoice tc = choose_tile(mw, mh, c.batch, c.pooled ? kBN / 4 : kBN, S, P);
-    a.TI = tc.TI; a.TR = tc.TR; a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_y = tc.tiles_y; a.tiles_i = tc.tiles_i;
-    const int stacks = c.N * c.M;
-    if (c.K == 3) { if (c.pooled) launch_m<3, true, false, false>(a, stacks, s); else launch_m<3, false, false, false>(a, stacks, s); }
-    else          { if (c.pooled) launch_m<1, true, false, false>(a, stacks, s); else launch_m<1, false, false, false>(a, stacks, s); }
+    a.C = c.Cin; a.Mtot = c.Cout;
+    if (c.K == 3) return c.pooled ? launch_m<3, true, false, false>(a, c, s) : launch_m<3, false, false, false>(a, c, s);
+    return c.pooled ? launch_m<1, true, false, false>(a, c, s) : launch_m<1, false, false, false>(a, c, s);
 }
 
-// Backward data: a.rect = backward rectangle at the unit's input boundary; inrect = extent of the delta view
+// Backward data: c.rect = backward rectangle at the unit's input boundary; inrect = extent of the delta view
 // (at the unit's output boundary, pooled coordinates if the unit has a pool).
-void mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
+int mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
 {
     MfmaConvArgs a;
-    a.in = c.in; a.out = c.out; a.mask = c.mask; a.din = c.din; a.dout = c.dout; a.rect = c.rect; a.own = c.own;
-    for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
+    fill_common(a, c, inrect);
     a.wt = wt; a.bias = nullptr;
-    a.C = c.Cout; a.Mtot = c.Cin; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
-    int mw, mh; rect_max(c.rect, c.N, c.M, mw, mh);
-    const TileChoice tc = choose_tile(mw, mh, c.batch, kBN, 1, c.K / 2);
-    a.TI = tc.TI; a.TR = tc.TR; a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_y = tc.tiles_y; a.tiles_i = tc.tiles_i;
-    const int stacks = c.N * c.M;
-    if (c.K == 3) { if (c.pooled) launch_m<3, false, true, true>(a, stacks, s); else launch_m<3, false, true, false>(a, stacks, s); }
-    else          { if (c.pooled) launch_m<1, false, true, true>(a, stacks, s); else launch_m<1, false, true, false>(a, stacks, s); }
+    a.C = c.Cout; a.Mtot = c.Cin;
+    if (c.K == 3) return c.pooled ? launch_m<3, false, true, true>(a, c, s) : launch_m<3, false, true, false>(a, c, s);
+    return c.pooled ? launch_m<1, false, true, true>(a, c, s) : launch_m<1, false, true, false>(a, c, s);
 }
 
 }  // namespace ftp
