@@ -14,13 +14,14 @@ namespace ftp {
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 template <int K, int WAVES_CO, int WAVES_CI, bool POOL>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 k_wgrad_mfma(MfmaWgradArgs a)
 {
     constexpr int WAVES_K = 4 / (WAVES_CO * WAVES_CI);
     constexpr int KK = K * K, P = K / 2;
     constexpr int BCO = 32 * WAVES_CO, BCI = 32 * WAVES_CI;
     constexpr int ZP = BCO + 1, XP = BCI + 1;          // odd strides: conflict-free transposing writes
+    constexpr int LB = K == 1 ? 8 : 4;                 // independent loads in flight per staging step
 
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -79,17 +80,17 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     const float* gp = at<float>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
                     float* zdst = Zl + (rowc * TCp + (rok ? zc : 0)) * ZP;
 #pragma unroll
-                    for (int cb = 0; cb < BCO / 4; cb += 8) {
-                        uint8_t m[8]; float g[8];
+                    for (int cb = 0; cb < BCO / 4; cb += LB) {
+                        uint8_t m[LB]; float g[LB];
 #pragma unroll
-                        for (int k = 0; k < 8; ++k) {
+                        for (int k = 0; k < LB; ++k) {
                             const int c = wave + 4 * (cb + k);
                             const int co = co0 + c < a.Cout ? co0 + c : a.Cout - 1;
                             m[k] = mp[(long long)co * a.mask.cs];
                             g[k] = gp[(long long)co * a.din.cs];
                         }
 #pragma unroll
-                        for (int k = 0; k < 8; ++k) {
+                        for (int k = 0; k < LB; ++k) {
                             const int c = wave + 4 * (cb + k);
                             float v = (m[k] & 1) ? g[k] : a.slope * g[k];
                             if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
@@ -114,16 +115,16 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     const float* xp = at<float>(a.in, stack, ti, tj, n0 + il, 0, inside ? gy : y0, inside ? gx : x0);
                     float* xdst = Xl + ((il * PH + r) * PW + (rok ? xc : 0)) * XP;
 #pragma unroll
-                    for (int cb = 0; cb < BCI / 4; cb += 8) {
-                        float g[8];
+                    for (int cb = 0; cb < BCI / 4; cb += LB) {
+                        float g[LB];
 #pragma unroll
-                        for (int k = 0; k < 8; ++k) {
+                        for (int k = 0; k < LB; ++k) {
                             const int c = wave + 4 * (cb + k);
                             const int ci = ci0 + c < a.Cin ? ci0 + c : a.Cin - 1;
                             g[k] = xp[(long long)ci * a.in.cs];
                         }
 #pragma unroll
-                        for (int k = 0; k < 8; ++k) {
+                        for (int k = 0; k < LB; ++k) {
                             const int c = wave + 4 * (cb + k);
                             if (rok) xdst[c] = (inside && ci0 + c < a.Cin) ? g[k] : 0.0f;
                         }
