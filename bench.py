@@ -84,27 +84,38 @@ def main():
     if args.per_kernel:
         for r in sorted(recs, key=lambda r: (r["layer"], r["pass"])):
             ms = r["total_ms"] / r["launches"]
-            print("%-14s layer %2d  %8.3f ms  %7.2f TFLOP/s  %7.1f GB/s" % (
-                r["pass"], r["layer"], ms, r["flops_per_launch"] / ms / 1e9, r["bytes_per_launch"] / ms / 1e6), file=sys.stderr)
+            print("%-14s layer %2d  %8.3f ms  %7.2f TFLOP/s  %7.1f GB/s  %s" % (
+                r["pass"], r["layer"], ms, r["flops_per_launch"] / ms / 1e9, r["bytes_per_launch"] / ms / 1e6, r["kernel"]), file=sys.stderr)
     ms_per_step = dt * 1e3 / args.steps
     images_per_s = cfg.batch * args.steps / dt
 
-    # roofline of the dominant kernel (largest share of the timed region)
-    dom = max(recs, key=lambda r: r["total_ms"])
-    avg_ms = dom["total_ms"] / dom["launches"]
-    ai = dom["flops_per_launch"] / max(dom["bytes_per_launch"], 1.0)
-    ly = cfg.layers[dom["layer"]] if dom["layer"] >= 0 else None
+    # roofline of the dominant kernel: the kernel symbol with the largest share of the timed region.  Its launches
+    # (one per layer that runs it) are pooled: achieved = algorithmic work of those launches / their summed duration,
+    # i.e. average algorithmic work per launch / average launch duration (what rocprofv3 --stats reports per symbol).
+    by_kernel = {}
+    for r in recs:
+        k = by_kernel.setdefault(r["kernel"], {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0, "layers": set()})
+        k["ms"] += r["total_ms"]
+        k["launches"] += r["launches"]
+        k["flops"] += r["flops_per_launch"] * r["launches"]
+        k["bytes"] += r["bytes_per_launch"] * r["launches"]
+        k["layers"].add(r["layer"])
+    name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
+    avg_ms = dom["ms"] / dom["launches"]
+    ai = dom["flops"] / max(dom["bytes"], 1.0)
     ridge = PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12 / (PEAK_HBM_GBS * 1e9)
-    if ly is not None and ly.kind == C.CONV and ai >= ridge:
+    if "mfma" in name and ai >= ridge:
         peak = PEAK_MFMA_TFLOPS[cfg.dtype]
-        roof = {"bound": "mfma", "achieved": dom["flops_per_launch"] / (avg_ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s"}
+        roof = {"bound": "mfma", "achieved": dom["flops"] / (dom["ms"] * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s"}
     else:
-        roof = {"bound": "hbm", "achieved": dom["bytes_per_launch"] / (avg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+        roof = {"bound": "hbm", "achieved": dom["bytes"] / (dom["ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = None
-    roof["kernel"] = "%s layer %d" % (dom["pass"], dom["layer"])
+    roof["kernel"] = name
+    roof["layers"] = sorted(dom["layers"])
+    roof["launches"] = dom["launches"]
     roof["avg_launch_ms"] = avg_ms
-    roof["share_of_step"] = dom["total_ms"] / (dt * 1e3)
+    roof["share_of_step"] = dom["ms"] / (dt * 1e3)
 
     phases = {}
     for r in recs:

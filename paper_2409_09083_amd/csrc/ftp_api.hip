@@ -123,7 +123,7 @@ int timed(const ftp_plan_s* plan, int pass, int layer, hipStream_t s, Fn&& launc
     (void)hipEventRecord(a, s);
     launch();
     (void)hipEventRecord(b, s);
-    pr.pending.push_back(Profiler::Rec{pass, layer, a, b});
+    pr.pending.push_back(Profiler::Rec{pass, layer, a, b, g_kernel_label});
     return check_hip();
 }
 
@@ -331,7 +331,7 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
         if (hipEventElapsedTime(&ms, (hipEvent_t)r.a, (hipEvent_t)r.b) != hipSuccess) { g_last_hip = (int)hipGetLastError(); return FTP_EHIP; }
         Profiler::Agg* hit = nullptr;
         for (Profiler::Agg& g : pr.agg) if (g.pass == r.pass && g.layer == r.layer) { hit = &g; break; }
-        if (!hit) { pr.agg.push_back(Profiler::Agg{r.pass, r.layer, 0, 0.0}); hit = &pr.agg.back(); }
+        if (!hit) { pr.agg.push_back(Profiler::Agg{r.pass, r.layer, 0, 0.0, r.kernel}); hit = &pr.agg.back(); }
         hit->launches += 1; hit->ms += ms;
     }
     pr.recycle();
@@ -342,6 +342,8 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
         ftp_kernel_time t;
         t.pass = g.pass; t.layer = g.layer; t.launches = g.launches; t.reserved = 0; t.total_ms = g.ms;
         t.flops_per_launch = 0; t.bytes_per_launch = 0;
+        std::memset(t.kernel, 0, sizeof(t.kernel));
+        if (g.kernel) std::strncpy(t.kernel, g.kernel, sizeof(t.kernel) - 1);
         if (g.pass == FTP_PASS_REDUCE) {
             t.bytes_per_launch = (stacks + 1.0) * (double)p.n_params * 4.0;
             t.flops_per_launch = (stacks - 1.0) * (double)p.n_params;
@@ -387,6 +389,8 @@ int ftp_last_hip_error(void) { return g_last_hip; }
 }  // extern "C"
 
 namespace ftp {
+
+thread_local const char* g_kernel_label = "";
 
 Profiler::event_t Profiler::get()
 {

@@ -286,12 +286,13 @@ void wgrad_t(const ConvArgs& a, hipStream_t s)
 
 }  // namespace
 
-void direct_conv_fwd(const ConvArgs& a, hipStream_t s) { if (a.bf16) conv_fwd_t<bf16_t>(a, s); else conv_fwd_t<float>(a, s); }
-void direct_conv_bwd_data(const ConvArgs& a, hipStream_t s) { if (a.bf16) conv_bwd_data_t<bf16_t>(a, s); else conv_bwd_data_t<float>(a, s); }
-void direct_wgrad(const ConvArgs& a, hipStream_t s) { if (a.bf16) wgrad_t<bf16_t>(a, s); else wgrad_t<float>(a, s); }
+void direct_conv_fwd(const ConvArgs& a, hipStream_t s) { g_kernel_label = "k_conv_fwd_direct"; if (a.bf16) conv_fwd_t<bf16_t>(a, s); else conv_fwd_t<float>(a, s); }
+void direct_conv_bwd_data(const ConvArgs& a, hipStream_t s) { g_kernel_label = "k_conv_bwd_data_direct"; if (a.bf16) conv_bwd_data_t<bf16_t>(a, s); else conv_bwd_data_t<float>(a, s); }
+void direct_wgrad(const ConvArgs& a, hipStream_t s) { g_kernel_label = "k_wgrad_direct"; if (a.bf16) wgrad_t<bf16_t>(a, s); else wgrad_t<float>(a, s); }
 
 void pool_fwd(const PoolArgs& a, hipStream_t s)
 {
+    g_kernel_label = "k_pool_fwd";
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
     if (a.bf16) hipLaunchKernelGGL(k_pool_fwd<bf16_t>, grid, block, 0, s, a.in, a.out, a.mask, a.rect, a.own, a.C, a.M, a.batch);
     else        hipLaunchKernelGGL(k_pool_fwd<float>, grid, block, 0, s, a.in, a.out, a.mask, a.rect, a.own, a.C, a.M, a.batch);
@@ -299,6 +300,7 @@ void pool_fwd(const PoolArgs& a, hipStream_t s)
 
 void pool_bwd(const PoolArgs& a, hipStream_t s)
 {
+    g_kernel_label = "k_pool_bwd";
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
     if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.mask, a.dout, a.rect, a.C, a.M, a.batch);
     else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.mask, a.dout, a.rect, a.C, a.M, a.batch);
@@ -306,6 +308,7 @@ void pool_bwd(const PoolArgs& a, hipStream_t s)
 
 void reduce_wgrad(const float* partial, float* wgrad, long long n_params, int stacks, hipStream_t s)
 {
+    g_kernel_label = "k_reduce_wgrad";
     dim3 grid((unsigned)((n_params + 255) / 256)), block(256);
     hipLaunchKernelGGL(k_reduce_wgrad, grid, block, 0, s, partial, wgrad, n_params, stacks);
 }

@@ -6,6 +6,9 @@
 
 namespace ftp {
 
+// Name of the main kernel of the most recent launch on this thread (for the timing records).
+extern thread_local const char* g_kernel_label;
+
 // One convolution unit (convolution + leaky ReLU, optionally with the 2x2 pool behind it).
 // Which fields a pass reads:
 //   forward        in (activation at the input), out (activation at the output), mask (decision codes at the

@@ -13,6 +13,7 @@
 // D[m = 8*(i/4) + 4*(lane/32) + i%4][n = lane%32] for accumulator register i of 16.
 #include "ftp_device.h"
 #include "ftp_launch.h"
+#include <cstdio>
 
 namespace ftp {
 
@@ -341,6 +342,11 @@ int launch_m(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     const int kCK = conv_stage_channels(K, BM);
     const size_t lds = (size_t)(KK * kCK * BM + kCK * a.cs) * sizeof(float);
     dim3 grid(a.tiles_x * a.tiles_r, (a.Mtot + BM - 1) / BM, c.N * c.M), block(256);
+    static char label[3][64];
+    const int v = BM == 128 ? 0 : BM == 64 ? 1 : 2;
+    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma<%d, %d, %d, %s, %s, %s>", K, BM == 128 ? 2 : 1, BM == 32 ? 1 : 2,
+                  POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false", POOL_IN ? "true" : "false");
+    g_kernel_label = label[v];
     if (BM == 128) hipLaunchKernelGGL((k_conv_mfma<K, 2, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
     else if (BM == 64) hipLaunchKernelGGL((k_conv_mfma<K, 1, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
     else hipLaunchKernelGGL((k_conv_mfma<K, 1, 1, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);

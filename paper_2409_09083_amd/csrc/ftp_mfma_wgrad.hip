@@ -14,14 +14,13 @@ namespace ftp {
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 template <int K, int WAVES_CO, int WAVES_CI, bool POOL>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256)
 k_wgrad_mfma(MfmaWgradArgs a)
 {
     constexpr int WAVES_K = 4 / (WAVES_CO * WAVES_CI);
     constexpr int KK = K * K, P = K / 2;
     constexpr int BCO = 32 * WAVES_CO, BCI = 32 * WAVES_CI;
     constexpr int ZP = BCO + 1, XP = BCI + 1;          // odd strides: conflict-free transposing writes
-    constexpr int LB = K == 1 ? 8 : 4;                 // independent loads in flight per staging step
 
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -79,24 +78,22 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, n0 + il, 0, sy, sx);
                     const float* gp = at<float>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
                     float* zdst = Zl + (rowc * TCp + (rok ? zc : 0)) * ZP;
+                    // all of this lane's loads are issued before the first use
+                    uint8_t m[BCO / 4]; float g[BCO / 4];
 #pragma unroll
-                    for (int cb = 0; cb < BCO / 4; cb += LB) {
-                        uint8_t m[LB]; float g[LB];
+                    for (int k = 0; k < BCO / 4; ++k) {
+                        const int c = wave + 4 * k;
+                        const int co = co0 + c < a.Cout ? co0 + c : a.Cout - 1;
+                        m[k] = mp[(long long)co * a.mask.cs];
+                        g[k] = gp[(long long)co * a.din.cs];
+                    }
 #pragma unroll
-                        for (int k = 0; k < LB; ++k) {
-                            const int c = wave + 4 * (cb + k);
-                            const int co = co0 + c < a.Cout ? co0 + c : a.Cout - 1;
-                            m[k] = mp[(long long)co * a.mask.cs];
-                            g[k] = gp[(long long)co * a.din.cs];
-                        }
-#pragma unroll
-                        for (int k = 0; k < LB; ++k) {
-                            const int c = wave + 4 * (cb + k);
-                            float v = (m[k] & 1) ? g[k] : a.slope * g[k];
-                            if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
-                            if (zc >= rw || co0 + c >= a.Cout) v = 0.0f;
-                            if (rok) zdst[c] = v;
-                        }
+                    for (int k = 0; k < BCO / 4; ++k) {
+                        const int c = wave + 4 * k;
+                        float v = (m[k] & 1) ? g[k] : a.slope * g[k];
+                        if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
+                        if (zc >= rw || co0 + c >= a.Cout) v = 0.0f;
+                        if (rok) zdst[c] = v;
                     }
                 }
             }
@@ -114,20 +111,17 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     const bool inside = xc < rw + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
                     const float* xp = at<float>(a.in, stack, ti, tj, n0 + il, 0, inside ? gy : y0, inside ? gx : x0);
                     float* xdst = Xl + ((il * PH + r) * PW + (rok ? xc : 0)) * XP;
+                    float g[BCI / 4];
 #pragma unroll
-                    for (int cb = 0; cb < BCI / 4; cb += LB) {
-                        float g[LB];
+                    for (int k = 0; k < BCI / 4; ++k) {
+                        const int c = wave + 4 * k;
+                        const int ci = ci0 + c < a.Cin ? ci0 + c : a.Cin - 1;
+                        g[k] = xp[(long long)ci * a.in.cs];
+                    }
 #pragma unroll
-                        for (int k = 0; k < LB; ++k) {
-                            const int c = wave + 4 * (cb + k);
-                            const int ci = ci0 + c < a.Cin ? ci0 + c : a.Cin - 1;
-                            g[k] = xp[(long long)ci * a.in.cs];
-                        }
-#pragma unroll
-                        for (int k = 0; k < LB; ++k) {
-                            const int c = wave + 4 * (cb + k);
-                            if (rok) xdst[c] = (inside && ci0 + c < a.Cin) ? g[k] : 0.0f;
-                        }
+                    for (int k = 0; k < BCI / 4; ++k) {
+                        const int c = wave + 4 * k;
+                        if (rok) xdst[c] = (inside && ci0 + c < a.Cin) ? g[k] : 0.0f;
                     }
                 }
             }
@@ -253,7 +247,7 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     const size_t lds = g.lds;
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
     dim3 grid(tiles, a.splits, c.N * c.M), block(256);
-#define FTP_WG(KK, WCI, PL) hipLaunchKernelGGL((k_wgrad_mfma<KK, 2, WCI, PL>), grid, block, lds, s, a)
+#define FTP_WG(KK, WCI, PL) do { g_kernel_label = "k_wgrad_mfma<" #KK ", 2, " #WCI ", " #PL ">"; hipLaunchKernelGGL((k_wgrad_mfma<KK, 2, WCI, PL>), grid, block, lds, s, a); } while (0)
     if (c.K == 3) {
         if (waves_ci == 2) { if (c.pooled) FTP_WG(3, 2, true); else FTP_WG(3, 2, false); }
         else               { if (c.pooled) FTP_WG(3, 1, true); else FTP_WG(3, 1, false); }

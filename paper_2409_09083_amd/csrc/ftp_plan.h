@@ -92,8 +92,8 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
 namespace ftp {
 struct Profiler {
     typedef void* event_t;              // hipEvent_t, kept opaque so that this header needs no HIP
-    struct Rec { int pass, layer; event_t a, b; };
-    struct Agg { int pass, layer, launches; double ms; };
+    struct Rec { int pass, layer; event_t a, b; const char* kernel; };
+    struct Agg { int pass, layer, launches; double ms; const char* kernel; };
     bool on = false;
     std::vector<Rec> pending;
     std::vector<event_t> free_list;

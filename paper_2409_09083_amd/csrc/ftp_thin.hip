@@ -105,6 +105,7 @@ void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
     for (int t = 0; t < a.N; ++t) mh = mh > a.rect.y1[t] - a.rect.y0[t] + 1 ? mh : a.rect.y1[t] - a.rect.y0[t] + 1;
     const int tiles_x = (mw + 15) / 16, tiles_y = (mh + 15) / 16;
     dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
+    g_kernel_label = "k_conv_bwd_data_thin";
 #define FTP_TB(T, KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_thin<T, KK, PL, 4>), grid, block, 0, s, a.din, a.mask, a.dout, a.rect, (const T*)a.w, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch, tiles_x)
     if (a.bf16) {
         if (a.K == 3) { if (a.pooled) FTP_TB(bf16_t, 3, true); else FTP_TB(bf16_t, 3, false); }
@@ -299,6 +300,7 @@ void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     const ThinGeom g = thin_geom(c);
     a.PK = g.PK;
     dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
+    g_kernel_label = "k_wgrad_mfma_thin";
     if (c.K == 3) {
         if (c.pooled) hipLaunchKernelGGL((k_wgrad_mfma_thin<3, true>), grid, block, g.lds, s, a);
         else          hipLaunchKernelGGL((k_wgrad_mfma_thin<3, false>), grid, block, g.lds, s, a);
