@@ -47,7 +47,7 @@ struct MfmaConvArgs {
     RectTab own;                                    // forward: owned part of it (decision codes are written there)
     int ix0[kTabGrid], ix1[kTabGrid], iy0[kTabGrid], iy1[kTabGrid];   // extent of the input view per tile column / row
     const float* wt;                                // relaid filter [tap][reduction channel][output channel]
-    const float* bias;
+    const void* bias;                               // element type of the maps
     int C, Mtot;                                    // reduction channels, output channels
     int Hc, Wc;                                     // map extent at the convolution
     int TC, tiles_x, tiles_r;                       // column block (when tiles_x > 1), column / row-run tile counts
@@ -58,7 +58,7 @@ struct MfmaConvArgs {
 };
 
 bool mfma_conv_eligible(const ConvArgs& a, bool backward);
-void prep_filter(const float* w, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s);
+void prep_filter(const void* w, int bf16, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s);
 int mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);       // non-zero: does not fit
 int mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
 

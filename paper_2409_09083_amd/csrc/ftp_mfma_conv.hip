@@ -23,8 +23,9 @@ constexpr int kBN = 256;        // pixels per workgroup tile
 
 // Filter relayout: OIHW -> [tap][reduction channel][output channel], so that a stage's slice is a set of
 // contiguous rows.  fwd: Wt[t][ci][co] = W[co][ci][t].  bwd: Wt[t][co][ci] = W[co][ci][K*K-1-t] (rotated).
+template <typename T>
 __global__ void __launch_bounds__(256)
-k_prep_filter(const float* __restrict__ w, float* __restrict__ wt_fwd, float* __restrict__ wt_bwd, int Cout, int Cin, int KK)
+k_prep_filter(const T* __restrict__ w, float* __restrict__ wt_fwd, float* __restrict__ wt_bwd, int Cout, int Cin, int KK)
 {
     const long long n = (long long)Cout * Cin * KK;
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -32,7 +33,7 @@ k_prep_filter(const float* __restrict__ w, float* __restrict__ wt_fwd, float* __
     const int t = (int)(i % KK);
     const int ci = (int)((i / KK) % Cin);
     const int co = (int)(i / ((long long)KK * Cin));
-    const float v = w[i];
+    const float v = ld(w + i);
     if (wt_fwd) wt_fwd[((long long)t * Cin + ci) * Cout + co] = v;
     if (wt_bwd) wt_bwd[((long long)(KK - 1 - t) * Cout + co) * Cin + ci] = v;
 }
@@ -94,7 +95,7 @@ __device__ __forceinline__ TilePix tile_pix(const TileGeom& g, int wq, int x1)
 }
 
 // WAVES_M x WAVES_N wavefronts; each computes MT x NT tiles of 32 channels x 32 pixels.
-template <int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+template <typename T, int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 __global__ void __launch_bounds__(256, 2)
 k_conv_mfma(MfmaConvArgs a)
 {
@@ -134,7 +135,7 @@ k_conv_mfma(MfmaConvArgs a)
     constexpr int MAXPOS = conv_max_positions(K) / 256;
     const int npos = g.npos;
     const View& sv = DELTA_IN ? a.din : a.in;          // source of the patch values
-    const float* __restrict__ src = (const float*)sv.p + (long long)stack * sv.ss + (long long)g.n_a * sv.ns;
+    const T* __restrict__ src = (const T*)sv.p + (long long)stack * sv.ss + (long long)g.n_a * sv.ns;
     const uint8_t* __restrict__ msk = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)g.n_a * a.mask.ns;
     int goff[MAXPOS];               // source element offset (channel 0); -1: zero padding / outside the view
     int moff[MAXPOS];               // DELTA_IN: offset in the decision-code map, winner code in the top bits
@@ -195,7 +196,7 @@ k_conv_mfma(MfmaConvArgs a)
 #pragma unroll
             for (int k = 0; k < kCK; ++k) {
                 const int ci = c0 + k < a.C ? c0 + k : a.C - 1;
-                greg[j][k] = src[go + (long long)ci * sv.cs];
+                greg[j][k] = ld(src + go + (long long)ci * sv.cs);
                 if (DELTA_IN) mreg[j][k] = msk[mo + (long long)ci * a.mask.cs];
             }
         }
@@ -261,7 +262,7 @@ k_conv_mfma(MfmaConvArgs a)
         if (POOL_OUT) pvalid = pvalid && (lane & 3) == 0;       // the window's first lane stores
         const bool powned = pvalid && !DELTA_IN && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
         const View& ov = DELTA_IN ? a.dout : a.out;
-        float* __restrict__ optr = at<float>(ov, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
+        T* __restrict__ optr = at<T>(ov, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
         uint8_t* __restrict__ mptr = at<uint8_t>(a.mask, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -270,10 +271,11 @@ k_conv_mfma(MfmaConvArgs a)
                 const int m = m0 + (wave_m * MT + mt) * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
                 float v = acc[mt][t][i];
                 if (DELTA_IN) {
-                    if (pvalid && m < a.Mtot) optr[(long long)m * ov.cs] = v;
+                    if (pvalid && m < a.Mtot) st(optr + (long long)m * ov.cs, v);
                 } else {
-                    const float b = (a.bias && m < a.Mtot) ? a.bias[m] : 0.0f;
-                    v = leaky(v + b, a.slope);
+                    const float b = (a.bias && m < a.Mtot) ? ld((const T*)a.bias + m) : 0.0f;
+                    // compared and recorded as the map will hold it (rounded to the storage type)
+                    v = stored(leaky(v + b, a.slope), (const T*)nullptr);
                     int bi = 0;
                     if (POOL_OUT) {
                         // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
@@ -283,7 +285,7 @@ k_conv_mfma(MfmaConvArgs a)
                         if (o3 > v) { v = o3; bi = 3; }
                     }
                     if (pvalid && m < a.Mtot) {
-                        optr[(long long)m * ov.cs] = v;
+                        st(optr + (long long)m * ov.cs, v);
                         if (powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
                     }
                 }
@@ -330,8 +332,8 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
     return c;
 }
 
-template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
-int launch_m(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
+template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
 {
     const int KK = K * K;
     const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? kBN / 4 : kBN, POOL_OUT ? 2 : 1, K / 2, conv_max_positions(K));
@@ -344,13 +346,19 @@ int launch_m(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     dim3 grid(a.tiles_x * a.tiles_r, (a.Mtot + BM - 1) / BM, c.N * c.M), block(256);
     static char label[3][64];
     const int v = BM == 128 ? 0 : BM == 64 ? 1 : 2;
-    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma<%d, %d, %d, %s, %s, %s>", K, BM == 128 ? 2 : 1, BM == 32 ? 1 : 2,
+    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma<%s, %d, %d, %d, %s, %s, %s>", sizeof(T) == 4 ? "float" : "unsigned short", K, BM == 128 ? 2 : 1, BM == 32 ? 1 : 2,
                   POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false", POOL_IN ? "true" : "false");
     g_kernel_label = label[v];
-    if (BM == 128) hipLaunchKernelGGL((k_conv_mfma<K, 2, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
-    else if (BM == 64) hipLaunchKernelGGL((k_conv_mfma<K, 1, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((k_conv_mfma<K, 1, 1, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    if (BM == 128) hipLaunchKernelGGL((k_conv_mfma<T, K, 2, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    else if (BM == 64) hipLaunchKernelGGL((k_conv_mfma<T, K, 1, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((k_conv_mfma<T, K, 1, 1, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
     return 0;
+}
+
+template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+int launch_m(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
+{
+    return c.bf16 ? launch_t<bf16_t, K, POOL_OUT, DELTA_IN, POOL_IN>(a, c, s) : launch_t<float, K, POOL_OUT, DELTA_IN, POOL_IN>(a, c, s);
 }
 
 void fill_common(MfmaConvArgs& a, const ConvArgs& c, const RectTab& inrect)
@@ -364,15 +372,16 @@ void fill_common(MfmaConvArgs& a, const ConvArgs& c, const RectTab& inrect)
 
 bool mfma_conv_eligible(const ConvArgs& a, bool backward)
 {
-    if (a.bf16) return false;
     const int Mtot = backward ? a.Cin : a.Cout, C = backward ? a.Cout : a.Cin;
     return Mtot >= 16 && Mtot % 4 == 0 && C >= 8;
 }
 
-void prep_filter(const float* w, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s)
+void prep_filter(const void* w, int bf16, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s)
 {
     const long long n = (long long)Cout * Cin * K * K;
-    hipLaunchKernelGGL(k_prep_filter, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w, wt_fwd, wt_bwd, Cout, Cin, K * K);
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (bf16) hipLaunchKernelGGL(k_prep_filter<bf16_t>, grid, block, 0, s, (const bf16_t*)w, wt_fwd, wt_bwd, Cout, Cin, K * K);
+    else      hipLaunchKernelGGL(k_prep_filter<float>, grid, block, 0, s, (const float*)w, wt_fwd, wt_bwd, Cout, Cin, K * K);
 }
 
 // Forward: c.rect = forward rectangle at the unit's output boundary; inrect = extent of the input view per stack.
@@ -381,7 +390,7 @@ int mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hip
 {
     MfmaConvArgs a;
     fill_common(a, c, inrect);
-    a.wt = wt; a.bias = (const float*)c.bias;
+    a.wt = wt; a.bias = c.bias;
     a.C = c.Cin; a.Mtot = c.Cout;
     if (c.K == 3) return c.pooled ? launch_m<3, true, false, false>(a, c, s) : launch_m<3, false, false, false>(a, c, s);
     return c.pooled ? launch_m<1, true, false, false>(a, c, s) : launch_m<1, false, false, false>(a, c, s);

@@ -13,7 +13,7 @@ namespace ftp {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-template <int K, int WAVES_CO, int WAVES_CI, bool POOL>
+template <typename T, int K, int WAVES_CO, int WAVES_CI, bool POOL>
 __global__ void __launch_bounds__(256)
 k_wgrad_mfma(MfmaWgradArgs a)
 {
@@ -76,7 +76,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
                     const int code = ((qy & 1) << 1) | (qx & 1);
                     const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, n0 + il, 0, sy, sx);
-                    const float* gp = at<float>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
+                    const T* gp = at<T>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
                     float* zdst = Zl + (rowc * TCp + (rok ? zc : 0)) * ZP;
                     // all of this lane's loads are issued before the first use
                     uint8_t m[BCO / 4]; float g[BCO / 4];
@@ -85,7 +85,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
                         const int c = wave + 4 * k;
                         const int co = co0 + c < a.Cout ? co0 + c : a.Cout - 1;
                         m[k] = mp[(long long)co * a.mask.cs];
-                        g[k] = gp[(long long)co * a.din.cs];
+                        g[k] = ld(gp + (long long)co * a.din.cs);
                     }
 #pragma unroll
                     for (int k = 0; k < BCO / 4; ++k) {
@@ -109,14 +109,14 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     const int il = prc / nph, r = prc - il * nph;
                     const int gy = yb - P + r, gx = x0 - P + xc;
                     const bool inside = xc < rw + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
-                    const float* xp = at<float>(a.in, stack, ti, tj, n0 + il, 0, inside ? gy : y0, inside ? gx : x0);
+                    const T* xp = at<T>(a.in, stack, ti, tj, n0 + il, 0, inside ? gy : y0, inside ? gx : x0);
                     float* xdst = Xl + ((il * PH + r) * PW + (rok ? xc : 0)) * XP;
                     float g[BCI / 4];
 #pragma unroll
                     for (int k = 0; k < BCI / 4; ++k) {
                         const int c = wave + 4 * k;
                         const int ci = ci0 + c < a.Cin ? ci0 + c : a.Cin - 1;
-                        g[k] = xp[(long long)ci * a.in.cs];
+                        g[k] = ld(xp + (long long)ci * a.in.cs);
                     }
 #pragma unroll
                     for (int k = 0; k < BCI / 4; ++k) {
@@ -223,7 +223,7 @@ WgradGeom wgrad_geom(const ConvArgs& c)
 // c.rect must hold the owned rectangles.
 bool mfma_wgrad_eligible(const ConvArgs& c)
 {
-    if (c.bf16 || c.has_bias || c.Cout < 32 || c.Cin < 16) return false;
+    if (c.has_bias || c.Cout < 32 || c.Cin < 16) return false;
     return wgrad_geom(c).lds <= 64 * 1024;
 }
 
@@ -247,7 +247,7 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     const size_t lds = g.lds;
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
     dim3 grid(tiles, a.splits, c.N * c.M), block(256);
-#define FTP_WG(KK, WCI, PL) do { g_kernel_label = "k_wgrad_mfma<" #KK ", 2, " #WCI ", " #PL ">"; hipLaunchKernelGGL((k_wgrad_mfma<KK, 2, WCI, PL>), grid, block, lds, s, a); } while (0)
+#define FTP_WG(KK, WCI, PL) do { if (c.bf16) { g_kernel_label = "k_wgrad_mfma<unsigned short, " #KK ", 2, " #WCI ", " #PL ">"; hipLaunchKernelGGL((k_wgrad_mfma<bf16_t, KK, 2, WCI, PL>), grid, block, lds, s, a); } else { g_kernel_label = "k_wgrad_mfma<float, " #KK ", 2, " #WCI ", " #PL ">"; hipLaunchKernelGGL((k_wgrad_mfma<float, KK, 2, WCI, PL>), grid, block, lds, s, a); } } while (0)
     if (c.K == 3) {
         if (waves_ci == 2) { if (c.pooled) FTP_WG(3, 2, true); else FTP_WG(3, 2, false); }
         else               { if (c.pooled) FTP_WG(3, 1, true); else FTP_WG(3, 1, false); }

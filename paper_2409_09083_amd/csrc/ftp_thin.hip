@@ -121,7 +121,7 @@ void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
 // D[m = co][n = (ci, tap)] += sum over pixel pairs of dZ[co][pixel] * X[ci][pixel + tap - P].
 // Workgroup = 32 output channels of one stack and one batch share; its 4 wavefronts take alternate pixel
 // rows of each staged block and are summed in wavefront order at the end.
-template <int K, bool POOL>
+template <typename T, int K, bool POOL>
 __global__ void __launch_bounds__(256)
 k_wgrad_mfma_thin(MfmaWgradArgs a)
 {
@@ -168,13 +168,13 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
                     const int qx = x0 + (col < rw ? col : rw - 1), sx = POOL ? (qx >> 1) : qx;
                     const int code = ((qy & 1) << 1) | (qx & 1);
                     const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, n0 + il, 0, sy, sx);
-                    const float* gp = at<float>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
+                    const T* gp = at<T>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
                     uint8_t m[8]; float g[8];
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
                         const int co = co0 + wave + 4 * k < a.Cout ? co0 + wave + 4 * k : a.Cout - 1;
                         m[k] = mp[(long long)co * a.mask.cs];
-                        g[k] = gp[(long long)co * a.din.cs];
+                        g[k] = ld(gp + (long long)co * a.din.cs);
                     }
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
@@ -196,7 +196,7 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
                         const int gx = x0 - P + col;
                         float v = 0.0f;
                         if (col < rw + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc)
-                            v = *at<float>(a.in, stack, ti, tj, n0 + il, ci, gy, gx);
+                            v = ld(at<T>(a.in, stack, ti, tj, n0 + il, ci, gy, gx));
                         Xl[ci * XCS + (il * PH + r) * PW + col] = v;
                     }
                 }
@@ -286,7 +286,7 @@ int thin_wgrad_splits(int cout, int stacks, int batch)
 // c.rect must hold the owned rectangles.
 bool thin_wgrad_eligible(const ConvArgs& c)
 {
-    if (c.bf16 || c.has_bias || c.Cin * c.K * c.K > 32) return false;
+    if (c.has_bias || c.Cin * c.K * c.K > 32) return false;
     return thin_geom(c).lds <= 64 * 1024;
 }
 
@@ -301,13 +301,15 @@ void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     a.PK = g.PK;
     dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
     g_kernel_label = "k_wgrad_mfma_thin";
-    if (c.K == 3) {
-        if (c.pooled) hipLaunchKernelGGL((k_wgrad_mfma_thin<3, true>), grid, block, g.lds, s, a);
-        else          hipLaunchKernelGGL((k_wgrad_mfma_thin<3, false>), grid, block, g.lds, s, a);
+#define FTP_TW(T, KK, PL) hipLaunchKernelGGL((k_wgrad_mfma_thin<T, KK, PL>), grid, block, g.lds, s, a)
+    if (c.bf16) {
+        if (c.K == 3) { if (c.pooled) FTP_TW(bf16_t, 3, true); else FTP_TW(bf16_t, 3, false); }
+        else          { if (c.pooled) FTP_TW(bf16_t, 1, true); else FTP_TW(bf16_t, 1, false); }
     } else {
-        if (c.pooled) hipLaunchKernelGGL((k_wgrad_mfma_thin<1, true>), grid, block, g.lds, s, a);
-        else          hipLaunchKernelGGL((k_wgrad_mfma_thin<1, false>), grid, block, g.lds, s, a);
+        if (c.K == 3) { if (c.pooled) FTP_TW(float, 3, true); else FTP_TW(float, 3, false); }
+        else          { if (c.pooled) FTP_TW(float, 1, true); else FTP_TW(float, 1, false); }
     }
+#undef FTP_TW
     if (a.splits > 1) {
         const long long lp = (long long)c.Cout * c.Cin * c.K * c.K;
         dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);
