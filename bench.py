@@ -42,6 +42,16 @@ def cpu_baseline(cfg, budget_images):
             "sample": "%d of %d images of the same workload, forward + backward, %.1f s" % (n, cfg.batch, dt)}
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc runs kept under profiles/ (None if not measured)."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +62,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-kernel", action="store_true", help="print the per-kernel timing table to stderr")
     ap.add_argument("--cpu-images", type=int, default=0, help="images for the oracle timing (0 = automatic)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run one plain device copy of 256 MiB (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -69,6 +81,13 @@ def main():
     del x, dy
     torch.cuda.synchronize()
 
+    if args.traffic_probe:
+        probe = torch.empty(2, 64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        probe[0].normal_()
+        torch.cuda.synchronize()
+        probe[1].copy_(probe[0])            # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del probe
     for _ in range(args.warmup):
         s.step()
     torch.cuda.synchronize()
@@ -110,7 +129,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dom["bytes"] / (dom["ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = measured_traffic(cfg.name, name)
     roof["kernel"] = name
     roof["layers"] = sorted(dom["layers"])
     roof["launches"] = dom["launches"]
