@@ -24,20 +24,21 @@ __device__ __forceinline__ float thin_delta_z(const View& din, const View& mask,
 }
 
 // ---- delta at the input of a convolution with at most CIT input channels ------------------------------------
-// Workgroup = 16 x 16 pixels of one (stack, image); LDS = dZ patch of COC channels with the filter halo.
+// Workgroup = 64 x 4 pixels of one (stack, image): wide tiles keep the reads of the (pooled) delta rows long.
+// LDS = dZ patch of COC channels with the filter halo.
 template <typename T, int K, bool POOL, int CIT>
 __global__ void __launch_bounds__(256)
 k_conv_bwd_data_thin(View din, View mask, View dout, RectTab rt, const T* __restrict__ w,
                      int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch, int tiles_x)
 {
-    constexpr int P = K / 2, TS = 16, PS = TS + 2 * P, PP = PS + 1, COC = 16;
-    __shared__ float dz[COC][PS][PP];
+    constexpr int P = K / 2, TSX = 64, TSY = 4, PSX = TSX + 2 * P, PSY = TSY + 2 * P, PP = PSX + 1, COC = 16;
+    __shared__ float dz[COC][PSY][PP];
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
     const int bx = blockIdx.x % tiles_x, by = blockIdx.x / tiles_x;
-    const int ox0 = rt.x0[tj] + bx * TS, oy0 = rt.y0[ti] + by * TS;
+    const int ox0 = rt.x0[tj] + bx * TSX, oy0 = rt.y0[ti] + by * TSY;
     if (ox0 > rt.x1[tj] || oy0 > rt.y1[ti]) return;
-    const int tx = threadIdx.x % TS, ty = threadIdx.x / TS;
+    const int tx = threadIdx.x % TSX, ty = threadIdx.x / TSX;
     const int ix = ox0 + tx, iy = oy0 + ty;
     float acc[CIT];
 #pragma unroll
@@ -45,8 +46,8 @@ k_conv_bwd_data_thin(View din, View mask, View dout, RectTab rt, const T* __rest
     for (int c0 = 0; c0 < Cout; c0 += COC) {
         __syncthreads();
         // every thread owns fixed patch positions and walks the channels, 4 loads in flight at a time
-        for (int sp = threadIdx.x; sp < PS * PS; sp += 256) {
-            const int r = sp / PS, q = sp - r * PS;
+        for (int sp = threadIdx.x; sp < PSY * PSX; sp += 256) {
+            const int r = sp / PSX, q = sp - r * PSX;
             const int qy = oy0 - P + r, qx = ox0 - P + q;
             // dZ positions that only out-of-rectangle pixels of the tile would read may lie outside the delta view
             const bool ok = qy >= 0 && qy < Hc && qx >= 0 && qx < Wc && qy <= rt.y1[ti] + P && qx <= rt.x1[tj] + P;
@@ -103,7 +104,7 @@ void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
     int mw = 0, mh = 0;
     for (int t = 0; t < a.M; ++t) mw = mw > a.rect.x1[t] - a.rect.x0[t] + 1 ? mw : a.rect.x1[t] - a.rect.x0[t] + 1;
     for (int t = 0; t < a.N; ++t) mh = mh > a.rect.y1[t] - a.rect.y0[t] + 1 ? mh : a.rect.y1[t] - a.rect.y0[t] + 1;
-    const int tiles_x = (mw + 15) / 16, tiles_y = (mh + 15) / 16;
+    const int tiles_x = (mw + 63) / 64, tiles_y = (mh + 3) / 4;
     dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
     g_kernel_label = "k_conv_bwd_data_thin";
 #define FTP_TB(T, KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_thin<T, KK, PL, 4>), grid, block, 0, s, a.din, a.mask, a.dout, a.rect, (const T*)a.w, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch, tiles_x)
