@@ -180,15 +180,19 @@ k_conv_mfma(MfmaConvArgs a)
     float4 wreg[WREG];
     float greg[MAXPOS][kCK];
     uint8_t mreg[MAXPOS][kCK];
+    // All loads are unconditional (addresses clamped into range) so that none of them has to be waited for
+    // before the next one is issued; what they should not have read is zeroed when it is written to LDS.
     auto prefetch = [&](int c0) {
 #pragma unroll
         for (int u = 0; u < WREG; ++u) {
-            const int idx = tid + u * 256;
+            int idx = tid + u * 256;
+            if (idx >= KK * kCK * (BM / 4)) idx = KK * kCK * (BM / 4) - 1;
             const int row = idx / (BM / 4), c4 = idx - row * (BM / 4);
             const int tap = row / kCK, cl = row - tap * kCK;
-            const int ci = c0 + cl, m = m0 + c4 * 4;
-            wreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (idx < KK * kCK * (BM / 4) && ci < a.C && m < a.Mtot) wreg[u] = *(const float4*)(wt + ((long long)tap * a.C + ci) * a.Mtot + m);
+            int ci = c0 + cl, m = m0 + c4 * 4;
+            if (ci >= a.C) ci = a.C - 1;
+            if (m >= a.Mtot) m = a.Mtot - 4;
+            wreg[u] = *(const float4*)(wt + ((long long)tap * a.C + ci) * a.Mtot + m);
         }
 #pragma unroll
         for (int j = 0; j < MAXPOS; ++j) {
@@ -205,7 +209,12 @@ k_conv_mfma(MfmaConvArgs a)
 #pragma unroll
         for (int u = 0; u < WREG; ++u) {
             const int idx = tid + u * 256;
-            if (idx < KK * kCK * (BM / 4)) *(float4*)(Wl + idx * 4) = wreg[u];
+            if (idx < KK * kCK * (BM / 4)) {
+                const int row = idx / (BM / 4), c4 = idx - row * (BM / 4);
+                const int cl = row % kCK;
+                const bool ok = c0 + cl < a.C && m0 + c4 * 4 < a.Mtot;
+                *(float4*)(Wl + idx * 4) = ok ? wreg[u] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
 #pragma unroll
         for (int j = 0; j < MAXPOS; ++j) {
@@ -232,22 +241,27 @@ k_conv_mfma(MfmaConvArgs a)
         commit(c0);
         __syncthreads();
         if (c0 + kCK < a.C) prefetch(c0 + kCK);
-#pragma unroll
-        for (int tap = 0; tap < KK; ++tap) {
+        // one step = 2 reduction channels of one tap; the operands of step j+1 are read from LDS before the
+        // matrix-core instructions of step j are issued, so the LDS latency hides behind them
+        constexpr int NSTEP = KK * (kCK / 2);
+        float av[2][MT], bv[2][NT];
+        auto load_step = [&](int j, int buf) {
+            const int tap = j / (kCK / 2), i = j - tap * (kCK / 2);
             const int toff = (tap / K) * PW + (tap % K);
 #pragma unroll
-            for (int i = 0; i < kCK / 2; ++i) {
-                float av[MT], bv[NT];
+            for (int mt = 0; mt < MT; ++mt) av[buf][mt] = Wl[(tap * kCK + 2 * i) * BM + baseA + 32 * mt];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) av[mt] = Wl[(tap * kCK + 2 * i) * BM + baseA + 32 * mt];
+            for (int t = 0; t < NT; ++t) bv[buf][t] = Xl[baseB[t] + 2 * i * CS + toff];
+        };
+        load_step(0, 0);
 #pragma unroll
-                for (int t = 0; t < NT; ++t) bv[t] = Xl[baseB[t] + 2 * i * CS + toff];
+        for (int j = 0; j < NSTEP; ++j) {
+            if (j + 1 < NSTEP) load_step(j + 1, (j + 1) & 1);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                    for (int t = 0; t < NT; ++t)
-                        acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt], bv[t], acc[mt][t], 0, 0, 0);
-            }
+                for (int t = 0; t < NT; ++t)
+                    acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j & 1][mt], bv[j & 1][t], acc[mt][t], 0, 0, 0);
         }
     }
 
