@@ -13,17 +13,24 @@ namespace ftp {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
+// LDS positions of one staged chunk: pixels of dZ, patch positions of X (a multiple of 64).
+constexpr int kWgradZPos = 64, kWgradXPos = 192;
+
 template <typename T, int K, int WAVES_CO, int WAVES_CI, bool POOL>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 k_wgrad_mfma(MfmaWgradArgs a)
 {
     constexpr int WAVES_K = 4 / (WAVES_CO * WAVES_CI);
     constexpr int KK = K * K, P = K / 2;
     constexpr int BCO = 32 * WAVES_CO, BCI = 32 * WAVES_CI;
     constexpr int ZP = BCO + 1, XP = BCI + 1;          // odd strides: conflict-free transposing writes
+    constexpr int NZ = BCO / 4, NX = BCI / 4;          // channels each wavefront stages
+    constexpr int ZPOS = kWgradZPos, XPOS = kWgradXPos, XPASS = XPOS / 64;
+    constexpr int MAXC = 64 - 2 * P;                   // widest column block: 3 patch rows fit XPOS
 
     extern __shared__ float lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: keeps the loop control scalar
     const int wave_co = wave % WAVES_CO, wave_ci = (wave / WAVES_CO) % WAVES_CI, wave_k = wave / (WAVES_CO * WAVES_CI);
     const int hi = lane >> 5, l32 = lane & 31;
     const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
@@ -34,15 +41,22 @@ k_wgrad_mfma(MfmaWgradArgs a)
     const int split = blockIdx.y;
     const int nb0 = (int)((long long)split * a.batch / a.splits), nb1 = (int)((long long)(split + 1) * a.batch / a.splits);
 
-    // chunk geometry for this stack: TI images x TR rows x rw columns (rows padded to even)
-    const int TCp = (rw + 1) & ~1;
-    int TR = a.PK / TCp; if (TR < 1) TR = 1; if (TR > rh) TR = rh;
-    int TI = 1;
-    if (TR == rh) { TI = a.PK / (TCp * rh); if (TI < 1) TI = 1; }
-    const int PW = TCp + 2 * P, PH = TR + 2 * P;      // patch rows as wide as the padded pixel rows
-    float* Zl = lds;                                   // [TI*TR*TCp][ZP]
-    float* Xl = lds + a.PK * ZP;                       // [TI*PH*PW][XP]
+    // Chunk geometry of this stack: TI images x TR rows x TC columns of the owned rectangle, at most ZPOS
+    // pixels (rows padded to an even length TCp) and at most XPOS patch positions.
+    const int col_blocks = (rw + MAXC - 1) / MAXC;
+    const int TC = (rw + col_blocks - 1) / col_blocks;
+    const int TCp = (TC + 1) & ~1, PW = TCp + 2 * P;
+    int TR = ZPOS / TCp; if (TR > rh) TR = rh;
     const int row_blocks = (rh + TR - 1) / TR;
+    int TI = 1;
+    if (TR == rh && col_blocks == 1) {
+        TI = ZPOS / (TCp * rh);
+        const int by_patch = XPOS / ((rh + 2 * P) * PW);
+        if (TI > by_patch) TI = by_patch;
+        if (TI < 1) TI = 1;
+    }
+    float* Zl = lds;                                   // [pixel][ZP]
+    float* Xl = lds + ZPOS * ZP;                       // [patch position][XP]
 
     v16f acc[KK];
 #pragma unroll
@@ -51,96 +65,132 @@ k_wgrad_mfma(MfmaWgradArgs a)
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
 
     const int co_l = wave_co * 32 + l32, ci_l = wave_ci * 32 + l32;
-    // staging: lane -> (row within a pass, column)
-    const int zrows = 64 / TCp > 0 ? 64 / TCp : 1, zsub = lane / TCp, zcol = lane - zsub * TCp;
-    const int xrows = 64 / PW > 0 ? 64 / PW : 1, xsub = lane / PW, xcol = lane - xsub * PW;
 
-    for (int n0 = nb0; n0 < nb1; n0 += TI) {
-        const int ni = (nb1 - n0) < TI ? (nb1 - n0) : TI;
-        for (int rb = 0; rb < row_blocks; ++rb) {
-            const int yb = y0 + rb * TR;
-            const int nr = (y1 - yb + 1) < TR ? (y1 - yb + 1) : TR;
+    struct Chunk { int n0, yb, xb, ni, nr, nc; };
+    auto chunk_at = [&](int n0, int rb, int cb) {
+        Chunk c;
+        c.n0 = n0; c.ni = (nb1 - n0) < TI ? (nb1 - n0) : TI;
+        c.yb = y0 + rb * TR; c.nr = (y1 - c.yb + 1) < TR ? (y1 - c.yb + 1) : TR;
+        c.xb = x0 + cb * TC; c.nc = (x1 - c.xb + 1) < TC ? (x1 - c.xb + 1) : TC;
+        return c;
+    };
+
+    // Registers that carry one chunk from HBM to LDS.  Lane -> position (pixel of dZ, patch position of X,
+    // both row-major over the chunk), wavefront -> every fourth channel; all loads are unconditional (clamped
+    // addresses) and independent, so they are in flight together, and what must be zero is zeroed at the
+    // LDS write.  zinfo: bit 0 position exists, bit 1 padding column, bits 2-3 the pixel's place in its pool
+    // window.  xinfo: per pass bit 0 position exists, bit 1 inside the map.
+    uint32_t zm[NZ]; float zg[NZ]; float xg[XPASS][NX];
+    int zinfo = 0, xinfo = 0;
+
+    auto load = [&](const Chunk& c) {
+        {
+            const int npos = c.ni * c.nr * TCp;
+            const bool ok = lane < npos;
+            const int p = ok ? lane : 0;
+            const int row = p / TCp, zc = p - row * TCp;
+            const int il = row / c.nr, r = row - il * c.nr;
+            const int qy = c.yb + r, qx = c.xb + (zc < c.nc ? zc : c.nc - 1);
+            const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
+            zinfo = (ok ? 1 : 0) | (zc >= c.nc ? 2 : 0) | ((((qy & 1) << 1) | (qx & 1)) << 2);
+            const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, c.n0 + il, 0, sy, sx);
+            const T* gp = at<T>(a.din, stack, ti, tj, c.n0 + il, 0, sy, sx);
+#pragma unroll
+            for (int k = 0; k < NZ; ++k) {
+                const int ch = wave + 4 * k;
+                const int co = co0 + ch < a.Cout ? co0 + ch : a.Cout - 1;
+                zm[k] = mp[(long long)co * a.mask.cs];
+                zg[k] = ld(gp + (long long)co * a.din.cs);
+            }
+        }
+        {
+            const int nph = c.nr + 2 * P;
+            const int npos = c.ni * nph * PW;
+            xinfo = 0;
+#pragma unroll
+            for (int pass = 0; pass < XPASS; ++pass) {
+                if (pass * 64 < npos) {
+                    const int pp = lane + 64 * pass;
+                    const bool ok = pp < npos;
+                    const int p = ok ? pp : 0;
+                    const int prow = p / PW, xc = p - prow * PW;
+                    const int il = prow / nph, r = prow - il * nph;
+                    const int gy = c.yb - P + r, gx = c.xb - P + xc;
+                    const bool inside = xc < c.nc + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
+                    xinfo |= ((ok ? 1 : 0) | (inside ? 2 : 0)) << (2 * pass);
+                    const T* xp = at<T>(a.in, stack, ti, tj, c.n0 + il, 0, inside ? gy : y0, inside ? gx : x0);
+#pragma unroll
+                    for (int k = 0; k < NX; ++k) {
+                        const int ch = wave + 4 * k;
+                        const int ci = ci0 + ch < a.Cin ? ci0 + ch : a.Cin - 1;
+                        xg[pass][k] = ld(xp + (long long)ci * a.in.cs);
+                    }
+                }
+            }
+        }
+    };
+
+    auto store = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): every load of the chunk has landed
+        if (zinfo & 1) {
+            float* zdst = Zl + lane * ZP;
+            const int code = (zinfo >> 2) & 3;
+#pragma unroll
+            for (int k = 0; k < NZ; ++k) {
+                const int ch = wave + 4 * k;
+                float v = (zm[k] & 1) ? zg[k] : a.slope * zg[k];
+                if (POOL && ((zm[k] >> 1) & 3) != (uint32_t)code) v = 0.0f;
+                if ((zinfo & 2) || co0 + ch >= a.Cout) v = 0.0f;
+                zdst[ch] = v;
+            }
+        }
+#pragma unroll
+        for (int pass = 0; pass < XPASS; ++pass) {
+            const int f = xinfo >> (2 * pass);
+            if (f & 1) {
+                float* xdst = Xl + (lane + 64 * pass) * XP;
+#pragma unroll
+                for (int k = 0; k < NX; ++k) {
+                    const int ch = wave + 4 * k;
+                    xdst[ch] = ((f & 2) && ci0 + ch < a.Cin) ? xg[pass][k] : 0.0f;
+                }
+            }
+        }
+    };
+
+    auto multiply = [&](const Chunk& c) {
+        const int nrows = c.ni * c.nr, nph = c.nr + 2 * P, ncp = (c.nc + 1) & ~1;
+        for (int rr = wave_k; rr < nrows; rr += WAVES_K) {
+            const int il = rr / c.nr, r = rr - il * c.nr;
+            const float* zrow = Zl + (rr * TCp + hi) * ZP + co_l;
+            const float* xrow = Xl + ((il * nph + r) * PW + hi) * XP + ci_l;
+            for (int xp = 0; xp < ncp; xp += 2) {
+                const float av = zrow[xp * ZP];
+#pragma unroll
+                for (int t = 0; t < KK; ++t) {
+                    const float bv = xrow[((t / K) * PW + xp + (t % K)) * XP];
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    // The next chunk travels from HBM into registers while the matrix cores work on the current one.
+    if (nb0 < nb1) {
+        int n0 = nb0, rb = 0, cb = 0;
+        Chunk cur = chunk_at(n0, rb, cb);
+        load(cur);
+        for (;;) {
+            __syncthreads();                            // the previous chunk has been consumed
+            store();
             __syncthreads();
-            // ---- stage dZ: [image][row][padded column][co] -------------------------------------------------
-            // A wavefront covers `zrows` rows of TCp columns at once (lane -> row, column) and walks its share
-            // of the channels 8 at a time, so that 16 independent loads are in flight.
-            {
-                const int nrows = ni * nr;
-                for (int rbase = 0; rbase < nrows; rbase += zrows)
-                for (int cofs = 0; cofs < TCp; cofs += 64) {             // rows wider than a wavefront take several passes
-                    const int row = rbase + zsub, zc = zcol + cofs;
-                    const bool rok = zsub < zrows && row < nrows && zc < TCp;
-                    const int rowc = rok ? row : 0;
-                    const int il = rowc / nr, r = rowc - il * nr;
-                    const int qy = yb + r, qx = x0 + (zc < rw ? zc : rw - 1);
-                    const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
-                    const int code = ((qy & 1) << 1) | (qx & 1);
-                    const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, n0 + il, 0, sy, sx);
-                    const T* gp = at<T>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
-                    float* zdst = Zl + (rowc * TCp + (rok ? zc : 0)) * ZP;
-                    // all of this lane's loads are issued before the first use
-                    uint8_t m[BCO / 4]; float g[BCO / 4];
-#pragma unroll
-                    for (int k = 0; k < BCO / 4; ++k) {
-                        const int c = wave + 4 * k;
-                        const int co = co0 + c < a.Cout ? co0 + c : a.Cout - 1;
-                        m[k] = mp[(long long)co * a.mask.cs];
-                        g[k] = ld(gp + (long long)co * a.din.cs);
-                    }
-#pragma unroll
-                    for (int k = 0; k < BCO / 4; ++k) {
-                        const int c = wave + 4 * k;
-                        float v = (m[k] & 1) ? g[k] : a.slope * g[k];
-                        if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
-                        if (zc >= rw || co0 + c >= a.Cout) v = 0.0f;
-                        if (rok) zdst[c] = v;
-                    }
-                }
-            }
-            // ---- stage X: [image][patch row][patch column][ci] --------------------------------------------
-            {
-                const int nph = nr + 2 * P;
-                const int nprow = ni * nph;
-                for (int rbase = 0; rbase < nprow; rbase += xrows)
-                for (int cofs = 0; cofs < PW; cofs += 64) {
-                    const int prow = rbase + xsub, xc = xcol + cofs;
-                    const bool rok = xsub < xrows && prow < nprow && xc < PW;
-                    const int prc = rok ? prow : 0;
-                    const int il = prc / nph, r = prc - il * nph;
-                    const int gy = yb - P + r, gx = x0 - P + xc;
-                    const bool inside = xc < rw + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
-                    const T* xp = at<T>(a.in, stack, ti, tj, n0 + il, 0, inside ? gy : y0, inside ? gx : x0);
-                    float* xdst = Xl + ((il * PH + r) * PW + (rok ? xc : 0)) * XP;
-                    float g[BCI / 4];
-#pragma unroll
-                    for (int k = 0; k < BCI / 4; ++k) {
-                        const int c = wave + 4 * k;
-                        const int ci = ci0 + c < a.Cin ? ci0 + c : a.Cin - 1;
-                        g[k] = ld(xp + (long long)ci * a.in.cs);
-                    }
-#pragma unroll
-                    for (int k = 0; k < BCI / 4; ++k) {
-                        const int c = wave + 4 * k;
-                        if (rok) xdst[c] = (inside && ci0 + c < a.Cin) ? g[k] : 0.0f;
-                    }
-                }
-            }
-            __syncthreads();
-            // ---- multiply ------------------------------------------------------------------------------------
-            const int nrows = ni * nr;
-            for (int rr = wave_k; rr < nrows; rr += WAVES_K) {
-                const int il = rr / nr, r = rr - il * nr;
-                const float* zrow = Zl + (rr * TCp + hi) * ZP + co_l;
-                const float* xrow = Xl + ((il * PH + r) * PW + hi) * XP + ci_l;
-                for (int xp = 0; xp < TCp; xp += 2) {
-                    const float av = zrow[xp * ZP];
-#pragma unroll
-                    for (int t = 0; t < KK; ++t) {
-                        const float bv = xrow[((t / K) * PW + xp + (t % K)) * XP];
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t], 0, 0, 0);
-                    }
-                }
-            }
+            if (++cb == col_blocks) { cb = 0; if (++rb == row_blocks) { rb = 0; n0 += TI; } }
+            const bool more = n0 < nb1;
+            Chunk nxt = cur;
+            if (more) { nxt = chunk_at(n0, rb, cb); load(nxt); }
+            multiply(cur);
+            if (!more) break;
+            cur = nxt;
         }
     }
 
@@ -192,44 +242,16 @@ k_wgrad_splitk_reduce(const float* __restrict__ scratch, float* __restrict__ par
     partial[(long long)stack * n_params + w_off + i] = v;
 }
 
-namespace {
-
-struct WgradGeom { int PK; size_t lds; int waves_ci; };
-
-// Pixels staged per step and the LDS the largest stack needs (c.rect = owned rectangles).
-WgradGeom wgrad_geom(const ConvArgs& c)
-{
-    WgradGeom g;
-    g.PK = 64;
-    const int P = c.K / 2;
-    int max_pos = 1;
-    for (int t = 0; t < c.M; ++t) { const int w = ((c.rect.x1[t] - c.rect.x0[t] + 2) & ~1); if (w > g.PK) g.PK = w; }   // one full padded row at least
-    for (int i = 0; i < c.N; ++i)
-        for (int j = 0; j < c.M; ++j) {
-            const int rw = c.rect.x1[j] - c.rect.x0[j] + 1, rh = c.rect.y1[i] - c.rect.y0[i] + 1;
-            const int TCp = (rw + 1) & ~1;
-            int TR = g.PK / TCp; if (TR < 1) TR = 1; if (TR > rh) TR = rh;
-            int TI = 1; if (TR == rh) { TI = g.PK / (TCp * rh); if (TI < 1) TI = 1; }
-            const int pos = TI * (TR + 2 * P) * (TCp + 2 * P);
-            if (pos > max_pos) max_pos = pos;
-        }
-    g.waves_ci = c.Cin >= 64 ? 2 : 1;
-    g.lds = ((size_t)g.PK * (64 + 1) + (size_t)max_pos * (32 * g.waves_ci + 1)) * sizeof(float);
-    return g;
-}
-
-}  // namespace
-
 // c.rect must hold the owned rectangles.
 bool mfma_wgrad_eligible(const ConvArgs& c)
 {
-    if (c.has_bias || c.Cout < 32 || c.Cin < 16) return false;
-    return wgrad_geom(c).lds <= 64 * 1024;
+    return !c.has_bias && c.Cout >= 32 && c.Cin >= 16;
 }
 
 int mfma_wgrad_splits(const ConvArgs& c)
 {
-    return wgrad_batch_shares(c.Cout, c.Cin, c.N * c.M, c.batch);
+    const int tile_px = ((c.Wc + c.M - 1) / c.M) * ((c.Hc + c.N - 1) / c.N);
+    return wgrad_batch_shares(c.Cout, c.Cin, c.K, c.N * c.M, c.batch, tile_px);
 }
 
 // c.rect = owned rectangle at the convolution output (before the pool); scratch holds the batch shares.
@@ -240,14 +262,19 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
     a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
     a.splits = mfma_wgrad_splits(c);
-    const WgradGeom g = wgrad_geom(c);
-    a.PK = g.PK;
-    const int waves_ci = g.waves_ci;
+    a.PK = kWgradZPos;
+    const int waves_ci = c.Cin >= 64 ? 2 : 1;
     const int BCO = 64, BCI = 32 * waves_ci;
-    const size_t lds = g.lds;
+    const size_t lds = ((size_t)kWgradZPos * (BCO + 1) + (size_t)kWgradXPos * (BCI + 1)) * sizeof(float);
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
     dim3 grid(tiles, a.splits, c.N * c.M), block(256);
-#define FTP_WG(KK, WCI, PL) do { if (c.bf16) { g_kernel_label = "k_wgrad_mfma<unsigned short, " #KK ", 2, " #WCI ", " #PL ">"; hipLaunchKernelGGL((k_wgrad_mfma<bf16_t, KK, 2, WCI, PL>), grid, block, lds, s, a); } else { g_kernel_label = "k_wgrad_mfma<float, " #KK ", 2, " #WCI ", " #PL ">"; hipLaunchKernelGGL((k_wgrad_mfma<float, KK, 2, WCI, PL>), grid, block, lds, s, a); } } while (0)
+    // more than 64 KB of dynamic LDS has to be granted per kernel, once
+#define FTP_WG1(TT, TN, KK, WCI, PL) do { \
+        static bool granted = false; \
+        if (!granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_mfma<TT, KK, 2, WCI, PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); granted = true; } \
+        g_kernel_label = "k_wgrad_mfma<" TN ", " #KK ", 2, " #WCI ", " #PL ">"; \
+        hipLaunchKernelGGL((k_wgrad_mfma<TT, KK, 2, WCI, PL>), grid, block, lds, s, a); } while (0)
+#define FTP_WG(KK, WCI, PL) do { if (c.bf16) FTP_WG1(bf16_t, "unsigned short", KK, WCI, PL); else FTP_WG1(float, "float", KK, WCI, PL); } while (0)
     if (c.K == 3) {
         if (waves_ci == 2) { if (c.pooled) FTP_WG(3, 2, true); else FTP_WG(3, 2, false); }
         else               { if (c.pooled) FTP_WG(3, 1, true); else FTP_WG(3, 1, false); }
@@ -256,6 +283,7 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
         else               { if (c.pooled) FTP_WG(1, 1, true); else FTP_WG(1, 1, false); }
     }
 #undef FTP_WG
+#undef FTP_WG1
     if (a.splits > 1) {
         const long long lp = (long long)c.Cout * c.Cin * c.K * c.K;
         dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);

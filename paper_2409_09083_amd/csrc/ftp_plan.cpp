@@ -237,7 +237,9 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
         for (const Unit& u : p.units) {
             if (u.kind != UNIT_CONV) continue;
             const ftp_layer& ly = p.layers[u.layer];
-            const int shares = wgrad_batch_shares(ly.cout, ly.cin, N * M, batch);
+            const int tile_px = ((p.W[u.bi] + M - 1) / M) * ((p.H[u.bi] + N - 1) / N);
+            const int shares = std::max(wgrad_batch_shares(ly.cout, ly.cin, ly.k, N * M, batch, tile_px),
+                                        wgrad_batch_shares_thin(ly.cout, N * M, batch));
             if (shares > 1) scratch = std::max(scratch, stacks * shares * (size_t)ly.cout * ly.cin * ly.k * ly.k * sizeof(float));
         }
         p.wgrad_scratch_offset = alloc(scratch);

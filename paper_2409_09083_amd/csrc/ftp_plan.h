@@ -72,11 +72,29 @@ struct Plan {
     double useful_macs = 0, executed_macs = 0, halo_bytes[2] = {0, 0};
 };
 
-// Number of batch shares the matrix-core filter-gradient kernel splits one stack's reduction into, so
-// that layers with few (co, ci) blocks still fill the chip; the shares are summed in a fixed order.
-inline int wgrad_batch_shares(int cout, int cin, int stacks, int batch)
+// Number of batch shares the matrix-core filter-gradient kernel splits one stack's reduction into.  A
+// workgroup handles one 64 x 64 block of (co, ci) of one stack and one share; the chip runs one such
+// workgroup per compute unit at a time, so the launch takes ceil(workgroups / 256) rounds of
+// ceil(batch / shares) images each.  The count that minimises rounds x images plus the cost of writing and
+// re-reading the shares (summed afterwards in a fixed order) is taken.  tile_px = pixels of the largest tile.
+inline int wgrad_batch_shares(int cout, int cin, int k, int stacks, int batch, int tile_px)
 {
-    const int blocks = ((cout + 63) / 64) * ((cin + 63) / 64) * stacks;
+    const double blocks = (double)((cout + 63) / 64) * ((cin + 63) / 64) * stacks;
+    const double unit_us = (double)tile_px * k * k * 32.0 / 2400.0 / 0.7;                 // one image of one block
+    const double share_us = (double)stacks * cout * cin * k * k * 8.0 / 3.0e6;          // one more share: write + read
+    int best = 1; double best_t = 0;
+    for (int s = 1; s <= batch; ++s) {
+        const double rounds = (double)(long long)((blocks * s + 255) / 256);
+        const double t = rounds * ((batch + s - 1) / s) * unit_us + (s > 1 ? s * share_us : 0.0);
+        if (s == 1 || t < best_t) { best = s; best_t = t; }
+    }
+    return best;
+}
+
+// The same for the kernel of layers with very few input channels (blocks of 32 output channels).
+inline int wgrad_batch_shares_thin(int cout, int stacks, int batch)
+{
+    const int blocks = ((cout + 31) / 32) * stacks;
     int shares = (1024 + blocks - 1) / blocks;
     if (shares > batch) shares = batch;
     return shares < 1 ? 1 : shares;

@@ -276,14 +276,6 @@ ThinGeom thin_geom(const ConvArgs& c)
 
 }  // namespace
 
-int thin_wgrad_splits(int cout, int stacks, int batch)
-{
-    const int blocks = ((cout + 31) / 32) * stacks;
-    int shares = (1024 + blocks - 1) / blocks;
-    if (shares > batch) shares = batch;
-    return shares < 1 ? 1 : shares;
-}
-
 // c.rect must hold the owned rectangles.
 bool thin_wgrad_eligible(const ConvArgs& c)
 {
@@ -297,7 +289,7 @@ void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.rect;
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
     a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
-    a.splits = thin_wgrad_splits(c.Cout, c.N * c.M, c.batch);
+    a.splits = wgrad_batch_shares_thin(c.Cout, c.N * c.M, c.batch);
     const ThinGeom g = thin_geom(c);
     a.PK = g.PK;
     dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
