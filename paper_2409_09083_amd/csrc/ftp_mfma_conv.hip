@@ -14,6 +14,8 @@
 #include "ftp_device.h"
 #include "ftp_launch.h"
 #include <cstdio>
+#include <cstdlib>
+#include <cstring>
 
 namespace ftp {
 
@@ -94,6 +96,67 @@ __device__ __forceinline__ TilePix tile_pix(const TileGeom& g, int wq, int x1)
     return t;
 }
 
+// Epilogue shared by the convolution kernels: bias, leaky ReLU, the fused 2x2 max-pool, the decision codes and
+// the stores.  A lane holds, per 32x32 tile, 16 channels (8*(i/4) + 4*hi + i%4) of one pixel.  `bias_lds` is LDS
+// no wavefront reads any more once all of them have arrived here (BM floats are used).
+template <typename T, int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, int NT>
+__device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileGeom& g, v16f (&acc)[MT][NT], float* bias_lds,
+                                              int m0, int x0, int x1, int y0, int stack, int ti, int tj)
+{
+    constexpr int BM = 32 * MT * WAVES_M;
+    constexpr int P = K / 2, S = POOL_OUT ? 2 : 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
+    const int hi = lane >> 5, l32 = lane & 31;
+    // The bias goes through LDS: a global load between the stores below would make every store wait for all
+    // earlier ones (loads and stores share one counter).
+    if (!DELTA_IN) {
+        __syncthreads();                               // every wavefront has left the multiply loop
+        if (tid < BM) bias_lds[tid] = (a.bias && m0 + tid < a.Mtot) ? ld((const T*)a.bias + m0 + tid) : 0.0f;
+        __syncthreads();
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int q = (wave_n * NT + t) * 32 + l32;
+        const TilePix tp = tile_pix<S, P>(g, POOL_OUT ? (q >> 2) : q, x1);
+        const int pn = tp.n, py = y0 + tp.y, pxx = g.ox0 + tp.xl;
+        bool pvalid = tp.valid;
+        if (POOL_OUT) pvalid = pvalid && (lane & 3) == 0;       // the window's first lane stores
+        const bool powned = pvalid && !DELTA_IN && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
+        const View& ov = DELTA_IN ? a.dout : a.out;
+        T* __restrict__ optr = at<T>(ov, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
+        uint8_t* __restrict__ mptr = at<uint8_t>(a.mask, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int ml = (wave_m * MT + mt) * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
+                const int m = m0 + ml;
+                float v = acc[mt][t][i];
+                if (DELTA_IN) {
+                    if (pvalid && m < a.Mtot) st(optr + (long long)m * ov.cs, v);
+                } else {
+                    // compared and recorded as the map will hold it (rounded to the storage type)
+                    v = stored(leaky(v + bias_lds[ml], a.slope), (const T*)nullptr);
+                    int bi = 0;
+                    if (POOL_OUT) {
+                        // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
+                        const float o1 = __shfl_xor(v, 1, 64), o2 = __shfl_xor(v, 2, 64), o3 = __shfl_xor(v, 3, 64);
+                        if (o1 > v) { v = o1; bi = 1; }
+                        if (o2 > v) { v = o2; bi = 2; }
+                        if (o3 > v) { v = o3; bi = 3; }
+                    }
+                    if (pvalid && m < a.Mtot) {
+                        st(optr + (long long)m * ov.cs, v);
+                        if (powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
+                    }
+                }
+            }
+        }
+    }
+}
+
 // WAVES_M x WAVES_N wavefronts; each computes MT x NT tiles of 32 channels x 32 pixels.
 template <typename T, int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 __global__ void __launch_bounds__(256, 2)
@@ -110,7 +173,8 @@ k_conv_mfma(MfmaConvArgs a)
     float* Wl = lds;                                   // [KK][kCK][BM]
     float* Xl = lds + KK * kCK * BM;                   // [kCK][patch positions]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: keeps what depends on it scalar
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
     const int hi = lane >> 5, l32 = lane & 31;
     const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
@@ -265,53 +329,174 @@ k_conv_mfma(MfmaConvArgs a)
         }
     }
 
-    // ---- epilogue ------------------------------------------------------------------------------------------
-    // A lane holds, per 32x32 tile, 16 channels (8*(i/4) + 4*hi + i%4) of one pixel.
+    conv_epilogue<T, K, WAVES_M, MT, POOL_OUT, DELTA_IN>(a, g, acc, lds, m0, x0, x1, y0, stack, ti, tj);
+}
+
+// ---- variant with direct HBM -> LDS loads (fp32 maps) ---------------------------------------------------------
+// The same tiles, multiply loop and epilogue, but a stage's patch and filter slice travel with
+// buffer_load_dword ... lds: every lane's dword lands in LDS at (wave-uniform base + 4 * lane), no registers and
+// no LDS-write instructions in between, and offsets beyond the buffer's records read as zero, which provides
+// the zero padding.  Two LDS buffers alternate: stage i+1 is in flight while the matrix cores work on stage i.
+#define FTP_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+constexpr unsigned kOobOffset = 0x80000000u;          // beyond the records of every buffer resource below
+constexpr unsigned kBufRecords = 0x7FFFFFFFu;
+__host__ __device__ constexpr int conv_dl_stage_channels(int K, int BM) { return K == 1 ? 16 : (BM == 128 ? 4 : 8); }
+
+template <int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN>
+__global__ void __launch_bounds__(256, 2)
+k_conv_mfma_dl(MfmaConvArgs a)
+{
+    typedef float T;
+    constexpr int WAVES_N = 4 / WAVES_M;
+    constexpr int NT = kBN / 32 / WAVES_N;
+    constexpr int BM = 32 * MT * WAVES_M;
+    constexpr int kCK = conv_dl_stage_channels(K, BM);
+    constexpr int KK = K * K, P = K / 2;
+    constexpr int S = POOL_OUT ? 2 : 1;
+    constexpr int XMAX = conv_max_positions(K);
+    constexpr int MAXPOS = XMAX / 256;
+    constexpr int WF = KK * kCK * BM;                  // floats of one filter slice [tap][channel][BM]
+    constexpr int WINSTR = WF / 64 / 4;                // filter load instructions per wavefront and stage
+    __shared__ float bufA[WF + kCK * XMAX];
+    __shared__ float bufB[WF + kCK * XMAX];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
+    const int hi = lane >> 5, l32 = lane & 31;
+    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
+    const int x0 = a.rect.x0[tj], x1 = a.rect.x1[tj], y0 = a.rect.y0[ti], y1 = a.rect.y1[ti];
+    const TileGeom g = tile_geom<S, P>(a, x0, x1, y0, y1, blockIdx.x);
+    if (g.empty) return;
+    const int m0 = blockIdx.y * BM;
+    const int PW = g.PW, CS = a.cs;                    // CS: a multiple of 64
+
+    int baseB[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int q = (wave_n * NT + t) * 32 + l32;
         const TilePix tp = tile_pix<S, P>(g, POOL_OUT ? (q >> 2) : q, x1);
-        const int pn = tp.n, py = y0 + tp.y, pxx = g.ox0 + tp.xl;
-        bool pvalid = tp.valid;
-        if (POOL_OUT) pvalid = pvalid && (lane & 3) == 0;       // the window's first lane stores
-        const bool powned = pvalid && !DELTA_IN && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
-        const View& ov = DELTA_IN ? a.dout : a.out;
-        T* __restrict__ optr = at<T>(ov, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
-        uint8_t* __restrict__ mptr = at<uint8_t>(a.mask, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
+        const int pos = POOL_OUT ? (q & 3) : 0;
+        baseB[t] = (tp.valid ? (tp.prow + (pos >> 1)) * PW + tp.xl * S + (pos & 1) : 0) + hi * CS;
+    }
+    const int baseA = hi * BM + wave_m * (32 * MT) + l32;
+
+    // ---- byte offset of each lane's patch positions from the workgroup's base (channel 0); padding -> out of range
+    const int npos = g.npos;
+    const View& sv = DELTA_IN ? a.din : a.in;
+    const T* src = (const T*)sv.p + (long long)stack * sv.ss + (long long)g.n_a * sv.ns;
+    unsigned xoff[MAXPOS];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
+    for (int j = 0; j < MAXPOS; ++j) {
+        const int s = tid + j * 256;
+        xoff[j] = kOobOffset;
+        if (s < npos) {
+            const int pr = s / PW, c = s - pr * PW;
+            int k = 0, lr = pr, ybase = g.y_a * S;
+            if (pr >= g.first_cnt) {
+                const int t = pr - g.first_cnt;
+                k = 1 + t / g.per_cnt; lr = t - (k - 1) * g.per_cnt; ybase = 0;
+            }
+            const int gy = y0 * S + ybase + lr - P, gx = g.ox0 * S - P + c;
+            if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc
+                && gy >= a.iy0[ti] && gy <= a.iy1[ti] && gx >= a.ix0[tj] && gx <= a.ix1[tj])
+                xoff[j] = 4u * (unsigned)(k * (int)sv.ns + (gy - sv.y0[ti]) * sv.pitch + (gx - sv.x0[tj]));
+        }
+    }
+    // filter: a load instruction covers 64 consecutive floats of the slice; with BM >= 64 that is (part of) one
+    // row, with BM = 32 two rows (two consecutive reduction channels)
+    unsigned woff;
+    {
+        const int col = BM >= 64 ? (wave % (BM / 64 > 0 ? BM / 64 : 1)) * 64 + lane : (lane & 31);
+        woff = m0 + col < a.Mtot ? 4u * (unsigned)((BM >= 64 ? 0 : (lane >> 5) * a.Mtot) + col) : kOobOffset;
+    }
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)src, (short)0, (int)kBufRecords, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.wt, (short)0, (int)kBufRecords, 0x00020000);
+
+    v16f acc[MT][NT];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int m = m0 + (wave_m * MT + mt) * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
-                float v = acc[mt][t][i];
-                if (DELTA_IN) {
-                    if (pvalid && m < a.Mtot) st(optr + (long long)m * ov.cs, v);
-                } else {
-                    const float b = (a.bias && m < a.Mtot) ? ld((const T*)a.bias + m) : 0.0f;
-                    // compared and recorded as the map will hold it (rounded to the storage type)
-                    v = stored(leaky(v + b, a.slope), (const T*)nullptr);
-                    int bi = 0;
-                    if (POOL_OUT) {
-                        // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
-                        const float o1 = __shfl_xor(v, 1, 64), o2 = __shfl_xor(v, 2, 64), o3 = __shfl_xor(v, 3, 64);
-                        if (o1 > v) { v = o1; bi = 1; }
-                        if (o2 > v) { v = o2; bi = 2; }
-                        if (o3 > v) { v = o3; bi = 3; }
-                    }
-                    if (pvalid && m < a.Mtot) {
-                        st(optr + (long long)m * ov.cs, v);
-                        if (powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
-                    }
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mt][t][i] = 0.0f;
+
+    auto issue = [&](float* buf, int c0) {
+        float* Wl = buf;
+        float* Xl = buf + WF;
+#pragma unroll
+        for (int u = 0; u < WINSTR; ++u) {
+            const int idx = wave + 4 * u;                              // 64-float piece of the slice
+            const int row = BM >= 64 ? idx / (BM / 64 > 0 ? BM / 64 : 1) : 2 * idx;
+            const int tap = row / kCK, k = row - tap * kCK;
+            const unsigned so = 4u * (unsigned)((tap * a.C + c0 + k) * a.Mtot + m0);
+            unsigned vo;
+            if (BM >= 64) vo = c0 + k < a.C ? woff : kOobOffset;
+            else          vo = c0 + k + (lane >> 5) < a.C ? woff : kOobOffset;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_LDS_PTR(Wl + idx * 64), 4, vo, so, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < MAXPOS; ++j) {
+            const int blk = wave + 4 * j;
+            if (blk * 64 < npos) {
+#pragma unroll
+                for (int k = 0; k < kCK; ++k) {
+                    const unsigned vo = c0 + k < a.C ? xoff[j] : kOobOffset;
+                    const unsigned so = 4u * (unsigned)((c0 + k) * (int)sv.cs);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_LDS_PTR(Xl + k * CS + blk * 64), 4, vo, so, 0, 0);
                 }
             }
         }
+    };
+
+    // one step = 2 reduction channels of one tap; the operands of step j+1 are read from LDS before the
+    // matrix-core instructions of step j are issued
+    auto multiply = [&](const float* buf) {
+        const float* Wl = buf;
+        const float* Xl = buf + WF;
+        constexpr int NSTEP = KK * (kCK / 2);
+        float av[2][MT], bv[2][NT];
+        auto load_step = [&](int j, int b) {
+            const int tap = j / (kCK / 2), i = j - tap * (kCK / 2);
+            const int toff = (tap / K) * PW + (tap % K);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) av[b][mt] = Wl[(tap * kCK + 2 * i) * BM + baseA + 32 * mt];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) bv[b][t] = Xl[baseB[t] + 2 * i * CS + toff];
+        };
+        load_step(0, 0);
+#pragma unroll
+        for (int j = 0; j < NSTEP; ++j) {
+            if (j + 1 < NSTEP) load_step(j + 1, (j + 1) & 1);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j & 1][mt], bv[j & 1][t], acc[mt][t], 0, 0, 0);
+        }
+    };
+
+    const int nst = (a.C + kCK - 1) / kCK;
+    issue(bufA, 0);
+    for (int st = 0; st < nst; st += 2) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's share of the stage has landed
+        __syncthreads();                               // ... and everybody's; the other buffer is free again
+        if (st + 1 < nst) issue(bufB, (st + 1) * kCK);
+        multiply(bufA);
+        if (st + 1 < nst) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            if (st + 2 < nst) issue(bufA, (st + 2) * kCK);
+            multiply(bufB);
+        }
     }
+    conv_epilogue<T, K, WAVES_M, MT, POOL_OUT, DELTA_IN>(a, g, acc, bufA, m0, x0, x1, y0, stack, ti, tj);
 }
 
 // ---- host side ------------------------------------------------------------------------------------------------
 namespace {
 
-struct TileChoice { int TC, tiles_x, tiles_r, cap, cs; };
+struct TileChoice { int TC, tiles_x, tiles_r, cap, cs, max_img; };
 
 // Tile capacity (pixels or pool windows), column blocking and the worst-case patch size over all stacks.
 TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int S, int P, int max_pos)
@@ -324,7 +509,7 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
     c.TC = (mw + c.tiles_x - 1) / c.tiles_x;
     c.cap = cap0;
     for (;;) {
-        c.tiles_r = 1; c.cs = 1;
+        c.tiles_r = 1; c.cs = 1; c.max_img = 1;
         bool fits = true;
         for (int i = 0; i < N; ++i)
             for (int j = 0; j < M; ++j) {
@@ -335,6 +520,7 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
                 const int tiles = (rtot + trf - 1) / trf;
                 if (tiles > c.tiles_r) c.tiles_r = tiles;
                 int nimg = (trf + rh - 2) / rh + 1; if (nimg > batch) nimg = batch;
+                if (nimg > c.max_img) c.max_img = nimg;
                 const int rows = trf < rtot ? trf : rtot;
                 const int npos = (S * rows + 2 * P * nimg) * (tc * S + 2 * P);
                 if (npos > c.cs) c.cs = npos;
@@ -346,6 +532,33 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
     return c;
 }
 
+// FTP_CONV_LOADS=staged keeps the register-staged kernel for fp32 maps too (for comparisons).
+bool direct_loads_enabled()
+{
+    static const bool on = [] { const char* e = getenv("FTP_CONV_LOADS"); return !(e && std::strcmp(e, "staged") == 0); }();
+    return on;
+}
+
+// Largest byte offset a workgroup forms from its base pointer: the images a tile can span plus all channels.
+bool offsets_fit_32bit(const MfmaConvArgs& a, const View& v, int max_img)
+{
+    const double bytes = 4.0 * ((double)max_img * (double)v.ns + (double)a.C * (double)v.cs);
+    return bytes < 2.0e9 && 4.0 * 9.0 * (double)a.C * (double)a.Mtot < 2.0e9;
+}
+
+template <int K, bool POOL_OUT, bool DELTA_IN>
+void launch_dl(const MfmaConvArgs& a, int BM, dim3 grid, hipStream_t s)
+{
+    static char label[3][64];
+    const int v = BM == 128 ? 0 : BM == 64 ? 1 : 2;
+    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%d, %d, %d, %s, %s>", K, BM == 128 ? 2 : 1, BM == 32 ? 1 : 2,
+                  POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false");
+    g_kernel_label = label[v];
+    if (BM == 128) hipLaunchKernelGGL((k_conv_mfma_dl<K, 2, 2, POOL_OUT, DELTA_IN>), grid, dim3(256), 0, s, a);
+    else if (BM == 64) hipLaunchKernelGGL((k_conv_mfma_dl<K, 1, 2, POOL_OUT, DELTA_IN>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((k_conv_mfma_dl<K, 1, 1, POOL_OUT, DELTA_IN>), grid, dim3(256), 0, s, a);
+}
+
 template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
 {
@@ -355,6 +568,11 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_r = tc.tiles_r; a.cap = tc.cap; a.cs = tc.cs;
     // output channels per workgroup: 128 (2x2 wavefronts of 64 x 128 pixels), 64 (1x4 of 64 x 64) or 32 (1x4 of 32 x 64)
     const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
+    if (sizeof(T) == 4 && !DELTA_IN && direct_loads_enabled() && offsets_fit_32bit(a, a.in, tc.max_img)) {
+        a.cs = (tc.cs + 63) & ~63;
+        launch_dl<K, POOL_OUT, false>(a, BM, dim3(a.tiles_x * a.tiles_r, (a.Mtot + BM - 1) / BM, c.N * c.M), s);
+        return 0;
+    }
     const int kCK = conv_stage_channels(K, BM);
     const size_t lds = (size_t)(KK * kCK * BM + kCK * a.cs) * sizeof(float);
     dim3 grid(a.tiles_x * a.tiles_r, (a.Mtot + BM - 1) / BM, c.N * c.M), block(256);
