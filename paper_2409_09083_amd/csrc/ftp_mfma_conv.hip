@@ -341,19 +341,20 @@ k_conv_mfma(MfmaConvArgs a)
 constexpr unsigned kOobOffset = 0x80000000u;          // beyond the records of every buffer resource below
 constexpr unsigned kBufRecords = 0x7FFFFFFFu;
 __host__ __device__ constexpr int conv_dl_stage_channels(int K, int BM) { return K == 1 ? 16 : (BM == 128 ? 4 : 8); }
+__host__ __device__ constexpr int conv_dl_max_positions(int K, int BN) { return K == 1 ? 256 : (BN == 256 ? 512 : 256); }   // patch positions in LDS
 
-template <int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN>
+template <int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN>
 __global__ void __launch_bounds__(256, 2)
 k_conv_mfma_dl(MfmaConvArgs a)
 {
     typedef float T;
     constexpr int WAVES_N = 4 / WAVES_M;
-    constexpr int NT = kBN / 32 / WAVES_N;
+    constexpr int NT = BN / 32 / WAVES_N;
     constexpr int BM = 32 * MT * WAVES_M;
     constexpr int kCK = conv_dl_stage_channels(K, BM);
     constexpr int KK = K * K, P = K / 2;
     constexpr int S = POOL_OUT ? 2 : 1;
-    constexpr int XMAX = conv_max_positions(K);
+    constexpr int XMAX = conv_dl_max_positions(K, BN);
     constexpr int MAXPOS = XMAX / 256;
     constexpr int WF = KK * kCK * BM;                  // floats of one filter slice [tap][channel][BM]
     constexpr int WINSTR = WF / 64 / 4;                // filter load instructions per wavefront and stage
@@ -369,7 +370,7 @@ k_conv_mfma_dl(MfmaConvArgs a)
     const TileGeom g = tile_geom<S, P>(a, x0, x1, y0, y1, blockIdx.x);
     if (g.empty) return;
     const int m0 = blockIdx.y * BM;
-    const int PW = g.PW, CS = a.cs;                    // CS: a multiple of 64
+    const int PW = g.PW, CS = a.cs;                    // CS: whole 64-position blocks cover every patch
 
     int baseB[NT];
 #pragma unroll
@@ -546,17 +547,60 @@ bool offsets_fit_32bit(const MfmaConvArgs& a, const View& v, int max_img)
     return bytes < 2.0e9 && 4.0 * 9.0 * (double)a.C * (double)a.Mtot < 2.0e9;
 }
 
+// Workgroup shapes of the direct-load kernel: output channels x pixels, and the workgroups of each that share a CU.
+struct DlShape { int BM, BN, per_cu; };
+
 template <int K, bool POOL_OUT, bool DELTA_IN>
-void launch_dl(const MfmaConvArgs& a, int BM, dim3 grid, hipStream_t s)
+void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 {
-    static char label[3][64];
-    const int v = BM == 128 ? 0 : BM == 64 ? 1 : 2;
-    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%d, %d, %d, %s, %s>", K, BM == 128 ? 2 : 1, BM == 32 ? 1 : 2,
+    static char label[6][64];
+    const int v = (sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1);
+    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%d, %d, %d, %d, %s, %s>", K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN,
                   POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false");
     g_kernel_label = label[v];
-    if (BM == 128) hipLaunchKernelGGL((k_conv_mfma_dl<K, 2, 2, POOL_OUT, DELTA_IN>), grid, dim3(256), 0, s, a);
-    else if (BM == 64) hipLaunchKernelGGL((k_conv_mfma_dl<K, 1, 2, POOL_OUT, DELTA_IN>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((k_conv_mfma_dl<K, 1, 1, POOL_OUT, DELTA_IN>), grid, dim3(256), 0, s, a);
+#define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<K, WM, MT, BN, POOL_OUT, DELTA_IN>), grid, dim3(256), 0, s, a)
+    if (sh.BN == 256) { if (sh.BM == 128) FTP_DL(2, 2, 256); else if (sh.BM == 64) FTP_DL(1, 2, 256); else FTP_DL(1, 1, 256); }
+    else              { if (sh.BM == 128) FTP_DL(2, 2, 128); else if (sh.BM == 64) FTP_DL(1, 2, 128); else FTP_DL(1, 1, 128); }
+#undef FTP_DL
+}
+
+// Picks the workgroup shape whose launch finishes first.  All workgroups of a launch do the same amount of
+// matrix-core work (BM x BN x reduction), `per_cu` of them share one CU's matrix cores, and the last, partly
+// filled round of a launch leaves CUs idle: few large workgroups waste most there, many small ones least, while
+// larger ones re-read less.  cost = (full rounds + the last round's depth per CU) x work of one workgroup.
+template <int K, bool POOL_OUT>
+DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc_out)
+{
+    const int S = POOL_OUT ? 2 : 1;
+    DlShape best = {0, 0, 0}; double best_cost = 0;
+    for (int BN = 256; BN >= 128; BN /= 2)
+        for (int BM = 128; BM >= 32; BM /= 2) {
+            if (BM == 128 && a.Mtot < 128) continue;
+            if (BM == 64 && a.Mtot <= 32) continue;
+            if (BM == 32 && a.Mtot > 32 && a.Mtot % 64 == 0) continue;          // 32 only where 64 would be padded
+            const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, conv_dl_max_positions(K, BN));
+            if (tc.cs > conv_dl_max_positions(K, BN)) continue;
+            // tiles that exist: every stack has its own count, the grid is sized for the largest
+            long long wgs = 0;
+            for (int i = 0; i < c.N; ++i)
+                for (int j = 0; j < c.M; ++j) {
+                    const int rw = a.rect.x1[j] - a.rect.x0[j] + 1, rh = a.rect.y1[i] - a.rect.y0[i] + 1;
+                    const int tcw = tc.tiles_x == 1 ? rw : tc.TC;
+                    int trf = tc.cap / tcw; if (trf < 1) trf = 1;
+                    const long long rtot = (long long)c.batch * rh;
+                    wgs += ((rtot + trf - 1) / trf) * ((rw + tcw - 1) / tcw);
+                }
+            const int mblocks = (a.Mtot + BM - 1) / BM;
+            wgs *= mblocks;
+            const int per_cu = BN == 256 ? (BM == 32 ? 3 : 2) : (BM == 32 ? 4 : 3);
+            const long long slots = 256LL * per_cu;
+            const double rounds = (double)(wgs / slots) * per_cu + (double)((wgs % slots + 255) / 256);
+            // in units of 1/128 cycle: multiply loop, epilogue (about 25k cycles for 128 x 256), set-up (about 10k cycles)
+            const double work = (double)BM * BN * a.C * K * K + 3.2e6 * (BM * BN) / (128.0 * 256.0) + 1.3e6;
+            const double cost = rounds * work * (BN == 256 ? 1.0 : 1.03);
+            if (best.BM == 0 || cost < best_cost) { best = {BM, BN, per_cu}; best_cost = cost; *tc_out = tc; }
+        }
+    return best;
 }
 
 template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
@@ -568,10 +612,14 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_r = tc.tiles_r; a.cap = tc.cap; a.cs = tc.cs;
     // output channels per workgroup: 128 (2x2 wavefronts of 64 x 128 pixels), 64 (1x4 of 64 x 64) or 32 (1x4 of 32 x 64)
     const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
-    if (sizeof(T) == 4 && !DELTA_IN && direct_loads_enabled() && offsets_fit_32bit(a, a.in, tc.max_img)) {
-        a.cs = (tc.cs + 63) & ~63;
-        launch_dl<K, POOL_OUT, false>(a, BM, dim3(a.tiles_x * a.tiles_r, (a.Mtot + BM - 1) / BM, c.N * c.M), s);
-        return 0;
+    if (sizeof(T) == 4 && !DELTA_IN && direct_loads_enabled()) {
+        TileChoice td;
+        const DlShape sh = choose_dl_shape<K, POOL_OUT>(a, c, &td);
+        if (sh.BM && offsets_fit_32bit(a, a.in, td.max_img)) {
+            a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = (td.cs + 63) & ~63;
+            launch_dl<K, POOL_OUT, false>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
+            return 0;
+        }
     }
     const int kCK = conv_stage_channels(K, BM);
     const size_t lds = (size_t)(KK * kCK * BM + kCK * a.cs) * sizeof(float);
