@@ -108,10 +108,16 @@ int ftp_plan_work(const ftp_plan_t* plan, double* useful_macs, double* executed_
  *   [7] group whose rectangles apply (per-stack only)
  * A per-stack buffer is laid out [stack][image][channel][slot height][slot width]; a stack's
  * rectangle occupies the top-left part of its slot.  Activations and deltas have the plan's type.
- * FTP_BUF_MASK is the decision code back-propagation reads, one byte per element of a whole map,
+ * FTP_BUF_DELTA holds dLoss/dZ: where the boundary is the output of a convolution (with or without its
+ * fused pool) the delta is dLoss/dY times the leaky-ReLU derivative there (Sec. 4.1, delta gradients);
+ * for boundary L that is a scaled copy of the caller's dy kept in the workspace.
+ * FTP_BUF_MASK is the decision code of the forward pass, one byte per element of a whole map,
  * written by the owning stack: bit 0 = activation > 0, bits 1-2 = index 2*dy+dx of the first
- * maximum of the 2x2 window (pooled boundaries only). */
-typedef enum { FTP_BUF_ACT = 0, FTP_BUF_MASK = 1, FTP_BUF_DELTA = 2 } ftp_buf_kind;
+ * maximum of the 2x2 window (pooled boundaries only); back-propagation reads the winners from it.
+ * FTP_BUF_SIGN (outputs of convolutions only) holds the same bit 0 packed for back-propagation:
+ * whole map of 32-bit words [image][ceil(C/32)][H][W], bit c%32 of word c/32 = activation of
+ * channel c > 0; out[5] is the number of words per pixel. */
+typedef enum { FTP_BUF_ACT = 0, FTP_BUF_MASK = 1, FTP_BUF_DELTA = 2, FTP_BUF_SIGN = 3 } ftp_buf_kind;
 int ftp_plan_buffer(const ftp_plan_t* plan, int32_t boundary, ftp_buf_kind which, int64_t out[8]);
 
 /* Forward pass of all groups (Sec. 4.1 forward, Sec. 4.2 fusing and grouping).
@@ -149,7 +155,8 @@ int ftp_reduce_wgrad(const ftp_plan_t* plan, const float* wgrad_partials, float*
  * at most `capacity` are written to `out` (host). */
 typedef enum {
     FTP_PASS_CONV_FWD = 0, FTP_PASS_CONV_BWD_DATA = 1, FTP_PASS_WGRAD = 2, FTP_PASS_REDUCE = 3,
-    FTP_PASS_POOL_FWD = 4, FTP_PASS_POOL_BWD = 5
+    FTP_PASS_POOL_FWD = 4, FTP_PASS_POOL_BWD = 5,
+    FTP_PASS_SCALE_DY = 6          /* dy times the last activation's derivative; layer = last convolution */
 } ftp_pass;
 typedef struct {
     int32_t pass, layer, launches, reserved;   /* layer = primitive layer index, -1 for the reduction */

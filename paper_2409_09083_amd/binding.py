@@ -29,7 +29,7 @@ class ftp_kernel_time(ctypes.Structure):
                 ("bytes_per_launch", ctypes.c_double), ("kernel", ctypes.c_char * 64)]
 
 
-PASS_NAMES = {0: "conv_fwd", 1: "conv_bwd_data", 2: "wgrad", 3: "reduce", 4: "pool_fwd", 5: "pool_bwd"}
+PASS_NAMES = {0: "conv_fwd", 1: "conv_bwd_data", 2: "wgrad", 3: "reduce", 4: "pool_fwd", 5: "pool_bwd", 6: "scale_dy"}
 
 
 class FtpError(RuntimeError):
@@ -154,7 +154,7 @@ def ftp_plan_work(plan):
     return {"useful_macs": u.value, "executed_macs": e.value, "halo_bytes_fwd": halo[0], "halo_bytes_bwd": halo[1]}
 
 
-FTP_BUF_ACT, FTP_BUF_MASK, FTP_BUF_DELTA = 0, 1, 2
+FTP_BUF_ACT, FTP_BUF_MASK, FTP_BUF_DELTA, FTP_BUF_SIGN = 0, 1, 2, 3
 
 
 def ftp_plan_buffer(plan, boundary, which):

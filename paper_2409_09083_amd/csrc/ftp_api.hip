@@ -76,6 +76,10 @@ ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void*
     a.mask = make_view(p, u.out_mask, u.group, u.bo, ub);
     a.din = make_view(p, u.in_delta, u.group, u.bo, ub);
     a.dout = make_view(p, u.out_delta, u.group, u.bi, ub);
+    a.osign = make_view(p, u.out_sign, u.group, u.bo, ub);
+    a.isign = make_view(p, u.in_sign, u.group, u.bi, ub);
+    a.scale_out = u.scale_out_delta ? 1 : 0;
+    a.in_slope = u.in_slope;
     a.w = weights[u.layer];
     a.bias = (biases && ly.has_bias) ? biases[u.layer] : nullptr;
     a.n_params = (long long)p.n_params; a.w_off = (long long)u.param_offset; a.b_off = (long long)u.bias_offset;
@@ -97,6 +101,9 @@ PoolArgs pool_args(const Plan& p, const Unit& u, const UserBufs& ub)
     a.mask = make_view(p, u.out_mask, u.group, u.bo, ub);
     a.din = make_view(p, u.in_delta, u.group, u.bo, ub);
     a.dout = make_view(p, u.out_delta, u.group, u.bi, ub);
+    a.isign = make_view(p, u.in_sign, u.group, u.bi, ub);
+    a.scale_out = u.scale_out_delta ? 1 : 0;
+    a.in_slope = u.in_slope;
     a.C = p.C[u.bi]; a.N = p.N; a.M = p.M; a.batch = p.batch;
     a.bf16 = p.dtype == FTP_BF16;
     return a;
@@ -212,6 +219,7 @@ int ftp_plan_buffer(const ftp_plan_t* plan, int32_t boundary, ftp_buf_kind which
         case FTP_BUF_ACT: b = &p.act[boundary]; break;
         case FTP_BUF_MASK: b = &p.mask[boundary]; break;
         case FTP_BUF_DELTA: b = &p.delta[boundary]; break;
+        case FTP_BUF_SIGN: b = &p.sign[boundary]; break;
         default: return FTP_EINVAL;
     }
     out[0] = b->kind; out[1] = (int64_t)b->offset; out[2] = b->per_stack ? 1 : 0;
@@ -264,6 +272,16 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
     if (rc != FTP_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     UserBufs ub; ub.x = x; ub.dy = dy; ub.dx = dx; ub.ws = workspace;
+    const int L = p.n_layers;
+    if (p.act_slope[L] >= 0.0f) {
+        // deltas are kept as dLoss/dZ: fold the last activation's derivative into a copy of dy
+        const uint32_t* sg = (const uint32_t*)((const char*)workspace + p.sign[L].offset);
+        void* dst = (char*)workspace + p.dy_scaled.offset;
+        rc = timed(plan, FTP_PASS_SCALE_DY, p.units.back().layer, s, [&] {
+            scale_dy(dy, sg, dst, p.batch, p.C[L], (long long)p.H[L] * p.W[L], p.act_slope[L], p.dtype == FTP_BF16, s);
+        });
+        if (rc != FTP_OK) return rc;
+    }
     for (int i = (int)p.units.size() - 1; i >= 0; --i) {
         const Unit& u = p.units[i];
         if (u.kind == UNIT_CONV) {
@@ -354,7 +372,10 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
             const double in_el = B * p.C[u->bi] * p.H[u->bi] * p.W[u->bi];
             const double out_el = B * p.C[u->bo] * p.H[u->bo] * p.W[u->bo];
             const double has_arg = (u->pooled || u->kind == UNIT_POOL) ? 1.0 : 0.0;
-            if (u->kind == UNIT_CONV) {
+            if (g.pass == FTP_PASS_SCALE_DY) {
+                t.flops_per_launch = out_el;
+                t.bytes_per_launch = out_el * (2.0 * es + 1.0);
+            } else if (u->kind == UNIT_CONV) {
                 const double wel = (double)ly.cout * ly.cin * ly.k * ly.k;
                 t.flops_per_launch = 2.0 * wel * B * p.H[g.layer] * p.W[g.layer];
                 if (g.pass == FTP_PASS_CONV_FWD) t.bytes_per_launch = (in_el + out_el + wel) * es + out_el * has_arg;

@@ -51,4 +51,20 @@ __device__ __forceinline__ T* at(const View& v, int stack, int ti, int tj, int n
 
 __device__ __forceinline__ float leaky(float z, float slope) { return z > 0.0f ? z : slope * z; }
 
+// Packed activation signs of a boundary (whole map): bit c % 32 of the 32-bit word [image][c / 32][y][x] is set
+// where the activation of channel c is > 0.
+__device__ __forceinline__ uint32_t sign_bit(const View& sg, int stack, int ti, int tj, int n, int c, int y, int x)
+{
+    return (*at<uint32_t>(sg, stack, ti, tj, n, c >> 5, y, x) >> (c & 31)) & 1u;
+}
+
+// What a pass writes into the delta map of a boundary that carries an activation: dLoss/dY, rounded as a map of
+// type T holds it, times the leaky-ReLU derivative there (1 where the activation is positive, else slope).
+template <typename T>
+__device__ __forceinline__ float scaled_delta(float v, uint32_t positive, float slope)
+{
+    const float r = stored(v, (const T*)nullptr);
+    return positive ? r : slope * r;
+}
+
 }  // namespace ftp

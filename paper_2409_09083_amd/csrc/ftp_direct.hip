@@ -7,18 +7,19 @@
 namespace ftp {
 
 // ---- delta at the convolution output ---------------------------------------------------------------
-// dZ(q) = delta * leaky'(Y); with a pool behind the convolution the delta sits at pooled resolution
-// and reaches only the window's recorded winner (Sec. 4.1, back-propagation of the delta).  Sign and
-// winner come from the decision code the owning stack wrote in the forward pass.
+// The delta maps hold dLoss/dZ (the activation derivative is folded in by whoever writes them).  With a pool
+// behind the convolution the delta sits at pooled resolution and reaches only the window's recorded winner
+// (Sec. 4.1, back-propagation of the delta); the winner comes from the decision code the owning stack wrote
+// in the forward pass.
 template <typename T, bool POOL>
 __device__ __forceinline__ float delta_z(const View& din, const View& mask, int stack, int ti, int tj,
-                                         int n, int co, int qy, int qx, float slope)
+                                         int n, int co, int qy, int qx)
 {
-    const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
+    if (!POOL) return ld(at<T>(din, stack, ti, tj, n, co, qy, qx));
+    const int sy = qy >> 1, sx = qx >> 1;
     const uint8_t m = *at<uint8_t>(mask, stack, ti, tj, n, co, sy, sx);
-    if (POOL && ((m >> 1) & 3) != (((qy & 1) << 1) | (qx & 1))) return 0.0f;
-    const float g = ld(at<T>(din, stack, ti, tj, n, co, sy, sx));
-    return (m & 1) ? g : slope * g;
+    if (((m >> 1) & 3) != (((qy & 1) << 1) | (qx & 1))) return 0.0f;
+    return ld(at<T>(din, stack, ti, tj, n, co, sy, sx));
 }
 
 __device__ __forceinline__ bool in_rect(const RectTab& r, int ti, int tj, int y, int x)
@@ -29,9 +30,10 @@ __device__ __forceinline__ bool in_rect(const RectTab& r, int ti, int tj, int y,
 // ---- forward: convolution + leaky ReLU (+ 2x2 max-pool) ------------------------------------------------
 template <typename T, int K, bool POOL, int COB>
 __global__ void __launch_bounds__(64)
-k_conv_fwd_direct(View in, View out, View mask, RectTab rt, RectTab own, const T* __restrict__ w, const T* __restrict__ bias,
-                  int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
+k_conv_fwd_direct(View in, View out, View mask, View osign, RectTab rt, RectTab own, const T* __restrict__ w,
+                  const T* __restrict__ bias, int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
 {
+    static_assert(COB == 8, "a workgroup's channels fill one byte of the sign word");
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
     const int rw = rt.x1[tj] - rt.x0[tj] + 1, rh = rt.y1[ti] - rt.y0[ti] + 1;
@@ -73,6 +75,8 @@ k_conv_fwd_direct(View in, View out, View mask, RectTab rt, RectTab own, const T
                 }
         }
     }
+    const bool owned = in_rect(own, ti, tj, oy, ox);
+    uint32_t signs = 0;
 #pragma unroll
     for (int j = 0; j < COB; ++j) {
         const int co = co0 + j;
@@ -90,15 +94,18 @@ k_conv_fwd_direct(View in, View out, View mask, RectTab rt, RectTab own, const T
             }
         }
         st(at<T>(out, stack, ti, tj, n, co, oy, ox), best);
-        if (in_rect(own, ti, tj, oy, ox)) *at<uint8_t>(mask, stack, ti, tj, n, co, oy, ox) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
+        if (owned) *at<uint8_t>(mask, stack, ti, tj, n, co, oy, ox) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
+        signs |= (best > 0.0f ? 1u : 0u) << j;
     }
+    // these 8 channels are byte (co0 / 8) % 4 of their sign word
+    if (owned) ((uint8_t*)at<uint32_t>(osign, stack, ti, tj, n, co0 >> 5, oy, ox))[(co0 >> 3) & 3] = (uint8_t)signs;
 }
 
 // ---- backward: delta at the convolution input -------------------------------------------------------
 template <typename T, int K, bool POOL, int CIB>
 __global__ void __launch_bounds__(64)
-k_conv_bwd_data_direct(View din, View mask, View dout, RectTab rt, const T* __restrict__ w,
-                       int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
+k_conv_bwd_data_direct(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt,
+                       const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
@@ -118,7 +125,7 @@ k_conv_bwd_data_direct(View din, View mask, View dout, RectTab rt, const T* __re
             for (int kx = 0; kx < K; ++kx) {
                 const int qy = iy + P - ky, qx = ix + P - kx;
                 if (qy < 0 || qy >= Hc || qx < 0 || qx >= Wc) continue;
-                const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx, slope);
+                const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx);
 #pragma unroll
                 for (int j = 0; j < CIB; ++j) {
                     const int ci = ci0 + j;
@@ -128,7 +135,11 @@ k_conv_bwd_data_direct(View din, View mask, View dout, RectTab rt, const T* __re
     }
 #pragma unroll
     for (int j = 0; j < CIB; ++j)
-        if (ci0 + j < Cin) st(at<T>(dout, stack, ti, tj, n, ci0 + j, iy, ix), acc[j]);
+        if (ci0 + j < Cin) {
+            float v = acc[j];
+            if (scale_out) v = scaled_delta<T>(v, sign_bit(isign, stack, ti, tj, n, ci0 + j, iy, ix), in_slope);
+            st(at<T>(dout, stack, ti, tj, n, ci0 + j, iy, ix), v);
+        }
 }
 
 // ---- backward: per-stack partial filter gradient -----------------------------------------------------
@@ -137,7 +148,7 @@ k_conv_bwd_data_direct(View din, View mask, View dout, RectTab rt, const T* __re
 template <typename T, int K, bool POOL>
 __global__ void __launch_bounds__(256)
 k_wgrad_direct(View xin, View din, View mask, RectTab own, float* __restrict__ partial, long long n_params,
-               long long w_off, long long b_off, int has_bias, int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
+               long long w_off, long long b_off, int has_bias, int Cin, int Cout, int Hc, int Wc, int M, int batch)
 {
     const int ci = blockIdx.x, co = blockIdx.y, stack = blockIdx.z;
     const int ti = stack / M, tj = stack % M;
@@ -150,7 +161,7 @@ k_wgrad_direct(View xin, View din, View mask, RectTab own, float* __restrict__ p
     for (int it = threadIdx.x; it < items; it += 256) {
         const int n = it / px, r = it - n * px;
         const int qy = own.y0[ti] + r / rw, qx = own.x0[tj] + r % rw;
-        const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx, slope);
+        const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx);
         acc[KK] += dz;
 #pragma unroll
         for (int ky = 0; ky < K; ++ky)
@@ -205,7 +216,7 @@ k_pool_fwd(View in, View out, View mask, RectTab rt, RectTab own, int C, int M, 
 
 template <typename T>
 __global__ void __launch_bounds__(64)
-k_pool_bwd(View din, View mask, View dout, RectTab rt, int C, int M, int batch)
+k_pool_bwd(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt, int C, int M, int batch)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
@@ -215,7 +226,8 @@ k_pool_bwd(View din, View mask, View dout, RectTab rt, int C, int M, int batch)
     const int iy = rt.y0[ti] + pid / rw, ix = rt.x0[tj] + pid % rw;
     const int c = blockIdx.y;
     const uint8_t a = (*at<uint8_t>(mask, stack, ti, tj, n, c, iy >> 1, ix >> 1) >> 1) & 3;
-    const float g = (a == (uint8_t)(((iy & 1) << 1) | (ix & 1))) ? ld(at<T>(din, stack, ti, tj, n, c, iy >> 1, ix >> 1)) : 0.0f;
+    float g = (a == (uint8_t)(((iy & 1) << 1) | (ix & 1))) ? ld(at<T>(din, stack, ti, tj, n, c, iy >> 1, ix >> 1)) : 0.0f;
+    if (scale_out) g = scaled_delta<T>(g, sign_bit(isign, stack, ti, tj, n, c, iy, ix), in_slope);
     st(at<T>(dout, stack, ti, tj, n, c, iy, ix), g);
 }
 
@@ -256,7 +268,7 @@ void conv_fwd_t(const ConvArgs& a, hipStream_t s)
     constexpr int COB = 8;
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cout + COB - 1) / COB, a.N * a.M * a.batch), block(64);
     const T* w = (const T*)a.w; const T* b = (const T*)a.bias;
-#define FTP_FWD(KK, PL) hipLaunchKernelGGL((k_conv_fwd_direct<T, KK, PL, COB>), grid, block, 0, s, a.in, a.out, a.mask, a.rect, a.own, w, b, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+#define FTP_FWD(KK, PL) hipLaunchKernelGGL((k_conv_fwd_direct<T, KK, PL, COB>), grid, block, 0, s, a.in, a.out, a.mask, a.osign, a.rect, a.own, w, b, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
     if (a.K == 3) { if (a.pooled) FTP_FWD(3, true); else FTP_FWD(3, false); }
     else          { if (a.pooled) FTP_FWD(1, true); else FTP_FWD(1, false); }
 #undef FTP_FWD
@@ -268,7 +280,7 @@ void conv_bwd_data_t(const ConvArgs& a, hipStream_t s)
     constexpr int CIB = 8;
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cin + CIB - 1) / CIB, a.N * a.M * a.batch), block(64);
     const T* w = (const T*)a.w;
-#define FTP_BWD(KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, PL, CIB>), grid, block, 0, s, a.din, a.mask, a.dout, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+#define FTP_BWD(KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, PL, CIB>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch)
     if (a.K == 3) { if (a.pooled) FTP_BWD(3, true); else FTP_BWD(3, false); }
     else          { if (a.pooled) FTP_BWD(1, true); else FTP_BWD(1, false); }
 #undef FTP_BWD
@@ -278,7 +290,7 @@ template <typename T>
 void wgrad_t(const ConvArgs& a, hipStream_t s)
 {
     dim3 grid(a.Cin, a.Cout, a.N * a.M), block(256);
-#define FTP_WG(KK, PL) hipLaunchKernelGGL((k_wgrad_direct<T, KK, PL>), grid, block, 0, s, a.in, a.din, a.mask, a.rect, a.partial, a.n_params, a.w_off, a.b_off, a.has_bias, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
+#define FTP_WG(KK, PL) hipLaunchKernelGGL((k_wgrad_direct<T, KK, PL>), grid, block, 0, s, a.in, a.din, a.mask, a.rect, a.partial, a.n_params, a.w_off, a.b_off, a.has_bias, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch)
     if (a.K == 3) { if (a.pooled) FTP_WG(3, true); else FTP_WG(3, false); }
     else          { if (a.pooled) FTP_WG(1, true); else FTP_WG(1, false); }
 #undef FTP_WG
@@ -302,8 +314,29 @@ void pool_bwd(const PoolArgs& a, hipStream_t s)
 {
     g_kernel_label = "k_pool_bwd";
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
-    if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.mask, a.dout, a.rect, a.C, a.M, a.batch);
-    else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.mask, a.dout, a.rect, a.C, a.M, a.batch);
+    if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.M, a.batch);
+    else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.M, a.batch);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_scale_dy(const T* __restrict__ dy, const uint32_t* __restrict__ sign, T* __restrict__ dst, int C, long long HW, float slope)
+{
+    const int n = blockIdx.z, c = blockIdx.y, G = (C + 31) / 32;
+    const T* src = dy + ((long long)n * C + c) * HW;
+    T* out = dst + ((long long)n * C + c) * HW;
+    const uint32_t* sg = sign + ((long long)n * G + (c >> 5)) * HW;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < HW; i += (long long)gridDim.x * blockDim.x)
+        st(out + i, scaled_delta<T>(ld(src + i), (sg[i] >> (c & 31)) & 1u, slope));
+}
+
+void scale_dy(const void* dy, const uint32_t* sign, void* dst, int batch, int C, long long HW, float slope, int bf16, hipStream_t s)
+{
+    g_kernel_label = "k_scale_dy";
+    long long bx = (HW + 255) / 256; if (bx > 64) bx = 64;
+    dim3 grid((unsigned)bx, C, batch), block(256);
+    if (bf16) hipLaunchKernelGGL(k_scale_dy<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, sign, (bf16_t*)dst, C, HW, slope);
+    else      hipLaunchKernelGGL(k_scale_dy<float>, grid, block, 0, s, (const float*)dy, sign, (float*)dst, C, HW, slope);
 }
 
 void reduce_wgrad(const float* partial, float* wgrad, long long n_params, int stacks, hipStream_t s)

@@ -14,12 +14,20 @@ extern thread_local const char* g_kernel_label;
 //   forward        in (activation at the input), out (activation at the output), mask (decision codes at the
 //                  output boundary, written for owned pixels), rect = forward rectangle at the output boundary,
 //                  own = owned rectangle there
-//   backward data  din (delta at the output boundary), mask, dout (delta at the input),
-//                  rect = backward rectangle at the input boundary
+//   backward data  din (delta at the output boundary), mask (pooled units: winners), dout (delta at the input),
+//                  rect = backward rectangle at the input boundary; isign / scale_out / in_slope: see below
 //   filter grad    in, din, mask, rect = owned rectangle at the convolution output (before the pool)
 // Decision code: bit 0 = activation > 0, bits 1-2 = winner 2*dy+dx of the 2x2 window (pooled units).
+// The forward pass also packs bit 0 into the sign map of the output boundary (osign): 32-bit words
+// [image][channel / 32][y][x], bit channel % 32.
+// Deltas are stored as dLoss/dZ: a delta map already carries the leaky-ReLU derivative of the convolution unit
+// that produced its boundary, so readers only route through pool winners.  A pass that writes the delta of its
+// input boundary applies that boundary's derivative itself (scale_out: the bit in isign selects 1 or in_slope).
 struct ConvArgs {
     View in, out, mask, din, dout;
+    View osign, isign;              // sign maps at the output / input boundary
+    int scale_out = 0;
+    float in_slope = 1.0f;
     RectTab rect, own;
     const void* w = nullptr;        // filter, OIHW
     const void* bias = nullptr;
@@ -36,9 +44,15 @@ struct ConvArgs {
 
 struct PoolArgs {
     View in, out, mask, din, dout;
+    View isign;                     // sign map at the input boundary (backward: see ConvArgs)
+    int scale_out = 0;
+    float in_slope = 1.0f;
     RectTab rect, own;
     int C = 0, N = 1, M = 1, batch = 1, bf16 = 0;
 };
+
+// dst = dy * (activation > 0 ? 1 : slope) over a whole map [batch][C][HW]; sign = packed signs of that boundary.
+void scale_dy(const void* dy, const uint32_t* sign, void* dst, int batch, int C, long long HW, float slope, int bf16, hipStream_t s);
 
 // Kernel argument block of the matrix-core convolution (forward and delta back-propagation).
 struct MfmaConvArgs {
@@ -55,6 +69,10 @@ struct MfmaConvArgs {
     int cs;                                         // LDS channel stride of the patch = largest patch of any stack
     float slope;
     int M, batch;
+    View osign;                                     // forward: sign map of the output boundary
+    View isign;                                     // backward: sign map of the boundary the deltas are written to
+    int scale_out;                                  // ... whose activation derivative (1 or in_slope) the epilogue applies
+    float in_slope;
 };
 
 bool mfma_conv_eligible(const ConvArgs& a, bool backward);

@@ -116,6 +116,40 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
         if (tid < BM) bias_lds[tid] = (a.bias && m0 + tid < a.Mtot) ? ld((const T*)a.bias + m0 + tid) : 0.0f;
         __syncthreads();
     }
+    if (DELTA_IN) {
+        // Deltas are stored as dLoss/dZ: where the boundary written to carries an activation, its derivative is
+        // applied now.  A lane's 16 channels of a 32-channel block share one sign word; all words are loaded
+        // before the first store, so that no load has to wait for stores.
+        const View& ov = a.dout;
+        T* optr[NT]; bool pv[NT];
+        uint32_t sw[NT][MT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int q = (wave_n * NT + t) * 32 + l32;
+            const TilePix tp = tile_pix<S, P>(g, q, x1);
+            pv[t] = tp.valid;
+            const int pn = pv[t] ? tp.n : 0, py = pv[t] ? y0 + tp.y : y0, pxx = pv[t] ? g.ox0 + tp.xl : x0;
+            optr[t] = at<T>(ov, stack, ti, tj, pn, 0, py, pxx);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int mb = m0 + (wave_m * MT + mt) * 32;            // first channel of the block
+                sw[t][mt] = (a.scale_out && mb < a.Mtot) ? *at<uint32_t>(a.isign, stack, ti, tj, pn, mb >> 5, py, pxx) : 0xFFFFFFFFu;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int bit = 8 * (i >> 2) + 4 * hi + (i & 3);
+                    const int m = m0 + (wave_m * MT + mt) * 32 + bit;
+                    float v = acc[mt][t][i];
+                    if (a.scale_out) v = scaled_delta<T>(v, (sw[t][mt] >> bit) & 1u, a.in_slope);
+                    if (pv[t] && m < a.Mtot) st(optr[t] + (long long)m * ov.cs, v);
+                }
+        return;
+    }
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int q = (wave_n * NT + t) * 32 + l32;
@@ -123,36 +157,37 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
         const int pn = tp.n, py = y0 + tp.y, pxx = g.ox0 + tp.xl;
         bool pvalid = tp.valid;
         if (POOL_OUT) pvalid = pvalid && (lane & 3) == 0;       // the window's first lane stores
-        const bool powned = pvalid && !DELTA_IN && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
-        const View& ov = DELTA_IN ? a.dout : a.out;
-        T* __restrict__ optr = at<T>(ov, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
+        const bool powned = pvalid && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
+        T* __restrict__ optr = at<T>(a.out, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
         uint8_t* __restrict__ mptr = at<uint8_t>(a.mask, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
+            uint32_t signs = 0;                                 // this lane's 16 channels of the block's sign word
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int ml = (wave_m * MT + mt) * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
                 const int m = m0 + ml;
-                float v = acc[mt][t][i];
-                if (DELTA_IN) {
-                    if (pvalid && m < a.Mtot) st(optr + (long long)m * ov.cs, v);
-                } else {
-                    // compared and recorded as the map will hold it (rounded to the storage type)
-                    v = stored(leaky(v + bias_lds[ml], a.slope), (const T*)nullptr);
-                    int bi = 0;
-                    if (POOL_OUT) {
-                        // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
-                        const float o1 = __shfl_xor(v, 1, 64), o2 = __shfl_xor(v, 2, 64), o3 = __shfl_xor(v, 3, 64);
-                        if (o1 > v) { v = o1; bi = 1; }
-                        if (o2 > v) { v = o2; bi = 2; }
-                        if (o3 > v) { v = o3; bi = 3; }
-                    }
-                    if (pvalid && m < a.Mtot) {
-                        st(optr + (long long)m * ov.cs, v);
-                        if (powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
-                    }
+                // compared and recorded as the map will hold it (rounded to the storage type)
+                float v = stored(leaky(acc[mt][t][i] + bias_lds[ml], a.slope), (const T*)nullptr);
+                int bi = 0;
+                if (POOL_OUT) {
+                    // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
+                    const float o1 = __shfl_xor(v, 1, 64), o2 = __shfl_xor(v, 2, 64), o3 = __shfl_xor(v, 3, 64);
+                    if (o1 > v) { v = o1; bi = 1; }
+                    if (o2 > v) { v = o2; bi = 2; }
+                    if (o3 > v) { v = o3; bi = 3; }
+                }
+                if (pvalid && m < a.Mtot) {
+                    st(optr + (long long)m * a.out.cs, v);
+                    if (powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
+                    signs |= (v > 0.0f ? 1u : 0u) << (8 * (i >> 2) + 4 * hi + (i & 3));
                 }
             }
+            // the other half of the block's channels sits 32 lanes away (same pixel)
+            signs |= (uint32_t)__shfl_xor((int)signs, 32, 64);
+            const int mb = m0 + (wave_m * MT + mt) * 32;
+            if (powned && hi == 0 && mb < a.Mtot)
+                *at<uint32_t>(a.osign, stack, ti, tj, pn, mb >> 5, py, pxx) = signs;
         }
     }
 }
@@ -265,7 +300,7 @@ k_conv_mfma(MfmaConvArgs a)
             for (int k = 0; k < kCK; ++k) {
                 const int ci = c0 + k < a.C ? c0 + k : a.C - 1;
                 greg[j][k] = ld(src + go + (long long)ci * sv.cs);
-                if (DELTA_IN) mreg[j][k] = msk[mo + (long long)ci * a.mask.cs];
+                if (DELTA_IN && POOL_IN) mreg[j][k] = msk[mo + (long long)ci * a.mask.cs];
             }
         }
     };
@@ -289,10 +324,8 @@ k_conv_mfma(MfmaConvArgs a)
 #pragma unroll
                 for (int k = 0; k < kCK; ++k) {
                     float v = greg[j][k];
-                    if (DELTA_IN) {
-                        v = (mreg[j][k] & 1) ? v : a.slope * v;
-                        if (POOL_IN && ((mreg[j][k] >> 1) & 3) != code) v = 0.0f;
-                    }
+                    // the delta maps hold dLoss/dZ; through a pool only the window's winner receives it
+                    if (DELTA_IN && POOL_IN && ((mreg[j][k] >> 1) & 3) != code) v = 0.0f;
                     if (!inside || c0 + k >= a.C) v = 0.0f;
                     Xl[k * CS + s] = v;
                 }
@@ -612,12 +645,13 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_r = tc.tiles_r; a.cap = tc.cap; a.cs = tc.cs;
     // output channels per workgroup: 128 (2x2 wavefronts of 64 x 128 pixels), 64 (1x4 of 64 x 64) or 32 (1x4 of 32 x 64)
     const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
-    if (sizeof(T) == 4 && !DELTA_IN && direct_loads_enabled()) {
+    // fp32 maps whose patch needs no routing through pool winners take the direct-load kernel
+    if (sizeof(T) == 4 && !POOL_IN && direct_loads_enabled()) {
         TileChoice td;
         const DlShape sh = choose_dl_shape<K, POOL_OUT>(a, c, &td);
-        if (sh.BM && offsets_fit_32bit(a, a.in, td.max_img)) {
+        if (sh.BM && offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img)) {
             a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = (td.cs + 63) & ~63;
-            launch_dl<K, POOL_OUT, false>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
+            launch_dl<K, POOL_OUT && !DELTA_IN, DELTA_IN>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
             return 0;
         }
     }
@@ -646,6 +680,7 @@ void fill_common(MfmaConvArgs& a, const ConvArgs& c, const RectTab& inrect)
     a.in = c.in; a.out = c.out; a.mask = c.mask; a.din = c.din; a.dout = c.dout; a.rect = c.rect; a.own = c.own;
     for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
     a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
+    a.osign = c.osign; a.isign = c.isign; a.scale_out = c.scale_out; a.in_slope = c.in_slope;
 }
 
 }  // namespace

@@ -99,7 +99,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
             for (int k = 0; k < NZ; ++k) {
                 const int ch = wave + 4 * k;
                 const int co = co0 + ch < a.Cout ? co0 + ch : a.Cout - 1;
-                zm[k] = mp[(long long)co * a.mask.cs];
+                zm[k] = POOL ? (uint32_t)mp[(long long)co * a.mask.cs] : 0u;      // only the pool winner is needed
                 zg[k] = ld(gp + (long long)co * a.din.cs);
             }
         }
@@ -138,7 +138,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
 #pragma unroll
             for (int k = 0; k < NZ; ++k) {
                 const int ch = wave + 4 * k;
-                float v = (zm[k] & 1) ? zg[k] : a.slope * zg[k];
+                float v = zg[k];                                       // the delta maps hold dLoss/dZ
                 if (POOL && ((zm[k] >> 1) & 3) != (uint32_t)code) v = 0.0f;
                 if ((zinfo & 2) || co0 + ch >= a.Cout) v = 0.0f;
                 zdst[ch] = v;

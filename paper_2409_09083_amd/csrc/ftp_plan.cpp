@@ -168,6 +168,7 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
 
     std::vector<BufRef>& act = p.act; std::vector<BufRef>& mask = p.mask; std::vector<BufRef>& delta = p.delta;
     act.assign(L + 1, BufRef()); mask.assign(L + 1, BufRef()); delta.assign(L + 1, BufRef());
+    p.sign.assign(L + 1, BufRef());
     p.home_group.assign(L + 1, 0);
     size_t pp_bytes = 0;                       // size of one ping-pong slot set for interior deltas
     for (int g = 0; g < (int)p.groups.size(); ++g) {
@@ -214,10 +215,27 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
                 }
                 act[b] = a; mask[b] = w; delta[b] = d;
                 p.home_group[b] = g;
+                if (u.kind == UNIT_CONV) {
+                    BufRef sg;
+                    sg.kind = BUF_WS; sg.channels = (p.C[b] + 31) / 32; sg.slot_w = p.W[b]; sg.slot_h = p.H[b];
+                    sg.bytes = (size_t)batch * sg.channels * p.H[b] * p.W[b] * 4; sg.offset = alloc(sg.bytes);
+                    p.sign[b] = sg;
+                }
             }
             p.units.push_back(u);
             l = u.bo;
         }
+    }
+    // activation derivative folded into the stored deltas
+    p.act_slope.assign(L + 1, -1.0f);
+    for (const Unit& u : p.units)
+        if (u.kind == UNIT_CONV) p.act_slope[u.bo] = p.layers[u.layer].leaky_slope;
+    if (p.act_slope[L] >= 0.0f) {
+        // the caller's dy is read-only: its scaled copy lives in the workspace and takes its place as delta of L
+        BufRef d = delta[L];
+        d.kind = BUF_WS; d.bytes = (size_t)batch * p.C[L] * p.H[L] * p.W[L] * p.esize; d.offset = alloc(d.bytes);
+        p.dy_scaled = d;
+        delta[L] = d;
     }
     act[0].kind = BUF_X; act[0].channels = p.C[0]; act[0].slot_w = p.W[0]; act[0].slot_h = p.H[0];
     delta[0].kind = BUF_DX; delta[0].channels = p.C[0]; delta[0].slot_w = p.W[0]; delta[0].slot_h = p.H[0];
@@ -250,6 +268,9 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
     for (Unit& u : p.units) {
         u.in_act = act[u.bi]; u.out_act = act[u.bo]; u.out_mask = mask[u.bo];
         u.in_delta = delta[u.bo]; u.out_delta = delta[u.bi];
+        u.out_sign = p.sign[u.bo]; u.in_sign = p.sign[u.bi];
+        u.scale_out_delta = p.act_slope[u.bi] >= 0.0f;
+        u.in_slope = u.scale_out_delta ? p.act_slope[u.bi] : 1.0f;
     }
     std::vector<size_t> layer_poff(L, 0), layer_boff(L, 0);
     for (int l = 0; l < L; ++l) {

@@ -50,6 +50,9 @@ struct Unit {
     int bi = 0, bo = 0;       // input / output boundary
     BufRef in_act, out_act, out_mask;         // forward (out_mask: decision codes at the output boundary)
     BufRef in_delta, out_delta;               // backward (in_delta lives at bo, out_delta at bi)
+    BufRef out_sign, in_sign;                 // packed activation signs at bo (written forward) and at bi (read backward)
+    bool scale_out_delta = false;             // the delta written at bi is multiplied by the activation derivative there
+    float in_slope = 1.0f;                    // leaky slope of the convolution whose output is boundary bi
     size_t param_offset = 0;                  // first filter element in the parameter vector
     size_t bias_offset = 0;
     size_t wt_fwd_offset = 0, wt_bwd_offset = 0;   // relaid filter copies in the workspace (bytes)
@@ -65,7 +68,13 @@ struct Plan {
     std::vector<int> group_of_layer;
     std::vector<Unit> units;
     std::vector<BufRef> act, mask, delta;     // home of each boundary's activation / decision codes / delta
+    std::vector<BufRef> sign;                 // packed activation signs (outputs of convolution units), 32 channels a word
     std::vector<int> home_group;              // group whose rectangles address a per-stack boundary
+    // Deltas are kept as dLoss/dZ: where boundary b is the output of a convolution unit (act_slope[b] >= 0), the
+    // delta map of b holds dLoss/dY_b times the leaky-ReLU derivative (1 or slope, from the sign map of b);
+    // -1 marks boundaries without an activation (the input, outputs of stand-alone pools).
+    std::vector<float> act_slope;
+    BufRef dy_scaled;                         // whole map at boundary L: the caller's dy times the derivative (if any)
     size_t workspace_bytes = 0, n_params = 0;
     size_t wgrad_scratch_offset = 0;          // batch shares of one layer's partial gradients (bytes)
     size_t split[4] = {0, 0, 0, 0};

@@ -12,24 +12,13 @@ namespace ftp {
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 // dZ of one element from the delta and the owner's decision code (see ftp_direct.hip: delta_z).
-template <typename T, bool POOL>
-__device__ __forceinline__ float thin_delta_z(const View& din, const View& mask, int stack, int ti, int tj,
-                                              int n, int co, int qy, int qx, float slope)
-{
-    const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
-    const uint8_t m = *at<uint8_t>(mask, stack, ti, tj, n, co, sy, sx);
-    if (POOL && ((m >> 1) & 3) != (((qy & 1) << 1) | (qx & 1))) return 0.0f;
-    const float g = ld(at<T>(din, stack, ti, tj, n, co, sy, sx));
-    return (m & 1) ? g : slope * g;
-}
-
 // ---- delta at the input of a convolution with at most CIT input channels ------------------------------------
 // Workgroup = 64 x 4 pixels of one (stack, image): wide tiles keep the reads of the (pooled) delta rows long.
 // LDS = dZ patch of COC channels with the filter halo.
 template <typename T, int K, bool POOL, int CIT>
 __global__ void __launch_bounds__(256)
-k_conv_bwd_data_thin(View din, View mask, View dout, RectTab rt, const T* __restrict__ w,
-                     int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch, int tiles_x)
+k_conv_bwd_data_thin(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt,
+                     const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch, int tiles_x)
 {
     constexpr int P = K / 2, TSX = 64, TSY = 4, PSX = TSX + 2 * P, PSY = TSY + 2 * P, PP = PSX + 1, COC = 16;
     __shared__ float dz[COC][PSY][PP];
@@ -62,12 +51,12 @@ k_conv_bwd_data_thin(View din, View mask, View dout, RectTab rt, const T* __rest
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const int co = c0 + cb + k < Cout ? c0 + cb + k : Cout - 1;
-                    m[k] = mp[(long long)co * mask.cs];
+                    m[k] = POOL ? mp[(long long)co * mask.cs] : (uint8_t)0;      // only the pool winner is needed
                     g[k] = ld(gp + (long long)co * din.cs);
                 }
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    float v = (m[k] & 1) ? g[k] : slope * g[k];
+                    float v = g[k];                                          // the delta maps hold dLoss/dZ
                     if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
                     if (!ok || c0 + cb + k >= Cout) v = 0.0f;
                     dz[cb + k][r][q] = v;
@@ -93,7 +82,11 @@ k_conv_bwd_data_thin(View din, View mask, View dout, RectTab rt, const T* __rest
     if (ix <= rt.x1[tj] && iy <= rt.y1[ti]) {
 #pragma unroll
         for (int j = 0; j < CIT; ++j)
-            if (j < Cin) st(at<T>(dout, stack, ti, tj, n, j, iy, ix), acc[j]);
+            if (j < Cin) {
+                float v = acc[j];
+                if (scale_out) v = scaled_delta<T>(v, sign_bit(isign, stack, ti, tj, n, j, iy, ix), in_slope);
+                st(at<T>(dout, stack, ti, tj, n, j, iy, ix), v);
+            }
     }
 }
 
@@ -107,7 +100,7 @@ void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
     const int tiles_x = (mw + 63) / 64, tiles_y = (mh + 3) / 4;
     dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
     g_kernel_label = "k_conv_bwd_data_thin";
-#define FTP_TB(T, KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_thin<T, KK, PL, 4>), grid, block, 0, s, a.din, a.mask, a.dout, a.rect, (const T*)a.w, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch, tiles_x)
+#define FTP_TB(T, KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_thin<T, KK, PL, 4>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, (const T*)a.w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch, tiles_x)
     if (a.bf16) {
         if (a.K == 3) { if (a.pooled) FTP_TB(bf16_t, 3, true); else FTP_TB(bf16_t, 3, false); }
         else          { if (a.pooled) FTP_TB(bf16_t, 1, true); else FTP_TB(bf16_t, 1, false); }
@@ -174,12 +167,12 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
                         const int co = co0 + wave + 4 * k < a.Cout ? co0 + wave + 4 * k : a.Cout - 1;
-                        m[k] = mp[(long long)co * a.mask.cs];
+                        m[k] = POOL ? mp[(long long)co * a.mask.cs] : (uint8_t)0;
                         g[k] = ld(gp + (long long)co * a.din.cs);
                     }
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
-                        float v = (m[k] & 1) ? g[k] : a.slope * g[k];
+                        float v = g[k];                                      // the delta maps hold dLoss/dZ
                         if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
                         if (col >= rw || co0 + wave + 4 * k >= a.Cout) v = 0.0f;
                         Zl[(row * TCp + col) * ZP + wave + 4 * k] = v;

@@ -97,8 +97,8 @@ class Session:
             return None, info
         if loc in (1, 2, 3, 4):
             return {1: self.x, 2: self.y, 3: self.dy, 4: self.dx}[loc], info
-        dt = torch.uint8 if which == B.FTP_BUF_MASK else self.tdtype
-        esz = 1 if which == B.FTP_BUF_MASK else (2 if self.bf16 else 4)
+        dt = {B.FTP_BUF_MASK: torch.uint8, B.FTP_BUF_SIGN: torch.int32}.get(which, self.tdtype)
+        esz = {B.FTP_BUF_MASK: 1, B.FTP_BUF_SIGN: 4}.get(which, 2 if self.bf16 else 4)
         lead = (self.stacks,) if info["per_stack"] else ()
         shape = lead + (self.batch, info["channels"], info["slot_h"], info["slot_w"])
         n = 1
@@ -145,7 +145,7 @@ class Session:
         if t is None:
             return
         src = torch.from_numpy(np.ascontiguousarray(full_map))
-        src = src.cuda() if which == B.FTP_BUF_MASK else src.float().cuda().to(t.dtype)
+        src = src.cuda() if which in (B.FTP_BUF_MASK, B.FTP_BUF_SIGN) else src.float().cuda().to(t.dtype)
         if not info["per_stack"]:
             t.copy_(src)
             return
@@ -156,4 +156,4 @@ class Session:
     @staticmethod
     def to_np(t):
         t = t.detach()
-        return t.cpu().numpy() if t.dtype == torch.uint8 else t.float().cpu().numpy()
+        return t.cpu().numpy() if t.dtype in (torch.uint8, torch.int32) else t.float().cpu().numpy()

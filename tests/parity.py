@@ -129,6 +129,21 @@ def oracle_mask(acts, args, b):
     return m
 
 
+def pack_signs(act):
+    """Sign map as the library lays it out: int32 words [image][ceil(C/32)][H][W], bit c % 32 = act[:, c] > 0."""
+    n, c, h, w = act.shape
+    g = (c + 31) // 32
+    words = np.zeros((n, g, h, w), dtype=np.uint32)
+    for ch in range(c):
+        words[:, ch // 32] |= (act[:, ch] > 0).astype(np.uint32) << np.uint32(ch % 32)
+    return words.view(np.int32)
+
+
+def unpack_signs(words, c):
+    w = words.view(np.uint32)
+    return np.stack([(w[:, ch // 32] >> np.uint32(ch % 32)) & 1 for ch in range(c)], axis=1).astype(bool)
+
+
 def check_forward_state(s, cfg, acts, args, tol_a):
     """Every map the plan keeps equals the oracle's: the assembled owned tiles, and each stack's whole
     forward rectangle (recomputed halo included).  Decision codes may differ from the oracle's only where
@@ -149,6 +164,10 @@ def check_forward_state(s, cfg, acts, args, tol_a):
         bad = (gm & 1) != (acts[b] > 0)
         if bad.any():
             assert float(np.abs(acts[b][bad]).max()) <= tol_a * scale, ("activation signs", b, int(bad.sum()))
+        gs = s.get_boundary(b, F.FTP_BUF_SIGN)
+        if gs is not None:
+            # the packed signs back-propagation reads are the same decisions as bit 0 of the codes
+            assert np.array_equal(unpack_signs(gs, acts[b].shape[1]), (gm & 1).astype(bool)), ("packed signs", b)
         if args[b - 1] is not None:
             bad = ((gm >> 1) & 3) != args[b - 1]
             if bad.any():
@@ -176,6 +195,7 @@ def import_forward_state(s, cfg, acts, args):
     for b in range(1, len(cfg.layers) + 1):
         s.set_boundary(b, acts[b])
         s.set_boundary(b, oracle_mask(acts, args, b), F.FTP_BUF_MASK)
+        s.set_boundary(b, pack_signs(acts[b]), F.FTP_BUF_SIGN)
 
 
 def check_grads(cfg, got_dx, got_wgrad, dx, dws, dbs, has_bias, tol_g, label):
