@@ -373,7 +373,9 @@ k_conv_mfma(MfmaConvArgs a)
 #define FTP_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 constexpr unsigned kOobOffset = 0x80000000u;          // beyond the records of every buffer resource below
 constexpr unsigned kBufRecords = 0x7FFFFFFFu;
-__host__ __device__ constexpr int conv_dl_stage_channels(int K, int BM) { return K == 1 ? 16 : (BM == 128 ? 4 : 8); }
+// Reduction channels per stage: the same for every workgroup shape, so that the summation order, and with it every
+// bit of the result, does not depend on which shape the launch heuristics pick (they look at the batch size).
+__host__ __device__ constexpr int conv_dl_stage_channels(int K, int /*BM*/) { return K == 1 ? 16 : 4; }
 __host__ __device__ constexpr int conv_dl_max_positions(int K, int BN) { return K == 1 ? 256 : (BN == 256 ? 512 : 256); }   // patch positions in LDS
 
 template <int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN>
@@ -390,7 +392,9 @@ k_conv_mfma_dl(MfmaConvArgs a)
     constexpr int XMAX = conv_dl_max_positions(K, BN);
     constexpr int MAXPOS = XMAX / 256;
     constexpr int WF = KK * kCK * BM;                  // floats of one filter slice [tap][channel][BM]
-    constexpr int WINSTR = WF / 64 / 4;                // filter load instructions per wavefront and stage
+    constexpr int WPIECES = WF / 64;                   // 64-float pieces of the slice, dealt round-robin to the 4 wavefronts
+    constexpr int WINSTR = (WPIECES + 3) / 4;
+    static_assert(WF % 64 == 0, "the filter slice is loaded in 64-float pieces");
     __shared__ float bufA[WF + kCK * XMAX];
     __shared__ float bufB[WF + kCK * XMAX];
 
@@ -461,6 +465,7 @@ k_conv_mfma_dl(MfmaConvArgs a)
 #pragma unroll
         for (int u = 0; u < WINSTR; ++u) {
             const int idx = wave + 4 * u;                              // 64-float piece of the slice
+            if (idx >= WPIECES) break;
             const int row = BM >= 64 ? idx / (BM / 64 > 0 ? BM / 64 : 1) : 2 * idx;
             const int tap = row / kCK, k = row - tap * kCK;
             const unsigned so = 4u * (unsigned)((tap * a.C + c0 + k) * a.Mtot + m0);

@@ -70,6 +70,7 @@ def _full_batch_properties(oracle, cfg, sample):
     s2.load(x=np.ascontiguousarray(x[sample]), weights=ws, dy=np.ascontiguousarray(dy[sample]))
     s2.step()
     torch.cuda.synchronize()
+    # the same images in a batch of another size: other launch shapes, same summation order
     assert P.rel_inf(s2.to_np(s2.y), y_full) <= 1e-6
     assert P.rel_inf(s2.to_np(s2.dx), dx_full) <= (1e-3 if bf else 1e-5)
     w2 = s2.to_np(s2.wgrad)
