@@ -90,6 +90,134 @@ k_conv_bwd_data_thin(View din, View mask, View dout, View isign, int scale_out, 
     }
 }
 
+// ---- the same for K = 3, register-tiled: every thread produces 4 neighbouring pixels of all CI input channels ----
+// Workgroup = TW x TH pixels of one (stack, image), TW = 4 * ntx <= 64, TH = nty <= 64, ntx * nty <= 256, chosen
+// on the host from the largest rectangle so that its tiles leave no ragged last column.  Per 8 output channels the
+// routed dZ patch (tile + filter halo) is staged in LDS - behind a pool one (delta, winner) pair per window
+// serves its 4 pixels - next to the filter slice [co][ci][tap].  A thread reads 3 x 6 patch values and 9 * CI
+// weights per output channel for 36 * CI multiply-adds.
+constexpr int kThin4Coc = 8, kThin4Patch = 1344;     // channels per stage, floats of one channel's patch
+
+template <typename T, bool POOL, int CI>
+__global__ void __launch_bounds__(256)
+k_conv_bwd_data_thin4(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt,
+                      const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch,
+                      int ntx, int nty, int tiles_x)
+{
+    constexpr int COC = kThin4Coc, CH = kThin4Patch, WR = 9 * CI;
+    __shared__ __attribute__((aligned(16))) float dz[COC * CH];
+    __shared__ __attribute__((aligned(16))) float wl[COC * WR];
+    const int tid = threadIdx.x;
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    const int TW = 4 * ntx, TH = nty, PP = (TW + 2 + 3) & ~3;
+    const int bx = blockIdx.x % tiles_x, by = blockIdx.x / tiles_x;
+    const int ox0 = rt.x0[tj] + bx * TW, oy0 = rt.y0[ti] + by * TH;
+    if (ox0 > rt.x1[tj] || oy0 > rt.y1[ti]) return;
+    const int tx = tid % ntx, ty = tid / ntx;
+    const bool worker = ty < nty;
+    const int px0 = ox0 - 1, py0 = oy0 - 1;            // map coordinates of the patch origin
+    float acc[CI][4];
+#pragma unroll
+    for (int j = 0; j < CI; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[j][q] = 0.0f;
+
+    for (int c0 = 0; c0 < Cout; c0 += COC) {
+        __syncthreads();
+        for (int i = tid; i < COC * WR; i += 256) {
+            const int c = i / WR, r = i - c * WR, ci = r / 9, t = r - ci * 9;
+            wl[i] = (c0 + c < Cout && ci < Cin) ? ld(w + ((size_t)(c0 + c) * Cin + ci) * 9 + t) : 0.0f;
+        }
+        if (POOL) {
+            // windows that overlap the patch; one that no pixel of the rectangle reads may lie outside the delta view
+            const int wy0 = py0 >> 1, wx0 = px0 >> 1;
+            const int nwy = ((oy0 + TH) >> 1) - wy0 + 1, nwx = ((ox0 + TW) >> 1) - wx0 + 1;
+            for (int idx = tid; idx < nwy * nwx; idx += 256) {
+                const int wyi = idx / nwx, wy = wy0 + wyi, wx = wx0 + (idx - wyi * nwx);
+                const bool need = wy >= 0 && 2 * wy < Hc && wx >= 0 && 2 * wx < Wc &&
+                                  2 * wy + 1 >= rt.y0[ti] - 1 && 2 * wy <= rt.y1[ti] + 1 &&
+                                  2 * wx + 1 >= rt.x0[tj] - 1 && 2 * wx <= rt.x1[tj] + 1;
+                const int sy = need ? wy : (rt.y0[ti] >> 1), sx = need ? wx : (rt.x0[tj] >> 1);
+                const uint8_t* mp = at<uint8_t>(mask, stack, ti, tj, n, 0, sy, sx);
+                const T* gp = at<T>(din, stack, ti, tj, n, 0, sy, sx);
+                float g[COC]; uint8_t m[COC];
+#pragma unroll
+                for (int c = 0; c < COC; ++c) {
+                    const int co = c0 + c < Cout ? c0 + c : Cout - 1;
+                    g[c] = ld(gp + (long long)co * din.cs);
+                    m[c] = mp[(long long)co * mask.cs];
+                }
+                const int r0 = 2 * wy - py0, q0 = 2 * wx - px0;
+#pragma unroll
+                for (int pos = 0; pos < 4; ++pos) {
+                    const int r = r0 + (pos >> 1), q = q0 + (pos & 1);
+                    if (r >= 0 && r < TH + 2 && q >= 0 && q < TW + 2) {
+#pragma unroll
+                        for (int c = 0; c < COC; ++c)
+                            dz[c * CH + r * PP + q] = (need && c0 + c < Cout && ((m[c] >> 1) & 3) == pos) ? g[c] : 0.0f;
+                    }
+                }
+            }
+        } else {
+            for (int idx = tid; idx < (TH + 2) * (TW + 2); idx += 256) {
+                const int r = idx / (TW + 2), q = idx - r * (TW + 2);
+                const int qy = py0 + r, qx = px0 + q;
+                const bool need = qy >= 0 && qy < Hc && qx >= 0 && qx < Wc && qy <= rt.y1[ti] + 1 && qx <= rt.x1[tj] + 1;
+                const T* gp = at<T>(din, stack, ti, tj, n, 0, need ? qy : rt.y0[ti], need ? qx : rt.x0[tj]);
+                float g[COC];
+#pragma unroll
+                for (int c = 0; c < COC; ++c) {
+                    const int co = c0 + c < Cout ? c0 + c : Cout - 1;
+                    g[c] = ld(gp + (long long)co * din.cs);
+                }
+#pragma unroll
+                for (int c = 0; c < COC; ++c) dz[c * CH + r * PP + q] = (need && c0 + c < Cout) ? g[c] : 0.0f;
+            }
+        }
+        __syncthreads();
+        if (worker) {
+#pragma unroll 2
+            for (int c = 0; c < COC; ++c) {
+                float d[3][6];
+#pragma unroll
+                for (int rr = 0; rr < 3; ++rr) {
+                    const float* row = dz + c * CH + (ty + rr) * PP + 4 * tx;
+                    const float4 a4 = *(const float4*)row;
+                    const float2 a2 = *(const float2*)(row + 4);
+                    d[rr][0] = a4.x; d[rr][1] = a4.y; d[rr][2] = a4.z; d[rr][3] = a4.w; d[rr][4] = a2.x; d[rr][5] = a2.y;
+                }
+                const float* wc = wl + c * WR;
+#pragma unroll
+                for (int j = 0; j < CI; ++j)
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+                        for (int kx = 0; kx < 3; ++kx) {
+                            const float wv = wc[j * 9 + ky * 3 + kx];
+                            // dX[y][x] += W[ky][kx] * dZ[y + 1 - ky][x + 1 - kx]; the patch starts at (y0 - 1, x0 - 1)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) acc[j][q] = fmaf(wv, d[2 - ky][q + 2 - kx], acc[j][q]);
+                        }
+            }
+        }
+    }
+    if (!worker) return;
+    const int iy = oy0 + ty;
+    if (iy > rt.y1[ti]) return;
+#pragma unroll
+    for (int j = 0; j < CI; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int ix = ox0 + 4 * tx + q;
+            if (j < Cin && ix <= rt.x1[tj]) {
+                float v = acc[j][q];
+                if (scale_out) v = scaled_delta<T>(v, sign_bit(isign, stack, ti, tj, n, j, iy, ix), in_slope);
+                st(at<T>(dout, stack, ti, tj, n, j, iy, ix), v);
+            }
+        }
+}
+
 bool thin_bwd_data_eligible(const ConvArgs& a) { return a.Cin <= 4; }
 
 void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
@@ -97,6 +225,27 @@ void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
     int mw = 0, mh = 0;
     for (int t = 0; t < a.M; ++t) mw = mw > a.rect.x1[t] - a.rect.x0[t] + 1 ? mw : a.rect.x1[t] - a.rect.x0[t] + 1;
     for (int t = 0; t < a.N; ++t) mh = mh > a.rect.y1[t] - a.rect.y0[t] + 1 ? mh : a.rect.y1[t] - a.rect.y0[t] + 1;
+    if (a.K == 3) {
+        // tile = 4*ntx x nty pixels fitted to the largest rectangle
+        int tiles_x = (mw + 63) / 64;
+        const int ntx = ((mw + tiles_x - 1) / tiles_x + 3) / 4;
+        tiles_x = (mw + 4 * ntx - 1) / (4 * ntx);
+        int nty_max = 256 / ntx; if (nty_max > 64) nty_max = 64;
+        const int tiles_y = (mh + nty_max - 1) / nty_max;
+        const int nty = (mh + tiles_y - 1) / tiles_y;
+        const int PP = (4 * ntx + 2 + 3) & ~3;
+        if ((nty + 2) * PP <= kThin4Patch) {
+            dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
+            g_kernel_label = "k_conv_bwd_data_thin4";
+#define FTP_T4(T, PL, CI) hipLaunchKernelGGL((k_conv_bwd_data_thin4<T, PL, CI>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, (const T*)a.w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch, ntx, nty, tiles_x)
+#define FTP_T4C(T, PL) do { if (a.Cin <= 3) FTP_T4(T, PL, 3); else FTP_T4(T, PL, 4); } while (0)
+            if (a.bf16) { if (a.pooled) FTP_T4C(bf16_t, true); else FTP_T4C(bf16_t, false); }
+            else        { if (a.pooled) FTP_T4C(float, true); else FTP_T4C(float, false); }
+#undef FTP_T4C
+#undef FTP_T4
+            return;
+        }
+    }
     const int tiles_x = (mw + 63) / 64, tiles_y = (mh + 3) / 4;
     dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
     g_kernel_label = "k_conv_bwd_data_thin";
