@@ -160,11 +160,12 @@ k_wgrad_mfma(MfmaWgradArgs a)
 
     auto multiply = [&](const Chunk& c) {
         const int nrows = c.ni * c.nr, nph = c.nr + 2 * P, ncp = (c.nc + 1) & ~1;
-        for (int rr = wave_k; rr < nrows; rr += WAVES_K) {
+        for (int rr = 0; rr < nrows; ++rr) {
             const int il = rr / c.nr, r = rr - il * c.nr;
             const float* zrow = Zl + (rr * TCp + hi) * ZP + co_l;
             const float* xrow = Xl + ((il * nph + r) * PW + hi) * XP + ci_l;
-            for (int xp = 0; xp < ncp; xp += 2) {
+            // wavefronts that share a (co, ci) tile take alternate pixel pairs of every row
+            for (int xp = 2 * wave_k; xp < ncp; xp += 2 * WAVES_K) {
                 const float av = zrow[xp * ZP];
 #pragma unroll
                 for (int t = 0; t < KK; ++t) {
