@@ -270,7 +270,8 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
 {
     constexpr int KK = K * K, P = K / 2, ZP = 33;
     extern __shared__ float lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: row bookkeeping stays scalar
     const int hi = lane >> 5, l32 = lane & 31;
     const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.own.x0[tj], x1 = a.own.x1[tj], y0 = a.own.y0[ti], y1 = a.own.y1[ti];
@@ -281,6 +282,7 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
 
     const int TCp = (rw + 1) & ~1;
     int TR = a.PK / TCp; if (TR < 1) TR = 1; if (TR > rh) TR = rh;
+    if (POOL && TR > 1) TR &= ~1;                      // whole windows (the host provides PK >= two rows)
     int TI = 1;
     if (TR == rh) { TI = a.PK / (TCp * rh); if (TI < 1) TI = 1; }
     const int PW = TCp + 2 * P, PH = TR + 2 * P;
@@ -303,54 +305,95 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
             const int yb = y0 + rb * TR;
             const int nr = (y1 - yb + 1) < TR ? (y1 - yb + 1) : TR;
             __syncthreads();
-            // dZ rows: wavefront w takes channels w, w+4, ... (8 of them, loaded together); lanes run along the row
-            for (int row = 0; row < ni * nr; ++row) {
-                const int il = row / nr, r = row - il * nr;
-                const int qy = yb + r, sy = POOL ? (qy >> 1) : qy;
-                for (int col = lane; col < TCp; col += 64) {
-                    const int qx = x0 + (col < rw ? col : rw - 1), sx = POOL ? (qx >> 1) : qx;
-                    const int code = ((qy & 1) << 1) | (qx & 1);
+            // dZ, pixel-major [pixel][co]: wavefront w takes channels w, w+4, ... (8 of them).  All loads of a pass
+            // are unconditional (clamped) and issued together; what must be zero is zeroed at the LDS write.
+            if (POOL) {
+                // behind a pool one (delta, winner) pair per window and channel serves the window's 4 pixels;
+                // owned rectangles of a pooled convolution start and end on window borders
+                const int wpr = TCp >> 1, wrows = nr >> 1;
+                const int nwin = ni * wrows * wpr;
+                for (int wb = 0; wb < nwin; wb += 64) {
+                    const bool ok = wb + lane < nwin;
+                    const int wi = ok ? wb + lane : 0;
+                    const int wrow = wi / wpr, wx = wi - wrow * wpr;
+                    const int il = wrow / wrows, wr = wrow - il * wrows;
+                    const int sy = (yb >> 1) + wr, sx = (x0 >> 1) + wx;
                     const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, n0 + il, 0, sy, sx);
                     const T* gp = at<T>(a.din, stack, ti, tj, n0 + il, 0, sy, sx);
                     uint8_t m[8]; float g[8];
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
                         const int co = co0 + wave + 4 * k < a.Cout ? co0 + wave + 4 * k : a.Cout - 1;
-                        m[k] = POOL ? mp[(long long)co * a.mask.cs] : (uint8_t)0;
+                        m[k] = mp[(long long)co * a.mask.cs];
                         g[k] = ld(gp + (long long)co * a.din.cs);
                     }
+                    if (ok) {
+#pragma unroll
+                        for (int pos = 0; pos < 4; ++pos) {
+                            float* zdst = Zl + ((il * nr + 2 * wr + (pos >> 1)) * TCp + 2 * wx + (pos & 1)) * ZP + wave;
+#pragma unroll
+                            for (int k = 0; k < 8; ++k)
+                                zdst[4 * k] = (((m[k] >> 1) & 3) == pos && co0 + wave + 4 * k < a.Cout) ? g[k] : 0.0f;
+                        }
+                    }
+                }
+            } else {
+                const int npos = ni * nr * TCp;
+                for (int pb = 0; pb < npos; pb += 64) {
+                    const bool ok = pb + lane < npos;
+                    const int pos = ok ? pb + lane : 0;
+                    const int row = pos / TCp, col = pos - row * TCp;
+                    const int il = row / nr, r = row - il * nr;
+                    const T* gp = at<T>(a.din, stack, ti, tj, n0 + il, 0, yb + r, x0 + (col < rw ? col : rw - 1));
+                    float g[8];
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
-                        float v = g[k];                                      // the delta maps hold dLoss/dZ
-                        if (POOL && ((m[k] >> 1) & 3) != code) v = 0.0f;
-                        if (col >= rw || co0 + wave + 4 * k >= a.Cout) v = 0.0f;
-                        Zl[(row * TCp + col) * ZP + wave + 4 * k] = v;
+                        const int co = co0 + wave + 4 * k < a.Cout ? co0 + wave + 4 * k : a.Cout - 1;
+                        g[k] = ld(gp + (long long)co * a.din.cs);
+                    }
+                    if (ok) {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k)
+                            Zl[pos * ZP + wave + 4 * k] = (col < rw && co0 + wave + 4 * k < a.Cout) ? g[k] : 0.0f;
                     }
                 }
             }
-            // X patch rows in natural order [ci][image][row][column]
+            // X patch in natural order [ci][image][row][column]: a wavefront takes whole rows (the row's place in the
+            // patch is wave-uniform, no per-lane division), 4 rows in flight
             {
                 const int nph = nr + 2 * P;
-                for (int prow = wave; prow < a.Cin * ni * nph; prow += 4) {
-                    const int ci = prow / (ni * nph), rem = prow - ci * (ni * nph);
-                    const int il = rem / nph, r = rem - il * nph;
-                    const int gy = yb - P + r;
-                    for (int col = lane; col < PW; col += 64) {
-                        const int gx = x0 - P + col;
-                        float v = 0.0f;
-                        if (col < rw + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc)
-                            v = ld(at<T>(a.in, stack, ti, tj, n0 + il, ci, gy, gx));
-                        Xl[ci * XCS + (il * PH + r) * PW + col] = v;
+                const int rows = a.Cin * ni * nph;
+                for (int pr0 = 0; pr0 < rows; pr0 += 16)
+                for (int cb = 0; cb < PW; cb += 64) {
+                    const int col = cb + lane;
+                    const int gx = x0 - P + col;
+                    const bool xin = col < rw + 2 * P && gx >= 0 && gx < a.Wc;
+                    float v[4]; int dst[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int prow = pr0 + wave + 4 * u;
+                        const bool rok = prow < rows;
+                        const int pc = rok ? prow : 0;
+                        const int ci = pc / (ni * nph), rem = pc - ci * (ni * nph);
+                        const int il = rem / nph, r = rem - il * nph;
+                        const int gy = yb - P + r;
+                        const bool inside = xin && gy >= 0 && gy < a.Hc;
+                        v[u] = ld(at<T>(a.in, stack, ti, tj, n0 + il, ci, inside ? gy : y0, inside ? gx : x0));
+                        if (!inside) v[u] = 0.0f;
+                        dst[u] = (rok && col < PW) ? ci * XCS + (il * PH + r) * PW + col : -1;
                     }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) if (dst[u] >= 0) Xl[dst[u]] = v[u];
                 }
             }
             __syncthreads();
+            // the 4 wavefronts take alternate pixel pairs of every row
             const int nrows = ni * nr;
-            for (int rr = wave; rr < nrows; rr += 4) {
+            for (int rr = 0; rr < nrows; ++rr) {
                 const int il = rr / nr, r = rr - il * nr;
                 const float* zrow = Zl + (rr * TCp + hi) * ZP + l32;
                 const float* xrow = Xl + lane_off + (il * PH + r) * PW;
-                for (int xp = 0; xp < TCp; xp += 2)
+                for (int xp = 2 * wave; xp < TCp; xp += 8)
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(zrow[xp * ZP], xrow[xp], acc, 0, 0, 0);
             }
         }
@@ -400,12 +443,14 @@ ThinGeom thin_geom(const ConvArgs& c)
     g.PK = 256;
     const int P = c.K / 2;
     int max_pos = 1;
-    for (int t = 0; t < c.M; ++t) { const int w = ((c.rect.x1[t] - c.rect.x0[t] + 2) & ~1); if (w > g.PK) g.PK = w; }
+    // one padded row at least; behind a pool two, so that a chunk holds whole windows
+    for (int t = 0; t < c.M; ++t) { const int w = ((c.rect.x1[t] - c.rect.x0[t] + 2) & ~1) * (c.pooled ? 2 : 1); if (w > g.PK) g.PK = w; }
     for (int i = 0; i < c.N; ++i)
         for (int j = 0; j < c.M; ++j) {
             const int rw = c.rect.x1[j] - c.rect.x0[j] + 1, rh = c.rect.y1[i] - c.rect.y0[i] + 1;
             const int TCp = (rw + 1) & ~1;
             int TR = g.PK / TCp; if (TR < 1) TR = 1; if (TR > rh) TR = rh;
+            if (c.pooled && TR > 1) TR &= ~1;
             int TI = 1; if (TR == rh) { TI = g.PK / (TCp * rh); if (TI < 1) TI = 1; }
             const int pos = TI * (TR + 2 * P) * (TCp + 2 * P);
             if (pos > max_pos) max_pos = pos;
@@ -422,6 +467,11 @@ ThinGeom thin_geom(const ConvArgs& c)
 bool thin_wgrad_eligible(const ConvArgs& c)
 {
     if (c.has_bias || c.Cin * c.K * c.K > 32) return false;
+    if (c.pooled) {
+        // owned rectangles of a pooled convolution consist of whole windows; anything else goes to the generic kernel
+        for (int t = 0; t < c.M; ++t) if ((c.rect.x0[t] & 1) || !((c.rect.x1[t] - c.rect.x0[t]) & 1)) return false;
+        for (int t = 0; t < c.N; ++t) if ((c.rect.y0[t] & 1) || !((c.rect.y1[t] - c.rect.y0[t]) & 1)) return false;
+    }
     return thin_geom(c).lds <= 64 * 1024;
 }
 
