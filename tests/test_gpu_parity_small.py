@@ -19,6 +19,8 @@ _NETS = {
     "pools": ((conv(3, 8), pool(8), conv(8, 16), conv(16, 8, 1), pool(8), conv(8, 12)), 48, 40),
     "poolfirst": ((pool(3), conv(3, 6), pool(6), pool(6), conv(6, 10), conv(10, 4, 1)), 64, 48),
     "wide": ((conv(3, 20), pool(20), conv(20, 40), conv(40, 24, 1), conv(24, 33)), 28, 36),
+    # 4 input channels, 128-channel workgroups, 1x1 with many reduction channels, tiles wider than one column block
+    "deep": ((conv(4, 32), pool(32), conv(32, 128), conv(128, 64, 1), pool(64), conv(64, 160), conv(160, 128)), 144, 136),
 }
 
 
@@ -29,7 +31,7 @@ def _mk(net, grid, grouping, dtype="f32", batch=2):
     return Config("%s_%s" % (net, grouping), batch, layers[0].cin, h, w, layers, grid, ends, dtype)
 
 
-@pytest.mark.parametrize("net", sorted(_NETS))
+@pytest.mark.parametrize("net", ["convs", "poolfirst", "pools", "wide"])
 @pytest.mark.parametrize("grouping", ["whole", "each", "split"])
 @pytest.mark.parametrize("grid", [(1, 1), (3, 2), (2, 4)])
 def test_small_nets_f32(oracle, net, grouping, grid):
@@ -40,6 +42,16 @@ def test_small_nets_f32(oracle, net, grouping, grid):
 @pytest.mark.parametrize("grouping", ["whole", "each"])
 def test_small_nets_bf16(oracle, net, grouping):
     P.check_case(oracle, _mk(net, (3, 2), grouping, "bf16"))
+
+
+@pytest.mark.parametrize("grid", [(1, 1), (2, 3)])
+@pytest.mark.parametrize("grouping", ["whole", "split"])
+def test_deep_net_f32(oracle, grid, grouping):
+    P.check_case(oracle, _mk("deep", grid, grouping, batch=3))
+
+
+def test_deep_net_bf16(oracle):
+    P.check_case(oracle, _mk("deep", (2, 2), "split", "bf16", batch=2))
 
 
 @pytest.mark.parametrize("grouping", ["whole", "split"])
