@@ -611,11 +611,10 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc
 {
     const int S = POOL_OUT ? 2 : 1;
     DlShape best = {0, 0, 0}; double best_cost = 0;
-    for (int BN = 256; BN >= 128; BN /= 2)
-        for (int BM = 128; BM >= 32; BM /= 2) {
-            if (BM == 128 && a.Mtot < 128) continue;
-            if (BM == 64 && a.Mtot <= 32) continue;
-            if (BM == 32 && a.Mtot > 32 && a.Mtot % 64 == 0) continue;          // 32 only where 64 would be padded
+    // as many output channels per workgroup as the layer has (up to 128): every further channel block re-reads the
+    // whole input patch, and with many blocks in flight the filter no longer stays in the L2 cache
+    const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
+    for (int BN = 256; BN >= 128; BN /= 2) {
             const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, conv_dl_max_positions(K, BN));
             if (tc.cs > conv_dl_max_positions(K, BN)) continue;
             // tiles that exist: every stack has its own count, the grid is sized for the largest
