@@ -14,7 +14,7 @@ namespace ftp {
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 // LDS positions of one staged chunk: pixels of dZ, patch positions of X (a multiple of 64).
-constexpr int kWgradZPos = 64, kWgradXPos = 192;
+constexpr int kWgradZPos = 64, kWgradXPos = 192;      // the limits wgrad_chunks() cuts to
 
 template <typename T, int K, int WAVES_CO, int WAVES_CI, bool POOL>
 __global__ void __launch_bounds__(256, 2)
@@ -26,7 +26,6 @@ k_wgrad_mfma(MfmaWgradArgs a)
     constexpr int ZP = BCO + 1, XP = BCI + 1;          // odd strides: conflict-free transposing writes
     constexpr int NZ = BCO / 4, NX = BCI / 4;          // channels each wavefront stages
     constexpr int ZPOS = kWgradZPos, XPOS = kWgradXPos, XPASS = XPOS / 64;
-    constexpr int MAXC = 64 - 2 * P;                   // widest column block: 3 patch rows fit XPOS
 
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -39,22 +38,13 @@ k_wgrad_mfma(MfmaWgradArgs a)
     const int tiles_ci = (a.Cin + BCI - 1) / BCI;
     const int co0 = (blockIdx.x / tiles_ci) * BCO, ci0 = (blockIdx.x % tiles_ci) * BCI;
     const int split = blockIdx.y;
-    const int nb0 = (int)((long long)split * a.batch / a.splits), nb1 = (int)((long long)(split + 1) * a.batch / a.splits);
 
     // Chunk geometry of this stack: TI images x TR rows x TC columns of the owned rectangle, at most ZPOS
-    // pixels (rows padded to an even length TCp) and at most XPOS patch positions.
-    const int col_blocks = (rw + MAXC - 1) / MAXC;
-    const int TC = (rw + col_blocks - 1) / col_blocks;
-    const int TCp = (TC + 1) & ~1, PW = TCp + 2 * P;
-    int TR = ZPOS / TCp; if (TR > rh) TR = rh;
-    const int row_blocks = (rh + TR - 1) / TR;
-    int TI = 1;
-    if (TR == rh && col_blocks == 1) {
-        TI = ZPOS / (TCp * rh);
-        const int by_patch = XPOS / ((rh + 2 * P) * PW);
-        if (TI > by_patch) TI = by_patch;
-        if (TI < 1) TI = 1;
-    }
+    // pixels (rows padded to an even length TCp) and at most XPOS patch positions.  The stack's chunk list
+    // (image block, row block, column block) is cut into a.splits contiguous shares.
+    const WgradChunks wc = wgrad_chunks(rw, rh, a.batch, P);
+    const int col_blocks = wc.col_blocks, TC = wc.TC, TCp = wc.TCp, PW = wc.PW, TR = wc.TR, row_blocks = wc.row_blocks, TI = wc.TI;
+    const int id0 = (int)((long long)split * wc.total / a.splits), id1 = (int)((long long)(split + 1) * wc.total / a.splits);
     float* Zl = lds;                                   // [pixel][ZP]
     float* Xl = lds + ZPOS * ZP;                       // [patch position][XP]
 
@@ -67,9 +57,9 @@ k_wgrad_mfma(MfmaWgradArgs a)
     const int co_l = wave_co * 32 + l32, ci_l = wave_ci * 32 + l32;
 
     struct Chunk { int n0, yb, xb, ni, nr, nc; };
-    auto chunk_at = [&](int n0, int rb, int cb) {
+    auto chunk_at = [&](int ib, int rb, int cb) {
         Chunk c;
-        c.n0 = n0; c.ni = (nb1 - n0) < TI ? (nb1 - n0) : TI;
+        c.n0 = ib * TI; c.ni = (a.batch - c.n0) < TI ? (a.batch - c.n0) : TI;
         c.yb = y0 + rb * TR; c.nr = (y1 - c.yb + 1) < TR ? (y1 - c.yb + 1) : TR;
         c.xb = x0 + cb * TC; c.nc = (x1 - c.xb + 1) < TC ? (x1 - c.xb + 1) : TC;
         return c;
@@ -177,18 +167,20 @@ k_wgrad_mfma(MfmaWgradArgs a)
     };
 
     // The next chunk travels from HBM into registers while the matrix cores work on the current one.
-    if (nb0 < nb1) {
-        int n0 = nb0, rb = 0, cb = 0;
-        Chunk cur = chunk_at(n0, rb, cb);
+    if (id0 < id1) {
+        int id = id0;
+        int ib = id / (row_blocks * col_blocks), rem = id - ib * (row_blocks * col_blocks);
+        int rb = rem / col_blocks, cb = rem - rb * col_blocks;
+        Chunk cur = chunk_at(ib, rb, cb);
         load(cur);
         for (;;) {
             __syncthreads();                            // the previous chunk has been consumed
             store();
             __syncthreads();
-            if (++cb == col_blocks) { cb = 0; if (++rb == row_blocks) { rb = 0; n0 += TI; } }
-            const bool more = n0 < nb1;
+            if (++cb == col_blocks) { cb = 0; if (++rb == row_blocks) { rb = 0; ++ib; } }
+            const bool more = ++id < id1;
             Chunk nxt = cur;
-            if (more) { nxt = chunk_at(n0, rb, cb); load(nxt); }
+            if (more) { nxt = chunk_at(ib, rb, cb); load(nxt); }
             multiply(cur);
             if (!more) break;
             cur = nxt;
@@ -249,12 +241,6 @@ bool mfma_wgrad_eligible(const ConvArgs& c)
     return !c.has_bias && c.Cout >= 32 && c.Cin >= 16;
 }
 
-int mfma_wgrad_splits(const ConvArgs& c)
-{
-    const int tile_px = ((c.Wc + c.M - 1) / c.M) * ((c.Hc + c.N - 1) / c.N);
-    return wgrad_batch_shares(c.Cout, c.Cin, c.K, c.N * c.M, c.batch, tile_px);
-}
-
 // c.rect = owned rectangle at the convolution output (before the pool); scratch holds the batch shares.
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
 {
@@ -262,7 +248,7 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.rect;
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
     a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
-    a.splits = mfma_wgrad_splits(c);
+    a.splits = c.wgrad_shares;
     a.PK = kWgradZPos;
     const int waves_ci = c.Cin >= 64 ? 2 : 1;
     const int BCO = 64, BCI = 32 * waves_ci;

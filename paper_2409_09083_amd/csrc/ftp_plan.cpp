@@ -252,12 +252,19 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
     }
     {
         size_t scratch = 0;
-        for (const Unit& u : p.units) {
+        for (Unit& u : p.units) {
             if (u.kind != UNIT_CONV) continue;
             const ftp_layer& ly = p.layers[u.layer];
-            const int tile_px = ((p.W[u.bi] + M - 1) / M) * ((p.H[u.bi] + N - 1) / N);
-            const int shares = std::max(wgrad_batch_shares(ly.cout, ly.cin, ly.k, N * M, batch, tile_px),
-                                        wgrad_batch_shares_thin(ly.cout, N * M, batch));
+            // chunk count of the largest owned rectangle at the convolution output
+            const GroupRects& gr = p.groups[u.group];
+            int chunks = 1;
+            for (int i = 0; i < N; ++i)
+                for (int j = 0; j < M; ++j) {
+                    const Seg sx = gr.at(FTP_RECT_OWN, u.layer + 1, 0, j), sy = gr.at(FTP_RECT_OWN, u.layer + 1, 1, i);
+                    chunks = std::max(chunks, wgrad_chunks(sx.b - sx.a + 1, sy.b - sy.a + 1, batch, ly.k / 2).total);
+                }
+            u.wgrad_shares = wgrad_shares(ly.cout, ly.cin, ly.k, N * M, chunks);
+            const int shares = std::max(u.wgrad_shares, wgrad_batch_shares_thin(ly.cout, N * M, batch));
             if (shares > 1) scratch = std::max(scratch, stacks * shares * (size_t)ly.cout * ly.cin * ly.k * ly.k * sizeof(float));
         }
         p.wgrad_scratch_offset = alloc(scratch);

@@ -56,6 +56,7 @@ struct Unit {
     size_t param_offset = 0;                  // first filter element in the parameter vector
     size_t bias_offset = 0;
     size_t wt_fwd_offset = 0, wt_bwd_offset = 0;   // relaid filter copies in the workspace (bytes)
+    int wgrad_shares = 1;                     // shares of the matrix-core filter gradient (the scratch is sized for them)
 };
 
 struct Plan {
@@ -81,20 +82,53 @@ struct Plan {
     double useful_macs = 0, executed_macs = 0, halo_bytes[2] = {0, 0};
 };
 
-// Number of batch shares the matrix-core filter-gradient kernel splits one stack's reduction into.  A
-// workgroup handles one 64 x 64 block of (co, ci) of one stack and one share; the chip runs one such
-// workgroup per compute unit at a time, so the launch takes ceil(workgroups / 256) rounds of
-// ceil(batch / shares) images each.  The count that minimises rounds x images plus the cost of writing and
-// re-reading the shares (summed afterwards in a fixed order) is taken.  tile_px = pixels of the largest tile.
-inline int wgrad_batch_shares(int cout, int cin, int k, int stacks, int batch, int tile_px)
+#if defined(__HIPCC__)
+#define FTP_HD __host__ __device__
+#else
+#define FTP_HD
+#endif
+
+// How the matrix-core filter-gradient kernel cuts one stack's owned rectangle (rw x rh, batch images) into chunks
+// of at most 64 pixels (rows padded to an even length) and 192 patch positions: column blocks of TC, row blocks
+// of TR, and, where a whole rectangle is smaller than a chunk, TI images at once.  Used by the kernel and by the
+// host (share count), so both see the same numbers.
+struct WgradChunks { int col_blocks, TC, TCp, PW, TR, row_blocks, TI, img_blocks, total; };
+FTP_HD inline WgradChunks wgrad_chunks(int rw, int rh, int batch, int P)
+{
+    const int ZPOS = 64, XPOS = 192, MAXC = 64 - 2 * P;      // widest column block: 3 patch rows fit XPOS
+    WgradChunks c;
+    c.col_blocks = (rw + MAXC - 1) / MAXC;
+    c.TC = (rw + c.col_blocks - 1) / c.col_blocks;
+    c.TCp = (c.TC + 1) & ~1; c.PW = c.TCp + 2 * P;
+    c.TR = ZPOS / c.TCp; if (c.TR > rh) c.TR = rh;
+    c.row_blocks = (rh + c.TR - 1) / c.TR;
+    c.TI = 1;
+    if (c.TR == rh && c.col_blocks == 1) {
+        c.TI = ZPOS / (c.TCp * rh);
+        const int by_patch = XPOS / ((rh + 2 * P) * c.PW);
+        if (c.TI > by_patch) c.TI = by_patch;
+        if (c.TI < 1) c.TI = 1;
+    }
+    c.img_blocks = (batch + c.TI - 1) / c.TI;
+    c.total = c.img_blocks * c.row_blocks * c.col_blocks;
+    return c;
+}
+
+// Number of shares the matrix-core filter-gradient kernel splits one stack's chunk list into (contiguous ranges,
+// summed afterwards in share order).  A workgroup handles one 64 x 64 block of (co, ci) of one stack and one share;
+// two workgroups share a CU's matrix cores, so a launch takes ceil(workgroups / 512) rounds of 2 x ceil(chunks /
+// shares) chunk times.  The count that minimises that plus the cost of writing and re-reading the shares is taken.
+// chunks = chunk count of the largest stack.
+inline int wgrad_shares(int cout, int cin, int k, int stacks, int chunks)
 {
     const double blocks = (double)((cout + 63) / 64) * ((cin + 63) / 64) * stacks;
-    const double unit_us = (double)tile_px * k * k * 32.0 / 2400.0 / 0.7;                 // one image of one block
+    const double unit_us = 64.0 * k * k * 32.0 / 2400.0 / 0.7;                          // one chunk of one block
     const double share_us = (double)stacks * cout * cin * k * k * 8.0 / 3.0e6;          // one more share: write + read
+    const int smax = chunks < 256 ? chunks : 256;
     int best = 1; double best_t = 0;
-    for (int s = 1; s <= batch; ++s) {
-        const double rounds = (double)(long long)((blocks * s + 255) / 256);
-        const double t = rounds * ((batch + s - 1) / s) * unit_us + (s > 1 ? s * share_us : 0.0);
+    for (int s = 1; s <= smax; ++s) {
+        const double rounds = (double)(long long)((blocks * s + 511) / 512);
+        const double t = rounds * 2.0 * ((chunks + s - 1) / s) * unit_us + (s > 1 ? s * share_us : 0.0);
         if (s == 1 || t < best_t) { best = s; best_t = t; }
     }
     return best;
