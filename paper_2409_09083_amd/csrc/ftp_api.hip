@@ -90,7 +90,7 @@ ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void*
     a.slope = ly.leaky_slope;
     a.N = p.N; a.M = p.M; a.batch = p.batch;
     a.bf16 = p.dtype == FTP_BF16;
-    a.wgrad_shares = u.wgrad_shares;
+    a.wgrad_shares = u.wgrad_shares; a.wgrad_shares_thin = u.wgrad_shares_thin;
     return a;
 }
 

@@ -40,7 +40,7 @@ struct ConvArgs {
     float slope = 0.1f;
     int N = 1, M = 1, batch = 1;
     int bf16 = 0;
-    int wgrad_shares = 1;           // shares of the matrix-core filter gradient (from the plan, which sized the scratch)
+    int wgrad_shares = 1, wgrad_shares_thin = 1;   // shares of the matrix-core filter-gradient kernels (from the plan, which sized the scratch)
 };
 
 struct PoolArgs {

@@ -264,7 +264,16 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
                     chunks = std::max(chunks, wgrad_chunks(sx.b - sx.a + 1, sy.b - sy.a + 1, batch, ly.k / 2).total);
                 }
             u.wgrad_shares = wgrad_shares(ly.cout, ly.cin, ly.k, N * M, chunks);
-            const int shares = std::max(u.wgrad_shares, wgrad_batch_shares_thin(ly.cout, N * M, batch));
+            int wmax = 0, tchunks = 1;
+            for (int j = 0; j < M; ++j) { const Seg sx = gr.at(FTP_RECT_OWN, u.layer + 1, 0, j); wmax = std::max(wmax, (sx.b - sx.a + 2) & ~1); }
+            const int PK = thin_wgrad_pk(wmax, u.pooled);
+            for (int i = 0; i < N; ++i)
+                for (int j = 0; j < M; ++j) {
+                    const Seg sx = gr.at(FTP_RECT_OWN, u.layer + 1, 0, j), sy = gr.at(FTP_RECT_OWN, u.layer + 1, 1, i);
+                    tchunks = std::max(tchunks, thin_wgrad_chunks(sx.b - sx.a + 1, sy.b - sy.a + 1, batch, PK, u.pooled).total);
+                }
+            u.wgrad_shares_thin = wgrad_shares_thin(ly.cout, N * M, tchunks);
+            const int shares = std::max(u.wgrad_shares, u.wgrad_shares_thin);
             if (shares > 1) scratch = std::max(scratch, stacks * shares * (size_t)ly.cout * ly.cin * ly.k * ly.k * sizeof(float));
         }
         p.wgrad_scratch_offset = alloc(scratch);

@@ -56,7 +56,7 @@ struct Unit {
     size_t param_offset = 0;                  // first filter element in the parameter vector
     size_t bias_offset = 0;
     size_t wt_fwd_offset = 0, wt_bwd_offset = 0;   // relaid filter copies in the workspace (bytes)
-    int wgrad_shares = 1;                     // shares of the matrix-core filter gradient (the scratch is sized for them)
+    int wgrad_shares = 1, wgrad_shares_thin = 1;   // shares of the two matrix-core filter-gradient kernels (the scratch is sized for them)
 };
 
 struct Plan {
@@ -134,12 +134,34 @@ inline int wgrad_shares(int cout, int cin, int k, int stacks, int chunks)
     return best;
 }
 
-// The same for the kernel of layers with very few input channels (blocks of 32 output channels).
-inline int wgrad_batch_shares_thin(int cout, int stacks, int batch)
+// The kernel for layers with very few input channels stages PK pixels per chunk: TI images x TR rows of the owned
+// rectangle (rows padded to even; behind a pool TR is even so that a chunk holds whole windows).
+FTP_HD inline int thin_wgrad_pk(int widest_padded_row, bool pooled)
+{
+    const int need = widest_padded_row * (pooled ? 2 : 1);
+    return need > 256 ? need : 256;
+}
+struct ThinChunks { int TCp, TR, TI, row_blocks, img_blocks, total; };
+FTP_HD inline ThinChunks thin_wgrad_chunks(int rw, int rh, int batch, int PK, bool pooled)
+{
+    ThinChunks c;
+    c.TCp = (rw + 1) & ~1;
+    c.TR = PK / c.TCp; if (c.TR < 1) c.TR = 1; if (c.TR > rh) c.TR = rh;
+    if (pooled && c.TR > 1) c.TR &= ~1;
+    c.TI = 1;
+    if (c.TR == rh) { c.TI = PK / (c.TCp * rh); if (c.TI < 1) c.TI = 1; }
+    c.row_blocks = (rh + c.TR - 1) / c.TR;
+    c.img_blocks = (batch + c.TI - 1) / c.TI;
+    c.total = c.img_blocks * c.row_blocks;
+    return c;
+}
+// Shares of its chunk list (blocks of 32 output channels x stacks x shares should reach about 1024 workgroups).
+inline int wgrad_shares_thin(int cout, int stacks, int chunks)
 {
     const int blocks = ((cout + 31) / 32) * stacks;
     int shares = (1024 + blocks - 1) / blocks;
-    if (shares > batch) shares = batch;
+    if (shares > chunks) shares = chunks;
+    if (shares > 256) shares = 256;
     return shares < 1 ? 1 : shares;
 }
 

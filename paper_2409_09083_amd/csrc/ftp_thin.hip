@@ -6,6 +6,7 @@
 //    and reduces over pixels, so the matrix cores are used without padding the 3 channels to 32.
 #include "ftp_device.h"
 #include "ftp_launch.h"
+#include <algorithm>
 
 namespace ftp {
 
@@ -278,18 +279,15 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
     const int rw = x1 - x0 + 1, rh = y1 - y0 + 1;
     const int co0 = blockIdx.x * 32;
     const int split = blockIdx.y;
-    const int nb0 = (int)((long long)split * a.batch / a.splits), nb1 = (int)((long long)(split + 1) * a.batch / a.splits);
 
-    const int TCp = (rw + 1) & ~1;
-    int TR = a.PK / TCp; if (TR < 1) TR = 1; if (TR > rh) TR = rh;
-    if (POOL && TR > 1) TR &= ~1;                      // whole windows (the host provides PK >= two rows)
-    int TI = 1;
-    if (TR == rh) { TI = a.PK / (TCp * rh); if (TI < 1) TI = 1; }
+    const ThinChunks tc = thin_wgrad_chunks(rw, rh, a.batch, a.PK, POOL);
+    const int TCp = tc.TCp, TR = tc.TR, TI = tc.TI, row_blocks = tc.row_blocks;
+    // this share's part of the stack's chunk list (image block, row block)
+    const int id0 = (int)((long long)split * tc.total / a.splits), id1 = (int)((long long)(split + 1) * tc.total / a.splits);
     const int PW = TCp + 2 * P, PH = TR + 2 * P;
     const int XCS = TI * PH * PW;                      // channel stride of the X patch
     float* Zl = lds;                                   // [TI*TR*TCp][ZP]
     float* Xl = lds + a.PK * ZP;                       // [Cin][TI][PH][PW]
-    const int row_blocks = (rh + TR - 1) / TR;
 
     // B operand of lane n = (ci, tap): fixed offset into the patch
     const int nn = l32 < a.Cin * KK ? l32 : 0;
@@ -299,9 +297,11 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
 
-    for (int n0 = nb0; n0 < nb1; n0 += TI) {
-        const int ni = (nb1 - n0) < TI ? (nb1 - n0) : TI;
-        for (int rb = 0; rb < row_blocks; ++rb) {
+    for (int id = id0; id < id1; ++id) {
+        {
+            const int ib = id / row_blocks, rb = id - ib * row_blocks;
+            const int n0 = ib * TI;
+            const int ni = (a.batch - n0) < TI ? (a.batch - n0) : TI;
             const int yb = y0 + rb * TR;
             const int nr = (y1 - yb + 1) < TR ? (y1 - yb + 1) : TR;
             __syncthreads();
@@ -440,19 +440,14 @@ struct ThinGeom { int PK; size_t lds; };
 ThinGeom thin_geom(const ConvArgs& c)
 {
     ThinGeom g;
-    g.PK = 256;
     const int P = c.K / 2;
-    int max_pos = 1;
-    // one padded row at least; behind a pool two, so that a chunk holds whole windows
-    for (int t = 0; t < c.M; ++t) { const int w = ((c.rect.x1[t] - c.rect.x0[t] + 2) & ~1) * (c.pooled ? 2 : 1); if (w > g.PK) g.PK = w; }
+    int wmax = 0, max_pos = 1;
+    for (int t = 0; t < c.M; ++t) wmax = std::max(wmax, (c.rect.x1[t] - c.rect.x0[t] + 2) & ~1);
+    g.PK = thin_wgrad_pk(wmax, c.pooled != 0);
     for (int i = 0; i < c.N; ++i)
         for (int j = 0; j < c.M; ++j) {
-            const int rw = c.rect.x1[j] - c.rect.x0[j] + 1, rh = c.rect.y1[i] - c.rect.y0[i] + 1;
-            const int TCp = (rw + 1) & ~1;
-            int TR = g.PK / TCp; if (TR < 1) TR = 1; if (TR > rh) TR = rh;
-            if (c.pooled && TR > 1) TR &= ~1;
-            int TI = 1; if (TR == rh) { TI = g.PK / (TCp * rh); if (TI < 1) TI = 1; }
-            const int pos = TI * (TR + 2 * P) * (TCp + 2 * P);
+            const ThinChunks tc = thin_wgrad_chunks(c.rect.x1[j] - c.rect.x0[j] + 1, c.rect.y1[i] - c.rect.y0[i] + 1, c.batch, g.PK, c.pooled != 0);
+            const int pos = tc.TI * (tc.TR + 2 * P) * (tc.TCp + 2 * P);
             if (pos > max_pos) max_pos = pos;
         }
     size_t words = (size_t)g.PK * 33 + (size_t)max_pos * c.Cin + 2;     // +2: the second pixel of the last pair
@@ -481,7 +476,7 @@ void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.rect;
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
     a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
-    a.splits = wgrad_batch_shares_thin(c.Cout, c.N * c.M, c.batch);
+    a.splits = c.wgrad_shares_thin;
     const ThinGeom g = thin_geom(c);
     a.PK = g.PK;
     dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
