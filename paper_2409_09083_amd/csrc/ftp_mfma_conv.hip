@@ -378,7 +378,11 @@ constexpr unsigned kBufRecords = 0x7FFFFFFFu;
 __host__ __device__ constexpr int conv_dl_stage_channels(int K, int /*BM*/) { return K == 1 ? 16 : 4; }
 __host__ __device__ constexpr int conv_dl_max_positions(int K, int BN) { return K == 1 ? 256 : (BN == 256 ? 512 : 256); }   // patch positions in LDS
 
-template <int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN>
+// POOL_IN (delta back-propagation through a fused pool): the patch lives at the convolution output, the delta at
+// pooled resolution; a patch position receives its window's delta only if it is the window's winner for that
+// channel.  The winner codes of the stage after next are loaded into registers one stage ahead, and a lane whose
+// position lost simply loads from an out-of-range offset (= 0).
+template <int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 __global__ void __launch_bounds__(256, 2)
 k_conv_mfma_dl(MfmaConvArgs a)
 {
@@ -424,10 +428,12 @@ k_conv_mfma_dl(MfmaConvArgs a)
     const View& sv = DELTA_IN ? a.din : a.in;
     const T* src = (const T*)sv.p + (long long)stack * sv.ss + (long long)g.n_a * sv.ns;
     unsigned xoff[MAXPOS];
+    int moff[MAXPOS];               // POOL_IN: element offset in the code map (channel 0), this position's place in its window in the top bits
+    const uint8_t* __restrict__ msk = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)g.n_a * a.mask.ns;
 #pragma unroll
     for (int j = 0; j < MAXPOS; ++j) {
         const int s = tid + j * 256;
-        xoff[j] = kOobOffset;
+        xoff[j] = kOobOffset; moff[j] = 0;
         if (s < npos) {
             const int pr = s / PW, c = s - pr * PW;
             int k = 0, lr = pr, ybase = g.y_a * S;
@@ -436,11 +442,29 @@ k_conv_mfma_dl(MfmaConvArgs a)
                 k = 1 + t / g.per_cnt; lr = t - (k - 1) * g.per_cnt; ybase = 0;
             }
             const int gy = y0 * S + ybase + lr - P, gx = g.ox0 * S - P + c;
-            if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc
-                && gy >= a.iy0[ti] && gy <= a.iy1[ti] && gx >= a.ix0[tj] && gx <= a.ix1[tj])
-                xoff[j] = 4u * (unsigned)(k * (int)sv.ns + (gy - sv.y0[ti]) * sv.pitch + (gx - sv.x0[tj]));
+            if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc) {
+                const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
+                // positions no valid output pixel of this stack reads may lie outside the view
+                if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
+                    xoff[j] = 4u * (unsigned)(k * (int)sv.ns + (sy - sv.y0[ti]) * sv.pitch + (sx - sv.x0[tj]));
+                    if (POOL_IN) moff[j] = (k * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]))
+                                           | ((((gy & 1) << 1) | (gx & 1)) << 29);
+                }
+            }
         }
     }
+    // winner codes of one stage, per position and channel
+    uint8_t codes[MAXPOS][kCK];
+    auto load_codes = [&](int c0) {
+        if (!POOL_IN) return;
+#pragma unroll
+        for (int j = 0; j < MAXPOS; ++j)
+#pragma unroll
+            for (int k = 0; k < kCK; ++k) {
+                const int ci = c0 + k < a.C ? c0 + k : a.C - 1;
+                codes[j][k] = msk[(moff[j] & 0x1FFFFFFF) + (long long)ci * a.mask.cs];
+            }
+    };
     // filter: a load instruction covers 64 consecutive floats of the slice; with BM >= 64 that is (part of) one
     // row, with BM = 32 two rows (two consecutive reduction channels)
     unsigned woff;
@@ -480,7 +504,8 @@ k_conv_mfma_dl(MfmaConvArgs a)
             if (blk * 64 < npos) {
 #pragma unroll
                 for (int k = 0; k < kCK; ++k) {
-                    const unsigned vo = c0 + k < a.C ? xoff[j] : kOobOffset;
+                    unsigned vo = c0 + k < a.C ? xoff[j] : kOobOffset;
+                    if (POOL_IN && ((codes[j][k] >> 1) & 3) != ((unsigned)moff[j] >> 29)) vo = kOobOffset;
                     const unsigned so = 4u * (unsigned)((c0 + k) * (int)sv.cs);
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_LDS_PTR(Xl + k * CS + blk * 64), 4, vo, so, 0, 0);
                 }
@@ -516,16 +541,18 @@ k_conv_mfma_dl(MfmaConvArgs a)
     };
 
     const int nst = (a.C + kCK - 1) / kCK;
-    issue(bufA, 0);
+    load_codes(0);
+    issue(bufA, 0);                                     // (waits for the codes it selects by)
+    load_codes(kCK);
     for (int st = 0; st < nst; st += 2) {
         __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's share of the stage has landed
         __syncthreads();                               // ... and everybody's; the other buffer is free again
-        if (st + 1 < nst) issue(bufB, (st + 1) * kCK);
+        if (st + 1 < nst) { issue(bufB, (st + 1) * kCK); load_codes((st + 2) * kCK); }
         multiply(bufA);
         if (st + 1 < nst) {
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
-            if (st + 2 < nst) issue(bufA, (st + 2) * kCK);
+            if (st + 2 < nst) { issue(bufA, (st + 2) * kCK); load_codes((st + 3) * kCK); }
             multiply(bufB);
         }
     }
@@ -588,15 +615,15 @@ bool offsets_fit_32bit(const MfmaConvArgs& a, const View& v, int max_img)
 // Workgroup shapes of the direct-load kernel: output channels x pixels, and the workgroups of each that share a CU.
 struct DlShape { int BM, BN, per_cu; };
 
-template <int K, bool POOL_OUT, bool DELTA_IN>
+template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 {
     static char label[6][64];
     const int v = (sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1);
-    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%d, %d, %d, %d, %s, %s>", K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN,
-                  POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false");
+    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%d, %d, %d, %d, %s, %s, %s>", K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN,
+                  POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false", POOL_IN ? "true" : "false");
     g_kernel_label = label[v];
-#define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<K, WM, MT, BN, POOL_OUT, DELTA_IN>), grid, dim3(256), 0, s, a)
+#define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN>), grid, dim3(256), 0, s, a)
     if (sh.BN == 256) { if (sh.BM == 128) FTP_DL(2, 2, 256); else if (sh.BM == 64) FTP_DL(1, 2, 256); else FTP_DL(1, 1, 256); }
     else              { if (sh.BM == 128) FTP_DL(2, 2, 128); else if (sh.BM == 64) FTP_DL(1, 2, 128); else FTP_DL(1, 1, 128); }
 #undef FTP_DL
@@ -649,13 +676,15 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_r = tc.tiles_r; a.cap = tc.cap; a.cs = tc.cs;
     // output channels per workgroup: 128 (2x2 wavefronts of 64 x 128 pixels), 64 (1x4 of 64 x 64) or 32 (1x4 of 32 x 64)
     const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
-    // fp32 maps whose patch needs no routing through pool winners take the direct-load kernel
-    if (sizeof(T) == 4 && !POOL_IN && direct_loads_enabled()) {
+    // fp32 maps take the direct-load kernel
+    if (sizeof(T) == 4 && direct_loads_enabled()) {
         TileChoice td;
         const DlShape sh = choose_dl_shape<K, POOL_OUT>(a, c, &td);
-        if (sh.BM && offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img)) {
+        // (the kernel keeps code-map offsets in 29 bits)
+        const bool codes_fit = !(POOL_IN && DELTA_IN) || (double)td.max_img * (double)a.mask.ns < 5.0e8;
+        if (sh.BM && codes_fit && offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img)) {
             a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = (td.cs + 63) & ~63;
-            launch_dl<K, POOL_OUT && !DELTA_IN, DELTA_IN>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
+            launch_dl<K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
             return 0;
         }
     }
