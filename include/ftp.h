@@ -161,7 +161,7 @@ typedef enum {
 typedef struct {
     int32_t pass, layer, launches, reserved;   /* layer = primitive layer index, -1 for the reduction */
     double total_ms, flops_per_launch, bytes_per_launch;
-    char kernel[64];                           /* name of the kernel the launches ran */
+    char kernel[96];                           /* name of the kernel the launches ran */
 } ftp_kernel_time;
 int ftp_profile(ftp_plan_t* plan, int32_t enable);
 int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, int32_t* count);

@@ -26,7 +26,7 @@ class ftp_layer(ctypes.Structure):
 class ftp_kernel_time(ctypes.Structure):
     _fields_ = [("pass_", ctypes.c_int32), ("layer", ctypes.c_int32), ("launches", ctypes.c_int32),
                 ("reserved", ctypes.c_int32), ("total_ms", ctypes.c_double), ("flops_per_launch", ctypes.c_double),
-                ("bytes_per_launch", ctypes.c_double), ("kernel", ctypes.c_char * 64)]
+                ("bytes_per_launch", ctypes.c_double), ("kernel", ctypes.c_char * 96)]
 
 
 PASS_NAMES = {0: "conv_fwd", 1: "conv_bwd_data", 2: "wgrad", 3: "reduce", 4: "pool_fwd", 5: "pool_bwd", 6: "scale_dy"}

@@ -2,13 +2,12 @@
 // delta back-propagation (which is the same convolution with the 180-degree rotated, transposed
 // filter applied to dZ).  D[m][pixel] = sum_k Wt[k][m] * patch[k][pixel], k = (tap, channel).
 //
-// One workgroup (4 wavefronts) produces BM = 32/64/128 output channels for a tile of up to 256 pixels of
-// one stack (pooled layers: 64 windows of 4 pixels).  A tile is a run of consecutive rows of the
+// One workgroup (4 wavefronts) produces BM = 32/64/128 output channels for a tile of up to 128 or 256 pixels of
+// one stack (pooled layers: 32 or 64 windows of 4 pixels).  A tile is a run of consecutive rows of the
 // stack's rectangle, counted through the batch (row index R = image * rows + row), times a block of
 // columns, so that small rectangles of several images fill one tile and medium ones leave no ragged
 // last tile per image.  The input patch (tile rows + filter halo per image, zero outside the real map)
-// and the filter slice of a few channels x K*K taps are staged in LDS; v_mfma_f32_32x32x2_f32 reads both
-// from there.  The next stage is prefetched into registers while the matrix cores work.
+// and the filter slice of a few channels x K*K taps sit in LDS; v_mfma_f32_32x32x2_f32 reads both from there.
 // MFMA lane layout (64 lanes): A[m = lane%32][k = lane/32], B[k = lane/32][n = lane%32],
 // D[m = 8*(i/4) + 4*(lane/32) + i%4][n = lane%32] for accumulator register i of 16.
 #include "ftp_device.h"
@@ -21,7 +20,6 @@ namespace ftp {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kBN = 256;        // pixels per workgroup tile
 
 // Filter relayout: OIHW -> [tap][reduction channel][output channel], so that a stage's slice is a set of
 // contiguous rows.  fwd: Wt[t][ci][co] = W[co][ci][t].  bwd: Wt[t][co][ci] = W[co][ci][K*K-1-t] (rotated).
@@ -39,11 +37,6 @@ k_prep_filter(const T* __restrict__ w, float* __restrict__ wt_fwd, float* __rest
     if (wt_fwd) wt_fwd[((long long)t * Cin + ci) * Cout + co] = v;
     if (wt_bwd) wt_bwd[((long long)(KK - 1 - t) * Cout + co) * Cin + ci] = v;
 }
-
-// Reduction channels staged per step: fewer for the 128-channel tile, whose accumulators leave fewer registers
-// for the prefetched next stage.
-__host__ __device__ constexpr int conv_stage_channels(int K, int BM) { return K == 1 ? (BM == 128 ? 16 : 32) : (BM == 128 ? 4 : 8); }
-__host__ __device__ constexpr int conv_max_positions(int K) { return K == 1 ? 256 : 512; }   // patch positions held in registers
 
 // Geometry of one tile: rows R0 .. R0+nrows-1 of the batch-flattened row index, columns ox0 .. ox0+TC-1.
 struct TileGeom {
@@ -192,185 +185,17 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
     }
 }
 
-// WAVES_M x WAVES_N wavefronts; each computes MT x NT tiles of 32 channels x 32 pixels.
-template <typename T, int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
-__global__ void __launch_bounds__(256, 2)
-k_conv_mfma(MfmaConvArgs a)
-{
-    constexpr int kCK = conv_stage_channels(K, 32 * MT * WAVES_M);   // reduction channels per LDS stage
-    constexpr int WAVES_N = 4 / WAVES_M;
-    constexpr int NT = kBN / 32 / WAVES_N;           // 32-pixel MFMA tiles per wavefront
-    constexpr int BM = 32 * MT * WAVES_M;
-    constexpr int KK = K * K, P = K / 2;
-    constexpr int S = POOL_OUT ? 2 : 1;
-
-    extern __shared__ float lds[];
-    float* Wl = lds;                                   // [KK][kCK][BM]
-    float* Xl = lds + KK * kCK * BM;                   // [kCK][patch positions]
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: keeps what depends on it scalar
-    const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
-    const int hi = lane >> 5, l32 = lane & 31;
-    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
-    const int x0 = a.rect.x0[tj], x1 = a.rect.x1[tj], y0 = a.rect.y0[ti], y1 = a.rect.y1[ti];
-    const TileGeom g = tile_geom<S, P>(a, x0, x1, y0, y1, blockIdx.x);
-    if (g.empty) return;                              // this stack has fewer tiles than the largest one
-    const int m0 = blockIdx.y * BM;
-    const int PW = g.PW, CS = a.cs;
-
-    // ---- LDS offset of each lane's pixel, per 32-pixel tile ---------------------------------------------
-    int baseB[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int q = (wave_n * NT + t) * 32 + l32;
-        const TilePix tp = tile_pix<S, P>(g, POOL_OUT ? (q >> 2) : q, x1);
-        const int pos = POOL_OUT ? (q & 3) : 0;
-        baseB[t] = (tp.valid ? (tp.prow + (pos >> 1)) * PW + tp.xl * S + (pos & 1) : 0) + hi * CS;
-    }
-    const int baseA = hi * BM + wave_m * (32 * MT) + l32;
-
-    // ---- per-thread patch positions (fixed over the channel loop): 32-bit offsets from per-workgroup bases ------
-    constexpr int MAXPOS = conv_max_positions(K) / 256;
-    const int npos = g.npos;
-    const View& sv = DELTA_IN ? a.din : a.in;          // source of the patch values
-    const T* __restrict__ src = (const T*)sv.p + (long long)stack * sv.ss + (long long)g.n_a * sv.ns;
-    const uint8_t* __restrict__ msk = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)g.n_a * a.mask.ns;
-    int goff[MAXPOS];               // source element offset (channel 0); -1: zero padding / outside the view
-    int moff[MAXPOS];               // DELTA_IN: offset in the decision-code map, winner code in the top bits
-#pragma unroll
-    for (int j = 0; j < MAXPOS; ++j) {
-        const int s = tid + j * 256;
-        goff[j] = -1; moff[j] = 0;
-        if (s < npos) {
-            const int pr = s / PW, c = s - pr * PW;
-            int k = 0, lr = pr, ybase = g.y_a * S;
-            if (pr >= g.first_cnt) {
-                const int t = pr - g.first_cnt;
-                k = 1 + t / g.per_cnt; lr = t - (k - 1) * g.per_cnt; ybase = 0;
-            }
-            const int gy = y0 * S + ybase + lr - P, gx = g.ox0 * S - P + c;   // coordinates at the convolution input
-            if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc) {
-                const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
-                // positions no valid output pixel of this stack reads may lie outside the view
-                if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
-                    goff[j] = k * (int)sv.ns + (sy - sv.y0[ti]) * sv.pitch + (sx - sv.x0[tj]);
-                    if (DELTA_IN) {
-                        moff[j] = k * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]);
-                        if (POOL_IN) moff[j] |= (((gy & 1) << 1) | (gx & 1)) << 29;
-                    }
-                }
-            }
-        }
-    }
-
-    v16f acc[MT][NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mt][t][i] = 0.0f;
-
-    const float* __restrict__ wt = a.wt;
-    // Software pipeline: the next stage's filter slice and patch are fetched into registers while the matrix
-    // cores work on the current stage, and written to LDS between two barriers.
-    constexpr int WREG = (KK * kCK * (BM / 4) + 255) / 256;
-    float4 wreg[WREG];
-    float greg[MAXPOS][kCK];
-    uint8_t mreg[MAXPOS][kCK];
-    // All loads are unconditional (addresses clamped into range) so that none of them has to be waited for
-    // before the next one is issued; what they should not have read is zeroed when it is written to LDS.
-    auto prefetch = [&](int c0) {
-#pragma unroll
-        for (int u = 0; u < WREG; ++u) {
-            int idx = tid + u * 256;
-            if (idx >= KK * kCK * (BM / 4)) idx = KK * kCK * (BM / 4) - 1;
-            const int row = idx / (BM / 4), c4 = idx - row * (BM / 4);
-            const int tap = row / kCK, cl = row - tap * kCK;
-            int ci = c0 + cl, m = m0 + c4 * 4;
-            if (ci >= a.C) ci = a.C - 1;
-            if (m >= a.Mtot) m = a.Mtot - 4;
-            wreg[u] = *(const float4*)(wt + ((long long)tap * a.C + ci) * a.Mtot + m);
-        }
-#pragma unroll
-        for (int j = 0; j < MAXPOS; ++j) {
-            const int go = goff[j] >= 0 ? goff[j] : 0, mo = moff[j] & 0x1FFFFFFF;
-#pragma unroll
-            for (int k = 0; k < kCK; ++k) {
-                const int ci = c0 + k < a.C ? c0 + k : a.C - 1;
-                greg[j][k] = ld(src + go + (long long)ci * sv.cs);
-                if (DELTA_IN && POOL_IN) mreg[j][k] = msk[mo + (long long)ci * a.mask.cs];
-            }
-        }
-    };
-    auto commit = [&](int c0) {
-#pragma unroll
-        for (int u = 0; u < WREG; ++u) {
-            const int idx = tid + u * 256;
-            if (idx < KK * kCK * (BM / 4)) {
-                const int row = idx / (BM / 4), c4 = idx - row * (BM / 4);
-                const int cl = row % kCK;
-                const bool ok = c0 + cl < a.C && m0 + c4 * 4 < a.Mtot;
-                *(float4*)(Wl + idx * 4) = ok ? wreg[u] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < MAXPOS; ++j) {
-            const int s = tid + j * 256;
-            if (s < npos) {
-                const bool inside = goff[j] >= 0;
-                const unsigned code = (unsigned)moff[j] >> 29;
-#pragma unroll
-                for (int k = 0; k < kCK; ++k) {
-                    float v = greg[j][k];
-                    // the delta maps hold dLoss/dZ; through a pool only the window's winner receives it
-                    if (DELTA_IN && POOL_IN && ((mreg[j][k] >> 1) & 3) != code) v = 0.0f;
-                    if (!inside || c0 + k >= a.C) v = 0.0f;
-                    Xl[k * CS + s] = v;
-                }
-            }
-        }
-    };
-    prefetch(0);
-    for (int c0 = 0; c0 < a.C; c0 += kCK) {
-        __syncthreads();
-        commit(c0);
-        __syncthreads();
-        if (c0 + kCK < a.C) prefetch(c0 + kCK);
-        // one step = 2 reduction channels of one tap; the operands of step j+1 are read from LDS before the
-        // matrix-core instructions of step j are issued, so the LDS latency hides behind them
-        constexpr int NSTEP = KK * (kCK / 2);
-        float av[2][MT], bv[2][NT];
-        auto load_step = [&](int j, int buf) {
-            const int tap = j / (kCK / 2), i = j - tap * (kCK / 2);
-            const int toff = (tap / K) * PW + (tap % K);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) av[buf][mt] = Wl[(tap * kCK + 2 * i) * BM + baseA + 32 * mt];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) bv[buf][t] = Xl[baseB[t] + 2 * i * CS + toff];
-        };
-        load_step(0, 0);
-#pragma unroll
-        for (int j = 0; j < NSTEP; ++j) {
-            if (j + 1 < NSTEP) load_step(j + 1, (j + 1) & 1);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j & 1][mt], bv[j & 1][t], acc[mt][t], 0, 0, 0);
-        }
-    }
-
-    conv_epilogue<T, K, WAVES_M, MT, POOL_OUT, DELTA_IN>(a, g, acc, lds, m0, x0, x1, y0, stack, ti, tj);
-}
-
-// ---- variant with direct HBM -> LDS loads (fp32 maps) ---------------------------------------------------------
-// The same tiles, multiply loop and epilogue, but a stage's patch and filter slice travel with
-// buffer_load_dword ... lds: every lane's dword lands in LDS at (wave-uniform base + 4 * lane), no registers and
-// no LDS-write instructions in between, and offsets beyond the buffer's records read as zero, which provides
-// the zero padding.  Two LDS buffers alternate: stage i+1 is in flight while the matrix cores work on stage i.
+// ---- the kernel ----------------------------------------------------------------------------------------------
+// WAVES_M x WAVES_N wavefronts; each computes MT x NT tiles of 32 channels x 32 pixels.  A stage's patch and
+// filter slice travel with buffer_load ... lds: every lane's element lands in LDS at (wave-uniform base +
+// 4 * lane), no registers and no LDS-write instructions in between, and offsets beyond the buffer's records read
+// as zero, which provides the zero padding.  16-bit (bfloat) elements arrive zero-extended in a dword and are
+// shifted into place when the multiply loop reads them.  Two LDS buffers alternate: stage i+1 is in flight while
+// the matrix cores work on stage i.
 #define FTP_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+// LDS dword as loaded -> value: fp32 as is, a zero-extended bfloat shifted into the high half
+__device__ __forceinline__ float widen(float v, const float*) { return v; }
+__device__ __forceinline__ float widen(float v, const bf16_t*) { return __uint_as_float(__float_as_uint(v) << 16); }
 constexpr unsigned kOobOffset = 0x80000000u;          // beyond the records of every buffer resource below
 constexpr unsigned kBufRecords = 0x7FFFFFFFu;
 // Reduction channels per stage: the same for every workgroup shape, so that the summation order, and with it every
@@ -382,11 +207,11 @@ __host__ __device__ constexpr int conv_dl_max_positions(int K, int BN) { return 
 // pooled resolution; a patch position receives its window's delta only if it is the window's winner for that
 // channel.  The winner codes of the stage after next are loaded into registers one stage ahead, and a lane whose
 // position lost simply loads from an out-of-range offset (= 0).
-template <int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+template <typename T, int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 __global__ void __launch_bounds__(256, 2)
 k_conv_mfma_dl(MfmaConvArgs a)
 {
-    typedef float T;
+    constexpr unsigned ES = sizeof(T);                 // bytes per map element
     constexpr int WAVES_N = 4 / WAVES_M;
     constexpr int NT = BN / 32 / WAVES_N;
     constexpr int BM = 32 * MT * WAVES_M;
@@ -446,7 +271,7 @@ k_conv_mfma_dl(MfmaConvArgs a)
                 const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
                 // positions no valid output pixel of this stack reads may lie outside the view
                 if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
-                    xoff[j] = 4u * (unsigned)(k * (int)sv.ns + (sy - sv.y0[ti]) * sv.pitch + (sx - sv.x0[tj]));
+                    xoff[j] = ES * (unsigned)(k * (int)sv.ns + (sy - sv.y0[ti]) * sv.pitch + (sx - sv.x0[tj]));
                     if (POOL_IN) moff[j] = (k * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]))
                                            | ((((gy & 1) << 1) | (gx & 1)) << 29);
                 }
@@ -506,8 +331,10 @@ k_conv_mfma_dl(MfmaConvArgs a)
                 for (int k = 0; k < kCK; ++k) {
                     unsigned vo = c0 + k < a.C ? xoff[j] : kOobOffset;
                     if (POOL_IN && ((codes[j][k] >> 1) & 3) != ((unsigned)moff[j] >> 29)) vo = kOobOffset;
-                    const unsigned so = 4u * (unsigned)((c0 + k) * (int)sv.cs);
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_LDS_PTR(Xl + k * CS + blk * 64), 4, vo, so, 0, 0);
+                    const unsigned so = ES * (unsigned)((c0 + k) * (int)sv.cs);
+                    // (the element size has to be a literal)
+                    if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_LDS_PTR(Xl + k * CS + blk * 64), 4, vo, so, 0, 0);
+                    else                          __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_LDS_PTR(Xl + k * CS + blk * 64), 2, vo, so, 0, 0);
                 }
             }
         }
@@ -526,7 +353,7 @@ k_conv_mfma_dl(MfmaConvArgs a)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) av[b][mt] = Wl[(tap * kCK + 2 * i) * BM + baseA + 32 * mt];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) bv[b][t] = Xl[baseB[t] + 2 * i * CS + toff];
+            for (int t = 0; t < NT; ++t) bv[b][t] = widen(Xl[baseB[t] + 2 * i * CS + toff], (const T*)nullptr);
         };
         load_step(0, 0);
 #pragma unroll
@@ -598,32 +425,25 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
     return c;
 }
 
-// FTP_CONV_LOADS=staged keeps the register-staged kernel for fp32 maps too (for comparisons).
-bool direct_loads_enabled()
-{
-    static const bool on = [] { const char* e = getenv("FTP_CONV_LOADS"); return !(e && std::strcmp(e, "staged") == 0); }();
-    return on;
-}
-
 // Largest byte offset a workgroup forms from its base pointer: the images a tile can span plus all channels.
 bool offsets_fit_32bit(const MfmaConvArgs& a, const View& v, int max_img)
 {
-    const double bytes = 4.0 * ((double)max_img * (double)v.ns + (double)a.C * (double)v.cs);
+    const double bytes = 4.0 * ((double)max_img * (double)v.ns + (double)a.C * (double)v.cs);      // (fp32 element size as the bound)
     return bytes < 2.0e9 && 4.0 * 9.0 * (double)a.C * (double)a.Mtot < 2.0e9;
 }
 
 // Workgroup shapes of the direct-load kernel: output channels x pixels, and the workgroups of each that share a CU.
 struct DlShape { int BM, BN, per_cu; };
 
-template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 {
-    static char label[6][64];
+    static char label[6][80];
     const int v = (sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1);
-    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%d, %d, %d, %d, %s, %s, %s>", K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN,
-                  POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false", POOL_IN ? "true" : "false");
+    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%s, %d, %d, %d, %d, %s, %s, %s>", sizeof(T) == 4 ? "float" : "unsigned short",
+                  K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN, POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false", POOL_IN ? "true" : "false");
     g_kernel_label = label[v];
-#define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN>), grid, dim3(256), 0, s, a)
+#define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN>), grid, dim3(256), 0, s, a)
     if (sh.BN == 256) { if (sh.BM == 128) FTP_DL(2, 2, 256); else if (sh.BM == 64) FTP_DL(1, 2, 256); else FTP_DL(1, 1, 256); }
     else              { if (sh.BM == 128) FTP_DL(2, 2, 128); else if (sh.BM == 64) FTP_DL(1, 2, 128); else FTP_DL(1, 1, 128); }
 #undef FTP_DL
@@ -667,38 +487,19 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc
     return best;
 }
 
+// Returns non-zero if the layer's geometry does not fit the kernel (offsets beyond 32 bits, a row of some stack
+// wider than the patch buffer); the caller then uses a direct kernel.
 template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
 int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
 {
-    const int KK = K * K;
-    const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? kBN / 4 : kBN, POOL_OUT ? 2 : 1, K / 2, conv_max_positions(K));
-    if (tc.cs > conv_max_positions(K)) return 1;       // a single row of some stack does not fit the staging registers
-    a.TC = tc.TC; a.tiles_x = tc.tiles_x; a.tiles_r = tc.tiles_r; a.cap = tc.cap; a.cs = tc.cs;
-    // output channels per workgroup: 128 (2x2 wavefronts of 64 x 128 pixels), 64 (1x4 of 64 x 64) or 32 (1x4 of 32 x 64)
-    const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
-    // fp32 maps take the direct-load kernel
-    if (sizeof(T) == 4 && direct_loads_enabled()) {
-        TileChoice td;
-        const DlShape sh = choose_dl_shape<K, POOL_OUT>(a, c, &td);
-        // (the kernel keeps code-map offsets in 29 bits)
-        const bool codes_fit = !(POOL_IN && DELTA_IN) || (double)td.max_img * (double)a.mask.ns < 5.0e8;
-        if (sh.BM && codes_fit && offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img)) {
-            a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = (td.cs + 63) & ~63;
-            launch_dl<K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
-            return 0;
-        }
-    }
-    const int kCK = conv_stage_channels(K, BM);
-    const size_t lds = (size_t)(KK * kCK * BM + kCK * a.cs) * sizeof(float);
-    dim3 grid(a.tiles_x * a.tiles_r, (a.Mtot + BM - 1) / BM, c.N * c.M), block(256);
-    static char label[3][64];
-    const int v = BM == 128 ? 0 : BM == 64 ? 1 : 2;
-    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma<%s, %d, %d, %d, %s, %s, %s>", sizeof(T) == 4 ? "float" : "unsigned short", K, BM == 128 ? 2 : 1, BM == 32 ? 1 : 2,
-                  POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false", POOL_IN ? "true" : "false");
-    g_kernel_label = label[v];
-    if (BM == 128) hipLaunchKernelGGL((k_conv_mfma<T, K, 2, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
-    else if (BM == 64) hipLaunchKernelGGL((k_conv_mfma<T, K, 1, 2, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((k_conv_mfma<T, K, 1, 1, POOL_OUT, DELTA_IN, POOL_IN>), grid, block, lds, s, a);
+    TileChoice td;
+    const DlShape sh = choose_dl_shape<K, POOL_OUT>(a, c, &td);
+    if (!sh.BM) return 1;
+    // (the kernel keeps code-map offsets in 29 bits)
+    if (POOL_IN && DELTA_IN && (double)td.max_img * (double)a.mask.ns >= 5.0e8) return 1;
+    if (!offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img)) return 1;
+    a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = (td.cs + 63) & ~63;
+    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
     return 0;
 }
 
