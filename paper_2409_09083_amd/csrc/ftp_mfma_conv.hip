@@ -359,6 +359,7 @@ k_conv_mfma_dl(MfmaConvArgs a)
 #pragma unroll
         for (int j = 0; j < NSTEP; ++j) {
             if (j + 1 < NSTEP) load_step(j + 1, (j + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);         // keep these reads ahead of the matrix-core instructions below
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
