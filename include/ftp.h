@@ -111,12 +111,12 @@ int ftp_plan_work(const ftp_plan_t* plan, double* useful_macs, double* executed_
  * FTP_BUF_DELTA holds dLoss/dZ: where the boundary is the output of a convolution (with or without its
  * fused pool) the delta is dLoss/dY times the leaky-ReLU derivative there (Sec. 4.1, delta gradients);
  * for boundary L that is a scaled copy of the caller's dy kept in the workspace.
- * FTP_BUF_MASK is the decision code of the forward pass, one byte per element of a whole map,
- * written by the owning stack: bit 0 = activation > 0, bits 1-2 = index 2*dy+dx of the first
- * maximum of the 2x2 window (pooled boundaries only); back-propagation reads the winners from it.
- * FTP_BUF_SIGN (outputs of convolutions only) holds the same bit 0 packed for back-propagation:
- * whole map of 32-bit words [image][ceil(C/32)][H][W], bit c%32 of word c/32 = activation of
- * channel c > 0; out[5] is the number of words per pixel. */
+ * FTP_BUF_MASK (boundaries produced by a pool, fused or not) is the decision code of the forward
+ * pass, one byte per element of a whole map, written by the owning stack: bit 0 = activation > 0,
+ * bits 1-2 = index 2*dy+dx of the first maximum of the 2x2 window; back-propagation reads the
+ * winners from it.  FTP_BUF_SIGN (outputs of convolutions, with or without fused pool) holds the
+ * activation signs packed for back-propagation: whole map of 32-bit words [image][ceil(C/32)][H][W],
+ * bit c%32 of word c/32 = activation of channel c > 0; out[5] is the number of words per pixel. */
 typedef enum { FTP_BUF_ACT = 0, FTP_BUF_MASK = 1, FTP_BUF_DELTA = 2, FTP_BUF_SIGN = 3 } ftp_buf_kind;
 int ftp_plan_buffer(const ftp_plan_t* plan, int32_t boundary, ftp_buf_kind which, int64_t out[8]);
 

@@ -94,7 +94,7 @@ k_conv_fwd_direct(View in, View out, View mask, View osign, RectTab rt, RectTab 
             }
         }
         st(at<T>(out, stack, ti, tj, n, co, oy, ox), best);
-        if (owned) *at<uint8_t>(mask, stack, ti, tj, n, co, oy, ox) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
+        if (POOL && owned) *at<uint8_t>(mask, stack, ti, tj, n, co, oy, ox) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
         signs |= (best > 0.0f ? 1u : 0u) << j;
     }
     // these 8 channels are byte (co0 / 8) % 4 of their sign word

@@ -152,7 +152,8 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
         if (POOL_OUT) pvalid = pvalid && (lane & 3) == 0;       // the window's first lane stores
         const bool powned = pvalid && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
         T* __restrict__ optr = at<T>(a.out, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
-        uint8_t* __restrict__ mptr = at<uint8_t>(a.mask, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
+        // (code bytes exist only behind a pool)
+        uint8_t* __restrict__ mptr = POOL_OUT ? at<uint8_t>(a.mask, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0) : nullptr;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             uint32_t signs = 0;                                 // this lane's 16 channels of the block's sign word
@@ -172,7 +173,7 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
                 }
                 if (pvalid && m < a.Mtot) {
                     st(optr + (long long)m * a.out.cs, v);
-                    if (powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
+                    if (POOL_OUT && powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
                     signs |= (v > 0.0f ? 1u : 0u) << (8 * (i >> 2) + 4 * hi + (i & 3));
                 }
             }

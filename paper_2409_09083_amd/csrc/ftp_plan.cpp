@@ -190,8 +190,11 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
                 BufRef a, w, d;
                 a.channels = w.channels = d.channels = p.C[b];
                 const size_t map_elems = (size_t)batch * p.C[b] * p.H[b] * p.W[b];
-                // decision codes: one byte per element of the whole map, written by the owners
-                w.kind = BUF_WS; w.slot_w = p.W[b]; w.slot_h = p.H[b]; w.bytes = map_elems; w.offset = alloc(w.bytes);
+                // decision codes (pool winner + sign): one byte per element of the whole map, written by the owners;
+                // kept only where a pool produced the boundary - elsewhere the packed sign map below says it all
+                if (u.pooled || u.kind == UNIT_POOL) {
+                    w.kind = BUF_WS; w.slot_w = p.W[b]; w.slot_h = p.H[b]; w.bytes = map_elems; w.offset = alloc(w.bytes);
+                }
                 if (is_group_edge[b]) {
                     a.slot_w = d.slot_w = p.W[b];
                     a.slot_h = d.slot_h = p.H[b];

@@ -158,17 +158,17 @@ def check_forward_state(s, cfg, acts, args, tol_a):
             for (r, slot) in s.get_slots(b):
                 ref = acts[b][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]
                 assert np.max(np.abs(slot - ref)) <= tol_a * scale, ("held rectangle", b, r)
-        gm = s.get_boundary(b, F.FTP_BUF_MASK)
-        if gm is None:
-            continue
-        bad = (gm & 1) != (acts[b] > 0)
-        if bad.any():
-            assert float(np.abs(acts[b][bad]).max()) <= tol_a * scale, ("activation signs", b, int(bad.sum()))
-        gs = s.get_boundary(b, F.FTP_BUF_SIGN)
+        gm = s.get_boundary(b, F.FTP_BUF_MASK)       # behind pools only
+        gs = s.get_boundary(b, F.FTP_BUF_SIGN)       # behind convolutions only
         if gs is not None:
-            # the packed signs back-propagation reads are the same decisions as bit 0 of the codes
-            assert np.array_equal(unpack_signs(gs, acts[b].shape[1]), (gm & 1).astype(bool)), ("packed signs", b)
-        if args[b - 1] is not None:
+            sg = unpack_signs(gs, acts[b].shape[1])
+            bad = sg != (acts[b] > 0)
+            if bad.any():
+                assert float(np.abs(acts[b][bad]).max()) <= tol_a * scale, ("activation signs", b, int(bad.sum()))
+            if gm is not None:
+                # bit 0 of the code bytes is the same decision
+                assert np.array_equal(sg, (gm & 1).astype(bool)), ("packed signs", b)
+        if gm is not None and args[b - 1] is not None:
             bad = ((gm >> 1) & 3) != args[b - 1]
             if bad.any():
                 gap = pool_gap(acts[b - 1])
@@ -179,12 +179,11 @@ def decisions_agree(s, cfg, acts, args):
     """True if every leaky sign and pool winner the GPU's forward pass recorded equals the oracle's."""
     import paper_2409_09083_amd as F
     for b in range(1, len(cfg.layers) + 1):
+        gs = s.get_boundary(b, F.FTP_BUF_SIGN)
+        if gs is not None and (unpack_signs(gs, acts[b].shape[1]) != (acts[b] > 0)).any():
+            return False
         gm = s.get_boundary(b, F.FTP_BUF_MASK)
-        if gm is None:
-            continue
-        want = oracle_mask(acts, args, b)
-        keep = 0x7 if args[b - 1] is not None else 0x1
-        if ((gm & keep) != (want & keep)).any():
+        if gm is not None and args[b - 1] is not None and (((gm >> 1) & 3) != args[b - 1]).any():
             return False
     return True
 
