@@ -155,7 +155,8 @@ def main():
         "phases_ms_per_step": phases,
     }
     if not args.no_cpu_baseline:
-        n_img = args.cpu_images or (1 if cfg.name.startswith(("cfg4", "cfg5")) else cfg.batch)
+        # about 10-20 s of oracle time: 12 images of the large workloads (the oracle is linear in the batch)
+        n_img = args.cpu_images or (12 if cfg.name.startswith(("cfg4", "cfg5")) else cfg.batch)
         out["cpu_baseline"] = cpu_baseline(cfg, n_img)
     s.close()
     print(json.dumps(out))
