@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--config", default="cfg4", choices=["tiny", "cfg2_perblock", "cfg2_fused", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--group-size", type=int, default=4, help="layers per group (cfg5 sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--with-update", action="store_true",
+                    help="close every step with the fused gradient sum + filter update (lr 0) instead of the plain gradient sum")
     ap.add_argument("--per-kernel", action="store_true", help="print the per-kernel timing table to stderr")
     ap.add_argument("--cpu-images", type=int, default=0, help="images for the oracle timing (0 = automatic)")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -88,13 +90,15 @@ def main():
         probe[1].copy_(probe[0])            # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del probe
+    # lr = 0 keeps the weights (and with them every step's work) unchanged while the update kernels run in full
+    one_step = (lambda: s.train_step(0.0)) if args.with_update else s.step
     for _ in range(args.warmup):
-        s.step()
+        one_step()
     torch.cuda.synchronize()
     F.ftp_profile(s.plan, True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        s.step()
+        one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     F.ftp_profile(s.plan, False)

@@ -145,6 +145,18 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x,
  *   wgrad_partials device fp32 [N*M][n_params];  wgrad device fp32 [n_params] */
 int ftp_reduce_wgrad(const ftp_plan_t* plan, const float* wgrad_partials, float* wgrad, void* stream);
 
+/* Gradient sum fused with the filter update that closes a training cycle (Sec. 4.1: the final
+ * gradient "can then be used to update" the filters, once per batch for all layers).  The paper
+ * names no optimiser; this is the plain gradient-descent step
+ *   W_l[i] <- W_l[i] - lr * sum over stacks of wgrad_partials[stack][offset_l + i]
+ * (biases likewise), with the same summation order as ftp_reduce_wgrad.  Arithmetic in fp32; with
+ * FTP_BF16 the updated value is rounded to the storage type.
+ *   weights, biases  host arrays of n_layers device pointers as for ftp_forward, updated in place
+ *                    (biases may be null if no layer has one)
+ *   wgrad            device fp32 [n_params] or null: also receives the summed gradient */
+int ftp_sgd_step(const ftp_plan_t* plan, const float* wgrad_partials, void* const* weights, void* const* biases,
+                 float lr, float* wgrad, void* stream);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch of the three passes is
  * bracketed by two HIP events on the caller's stream (host objects, created on first use and
  * owned by the plan).  ftp_profile(plan, 1) clears earlier records and starts collecting,
@@ -156,7 +168,8 @@ int ftp_reduce_wgrad(const ftp_plan_t* plan, const float* wgrad_partials, float*
 typedef enum {
     FTP_PASS_CONV_FWD = 0, FTP_PASS_CONV_BWD_DATA = 1, FTP_PASS_WGRAD = 2, FTP_PASS_REDUCE = 3,
     FTP_PASS_POOL_FWD = 4, FTP_PASS_POOL_BWD = 5,
-    FTP_PASS_SCALE_DY = 6          /* dy times the last activation's derivative; layer = last convolution */
+    FTP_PASS_SCALE_DY = 6,         /* dy times the last activation's derivative; layer = last convolution */
+    FTP_PASS_UPDATE = 7            /* ftp_sgd_step; layer = the convolution updated */
 } ftp_pass;
 typedef struct {
     int32_t pass, layer, launches, reserved;   /* layer = primitive layer index, -1 for the reduction */

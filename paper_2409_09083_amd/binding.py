@@ -29,7 +29,7 @@ class ftp_kernel_time(ctypes.Structure):
                 ("bytes_per_launch", ctypes.c_double), ("kernel", ctypes.c_char * 96)]
 
 
-PASS_NAMES = {0: "conv_fwd", 1: "conv_bwd_data", 2: "wgrad", 3: "reduce", 4: "pool_fwd", 5: "pool_bwd", 6: "scale_dy"}
+PASS_NAMES = {0: "conv_fwd", 1: "conv_bwd_data", 2: "wgrad", 3: "reduce", 4: "pool_fwd", 5: "pool_bwd", 6: "scale_dy", 7: "update"}
 
 
 class FtpError(RuntimeError):
@@ -73,13 +73,14 @@ def _load():
     lib.ftp_forward.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp]
     lib.ftp_backward.argtypes = [vp, vp, vp, ctypes.POINTER(vp), vp, vp, vp, vp]
     lib.ftp_reduce_wgrad.argtypes = [vp, vp, vp, vp]
+    lib.ftp_sgd_step.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_float, vp, vp]
     lib.ftp_profile.argtypes = [vp, i32]
     lib.ftp_profile_read.argtypes = [vp, ctypes.POINTER(ftp_kernel_time), i32, ctypes.POINTER(i32)]
     lib.ftp_strerror.argtypes = [ctypes.c_int]
     lib.ftp_strerror.restype = ctypes.c_char_p
     lib.ftp_last_hip_error.restype = ctypes.c_int
     for f in ("ftp_profile", "ftp_profile_read", "ftp_plan_buffer", "ftp_plan_rect", "ftp_plan_map_shape", "ftp_plan_sizes", "ftp_plan_work", "ftp_forward",
-              "ftp_backward", "ftp_reduce_wgrad"):
+              "ftp_backward", "ftp_reduce_wgrad", "ftp_sgd_step"):
         getattr(lib, f).restype = ctypes.c_int
     return lib
 
@@ -87,7 +88,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ("ftp_profile", "ftp_profile_read", "ftp_plan", "ftp_plan_destroy", "ftp_plan_buffer", "ftp_plan_rect", "ftp_plan_map_shape", "ftp_plan_sizes", "ftp_plan_work",
-           "ftp_forward", "ftp_backward", "ftp_reduce_wgrad", "ftp_strerror", "ftp_last_hip_error")
+           "ftp_forward", "ftp_backward", "ftp_reduce_wgrad", "ftp_sgd_step", "ftp_strerror", "ftp_last_hip_error")
 
 
 def _check(rc, where):
@@ -176,6 +177,11 @@ def ftp_backward(plan, dy, x, weights, workspace, dx, wgrad_partials, stream=0):
 
 def ftp_reduce_wgrad(plan, wgrad_partials, wgrad, stream=0):
     _check(_lib.ftp_reduce_wgrad(plan, wgrad_partials, wgrad, stream), "ftp_reduce_wgrad")
+
+
+def ftp_sgd_step(plan, wgrad_partials, weights, biases, lr, wgrad=0, stream=0):
+    n = len(weights)
+    _check(_lib.ftp_sgd_step(plan, wgrad_partials, _ptr_array(weights, n), _ptr_array(biases, n), lr, wgrad, stream), "ftp_sgd_step")
 
 
 def ftp_profile(plan, enable):

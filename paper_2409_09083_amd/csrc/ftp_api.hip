@@ -330,6 +330,32 @@ int ftp_reduce_wgrad(const ftp_plan_t* plan, const float* wgrad_partials, float*
     return timed(plan, FTP_PASS_REDUCE, -1, s, [&] { reduce_wgrad(wgrad_partials, wgrad, (long long)p.n_params, p.N * p.M, s); });
 }
 
+int ftp_sgd_step(const ftp_plan_t* plan, const float* wgrad_partials, void* const* weights, void* const* biases,
+                 float lr, float* wgrad, void* stream)
+{
+    if (!plan || !wgrad_partials || !weights) return FTP_EINVAL;
+    const Plan& p = plan->p;
+    int rc = check_weights(p, (const void* const*)weights, (const void* const*)biases);
+    if (rc != FTP_OK) return rc;
+    if (any_bias(p) && !biases) return FTP_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int stacks = p.N * p.M, bf16 = p.dtype == FTP_BF16;
+    for (const Unit& u : p.units) {
+        if (u.kind != UNIT_CONV) continue;
+        const ftp_layer& ly = p.layers[u.layer];
+        const long long wcount = (long long)ly.cout * ly.cin * ly.k * ly.k;
+        rc = timed(plan, FTP_PASS_UPDATE, u.layer, s, [&] {
+            sgd_update(wgrad_partials + u.param_offset, (long long)p.n_params, stacks, weights[u.layer], wcount, lr,
+                       wgrad ? wgrad + u.param_offset : nullptr, bf16, s);
+            if (ly.has_bias)
+                sgd_update(wgrad_partials + u.bias_offset, (long long)p.n_params, stacks, biases[u.layer], ly.cout, lr,
+                           wgrad ? wgrad + u.bias_offset : nullptr, bf16, s);
+        });
+        if (rc != FTP_OK) return rc;
+    }
+    return FTP_OK;
+}
+
 int ftp_profile(ftp_plan_t* plan, int32_t enable)
 {
     if (!plan) return FTP_EINVAL;
@@ -373,7 +399,11 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
             const double in_el = B * p.C[u->bi] * p.H[u->bi] * p.W[u->bi];
             const double out_el = B * p.C[u->bo] * p.H[u->bo] * p.W[u->bo];
             const double has_arg = (u->pooled || u->kind == UNIT_POOL) ? 1.0 : 0.0;
-            if (g.pass == FTP_PASS_SCALE_DY) {
+            if (g.pass == FTP_PASS_UPDATE) {
+                const double wel = (double)ly.cout * ly.cin * ly.k * ly.k + (ly.has_bias ? ly.cout : 0);
+                t.flops_per_launch = (stacks + 1.0) * wel;
+                t.bytes_per_launch = stacks * wel * 4.0 + 2.0 * wel * es;
+            } else if (g.pass == FTP_PASS_SCALE_DY) {
                 t.flops_per_launch = out_el;
                 t.bytes_per_launch = out_el * (2.0 * es + 1.0);
             } else if (u->kind == UNIT_CONV) {

@@ -234,11 +234,8 @@ k_pool_bwd(View din, View mask, View dout, View isign, int scale_out, float in_s
 // ---- sum of the per-stack partial gradients ------------------------------------------------------------
 // Balanced pairwise order over the stack index (pairs (2k, 2k+1) at each level, an odd tail is carried
 // up), evaluated with a binary-counter stack so that one pass over the partials suffices.
-__global__ void __launch_bounds__(256)
-k_reduce_wgrad(const float* __restrict__ partial, float* __restrict__ wgrad, long long n_params, int stacks)
+__device__ __forceinline__ float pairwise_stack_sum(const float* __restrict__ partial, long long n_params, int stacks, long long p)
 {
-    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= n_params) return;
     float stk[10];
     int top = 0;
     for (int s = 0; s < stacks; ++s) {
@@ -248,7 +245,28 @@ k_reduce_wgrad(const float* __restrict__ partial, float* __restrict__ wgrad, lon
     }
     float v = stk[--top];
     while (top > 0) v = stk[--top] + v;
-    wgrad[p] = v;
+    return v;
+}
+
+__global__ void __launch_bounds__(256)
+k_reduce_wgrad(const float* __restrict__ partial, float* __restrict__ wgrad, long long n_params, int stacks)
+{
+    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n_params) return;
+    wgrad[p] = pairwise_stack_sum(partial, n_params, stacks, p);
+}
+
+// The same sum fused with the gradient-descent step on one parameter tensor (Sec. 4.1, filter update).
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_sgd_update(const float* __restrict__ partial, long long n_params, int stacks, T* __restrict__ w, long long count, float lr,
+             float* __restrict__ wgrad)
+{
+    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= count) return;
+    const float g = pairwise_stack_sum(partial, n_params, stacks, p);
+    if (wgrad) wgrad[p] = g;
+    st(w + p, ld(w + p) - lr * g);
 }
 
 // ---- launchers ---------------------------------------------------------------------------------------------
@@ -337,6 +355,15 @@ void scale_dy(const void* dy, const uint32_t* sign, void* dst, int batch, int C,
     dim3 grid((unsigned)bx, C, batch), block(256);
     if (bf16) hipLaunchKernelGGL(k_scale_dy<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, sign, (bf16_t*)dst, C, HW, slope);
     else      hipLaunchKernelGGL(k_scale_dy<float>, grid, block, 0, s, (const float*)dy, sign, (float*)dst, C, HW, slope);
+}
+
+void sgd_update(const float* partial, long long n_params, int stacks, void* w, long long count, float lr, float* wgrad,
+                int bf16, hipStream_t s)
+{
+    g_kernel_label = "k_sgd_update";
+    dim3 grid((unsigned)((count + 255) / 256)), block(256);
+    if (bf16) hipLaunchKernelGGL(k_sgd_update<bf16_t>, grid, block, 0, s, partial, n_params, stacks, (bf16_t*)w, count, lr, wgrad);
+    else      hipLaunchKernelGGL(k_sgd_update<float>, grid, block, 0, s, partial, n_params, stacks, (float*)w, count, lr, wgrad);
 }
 
 void reduce_wgrad(const float* partial, float* wgrad, long long n_params, int stacks, hipStream_t s)

@@ -52,6 +52,11 @@ struct PoolArgs {
     int C = 0, N = 1, M = 1, batch = 1, bf16 = 0;
 };
 
+// w[i] <- w[i] - lr * sum over stacks of partial[stack][i] (pairwise order of reduce_wgrad), i < count; partial and
+// wgrad point at the first parameter of the tensor inside the parameter vector (stride n_params between stacks).
+void sgd_update(const float* partial, long long n_params, int stacks, void* w, long long count, float lr, float* wgrad,
+                int bf16, hipStream_t s);
+
 // dst = dy * (activation > 0 ? 1 : slope) over a whole map [batch][C][HW]; sign = packed signs of that boundary.
 void scale_dy(const void* dy, const uint32_t* sign, void* dst, int batch, int C, long long HW, float slope, int bf16, hipStream_t s);
 

@@ -84,10 +84,21 @@ class Session:
     def reduce(self):
         B.ftp_reduce_wgrad(self.plan, self.partials.data_ptr(), self.wgrad.data_ptr(), self._stream())
 
+    def sgd_step(self, lr, keep_wgrad=True):
+        """Gradient sum fused with W <- W - lr * dW on the session's weight tensors."""
+        B.ftp_sgd_step(self.plan, self.partials.data_ptr(), self._wptrs(), self._bptrs(), lr,
+                       self.wgrad.data_ptr() if keep_wgrad else 0, self._stream())
+
     def step(self):
         self.forward()
         self.backward()
         self.reduce()
+
+    def train_step(self, lr):
+        """One training cycle: forward, back-propagation, gradient sum + filter update."""
+        self.forward()
+        self.backward()
+        self.sgd_step(lr)
 
     # ---- inspection of the workspace (tests, debugging): plain tensor views and copies, no arithmetic ----
     def _buffer(self, boundary, which):
