@@ -6,6 +6,8 @@
 
 namespace ftp {
 
+__device__ __forceinline__ float4 operator+(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+
 // ---- delta at the convolution output ---------------------------------------------------------------
 // The delta maps hold dLoss/dZ (the activation derivative is folded in by whoever writes them).  With a pool
 // behind the convolution the delta sits at pooled resolution and reaches only the window's recorded winner
@@ -234,26 +236,65 @@ k_pool_bwd(View din, View mask, View dout, View isign, int scale_out, float in_s
 // ---- sum of the per-stack partial gradients ------------------------------------------------------------
 // Balanced pairwise order over the stack index (pairs (2k, 2k+1) at each level, an odd tail is carried
 // up), evaluated with a binary-counter stack so that one pass over the partials suffices.
-__device__ __forceinline__ float pairwise_stack_sum(const float* __restrict__ partial, long long n_params, int stacks, long long p)
+// Balanced pairwise sum of up to 8 items, n of them present: pairs (2k, 2k+1) at each level, an item without a
+// partner is carried up unchanged.  All indices are compile-time, so everything stays in registers.
+template <typename V>
+__device__ __forceinline__ V tree8(const V (&b)[8], int n)
 {
-    float stk[10];
-    int top = 0;
-    for (int s = 0; s < stacks; ++s) {
-        float v = partial[(long long)s * n_params + p];
-        for (int k = s; k & 1; k >>= 1) v = stk[--top] + v;
-        stk[top++] = v;
-    }
-    float v = stk[--top];
-    while (top > 0) v = stk[--top] + v;
-    return v;
+    V p[4], q[2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) p[j] = 2 * j + 1 < n ? b[2 * j] + b[2 * j + 1] : b[2 * j];
+    const int n1 = (n + 1) >> 1;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) q[j] = 2 * j + 1 < n1 ? p[2 * j] + p[2 * j + 1] : p[2 * j];
+    const int n2 = (n1 + 1) >> 1;
+    return n2 > 1 ? q[0] + q[1] : q[0];
 }
 
+// The balanced pairwise tree over up to 512 stacks, evaluated as nested 8-way trees (the tree over the whole list
+// restricted to an aligned group of 8 is the 8-way tree of that group).  The 8 loads of a group are in flight together.
+template <typename V>
+__device__ __forceinline__ V pairwise_stack_sum(const V* __restrict__ partial, long long stride, int stacks)
+{
+    V top[8];
+    const int n_top = (stacks + 63) >> 6;
+    for (int a = 0; a < 8; ++a) {
+        if (a >= n_top) break;
+        V mid[8];
+        const int left_a = stacks - 64 * a, n_mid = left_a >= 64 ? 8 : (left_a + 7) >> 3;
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            if (m < n_mid) {
+                V buf[8];
+                const int s0 = 64 * a + 8 * m, n = stacks - s0 >= 8 ? 8 : stacks - s0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) buf[u] = partial[(long long)(s0 + (u < n ? u : 0)) * stride];
+                mid[m] = tree8(buf, n);
+            } else {
+                mid[m] = mid[0];
+            }
+        }
+        const V v = tree8(mid, n_mid);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) if (t == a) top[t] = v;
+    }
+#pragma unroll
+    for (int t = 1; t < 8; ++t) if (t >= n_top) top[t] = top[0];
+    return tree8(top, n_top);
+}
+
+// 4 parameters per thread where the vector is long and aligned enough, one per thread for the rest.
 __global__ void __launch_bounds__(256)
 k_reduce_wgrad(const float* __restrict__ partial, float* __restrict__ wgrad, long long n_params, int stacks)
 {
-    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= n_params) return;
-    wgrad[p] = pairwise_stack_sum(partial, n_params, stacks, p);
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long n4 = (n_params % 4 == 0) ? n_params / 4 : 0;        // rows of the partials stay 16-byte aligned
+    if (i < n4) {
+        ((float4*)wgrad)[i] = pairwise_stack_sum((const float4*)partial + i, n_params / 4, stacks);
+    } else {
+        const long long p = 4 * n4 + (i - n4);
+        if (p < n_params) wgrad[p] = pairwise_stack_sum(partial + p, n_params, stacks);
+    }
 }
 
 // The same sum fused with the gradient-descent step on one parameter tensor (Sec. 4.1, filter update).
@@ -264,7 +305,7 @@ k_sgd_update(const float* __restrict__ partial, long long n_params, int stacks, 
 {
     const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= count) return;
-    const float g = pairwise_stack_sum(partial, n_params, stacks, p);
+    const float g = pairwise_stack_sum(partial + p, n_params, stacks);
     if (wgrad) wgrad[p] = g;
     st(w + p, ld(w + p) - lr * g);
 }
@@ -336,25 +377,46 @@ void pool_bwd(const PoolArgs& a, hipStream_t s)
     else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.M, a.batch);
 }
 
-template <typename T>
+// 4 consecutive elements of one (image, channel) plane per thread (HW is a multiple of 4: the rows of a plane and of
+// the sign words then stay 16-byte aligned), else one element per thread.
+template <typename T, int V>
 __global__ void __launch_bounds__(256)
-k_scale_dy(const T* __restrict__ dy, const uint32_t* __restrict__ sign, T* __restrict__ dst, int C, long long HW, float slope)
+k_scale_dy(const T* __restrict__ dy, const uint32_t* __restrict__ sign, T* __restrict__ dst, int C, long long HW, long long total, float slope)
 {
-    const int n = blockIdx.z, c = blockIdx.y, G = (C + 31) / 32;
-    const T* src = dy + ((long long)n * C + c) * HW;
-    T* out = dst + ((long long)n * C + c) * HW;
-    const uint32_t* sg = sign + ((long long)n * G + (c >> 5)) * HW;
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < HW; i += (long long)gridDim.x * blockDim.x)
-        st(out + i, scaled_delta<T>(ld(src + i), (sg[i] >> (c & 31)) & 1u, slope));
+    const long long e = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * V;
+    if (e >= total) return;
+    const long long plane = e / HW, off = e - plane * HW;
+    const int c = (int)(plane % C), G = (C + 31) / 32;
+    const long long n = plane / C;
+    const uint32_t* sg = sign + (n * G + (c >> 5)) * HW + off;
+    if (V == 4 && sizeof(T) == 4) {
+        const float4 v = *(const float4*)(dy + e);
+        const uint4 w = *(const uint4*)sg;
+        float4 r;
+        r.x = scaled_delta<T>(v.x, (w.x >> (c & 31)) & 1u, slope);
+        r.y = scaled_delta<T>(v.y, (w.y >> (c & 31)) & 1u, slope);
+        r.z = scaled_delta<T>(v.z, (w.z >> (c & 31)) & 1u, slope);
+        r.w = scaled_delta<T>(v.w, (w.w >> (c & 31)) & 1u, slope);
+        *(float4*)(dst + e) = r;
+    } else {
+#pragma unroll
+        for (int u = 0; u < V; ++u) st(dst + e + u, scaled_delta<T>(ld(dy + e + u), (sg[u] >> (c & 31)) & 1u, slope));
+    }
 }
 
 void scale_dy(const void* dy, const uint32_t* sign, void* dst, int batch, int C, long long HW, float slope, int bf16, hipStream_t s)
 {
     g_kernel_label = "k_scale_dy";
-    long long bx = (HW + 255) / 256; if (bx > 64) bx = 64;
-    dim3 grid((unsigned)bx, C, batch), block(256);
-    if (bf16) hipLaunchKernelGGL(k_scale_dy<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, sign, (bf16_t*)dst, C, HW, slope);
-    else      hipLaunchKernelGGL(k_scale_dy<float>, grid, block, 0, s, (const float*)dy, sign, (float*)dst, C, HW, slope);
+    const long long total = (long long)batch * C * HW;
+    const int V = HW % 4 == 0 ? 4 : 1;
+    dim3 grid((unsigned)((total / V + 255) / 256)), block(256);
+    if (bf16) {
+        if (V == 4) hipLaunchKernelGGL((k_scale_dy<bf16_t, 4>), grid, block, 0, s, (const bf16_t*)dy, sign, (bf16_t*)dst, C, HW, total, slope);
+        else        hipLaunchKernelGGL((k_scale_dy<bf16_t, 1>), grid, block, 0, s, (const bf16_t*)dy, sign, (bf16_t*)dst, C, HW, total, slope);
+    } else {
+        if (V == 4) hipLaunchKernelGGL((k_scale_dy<float, 4>), grid, block, 0, s, (const float*)dy, sign, (float*)dst, C, HW, total, slope);
+        else        hipLaunchKernelGGL((k_scale_dy<float, 1>), grid, block, 0, s, (const float*)dy, sign, (float*)dst, C, HW, total, slope);
+    }
 }
 
 void sgd_update(const float* partial, long long n_params, int stacks, void* w, long long count, float lr, float* wgrad,
@@ -369,7 +431,8 @@ void sgd_update(const float* partial, long long n_params, int stacks, void* w, l
 void reduce_wgrad(const float* partial, float* wgrad, long long n_params, int stacks, hipStream_t s)
 {
     g_kernel_label = "k_reduce_wgrad";
-    dim3 grid((unsigned)((n_params + 255) / 256)), block(256);
+    const long long threads = n_params % 4 == 0 ? n_params / 4 : n_params;
+    dim3 grid((unsigned)((threads + 255) / 256)), block(256);
     hipLaunchKernelGGL(k_reduce_wgrad, grid, block, 0, s, partial, wgrad, n_params, stacks);
 }
 
