@@ -54,6 +54,16 @@ def test_deep_net_bf16(oracle):
     P.check_case(oracle, _mk("deep", (2, 2), "split", "bf16", batch=2))
 
 
+@pytest.mark.parametrize("grid,grouping", [((16, 16), "whole"), ((16, 16), "each"), ((8, 16), "split")])
+def test_many_tiny_tiles(oracle, grid, grouping):
+    """The largest grid: tiles of 4 x 4 pixels (2 x 2 behind the pool), several images per chunk in the
+    filter-gradient kernels, one column of threads in the thin kernels."""
+    layers = (conv(3, 16), pool(16), conv(16, 32), conv(32, 16, 1), conv(16, 32))
+    L = len(layers)
+    ends = {"whole": (L,), "each": tuple(range(1, L + 1)), "split": (L // 2, L)}[grouping]
+    P.check_case(oracle, Config("tiny_tiles_%s" % grouping, 3, 3, 64, 64, layers, grid, ends, "f32"), partial_check=False)
+
+
 @pytest.mark.parametrize("grouping", ["whole", "split"])
 def test_bias(oracle, grouping):
     P.check_case(oracle, _mk("pools", (2, 3), grouping), has_bias=True)
