@@ -250,6 +250,8 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
                     prep_filter(a.w, a.bf16, wt, nullptr, a.Cout, a.Cin, a.K, s);
                     if (mfma_conv_fwd(a, ext, wt, s)) direct_conv_fwd(a, s);
                 });
+            } else if (use_mfma() && thin_conv_fwd_eligible(a)) {
+                rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { thin_conv_fwd(a, s); });
             } else {
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { direct_conv_fwd(a, s); });
             }

@@ -103,6 +103,8 @@ struct MfmaWgradArgs {
 bool mfma_wgrad_eligible(const ConvArgs& a);
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s);
 
+bool thin_conv_fwd_eligible(const ConvArgs& a);
+void thin_conv_fwd(const ConvArgs& a, hipStream_t s);
 bool thin_bwd_data_eligible(const ConvArgs& a);
 void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s);
 bool thin_wgrad_eligible(const ConvArgs& c);

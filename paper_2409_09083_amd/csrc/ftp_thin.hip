@@ -12,7 +12,152 @@ namespace ftp {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
+__device__ __forceinline__ bool in_rect_thin(const RectTab& r, int ti, int tj, int y, int x)
+{
+    return y >= r.y0[ti] && y <= r.y1[ti] && x >= r.x0[tj] && x <= r.x1[tj];
+}
+
 // dZ of one element from the delta and the owner's decision code (see ftp_direct.hip: delta_z).
+// ---- forward of a K = 3 convolution with at most 4 input channels (+ leaky ReLU, + fused 2x2 pool) ---------------
+// Workgroup = ntx x nty threads on one (stack, image); a thread produces one pool window (2 x 2 convolution outputs)
+// or, without a pool, two neighbouring pixels, for every output channel in turn.  The input patch of the tile
+// (all input channels, filter halo, zero outside the map) and the filter with its bias sit in LDS; a thread keeps
+// its own 4 x 4 (or 3 x 4) patch per input channel in registers and reads the 9 * CI weights of an output channel
+// as broadcast vectors.  A thread sees all channels of its pixel, so it writes the sign words itself.
+constexpr int kThinFwdPatch = 1280, kThinFwdCout = 64;     // floats of one channel's patch; channels whose weights fit LDS
+
+template <typename T, bool POOL, int CI>
+__global__ void __launch_bounds__(256)
+k_conv_fwd_thin(View in, View out, View mask, View osign, RectTab rt, RectTab own, const T* __restrict__ w,
+                const T* __restrict__ bias, int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch,
+                int ntx, int nty, int tiles_x)
+{
+    constexpr int PH = POOL ? 4 : 3, PWD = 4, WR = 9 * CI;         // register patch rows / columns, weights per channel
+    constexpr int SY = POOL ? 2 : 1, SX = 2;                        // convolution pixels per thread
+    __shared__ __attribute__((aligned(16))) float xp[CI * kThinFwdPatch];
+    __shared__ __attribute__((aligned(16))) float wl[kThinFwdCout * (WR + 1)];
+    const int tid = threadIdx.x;
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    // the rectangle is in output coordinates (pooled if POOL); tiles of ntx x nty threads
+    const int bx = blockIdx.x % tiles_x, by = blockIdx.x / tiles_x;
+    const int OX = POOL ? 1 : 2;                                    // output pixels per thread along x
+    const int ox0 = rt.x0[tj] + bx * ntx * OX, oy0 = rt.y0[ti] + by * nty;
+    if (ox0 > rt.x1[tj] || oy0 > rt.y1[ti]) return;
+    // convolution-resolution origin of the patch and its extent
+    const int cx0 = ox0 * (POOL ? 2 : 1) - 1, cy0 = oy0 * SY - 1;
+    const int PW = SX * ntx + 2, PHT = SY * nty + 2, PP = (PW + 1) & ~1;
+    for (int i = tid; i < CI * PHT * PW; i += 256) {
+        const int ci = i / (PHT * PW), rem = i - ci * (PHT * PW), r = rem / PW, q = rem - r * PW;
+        const int y = cy0 + r, x = cx0 + q;
+        // positions only pixels beyond the rectangle would read may lie outside the input view
+        const int ylim = (rt.y1[ti] + 1) * SY, xlim = (rt.x1[tj] + 1) * (POOL ? 2 : 1);
+        const bool okp = ci < Cin && y >= 0 && y < Hc && x >= 0 && x < Wc && y <= ylim && x <= xlim;
+        xp[ci * kThinFwdPatch + r * PP + q] = okp ? ld(at<T>(in, stack, ti, tj, n, ci, y, x)) : 0.0f;
+    }
+    for (int i = tid; i < Cout * (WR + 1); i += 256) {
+        const int co = i / (WR + 1), r = i - co * (WR + 1);
+        float v = 0.0f;
+        if (r < WR) { const int ci = r / 9, t = r - ci * 9; if (ci < Cin) v = ld(w + ((size_t)co * Cin + ci) * 9 + t); }
+        else if (bias) v = ld(bias + co);
+        wl[i] = v;
+    }
+    __syncthreads();
+    const int tx = tid % ntx, ty = tid / ntx;
+    if (ty >= nty) return;
+    const int oy = oy0 + ty, ox = ox0 + tx * OX;
+    float p[CI][PH][PWD];
+#pragma unroll
+    for (int ci = 0; ci < CI; ++ci)
+#pragma unroll
+        for (int r = 0; r < PH; ++r) {
+            const float* row = xp + ci * kThinFwdPatch + (SY * ty + r) * PP + SX * tx;
+            const float2 a = *(const float2*)row, b = *(const float2*)(row + 2);
+            p[ci][r][0] = a.x; p[ci][r][1] = a.y; p[ci][r][2] = b.x; p[ci][r][3] = b.y;
+        }
+    const bool v0 = oy <= rt.y1[ti] && ox <= rt.x1[tj];
+    const bool v1 = !POOL && oy <= rt.y1[ti] && ox + 1 <= rt.x1[tj];
+    const bool o0 = v0 && in_rect_thin(own, ti, tj, oy, ox), o1 = v1 && in_rect_thin(own, ti, tj, oy, ox + 1);
+    uint32_t s0 = 0, s1 = 0;
+    for (int co = 0; co < Cout; ++co) {
+        const float* wc = wl + co * (WR + 1);
+        float acc[SY][SX];
+#pragma unroll
+        for (int a = 0; a < SY; ++a)
+#pragma unroll
+            for (int b = 0; b < SX; ++b) acc[a][b] = 0.0f;
+#pragma unroll
+        for (int ci = 0; ci < CI; ++ci)
+#pragma unroll
+            for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+                for (int kx = 0; kx < 3; ++kx) {
+                    const float wv = wc[ci * 9 + ky * 3 + kx];
+#pragma unroll
+                    for (int a = 0; a < SY; ++a)
+#pragma unroll
+                        for (int b = 0; b < SX; ++b) acc[a][b] = fmaf(wv, p[ci][a + ky][b + kx], acc[a][b]);
+                }
+        const float bv = wc[WR];
+        if (POOL) {
+            // candidates are compared as the map would hold them; the first maximum in window order wins
+            float best = stored(leaky(acc[0][0] + bv, slope), (const T*)nullptr);
+            int bi = 0;
+            const float c1 = stored(leaky(acc[0][1] + bv, slope), (const T*)nullptr);
+            const float c2 = stored(leaky(acc[SY - 1][0] + bv, slope), (const T*)nullptr);
+            const float c3 = stored(leaky(acc[SY - 1][1] + bv, slope), (const T*)nullptr);
+            if (c1 > best) { best = c1; bi = 1; }
+            if (c2 > best) { best = c2; bi = 2; }
+            if (c3 > best) { best = c3; bi = 3; }
+            if (v0) {
+                st(at<T>(out, stack, ti, tj, n, co, oy, ox), best);
+                if (o0) *at<uint8_t>(mask, stack, ti, tj, n, co, oy, ox) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
+            }
+            s0 |= (best > 0.0f ? 1u : 0u) << (co & 31);
+        } else {
+            const float a0 = stored(leaky(acc[0][0] + bv, slope), (const T*)nullptr);
+            const float a1 = stored(leaky(acc[0][1] + bv, slope), (const T*)nullptr);
+            if (v0) st(at<T>(out, stack, ti, tj, n, co, oy, ox), a0);
+            if (v1) st(at<T>(out, stack, ti, tj, n, co, oy, ox + 1), a1);
+            s0 |= (a0 > 0.0f ? 1u : 0u) << (co & 31);
+            s1 |= (a1 > 0.0f ? 1u : 0u) << (co & 31);
+        }
+        if ((co & 31) == 31 || co == Cout - 1) {
+            if (o0) *at<uint32_t>(osign, stack, ti, tj, n, co >> 5, oy, ox) = s0;
+            if (o1) *at<uint32_t>(osign, stack, ti, tj, n, co >> 5, oy, ox + 1) = s1;
+            s0 = s1 = 0;
+        }
+    }
+}
+
+bool thin_conv_fwd_eligible(const ConvArgs& a) { return a.K == 3 && a.Cin <= 4 && a.Cout <= kThinFwdCout; }
+
+void thin_conv_fwd(const ConvArgs& a, hipStream_t s)
+{
+    int mw = 0, mh = 0;
+    for (int t = 0; t < a.M; ++t) mw = mw > a.rect.x1[t] - a.rect.x0[t] + 1 ? mw : a.rect.x1[t] - a.rect.x0[t] + 1;
+    for (int t = 0; t < a.N; ++t) mh = mh > a.rect.y1[t] - a.rect.y0[t] + 1 ? mh : a.rect.y1[t] - a.rect.y0[t] + 1;
+    const int OX = a.pooled ? 1 : 2, SY = a.pooled ? 2 : 1;
+    // threads along x cover the widest rectangle without a ragged last tile; at most 32 of them
+    const int need_x = (mw + OX - 1) / OX;
+    int tiles_x = (need_x + 31) / 32;
+    const int ntx = (need_x + tiles_x - 1) / tiles_x;
+    tiles_x = (need_x + ntx - 1) / ntx;
+    int nty_max = 256 / ntx; if (nty_max > 32) nty_max = 32;
+    const int tiles_y = (mh + nty_max - 1) / nty_max;
+    const int nty = (mh + tiles_y - 1) / tiles_y;
+    const int PP = (2 * ntx + 2 + 1) & ~1;
+    if ((SY * nty + 2) * PP > kThinFwdPatch) { direct_conv_fwd(a, s); return; }
+    dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
+    g_kernel_label = "k_conv_fwd_thin";
+#define FTP_TF(T, PL, CI) hipLaunchKernelGGL((k_conv_fwd_thin<T, PL, CI>), grid, block, 0, s, a.in, a.out, a.mask, a.osign, a.rect, a.own, (const T*)a.w, (const T*)a.bias, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch, ntx, nty, tiles_x)
+#define FTP_TFC(T, PL) do { if (a.Cin <= 3) FTP_TF(T, PL, 3); else FTP_TF(T, PL, 4); } while (0)
+    if (a.bf16) { if (a.pooled) FTP_TFC(bf16_t, true); else FTP_TFC(bf16_t, false); }
+    else        { if (a.pooled) FTP_TFC(float, true); else FTP_TFC(float, false); }
+#undef FTP_TFC
+#undef FTP_TF
+}
+
 // ---- delta at the input of a convolution with at most CIT input channels ------------------------------------
 // Workgroup = 64 x 4 pixels of one (stack, image): wide tiles keep the reads of the (pooled) delta rows long.
 // LDS = dZ patch of COC channels with the filter halo.
