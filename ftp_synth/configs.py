@@ -32,8 +32,8 @@ class Layer:
                 (w + 2 * self.pad - self.k) // self.stride + 1)
 
 
-def conv(cin, cout, k=3, slope=0.1):
-    return Layer(CONV, k, 1, k // 2, cin, cout, slope)
+def conv(cin, cout, k=3, slope=0.1, stride=1):
+    return Layer(CONV, k, stride, k // 2, cin, cout, slope)
 
 
 def pool(c):

@@ -21,6 +21,11 @@ collected from the owning neighbours at the synchronisation point where the back
 enters the group, so nothing is exchanged inside a group.
 For a 2x2/2 pool the exact dependence is used in both directions (Eq. (1) and (2) are
 stated for convolutions): back a' = 2a, b' = 2b + 1; forth a' = floor(a/2), b' = floor(b/2).
+A pool on an odd-sized map drops the last row / column (no padding); so that the owned rectangles
+still cover that map, the tile holding the last pooled row / column also takes the dropped one
+(OWN and FWD alike: it is produced by the layer before and its delta is zero).
+A strided convolution (stride S, kernel K, padding floor(K/2)) maps H to floor((H - 1)/S) + 1
+positions; Eq. (1c-d) is used as printed, with its (S - 1) term, and then clamped to the map.
 """
 
 CONV, MAXPOOL = 0, 1
@@ -81,6 +86,18 @@ def eq2_forth(r, ly):
     return (x1 // 2, y1 // 2, x2 // 2, y2 // 2)
 
 
+def _keep_dropped(back, r, ly, out_hw, in_hw):
+    """Pool on an odd map: the rectangle that reaches the last pooled row / column extends to the map's end."""
+    if ly.kind != MAXPOOL:
+        return back
+    x1, y1, x2, y2 = back
+    if r[2] == out_hw[1] - 1:
+        x2 = in_hw[1] - 1
+    if r[3] == out_hw[0] - 1:
+        y2 = in_hw[0] - 1
+    return (x1, y1, x2, y2)
+
+
 def group_rects(layers, sizes, s, e, N, M, i, j):
     """{kind: {l: (x1,y1,x2,y2)}} for tile (i,j) of group (s,e), boundaries s..e."""
     He, We = sizes[e]
@@ -89,8 +106,8 @@ def group_rects(layers, sizes, s, e, N, M, i, j):
     O = {e: (xa, ya, xb, yb)}
     F = {e: O[e]}
     for l in range(e, s, -1):
-        O[l - 1] = _clamp(stride_back(O[l], layers[l - 1]), sizes[l - 1])
-        F[l - 1] = _clamp(eq1_back(F[l], layers[l - 1]), sizes[l - 1])
+        O[l - 1] = _clamp(_keep_dropped(stride_back(O[l], layers[l - 1]), O[l], layers[l - 1], sizes[l], sizes[l - 1]), sizes[l - 1])
+        F[l - 1] = _clamp(_keep_dropped(eq1_back(F[l], layers[l - 1]), F[l], layers[l - 1], sizes[l], sizes[l - 1]), sizes[l - 1])
     B = {s: O[s]}
     for l in range(s, e):
         B[l + 1] = _clamp(eq2_forth(B[l], layers[l]), sizes[l + 1])

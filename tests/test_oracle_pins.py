@@ -223,3 +223,139 @@ def test_bf16_rounding(oracle):
     r = oracle.round_bf16(a.copy())
     assert np.array_equal(r, rng.to_bf16_rne(a))
     assert r[1] == 1.0 and r[2] == np.float32(1.015625)     # ties go to the even mantissa
+
+
+# ---- general geometry: strided convolutions, K = 5 and 7, pools on odd maps (Eq. (1)/(2) are stated for any K_l, S_l) ----
+
+def _net_general():
+    return [conv(3, 4, 5, stride=2), pool(4), conv(4, 5, 3, stride=2), conv(5, 3, 7), pool(3), conv(3, 2, 1, stride=2)]
+
+
+def test_general_geometry_finite_differences_fp64(oracle):
+    """Central differences through strided / 5x5 / 7x7 convolutions and pools on odd maps (19 -> 10 -> 5 -> 3 -> 3 -> 1 -> 1)."""
+    rs = np.random.RandomState(23)
+    layers = _net_general()
+    x = _rand(rs, (2, 3, 19, 21))
+    ws = _weights(rs, layers)
+    bs = [None if w is None else _rand(rs, (w.shape[0],)) * 0.1 for w in ws]
+    acts, args = oracle.forward(layers, x, ws, bs)
+    assert [a.shape[2:] for a in acts] == [(19, 21), (10, 11), (5, 5), (3, 3), (3, 3), (1, 1), (1, 1)]
+    g = _rand(rs, acts[-1].shape)
+    for l, ly in enumerate(layers):
+        if ly.kind == CONV:
+            assert np.abs(acts[l + 1]).min() > 1e-5
+    dx, dws, dbs = oracle.backward(layers, acts, args, ws, g)
+    eps, checked = 1e-6, 0
+    for (arr, grad) in [(x, dx)] + [(ws[l], dws[l]) for l in range(len(layers)) if ws[l] is not None] \
+            + [(bs[l], dbs[l]) for l in range(len(layers)) if bs[l] is not None]:
+        flat, gflat = arr.reshape(-1), grad.reshape(-1)
+        for idx in rs.choice(flat.size, size=min(25, flat.size), replace=False):
+            old = flat[idx]
+            flat[idx] = old + eps
+            lp = _loss(oracle, layers, x, ws, bs, g)
+            flat[idx] = old - eps
+            lm = _loss(oracle, layers, x, ws, bs, g)
+            flat[idx] = old
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - gflat[idx]) <= 1e-6 * max(1.0, abs(fd)), (idx, fd, gflat[idx])
+            checked += 1
+    assert checked > 100
+
+
+@pytest.mark.parametrize("k", [1, 3, 5, 7])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_general_geometry_adjoints_fp64(oracle, k, stride):
+    """Linear layer (slope 1): <G, A x> == <A^T G, x> == <dW, W> for every kernel size and stride, odd and even maps."""
+    rs = np.random.RandomState(100 + 10 * k + stride)
+    for (h, w) in ((8, 11), (9, 6)):
+        ly = Layer(CONV, k, stride, k // 2, 2, 3, 1.0)
+        x = _rand(rs, (2, 2, h, w))
+        wt = _rand(rs, (3, 2, k, k))
+        acts, args = oracle.forward([ly], x, [wt], None)
+        assert acts[-1].shape[2:] == ((h - 1) // stride + 1, (w - 1) // stride + 1)
+        g = _rand(rs, acts[-1].shape)
+        dx, dws, _ = oracle.backward([ly], acts, args, [wt], g)
+        lhs = np.sum(g * acts[-1])
+        assert abs(lhs - np.sum(dx * x)) <= 1e-12 * abs(lhs)
+        assert abs(lhs - np.sum(dws[0] * wt)) <= 1e-12 * abs(lhs)
+
+
+@pytest.mark.parametrize("k", [3, 5, 7])
+def test_strided_conv_is_subsampled_scipy_correlate(oracle, k):
+    """A stride-2 convolution is the stride-1 'same' correlation kept at every second position."""
+    from scipy.signal import correlate2d
+    rs = np.random.RandomState(31 + k)
+    x = _rand(rs, (1, 2, 11, 8))
+    w = _rand(rs, (3, 2, k, k))
+    z1 = oracle.conv_fwd(x, w, None, 1, k // 2)
+    z2 = oracle.conv_fwd(x, w, None, 2, k // 2)
+    for co in range(3):
+        ref = sum(correlate2d(x[0, ci], w[co, ci], mode="same") for ci in range(2))
+        assert np.allclose(z1[0, co], ref, rtol=1e-13, atol=1e-13)
+        assert np.allclose(z2[0, co], ref[::2, ::2], rtol=1e-13, atol=1e-13)
+    # the adjoint of subsampling is zero insertion: strided delta back-propagation = stride-1 one of the upsampled delta
+    g = _rand(rs, z2.shape)
+    up = np.zeros_like(z1)
+    up[:, :, ::2, ::2] = g
+    assert np.allclose(oracle.conv_bwd_data(g, w, (11, 8), 2, k // 2), oracle.conv_bwd_data(up, w, (11, 8), 1, k // 2),
+                       rtol=1e-13, atol=1e-13)
+    dw2, db2 = oracle.conv_bwd_weight(x, g, k, 2, k // 2)
+    dw1, db1 = oracle.conv_bwd_weight(x, up, k, 1, k // 2)
+    assert np.allclose(dw2, dw1, rtol=1e-13, atol=1e-13) and np.allclose(db2, db1, rtol=1e-13, atol=1e-13)
+
+
+def test_strided_all_ones_closed_form(oracle):
+    """All-ones 7x7 input, 5x5 filter of ones, stride 2, pad 2: Z[o] = (rows covered) x (columns covered) x Cin."""
+    x = np.ones((1, 2, 7, 7))
+    w = np.ones((1, 2, 5, 5))
+    z = oracle.conv_fwd(x, w, None, 2, 2)
+    cover = np.array([3, 5, 5, 3])                       # taps of [2o-2, 2o+2] that fall inside [0, 6]
+    assert np.array_equal(z[0, 0], 2.0 * np.outer(cover, cover))
+
+
+def test_pool_on_odd_map_drops_last_row_and_column(oracle):
+    rs = np.random.RandomState(41)
+    x = _rand(rs, (1, 2, 7, 5))
+    y, arg = oracle.pool_fwd(x)
+    y2, arg2 = oracle.pool_fwd(np.ascontiguousarray(x[:, :, :6, :4]))
+    assert y.shape == (1, 2, 3, 2) and np.array_equal(y, y2) and np.array_equal(arg, arg2)
+    g = _rand(rs, y.shape)
+    dx = oracle.pool_bwd(g, arg, (7, 5))
+    assert np.all(dx[:, :, 6, :] == 0) and np.all(dx[:, :, :, 4] == 0)
+    assert np.array_equal(dx[:, :, :6, :4], oracle.pool_bwd(g, arg, (6, 4)))
+
+
+def test_general_geometry_against_torch_cpu_autograd(oracle):
+    """Library pin for strides, 5x5 / 7x7 kernels and floor-mode pools on odd maps."""
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    rs = np.random.RandomState(43)
+    layers = [conv(3, 6, 7, stride=2), pool(6), conv(6, 8, 5), conv(8, 4, 3, stride=2), pool(4), conv(4, 5, 1, stride=2)]
+    x = _rand(rs, (2, 3, 37, 30))
+    ws = _weights(rs, layers)
+    bs = [None if w is None else _rand(rs, (w.shape[0],)) * 0.1 for w in ws]
+    acts, args = oracle.forward(layers, x, ws, bs)
+    g = _rand(rs, acts[-1].shape)
+    dx, dws, dbs, deltas = oracle.backward(layers, acts, args, ws, g, keep_deltas=True)
+    tx = torch.tensor(x, requires_grad=True)
+    tws = [None if w is None else torch.tensor(w, requires_grad=True) for w in ws]
+    tbs = [None if b is None else torch.tensor(b, requires_grad=True) for b in bs]
+    t, tacts = tx, [tx]
+    for l, ly in enumerate(layers):
+        if ly.kind == CONV:
+            t = F.leaky_relu(F.conv2d(t, tws[l], tbs[l], stride=ly.stride, padding=ly.pad), ly.slope)
+        else:
+            t = F.max_pool2d(t, 2, 2)
+        t.retain_grad()
+        tacts.append(t)
+    (t * torch.tensor(g)).sum().backward()
+    for l in range(len(layers) + 1):
+        assert acts[l].shape == tuple(tacts[l].shape), l
+        assert np.allclose(acts[l], tacts[l].detach().numpy(), rtol=1e-12, atol=1e-12), l
+    assert np.allclose(dx, tx.grad.numpy(), rtol=1e-11, atol=1e-12)
+    for l in range(1, len(layers) + 1):
+        assert np.allclose(deltas[l], tacts[l].grad.numpy(), rtol=1e-11, atol=1e-12), l
+    for l, ly in enumerate(layers):
+        if ly.kind == CONV:
+            assert np.allclose(dws[l], tws[l].grad.numpy(), rtol=1e-11, atol=1e-12), l
+            assert np.allclose(dbs[l], tbs[l].grad.numpy(), rtol=1e-11, atol=1e-12), l

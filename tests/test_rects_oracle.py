@@ -121,8 +121,74 @@ def test_dependency_tracing_brute_force(oracle):
         assert rk[R.BWD][4] == (xs.min(), ys.min(), xs.max(), ys.max())
 
 
+def test_strided_conv_hand_derived():
+    """One 3x3 stride-2 convolution, 16 columns cut in two: Eq. (1a,c) gives [2a - 1, 2b + 2], Eq. (2a,c)
+    [ceil((a - 1)/2), floor((b + 1)/2)], both clamped; the owned input columns are [2a, 2b + 1]."""
+    layers = [conv(1, 1, 3, stride=2)]
+    sizes, plan = R.plan(layers, 16, 16, 1, 2, (1,))
+    assert sizes == [(16, 16), (8, 8)]
+    t0, t1 = plan[0][(0, 0)], plan[0][(0, 1)]
+    assert (t0[R.OWN][1], t1[R.OWN][1]) == ((0, 0, 3, 7), (4, 0, 7, 7))
+    assert (t0[R.OWN][0], t1[R.OWN][0]) == ((0, 0, 7, 15), (8, 0, 15, 15))
+    assert (t0[R.FWD][0], t1[R.FWD][0]) == ((0, 0, 8, 15), (7, 0, 15, 15))
+    assert (t0[R.BWD][1], t1[R.BWD][1]) == ((0, 0, 4, 7), (4, 0, 7, 7))
+    # 7x7 stride 2 on an odd map: 15 -> 8 positions; halo 3 + the (S - 1) term
+    layers = [conv(1, 1, 7, stride=2)]
+    sizes, plan = R.plan(layers, 15, 15, 2, 1, (1,))
+    assert sizes[1] == (8, 8)
+    t0, t1 = plan[0][(0, 0)], plan[0][(1, 0)]
+    assert (t0[R.FWD][0], t1[R.FWD][0]) == ((0, 0, 14, 10), (0, 5, 14, 14))
+    assert (t0[R.OWN][0], t1[R.OWN][0]) == ((0, 0, 14, 7), (0, 8, 14, 14))
+    assert (t0[R.BWD][1], t1[R.BWD][1]) == ((0, 0, 7, 5), (0, 3, 7, 7))
+
+
+def test_pool_on_odd_map_last_tile_takes_dropped_row():
+    layers = [pool(1)]
+    sizes, plan = R.plan(layers, 9, 7, 2, 3, (1,))
+    assert sizes[1] == (4, 3)
+    assert plan[0][(1, 2)][R.OWN][1] == (2, 2, 2, 3)
+    assert plan[0][(1, 2)][R.OWN][0] == (4, 4, 6, 8) == plan[0][(1, 2)][R.FWD][0]
+    assert plan[0][(0, 0)][R.OWN][0] == (0, 0, 1, 3)
+    assert plan[0][(1, 2)][R.BWD][1] == (2, 2, 2, 3)
+
+
+def test_strided_dependency_tracing_brute_force(oracle):
+    """Strided convolutions and a pool on an odd map, traced pixel by pixel (all-positive filters, slope 1, one
+    large input pixel at a time): B_e is exactly the bounding box of what O_s influences (Eq. 2 is the exact cone);
+    F_s starts where the bounding box of what O_e depends on starts and exceeds it at the far side by at most the
+    (S - 1) terms of Eq. (1c-d) carried down to the group input."""
+    layers = [Layer(CONV, 3, 2, 1, 1, 1, 1.0), Layer(CONV, 5, 1, 2, 1, 1, 1.0), pool(1), Layer(CONV, 3, 2, 1, 1, 1, 1.0)]
+    H, W = 23, 26
+    ws = [None if ly.kind != CONV else np.ones((1, 1, ly.k, ly.k)) for ly in layers]
+    sizes, plan = R.plan(layers, H, W, 2, 2, (4,))
+    assert sizes == [(23, 26), (12, 13), (12, 13), (6, 6), (3, 3)]
+    Ho, Wo = sizes[4]
+    dep = np.zeros((H, W, Ho, Wo), dtype=bool)
+    base_in = np.full((1, 1, H, W), 1.0)
+    base, _ = oracle.forward(layers, base_in, ws)
+    for y in range(H):
+        for x in range(W):
+            xin = base_in.copy()
+            xin[0, 0, y, x] = 50.0                   # whatever it reaches becomes the largest value of its pool window
+            acts, _ = oracle.forward(layers, xin, ws)
+            dep[y, x] = (acts[-1][0, 0] != base[-1][0, 0])
+    slack = ((2 - 1) * 2) * 2 + (2 - 1)              # last layer's term, doubled by the pool and by layer 0, plus layer 0's own
+    for (i, j), rk in plan[0].items():
+        o_e, o_s = rk[R.OWN][4], rk[R.OWN][0]
+        need = dep[:, :, o_e[1]:o_e[3] + 1, o_e[0]:o_e[2] + 1].any(axis=(2, 3))
+        ys, xs = np.nonzero(need)
+        f = rk[R.FWD][0]
+        assert (f[0], f[1]) == (xs.min(), ys.min())
+        assert 0 <= f[2] - xs.max() <= slack and 0 <= f[3] - ys.max() <= slack
+        infl = dep[o_s[1]:o_s[3] + 1, o_s[0]:o_s[2] + 1].any(axis=(0, 1))
+        ys, xs = np.nonzero(infl)
+        assert rk[R.BWD][4] == (xs.min(), ys.min(), xs.max(), ys.max())
+
+
 _EMU_NETS = {
     "convs": ([conv(2, 3), conv(3, 4), conv(4, 2)], 13, 11),
+    "strided": ([conv(2, 3, 3, stride=2), conv(3, 4, 5), conv(4, 3, 1, stride=2), conv(3, 2, 7, stride=2)], 37, 30),
+    "oddpools": ([conv(2, 3, 5), pool(3), conv(3, 4), pool(4), pool(4), conv(4, 2, 3, stride=2)], 31, 27),
     "pools": ([conv(2, 4), pool(4), conv(4, 3), conv(3, 4, 1), pool(4), conv(4, 2)], 24, 20),
     "poolfirst": ([pool(2), conv(2, 3), pool(3), pool(3), conv(3, 2)], 32, 24),
 }

@@ -37,6 +37,26 @@ class Held:
         return out
 
 
+    def crop_zero_outside(self, r):
+        """Values over r; positions this fragment does not cover are zero (deltas nothing contributes to)."""
+        x0, y0, x1, y1 = max(r[0], self.rect[0]), max(r[1], self.rect[1]), min(r[2], self.rect[2]), min(r[3], self.rect[3])
+        out = np.zeros(self.data.shape[:2] + (r[3] - r[1] + 1, r[2] - r[0] + 1), dtype=self.data.dtype)
+        if x0 <= x1 and y0 <= y1:
+            out[:, :, y0 - r[1]:y1 - r[1] + 1, x0 - r[0]:x1 - r[0] + 1] = self.crop((x0, y0, x1, y1))
+        return out
+
+
+def windows(r):
+    """Input positions of the 2x2 pool windows r."""
+    return (2 * r[0], 2 * r[1], 2 * r[2] + 1, 2 * r[3] + 1)
+
+
+def taps(r, ly):
+    """Input positions the convolution outputs r touch: [S a - P, S b + P] per dimension."""
+    S, P = ly.stride, ly.pad
+    return (S * r[0] - P, S * r[1] - P, S * r[2] + P, S * r[3] + P)
+
+
 def full(a):
     return Held((0, 0, a.shape[3] - 1, a.shape[2] - 1), a)
 
@@ -65,10 +85,10 @@ def run(layers, x, weights, dy, N, M, group_ends):
             for l in range(s, e):
                 ly = layers[l]
                 if ly.kind == CONV:
-                    src = h[l].crop_zero_padded(R.eq1_back(F[l + 1], ly), sizes[l])
+                    src = h[l].crop_zero_padded(taps(F[l + 1], ly), sizes[l])
                     y = O.leaky_fwd(O.conv_fwd(src, weights[l], None, ly.stride, 0), ly.slope)
                 else:
-                    y, a = O.pool_fwd(h[l].crop(R.eq1_back(F[l + 1], ly)))
+                    y, a = O.pool_fwd(h[l].crop(windows(F[l + 1])))
                     o = Ow[l + 1]
                     win[l + 1][:, :, o[1]:o[3] + 1, o[0]:o[2] + 1] = Held(F[l + 1], a).crop(o)
                 h[l + 1] = Held(F[l + 1], y)
@@ -98,17 +118,24 @@ def run(layers, x, weights, dy, N, M, group_ends):
                 ly = layers[l]
                 if ly.kind == MAXPOOL:
                     dxf = O.pool_bwd(d.data, wn[l + 1].data, (2 * d.data.shape[2], 2 * d.data.shape[3]))
-                    d = Held(B[l], Held(R.eq1_back(B[l + 1], ly), dxf).crop(B[l]))
+                    d = Held(B[l], Held(windows(B[l + 1]), dxf).crop_zero_outside(B[l]))     # a dropped row / column gets 0
                 else:
                     # leaky'(Y) from the sign code: slope where the sign is not positive
                     yy = np.where(sg[l + 1].data, 1.0, -1.0)
                     dz = Held(B[l + 1], O.leaky_bwd(d.data, yy, ly.slope))
                     own = Ow[l + 1]
-                    xin = h[l].crop_zero_padded(grow(own, ly.pad), sizes[l])
+                    xin = h[l].crop_zero_padded(taps(own, ly), sizes[l])
                     partial[tile][l], _ = O.conv_bwd_weight(xin, dz.crop(own), ly.k, ly.stride, 0, want_db=False)
-                    wrot = np.ascontiguousarray(weights[l][:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
-                    dzp = dz.crop_zero_padded(grow(B[l], ly.pad), sizes[l + 1])
-                    d = Held(B[l], O.conv_fwd(dzp, wrot, None, 1, 0))
+                    if ly.stride == 1:
+                        # correlation with the 180-degree rotated filter (Sec. 4.1)
+                        wrot = np.ascontiguousarray(weights[l][:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+                        dzp = dz.crop_zero_padded(grow(B[l], ly.pad), sizes[l + 1])
+                        d = Held(B[l], O.conv_fwd(dzp, wrot, None, 1, 0))
+                    else:
+                        # adjoint of the strided convolution on the positions the held deltas touch
+                        reach = taps(B[l + 1], ly)
+                        dxf = O.conv_bwd_data(dz.data, weights[l], (reach[3] - reach[1] + 1, reach[2] - reach[0] + 1), ly.stride, 0)
+                        d = Held(B[l], Held(reach, dxf).crop_zero_outside(B[l]))
             r = B[s]
             out[:, :, r[1]:r[3] + 1, r[0]:r[2] + 1] = d.data
         assert not np.isnan(out).any()
