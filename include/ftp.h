@@ -1,7 +1,7 @@
 /*
  * libftp - fused tile partitioning (FTP) of the feature-map dominated early layers of a CNN:
- * forward inference and back-propagation of 3x3 / 1x1 convolutions (leaky ReLU folded in) and
- * 2x2 max-pools, with feature and delta maps cut into an N x M grid of tiles, matching tiles of
+ * forward inference and back-propagation of K x K convolutions (K = 1, 3, 5, 7, stride 1 or 2; leaky ReLU folded
+ * in; the 3x3 / 1x1 stride-1 layers of the paper's networks take the matrix-core kernels) and 2x2 max-pools, with feature and delta maps cut into an N x M grid of tiles, matching tiles of
  * consecutive layers fused into independent execution stacks, layers combined into groups that
  * exchange boundary (halo) data only at the group input, and per-stack partial filter
  * gradients summed once per batch (Sec. 3, Sec. 4.1, Sec. 4.2 of the paper).
@@ -42,17 +42,19 @@ typedef enum { FTP_RECT_OWN = 0, FTP_RECT_FWD = 1, FTP_RECT_BWD = 2 } ftp_rect_k
 typedef enum {
     FTP_OK = 0,
     FTP_EINVAL = -1,        /* null pointer, non-positive size, index out of range            */
-    FTP_EUNSUPPORTED = -2,  /* conv with stride != 1, K not in {1,3}, pad != K/2, pool != 2x2/2 */
-    FTP_EGRID = -3,         /* a tile would own no pixel, an odd map meets a pool, grid > 16   */
+    FTP_EUNSUPPORTED = -2,  /* conv with stride not 1 or 2, K not in {1,3,5,7}, pad != K/2, pool != 2x2/2 */
+    FTP_EGRID = -3,         /* a tile would own no pixel, a map too small for its pool, grid > 16 */
     FTP_EGROUPS = -4,       /* group ends not strictly increasing or not ending at n_layers    */
     FTP_ENOMEM = -5,        /* host allocation failed                                          */
     FTP_EHIP = -6,          /* a HIP call failed; see ftp_last_hip_error                       */
     FTP_ECHANNELS = -7      /* cin of a layer does not match cout of the previous one          */
 } ftp_status;
 
-/* One primitive layer.  FTP_CONV: K x K convolution, stride 1, zero padding K/2, followed by
- * leaky ReLU with `leaky_slope` (Y = Z if Z > 0 else slope*Z; slope 1 gives a linear layer).
- * FTP_MAXPOOL: 2x2 window, stride 2, no padding (k = 2, stride = 2, pad = 0, cin == cout). */
+/* One primitive layer (Sec. 4.2: kernel K_l x K_l, stride S_l).  FTP_CONV: K x K convolution, stride 1 or 2, zero
+ * padding K/2 (an H-long map gives floor((H - 1)/S) + 1 positions), followed by leaky ReLU with `leaky_slope`
+ * (Y = Z if Z > 0 else slope*Z; slope 1 gives a linear layer).
+ * FTP_MAXPOOL: 2x2 window, stride 2, no padding (k = 2, stride = 2, pad = 0, cin == cout); on an odd map the last
+ * row / column is left out (floor(H/2) positions) and receives a zero delta. */
 typedef struct {
     int32_t kind, k, stride, pad, cin, cout;
     float leaky_slope;
@@ -60,7 +62,8 @@ typedef struct {
 } ftp_layer;
 
 /* Builds the partition plan (Sec. 4.2): map sizes, and per group and tile the owned rectangle
- * (equal split of the group's output map, projected back through the strides), the forward
+ * (equal split of the group's output map, projected back through the strides; the row / column a pool drops
+ * from an odd map goes to the last tile), the forward
  * rectangles of Eq. (1) walked from e to s (what a stack computes and keeps), and the backward
  * (delta) rectangles of Eq. (2) walked from s to e; all clamped to the map.
  * Host only, integer only; touches no GPU.

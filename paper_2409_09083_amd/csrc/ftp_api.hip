@@ -67,6 +67,13 @@ bool use_mfma()
     return on;
 }
 
+// The matrix-core and thin-layer kernels are written for the geometry of the paper's networks: stride 1, K <= 3
+// and, behind the convolution, a pool over an even map.  Everything else runs on the general direct kernels.
+bool plain_geometry(const ConvArgs& a)
+{
+    return a.S == 1 && a.K <= 3 && !(a.pooled && ((a.Hc | a.Wc) & 1));
+}
+
 ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void* const* weights, const void* const* biases)
 {
     ConvArgs a;
@@ -85,7 +92,9 @@ ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void*
     a.n_params = (long long)p.n_params; a.w_off = (long long)u.param_offset; a.b_off = (long long)u.bias_offset;
     a.has_bias = ly.has_bias;
     a.K = ly.k; a.Cin = ly.cin; a.Cout = ly.cout;
-    a.Hc = p.H[u.layer]; a.Wc = p.W[u.layer];
+    a.S = ly.stride;
+    a.Hi = p.H[u.layer]; a.Wi = p.W[u.layer];
+    a.Hc = p.H[u.layer + 1]; a.Wc = p.W[u.layer + 1];
     a.pooled = u.pooled ? 1 : 0;
     a.slope = ly.leaky_slope;
     a.N = p.N; a.M = p.M; a.batch = p.batch;
@@ -107,6 +116,7 @@ PoolArgs pool_args(const Plan& p, const Unit& u, const UserBufs& ub)
     a.in_slope = u.in_slope;
     a.C = p.C[u.bi]; a.N = p.N; a.M = p.M; a.batch = p.batch;
     a.bf16 = p.dtype == FTP_BF16;
+    a.Ho = p.H[u.bo]; a.Wo = p.W[u.bo];
     return a;
 }
 
@@ -243,14 +253,15 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
             ConvArgs a = conv_args(p, u, ub, weights, biases);
             a.rect = make_rect(p, u.group, FTP_RECT_FWD, u.bo);
             a.own = make_rect(p, u.group, FTP_RECT_OWN, u.bo);
-            if (use_mfma() && mfma_conv_eligible(a, false)) {
+            const bool fast = use_mfma() && plain_geometry(a);
+            if (fast && mfma_conv_eligible(a, false)) {
                 float* wt = (float*)((char*)workspace + u.wt_fwd_offset);
                 const RectTab ext = view_extent(p, u.in_act, u.group, u.bi);
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] {
                     prep_filter(a.w, a.bf16, wt, nullptr, a.Cout, a.Cin, a.K, s);
                     if (mfma_conv_fwd(a, ext, wt, s)) direct_conv_fwd(a, s);
                 });
-            } else if (use_mfma() && thin_conv_fwd_eligible(a)) {
+            } else if (fast && thin_conv_fwd_eligible(a)) {
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { thin_conv_fwd(a, s); });
             } else {
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { direct_conv_fwd(a, s); });
@@ -292,23 +303,24 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             a.partial = wgrad_partials;
             a.rect = make_rect(p, u.group, FTP_RECT_OWN, u.layer + 1);
             float* scratch = (float*)((char*)workspace + p.wgrad_scratch_offset);
-            if (use_mfma() && thin_wgrad_eligible(a)) {
+            const bool fast = use_mfma() && plain_geometry(a);
+            if (fast && thin_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { thin_wgrad(a, scratch, s); });
-            } else if (use_mfma() && mfma_wgrad_eligible(a)) {
+            } else if (fast && mfma_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { mfma_wgrad(a, scratch, s); });
             } else {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { direct_wgrad(a, s); });
             }
             if (rc != FTP_OK) return rc;
             a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
-            if (use_mfma() && mfma_conv_eligible(a, true)) {
+            if (fast && mfma_conv_eligible(a, true)) {
                 float* wt = (float*)((char*)workspace + u.wt_bwd_offset);
                 const RectTab ext = view_extent(p, u.in_delta, u.group, u.bo);
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] {
                     prep_filter(a.w, a.bf16, nullptr, wt, a.Cout, a.Cin, a.K, s);
                     if (mfma_conv_bwd_data(a, ext, wt, s)) direct_conv_bwd_data(a, s);
                 });
-            } else if (use_mfma() && thin_bwd_data_eligible(a)) {
+            } else if (fast && thin_bwd_data_eligible(a)) {
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { thin_conv_bwd_data(a, s); });
             } else {
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { direct_conv_bwd_data(a, s); });

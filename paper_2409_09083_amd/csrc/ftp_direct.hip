@@ -1,5 +1,5 @@
-// Direct (non-matrix-core) kernels of libftp for gfx950: the generic path for every layer shape,
-// and the path of choice for thin layers (3 input channels) and lone pools.
+// Direct (non-matrix-core) kernels of libftp for gfx950: the general path for every layer geometry
+// (K = 1, 3, 5, 7; stride 1 or 2, Eq. (1)/(2) with any K_l, S_l; pools over odd maps), and the path of lone pools.
 // One workgroup serves one (stack, image); stacks only read the rectangles the plan entitles them to.
 #include "ftp_device.h"
 #include "ftp_launch.h"
@@ -13,12 +13,14 @@ __device__ __forceinline__ float4 operator+(float4 a, float4 b) { return make_fl
 // behind the convolution the delta sits at pooled resolution and reaches only the window's recorded winner
 // (Sec. 4.1, back-propagation of the delta); the winner comes from the decision code the owning stack wrote
 // in the forward pass.
+// (Hp, Wp) = pooled extent: the last row / column of an odd convolution output lies in no window and has delta 0.
 template <typename T, bool POOL>
 __device__ __forceinline__ float delta_z(const View& din, const View& mask, int stack, int ti, int tj,
-                                         int n, int co, int qy, int qx)
+                                         int n, int co, int qy, int qx, int Hp, int Wp)
 {
     if (!POOL) return ld(at<T>(din, stack, ti, tj, n, co, qy, qx));
     const int sy = qy >> 1, sx = qx >> 1;
+    if (sy >= Hp || sx >= Wp) return 0.0f;
     const uint8_t m = *at<uint8_t>(mask, stack, ti, tj, n, co, sy, sx);
     if (((m >> 1) & 3) != (((qy & 1) << 1) | (qx & 1))) return 0.0f;
     return ld(at<T>(din, stack, ti, tj, n, co, sy, sx));
@@ -30,10 +32,11 @@ __device__ __forceinline__ bool in_rect(const RectTab& r, int ti, int tj, int y,
 }
 
 // ---- forward: convolution + leaky ReLU (+ 2x2 max-pool) ------------------------------------------------
-template <typename T, int K, bool POOL, int COB>
+// (Hi, Wi) = extent of the input map; output position o of a stride-S convolution reads inputs o*S - P + k.
+template <typename T, int K, int S, bool POOL, int COB>
 __global__ void __launch_bounds__(64)
 k_conv_fwd_direct(View in, View out, View mask, View osign, RectTab rt, RectTab own, const T* __restrict__ w,
-                  const T* __restrict__ bias, int Cin, int Cout, int Hc, int Wc, float slope, int M, int batch)
+                  const T* __restrict__ bias, int Cin, int Cout, int Hi, int Wi, float slope, int M, int batch)
 {
     static_assert(COB == 8, "a workgroup's channels fill one byte of the sign word");
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
@@ -43,13 +46,13 @@ k_conv_fwd_direct(View in, View out, View mask, View osign, RectTab rt, RectTab 
     if (pid >= rw * rh) return;
     const int oy = rt.y0[ti] + pid / rw, ox = rt.x0[tj] + pid % rw;
     const int co0 = blockIdx.y * COB;
-    constexpr int NP = POOL ? 2 : 1, P = K / 2, R = NP + K - 1;
+    constexpr int NP = POOL ? 2 : 1, P = K / 2, R = (NP - 1) * S + K;
     float acc[COB][NP * NP];
 #pragma unroll
     for (int j = 0; j < COB; ++j)
 #pragma unroll
         for (int d = 0; d < NP * NP; ++d) acc[j][d] = 0.0f;
-    const int by = oy * NP - P, bx = ox * NP - P;
+    const int by = oy * NP * S - P, bx = ox * NP * S - P;
     for (int ci = 0; ci < Cin; ++ci) {
         float patch[R * R];
 #pragma unroll
@@ -57,7 +60,7 @@ k_conv_fwd_direct(View in, View out, View mask, View osign, RectTab rt, RectTab 
 #pragma unroll
             for (int c = 0; c < R; ++c) {
                 const int y = by + r, x = bx + c;
-                patch[r * R + c] = (y >= 0 && y < Hc && x >= 0 && x < Wc) ? ld(at<T>(in, stack, ti, tj, n, ci, y, x)) : 0.0f;
+                patch[r * R + c] = (y >= 0 && y < Hi && x >= 0 && x < Wi) ? ld(at<T>(in, stack, ti, tj, n, ci, y, x)) : 0.0f;
             }
 #pragma unroll
         for (int j = 0; j < COB; ++j) {
@@ -73,7 +76,7 @@ k_conv_fwd_direct(View in, View out, View mask, View osign, RectTab rt, RectTab 
                     for (int dy = 0; dy < NP; ++dy)
 #pragma unroll
                         for (int dx = 0; dx < NP; ++dx)
-                            acc[j][dy * NP + dx] = fmaf(wv, patch[(dy + ky) * R + dx + kx], acc[j][dy * NP + dx]);
+                            acc[j][dy * NP + dx] = fmaf(wv, patch[(dy * S + ky) * R + dx * S + kx], acc[j][dy * NP + dx]);
                 }
         }
     }
@@ -104,7 +107,9 @@ k_conv_fwd_direct(View in, View out, View mask, View osign, RectTab rt, RectTab 
 }
 
 // ---- backward: delta at the convolution input -------------------------------------------------------
-template <typename T, int K, bool POOL, int CIB>
+// (Hc, Wc) = extent of the convolution output; input position i receives W[k] dZ[q] from every (q, k) with
+// q*S - P + k == i (for stride 2 only the taps of matching parity contribute).
+template <typename T, int K, int S, bool POOL, int CIB>
 __global__ void __launch_bounds__(64)
 k_conv_bwd_data_direct(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt,
                        const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch)
@@ -125,9 +130,11 @@ k_conv_bwd_data_direct(View din, View mask, View dout, View isign, int scale_out
         for (int ky = 0; ky < K; ++ky)
 #pragma unroll
             for (int kx = 0; kx < K; ++kx) {
-                const int qy = iy + P - ky, qx = ix + P - kx;
-                if (qy < 0 || qy >= Hc || qx < 0 || qx >= Wc) continue;
-                const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx);
+                const int sy = iy + P - ky, sx = ix + P - kx;
+                if (sy < 0 || sx < 0 || (S == 2 && ((sy | sx) & 1))) continue;
+                const int qy = sy / S, qx = sx / S;
+                if (qy >= Hc || qx >= Wc) continue;
+                const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx, Hc >> 1, Wc >> 1);
 #pragma unroll
                 for (int j = 0; j < CIB; ++j) {
                     const int ci = ci0 + j;
@@ -147,10 +154,10 @@ k_conv_bwd_data_direct(View din, View mask, View dout, View isign, int scale_out
 // ---- backward: per-stack partial filter gradient -----------------------------------------------------
 // One workgroup per (ci, co, stack) sums dZ * X over the batch and the stack's owned output pixels.
 // Lanes are combined with wavefront shuffles, waves through LDS in a fixed order: deterministic.
-template <typename T, int K, bool POOL>
+template <typename T, int K, int S, bool POOL>
 __global__ void __launch_bounds__(256)
 k_wgrad_direct(View xin, View din, View mask, RectTab own, float* __restrict__ partial, long long n_params,
-               long long w_off, long long b_off, int has_bias, int Cin, int Cout, int Hc, int Wc, int M, int batch)
+               long long w_off, long long b_off, int has_bias, int Cin, int Cout, int Hi, int Wi, int Hc, int Wc, int M, int batch)
 {
     const int ci = blockIdx.x, co = blockIdx.y, stack = blockIdx.z;
     const int ti = stack / M, tj = stack % M;
@@ -163,14 +170,14 @@ k_wgrad_direct(View xin, View din, View mask, RectTab own, float* __restrict__ p
     for (int it = threadIdx.x; it < items; it += 256) {
         const int n = it / px, r = it - n * px;
         const int qy = own.y0[ti] + r / rw, qx = own.x0[tj] + r % rw;
-        const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx);
+        const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx, Hc >> 1, Wc >> 1);
         acc[KK] += dz;
 #pragma unroll
         for (int ky = 0; ky < K; ++ky)
 #pragma unroll
             for (int kx = 0; kx < K; ++kx) {
-                const int y = qy - P + ky, x = qx - P + kx;
-                if (y >= 0 && y < Hc && x >= 0 && x < Wc)
+                const int y = qy * S - P + ky, x = qx * S - P + kx;
+                if (y >= 0 && y < Hi && x >= 0 && x < Wi)
                     acc[ky * K + kx] = fmaf(dz, ld(at<T>(xin, stack, ti, tj, n, ci, y, x)), acc[ky * K + kx]);
             }
     }
@@ -218,7 +225,7 @@ k_pool_fwd(View in, View out, View mask, RectTab rt, RectTab own, int C, int M, 
 
 template <typename T>
 __global__ void __launch_bounds__(64)
-k_pool_bwd(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt, int C, int M, int batch)
+k_pool_bwd(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt, int C, int Ho, int Wo, int M, int batch)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
@@ -227,8 +234,11 @@ k_pool_bwd(View din, View mask, View dout, View isign, int scale_out, float in_s
     if (pid >= rw * rh) return;
     const int iy = rt.y0[ti] + pid / rw, ix = rt.x0[tj] + pid % rw;
     const int c = blockIdx.y;
-    const uint8_t a = (*at<uint8_t>(mask, stack, ti, tj, n, c, iy >> 1, ix >> 1) >> 1) & 3;
-    float g = (a == (uint8_t)(((iy & 1) << 1) | (ix & 1))) ? ld(at<T>(din, stack, ti, tj, n, c, iy >> 1, ix >> 1)) : 0.0f;
+    float g = 0.0f;
+    if ((iy >> 1) < Ho && (ix >> 1) < Wo) {            // the last row / column of an odd map lies in no window
+        const uint8_t a = (*at<uint8_t>(mask, stack, ti, tj, n, c, iy >> 1, ix >> 1) >> 1) & 3;
+        if (a == (uint8_t)(((iy & 1) << 1) | (ix & 1))) g = ld(at<T>(din, stack, ti, tj, n, c, iy >> 1, ix >> 1));
+    }
     if (scale_out) g = scaled_delta<T>(g, sign_bit(isign, stack, ti, tj, n, c, iy, ix), in_slope);
     st(at<T>(dout, stack, ti, tj, n, c, iy, ix), g);
 }
@@ -321,15 +331,22 @@ inline int rect_max_px(const RectTab& rt, int N, int M)
     return mw * mh;
 }
 
+// Picks the instantiation for (K, stride, pooled); the planner admits K in {1, 3, 5, 7} and stride in {1, 2} only.
+#define FTP_GEOMETRY_S(LAUNCH, KK) \
+    do { if (a.S == 2) { if (a.pooled) LAUNCH(KK, 2, true); else LAUNCH(KK, 2, false); } \
+         else          { if (a.pooled) LAUNCH(KK, 1, true); else LAUNCH(KK, 1, false); } } while (0)
+#define FTP_GEOMETRY(LAUNCH) \
+    do { switch (a.K) { case 1: FTP_GEOMETRY_S(LAUNCH, 1); break; case 3: FTP_GEOMETRY_S(LAUNCH, 3); break; \
+                        case 5: FTP_GEOMETRY_S(LAUNCH, 5); break; default: FTP_GEOMETRY_S(LAUNCH, 7); break; } } while (0)
+
 template <typename T>
 void conv_fwd_t(const ConvArgs& a, hipStream_t s)
 {
     constexpr int COB = 8;
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cout + COB - 1) / COB, a.N * a.M * a.batch), block(64);
     const T* w = (const T*)a.w; const T* b = (const T*)a.bias;
-#define FTP_FWD(KK, PL) hipLaunchKernelGGL((k_conv_fwd_direct<T, KK, PL, COB>), grid, block, 0, s, a.in, a.out, a.mask, a.osign, a.rect, a.own, w, b, a.Cin, a.Cout, a.Hc, a.Wc, a.slope, a.M, a.batch)
-    if (a.K == 3) { if (a.pooled) FTP_FWD(3, true); else FTP_FWD(3, false); }
-    else          { if (a.pooled) FTP_FWD(1, true); else FTP_FWD(1, false); }
+#define FTP_FWD(KK, SS, PL) hipLaunchKernelGGL((k_conv_fwd_direct<T, KK, SS, PL, COB>), grid, block, 0, s, a.in, a.out, a.mask, a.osign, a.rect, a.own, w, b, a.Cin, a.Cout, a.Hi, a.Wi, a.slope, a.M, a.batch)
+    FTP_GEOMETRY(FTP_FWD);
 #undef FTP_FWD
 }
 
@@ -339,9 +356,8 @@ void conv_bwd_data_t(const ConvArgs& a, hipStream_t s)
     constexpr int CIB = 8;
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cin + CIB - 1) / CIB, a.N * a.M * a.batch), block(64);
     const T* w = (const T*)a.w;
-#define FTP_BWD(KK, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, PL, CIB>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch)
-    if (a.K == 3) { if (a.pooled) FTP_BWD(3, true); else FTP_BWD(3, false); }
-    else          { if (a.pooled) FTP_BWD(1, true); else FTP_BWD(1, false); }
+#define FTP_BWD(KK, SS, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, SS, PL, CIB>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch)
+    FTP_GEOMETRY(FTP_BWD);
 #undef FTP_BWD
 }
 
@@ -349,9 +365,8 @@ template <typename T>
 void wgrad_t(const ConvArgs& a, hipStream_t s)
 {
     dim3 grid(a.Cin, a.Cout, a.N * a.M), block(256);
-#define FTP_WG(KK, PL) hipLaunchKernelGGL((k_wgrad_direct<T, KK, PL>), grid, block, 0, s, a.in, a.din, a.mask, a.rect, a.partial, a.n_params, a.w_off, a.b_off, a.has_bias, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch)
-    if (a.K == 3) { if (a.pooled) FTP_WG(3, true); else FTP_WG(3, false); }
-    else          { if (a.pooled) FTP_WG(1, true); else FTP_WG(1, false); }
+#define FTP_WG(KK, SS, PL) hipLaunchKernelGGL((k_wgrad_direct<T, KK, SS, PL>), grid, block, 0, s, a.in, a.din, a.mask, a.rect, a.partial, a.n_params, a.w_off, a.b_off, a.has_bias, a.Cin, a.Cout, a.Hi, a.Wi, a.Hc, a.Wc, a.M, a.batch)
+    FTP_GEOMETRY(FTP_WG);
 #undef FTP_WG
 }
 
@@ -373,8 +388,8 @@ void pool_bwd(const PoolArgs& a, hipStream_t s)
 {
     g_kernel_label = "k_pool_bwd";
     dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
-    if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.M, a.batch);
-    else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.M, a.batch);
+    if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.Ho, a.Wo, a.M, a.batch);
+    else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.Ho, a.Wo, a.M, a.batch);
 }
 
 // 4 consecutive elements of one (image, channel) plane per thread (HW is a multiple of 4: the rows of a plane and of

@@ -35,7 +35,9 @@ struct ConvArgs {
     long long n_params = 0, w_off = 0, b_off = 0;
     int has_bias = 0;
     int K = 3, Cin = 0, Cout = 0;
-    int Hc = 0, Wc = 0;             // map extent at the convolution (input = output, stride 1)
+    int S = 1;                      // stride
+    int Hc = 0, Wc = 0;             // map extent at the convolution output (before the pool)
+    int Hi = 0, Wi = 0;             // map extent at the convolution input (equal to the output for stride 1)
     int pooled = 0;
     float slope = 0.1f;
     int N = 1, M = 1, batch = 1;
@@ -50,6 +52,7 @@ struct PoolArgs {
     float in_slope = 1.0f;
     RectTab rect, own;
     int C = 0, N = 1, M = 1, batch = 1, bf16 = 0;
+    int Ho = 0, Wo = 0;             // pooled map extent (floor of half the input extent)
 };
 
 // w[i] <- w[i] - lr * sum over stacks of partial[stack][i] (pairwise order of reduce_wgrad), i < count; partial and

@@ -16,8 +16,8 @@ inline Seg clampseg(Seg s, int len) { return Seg{std::max(s.a, 0), std::min(s.b,
 inline Seg hull(Seg p, Seg q) { return Seg{std::min(p.a, q.a), std::max(p.b, q.b)}; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// Eq. (1): interval at the input of `ly` that an output interval depends on.  A pool has no kernel
-// overlap: its windows are exactly [2a, 2b+1].
+// Eq. (1): interval at the input of `ly` that an output interval depends on (Eq. (1c-d) with its (S - 1) term, as
+// printed).  A pool has no kernel overlap: its windows are exactly [2a, 2b+1].
 inline Seg dep_back(Seg o, const ftp_layer& ly)
 {
     if (ly.kind == FTP_CONV) {
@@ -32,6 +32,14 @@ inline Seg own_back(Seg o, const ftp_layer& ly)
 {
     const int S = ly.stride;
     return Seg{o.a * S, o.b * S + (S - 1)};
+}
+
+// A pool on an odd length drops the last position; the tile that reaches the last pooled position keeps it, so
+// that the owned intervals still cover the map (it is produced by the layer before; its delta is zero).
+inline Seg keep_dropped(Seg back, Seg o, const ftp_layer& ly, int out_len, int in_len)
+{
+    if (ly.kind == FTP_MAXPOOL && o.b == out_len - 1) back.b = in_len - 1;
+    return back;
 }
 
 // Eq. (2): delta interval at the output of `ly` that a delta interval at its input depends on.
@@ -59,8 +67,10 @@ int fill_group(const Plan& p, GroupRects& g)
             g.at(FTP_RECT_OWN, g.e, dim, t) = o;
             g.at(FTP_RECT_FWD, g.e, dim, t) = o;
             for (int l = g.e; l > g.s; --l) {
-                g.at(FTP_RECT_OWN, l - 1, dim, t) = clampseg(own_back(g.at(FTP_RECT_OWN, l, dim, t), p.layers[l - 1]), len(l - 1));
-                g.at(FTP_RECT_FWD, l - 1, dim, t) = clampseg(dep_back(g.at(FTP_RECT_FWD, l, dim, t), p.layers[l - 1]), len(l - 1));
+                const ftp_layer& ly = p.layers[l - 1];
+                const Seg o1 = g.at(FTP_RECT_OWN, l, dim, t), f1 = g.at(FTP_RECT_FWD, l, dim, t);
+                g.at(FTP_RECT_OWN, l - 1, dim, t) = clampseg(keep_dropped(own_back(o1, ly), o1, ly, len(l), len(l - 1)), len(l - 1));
+                g.at(FTP_RECT_FWD, l - 1, dim, t) = clampseg(keep_dropped(dep_back(f1, ly), f1, ly, len(l), len(l - 1)), len(l - 1));
             }
             g.at(FTP_RECT_BWD, g.s, dim, t) = g.at(FTP_RECT_OWN, g.s, dim, t);
             for (int l = g.s; l < g.e; ++l)
@@ -120,15 +130,17 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
         const ftp_layer& ly = p.layers[l];
         const int c = p.C.back(), h = p.H.back(), w = p.W.back();
         if (ly.kind == FTP_CONV) {
-            if (ly.stride != 1 || (ly.k != 1 && ly.k != 3) || ly.pad != ly.k / 2) return fail(FTP_EUNSUPPORTED);
+            if ((ly.stride != 1 && ly.stride != 2) || (ly.k != 1 && ly.k != 3 && ly.k != 5 && ly.k != 7) || ly.pad != ly.k / 2)
+                return fail(FTP_EUNSUPPORTED);
             if (!(ly.leaky_slope >= 0.0f) || !std::isfinite(ly.leaky_slope)) return fail(FTP_EUNSUPPORTED);
             if (ly.cout < 1) return fail(FTP_EINVAL);
             if (ly.cin != c) return fail(FTP_ECHANNELS);
-            p.C.push_back(ly.cout); p.H.push_back(h); p.W.push_back(w);
+            p.C.push_back(ly.cout);
+            p.H.push_back((h + 2 * ly.pad - ly.k) / ly.stride + 1); p.W.push_back((w + 2 * ly.pad - ly.k) / ly.stride + 1);
         } else if (ly.kind == FTP_MAXPOOL) {
             if (ly.k != 2 || ly.stride != 2 || ly.pad != 0) return fail(FTP_EUNSUPPORTED);
             if (ly.cin != c || ly.cout != c) return fail(FTP_ECHANNELS);
-            if ((h & 1) || (w & 1)) return fail(FTP_EGRID);
+            if (h < 2 || w < 2) return fail(FTP_EGRID);
             p.C.push_back(c); p.H.push_back(h / 2); p.W.push_back(w / 2);
         } else {
             return fail(FTP_EUNSUPPORTED);

@@ -41,8 +41,9 @@ def oracle_run(oracle, cfg, x, ws, bs, dy, want_db=False):
 
 
 def pool_gap(a):
-    """Top-2 gap of every 2x2 window of a map (n, c, h, w) -> (n, c, h/2, w/2)."""
+    """Top-2 gap of every 2x2 window of a map (n, c, h, w) -> (n, c, floor(h/2), floor(w/2))."""
     n, c, h, w = a.shape
+    a = a[:, :, :h // 2 * 2, :w // 2 * 2]            # an odd map's last row / column lies in no window
     win = a.reshape(n, c, h // 2, 2, w // 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(n, c, h // 2, w // 2, 4)
     srt = np.sort(win, axis=-1)
     return srt[..., 3] - srt[..., 2]
