@@ -114,6 +114,15 @@ def config5(group_size=4):
                   uniform_groups(16, group_size), dtype="bf16")
 
 
+def general_stem():
+    """General-geometry workload (not one of the paper's networks): a 7x7 stride-2 stem on an odd-sized image,
+    strided 3x3 convolutions in place of two pools, a 5x5 layer and a pool that meets an odd map (19 -> 9)."""
+    layers = (conv(3, 64, 7, stride=2), pool(64), conv(64, 64),
+              conv(64, 128, 3, stride=2), conv(128, 64, 1), conv(64, 128, 5),
+              pool(128), conv(128, 256, 3, stride=2), pool(256), conv(256, 256))
+    return Config("gen_stem", 32, 3, 607, 607, layers, (3, 3), (3, 6, 10))
+
+
 ALL = {
     "tiny": tiny,
     "cfg2_perblock": lambda: config2(False),
@@ -121,6 +130,7 @@ ALL = {
     "cfg3": config3,
     "cfg4": config4,
     "cfg5": config5,
+    "gen_stem": general_stem,
 }
 
 

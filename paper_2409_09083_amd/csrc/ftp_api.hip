@@ -67,8 +67,9 @@ bool use_mfma()
     return on;
 }
 
-// The matrix-core and thin-layer kernels are written for the geometry of the paper's networks: stride 1, K <= 3
-// and, behind the convolution, a pool over an even map.  Everything else runs on the general direct kernels.
+// The thin-layer kernels and the matrix-core filter gradient are written for the geometry of the paper's networks:
+// stride 1, K <= 3 and, behind the convolution, a pool over an even map (the matrix-core convolution states its own
+// limits).  Everything else runs on the general direct kernels.
 bool plain_geometry(const ConvArgs& a)
 {
     return a.S == 1 && a.K <= 3 && !(a.pooled && ((a.Hc | a.Wc) & 1));
@@ -254,7 +255,7 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
             a.rect = make_rect(p, u.group, FTP_RECT_FWD, u.bo);
             a.own = make_rect(p, u.group, FTP_RECT_OWN, u.bo);
             const bool fast = use_mfma() && plain_geometry(a);
-            if (fast && mfma_conv_eligible(a, false)) {
+            if (use_mfma() && mfma_conv_eligible(a, false)) {
                 float* wt = (float*)((char*)workspace + u.wt_fwd_offset);
                 const RectTab ext = view_extent(p, u.in_act, u.group, u.bi);
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] {
@@ -302,18 +303,19 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             ConvArgs a = conv_args(p, u, ub, weights, nullptr);
             a.partial = wgrad_partials;
             a.rect = make_rect(p, u.group, FTP_RECT_OWN, u.layer + 1);
+            a.own = make_rect(p, u.group, FTP_RECT_OWN, u.layer);
             float* scratch = (float*)((char*)workspace + p.wgrad_scratch_offset);
             const bool fast = use_mfma() && plain_geometry(a);
             if (fast && thin_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { thin_wgrad(a, scratch, s); });
-            } else if (fast && mfma_wgrad_eligible(a)) {
+            } else if (use_mfma() && mfma_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { mfma_wgrad(a, scratch, s); });
             } else {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { direct_wgrad(a, s); });
             }
             if (rc != FTP_OK) return rc;
             a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
-            if (fast && mfma_conv_eligible(a, true)) {
+            if (use_mfma() && mfma_conv_eligible(a, true)) {
                 float* wt = (float*)((char*)workspace + u.wt_bwd_offset);
                 const RectTab ext = view_extent(p, u.in_delta, u.group, u.bo);
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] {
@@ -422,7 +424,7 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
                 t.bytes_per_launch = out_el * (2.0 * es + 1.0);
             } else if (u->kind == UNIT_CONV) {
                 const double wel = (double)ly.cout * ly.cin * ly.k * ly.k;
-                t.flops_per_launch = 2.0 * wel * B * p.H[g.layer] * p.W[g.layer];
+                t.flops_per_launch = 2.0 * wel * B * p.H[g.layer + 1] * p.W[g.layer + 1];
                 if (g.pass == FTP_PASS_CONV_FWD) t.bytes_per_launch = (in_el + out_el + wel) * es + out_el * has_arg;
                 else if (g.pass == FTP_PASS_CONV_BWD_DATA) t.bytes_per_launch = (in_el + 2.0 * out_el + wel) * es + out_el * has_arg;
                 else t.bytes_per_launch = (in_el + 2.0 * out_el) * es + out_el * has_arg + stacks * wel * 4.0;
@@ -440,8 +442,8 @@ const char* ftp_strerror(int code)
     switch (code) {
         case FTP_OK: return "ok";
         case FTP_EINVAL: return "invalid argument";
-        case FTP_EUNSUPPORTED: return "unsupported layer (conv needs stride 1, K in {1,3}, pad K/2, slope >= 0; pool needs 2x2 stride 2)";
-        case FTP_EGRID: return "tile grid does not fit the maps (empty tile, odd map before a pool, or more than 16 tiles per side)";
+        case FTP_EUNSUPPORTED: return "unsupported layer (conv needs stride 1 or 2, K in {1,3,5,7}, pad K/2, slope >= 0; pool needs 2x2 stride 2)";
+        case FTP_EGRID: return "tile grid does not fit the maps (empty tile, map too small for its pool, or more than 16 tiles per side)";
         case FTP_EGROUPS: return "group ends must be strictly increasing and end at the number of layers";
         case FTP_ENOMEM: return "host allocation failed";
         case FTP_EHIP: return "HIP call failed";

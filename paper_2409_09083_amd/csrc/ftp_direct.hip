@@ -331,10 +331,11 @@ inline int rect_max_px(const RectTab& rt, int N, int M)
     return mw * mh;
 }
 
-// Picks the instantiation for (K, stride, pooled); the planner admits K in {1, 3, 5, 7} and stride in {1, 2} only.
+// Picks the instantiation for (K, stride, pooled); the planner admits K in {1, 3, 5, 7} and stride in {1, 2} only,
+// and fuses a pool into the convolution in front of it only for stride 1 and K <= 3.
 #define FTP_GEOMETRY_S(LAUNCH, KK) \
-    do { if (a.S == 2) { if (a.pooled) LAUNCH(KK, 2, true); else LAUNCH(KK, 2, false); } \
-         else          { if (a.pooled) LAUNCH(KK, 1, true); else LAUNCH(KK, 1, false); } } while (0)
+    do { if (a.pooled) { if constexpr ((KK) <= 3) LAUNCH(KK, 1, true); } \
+         else if (a.S == 2) LAUNCH(KK, 2, false); else LAUNCH(KK, 1, false); } while (0)
 #define FTP_GEOMETRY(LAUNCH) \
     do { switch (a.K) { case 1: FTP_GEOMETRY_S(LAUNCH, 1); break; case 3: FTP_GEOMETRY_S(LAUNCH, 3); break; \
                         case 5: FTP_GEOMETRY_S(LAUNCH, 5); break; default: FTP_GEOMETRY_S(LAUNCH, 7); break; } } while (0)

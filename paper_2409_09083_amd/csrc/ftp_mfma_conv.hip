@@ -92,12 +92,12 @@ __device__ __forceinline__ TilePix tile_pix(const TileGeom& g, int wq, int x1)
 // Epilogue shared by the convolution kernels: bias, leaky ReLU, the fused 2x2 max-pool, the decision codes and
 // the stores.  A lane holds, per 32x32 tile, 16 channels (8*(i/4) + 4*hi + i%4) of one pixel.  `bias_lds` is LDS
 // no wavefront reads any more once all of them have arrived here (BM floats are used).
-template <typename T, int K, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, int NT>
+template <typename T, int K, int S, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, int NT>
 __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileGeom& g, v16f (&acc)[MT][NT], float* bias_lds,
                                               int m0, int x0, int x1, int y0, int stack, int ti, int tj)
 {
     constexpr int BM = 32 * MT * WAVES_M;
-    constexpr int P = K / 2, S = POOL_OUT ? 2 : 1;
+    constexpr int P = K / 2;                           // S: patch positions per tile pixel and dimension (pool or stride)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
@@ -201,25 +201,36 @@ constexpr unsigned kOobOffset = 0x80000000u;          // beyond the records of e
 constexpr unsigned kBufRecords = 0x7FFFFFFFu;
 // Reduction channels per stage: the same for every workgroup shape, so that the summation order, and with it every
 // bit of the result, does not depend on which shape the launch heuristics pick (they look at the batch size).
-__host__ __device__ constexpr int conv_dl_stage_channels(int K, int /*BM*/) { return K == 1 ? 16 : 4; }
-__host__ __device__ constexpr int conv_dl_max_positions(int K, int BN) { return K == 1 ? 256 : (BN == 256 ? 512 : 256); }   // patch positions in LDS
+// (5x5 and 7x7 filters take 2 channels per stage so that a slice of all taps still fits; a strided forward pass
+// reads a patch four times the size of its tile.)
+__host__ __device__ constexpr int conv_dl_stage_channels(int K, bool strided_fwd) { return K >= 5 ? 2 : (K == 1 && !strided_fwd) ? 16 : 4; }
+__host__ __device__ constexpr int conv_dl_max_positions(int K, int BN, bool strided_fwd)          // patch positions in LDS
+{
+    return strided_fwd ? 768 : K >= 5 ? (BN == 256 ? 768 : 512) : K == 1 ? 256 : (BN == 256 ? 512 : 256);
+}
 
 // POOL_IN (delta back-propagation through a fused pool): the patch lives at the convolution output, the delta at
 // pooled resolution; a patch position receives its window's delta only if it is the window's winner for that
 // channel.  The winner codes of the stage after next are loaded into registers one stage ahead, and a lane whose
 // position lost simply loads from an out-of-range offset (= 0).
-template <typename T, int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+// STRIDE = 2, forward: output pixel (y, x) reads the patch at (2y, 2x), as the first pixel of a pool window does.
+// STRIDE = 2, delta back-propagation: the adjoint of a strided convolution is the stride-1 one applied to the
+// deltas with zeros inserted between them; a patch position at even coordinates loads delta (y/2, x/2), every
+// other one loads from an out-of-range offset (three quarters of the matrix-core work multiply zeros).
+template <typename T, int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE>
 __global__ void __launch_bounds__(256, 2)
 k_conv_mfma_dl(MfmaConvArgs a)
 {
+    static_assert(STRIDE == 1 || !(POOL_OUT || POOL_IN), "strided convolutions with a fused pool take the direct kernels");
+    constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN, UP_IN = STRIDE == 2 && DELTA_IN, HALF_IN = POOL_IN || UP_IN;
     constexpr unsigned ES = sizeof(T);                 // bytes per map element
     constexpr int WAVES_N = 4 / WAVES_M;
     constexpr int NT = BN / 32 / WAVES_N;
     constexpr int BM = 32 * MT * WAVES_M;
-    constexpr int kCK = conv_dl_stage_channels(K, BM);
+    constexpr int kCK = conv_dl_stage_channels(K, STRIDED_FWD);
     constexpr int KK = K * K, P = K / 2;
-    constexpr int S = POOL_OUT ? 2 : 1;
-    constexpr int XMAX = conv_dl_max_positions(K, BN);
+    constexpr int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
+    constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD);
     constexpr int MAXPOS = XMAX / 256;
     constexpr int WF = KK * kCK * BM;                  // floats of one filter slice [tap][channel][BM]
     constexpr int WPIECES = WF / 64;                   // 64-float pieces of the slice, dealt round-robin to the 4 wavefronts
@@ -269,9 +280,9 @@ k_conv_mfma_dl(MfmaConvArgs a)
             }
             const int gy = y0 * S + ybase + lr - P, gx = g.ox0 * S - P + c;
             if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc) {
-                const int sy = POOL_IN ? (gy >> 1) : gy, sx = POOL_IN ? (gx >> 1) : gx;
+                const int sy = HALF_IN ? (gy >> 1) : gy, sx = HALF_IN ? (gx >> 1) : gx;
                 // positions no valid output pixel of this stack reads may lie outside the view
-                if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj]) {
+                if (sy >= a.iy0[ti] && sy <= a.iy1[ti] && sx >= a.ix0[tj] && sx <= a.ix1[tj] && !(UP_IN && ((gy | gx) & 1))) {
                     xoff[j] = ES * (unsigned)(k * (int)sv.ns + (sy - sv.y0[ti]) * sv.pitch + (sx - sv.x0[tj]));
                     if (POOL_IN) moff[j] = (k * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj]))
                                            | ((((gy & 1) << 1) | (gx & 1)) << 29);
@@ -385,7 +396,7 @@ k_conv_mfma_dl(MfmaConvArgs a)
             multiply(bufB);
         }
     }
-    conv_epilogue<T, K, WAVES_M, MT, POOL_OUT, DELTA_IN>(a, g, acc, bufA, m0, x0, x1, y0, stack, ti, tj);
+    conv_epilogue<T, K, S, WAVES_M, MT, POOL_OUT, DELTA_IN>(a, g, acc, bufA, m0, x0, x1, y0, stack, ti, tj);
 }
 
 // ---- host side ------------------------------------------------------------------------------------------------
@@ -428,26 +439,38 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
 }
 
 // Largest byte offset a workgroup forms from its base pointer: the images a tile can span plus all channels.
-bool offsets_fit_32bit(const MfmaConvArgs& a, const View& v, int max_img)
+bool offsets_fit_32bit(const MfmaConvArgs& a, const View& v, int max_img, int K)
 {
     const double bytes = 4.0 * ((double)max_img * (double)v.ns + (double)a.C * (double)v.cs);      // (fp32 element size as the bound)
-    return bytes < 2.0e9 && 4.0 * 9.0 * (double)a.C * (double)a.Mtot < 2.0e9;
+    return bytes < 2.0e9 && 4.0 * K * K * (double)a.C * (double)a.Mtot < 2.0e9;
 }
 
 // Workgroup shapes of the direct-load kernel: output channels x pixels, and the workgroups of each that share a CU.
 struct DlShape { int BM, BN, per_cu; };
 
-template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+// The largest workgroup whose filter slice (all taps of a stage) still fits LDS next to the patch.
+constexpr int conv_dl_max_bm(int K) { return K >= 7 ? 64 : 128; }
+
+template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE>
 void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 {
-    static char label[6][80];
+    static char label[6][96];
     const int v = (sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1);
-    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%s, %d, %d, %d, %d, %s, %s, %s>", sizeof(T) == 4 ? "float" : "unsigned short",
-                  K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN, POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false", POOL_IN ? "true" : "false");
+    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%s, %d, %d, %d, %d, %s, %s, %s, %d>", sizeof(T) == 4 ? "float" : "unsigned short",
+                  K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN, POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false",
+                  POOL_IN ? "true" : "false", STRIDE);
     g_kernel_label = label[v];
-#define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN>), grid, dim3(256), 0, s, a)
-    if (sh.BN == 256) { if (sh.BM == 128) FTP_DL(2, 2, 256); else if (sh.BM == 64) FTP_DL(1, 2, 256); else FTP_DL(1, 1, 256); }
-    else              { if (sh.BM == 128) FTP_DL(2, 2, 128); else if (sh.BM == 64) FTP_DL(1, 2, 128); else FTP_DL(1, 1, 128); }
+    constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN;
+#define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE>), grid, dim3(256), 0, s, a)
+    if (sh.BN == 256) {
+        if constexpr (!STRIDED_FWD) {
+            if (sh.BM == 128) { if constexpr (conv_dl_max_bm(K) >= 128) FTP_DL(2, 2, 256); }
+            else if (sh.BM == 64) FTP_DL(1, 2, 256); else FTP_DL(1, 1, 256);
+        }
+    } else {
+        if (sh.BM == 128) { if constexpr (conv_dl_max_bm(K) >= 128) FTP_DL(2, 2, 128); }
+        else if (sh.BM == 64) FTP_DL(1, 2, 128); else FTP_DL(1, 1, 128);
+    }
 #undef FTP_DL
 }
 
@@ -455,17 +478,19 @@ void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 // matrix-core work (BM x BN x reduction), `per_cu` of them share one CU's matrix cores, and the last, partly
 // filled round of a launch leaves CUs idle: few large workgroups waste most there, many small ones least, while
 // larger ones re-read less.  cost = (full rounds + the last round's depth per CU) x work of one workgroup.
-template <int K, bool POOL_OUT>
+template <int K, bool POOL_OUT, bool STRIDED_FWD>
 DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc_out)
 {
-    const int S = POOL_OUT ? 2 : 1;
+    const int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
     DlShape best = {0, 0, 0}; double best_cost = 0;
     // as many output channels per workgroup as the layer has (up to 128): every further channel block re-reads the
     // whole input patch, and with many blocks in flight the filter no longer stays in the L2 cache
-    const int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
-    for (int BN = 256; BN >= 128; BN /= 2) {
-            const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, conv_dl_max_positions(K, BN));
-            if (tc.cs > conv_dl_max_positions(K, BN)) continue;
+    int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
+    if (BM > conv_dl_max_bm(K)) BM = conv_dl_max_bm(K);
+    for (int BN = STRIDED_FWD ? 128 : 256; BN >= 128; BN /= 2) {
+            const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD);
+            const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos);
+            if (tc.cs > max_pos) continue;
             // tiles that exist: every stack has its own count, the grid is sized for the largest
             long long wgs = 0;
             for (int i = 0; i < c.N; ++i)
@@ -491,24 +516,25 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc
 
 // Returns non-zero if the layer's geometry does not fit the kernel (offsets beyond 32 bits, a row of some stack
 // wider than the patch buffer); the caller then uses a direct kernel.
-template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE>
 int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
 {
+    constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN;
     TileChoice td;
-    const DlShape sh = choose_dl_shape<K, POOL_OUT>(a, c, &td);
+    const DlShape sh = choose_dl_shape<K, POOL_OUT, STRIDED_FWD>(a, c, &td);
     if (!sh.BM) return 1;
     // (the kernel keeps code-map offsets in 29 bits)
     if (POOL_IN && DELTA_IN && (double)td.max_img * (double)a.mask.ns >= 5.0e8) return 1;
-    if (!offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img)) return 1;
+    if (!offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img, K)) return 1;
     a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = (td.cs + 63) & ~63;
-    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
+    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN, STRIDE>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
     return 0;
 }
 
-template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN>
+template <int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE = 1>
 int launch_m(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
 {
-    return c.bf16 ? launch_t<bf16_t, K, POOL_OUT, DELTA_IN, POOL_IN>(a, c, s) : launch_t<float, K, POOL_OUT, DELTA_IN, POOL_IN>(a, c, s);
+    return c.bf16 ? launch_t<bf16_t, K, POOL_OUT, DELTA_IN, POOL_IN, STRIDE>(a, c, s) : launch_t<float, K, POOL_OUT, DELTA_IN, POOL_IN, STRIDE>(a, c, s);
 }
 
 void fill_common(MfmaConvArgs& a, const ConvArgs& c, const RectTab& inrect)
@@ -521,9 +547,13 @@ void fill_common(MfmaConvArgs& a, const ConvArgs& c, const RectTab& inrect)
 
 }  // namespace
 
+// Geometry: stride 1 with K = 1, 3 (with or without the fused pool over an even map) or K = 5, 7 (no fused pool);
+// stride 2 with K = 1, 3 and no fused pool.
 bool mfma_conv_eligible(const ConvArgs& a, bool backward)
 {
     const int Mtot = backward ? a.Cin : a.Cout, C = backward ? a.Cout : a.Cin;
+    if (a.pooled && (a.S != 1 || a.K > 3 || ((a.Hc | a.Wc) & 1))) return false;
+    if (a.S == 2 && a.K > 3) return false;
     return Mtot >= 16 && Mtot % 4 == 0 && C >= 8;
 }
 
@@ -543,6 +573,10 @@ int mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hip
     fill_common(a, c, inrect);
     a.wt = wt; a.bias = c.bias;
     a.C = c.Cin; a.Mtot = c.Cout;
+    a.Hc = c.Hi; a.Wc = c.Wi;                           // the patch is cut from the input map
+    if (c.S == 2) return c.K == 3 ? launch_m<3, false, false, false, 2>(a, c, s) : launch_m<1, false, false, false, 2>(a, c, s);
+    if (c.K == 7) return launch_m<7, false, false, false>(a, c, s);
+    if (c.K == 5) return launch_m<5, false, false, false>(a, c, s);
     if (c.K == 3) return c.pooled ? launch_m<3, true, false, false>(a, c, s) : launch_m<3, false, false, false>(a, c, s);
     return c.pooled ? launch_m<1, true, false, false>(a, c, s) : launch_m<1, false, false, false>(a, c, s);
 }
@@ -555,6 +589,12 @@ int mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt
     fill_common(a, c, inrect);
     a.wt = wt; a.bias = nullptr;
     a.C = c.Cout; a.Mtot = c.Cin;
+    // the patch is cut from the deltas as the stride-1 convolution sees them: at the convolution output (stride 1,
+    // also through a pool), or with zeros inserted between them (stride 2: twice the extent)
+    a.Hc = c.S == 2 ? 2 * c.Hc : c.Hc; a.Wc = c.S == 2 ? 2 * c.Wc : c.Wc;
+    if (c.S == 2) return c.K == 3 ? launch_m<3, false, true, false, 2>(a, c, s) : launch_m<1, false, true, false, 2>(a, c, s);
+    if (c.K == 7) return launch_m<7, false, true, false>(a, c, s);
+    if (c.K == 5) return launch_m<5, false, true, false>(a, c, s);
     if (c.K == 3) return c.pooled ? launch_m<3, false, true, true>(a, c, s) : launch_m<3, false, true, false>(a, c, s);
     return c.pooled ? launch_m<1, false, true, true>(a, c, s) : launch_m<1, false, true, false>(a, c, s);
 }

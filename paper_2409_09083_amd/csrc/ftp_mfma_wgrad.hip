@@ -6,6 +6,13 @@
 // (channel contiguous) so that v_mfma_f32_32x32x2_f32 finds A[m = co][k = pixel] and B[k = pixel][n = ci]
 // at consecutive addresses: dZ as [pixel][co], X as [(row, column) incl. filter halo][ci].
 // Rows are padded to an even number of pixels (dZ = 0 there) because one MFMA consumes two pixels.
+// HALF: 0 = the deltas sit at the resolution of the owned rectangle; 1 = a pool follows the convolution: the
+// rectangle is at the convolution output, the deltas at pooled resolution, and a pixel receives its window's delta
+// only if it is the window's winner; 2 = stride-2 convolution: the rectangle is the stack's owned part of the
+// *input* map and pixel (y, x) carries delta (y/2, x/2) if both are even, else zero (the filter gradient of a strided
+// convolution is the stride-1 one of the deltas with zeros in between; three quarters of the products are zero).
+// TROWS: filter rows per workgroup (5x5: 2, 7x7: 1, else all): one accumulator tile per tap has to fit the registers,
+// so larger filters are split over blockIdx.x, each part staging the same chunks.
 #include "ftp_device.h"
 #include "ftp_launch.h"
 
@@ -14,18 +21,19 @@ namespace ftp {
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 // LDS positions of one staged chunk: pixels of dZ, patch positions of X (a multiple of 64).
-constexpr int kWgradZPos = 64, kWgradXPos = 192;      // the limits wgrad_chunks() cuts to
+constexpr int kWgradZPos = 64;                         // the limits wgrad_chunks() cuts to: this and wgrad_xpos(P)
 
-template <typename T, int K, int WAVES_CO, int WAVES_CI, bool POOL>
+template <typename T, int K, int WAVES_CO, int WAVES_CI, int HALF, int TROWS>
 __global__ void __launch_bounds__(256, 2)
 k_wgrad_mfma(MfmaWgradArgs a)
 {
+    constexpr bool POOL = HALF == 1;
     constexpr int WAVES_K = 4 / (WAVES_CO * WAVES_CI);
-    constexpr int KK = K * K, P = K / 2;
+    constexpr int KK = K * K, P = K / 2, NTAP = TROWS * K;
     constexpr int BCO = 32 * WAVES_CO, BCI = 32 * WAVES_CI;
     constexpr int ZP = BCO + 1, XP = BCI + 1;          // odd strides: conflict-free transposing writes
     constexpr int NZ = BCO / 4, NX = BCI / 4;          // channels each wavefront stages
-    constexpr int ZPOS = kWgradZPos, XPOS = kWgradXPos, XPASS = XPOS / 64;
+    constexpr int ZPOS = kWgradZPos, XPOS = wgrad_xpos(P), XPASS = XPOS / 64;
 
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -35,8 +43,10 @@ k_wgrad_mfma(MfmaWgradArgs a)
     const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.own.x0[tj], x1 = a.own.x1[tj], y0 = a.own.y0[ti], y1 = a.own.y1[ti];
     const int rw = x1 - x0 + 1, rh = y1 - y0 + 1;
-    const int tiles_ci = (a.Cin + BCI - 1) / BCI;
-    const int co0 = (blockIdx.x / tiles_ci) * BCO, ci0 = (blockIdx.x % tiles_ci) * BCI;
+    const int tiles_ci = (a.Cin + BCI - 1) / BCI, tiles = tiles_ci * ((a.Cout + BCO - 1) / BCO);
+    const int tile = TROWS == K ? blockIdx.x : blockIdx.x % tiles;
+    const int trow0 = TROWS == K ? 0 : (blockIdx.x / tiles) * TROWS;       // first filter row of this workgroup
+    const int co0 = (tile / tiles_ci) * BCO, ci0 = (tile % tiles_ci) * BCI;
     const int split = blockIdx.y;
 
     // Chunk geometry of this stack: TI images x TR rows x TC columns of the owned rectangle, at most ZPOS
@@ -48,9 +58,9 @@ k_wgrad_mfma(MfmaWgradArgs a)
     float* Zl = lds;                                   // [pixel][ZP]
     float* Xl = lds + ZPOS * ZP;                       // [patch position][XP]
 
-    v16f acc[KK];
+    v16f acc[NTAP];
 #pragma unroll
-    for (int t = 0; t < KK; ++t)
+    for (int t = 0; t < NTAP; ++t)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
 
@@ -81,7 +91,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
             const int row = p / TCp, zc = p - row * TCp;
             const int il = row / c.nr, r = row - il * c.nr;
             const int qy = c.yb + r, qx = c.xb + (zc < c.nc ? zc : c.nc - 1);
-            const int sy = POOL ? (qy >> 1) : qy, sx = POOL ? (qx >> 1) : qx;
+            const int sy = HALF ? (qy >> 1) : qy, sx = HALF ? (qx >> 1) : qx;
             zinfo = (ok ? 1 : 0) | (zc >= c.nc ? 2 : 0) | ((((qy & 1) << 1) | (qx & 1)) << 2);
             const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, c.n0 + il, 0, sy, sx);
             const T* gp = at<T>(a.din, stack, ti, tj, c.n0 + il, 0, sy, sx);
@@ -130,6 +140,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
                 const int ch = wave + 4 * k;
                 float v = zg[k];                                       // the delta maps hold dLoss/dZ
                 if (POOL && ((zm[k] >> 1) & 3) != (uint32_t)code) v = 0.0f;
+                if (HALF == 2 && code != 0) v = 0.0f;
                 if ((zinfo & 2) || co0 + ch >= a.Cout) v = 0.0f;
                 zdst[ch] = v;
             }
@@ -158,8 +169,9 @@ k_wgrad_mfma(MfmaWgradArgs a)
             for (int xp = 2 * wave_k; xp < ncp; xp += 2 * WAVES_K) {
                 const float av = zrow[xp * ZP];
 #pragma unroll
-                for (int t = 0; t < KK; ++t) {
-                    const float bv = xrow[((t / K) * PW + xp + (t % K)) * XP];
+                for (int t = 0; t < NTAP; ++t) {
+                    if (TROWS != K && trow0 + t / K >= K) break;           // (the last part of a split filter may be short)
+                    const float bv = xrow[((trow0 + t / K) * PW + xp + (t % K)) * XP];
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t], 0, 0, 0);
                 }
             }
@@ -192,7 +204,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
         __syncthreads();
         float* red = lds;                               // [WAVES_CO*WAVES_CI][16][64]
 #pragma unroll
-        for (int t = 0; t < KK; ++t) {
+        for (int t = 0; t < NTAP; ++t) {
             if (wave_k == 1) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) red[((wave % (WAVES_CO * WAVES_CI)) * 16 + i) * 64 + lane] = acc[t][i];
@@ -215,7 +227,8 @@ k_wgrad_mfma(MfmaWgradArgs a)
             const int co = co0 + wave_co * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
             if (co < a.Cout && ci < a.Cin) {
 #pragma unroll
-                for (int t = 0; t < KK; ++t) dst[((long long)co * a.Cin + ci) * KK + t] = acc[t][i];
+                for (int t = 0; t < NTAP; ++t)
+                    if (TROWS == K || trow0 + t / K < K) dst[((long long)co * a.Cin + ci) * KK + trow0 * K + t] = acc[t][i];
             }
         }
     }
@@ -235,39 +248,47 @@ k_wgrad_splitk_reduce(const float* __restrict__ scratch, float* __restrict__ par
     partial[(long long)stack * n_params + w_off + i] = v;
 }
 
-// c.rect must hold the owned rectangles.
+// Geometry: stride 1 with K = 1, 3 (with or without the fused pool), K = 5, 7 without; stride 2 with K = 1, 3.
 bool mfma_wgrad_eligible(const ConvArgs& c)
 {
+    if (c.pooled && (c.S != 1 || c.K > 3)) return false;
+    if (c.S == 2 && c.K > 3) return false;
     return !c.has_bias && c.Cout >= 32 && c.Cin >= 16;
 }
 
-// c.rect = owned rectangle at the convolution output (before the pool); scratch holds the batch shares.
+// c.rect = owned rectangle at the convolution output (before the pool), c.own = owned rectangle at the convolution
+// input (used for strided convolutions); scratch holds the batch shares.
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
 {
     MfmaWgradArgs a;
-    a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.rect;
+    a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.S == 2 ? c.own : c.rect;
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
-    a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
+    a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hi; a.Wc = c.Wi; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
     a.splits = c.wgrad_shares;
     a.PK = kWgradZPos;
-    const int waves_ci = c.Cin >= 64 ? 2 : 1;
+    // (64 input channels per workgroup where the patch of a 5x5 / 7x7 filter would not leave LDS for two workgroups)
+    const int waves_ci = (c.Cin >= 64 && c.K <= 3) ? 2 : 1;
     const int BCO = 64, BCI = 32 * waves_ci;
-    const size_t lds = ((size_t)kWgradZPos * (BCO + 1) + (size_t)kWgradXPos * (BCI + 1)) * sizeof(float);
+    const size_t lds = ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1)) * sizeof(float);
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
-    dim3 grid(tiles, a.splits, c.N * c.M), block(256);
+    const int parts = c.K == 5 ? 3 : c.K == 7 ? 7 : 1;                 // filter rows 2 + 2 + 1, or one at a time
+    dim3 grid(tiles * parts, a.splits, c.N * c.M), block(256);
     // more than 64 KB of dynamic LDS has to be granted per kernel, once
-#define FTP_WG1(TT, TN, KK, WCI, PL) do { \
+#define FTP_WG1(TT, TN, KK, WCI, HF, TR) do { \
         static bool granted = false; \
-        if (!granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_mfma<TT, KK, 2, WCI, PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); granted = true; } \
-        g_kernel_label = "k_wgrad_mfma<" TN ", " #KK ", 2, " #WCI ", " #PL ">"; \
-        hipLaunchKernelGGL((k_wgrad_mfma<TT, KK, 2, WCI, PL>), grid, block, lds, s, a); } while (0)
-#define FTP_WG(KK, WCI, PL) do { if (c.bf16) FTP_WG1(bf16_t, "unsigned short", KK, WCI, PL); else FTP_WG1(float, "float", KK, WCI, PL); } while (0)
-    if (c.K == 3) {
-        if (waves_ci == 2) { if (c.pooled) FTP_WG(3, 2, true); else FTP_WG(3, 2, false); }
-        else               { if (c.pooled) FTP_WG(3, 1, true); else FTP_WG(3, 1, false); }
+        if (!granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_mfma<TT, KK, 2, WCI, HF, TR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); granted = true; } \
+        g_kernel_label = "k_wgrad_mfma<" TN ", " #KK ", 2, " #WCI ", " #HF ", " #TR ">"; \
+        hipLaunchKernelGGL((k_wgrad_mfma<TT, KK, 2, WCI, HF, TR>), grid, block, lds, s, a); } while (0)
+#define FTP_WG(KK, WCI, HF, TR) do { if (c.bf16) FTP_WG1(bf16_t, "unsigned short", KK, WCI, HF, TR); else FTP_WG1(float, "float", KK, WCI, HF, TR); } while (0)
+    const int half = c.pooled ? 1 : c.S == 2 ? 2 : 0;
+    if (c.K == 7) FTP_WG(7, 1, 0, 1);
+    else if (c.K == 5) FTP_WG(5, 1, 0, 2);
+    else if (c.K == 3) {
+        if (waves_ci == 2) { if (half == 1) FTP_WG(3, 2, 1, 3); else if (half == 2) FTP_WG(3, 2, 2, 3); else FTP_WG(3, 2, 0, 3); }
+        else               { if (half == 1) FTP_WG(3, 1, 1, 3); else if (half == 2) FTP_WG(3, 1, 2, 3); else FTP_WG(3, 1, 0, 3); }
     } else {
-        if (waves_ci == 2) { if (c.pooled) FTP_WG(1, 2, true); else FTP_WG(1, 2, false); }
-        else               { if (c.pooled) FTP_WG(1, 1, true); else FTP_WG(1, 1, false); }
+        if (waves_ci == 2) { if (half == 1) FTP_WG(1, 2, 1, 1); else if (half == 2) FTP_WG(1, 2, 2, 1); else FTP_WG(1, 2, 0, 1); }
+        else               { if (half == 1) FTP_WG(1, 1, 1, 1); else if (half == 2) FTP_WG(1, 1, 2, 1); else FTP_WG(1, 1, 0, 1); }
     }
 #undef FTP_WG
 #undef FTP_WG1

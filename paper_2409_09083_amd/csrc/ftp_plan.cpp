@@ -191,7 +191,10 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
             u.group = g; u.layer = l; u.bi = l;
             if (p.layers[l].kind == FTP_CONV) {
                 u.kind = UNIT_CONV;
-                u.pooled = (l + 1 < gr.e) && p.layers[l + 1].kind == FTP_MAXPOOL;
+                // the pool behind a convolution is evaluated in its epilogue where the fast kernels can do that:
+                // stride 1, K <= 3, even map; otherwise it stays a step of its own
+                u.pooled = (l + 1 < gr.e) && p.layers[l + 1].kind == FTP_MAXPOOL && p.layers[l].stride == 1 && p.layers[l].k <= 3 &&
+                           !((p.H[l + 1] | p.W[l + 1]) & 1);
                 u.bo = l + 1 + (u.pooled ? 1 : 0);
             } else {
                 u.kind = UNIT_POOL; u.pooled = false; u.bo = l + 1;
@@ -270,12 +273,14 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
         for (Unit& u : p.units) {
             if (u.kind != UNIT_CONV) continue;
             const ftp_layer& ly = p.layers[u.layer];
-            // chunk count of the largest owned rectangle at the convolution output
+            // chunk count of the largest owned rectangle at the convolution output (a strided convolution's filter
+            // gradient runs over the owned input pixels: its deltas are read with zeros in between)
             const GroupRects& gr = p.groups[u.group];
             int chunks = 1;
+            const int wb = ly.stride == 2 ? u.layer : u.layer + 1;
             for (int i = 0; i < N; ++i)
                 for (int j = 0; j < M; ++j) {
-                    const Seg sx = gr.at(FTP_RECT_OWN, u.layer + 1, 0, j), sy = gr.at(FTP_RECT_OWN, u.layer + 1, 1, i);
+                    const Seg sx = gr.at(FTP_RECT_OWN, wb, 0, j), sy = gr.at(FTP_RECT_OWN, wb, 1, i);
                     chunks = std::max(chunks, wgrad_chunks(sx.b - sx.a + 1, sy.b - sy.a + 1, batch, ly.k / 2).total);
                 }
             u.wgrad_shares = wgrad_shares(ly.cout, ly.cin, ly.k, N * M, chunks);

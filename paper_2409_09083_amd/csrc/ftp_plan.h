@@ -92,15 +92,20 @@ struct Plan {
 // of at most 64 pixels (rows padded to an even length) and 192 patch positions: column blocks of TC, row blocks
 // of TR, and, where a whole rectangle is smaller than a chunk, TI images at once.  Used by the kernel and by the
 // host (share count), so both see the same numbers.
+// (Patch positions: 192 up to 3x3 filters, 256 for 5x5 and 7x7.)
+FTP_HD constexpr int wgrad_xpos(int P) { return P <= 1 ? 192 : 256; }
 struct WgradChunks { int col_blocks, TC, TCp, PW, TR, row_blocks, TI, img_blocks, total; };
 FTP_HD inline WgradChunks wgrad_chunks(int rw, int rh, int batch, int P)
 {
-    const int ZPOS = 64, XPOS = 192, MAXC = 64 - 2 * P;      // widest column block: 3 patch rows fit XPOS
+    const int ZPOS = 64, XPOS = wgrad_xpos(P);
+    int MAXC = (XPOS / (1 + 2 * P) - 2 * P) & ~1;            // widest column block: one row of pixels and its halo rows fit XPOS
+    if (MAXC > 64 - 2 * P) MAXC = 64 - 2 * P;
     WgradChunks c;
     c.col_blocks = (rw + MAXC - 1) / MAXC;
     c.TC = (rw + c.col_blocks - 1) / c.col_blocks;
     c.TCp = (c.TC + 1) & ~1; c.PW = c.TCp + 2 * P;
     c.TR = ZPOS / c.TCp; if (c.TR > rh) c.TR = rh;
+    while (c.TR > 1 && (c.TR + 2 * P) * c.PW > XPOS) --c.TR;
     c.row_blocks = (rh + c.TR - 1) / c.TR;
     c.TI = 1;
     if (c.TR == rh && c.col_blocks == 1) {
