@@ -306,7 +306,7 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             a.own = make_rect(p, u.group, FTP_RECT_OWN, u.layer);
             float* scratch = (float*)((char*)workspace + p.wgrad_scratch_offset);
             const bool fast = use_mfma() && plain_geometry(a);
-            if (fast && thin_wgrad_eligible(a)) {
+            if (use_mfma() && thin_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { thin_wgrad(a, scratch, s); });
             } else if (use_mfma() && mfma_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { mfma_wgrad(a, scratch, s); });

@@ -3,6 +3,7 @@
 // One workgroup serves one (stack, image); stacks only read the rectangles the plan entitles them to.
 #include "ftp_device.h"
 #include "ftp_launch.h"
+#include <algorithm>
 
 namespace ftp {
 
@@ -118,20 +119,35 @@ k_conv_bwd_data_direct(View din, View mask, View dout, View isign, int scale_out
     const int ti = stack / M, tj = stack % M;
     const int rw = rt.x1[tj] - rt.x0[tj] + 1, rh = rt.y1[ti] - rt.y0[ti] + 1;
     const int pid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (pid >= rw * rh) return;
-    const int iy = rt.y0[ti] + pid / rw, ix = rt.x0[tj] + pid % rw;
+    int ry, rx;
+    if (S == 2) {
+        // the four parity classes of the rectangle one after the other: neighbouring lanes then use the same taps
+        const int rw2 = (rw + 1) >> 1, rh2 = (rh + 1) >> 1;
+        const int cls = pid / (rw2 * rh2), idx = pid - cls * (rw2 * rh2);
+        ry = 2 * (idx / rw2) + (cls >> 1); rx = 2 * (idx % rw2) + (cls & 1);
+        if (cls >= 4 || ry >= rh || rx >= rw) return;
+    } else {
+        if (pid >= rw * rh) return;
+        ry = pid / rw; rx = pid - ry * rw;
+    }
+    const int iy = rt.y0[ti] + ry, ix = rt.x0[tj] + rx;
     const int ci0 = blockIdx.y * CIB;
     constexpr int P = K / 2;
     float acc[CIB];
 #pragma unroll
     for (int j = 0; j < CIB; ++j) acc[j] = 0.0f;
+    // stride 2: only the taps with ky = (iy + P) mod 2, + 2, ... (and likewise kx) meet an output position
+    constexpr int NTAP = (K + S - 1) / S;
+    const int ky0 = S == 2 ? ((iy + P) & 1) : 0, kx0 = S == 2 ? ((ix + P) & 1) : 0;
     for (int co = 0; co < Cout; ++co) {
 #pragma unroll
-        for (int ky = 0; ky < K; ++ky)
+        for (int my = 0; my < NTAP; ++my)
 #pragma unroll
-            for (int kx = 0; kx < K; ++kx) {
+            for (int mx = 0; mx < NTAP; ++mx) {
+                const int ky = ky0 + S * my, kx = kx0 + S * mx;
+                if (ky >= K || kx >= K) continue;
                 const int sy = iy + P - ky, sx = ix + P - kx;
-                if (sy < 0 || sx < 0 || (S == 2 && ((sy | sx) & 1))) continue;
+                if (sy < 0 || sx < 0) continue;
                 const int qy = sy / S, qx = sx / S;
                 if (qy >= Hc || qx >= Wc) continue;
                 const float dz = delta_z<T, POOL>(din, mask, stack, ti, tj, n, co, qy, qx, Hc >> 1, Wc >> 1);
@@ -355,7 +371,11 @@ template <typename T>
 void conv_bwd_data_t(const ConvArgs& a, hipStream_t s)
 {
     constexpr int CIB = 8;
-    dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, (a.Cin + CIB - 1) / CIB, a.N * a.M * a.batch), block(64);
+    int mw = 0, mh = 0;
+    for (int t = 0; t < a.M; ++t) mw = std::max(mw, a.rect.x1[t] - a.rect.x0[t] + 1);
+    for (int t = 0; t < a.N; ++t) mh = std::max(mh, a.rect.y1[t] - a.rect.y0[t] + 1);
+    const int threads = a.S == 2 ? 4 * ((mw + 1) / 2) * ((mh + 1) / 2) : mw * mh;      // stride 2: four parity classes
+    dim3 grid((threads + 63) / 64, (a.Cin + CIB - 1) / CIB, a.N * a.M * a.batch), block(64);
     const T* w = (const T*)a.w;
 #define FTP_BWD(KK, SS, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, SS, PL, CIB>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch)
     FTP_GEOMETRY(FTP_BWD);

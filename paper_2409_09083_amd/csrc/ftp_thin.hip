@@ -406,11 +406,12 @@ void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
 #undef FTP_TB
 }
 
-// ---- per-stack filter gradient with Cin*K*K <= 32 --------------------------------------------------------------
-// D[m = co][n = (ci, tap)] += sum over pixel pairs of dZ[co][pixel] * X[ci][pixel + tap - P].
+// ---- per-stack filter gradient of layers with very few input channels (Cin <= 4) ------------------------------
+// D[m = co][n = (ci, tap)] += sum over pixel pairs of dZ[co][pixel] * X[ci][S * pixel + tap - P], NB blocks of 32
+// columns n (one for 3x3 filters, five for a 7x7 filter on 3 channels).
 // Workgroup = 32 output channels of one stack and one batch share; its 4 wavefronts take alternate pixel
-// rows of each staged block and are summed in wavefront order at the end.
-template <typename T, int K, bool POOL>
+// pairs of each staged block and are summed in wavefront order at the end.
+template <typename T, int K, int S, int NB, bool POOL>
 __global__ void __launch_bounds__(256)
 k_wgrad_mfma_thin(MfmaWgradArgs a)
 {
@@ -429,18 +430,24 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
     const int TCp = tc.TCp, TR = tc.TR, TI = tc.TI, row_blocks = tc.row_blocks;
     // this share's part of the stack's chunk list (image block, row block)
     const int id0 = (int)((long long)split * tc.total / a.splits), id1 = (int)((long long)(split + 1) * tc.total / a.splits);
-    const int PW = TCp + 2 * P, PH = TR + 2 * P;
+    const int PW = S * TCp + 2 * P, PH = S * TR + 2 * P;
     const int XCS = TI * PH * PW;                      // channel stride of the X patch
     float* Zl = lds;                                   // [TI*TR*TCp][ZP]
     float* Xl = lds + a.PK * ZP;                       // [Cin][TI][PH][PW]
 
     // B operand of lane n = (ci, tap): fixed offset into the patch
-    const int nn = l32 < a.Cin * KK ? l32 : 0;
-    const int lane_off = (nn / KK) * XCS + ((nn % KK) / K) * PW + (nn % KK) % K + hi;
-
-    v16f acc;
+    int lane_off[NB];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+    for (int nb = 0; nb < NB; ++nb) {
+        const int nn = nb * 32 + l32 < a.Cin * KK ? nb * 32 + l32 : 0;
+        lane_off[nb] = (nn / KK) * XCS + ((nn % KK) / K) * PW + (nn % KK) % K + S * hi;
+    }
+
+    v16f acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
 
     for (int id = id0; id < id1; ++id) {
         {
@@ -506,13 +513,13 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
             // X patch in natural order [ci][image][row][column]: a wavefront takes whole rows (the row's place in the
             // patch is wave-uniform, no per-lane division), 4 rows in flight
             {
-                const int nph = nr + 2 * P;
+                const int nph = S * nr + 2 * P;
                 const int rows = a.Cin * ni * nph;
                 for (int pr0 = 0; pr0 < rows; pr0 += 16)
                 for (int cb = 0; cb < PW; cb += 64) {
                     const int col = cb + lane;
-                    const int gx = x0 - P + col;
-                    const bool xin = col < rw + 2 * P && gx >= 0 && gx < a.Wc;
+                    const int gx = S * x0 - P + col;
+                    const bool xin = col < S * rw + 2 * P && gx >= 0 && gx < a.Wc;
                     float v[4]; int dst[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
@@ -521,9 +528,9 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
                         const int pc = rok ? prow : 0;
                         const int ci = pc / (ni * nph), rem = pc - ci * (ni * nph);
                         const int il = rem / nph, r = rem - il * nph;
-                        const int gy = yb - P + r;
+                        const int gy = S * yb - P + r;
                         const bool inside = xin && gy >= 0 && gy < a.Hc;
-                        v[u] = ld(at<T>(a.in, stack, ti, tj, n0 + il, ci, inside ? gy : y0, inside ? gx : x0));
+                        v[u] = ld(at<T>(a.in, stack, ti, tj, n0 + il, ci, inside ? gy : S * y0, inside ? gx : S * x0));
                         if (!inside) v[u] = 0.0f;
                         dst[u] = (rok && col < PW) ? ci * XCS + (il * PH + r) * PW + col : -1;
                     }
@@ -537,30 +544,38 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
             for (int rr = 0; rr < nrows; ++rr) {
                 const int il = rr / nr, r = rr - il * nr;
                 const float* zrow = Zl + (rr * TCp + hi) * ZP + l32;
-                const float* xrow = Xl + lane_off + (il * PH + r) * PW;
-                for (int xp = 2 * wave; xp < TCp; xp += 8)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(zrow[xp * ZP], xrow[xp], acc, 0, 0, 0);
+                const float* xrow = Xl + (il * PH + S * r) * PW;
+                for (int xp = 2 * wave; xp < TCp; xp += 8) {
+                    const float av = zrow[xp * ZP];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, xrow[lane_off[nb] + S * xp], acc[nb], 0, 0, 0);
+                }
             }
         }
     }
 
     // sum the 4 wavefronts in order, then wavefront 0 stores D[co][(ci, tap)]
-    __syncthreads();
     float* red = lds;                                  // [3][16][64]
-    if (wave > 0) {
+    const long long layer_params = (long long)a.Cout * a.Cin * KK;
+    float* dst = a.splits > 1 ? a.scratch + ((long long)stack * a.splits + split) * layer_params
+                              : a.partial + (long long)stack * a.n_params + a.w_off;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) red[((wave - 1) * 16 + i) * 64 + lane] = acc[i];
-    }
-    __syncthreads();
-    if (wave == 0) {
-        const long long layer_params = (long long)a.Cout * a.Cin * KK;
-        float* dst = a.splits > 1 ? a.scratch + ((long long)stack * a.splits + split) * layer_params
-                                  : a.partial + (long long)stack * a.n_params + a.w_off;
+    for (int nb = 0; nb < NB; ++nb) {
+        __syncthreads();
+        if (wave > 0) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float v = ((acc[i] + red[(0 * 16 + i) * 64 + lane]) + red[(1 * 16 + i) * 64 + lane]) + red[(2 * 16 + i) * 64 + lane];
-            const int co = co0 + 8 * (i >> 2) + 4 * hi + (i & 3);
-            if (co < a.Cout && l32 < a.Cin * KK) dst[(long long)co * a.Cin * KK + l32] = v;
+            for (int i = 0; i < 16; ++i) red[((wave - 1) * 16 + i) * 64 + lane] = acc[nb][i];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const int n = nb * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float v = ((acc[nb][i] + red[(0 * 16 + i) * 64 + lane]) + red[(1 * 16 + i) * 64 + lane]) + red[(2 * 16 + i) * 64 + lane];
+                const int co = co0 + 8 * (i >> 2) + 4 * hi + (i & 3);
+                if (co < a.Cout && n < a.Cin * KK) dst[(long long)co * a.Cin * KK + n] = v;
+            }
         }
     }
 }
@@ -592,10 +607,10 @@ ThinGeom thin_geom(const ConvArgs& c)
     for (int i = 0; i < c.N; ++i)
         for (int j = 0; j < c.M; ++j) {
             const ThinChunks tc = thin_wgrad_chunks(c.rect.x1[j] - c.rect.x0[j] + 1, c.rect.y1[i] - c.rect.y0[i] + 1, c.batch, g.PK, c.pooled != 0);
-            const int pos = tc.TI * (tc.TR + 2 * P) * (tc.TCp + 2 * P);
+            const int pos = tc.TI * (c.S * tc.TR + 2 * P) * (c.S * tc.TCp + 2 * P);
             if (pos > max_pos) max_pos = pos;
         }
-    size_t words = (size_t)g.PK * 33 + (size_t)max_pos * c.Cin + 2;     // +2: the second pixel of the last pair
+    size_t words = (size_t)g.PK * 33 + (size_t)max_pos * c.Cin + 2 * c.S;   // the second pixel of the last pair
     if (words < 3 * 16 * 64) words = 3 * 16 * 64;                         // final sum of the wavefronts
     g.lds = words * sizeof(float);
     return g;
@@ -606,7 +621,8 @@ ThinGeom thin_geom(const ConvArgs& c)
 // c.rect must hold the owned rectangles.
 bool thin_wgrad_eligible(const ConvArgs& c)
 {
-    if (c.has_bias || c.Cin * c.K * c.K > 32) return false;
+    if (c.has_bias || !(c.Cin * c.K * c.K <= 32 || (c.Cin <= 4 && c.Cin * c.K * c.K <= 160))) return false;
+    if (c.pooled && (c.S != 1 || c.K > 3)) return false;
     if (c.pooled) {
         // owned rectangles of a pooled convolution consist of whole windows; anything else goes to the generic kernel
         for (int t = 0; t < c.M; ++t) if ((c.rect.x0[t] & 1) || !((c.rect.x1[t] - c.rect.x0[t]) & 1)) return false;
@@ -620,20 +636,24 @@ void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     MfmaWgradArgs a;
     a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.rect;
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
-    a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hc; a.Wc = c.Wc; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
+    a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hi; a.Wc = c.Wi; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
     a.splits = c.wgrad_shares_thin;
     const ThinGeom g = thin_geom(c);
     a.PK = g.PK;
     dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
     g_kernel_label = "k_wgrad_mfma_thin";
-#define FTP_TW(T, KK, PL) hipLaunchKernelGGL((k_wgrad_mfma_thin<T, KK, PL>), grid, block, g.lds, s, a)
-    if (c.bf16) {
-        if (c.K == 3) { if (c.pooled) FTP_TW(bf16_t, 3, true); else FTP_TW(bf16_t, 3, false); }
-        else          { if (c.pooled) FTP_TW(bf16_t, 1, true); else FTP_TW(bf16_t, 1, false); }
-    } else {
-        if (c.K == 3) { if (c.pooled) FTP_TW(float, 3, true); else FTP_TW(float, 3, false); }
-        else          { if (c.pooled) FTP_TW(float, 1, true); else FTP_TW(float, 1, false); }
-    }
+    const int nb = (c.Cin * c.K * c.K + 31) / 32;      // 1 (up to 3x3), 2 or 4 (5x5), 4 to 7 (7x7: 5 for 3 channels)
+#define FTP_TW(T, KK, SS, NB, PL) hipLaunchKernelGGL((k_wgrad_mfma_thin<T, KK, SS, NB, PL>), grid, block, g.lds, s, a)
+#define FTP_TWS(T, KK, NB) do { if (c.S == 2) FTP_TW(T, KK, 2, NB, false); else FTP_TW(T, KK, 1, NB, false); } while (0)
+#define FTP_TWK(T) do { \
+        if (c.K == 7)      { if (nb <= 4) FTP_TWS(T, 7, 4); else FTP_TWS(T, 7, 5); } \
+        else if (c.K == 5) { if (nb <= 2) FTP_TWS(T, 5, 2); else FTP_TWS(T, 5, 4); } \
+        else if (c.K == 3) { if (nb <= 1) { if (c.pooled) FTP_TW(T, 3, 1, 1, true); else FTP_TWS(T, 3, 1); } \
+                             else         { if (c.pooled) FTP_TW(T, 3, 1, 2, true); else FTP_TWS(T, 3, 2); } } \
+        else               { if (c.pooled) FTP_TW(T, 1, 1, 1, true); else FTP_TWS(T, 1, 1); } } while (0)
+    if (c.bf16) FTP_TWK(bf16_t); else FTP_TWK(float);
+#undef FTP_TWK
+#undef FTP_TWS
 #undef FTP_TW
     if (a.splits > 1) {
         const long long lp = (long long)c.Cout * c.Cin * c.K * c.K;
