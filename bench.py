@@ -59,6 +59,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg4", choices=["tiny", "cfg2_perblock", "cfg2_fused", "cfg3", "cfg4", "cfg5", "gen_stem"])
     ap.add_argument("--group-size", type=int, default=4, help="layers per group (cfg5 sweep)")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (batch-size sweeps; 0 = as configured)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-update", action="store_true",
                     help="close every step with the fused gradient sum + filter update (lr 0) instead of the plain gradient sum")
@@ -77,6 +78,8 @@ def main():
     from paper_2409_09083_amd.harness import Session
 
     cfg = pick_config(args.config, args.group_size)
+    if args.batch:
+        cfg = cfg.with_(batch=args.batch)
     x, ws, bs, dy = C.make_tensors(cfg)
     s = Session(cfg.layers, cfg.batch, cfg.in_c, cfg.in_h, cfg.in_w, cfg.grid, cfg.group_ends, cfg.dtype)
     s.load(x=x, weights=ws, dy=dy)

@@ -91,8 +91,9 @@ int ftp_plan_map_shape(const ftp_plan_t* plan, int32_t boundary, int32_t out_chw
  *   workspace_bytes      device scratch shared by ftp_forward and ftp_backward
  *   wgrad_partial_bytes  N*M*n_params*4
  *   n_params             length of the parameter vector
- *   per_stack_split[4]   largest per-stack share of: feature maps, delta maps, filters, other
- *                        (the memory breakdown of Sec. 5.2) */
+ *   per_stack_split[4]   what the largest stack has to hold: feature maps kept for back-propagation (recomputed
+ *                        halo included), the delta maps alive at a time, filters + its own partial gradient set,
+ *                        recorded decisions (pool winners, activation signs)  (the memory breakdown of Sec. 5.2) */
 int ftp_plan_sizes(const ftp_plan_t* plan, size_t* workspace_bytes, size_t* wgrad_partial_bytes,
                    size_t* n_params, size_t per_stack_split[4]);
 

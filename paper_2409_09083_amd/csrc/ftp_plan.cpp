@@ -351,7 +351,10 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
         }
         const int kind_out = u.bo == gr.e ? FTP_RECT_OWN : FTP_RECT_FWD;
         fmap += area_max(gr, kind_out, u.bo) * p.C[u.bo] * batch * p.esize;
-        other += area_max(gr, FTP_RECT_OWN, u.bo) * p.C[u.bo] * batch;                // decision codes of the own tile
+        // decisions of the own tile: a winner code byte per element behind a pool, a sign bit per element (32
+        // channels to a word) behind a convolution
+        other += area_max(gr, FTP_RECT_OWN, u.bo) * batch *
+                 ((u.pooled || u.kind == UNIT_POOL ? (double)p.C[u.bo] : 0.0) + (u.kind == UNIT_CONV ? 4.0 * ((p.C[u.bo] + 31) / 32) : 0.0));
         dmap = std::max(dmap, (area_max(gr, FTP_RECT_BWD, u.bo) * p.C[u.bo] + area_max(gr, FTP_RECT_BWD, u.bi) * p.C[u.bi]) * batch * p.esize);
     }
     fmap += area_max(p.groups[0], FTP_RECT_FWD, 0) * p.C[0] * batch * p.esize;

@@ -188,3 +188,23 @@ def test_null_arguments_rejected_without_gpu(F):
     with pytest.raises(F.binding.FtpError):
         F.ftp_plan_rect(plan, 1, 0, 0, 0, F.FTP_RECT_OWN)
     F.ftp_plan_destroy(plan)
+
+
+def test_per_stack_memory_report(F):
+    """Sec. 5.2: a stack's feature and delta maps shrink with the number of tiles (a little less than N x M because
+    of the halo), the filters and partial gradients do not."""
+    from paper_2409_09083_amd import memory_report as MR
+    cfg = C.config4()
+    rep = MR.report(cfg, [1, 2, 3, 6])
+    rows = {tuple(r["grid"]): r for r in rep["per_stack"]}
+    assert rows[(1, 1)]["total"] == rep["unpartitioned"]["total"]
+    # unpartitioned feature maps: input + every unit output, batch 64, fp32
+    shapes = cfg.boundary_shapes()
+    unit_out = [b for b in range(1, 17) if not (b < 16 and cfg.layers[b].kind == MAXPOOL)]     # fused pools keep no conv output
+    expect = sum(c * h * w for (c, h, w) in [shapes[0]] + [shapes[b] for b in unit_out]) * cfg.batch * 4
+    assert rows[(1, 1)]["feature_maps"] == expect
+    for n in (2, 3, 6):
+        r = rows[(n, n)]
+        assert r["filters_and_gradients"] == rows[(1, 1)]["filters_and_gradients"] == 3418976 * 8
+        assert 0.7 * n * n <= r["maps_vs_unpartitioned"] <= n * n
+    assert rows[(6, 6)]["total"] < rows[(3, 3)]["total"] < rows[(2, 2)]["total"] < rows[(1, 1)]["total"]
