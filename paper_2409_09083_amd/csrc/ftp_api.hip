@@ -259,7 +259,7 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
                 float* wt = (float*)((char*)workspace + u.wt_fwd_offset);
                 const RectTab ext = view_extent(p, u.in_act, u.group, u.bi);
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] {
-                    prep_filter(a.w, a.bf16, wt, nullptr, a.Cout, a.Cin, a.K, s);
+                    prep_filter(a.w, a.bf16, mfma_conv_packs_bf16(a), wt, nullptr, a.Cout, a.Cin, a.K, s);
                     if (mfma_conv_fwd(a, ext, wt, s)) direct_conv_fwd(a, s);
                 });
             } else if (fast && thin_conv_fwd_eligible(a)) {
@@ -319,7 +319,7 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
                 float* wt = (float*)((char*)workspace + u.wt_bwd_offset);
                 const RectTab ext = view_extent(p, u.in_delta, u.group, u.bo);
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] {
-                    prep_filter(a.w, a.bf16, nullptr, wt, a.Cout, a.Cin, a.K, s);
+                    prep_filter(a.w, a.bf16, mfma_conv_packs_bf16(a), nullptr, wt, a.Cout, a.Cin, a.K, s);
                     if (mfma_conv_bwd_data(a, ext, wt, s)) direct_conv_bwd_data(a, s);
                 });
             } else if (fast && thin_bwd_data_eligible(a)) {

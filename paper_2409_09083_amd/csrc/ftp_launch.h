@@ -85,7 +85,9 @@ struct MfmaConvArgs {
 };
 
 bool mfma_conv_eligible(const ConvArgs& a, bool backward);
-void prep_filter(const void* w, int bf16, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s);
+// packed16: relay the filter for the bfloat matrix-core path (what mfma_conv_packs_bf16 says for the layer)
+bool mfma_conv_packs_bf16(const ConvArgs& a);
+void prep_filter(const void* w, int bf16, int packed16, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s);
 int mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);       // non-zero: does not fit
 int mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
 

@@ -10,8 +10,12 @@
 // and the filter slice of a few channels x K*K taps sit in LDS; v_mfma_f32_32x32x2_f32 reads both from there.
 // MFMA lane layout (64 lanes): A[m = lane%32][k = lane/32], B[k = lane/32][n = lane%32],
 // D[m = 8*(i/4) + 4*(lane/32) + i%4][n = lane%32] for accumulator register i of 16.
+// With 16-bit (bfloat) maps and filters the stride-1 1x1 / 3x3 layers multiply with v_mfma_f32_32x32x8_bf16_1k
+// instead (A[m][k = 4*(lane/32) + j], B[k = 4*(lane/32) + j][n], j < 4, same D): products of two bfloats are exact in
+// fp32 and the sums are accumulated in fp32, so this is the same arithmetic at eight times the rate.
 #include "ftp_device.h"
 #include "ftp_launch.h"
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -36,6 +40,37 @@ k_prep_filter(const T* __restrict__ w, float* __restrict__ wt_fwd, float* __rest
     const float v = ld(w + i);
     if (wt_fwd) wt_fwd[((long long)t * Cin + ci) * Cout + co] = v;
     if (wt_bwd) wt_bwd[((long long)(KK - 1 - t) * Cout + co) * Cin + ci] = v;
+}
+
+// Filter relayout for the bfloat matrix-core path: [tap][quad of 4 reduction channels][output channel][4 bfloats],
+// taps padded to an even count with zeros (one instruction multiplies 4 channels of two taps, or 8 channels of
+// one), reduction channels padded to whole quads with zeros.  fwd: reduction = ci, output = co; bwd: reduction = co,
+// output = ci, taps rotated by 180 degrees.
+__global__ void __launch_bounds__(256)
+k_prep_filter16(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt_fwd, bf16_t* __restrict__ wt_bwd, int Cout, int Cin, int KK, int taps)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int j = (int)(i & 3);
+    if (wt_fwd) {
+        const int C4 = (Cin + 3) / 4;
+        const long long n = (long long)taps * C4 * Cout;
+        if ((i >> 2) < n) {
+            const long long e = i >> 2;
+            const int co = (int)(e % Cout), q = (int)((e / Cout) % C4), t = (int)(e / ((long long)Cout * C4));
+            const int ci = 4 * q + j;
+            wt_fwd[i] = (t < KK && ci < Cin) ? w[((long long)co * Cin + ci) * KK + t] : (bf16_t)0;
+        }
+    }
+    if (wt_bwd) {
+        const int C4 = (Cout + 3) / 4;
+        const long long n = (long long)taps * C4 * Cin;
+        if ((i >> 2) < n) {
+            const long long e = i >> 2;
+            const int ci = (int)(e % Cin), q = (int)((e / Cin) % C4), t = (int)(e / ((long long)Cin * C4));
+            const int co = 4 * q + j;
+            wt_bwd[i] = (t < KK && co < Cout) ? w[((long long)co * Cin + ci) * KK + (KK - 1 - t)] : (bf16_t)0;
+        }
+    }
 }
 
 // Geometry of one tile: rows R0 .. R0+nrows-1 of the batch-flattened row index, columns ox0 .. ox0+TC-1.
@@ -232,12 +267,16 @@ k_conv_mfma_dl(MfmaConvArgs a)
     constexpr int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
     constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD);
     constexpr int MAXPOS = XMAX / 256;
-    constexpr int WF = KK * kCK * BM;                  // floats of one filter slice [tap][channel][BM]
-    constexpr int WPIECES = WF / 64;                   // 64-float pieces of the slice, dealt round-robin to the 4 wavefronts
+    // bfloat matrix-core path: the filter slice is ROWS rows of [BM][4 bfloats]; a row is (tap, the stage's 4
+    // channels) for 3x3 (9 taps + 1 row of zeros) and (channels 4r .. 4r+3) for 1x1; step s multiplies rows 2s, 2s+1
+    constexpr bool BF = sizeof(T) == 2 && K <= 3 && STRIDE == 1;
+    constexpr int ROWS = K == 3 ? 10 : kCK / 4;
+    constexpr int WF = BF ? ROWS * BM * 2 : KK * kCK * BM;   // dwords of one filter slice (fp32: [tap][channel][BM])
+    constexpr int WPIECES = WF / 64;                   // 64-dword pieces of the slice, dealt round-robin to the 4 wavefronts
     constexpr int WINSTR = (WPIECES + 3) / 4;
     static_assert(WF % 64 == 0, "the filter slice is loaded in 64-float pieces");
-    __shared__ float bufA[WF + kCK * XMAX];
-    __shared__ float bufB[WF + kCK * XMAX];
+    __shared__ __attribute__((aligned(16))) float bufA[WF + kCK * XMAX];
+    __shared__ __attribute__((aligned(16))) float bufB[WF + kCK * XMAX];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -256,9 +295,9 @@ k_conv_mfma_dl(MfmaConvArgs a)
         const int q = (wave_n * NT + t) * 32 + l32;
         const TilePix tp = tile_pix<S, P>(g, POOL_OUT ? (q >> 2) : q, x1);
         const int pos = POOL_OUT ? (q & 3) : 0;
-        baseB[t] = (tp.valid ? (tp.prow + (pos >> 1)) * PW + tp.xl * S + (pos & 1) : 0) + hi * CS;
+        baseB[t] = (tp.valid ? (tp.prow + (pos >> 1)) * PW + tp.xl * S + (pos & 1) : 0) + (BF ? 0 : hi * CS);
     }
-    const int baseA = hi * BM + wave_m * (32 * MT) + l32;
+    const int baseA = (BF ? 0 : hi * BM) + wave_m * (32 * MT) + l32;
 
     // ---- byte offset of each lane's patch positions from the workgroup's base (channel 0); padding -> out of range
     const int npos = g.npos;
@@ -304,6 +343,8 @@ k_conv_mfma_dl(MfmaConvArgs a)
     };
     // filter: a load instruction covers 64 consecutive floats of the slice; with BM >= 64 that is (part of) one
     // row, with BM = 32 two rows (two consecutive reduction channels)
+    // (bfloat path: a piece is 32 output channels x 4 bfloats; a wavefront always gets the same part of a row)
+    const unsigned woff16 = m0 + (wave % (BM / 32)) * 32 + (lane >> 1) < a.Mtot ? 4u * (unsigned)lane : kOobOffset;
     unsigned woff;
     {
         const int col = BM >= 64 ? (wave % (BM / 64 > 0 ? BM / 64 : 1)) * 64 + lane : (lane & 31);
@@ -325,8 +366,17 @@ k_conv_mfma_dl(MfmaConvArgs a)
         float* Xl = buf + WF;
 #pragma unroll
         for (int u = 0; u < WINSTR; ++u) {
-            const int idx = wave + 4 * u;                              // 64-float piece of the slice
+            const int idx = wave + 4 * u;                              // 64-dword piece of the slice
             if (idx >= WPIECES) break;
+            if constexpr (BF) {
+                const int r = idx / (BM / 32), part = idx - r * (BM / 32);
+                const int C4 = (a.C + 3) >> 2;
+                const int tap = K == 3 ? r : 0, quad = (c0 >> 2) + (K == 3 ? 0 : r);
+                const unsigned so = 4u * (unsigned)((((tap * C4 + quad) * a.Mtot + m0) << 1) + part * 64);
+                const unsigned vo = quad < C4 ? woff16 : kOobOffset;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_LDS_PTR(Wl + idx * 64), 4, vo, so, 0, 0);
+                continue;
+            }
             const int row = BM >= 64 ? idx / (BM / 64 > 0 ? BM / 64 : 1) : 2 * idx;
             const int tap = row / kCK, k = row - tap * kCK;
             const unsigned so = 4u * (unsigned)((tap * a.C + c0 + k) * a.Mtot + m0);
@@ -357,6 +407,41 @@ k_conv_mfma_dl(MfmaConvArgs a)
     auto multiply = [&](const float* buf) {
         const float* Wl = buf;
         const float* Xl = buf + WF;
+        if constexpr (BF) {
+            // one step = rows 2s and 2s+1 of the slice: lanes 0-31 feed row 2s, lanes 32-63 row 2s+1 (4 reduction
+            // elements each); the 4 patch values of a lane are zero-extended bfloats and are packed two to a dword
+            typedef short v4s __attribute__((ext_vector_type(4)));
+            constexpr int NSTEP16 = ROWS / 2;
+            uint2 av[2][MT], bv[2][NT];
+            auto load_step = [&](int s2, int b) {
+                const int r = 2 * s2 + hi;
+                int boff;
+                if (K == 3) { const int tap = r < KK ? r : 0; boff = (tap / 3) * PW + (tap - (tap / 3) * 3); }
+                else        boff = 4 * r * CS;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) av[b][mt] = *(const uint2*)(Wl + ((r * BM + baseA + 32 * mt) << 1));
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const float* xp = Xl + baseB[t] + boff;
+                    const uint32_t x0 = __float_as_uint(xp[0]), x1 = __float_as_uint(xp[CS]);
+                    const uint32_t x2 = __float_as_uint(xp[2 * CS]), x3 = __float_as_uint(xp[3 * CS]);
+                    bv[b][t] = make_uint2(x0 | (x1 << 16), x2 | (x3 << 16));
+                }
+            };
+            load_step(0, 0);
+#pragma unroll
+            for (int j = 0; j < NSTEP16; ++j) {
+                if (j + 1 < NSTEP16) load_step(j + 1, (j + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(v4s, av[j & 1][mt]),
+                                                                             __builtin_bit_cast(v4s, bv[j & 1][t]), acc[mt][t], 0, 0, 0);
+            }
+            return;
+        }
         constexpr int NSTEP = KK * (kCK / 2);
         float av[2][MT], bv[2][NT];
         auto load_step = [&](int j, int b) {
@@ -557,8 +642,20 @@ bool mfma_conv_eligible(const ConvArgs& a, bool backward)
     return Mtot >= 16 && Mtot % 4 == 0 && C >= 8;
 }
 
-void prep_filter(const void* w, int bf16, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s)
+bool mfma_conv_packs_bf16(const ConvArgs& a) { return a.bf16 && a.K <= 3 && a.S == 1; }
+
+void prep_filter(const void* w, int bf16, int packed16, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s)
 {
+    if (packed16) {
+        // (fits the fp32 areas: at most 10 taps x (C + 3) x M x 2 bytes against K*K x C x M x 4)
+        const int taps = K == 3 ? 10 : 1;
+        const long long cmax = (long long)taps * (((wt_fwd ? Cin : Cout) + 3) / 4) * (wt_fwd ? Cout : Cin) * 4;
+        const long long cboth = (long long)taps * ((std::max(Cin, Cout) + 3) / 4) * std::max(Cin, Cout) * 4;
+        const long long n16 = wt_fwd && wt_bwd ? cboth : cmax;
+        hipLaunchKernelGGL(k_prep_filter16, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (const bf16_t*)w, (bf16_t*)wt_fwd, (bf16_t*)wt_bwd,
+                           Cout, Cin, K * K, taps);
+        return;
+    }
     const long long n = (long long)Cout * Cin * K * K;
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
     if (bf16) hipLaunchKernelGGL(k_prep_filter<bf16_t>, grid, block, 0, s, (const bf16_t*)w, wt_fwd, wt_bwd, Cout, Cin, K * K);

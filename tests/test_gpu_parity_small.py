@@ -112,3 +112,34 @@ def test_deterministic_bitwise(oracle):
         assert np.array_equal(a[k], b[k]), k
     a["session"].close()
     b["session"].close()
+
+
+def test_step_under_graph_capture(oracle):
+    """The three device calls allocate nothing and use no host synchronisation, so a step can be captured in a HIP
+    graph: every replay (with eager work and synchronisations in between) reproduces the eager results bit for bit."""
+    import torch
+    cfg = _mk("pools", (3, 2), "split")
+    x, ws, bs, dy = C.make_tensors(cfg)
+    s = P.make_session(cfg, x.shape[0])
+    s.load(x=x, weights=ws, dy=dy)
+    s.step()
+    torch.cuda.synchronize()
+    ref = [s.y.clone(), s.dx.clone(), s.wgrad.clone()]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        s.step()                                   # first launches outside the capture (one-time kernel attributes)
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            s.step()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for t in (s.y, s.dx, s.wgrad, s.partials):
+            t.fill_(float("nan"))                  # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, (s.y, s.dx, s.wgrad)):
+            assert torch.equal(a, b)
+    s.close()
