@@ -11,6 +11,9 @@
 // only if it is the window's winner; 2 = stride-2 convolution: the rectangle is the stack's owned part of the
 // *input* map and pixel (y, x) carries delta (y/2, x/2) if both are even, else zero (the filter gradient of a strided
 // convolution is the stride-1 one of the deltas with zeros in between; three quarters of the products are zero).
+// 16-bit (bfloat) maps multiply with v_mfma_f32_32x32x8_bf16_1k: 8 pixels per instruction (lanes 0-31 the first 4,
+// lanes 32-63 the next 4), counted through the chunk's pixel list; a small table in LDS gives each pixel's patch
+// position.  The staged values are widened bfloats, so taking their upper halves back is exact.
 // TROWS: filter rows per workgroup (5x5: 2, 7x7: 1, else all): one accumulator tile per tap has to fit the registers,
 // so larger filters are split over blockIdx.x, each part staging the same chunks.
 #include "ftp_device.h"
@@ -28,6 +31,7 @@ __global__ void __launch_bounds__(256, 2)
 k_wgrad_mfma(MfmaWgradArgs a)
 {
     constexpr bool POOL = HALF == 1;
+    constexpr bool BF = sizeof(T) == 2;
     constexpr int WAVES_K = 4 / (WAVES_CO * WAVES_CI);
     constexpr int KK = K * K, P = K / 2, NTAP = TROWS * K;
     constexpr int BCO = 32 * WAVES_CO, BCI = 32 * WAVES_CI;
@@ -57,6 +61,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
     const int id0 = (int)((long long)split * wc.total / a.splits), id1 = (int)((long long)(split + 1) * wc.total / a.splits);
     float* Zl = lds;                                   // [pixel][ZP]
     float* Xl = lds + ZPOS * ZP;                       // [patch position][XP]
+    int* posl = (int*)(Xl + XPOS * XP);                // bfloat path: [pixel] -> XP * patch position of its tap (0, 0)
 
     v16f acc[NTAP];
 #pragma unroll
@@ -80,8 +85,10 @@ k_wgrad_mfma(MfmaWgradArgs a)
     // addresses) and independent, so they are in flight together, and what must be zero is zeroed at the
     // LDS write.  zinfo: bit 0 position exists, bit 1 padding column, bits 2-3 the pixel's place in its pool
     // window.  xinfo: per pass bit 0 position exists, bit 1 inside the map.
+    // zinfo bit 4: the position lies in the pixel list rounded up to a multiple of 8 (bfloat path; zero if it does not
+    // exist); zpos: XP * patch position of the pixel.
     uint32_t zm[NZ]; float zg[NZ]; float xg[XPASS][NX];
-    int zinfo = 0, xinfo = 0;
+    int zinfo = 0, xinfo = 0, zpos = 0;
 
     auto load = [&](const Chunk& c) {
         {
@@ -92,7 +99,8 @@ k_wgrad_mfma(MfmaWgradArgs a)
             const int il = row / c.nr, r = row - il * c.nr;
             const int qy = c.yb + r, qx = c.xb + (zc < c.nc ? zc : c.nc - 1);
             const int sy = HALF ? (qy >> 1) : qy, sx = HALF ? (qx >> 1) : qx;
-            zinfo = (ok ? 1 : 0) | (zc >= c.nc ? 2 : 0) | ((((qy & 1) << 1) | (qx & 1)) << 2);
+            zinfo = (ok ? 1 : 0) | (zc >= c.nc ? 2 : 0) | ((((qy & 1) << 1) | (qx & 1)) << 2) | (lane < ((npos + 7) & ~7) ? 16 : 0);
+            zpos = ok ? ((il * (c.nr + 2 * P) + r) * PW + zc) * XP : 0;
             const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, c.n0 + il, 0, sy, sx);
             const T* gp = at<T>(a.din, stack, ti, tj, c.n0 + il, 0, sy, sx);
 #pragma unroll
@@ -132,7 +140,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
 
     auto store = [&]() {
         __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): every load of the chunk has landed
-        if (zinfo & 1) {
+        if (zinfo & (BF ? 16 : 1)) {
             float* zdst = Zl + lane * ZP;
             const int code = (zinfo >> 2) & 3;
 #pragma unroll
@@ -141,9 +149,10 @@ k_wgrad_mfma(MfmaWgradArgs a)
                 float v = zg[k];                                       // the delta maps hold dLoss/dZ
                 if (POOL && ((zm[k] >> 1) & 3) != (uint32_t)code) v = 0.0f;
                 if (HALF == 2 && code != 0) v = 0.0f;
-                if ((zinfo & 2) || co0 + ch >= a.Cout) v = 0.0f;
+                if ((zinfo & 2) || !(zinfo & 1) || co0 + ch >= a.Cout) v = 0.0f;
                 zdst[ch] = v;
             }
+            if (BF && wave == 0) posl[lane] = zpos;
         }
 #pragma unroll
         for (int pass = 0; pass < XPASS; ++pass) {
@@ -160,6 +169,29 @@ k_wgrad_mfma(MfmaWgradArgs a)
     };
 
     auto multiply = [&](const Chunk& c) {
+        if constexpr (BF) {
+            typedef short v4s __attribute__((ext_vector_type(4)));
+            const int nblk = (c.ni * c.nr * TCp + 7) >> 3;
+            // wavefronts that share a (co, ci) tile take alternate blocks of 8 pixels
+            for (int b = wave_k; b < nblk; b += WAVES_K) {
+                const int4 po = *(const int4*)(posl + 8 * b + 4 * hi);
+                const float* zp = Zl + (8 * b + 4 * hi) * ZP + co_l;
+                const uint32_t z0 = __float_as_uint(zp[0]), z1 = __float_as_uint(zp[ZP]), z2 = __float_as_uint(zp[2 * ZP]), z3 = __float_as_uint(zp[3 * ZP]);
+                // upper halves of two dwords -> one dword of two bfloats
+                const uint2 av = make_uint2(__builtin_amdgcn_perm(z1, z0, 0x07060302u), __builtin_amdgcn_perm(z3, z2, 0x07060302u));
+                const float* xb = Xl + ci_l;
+#pragma unroll
+                for (int t = 0; t < NTAP; ++t) {
+                    if (TROWS != K && trow0 + t / K >= K) break;
+                    const int off = ((trow0 + t / K) * PW + (t % K)) * XP;
+                    const uint32_t x0 = __float_as_uint(xb[po.x + off]), x1 = __float_as_uint(xb[po.y + off]);
+                    const uint32_t x2 = __float_as_uint(xb[po.z + off]), x3 = __float_as_uint(xb[po.w + off]);
+                    const uint2 bv = make_uint2(__builtin_amdgcn_perm(x1, x0, 0x07060302u), __builtin_amdgcn_perm(x3, x2, 0x07060302u));
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(v4s, av), __builtin_bit_cast(v4s, bv), acc[t], 0, 0, 0);
+                }
+            }
+            return;
+        }
         const int nrows = c.ni * c.nr, nph = c.nr + 2 * P, ncp = (c.nc + 1) & ~1;
         for (int rr = 0; rr < nrows; ++rr) {
             const int il = rr / c.nr, r = rr - il * c.nr;
@@ -269,7 +301,8 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     // (64 input channels per workgroup where the patch of a 5x5 / 7x7 filter would not leave LDS for two workgroups)
     const int waves_ci = (c.Cin >= 64 && c.K <= 3) ? 2 : 1;
     const int BCO = 64, BCI = 32 * waves_ci;
-    const size_t lds = ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1)) * sizeof(float);
+    // (+ the bfloat path's table of patch positions)
+    const size_t lds = ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1) + kWgradZPos) * sizeof(float);
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
     const int parts = c.K == 5 ? 3 : c.K == 7 ? 7 : 1;                 // filter rows 2 + 2 + 1, or one at a time
     dim3 grid(tiles * parts, a.splits, c.N * c.M), block(256);
