@@ -25,22 +25,14 @@ typedef uint16_t bf16_t;          // raw bfloat16 bits
 
 __device__ __forceinline__ float ld(const float* p) { return *p; }
 __device__ __forceinline__ float ld(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
+// fp32 -> bfloat, nearest with ties to even: the conversion instruction of gfx950 (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t bf16_bits(float v) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)v); }
 __device__ __forceinline__ void st(float* p, float v) { *p = v; }
-__device__ __forceinline__ void st(bf16_t* p, float v)
-{
-    uint32_t u = __float_as_uint(v);
-    if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);   // nearest, ties to even
-    *p = (bf16_t)(u >> 16);
-}
+__device__ __forceinline__ void st(bf16_t* p, float v) { *p = (bf16_t)bf16_bits(v); }
 
 // Value a map element holds after being stored with element type T (identity for fp32).
 __device__ __forceinline__ float stored(float v, const float*) { return v; }
-__device__ __forceinline__ float stored(float v, const bf16_t*)
-{
-    uint32_t u = __float_as_uint(v);
-    if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);
-    return __uint_as_float(u & 0xFFFF0000u);
-}
+__device__ __forceinline__ float stored(float v, const bf16_t*) { return __uint_as_float(bf16_bits(v) << 16); }
 
 template <typename T>
 __device__ __forceinline__ T* at(const View& v, int stack, int ti, int tj, int n, int c, int y, int x)

@@ -572,6 +572,10 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc
     // whole input patch, and with many blocks in flight the filter no longer stays in the L2 cache
     int BM = a.Mtot >= 128 ? 128 : a.Mtot > 32 ? 64 : 32;
     if (BM > conv_dl_max_bm(K)) BM = conv_dl_max_bm(K);
+    // The bfloat path finishes a stage's multiply long before the next stage's loads arrive; what hides that is more
+    // workgroups per CU, so its 3x3 layers take 64-channel workgroups (half the accumulator registers): config 5
+    // forward of the 64 -> 128 layer 0.89 -> 0.41 ms.  (32 channels re-read the patch too often; 1x1 layers lose.)
+    if (c.bf16 && K == 3 && !STRIDED_FWD && c.S == 1 && BM > 64) BM = 64;
     for (int BN = STRIDED_FWD ? 128 : 256; BN >= 128; BN /= 2) {
             const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD);
             const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos);
