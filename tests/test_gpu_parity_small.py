@@ -143,3 +143,35 @@ def test_step_under_graph_capture(oracle):
         for a, b in zip(ref, (s.y, s.dx, s.wgrad)):
             assert torch.equal(a, b)
     s.close()
+
+
+def _random_net(seed):
+    """A random small network over the whole admitted geometry (K, stride, pools on any map, channel counts on both
+    sides of the matrix-core thresholds), a random grid and grouping."""
+    import random
+    rnd = random.Random(seed)
+    while True:
+        h, w = rnd.randint(28, 84), rnd.randint(28, 84)
+        c = rnd.choice([3, 4, 8, 16, 32])
+        layers, ch, hh, ww = [], c, h, w
+        for _ in range(rnd.randint(3, 6)):
+            if rnd.random() < 0.25 and hh >= 8 and ww >= 8:
+                layers.append(pool(ch))
+                hh, ww = hh // 2, ww // 2
+            else:
+                co = rnd.choice([4, 8, 16, 24, 32, 48, 64, 96])
+                st = 2 if (rnd.random() < 0.3 and hh >= 12 and ww >= 12) else 1
+                layers.append(conv(ch, co, rnd.choice([1, 3, 3, 5, 7]), stride=st))
+                ch, hh, ww = co, (hh - 1) // st + 1, (ww - 1) // st + 1
+        N, M = rnd.randint(1, 3), rnd.randint(1, 3)
+        if hh < 2 * N or ww < 2 * M or all(ly.kind != 0 for ly in layers):
+            continue
+        L = len(layers)
+        cuts = sorted(rnd.sample(range(1, L), rnd.randint(0, min(2, L - 1))))
+        dtype = "bf16" if rnd.random() < 0.4 else "f32"
+        return Config("random_%d" % seed, rnd.randint(1, 3), c, h, w, tuple(layers), (N, M), tuple(cuts + [L]), dtype)
+
+
+@pytest.mark.parametrize("seed", list(range(48)))
+def test_random_general_networks(oracle, seed):
+    P.check_case(oracle, _random_net(seed))
