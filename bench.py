@@ -133,6 +133,9 @@ def main():
     if "mfma" in name and ai >= ridge:
         peak = PEAK_MFMA_TFLOPS[cfg.dtype]
         roof = {"bound": "mfma", "achieved": dom["flops"] / (dom["ms"] * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s"}
+    elif "mfma" not in name and ai >= PEAK_ALU_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        # a kernel of plain vector arithmetic above the ridge of the vector units
+        roof = {"bound": "alu", "achieved": dom["flops"] / (dom["ms"] * 1e-3) / 1e12, "peak": PEAK_ALU_TFLOPS, "unit": "TFLOP/s"}
     else:
         roof = {"bound": "hbm", "achieved": dom["bytes"] / (dom["ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
