@@ -113,20 +113,22 @@ k_conv_fwd_direct(View in, View out, View mask, View osign, RectTab rt, RectTab 
 template <typename T, int K, int S, bool POOL, int CIB>
 __global__ void __launch_bounds__(64)
 k_conv_bwd_data_direct(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt,
-                       const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch)
+                       const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch, int blocks_per_class)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
     const int rw = rt.x1[tj] - rt.x0[tj] + 1, rh = rt.y1[ti] - rt.y0[ti] + 1;
-    const int pid = blockIdx.x * blockDim.x + threadIdx.x;
-    int ry, rx;
+    int ry, rx, cls = 0;
     if (S == 2) {
-        // the four parity classes of the rectangle one after the other: neighbouring lanes then use the same taps
+        // a workgroup serves one of the four parity classes of the rectangle: its taps, and with them the filter
+        // elements it reads, are the same for all its lanes (scalar loads)
+        cls = blockIdx.x / blocks_per_class;
+        const int idx = (blockIdx.x - cls * blocks_per_class) * blockDim.x + threadIdx.x;
         const int rw2 = (rw + 1) >> 1, rh2 = (rh + 1) >> 1;
-        const int cls = pid / (rw2 * rh2), idx = pid - cls * (rw2 * rh2);
         ry = 2 * (idx / rw2) + (cls >> 1); rx = 2 * (idx % rw2) + (cls & 1);
-        if (cls >= 4 || ry >= rh || rx >= rw) return;
+        if (idx >= rw2 * rh2 || ry >= rh || rx >= rw) return;
     } else {
+        const int pid = blockIdx.x * blockDim.x + threadIdx.x;
         if (pid >= rw * rh) return;
         ry = pid / rw; rx = pid - ry * rw;
     }
@@ -138,7 +140,39 @@ k_conv_bwd_data_direct(View din, View mask, View dout, View isign, int scale_out
     for (int j = 0; j < CIB; ++j) acc[j] = 0.0f;
     // stride 2: only the taps with ky = (iy + P) mod 2, + 2, ... (and likewise kx) meet an output position
     constexpr int NTAP = (K + S - 1) / S;
-    const int ky0 = S == 2 ? ((iy + P) & 1) : 0, kx0 = S == 2 ? ((ix + P) & 1) : 0;
+    const int ky0 = S == 2 ? ((rt.y0[ti] + (cls >> 1) + P) & 1) : 0, kx0 = S == 2 ? ((rt.x0[tj] + (cls & 1) + P) & 1) : 0;
+    if constexpr (!POOL) {
+        // where each tap's delta sits inside a channel plane of the delta view is the same for every output channel:
+        // element offsets once (-1: outside the map), then one load and CIB multiply-adds per (co, tap)
+        int off[NTAP * NTAP];
+#pragma unroll
+        for (int my = 0; my < NTAP; ++my)
+#pragma unroll
+            for (int mx = 0; mx < NTAP; ++mx) {
+                const int ky = ky0 + S * my, kx = kx0 + S * mx;
+                const int sy = iy + P - ky, sx = ix + P - kx;
+                const int qy = sy / S, qx = sx / S;
+                const bool ok = ky < K && kx < K && sy >= 0 && sx >= 0 && qy < Hc && qx < Wc;
+                off[my * NTAP + mx] = ok ? (qy - din.y0[ti]) * din.pitch + (qx - din.x0[tj]) : -1;
+            }
+        const T* dp = at<T>(din, stack, ti, tj, n, 0, din.y0[ti], din.x0[tj]);
+        for (int co = 0; co < Cout; ++co, dp += din.cs) {
+#pragma unroll
+            for (int my = 0; my < NTAP; ++my)
+#pragma unroll
+                for (int mx = 0; mx < NTAP; ++mx) {
+                    const int ky = ky0 + S * my, kx = kx0 + S * mx;
+                    if (ky >= K || kx >= K) continue;                   // (the same for every lane of a strided workgroup)
+                    const int o = off[my * NTAP + mx];
+                    const float dz = o >= 0 ? ld(dp + o) : 0.0f;
+#pragma unroll
+                    for (int j = 0; j < CIB; ++j) {
+                        const int ci = ci0 + j;
+                        if (ci < Cin) acc[j] = fmaf(ld(w + (((size_t)co * Cin + ci) * K + ky) * K + kx), dz, acc[j]);
+                    }
+                }
+        }
+    } else {
     for (int co = 0; co < Cout; ++co) {
 #pragma unroll
         for (int my = 0; my < NTAP; ++my)
@@ -157,6 +191,7 @@ k_conv_bwd_data_direct(View din, View mask, View dout, View isign, int scale_out
                     if (ci < Cin) acc[j] = fmaf(ld(w + (((size_t)co * Cin + ci) * K + ky) * K + kx), dz, acc[j]);
                 }
             }
+    }
     }
 #pragma unroll
     for (int j = 0; j < CIB; ++j)
@@ -374,10 +409,10 @@ void conv_bwd_data_t(const ConvArgs& a, hipStream_t s)
     int mw = 0, mh = 0;
     for (int t = 0; t < a.M; ++t) mw = std::max(mw, a.rect.x1[t] - a.rect.x0[t] + 1);
     for (int t = 0; t < a.N; ++t) mh = std::max(mh, a.rect.y1[t] - a.rect.y0[t] + 1);
-    const int threads = a.S == 2 ? 4 * ((mw + 1) / 2) * ((mh + 1) / 2) : mw * mh;      // stride 2: four parity classes
-    dim3 grid((threads + 63) / 64, (a.Cin + CIB - 1) / CIB, a.N * a.M * a.batch), block(64);
+    const int bpc = (((mw + 1) / 2) * ((mh + 1) / 2) + 63) / 64;                       // stride 2: workgroups per parity class
+    dim3 grid(a.S == 2 ? 4 * bpc : (mw * mh + 63) / 64, (a.Cin + CIB - 1) / CIB, a.N * a.M * a.batch), block(64);
     const T* w = (const T*)a.w;
-#define FTP_BWD(KK, SS, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, SS, PL, CIB>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch)
+#define FTP_BWD(KK, SS, PL) hipLaunchKernelGGL((k_conv_bwd_data_direct<T, KK, SS, PL, CIB>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch, bpc)
     FTP_GEOMETRY(FTP_BWD);
 #undef FTP_BWD
 }
