@@ -322,6 +322,9 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
                     prep_filter(a.w, a.bf16, mfma_conv_packs_bf16(a), nullptr, wt, a.Cout, a.Cin, a.K, s);
                     if (mfma_conv_bwd_data(a, ext, wt, s)) direct_conv_bwd_data(a, s);
                 });
+            } else if (use_mfma() && thin_bwd_data_strided_eligible(a)) {
+                const RectTab ext = view_extent(p, u.in_delta, u.group, u.bo);
+                rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { thin_conv_bwd_data_strided(a, ext, s); });
             } else if (fast && thin_bwd_data_eligible(a)) {
                 rc = timed(plan, FTP_PASS_CONV_BWD_DATA, u.layer, s, [&] { thin_conv_bwd_data(a, s); });
             } else {

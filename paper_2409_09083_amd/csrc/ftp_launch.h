@@ -110,6 +110,8 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s);
 
 bool thin_conv_fwd_eligible(const ConvArgs& a);
 void thin_conv_fwd(const ConvArgs& a, hipStream_t s);
+bool thin_bwd_data_strided_eligible(const ConvArgs& a);
+void thin_conv_bwd_data_strided(const ConvArgs& a, const RectTab& ext, hipStream_t s);   // ext: extent of the delta view per stack
 bool thin_bwd_data_eligible(const ConvArgs& a);
 void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s);
 bool thin_wgrad_eligible(const ConvArgs& c);

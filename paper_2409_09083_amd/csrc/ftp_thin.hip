@@ -364,6 +364,123 @@ k_conv_bwd_data_thin4(View din, View mask, View dout, View isign, int scale_out,
         }
 }
 
+// ---- delta at the input of a stride-2 convolution with at most 4 input channels (the image side of a strided stem) ----
+// Input pixel (2j + a, 2i + b) receives W[ky][kx] dZ[qy][qx] from the taps with ky = a + P, kx = b + P (mod 2), at
+// qy = j + (a + P - ky) / 2, qx likewise: the four pixels of a cell (j, i) together use every tap exactly once and
+// read the deltas of the cells [j + QLO, j + QHI] x [i + QLO, i + QHI] (4 x 4 for a 7x7 filter).
+// Workgroup = 16 x 16 cells (32 x 32 pixels) of one (stack, image), one cell per thread.  Per 16 output channels the
+// delta patch (tile + that halo; zero outside the stack's delta rectangle) and the filter slice [co][tap][ci padded
+// to 4] (fp32) are staged in LDS; a thread reads its NQ x NQ deltas and one 16-byte filter vector per tap for
+// K * K * CI multiply-adds per output channel.
+template <int K> struct StridedTaps {
+    static constexpr int P = K / 2;
+    static constexpr int QLO = -((K - 1 - P) / 2), QHI = (1 + P) / 2, NQ = QHI - QLO + 1;
+};
+constexpr int kThinS2Coc = 16, kThinS2Cells = 16;
+
+template <typename T, int K, int CI>
+__global__ void __launch_bounds__(256)
+k_conv_bwd_data_thin_s2(View din, View dout, View isign, int scale_out, float in_slope, RectTab rt, RectTab ext,
+                        const T* __restrict__ w, int Cin, int Cout, int M, int batch, int tiles_x)
+{
+    typedef StridedTaps<K> G;
+    constexpr int P = G::P, QLO = G::QLO, NQ = G::NQ, KK = K * K;
+    constexpr int COC = kThinS2Coc, TC = kThinS2Cells, PD = TC + NQ - 1, PDP = PD + 1;     // patch extent, padded pitch
+    __shared__ __attribute__((aligned(16))) float dzl[COC * PD * PDP];
+    __shared__ __attribute__((aligned(16))) float wl[COC * KK * 4];
+    const int tid = threadIdx.x;
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    const int bx = blockIdx.x % tiles_x, by = blockIdx.x / tiles_x;
+    const int J0 = (rt.y0[ti] >> 1) + by * TC, I0 = (rt.x0[tj] >> 1) + bx * TC;      // first cell of the tile
+    if (2 * J0 > rt.y1[ti] || 2 * I0 > rt.x1[tj]) return;
+    const int cy = tid / TC, cx = tid % TC;
+    float acc[2][2][CI];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int c = 0; c < CI; ++c) acc[a][b][c] = 0.0f;
+
+    for (int c0 = 0; c0 < Cout; c0 += COC) {
+        __syncthreads();                               // the previous slice has been consumed
+        // delta patch: rows QLO .. of the tile's cells, COC channels; lanes run along a patch row
+        for (int e = tid; e < COC * PD * PD; e += 256) {
+            const int c = e / (PD * PD), r = e - c * (PD * PD);
+            const int py = r / PD, px = r - py * PD;
+            const int qy = J0 + QLO + py, qx = I0 + QLO + px;
+            float v = 0.0f;
+            if (c0 + c < Cout && qy >= ext.y0[ti] && qy <= ext.y1[ti] && qx >= ext.x0[tj] && qx <= ext.x1[tj])
+                v = ld(at<T>(din, stack, ti, tj, n, c0 + c, qy, qx));
+            dzl[(c * PD + py) * PDP + px] = v;
+        }
+        // filter slice as fp32, [co][tap][ci (4)]
+        for (int e = tid; e < COC * KK * 4; e += 256) {
+            const int c = e / (KK * 4), r = e - c * (KK * 4);
+            const int t = r >> 2, ci = r & 3;
+            wl[e] = (c0 + c < Cout && ci < Cin) ? ld(w + ((size_t)(c0 + c) * Cin + ci) * KK + t) : 0.0f;
+        }
+        __syncthreads();
+        for (int c = 0; c < COC; ++c) {
+            if (c0 + c >= Cout) break;
+            float dv[NQ][NQ];
+#pragma unroll
+            for (int y = 0; y < NQ; ++y)
+#pragma unroll
+                for (int x = 0; x < NQ; ++x) dv[y][x] = dzl[(c * PD + cy + y) * PDP + cx + x];
+            const float4* wc = (const float4*)(wl + c * KK * 4);
+#pragma unroll
+            for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+                for (int kx = 0; kx < K; ++kx) {
+                    const int a = (ky + P) & 1, b = (kx + P) & 1;
+                    const int dy = (a + P - ky) / 2 - QLO, dx = (b + P - kx) / 2 - QLO;     // compile-time after unrolling
+                    const float4 wv = wc[ky * K + kx];
+                    const float d = dv[dy][dx];
+                    acc[a][b][0] = fmaf(wv.x, d, acc[a][b][0]);
+                    if (CI > 1) acc[a][b][1] = fmaf(wv.y, d, acc[a][b][1]);
+                    if (CI > 2) acc[a][b][2] = fmaf(wv.z, d, acc[a][b][2]);
+                    if (CI > 3) acc[a][b][3] = fmaf(wv.w, d, acc[a][b][3]);
+                }
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int iy = 2 * (J0 + cy) + a, ix = 2 * (I0 + cx) + b;
+            if (iy < rt.y0[ti] || iy > rt.y1[ti] || ix < rt.x0[tj] || ix > rt.x1[tj]) continue;
+#pragma unroll
+            for (int c = 0; c < CI; ++c)
+                if (c < Cin) {
+                    float v = acc[a][b][c];
+                    if (scale_out) v = scaled_delta<T>(v, sign_bit(isign, stack, ti, tj, n, c, iy, ix), in_slope);
+                    st(at<T>(dout, stack, ti, tj, n, c, iy, ix), v);
+                }
+        }
+}
+
+bool thin_bwd_data_strided_eligible(const ConvArgs& a) { return a.S == 2 && a.Cin <= 4 && !a.pooled && a.K >= 3; }
+
+// c.rect = backward rectangle at the input boundary; ext = extent of the delta view per stack.
+void thin_conv_bwd_data_strided(const ConvArgs& a, const RectTab& ext, hipStream_t s)
+{
+    int mw = 0, mh = 0;                                // cells per dimension of the largest rectangle
+    for (int t = 0; t < a.M; ++t) mw = std::max(mw, (a.rect.x1[t] >> 1) - (a.rect.x0[t] >> 1) + 1);
+    for (int t = 0; t < a.N; ++t) mh = std::max(mh, (a.rect.y1[t] >> 1) - (a.rect.y0[t] >> 1) + 1);
+    const int tiles_x = (mw + kThinS2Cells - 1) / kThinS2Cells, tiles_y = (mh + kThinS2Cells - 1) / kThinS2Cells;
+    dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
+    g_kernel_label = "k_conv_bwd_data_thin_s2";
+#define FTP_S2(T, KK, CI) hipLaunchKernelGGL((k_conv_bwd_data_thin_s2<T, KK, CI>), grid, block, 0, s, a.din, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, ext, (const T*)a.w, a.Cin, a.Cout, a.M, a.batch, tiles_x)
+#define FTP_S2C(T, KK) do { if (a.Cin <= 3) FTP_S2(T, KK, 3); else FTP_S2(T, KK, 4); } while (0)
+#define FTP_S2K(T) do { if (a.K == 7) FTP_S2C(T, 7); else if (a.K == 5) FTP_S2C(T, 5); else FTP_S2C(T, 3); } while (0)
+    if (a.bf16) FTP_S2K(bf16_t); else FTP_S2K(float);
+#undef FTP_S2K
+#undef FTP_S2C
+#undef FTP_S2
+}
+
 bool thin_bwd_data_eligible(const ConvArgs& a) { return a.Cin <= 4; }
 
 void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
