@@ -274,24 +274,50 @@ k_pool_fwd(View in, View out, View mask, RectTab rt, RectTab own, int C, int M, 
     if (in_rect(own, ti, tj, oy, ox)) *at<uint8_t>(mask, stack, ti, tj, n, c, oy, ox) = (uint8_t)((bi << 1) | (best > 0.0f ? 1 : 0));
 }
 
+// One pool window (2 x 2 input pixels) per thread: the winner code and the pooled delta are loaded once (and
+// independently of each other), the four results are written row by row, two pixels at a time where both lie in the
+// rectangle and the pair sits on an aligned address.  Windows that only touch the rectangle's border, and the last row
+// / column of an odd map (which lies in no window and gets 0), are handled element by element.
 template <typename T>
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(256)
 k_pool_bwd(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt, int C, int Ho, int Wo, int M, int batch)
 {
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
-    const int rw = rt.x1[tj] - rt.x0[tj] + 1, rh = rt.y1[ti] - rt.y0[ti] + 1;
+    const int x0 = rt.x0[tj], x1 = rt.x1[tj], y0 = rt.y0[ti], y1 = rt.y1[ti];
+    const int wx0 = x0 >> 1, wy0 = y0 >> 1, ww = (x1 >> 1) - wx0 + 1, wh = (y1 >> 1) - wy0 + 1;
     const int pid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (pid >= rw * rh) return;
-    const int iy = rt.y0[ti] + pid / rw, ix = rt.x0[tj] + pid % rw;
+    if (pid >= ww * wh) return;
+    const int wy = wy0 + pid / ww, wx = wx0 + pid % ww;
     const int c = blockIdx.y;
-    float g = 0.0f;
-    if ((iy >> 1) < Ho && (ix >> 1) < Wo) {            // the last row / column of an odd map lies in no window
-        const uint8_t a = (*at<uint8_t>(mask, stack, ti, tj, n, c, iy >> 1, ix >> 1) >> 1) & 3;
-        if (a == (uint8_t)(((iy & 1) << 1) | (ix & 1))) g = ld(at<T>(din, stack, ti, tj, n, c, iy >> 1, ix >> 1));
+    const bool has = wy < Ho && wx < Wo;
+    // the loads are unconditional: a window of the dropped row / column reads the rectangle's first window instead,
+    // which (like every window the rectangle touches) lies inside the stack's delta rectangle at the pooled boundary
+    const int sy = has ? wy : wy0, sx = has ? wx : wx0;
+    const uint8_t code = *at<uint8_t>(mask, stack, ti, tj, n, c, sy, sx);
+    const float gd = ld(at<T>(din, stack, ti, tj, n, c, sy, sx));
+    const int win = has ? ((code >> 1) & 3) : -1;
+#pragma unroll
+    for (int dy = 0; dy < 2; ++dy) {
+        const int iy = 2 * wy + dy;
+        if (iy < y0 || iy > y1) continue;
+        float g[2]; bool ok[2];
+#pragma unroll
+        for (int dx = 0; dx < 2; ++dx) {
+            const int ix = 2 * wx + dx;
+            ok[dx] = ix >= x0 && ix <= x1;
+            g[dx] = win == 2 * dy + dx ? gd : 0.0f;
+            if (scale_out && ok[dx]) g[dx] = scaled_delta<T>(g[dx], sign_bit(isign, stack, ti, tj, n, c, iy, ix), in_slope);
+        }
+        T* p = at<T>(dout, stack, ti, tj, n, c, iy, 2 * wx);
+        if (ok[0] && ok[1] && ((uintptr_t)p & (2 * sizeof(T) - 1)) == 0) {
+            if constexpr (sizeof(T) == 4) *(float2*)p = make_float2(g[0], g[1]);
+            else *(uint32_t*)p = bf16_bits(g[0]) | (bf16_bits(g[1]) << 16);
+        } else {
+            if (ok[0]) st(p, g[0]);
+            if (ok[1]) st(p + 1, g[1]);
+        }
     }
-    if (scale_out) g = scaled_delta<T>(g, sign_bit(isign, stack, ti, tj, n, c, iy, ix), in_slope);
-    st(at<T>(dout, stack, ti, tj, n, c, iy, ix), g);
 }
 
 // ---- sum of the per-stack partial gradients ------------------------------------------------------------
@@ -443,7 +469,11 @@ void pool_fwd(const PoolArgs& a, hipStream_t s)
 void pool_bwd(const PoolArgs& a, hipStream_t s)
 {
     g_kernel_label = "k_pool_bwd";
-    dim3 grid((rect_max_px(a.rect, a.N, a.M) + 63) / 64, a.C, a.N * a.M * a.batch), block(64);
+    int mw = 0, mh = 0;                                // windows touched by the largest rectangle
+    for (int t = 0; t < a.M; ++t) mw = std::max(mw, (a.rect.x1[t] >> 1) - (a.rect.x0[t] >> 1) + 1);
+    for (int t = 0; t < a.N; ++t) mh = std::max(mh, (a.rect.y1[t] >> 1) - (a.rect.y0[t] >> 1) + 1);
+    const int bs = mw * mh <= 64 ? 64 : mw * mh <= 128 ? 128 : 256;          // small rectangles: no idle wavefronts
+    dim3 grid((mw * mh + bs - 1) / bs, a.C, a.N * a.M * a.batch), block(bs);
     if (a.bf16) hipLaunchKernelGGL(k_pool_bwd<bf16_t>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.Ho, a.Wo, a.M, a.batch);
     else        hipLaunchKernelGGL(k_pool_bwd<float>, grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, a.C, a.Ho, a.Wo, a.M, a.batch);
 }
