@@ -92,8 +92,9 @@ struct Plan {
 // of at most 64 pixels (rows padded to an even length) and 192 patch positions: column blocks of TC, row blocks
 // of TR, and, where a whole rectangle is smaller than a chunk, TI images at once.  Used by the kernel and by the
 // host (share count), so both see the same numbers.
-// (Patch positions: 192 up to 3x3 filters, 256 for 5x5 and 7x7.)
-FTP_HD constexpr int wgrad_xpos(int P) { return P <= 1 ? 192 : 256; }
+// (Patch positions: a 1x1 filter reads exactly the chunk's 64 pixels; 192 for 3x3 filters, 256 for 5x5 and 7x7.
+// The smaller the patch, the more workgroups share a CU's LDS.)
+FTP_HD constexpr int wgrad_xpos(int P) { return P == 0 ? 64 : P == 1 ? 192 : 256; }
 struct WgradChunks { int col_blocks, TC, TCp, PW, TR, row_blocks, TI, img_blocks, total; };
 FTP_HD inline WgradChunks wgrad_chunks(int rw, int rh, int batch, int P)
 {
