@@ -123,17 +123,19 @@ FTP_HD inline WgradChunks wgrad_chunks(int rw, int rh, int batch, int P)
 // Number of shares the matrix-core filter-gradient kernel splits one stack's chunk list into (contiguous ranges,
 // summed afterwards in share order).  A workgroup handles one 64 x 64 block of (co, ci) of one stack and one share;
 // two workgroups share a CU's matrix cores, so a launch takes ceil(workgroups / 512) rounds of 2 x ceil(chunks /
-// shares) chunk times.  The count that minimises that plus the cost of writing and re-reading the shares is taken.
+// shares) chunk times (1x1 filters: four smaller workgroups per CU, bound by staging rather than by the matrix
+// cores, hence 1024 slots at the same time per round).  The count that minimises that plus the cost of writing and re-reading the shares is taken.
 // chunks = chunk count of the largest stack.
 inline int wgrad_shares(int cout, int cin, int k, int stacks, int chunks)
 {
     const double blocks = (double)((cout + 63) / 64) * ((cin + 63) / 64) * stacks;
     const double unit_us = 64.0 * k * k * 32.0 / 2400.0 / 0.7;                          // one chunk of one block
     const double share_us = (double)stacks * cout * cin * k * k * 8.0 / 3.0e6;          // one more share: write + read
+    const double slots = k == 1 ? 1024.0 : 512.0;                                       // 1x1: four workgroups per CU
     const int smax = chunks < 256 ? chunks : 256;
     int best = 1; double best_t = 0;
     for (int s = 1; s <= smax; ++s) {
-        const double rounds = (double)(long long)((blocks * s + 511) / 512);
+        const double rounds = (double)(long long)((blocks * s + slots - 1) / slots);
         const double t = rounds * 2.0 * ((chunks + s - 1) / s) * unit_us + (s > 1 ? s * share_us : 0.0);
         if (s == 1 || t < best_t) { best = s; best_t = t; }
     }
