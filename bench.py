@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-update", action="store_true",
                     help="close every step with the fused gradient sum + filter update (lr 0) instead of the plain gradient sum")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run the filter gradients on a second stream beside the delta back-propagation (ftp_set_overlap); "
+                         "the per-kernel records then show overlapped, hence longer, launches")
     ap.add_argument("--per-kernel", action="store_true", help="print the per-kernel timing table to stderr")
     ap.add_argument("--cpu-images", type=int, default=0, help="images for the oracle timing (0 = automatic)")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -84,6 +87,8 @@ def main():
     s = Session(cfg.layers, cfg.batch, cfg.in_c, cfg.in_h, cfg.in_w, cfg.grid, cfg.group_ends, cfg.dtype)
     s.load(x=x, weights=ws, dy=dy)
     del x, dy
+    if args.overlap:
+        s.set_overlap(True)
     torch.cuda.synchronize()
 
     if args.traffic_probe:

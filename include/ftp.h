@@ -161,6 +161,16 @@ int ftp_reduce_wgrad(const ftp_plan_t* plan, const float* wgrad_partials, float*
 int ftp_sgd_step(const ftp_plan_t* plan, const float* wgrad_partials, void* const* weights, void* const* biases,
                  float lr, float* wgrad, void* stream);
 
+/* Backward pass on two streams (Sec. 4.1: the delta back-propagation and the filter gradients of a layer both start
+ * from the same delta map and do not depend on each other).  When enabled, ftp_backward runs each unit's filter
+ * gradient on a second HIP stream of its own (default priority; a host object created on first use and owned by the
+ * plan) beside the unit's delta back-propagation on the caller's stream, ordered with events so that no kernel
+ * overwrites a map another one still reads; before ftp_backward returns, the caller's stream has been made to wait for
+ * the second one, so the caller sees one stream as before.  Results are bit-identical either way.  Off by default
+ * (on if the environment variable FTP_OVERLAP is 1 when the plan is created).  Kernels that run side by side share the
+ * GPU, so the per-kernel records of ftp_profile then show longer launches while the whole pass gets shorter. */
+int ftp_set_overlap(ftp_plan_t* plan, int32_t enable);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch of the three passes is
  * bracketed by two HIP events on the caller's stream (host objects, created on first use and
  * owned by the plan).  ftp_profile(plan, 1) clears earlier records and starts collecting,

@@ -75,11 +75,12 @@ def _load():
     lib.ftp_reduce_wgrad.argtypes = [vp, vp, vp, vp]
     lib.ftp_sgd_step.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_float, vp, vp]
     lib.ftp_profile.argtypes = [vp, i32]
+    lib.ftp_set_overlap.argtypes = [vp, i32]
     lib.ftp_profile_read.argtypes = [vp, ctypes.POINTER(ftp_kernel_time), i32, ctypes.POINTER(i32)]
     lib.ftp_strerror.argtypes = [ctypes.c_int]
     lib.ftp_strerror.restype = ctypes.c_char_p
     lib.ftp_last_hip_error.restype = ctypes.c_int
-    for f in ("ftp_profile", "ftp_profile_read", "ftp_plan_buffer", "ftp_plan_rect", "ftp_plan_map_shape", "ftp_plan_sizes", "ftp_plan_work", "ftp_forward",
+    for f in ("ftp_profile", "ftp_profile_read", "ftp_set_overlap", "ftp_plan_buffer", "ftp_plan_rect", "ftp_plan_map_shape", "ftp_plan_sizes", "ftp_plan_work", "ftp_forward",
               "ftp_backward", "ftp_reduce_wgrad", "ftp_sgd_step"):
         getattr(lib, f).restype = ctypes.c_int
     return lib
@@ -87,7 +88,7 @@ def _load():
 
 _lib = _load()
 
-EXPORTS = ("ftp_profile", "ftp_profile_read", "ftp_plan", "ftp_plan_destroy", "ftp_plan_buffer", "ftp_plan_rect", "ftp_plan_map_shape", "ftp_plan_sizes", "ftp_plan_work",
+EXPORTS = ("ftp_profile", "ftp_profile_read", "ftp_set_overlap", "ftp_plan", "ftp_plan_destroy", "ftp_plan_buffer", "ftp_plan_rect", "ftp_plan_map_shape", "ftp_plan_sizes", "ftp_plan_work",
            "ftp_forward", "ftp_backward", "ftp_reduce_wgrad", "ftp_sgd_step", "ftp_strerror", "ftp_last_hip_error")
 
 
@@ -182,6 +183,10 @@ def ftp_reduce_wgrad(plan, wgrad_partials, wgrad, stream=0):
 def ftp_sgd_step(plan, wgrad_partials, weights, biases, lr, wgrad=0, stream=0):
     n = len(weights)
     _check(_lib.ftp_sgd_step(plan, wgrad_partials, _ptr_array(weights, n), _ptr_array(biases, n), lr, wgrad, stream), "ftp_sgd_step")
+
+
+def ftp_set_overlap(plan, enable):
+    _check(_lib.ftp_set_overlap(plan, 1 if enable else 0), "ftp_set_overlap")
 
 
 def ftp_profile(plan, enable):

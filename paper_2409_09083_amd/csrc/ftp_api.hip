@@ -157,6 +157,13 @@ int check_weights(const Plan& p, const void* const* weights, const void* const* 
     return FTP_OK;
 }
 
+// FTP_OVERLAP=1: plans start with the two-stream backward pass switched on (see ftp_set_overlap).
+bool overlap_default()
+{
+    const char* e = std::getenv("FTP_OVERLAP");
+    return e && std::strcmp(e, "1") == 0;
+}
+
 bool any_bias(const Plan& p)
 {
     for (const ftp_layer& ly : p.layers) if (ly.kind == FTP_CONV && ly.has_bias) return true;
@@ -171,7 +178,16 @@ int ftp_plan(const ftp_layer* layers, int32_t n_layers, int32_t batch, int32_t i
              int32_t grid_rows, int32_t grid_cols, const int32_t* group_ends, int32_t n_groups,
              ftp_dtype dtype, ftp_plan_t** out_plan)
 {
-    return build_plan(layers, n_layers, batch, in_c, in_h, in_w, grid_rows, grid_cols, group_ends, n_groups, dtype, out_plan);
+    const int rc = build_plan(layers, n_layers, batch, in_c, in_h, in_w, grid_rows, grid_cols, group_ends, n_groups, dtype, out_plan);
+    if (rc == FTP_OK) (*out_plan)->overlap.on = overlap_default();
+    return rc;
+}
+
+int ftp_set_overlap(ftp_plan_t* plan, int32_t enable)
+{
+    if (!plan) return FTP_EINVAL;
+    plan->overlap.on = enable != 0;
+    return FTP_OK;
 }
 
 void ftp_plan_destroy(ftp_plan_t* plan) { delete plan; }
@@ -297,6 +313,38 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
         });
         if (rc != FTP_OK) return rc;
     }
+    // Optional second stream: the filter gradient of unit i (reads the delta at its output boundary, writes the
+    // partial gradients) runs beside the delta back-propagation of unit i (reads the same delta, writes the delta at
+    // its input boundary).  The next step on `s` overwrites the ping-pong region the gradient is reading, so it waits
+    // for it; the next gradient waits for the step that produces its delta.
+    Overlap& ov = plan->overlap;
+    const bool overlap = ov.on;
+    hipStream_t aux = s;
+    size_t next_event = 0;
+    auto new_event = [&]() -> hipEvent_t {
+        if (next_event == ov.events.size()) {
+            hipEvent_t e = nullptr;
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+            ov.events.push_back(e);
+        }
+        return (hipEvent_t)ov.events[next_event++];
+    };
+    // makes stream `to` wait for everything enqueued on `from` so far
+    auto order = [&](hipStream_t from, hipStream_t to) -> int {
+        hipEvent_t e = new_event();
+        if (!e || hipEventRecord(e, from) != hipSuccess || hipStreamWaitEvent(to, e, 0) != hipSuccess) { g_last_hip = (int)hipGetLastError(); return FTP_EHIP; }
+        return FTP_OK;
+    };
+    if (overlap) {
+        if (!ov.aux) {
+            hipStream_t st = nullptr;
+            if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) { g_last_hip = (int)hipGetLastError(); return FTP_EHIP; }
+            ov.aux = st;
+        }
+        aux = (hipStream_t)ov.aux;
+        if ((rc = order(s, aux)) != FTP_OK) return rc;          // the forward pass, dy scaling, earlier calls
+    }
+    bool gradient_in_flight = false;
     for (int i = (int)p.units.size() - 1; i >= 0; --i) {
         const Unit& u = p.units[i];
         if (u.kind == UNIT_CONV) {
@@ -306,14 +354,18 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             a.own = make_rect(p, u.group, FTP_RECT_OWN, u.layer);
             float* scratch = (float*)((char*)workspace + p.wgrad_scratch_offset);
             const bool fast = use_mfma() && plain_geometry(a);
+            // (the previous gradient is still reading the region this unit's delta step will overwrite; gradients
+            // are serial among themselves on `aux`, they share the scratch)
+            if (overlap && gradient_in_flight && (rc = order(aux, s)) != FTP_OK) return rc;
             if (use_mfma() && thin_wgrad_eligible(a)) {
-                rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { thin_wgrad(a, scratch, s); });
+                rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { thin_wgrad(a, scratch, aux); });
             } else if (use_mfma() && mfma_wgrad_eligible(a)) {
-                rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { mfma_wgrad(a, scratch, s); });
+                rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { mfma_wgrad(a, scratch, aux); });
             } else {
-                rc = timed(plan, FTP_PASS_WGRAD, u.layer, s, [&] { direct_wgrad(a, s); });
+                rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { direct_wgrad(a, aux); });
             }
             if (rc != FTP_OK) return rc;
+            gradient_in_flight = overlap;
             a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
             if (use_mfma() && mfma_conv_eligible(a, true)) {
                 float* wt = (float*)((char*)workspace + u.wt_bwd_offset);
@@ -333,10 +385,13 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
         } else {
             PoolArgs a = pool_args(p, u, ub);
             a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
+            if (overlap && gradient_in_flight) { if ((rc = order(aux, s)) != FTP_OK) return rc; gradient_in_flight = false; }
             rc = timed(plan, FTP_PASS_POOL_BWD, u.layer, s, [&] { pool_bwd(a, s); });
         }
         if (rc != FTP_OK) return rc;
+        if (overlap && i > 0 && (rc = order(s, aux)) != FTP_OK) return rc;      // the next gradient reads the delta just written
     }
+    if (overlap && (rc = order(aux, s)) != FTP_OK) return rc;                   // the caller's stream sees every partial gradient
     return FTP_OK;
 }
 
@@ -475,6 +530,12 @@ void Profiler::recycle()
 {
     for (const Rec& r : pending) { free_list.push_back(r.a); free_list.push_back(r.b); }
     pending.clear();
+}
+
+Overlap::~Overlap()
+{
+    for (void* e : events) (void)hipEventDestroy((hipEvent_t)e);
+    if (aux) (void)hipStreamDestroy((hipStream_t)aux);
 }
 
 Profiler::~Profiler()

@@ -195,7 +195,19 @@ struct Profiler {
 };
 }  // namespace ftp
 
+// Second stream of the backward pass (optional): the filter gradient of a unit runs beside the delta
+// back-propagation of the same unit.  Host objects only, created on first use and owned by the plan.
+namespace ftp {
+struct Overlap {
+    bool on = false;
+    void* aux = nullptr;                // hipStream_t (default priority)
+    std::vector<void*> events;          // hipEvent_t, reused call after call
+    ~Overlap();
+};
+}  // namespace ftp
+
 struct ftp_plan_s {
     ftp::Plan p;
     mutable ftp::Profiler prof;
+    mutable ftp::Overlap overlap;
 };

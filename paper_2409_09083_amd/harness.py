@@ -70,6 +70,10 @@ class Session:
             return None
         return [0 if b is None else b.data_ptr() for b in self.biases]
 
+    def set_overlap(self, enable):
+        """Filter gradients on a second stream beside the delta back-propagation (same results, shorter pass)."""
+        B.ftp_set_overlap(self.plan, enable)
+
     def _stream(self):
         return torch.cuda.current_stream().cuda_stream
 

@@ -114,3 +114,32 @@ def test_sgd_step_bf16(oracle):
         # a fused multiply-add may round the fp32 intermediate differently: at most one bf16 step apart
         assert np.max(np.abs(got - want)) <= 2.0 ** -7 * float(np.abs(want).max()), l
     s.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_two_stream_backward_is_bit_identical(oracle, dtype):
+    """ftp_set_overlap: the filter gradients on a second stream beside the delta back-propagation give the same bits
+    (the same kernels in the same order per buffer), call after call, also through several groups and lone pools."""
+    import torch
+    layers = (conv(3, 16), pool(16), conv(16, 32), conv(32, 32, 1), pool(32), pool(32), conv(32, 48), conv(48, 32, 5), conv(32, 64, 3, stride=2))
+    cfg = Config("overlap", 3, 3, 96, 80, layers, (2, 3), (3, 6, 9), dtype)
+    x, ws, bs, dy = C.make_tensors(cfg)
+    s = P.make_session(cfg, x.shape[0])
+    s.load(x=x, weights=ws, dy=dy)
+    s.step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (s.y, s.dx, s.wgrad, s.partials)]
+    s.set_overlap(True)
+    for _ in range(3):
+        for t in (s.dx, s.wgrad, s.partials):
+            t.fill_(float("nan"))
+        s.step()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, (s.y, s.dx, s.wgrad, s.partials)):
+            assert torch.equal(a, b)
+    s.set_overlap(False)
+    s.step()
+    torch.cuda.synchronize()
+    for a, b in zip(ref, (s.y, s.dx, s.wgrad, s.partials)):
+        assert torch.equal(a, b)
+    s.close()
