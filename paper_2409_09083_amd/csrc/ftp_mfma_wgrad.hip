@@ -236,18 +236,20 @@ k_wgrad_mfma(MfmaWgradArgs a)
         __syncthreads();
         float* red = lds;                               // [WAVES_CO*WAVES_CI][16][64]
 #pragma unroll
-        for (int t = 0; t < NTAP; ++t) {
-            if (wave_k == 1) {
+        for (int t = 0; t < NTAP; ++t)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) red[((wave % (WAVES_CO * WAVES_CI)) * 16 + i) * 64 + lane] = acc[t][i];
-            }
-            __syncthreads();
-            if (wave_k == 0) {
+            for (int k = 1; k < WAVES_K; ++k) {            // in wavefront order
+                if (wave_k == k) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[t][i] += red[((wave % (WAVES_CO * WAVES_CI)) * 16 + i) * 64 + lane];
+                    for (int i = 0; i < 16; ++i) red[((wave % (WAVES_CO * WAVES_CI)) * 16 + i) * 64 + lane] = acc[t][i];
+                }
+                __syncthreads();
+                if (wave_k == 0) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[t][i] += red[((wave % (WAVES_CO * WAVES_CI)) * 16 + i) * 64 + lane];
+                }
+                __syncthreads();
             }
-            __syncthreads();
-        }
     }
     if (wave_k == 0) {
         const long long layer_params = (long long)a.Cout * a.Cin * KK;
@@ -300,28 +302,31 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     a.PK = kWgradZPos;
     // (64 input channels per workgroup where the patch of a 5x5 / 7x7 filter would not leave LDS for two workgroups)
     const int waves_ci = (c.Cin >= 64 && c.K <= 3) ? 2 : 1;
-    const int BCO = 64, BCI = 32 * waves_ci;
+    // (32 output channels per workgroup for the 3x3 layers that have no more: all four wavefronts then split the pixels)
+    const int waves_co = (c.Cout <= 32 && c.K == 3 && waves_ci == 1) ? 1 : 2;
+    const int BCO = 32 * waves_co, BCI = 32 * waves_ci;
     // (+ the bfloat path's table of patch positions)
     const size_t lds = ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1) + kWgradZPos) * sizeof(float);
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
     const int parts = c.K == 5 ? 3 : c.K == 7 ? 7 : 1;                 // filter rows 2 + 2 + 1, or one at a time
     dim3 grid(tiles * parts, a.splits, c.N * c.M), block(256);
     // more than 64 KB of dynamic LDS has to be granted per kernel, once
-#define FTP_WG1(TT, TN, KK, WCI, HF, TR) do { \
+#define FTP_WG1(TT, TN, KK, WCO, WCI, HF, TR) do { \
         static bool granted = false; \
-        if (!granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_mfma<TT, KK, 2, WCI, HF, TR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); granted = true; } \
-        g_kernel_label = "k_wgrad_mfma<" TN ", " #KK ", 2, " #WCI ", " #HF ", " #TR ">"; \
-        hipLaunchKernelGGL((k_wgrad_mfma<TT, KK, 2, WCI, HF, TR>), grid, block, lds, s, a); } while (0)
-#define FTP_WG(KK, WCI, HF, TR) do { if (c.bf16) FTP_WG1(bf16_t, "unsigned short", KK, WCI, HF, TR); else FTP_WG1(float, "float", KK, WCI, HF, TR); } while (0)
+        if (!granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_mfma<TT, KK, WCO, WCI, HF, TR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); granted = true; } \
+        g_kernel_label = "k_wgrad_mfma<" TN ", " #KK ", " #WCO ", " #WCI ", " #HF ", " #TR ">"; \
+        hipLaunchKernelGGL((k_wgrad_mfma<TT, KK, WCO, WCI, HF, TR>), grid, block, lds, s, a); } while (0)
+#define FTP_WG(KK, WCO, WCI, HF, TR) do { if (c.bf16) FTP_WG1(bf16_t, "unsigned short", KK, WCO, WCI, HF, TR); else FTP_WG1(float, "float", KK, WCO, WCI, HF, TR); } while (0)
     const int half = c.pooled ? 1 : c.S == 2 ? 2 : 0;
-    if (c.K == 7) FTP_WG(7, 1, 0, 1);
-    else if (c.K == 5) FTP_WG(5, 1, 0, 2);
+    if (c.K == 7) FTP_WG(7, 2, 1, 0, 1);
+    else if (c.K == 5) FTP_WG(5, 2, 1, 0, 2);
     else if (c.K == 3) {
-        if (waves_ci == 2) { if (half == 1) FTP_WG(3, 2, 1, 3); else if (half == 2) FTP_WG(3, 2, 2, 3); else FTP_WG(3, 2, 0, 3); }
-        else               { if (half == 1) FTP_WG(3, 1, 1, 3); else if (half == 2) FTP_WG(3, 1, 2, 3); else FTP_WG(3, 1, 0, 3); }
+        if (waves_co == 1)      { if (half == 1) FTP_WG(3, 1, 1, 1, 3); else if (half == 2) FTP_WG(3, 1, 1, 2, 3); else FTP_WG(3, 1, 1, 0, 3); }
+        else if (waves_ci == 2) { if (half == 1) FTP_WG(3, 2, 2, 1, 3); else if (half == 2) FTP_WG(3, 2, 2, 2, 3); else FTP_WG(3, 2, 2, 0, 3); }
+        else                    { if (half == 1) FTP_WG(3, 2, 1, 1, 3); else if (half == 2) FTP_WG(3, 2, 1, 2, 3); else FTP_WG(3, 2, 1, 0, 3); }
     } else {
-        if (waves_ci == 2) { if (half == 1) FTP_WG(1, 2, 1, 1); else if (half == 2) FTP_WG(1, 2, 2, 1); else FTP_WG(1, 2, 0, 1); }
-        else               { if (half == 1) FTP_WG(1, 1, 1, 1); else if (half == 2) FTP_WG(1, 1, 2, 1); else FTP_WG(1, 1, 0, 1); }
+        if (waves_ci == 2) { if (half == 1) FTP_WG(1, 2, 2, 1, 1); else if (half == 2) FTP_WG(1, 2, 2, 2, 1); else FTP_WG(1, 2, 2, 0, 1); }
+        else               { if (half == 1) FTP_WG(1, 2, 1, 1, 1); else if (half == 2) FTP_WG(1, 2, 1, 2, 1); else FTP_WG(1, 2, 1, 0, 1); }
     }
 #undef FTP_WG
 #undef FTP_WG1

@@ -30,6 +30,8 @@ _NETS.update({
     "oddpools": ((conv(3, 8, 5), pool(8), conv(8, 16), pool(16), pool(16), conv(16, 8, 3, stride=2), conv(8, 5, 7)), 61, 51),
     # wide enough for the matrix-core kernels: strided 3x3 / 1x1, 5x5 and 7x7, odd maps
     "stridedmfma": ((conv(8, 32, 3, stride=2), conv(32, 64, 5), conv(64, 32, 7), conv(32, 64, 1, stride=2), conv(64, 48, 3, stride=2), conv(48, 32, 5)), 91, 70),
+    # 32 output channels: the filter-gradient kernel's 32-channel workgroups (plain, pooled, strided)
+    "cout32": ((conv(3, 16), pool(16), conv(16, 32), pool(32), conv(32, 32), conv(32, 32, 3, stride=2), conv(32, 32)), 88, 72),
     "stridedwide": ((conv(3, 32, 3, stride=2), conv(32, 64, 3, stride=2), pool(64), conv(64, 32, 1), conv(32, 48, 5)), 70, 90),
 })
 
@@ -54,14 +56,14 @@ def test_small_nets_bf16(oracle, net, grouping):
     P.check_case(oracle, _mk(net, (3, 2), grouping, "bf16"))
 
 
-@pytest.mark.parametrize("net", ["strided", "oddpools", "stridedwide", "stridedmfma"])
+@pytest.mark.parametrize("net", ["strided", "oddpools", "stridedwide", "stridedmfma", "cout32"])
 @pytest.mark.parametrize("grouping", ["whole", "each", "split"])
 @pytest.mark.parametrize("grid", [(1, 1), (2, 3)])
 def test_general_geometry_f32(oracle, net, grouping, grid):
     P.check_case(oracle, _mk(net, grid, grouping))
 
 
-@pytest.mark.parametrize("net", ["strided", "oddpools", "stridedmfma"])
+@pytest.mark.parametrize("net", ["strided", "oddpools", "stridedmfma", "cout32"])
 def test_general_geometry_bf16_and_bias(oracle, net):
     P.check_case(oracle, _mk(net, (2, 2), "split", "bf16"))
     P.check_case(oracle, _mk(net, (3, 2), "whole"), has_bias=True)
