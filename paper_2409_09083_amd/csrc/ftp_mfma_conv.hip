@@ -579,30 +579,41 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc
     // (the cost model below is for kernels bound by the matrix cores; the bfloat 3x3 path is bound by latency and
     // does best with the most workgroups per CU: 64 channels x 128 pixels; config 5: 14.6 -> 14.4 ms per step)
     const bool small_wg = c.bf16 && K == 3 && !STRIDED_FWD && c.S == 1 && BM == 64;
+    auto consider = [&](int bm, int BN) -> long long {
+        const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD);
+        const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos);
+        if (tc.cs > max_pos) return -1;
+        // tiles that exist: every stack has its own count, the grid is sized for the largest
+        long long wgs = 0;
+        for (int i = 0; i < c.N; ++i)
+            for (int j = 0; j < c.M; ++j) {
+                const int rw = a.rect.x1[j] - a.rect.x0[j] + 1, rh = a.rect.y1[i] - a.rect.y0[i] + 1;
+                const int tcw = tc.tiles_x == 1 ? rw : tc.TC;
+                int trf = tc.cap / tcw; if (trf < 1) trf = 1;
+                const long long rtot = (long long)c.batch * rh;
+                wgs += ((rtot + trf - 1) / trf) * ((rw + tcw - 1) / tcw);
+            }
+        const int mblocks = (a.Mtot + bm - 1) / bm;
+        wgs *= mblocks;
+        const int per_cu = BN == 256 ? (bm == 32 ? 3 : 2) : (bm == 32 ? 4 : 3);
+        const long long slots = 256LL * per_cu;
+        const double rounds = (double)(wgs / slots) * per_cu + (double)((wgs % slots + 255) / 256);
+        // in units of 1/128 cycle: multiply loop, epilogue (about 25k cycles for 128 x 256), set-up (about 10k cycles)
+        const double work = (double)bm * BN * a.C * K * K + 3.2e6 * (bm * BN) / (128.0 * 256.0) + 1.3e6;
+        const double cost = rounds * work * (BN == 256 ? 1.0 : 1.03);
+        if (best.BM == 0 || cost < best_cost) { best = {bm, BN, per_cu}; best_cost = cost; *tc_out = tc; }
+        return wgs;
+    };
+    long long widest_wgs = 0;
     for (int BN = (STRIDED_FWD || small_wg) ? 128 : 256; BN >= 128; BN /= 2) {
-            const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD);
-            const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos);
-            if (tc.cs > max_pos) continue;
-            // tiles that exist: every stack has its own count, the grid is sized for the largest
-            long long wgs = 0;
-            for (int i = 0; i < c.N; ++i)
-                for (int j = 0; j < c.M; ++j) {
-                    const int rw = a.rect.x1[j] - a.rect.x0[j] + 1, rh = a.rect.y1[i] - a.rect.y0[i] + 1;
-                    const int tcw = tc.tiles_x == 1 ? rw : tc.TC;
-                    int trf = tc.cap / tcw; if (trf < 1) trf = 1;
-                    const long long rtot = (long long)c.batch * rh;
-                    wgs += ((rtot + trf - 1) / trf) * ((rw + tcw - 1) / tcw);
-                }
-            const int mblocks = (a.Mtot + BM - 1) / BM;
-            wgs *= mblocks;
-            const int per_cu = BN == 256 ? (BM == 32 ? 3 : 2) : (BM == 32 ? 4 : 3);
-            const long long slots = 256LL * per_cu;
-            const double rounds = (double)(wgs / slots) * per_cu + (double)((wgs % slots + 255) / 256);
-            // in units of 1/128 cycle: multiply loop, epilogue (about 25k cycles for 128 x 256), set-up (about 10k cycles)
-            const double work = (double)BM * BN * a.C * K * K + 3.2e6 * (BM * BN) / (128.0 * 256.0) + 1.3e6;
-            const double cost = rounds * work * (BN == 256 ? 1.0 : 1.03);
-            if (best.BM == 0 || cost < best_cost) { best = {BM, BN, per_cu}; best_cost = cost; *tc_out = tc; }
-        }
+        const long long w = consider(BM, BN);
+        if (w > widest_wgs) widest_wgs = w;
+    }
+    // A launch that does not even fill the CUs once (small batches) is bound by the length of one workgroup's chain
+    // of matrix-core instructions: narrower channel blocks shorten it and bring more CUs to work (config 2, batch 1).
+    if (widest_wgs > 0 && widest_wgs < 256)
+        for (int bm = BM / 2; bm >= 32; bm /= 2)
+            for (int BN = STRIDED_FWD ? 128 : 256; BN >= 128; BN /= 2) consider(bm, BN);
     return best;
 }
 
