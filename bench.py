@@ -169,6 +169,20 @@ def main():
         "halo_bytes_per_step": [work["halo_bytes_fwd"], work["halo_bytes_bwd"]],
         "phases_ms_per_step": phases,
     }
+    if not args.overlap:
+        # the same K steps once more with the two-stream backward pass (ftp_set_overlap) and without per-kernel events:
+        # reported beside `value`, which stays the single-stream figure the roofline above belongs to
+        s.set_overlap(True)
+        for _ in range(min(args.warmup, 2)):
+            one_step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step()
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t1
+        s.set_overlap(False)
+        out["two_stream_backward"] = {"value": cfg.batch * args.steps / dt2, "unit": "images/s", "ms_per_step": dt2 * 1e3 / args.steps}
     if not args.no_cpu_baseline:
         # about 10-20 s of oracle time: 12 images of the large workloads (the oracle is linear in the batch)
         n_img = args.cpu_images or (12 if cfg.name.startswith(("cfg4", "cfg5")) else cfg.batch)
