@@ -21,6 +21,9 @@
  * in both cases).  Parameter vector: concatenation over the convolution layers in layer order
  * of the filter (Cout*Cin*K*K) followed, if the layer has a bias, by the bias (Cout).
  *
+ * A network without convolutions has no parameters (n_params = 0): the gradient pointers may then be null and the
+ * gradient sum and the filter update do nothing.
+ *
  * All functions return 0 on success or a negative ftp_status; nothing throws or aborts.
  */
 #ifndef FTP_H_

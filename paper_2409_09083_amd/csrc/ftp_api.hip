@@ -297,8 +297,9 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
 int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const void* const* weights,
                  void* workspace, void* dx, float* wgrad_partials, void* stream)
 {
-    if (!plan || !dy || !x || !workspace || !dx || !wgrad_partials) return FTP_EINVAL;
+    if (!plan || !dy || !x || !workspace || !dx) return FTP_EINVAL;
     const Plan& p = plan->p;
+    if (!wgrad_partials && p.n_params > 0) return FTP_EINVAL;       // (a network of pools only has no parameters)
     int rc = check_weights(p, weights, nullptr);
     if (rc != FTP_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
@@ -397,9 +398,10 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
 
 int ftp_reduce_wgrad(const ftp_plan_t* plan, const float* wgrad_partials, float* wgrad, void* stream)
 {
-    if (!plan || !wgrad_partials || !wgrad) return FTP_EINVAL;
+    if (!plan) return FTP_EINVAL;
     const Plan& p = plan->p;
-    if (p.n_params == 0) return FTP_OK;
+    if (p.n_params == 0) return FTP_OK;                               // (a network of pools only: nothing to sum)
+    if (!wgrad_partials || !wgrad) return FTP_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     return timed(plan, FTP_PASS_REDUCE, -1, s, [&] { reduce_wgrad(wgrad_partials, wgrad, (long long)p.n_params, p.N * p.M, s); });
 }
@@ -407,8 +409,10 @@ int ftp_reduce_wgrad(const ftp_plan_t* plan, const float* wgrad_partials, float*
 int ftp_sgd_step(const ftp_plan_t* plan, const float* wgrad_partials, void* const* weights, void* const* biases,
                  float lr, float* wgrad, void* stream)
 {
-    if (!plan || !wgrad_partials || !weights) return FTP_EINVAL;
+    if (!plan) return FTP_EINVAL;
     const Plan& p = plan->p;
+    if (p.n_params == 0) return FTP_OK;                               // (a network of pools only: nothing to update)
+    if (!wgrad_partials || !weights) return FTP_EINVAL;
     int rc = check_weights(p, (const void* const*)weights, (const void* const*)biases);
     if (rc != FTP_OK) return rc;
     if (any_bias(p) && !biases) return FTP_EINVAL;

@@ -177,3 +177,32 @@ def _random_net(seed):
 @pytest.mark.parametrize("seed", list(range(48)))
 def test_random_general_networks(oracle, seed):
     P.check_case(oracle, _random_net(seed))
+
+
+def test_network_without_parameters(oracle):
+    """Degenerate case: pools only.  No filter, no gradient vector; y and dx still have to match (winner routing through
+    two pools, the second on an odd map)."""
+    import torch
+    layers = (pool(5), pool(5))
+    cfg = Config("pools_only", 2, 5, 42, 30, layers, (2, 2), (1, 2))
+    x, ws, bs, dy = C.make_tensors(cfg)
+    acts, args = oracle.forward(cfg.layers, x, ws)
+    dx, _, _ = oracle.backward(cfg.layers, acts, args, ws, dy, want_db=False)
+    s = P.make_session(cfg, x.shape[0])
+    assert s.n_params == 0
+    s.load(x=x, weights=ws, dy=dy)
+    s.step()
+    torch.cuda.synchronize()
+    assert np.array_equal(s.to_np(s.y), acts[-1])
+    assert np.array_equal(s.to_np(s.dx), dx)
+    s.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_one_pixel_tiles_and_single_channels(oracle, dtype):
+    """Degenerate tilings: every tile owns a single pixel of the group outputs (everything else it touches is halo),
+    and layers with a single input or output channel."""
+    layers = (conv(1, 8), pool(8), conv(8, 16), conv(16, 1, 1), conv(1, 4, 5))
+    P.check_case(oracle, Config("one_pixel_%s" % dtype, 2, 1, 12, 10, layers, (6, 5), (2, 5), dtype), partial_check=False)
+    layers = (conv(3, 16), conv(16, 32), conv(32, 16, 3, stride=2))
+    P.check_case(oracle, Config("one_pixel_s2_%s" % dtype, 1, 3, 16, 14, layers, (8, 7), (3,), dtype), partial_check=False)
