@@ -206,3 +206,18 @@ def test_one_pixel_tiles_and_single_channels(oracle, dtype):
     P.check_case(oracle, Config("one_pixel_%s" % dtype, 2, 1, 12, 10, layers, (6, 5), (2, 5), dtype), partial_check=False)
     layers = (conv(3, 16), conv(16, 32), conv(32, 16, 3, stride=2))
     P.check_case(oracle, Config("one_pixel_s2_%s" % dtype, 1, 3, 16, 14, layers, (8, 7), (3,), dtype), partial_check=False)
+
+
+@pytest.mark.parametrize("grid", [(1, 1), (2, 2)])
+def test_filters_larger_than_the_map(oracle, grid):
+    """7x7 and 5x5 filters on maps of a few pixels: most taps fall into the zero padding, halos cover the whole map."""
+    layers = (conv(4, 16, 7), conv(16, 32, 5, stride=2), conv(32, 16, 7), conv(16, 8, 3))
+    P.check_case(oracle, Config("tiny_maps", 3, 4, 5, 4, layers, grid, (2, 4)), partial_check=False)
+    layers = (conv(16, 32, 5), pool(32), conv(32, 32, 7))
+    P.check_case(oracle, Config("tiny_maps_pool", 2, 16, 6, 7, layers, grid, (3,), "bf16"), partial_check=False)
+
+
+def test_largest_grid_general_geometry(oracle):
+    """16 x 16 tiles of 2 x 2 output pixels through a strided layer, a lone pool and a 5x5 layer."""
+    layers = (conv(3, 16, 3, stride=2), conv(16, 32), pool(32), conv(32, 16, 5))
+    P.check_case(oracle, Config("grid16_general", 2, 3, 128, 128, layers, (16, 16), (2, 4)), partial_check=False)
