@@ -187,6 +187,16 @@ def test_null_arguments_rejected_without_gpu(F):
         F.ftp_plan_rect(plan, 0, 3, 0, 0, F.FTP_RECT_OWN)
     with pytest.raises(F.binding.FtpError):
         F.ftp_plan_rect(plan, 1, 0, 0, 0, F.FTP_RECT_OWN)
+    F.ftp_set_overlap(plan, True)                # host state only: no GPU call until ftp_backward runs
+    F.ftp_set_overlap(plan, False)
+    with pytest.raises(F.binding.FtpError) as e:
+        F.ftp_set_overlap(None, True)
+    assert e.value.code == F.FTP_EINVAL
+    F.ftp_plan_destroy(plan)
+    # a network without parameters: nothing to sum or update, null gradient pointers are fine
+    plan = F.ftp_plan([pool(3)], 1, 3, 8, 8, 1, 1, [1])
+    assert F.ftp_plan_sizes(plan)["n_params"] == 0
+    F.ftp_reduce_wgrad(plan, 0, 0, 0)
     F.ftp_plan_destroy(plan)
 
 
