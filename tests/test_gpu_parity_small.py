@@ -221,3 +221,35 @@ def test_largest_grid_general_geometry(oracle):
     """16 x 16 tiles of 2 x 2 output pixels through a strided layer, a lone pool and a 5x5 layer."""
     layers = (conv(3, 16, 3, stride=2), conv(16, 32), pool(32), conv(32, 16, 5))
     P.check_case(oracle, Config("grid16_general", 2, 3, 128, 128, layers, (16, 16), (2, 4)), partial_check=False)
+
+
+def _random_wide_net(seed):
+    """Like _random_net with wider layers (several channel blocks per kernel), larger grids and optional biases."""
+    import random
+    rnd = random.Random(1000 + seed)
+    while True:
+        h, w = rnd.randint(40, 100), rnd.randint(40, 100)
+        c = rnd.choice([3, 16, 32, 64])
+        layers, ch, hh, ww = [], c, h, w
+        for _ in range(rnd.randint(2, 5)):
+            if rnd.random() < 0.25 and hh >= 8 and ww >= 8:
+                layers.append(pool(ch))
+                hh, ww = hh // 2, ww // 2
+            else:
+                co = rnd.choice([32, 64, 80, 128, 160])
+                st = 2 if (rnd.random() < 0.25 and hh >= 16 and ww >= 16) else 1
+                layers.append(conv(ch, co, rnd.choice([1, 3, 3, 3, 5]), stride=st))
+                ch, hh, ww = co, (hh - 1) // st + 1, (ww - 1) // st + 1
+        N, M = rnd.randint(1, 4), rnd.randint(1, 4)
+        if hh < 2 * N or ww < 2 * M or all(ly.kind != 0 for ly in layers):
+            continue
+        L = len(layers)
+        cuts = sorted(rnd.sample(range(1, L), rnd.randint(0, min(2, L - 1))))
+        dtype = "bf16" if rnd.random() < 0.5 else "f32"
+        return Config("random_wide_%d" % seed, rnd.randint(1, 4), c, h, w, tuple(layers), (N, M), tuple(cuts + [L]), dtype), rnd.random() < 0.25
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_wide_networks(oracle, seed):
+    cfg, has_bias = _random_wide_net(seed)
+    P.check_case(oracle, cfg, has_bias=has_bias, partial_check=False)
