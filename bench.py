@@ -183,6 +183,14 @@ def main():
         dt2 = time.perf_counter() - t1
         s.set_overlap(False)
         out["two_stream_backward"] = {"value": cfg.batch * args.steps / dt2, "unit": "images/s", "ms_per_step": dt2 * 1e3 / args.steps}
+    # forward inference alone (ftp_forward), for reference
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        s.forward()
+    torch.cuda.synchronize()
+    dt3 = time.perf_counter() - t2
+    out["forward_only"] = {"value": cfg.batch * args.steps / dt3, "unit": "images/s", "ms_per_pass": dt3 * 1e3 / args.steps}
     if not args.no_cpu_baseline:
         # about 10-20 s of oracle time: 12 images of the large workloads (the oracle is linear in the batch)
         n_img = args.cpu_images or (12 if cfg.name.startswith(("cfg4", "cfg5")) else cfg.batch)
