@@ -49,10 +49,6 @@ def _clamp(r, hw):
     return (max(x1, 0), max(y1, 0), min(x2, w - 1), min(y2, h - 1))
 
 
-def _union(a, b):
-    return (min(a[0], b[0]), min(a[1], b[1]), max(a[2], b[2]), max(a[3], b[3]))
-
-
 def equal_split(length, parts, t):
     return (t * length) // parts, ((t + 1) * length) // parts - 1
 

@@ -154,19 +154,21 @@ class Session:
             out.append((r, self.to_np(t[s][idx][:, :, :r[3] - r[1] + 1, :r[2] - r[0] + 1])))
         return out
 
-    def set_boundary(self, boundary, full_map, which=B.FTP_BUF_ACT):
-        """Writes a whole map into the plan's buffer(s) of a boundary (every stack gets its rectangle)."""
+    def set_boundary(self, boundary, full_map, which=B.FTP_BUF_ACT, images=None):
+        """Writes a whole map into the plan's buffer(s) of a boundary (every stack gets its rectangle).
+        images: optional list of image indices the rows of `full_map` belong to (default: the whole batch)."""
         t, info = self._buffer(boundary, which)
         if t is None:
             return
         src = torch.from_numpy(np.ascontiguousarray(full_map))
         src = src.cuda() if which in (B.FTP_BUF_MASK, B.FTP_BUF_SIGN) else src.float().cuda().to(t.dtype)
+        idx = slice(None) if images is None else torch.as_tensor(list(images), device=t.device)
         if not info["per_stack"]:
-            t.copy_(src)
+            t[idx] = src
             return
         for s in range(self.stacks):
             r = self._rect(info, boundary, s, info["rect_kind"])
-            t[s, :, :, :r[3] - r[1] + 1, :r[2] - r[0] + 1] = src[:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]
+            t[s, idx, :, :r[3] - r[1] + 1, :r[2] - r[0] + 1] = src[:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]
 
     @staticmethod
     def to_np(t):

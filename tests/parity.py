@@ -18,6 +18,11 @@ from ftp_synth.configs import CONV
 TOL_ACT_F32 = 1e-5     # activations, fp32
 TOL_GRAD_F32 = 1e-4    # dX and dW, fp32
 TOL_BF16 = 2e-2        # everything, bf16 storage
+# Chain check with flipped decisions (see check_case): relative L2 bounds and the largest share of decisions
+# that may flip, each twice the largest value measured on the MI355X over the whole test suite.
+CHAIN_L2_F32 = 2e-2
+CHAIN_L2_BF16 = 5e-1
+CHAIN_MAX_FLIP_SHARE = {False: 1e-4, True: 4e-2}
 
 
 def rel_inf(a, b):
@@ -145,22 +150,23 @@ def unpack_signs(words, c):
     return np.stack([(w[:, ch // 32] >> np.uint32(ch % 32)) & 1 for ch in range(c)], axis=1).astype(bool)
 
 
-def check_forward_state(s, cfg, acts, args, tol_a):
+def check_forward_state(s, cfg, acts, args, tol_a, images=None):
     """Every map the plan keeps equals the oracle's: the assembled owned tiles, and each stack's whole
     forward rectangle (recomputed halo included).  Decision codes may differ from the oracle's only where
-    the oracle's own value is within the activation tolerance of the kink (|Y| small, top-2 gap small)."""
+    the oracle's own value is within the activation tolerance of the kink (|Y| small, top-2 gap small).
+    images: the images of the session's batch that `acts` / `args` hold (default: all of them)."""
     import paper_2409_09083_amd as F
     for b in range(1, len(cfg.layers) + 1):
-        got = s.get_boundary(b)
+        got = s.get_boundary(b, images=images)
         scale = float(np.max(np.abs(acts[b])))
         if got is not None:
             e = rel_inf(got, acts[b])
             assert e <= tol_a, ("activation at boundary", b, e)
-            for (r, slot) in s.get_slots(b):
+            for (r, slot) in s.get_slots(b, images=images):
                 ref = acts[b][:, :, r[1]:r[3] + 1, r[0]:r[2] + 1]
                 assert np.max(np.abs(slot - ref)) <= tol_a * scale, ("held rectangle", b, r)
-        gm = s.get_boundary(b, F.FTP_BUF_MASK)       # behind pools only
-        gs = s.get_boundary(b, F.FTP_BUF_SIGN)       # behind convolutions only
+        gm = s.get_boundary(b, F.FTP_BUF_MASK, images=images)       # behind pools only
+        gs = s.get_boundary(b, F.FTP_BUF_SIGN, images=images)       # behind convolutions only
         if gs is not None:
             sg = unpack_signs(gs, acts[b].shape[1])
             bad = sg != (acts[b] > 0)
@@ -176,26 +182,35 @@ def check_forward_state(s, cfg, acts, args, tol_a):
                 assert float(gap[bad].max()) <= 2 * tol_a * scale, ("pool winners", b, int(bad.sum()))
 
 
-def decisions_agree(s, cfg, acts, args):
-    """True if every leaky sign and pool winner the GPU's forward pass recorded equals the oracle's."""
+def decision_flips(s, cfg, acts, args, images=None):
+    """(flipped, total): how many of the decisions the GPU's forward pass recorded (leaky signs, pool winners)
+    differ from the oracle's, and how many decisions there are."""
     import paper_2409_09083_amd as F
+    flipped = total = 0
     for b in range(1, len(cfg.layers) + 1):
-        gs = s.get_boundary(b, F.FTP_BUF_SIGN)
-        if gs is not None and (unpack_signs(gs, acts[b].shape[1]) != (acts[b] > 0)).any():
-            return False
-        gm = s.get_boundary(b, F.FTP_BUF_MASK)
-        if gm is not None and args[b - 1] is not None and (((gm >> 1) & 3) != args[b - 1]).any():
-            return False
-    return True
+        gs = s.get_boundary(b, F.FTP_BUF_SIGN, images=images)
+        if gs is not None:
+            flipped += int((unpack_signs(gs, acts[b].shape[1]) != (acts[b] > 0)).sum())
+            total += acts[b].size
+        gm = s.get_boundary(b, F.FTP_BUF_MASK, images=images)
+        if gm is not None and args[b - 1] is not None:
+            flipped += int((((gm >> 1) & 3) != args[b - 1]).sum())
+            total += args[b - 1].size
+    return flipped, total
 
 
-def import_forward_state(s, cfg, acts, args):
+def decisions_agree(s, cfg, acts, args, images=None):
+    """True if every leaky sign and pool winner the GPU's forward pass recorded equals the oracle's."""
+    return decision_flips(s, cfg, acts, args, images)[0] == 0
+
+
+def import_forward_state(s, cfg, acts, args, images=None):
     """oracle -> GPU: the plan's workspace receives the oracle's forward maps and decision codes."""
     import paper_2409_09083_amd as F
     for b in range(1, len(cfg.layers) + 1):
-        s.set_boundary(b, acts[b])
-        s.set_boundary(b, oracle_mask(acts, args, b), F.FTP_BUF_MASK)
-        s.set_boundary(b, pack_signs(acts[b]), F.FTP_BUF_SIGN)
+        s.set_boundary(b, acts[b], images=images)
+        s.set_boundary(b, oracle_mask(acts, args, b), F.FTP_BUF_MASK, images=images)
+        s.set_boundary(b, pack_signs(acts[b]), F.FTP_BUF_SIGN, images=images)
 
 
 def check_grads(cfg, got_dx, got_wgrad, dx, dws, dbs, has_bias, tol_g, label):
@@ -236,7 +251,8 @@ def check_case(oracle, cfg, seed=C.rng.MASTER_SEED, has_bias=False, strict_chain
     s.reduce()
     torch.cuda.synchronize()
     chain_dx, chain_w, chain_p = s.to_np(s.dx), s.to_np(s.wgrad), s.to_np(s.partials)
-    agree = decisions_agree(s, cfg, acts, args)
+    flipped, total = decision_flips(s, cfg, acts, args)
+    agree = flipped == 0
     if strict_chain is None:
         strict_chain = agree
     if strict_chain:
@@ -244,11 +260,17 @@ def check_case(oracle, cfg, seed=C.rng.MASTER_SEED, has_bias=False, strict_chain
         assert agree
         check_grads(cfg, chain_dx, chain_w, dx, dws, dbs, has_bias, tol_g, "chain")
     else:
-        # some decisions sit on their kink and flipped: each flip moves a few gradient entries by O(1), so
-        # only a loose norm-wise sanity bound is meaningful here (bf16 storage through 16 layers flips a percent of
-        # the decisions); the elementwise bars are enforced on the forward state above and on given state below
-        assert rel_l2(chain_dx, dx) <= (5e-1 if bf else 2e-2), ("chain dx", rel_l2(chain_dx, dx))
-        assert rel_l2(chain_w, ref) <= (5e-1 if bf else 2e-2), ("chain dW", rel_l2(chain_w, ref))
+        # some decisions sit on their kink and flipped: each flip moves a few gradient entries by O(1), so only a
+        # norm-wise bound is meaningful here; the elementwise bars are enforced on the forward state above and on
+        # given state below.  The bound is twice the largest error measured on the MI355X for that storage type
+        # (the test prints what it measures, with the share of flipped decisions).
+        e_dx, e_w = rel_l2(chain_dx, dx), rel_l2(chain_w, ref)
+        bound = CHAIN_L2_BF16 if bf else CHAIN_L2_F32
+        print("chain %s: %d of %d decisions flipped (%.3g %%), rel L2 error dx %.3g dW %.3g (bound %.3g)"
+              % (cfg.name, flipped, total, 100.0 * flipped / max(total, 1), e_dx, e_w, bound))
+        assert flipped <= CHAIN_MAX_FLIP_SHARE[bf] * total, ("flipped decisions", flipped, total)
+        assert e_dx <= bound, ("chain dx", e_dx)
+        assert e_w <= bound, ("chain dW", e_w)
     assert np.allclose(chain_p.astype(np.float64).sum(axis=0), chain_w, rtol=1e-5, atol=1e-6 * np.abs(ref).max())
 
     # given state: identical decisions on both sides, strict elementwise bars

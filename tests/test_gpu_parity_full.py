@@ -1,10 +1,12 @@
 """GPU parity at the full sizes of the five configurations, in the launch configuration bench.py times.
 
-Configurations 1-3 are checked whole against the oracle.  For the 16-layer stacks (configurations 4
-and 5) the oracle checks a 2-image batch of the same shape, grid and grouping element by element; the
-full batch is then tied to it by properties that hold at any size: sampled images of the full batch
-equal the oracle's forward, per-image results do not depend on the batch they sit in, and the filter
-gradient is additive over the batch (one update per batch, Sec. 3).
+Configurations 1-3 are checked whole against the oracle.  The 16-layer stacks (configurations 4 and 5) are
+checked twice: a 2-image batch of the same shape, grid and grouping through check_case (every grouping of the
+sweep), and the full batch against the oracle run in chunks of 8 images: every kept map and decision of the
+forward pass chunk by chunk, then ONE ftp_backward at the full batch whose dx is compared image by image and whose
+filter gradient is compared with the fp64 sum of the chunks' oracle gradients (Sec. 4.1: partial sums add up;
+Sec. 3: one update per batch).  Further properties that hold at any size tie batch sizes together: per-image
+results do not depend on the batch they sit in, and the filter gradient is additive over the batch.
 """
 import numpy as np
 import pytest
@@ -23,7 +25,7 @@ def test_config4_shape_two_images(oracle):
     P.check_case(oracle, C.config4().with_(batch=2), partial_check=False)
 
 
-@pytest.mark.parametrize("g", [1, 4, 16])
+@pytest.mark.parametrize("g", [1, 2, 4, 8, 16])
 def test_config5_shape_two_images(oracle, g):
     P.check_case(oracle, C.config5(g).with_(batch=2), partial_check=False)
 
@@ -85,3 +87,66 @@ def test_config4_full_batch(oracle):
 
 def test_config5_full_batch(oracle):
     _full_batch_properties(oracle, C.config5(4), [0, 31])
+
+
+def _full_batch_against_oracle(oracle, cfg, chunk=8):
+    """The whole batch in the launch configuration bench.py times, against the oracle run chunk by chunk."""
+    import torch
+    bf = cfg.dtype == "bf16"
+    tol_a, tol_g = (P.TOL_BF16, P.TOL_BF16) if bf else (P.TOL_ACT_F32, P.TOL_GRAD_F32)
+    x, ws, bs, dy = C.make_tensors(cfg)
+    s = P.make_session(cfg, cfg.batch)
+    s.load(x=x, weights=ws, dy=dy)
+    # chain: back-propagation through the GPU's own forward state
+    s.step()
+    torch.cuda.synchronize()
+    chain_dx, chain_w = s.to_np(s.dx), s.to_np(s.wgrad)
+    s.forward()                                   # (the state the checks below read is that of a forward pass)
+    torch.cuda.synchronize()
+    y = s.to_np(s.y)
+    ref_dx = np.empty_like(x)
+    ref_w = np.zeros(s.n_params, dtype=np.float64)
+    flipped = total = 0
+    for c0 in range(0, cfg.batch, chunk):
+        idx = list(range(c0, min(cfg.batch, c0 + chunk)))
+        acts, args = oracle.forward(cfg.layers, np.ascontiguousarray(x[idx]), ws, None, bf16_store=bf)
+        assert P.rel_inf(y[idx], acts[-1]) <= tol_a, ("y", c0)
+        P.check_forward_state(s, cfg, acts, args, tol_a, images=idx)
+        f, t = P.decision_flips(s, cfg, acts, args, images=idx)
+        flipped += f; total += t
+        dxc, dws, _ = oracle.backward(cfg.layers, acts, args, ws, np.ascontiguousarray(dy[idx]), bf16_store=bf, want_db=False)
+        ref_dx[idx] = dxc
+        ref_w += P.flat_grad(cfg, dws).astype(np.float64)
+        # oracle -> GPU: from here on this chunk's images carry the oracle's forward state
+        P.import_forward_state(s, cfg, acts, args, images=idx)
+        del acts, args, dws, dxc
+    e_dx, e_w = P.rel_l2(chain_dx, ref_dx), P.rel_l2(chain_w, ref_w)
+    print("full batch %s: %d of %d decisions flipped (%.3g %%), chain rel L2 error dx %.3g dW %.3g"
+          % (cfg.name, flipped, total, 100.0 * flipped / total, e_dx, e_w))
+    if flipped == 0:
+        for n in range(cfg.batch):
+            assert P.rel_inf(chain_dx[n], ref_dx[n]) <= tol_g, ("chain dx", n)
+    else:
+        bound = P.CHAIN_L2_BF16 if bf else P.CHAIN_L2_F32
+        assert flipped <= P.CHAIN_MAX_FLIP_SHARE[bf] * total
+        assert e_dx <= bound and e_w <= bound, (e_dx, e_w)
+    # given state: one back-propagation of the whole batch through the oracle's decisions, strict bars
+    s.backward()
+    s.reduce()
+    torch.cuda.synchronize()
+    got_dx, got_w = s.to_np(s.dx), s.to_np(s.wgrad)
+    for n in range(cfg.batch):
+        e = P.rel_inf(got_dx[n], ref_dx[n])
+        assert e <= tol_g, ("dx of image", n, e)
+    for (l, a, b) in P.param_slices(cfg):
+        e = P.rel_inf(got_w[a:b], ref_w[a:b])
+        assert e <= tol_g, ("dW of layer", l, e)
+    s.close()
+
+
+def test_config4_full_batch_oracle(oracle):
+    _full_batch_against_oracle(oracle, C.config4())
+
+
+def test_config5_full_batch_oracle(oracle):
+    _full_batch_against_oracle(oracle, C.config5(4))

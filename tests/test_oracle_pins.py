@@ -359,3 +359,66 @@ def test_general_geometry_against_torch_cpu_autograd(oracle):
         if ly.kind == CONV:
             assert np.allclose(dws[l], tws[l].grad.numpy(), rtol=1e-11, atol=1e-12), l
             assert np.allclose(dbs[l], tbs[l].grad.numpy(), rtol=1e-11, atol=1e-12), l
+
+
+def test_bf16_storage_branch_layer_by_layer_with_torch(oracle):
+    """Pin of the reduced-precision storage branch (bf16_store=True): the network re-derived one layer at a time with
+    torch's fp64 conv2d / max_pool2d and its autograd, rounding to bf16 with the input generator's own rounding routine
+    exactly where a map is stored: every activation after its leaky ReLU (pools pick among stored values), every
+    delta dLoss/dX once it leaves a layer; dZ = dY * leaky' and the filter gradients are not stored as bf16."""
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    from ftp_synth import rng
+
+    rs = np.random.RandomState(11)
+    layers = [conv(3, 6), pool(6), conv(6, 8), conv(8, 4, 1), pool(4), conv(4, 5)]
+    x = rng.to_bf16_rne(rs.uniform(0, 1, (2, 3, 24, 20)).astype(np.float32))
+    ws = [None if ly.kind != CONV else
+          rng.to_bf16_rne((rs.standard_normal((ly.cout, ly.cin, ly.k, ly.k)) * np.sqrt(2.0 / (ly.cin * ly.k * ly.k))).astype(np.float32))
+          for ly in layers]
+    acts, args = oracle.forward(layers, x, ws, None, bf16_store=True)
+    g = rng.to_bf16_rne(rs.standard_normal(acts[-1].shape).astype(np.float32))
+    dx, dws, _ = oracle.backward(layers, acts, args, ws, g, bf16_store=True, want_db=False)
+    # every stored map holds bf16 values, and storing in bf16 really changes the result
+    for a in acts:
+        assert np.array_equal(rng.to_bf16_rne(a), a)
+    acts_plain, _ = oracle.forward(layers, x, ws, None, bf16_store=False)
+    assert not np.array_equal(acts_plain[-1], acts[-1])
+
+    slope32 = np.float32(0.1)
+    # forward
+    t_acts, t_arg = [x], [None] * len(layers)
+    for l, ly in enumerate(layers):
+        a = torch.tensor(t_acts[-1].astype(np.float64))
+        if ly.kind == CONV:
+            z = F.conv2d(a, torch.tensor(ws[l].astype(np.float64)), None, ly.stride, ly.pad).numpy().astype(np.float32)
+            y = np.where(z > 0, z, slope32 * z).astype(np.float32)           # leaky in the storage precision's fp32
+            t_acts.append(rng.to_bf16_rne(y))
+        else:
+            y, ind = F.max_pool2d(a, 2, 2, return_indices=True)
+            t_acts.append(y.numpy().astype(np.float32))
+            t_arg[l] = ind
+    for l in range(len(layers) + 1):
+        assert np.array_equal(t_acts[l], acts[l]), ("stored activation", l)
+    # backward
+    tg = g
+    for l in range(len(layers) - 1, -1, -1):
+        ly = layers[l]
+        if ly.kind == CONV:
+            dz = np.where(t_acts[l + 1] > 0, tg, slope32 * tg).astype(np.float32)      # kept in fp32, not stored as bf16
+            a = torch.tensor(t_acts[l].astype(np.float64), requires_grad=True)
+            w = torch.tensor(ws[l].astype(np.float64), requires_grad=True)
+            (F.conv2d(a, w, None, ly.stride, ly.pad) * torch.tensor(dz.astype(np.float64))).sum().backward()
+            dw = w.grad.numpy().astype(np.float32)
+            scale = np.abs(dw).max()
+            assert np.max(np.abs(dw - dws[l])) <= 2e-7 * scale, ("filter gradient", l)       # fp64 sums rounded to fp32 once
+            assert not np.array_equal(rng.to_bf16_rne(dws[l]), dws[l])
+            tg = rng.to_bf16_rne(a.grad.numpy().astype(np.float32))
+        else:
+            a = torch.tensor(t_acts[l].astype(np.float64), requires_grad=True)
+            (F.max_pool2d(a, 2, 2) * torch.tensor(tg.astype(np.float64))).sum().backward()
+            tg = rng.to_bf16_rne(a.grad.numpy().astype(np.float32))
+    assert np.array_equal(tg, dx)
+    # the same with the rounding of the deltas left out is a different result (the pin sees that rounding)
+    dx_plain, _, _ = oracle.backward(layers, acts, args, ws, g, bf16_store=False, want_db=False)
+    assert not np.array_equal(dx_plain, dx)
