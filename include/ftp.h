@@ -50,7 +50,8 @@ typedef enum {
     FTP_EGROUPS = -4,       /* group ends not strictly increasing or not ending at n_layers    */
     FTP_ENOMEM = -5,        /* host allocation failed                                          */
     FTP_EHIP = -6,          /* a HIP call failed; see ftp_last_hip_error                       */
-    FTP_ECHANNELS = -7      /* cin of a layer does not match cout of the previous one          */
+    FTP_ECHANNELS = -7,     /* cin of a layer does not match cout of the previous one          */
+    FTP_ETOOLARGE = -8      /* the plan's workspace exceeds FTP_STATIC_WORKSPACE_BYTES (ftp_forward_static) */
 } ftp_status;
 
 /* One primitive layer (Sec. 4.2: kernel K_l x K_l, stride S_l).  FTP_CONV: K x K convolution, stride 1 or 2, zero
@@ -135,6 +136,20 @@ int ftp_plan_buffer(const ftp_plan_t* plan, int32_t boundary, ftp_buf_kind which
  *   y        device, output map [batch][C_L][H_L][W_L] */
 int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weights,
                 const void* const* biases, void* workspace, void* y, void* stream);
+
+/* ftp_forward for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops (forward inference), harnesses that forbid hipMalloc.  Same kernels, same launch order
+ * and bit-identical y as ftp_forward, but the workspace is a fixed array of FTP_STATIC_WORKSPACE_BYTES that lives in
+ * the library's device image (every GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates nothing, on the device or through any library.  Plans whose ftp_plan_sizes workspace_bytes exceed the
+ * limit are rejected with FTP_ETOOLARGE before anything is launched.  x, weights, biases, y, stream as for
+ * ftp_forward, on the current device.  The array keeps the previous call's contents (the forward pass needs
+ * nothing cleared) and is shared by every call on that GPU: calls that overlap on one GPU (two streams, two threads)
+ * race and must be serialised by the caller; ftp_backward cannot follow (it needs the caller's own workspace).
+ * The first call on a device looks the array's address up (hipGetSymbolAddress); make that call outside a capture. */
+#define FTP_STATIC_WORKSPACE_BYTES (64u * 1024u * 1024u)
+int ftp_forward_static(const ftp_plan_t* plan, const void* x, const void* const* weights,
+                       const void* const* biases, void* y, void* stream);
 
 /* Back-propagation of all groups in reverse (Sec. 4.1 delta and filter gradients).
  *   dy        device, dLoss/dy, shape of y

@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libftp.so")
 FTP_CONV, FTP_MAXPOOL = 0, 1
 FTP_F32, FTP_BF16 = 0, 1
 FTP_RECT_OWN, FTP_RECT_FWD, FTP_RECT_BWD = 0, 1, 2
-FTP_OK, FTP_EINVAL, FTP_EUNSUPPORTED, FTP_EGRID, FTP_EGROUPS, FTP_ENOMEM, FTP_EHIP, FTP_ECHANNELS = 0, -1, -2, -3, -4, -5, -6, -7
+FTP_OK, FTP_EINVAL, FTP_EUNSUPPORTED, FTP_EGRID, FTP_EGROUPS, FTP_ENOMEM, FTP_EHIP, FTP_ECHANNELS, FTP_ETOOLARGE = 0, -1, -2, -3, -4, -5, -6, -7, -8
+FTP_STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024
 
 
 class ftp_layer(ctypes.Structure):
@@ -71,6 +72,7 @@ def _load():
                                   ctypes.POINTER(ctypes.c_double)]
     lib.ftp_plan_buffer.argtypes = [vp, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
     lib.ftp_forward.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp]
+    lib.ftp_forward_static.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp]
     lib.ftp_backward.argtypes = [vp, vp, vp, ctypes.POINTER(vp), vp, vp, vp, vp]
     lib.ftp_reduce_wgrad.argtypes = [vp, vp, vp, vp]
     lib.ftp_sgd_step.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_float, vp, vp]
@@ -81,7 +83,7 @@ def _load():
     lib.ftp_strerror.restype = ctypes.c_char_p
     lib.ftp_last_hip_error.restype = ctypes.c_int
     for f in ("ftp_profile", "ftp_profile_read", "ftp_set_overlap", "ftp_plan_buffer", "ftp_plan_rect", "ftp_plan_map_shape", "ftp_plan_sizes", "ftp_plan_work", "ftp_forward",
-              "ftp_backward", "ftp_reduce_wgrad", "ftp_sgd_step"):
+              "ftp_forward_static", "ftp_backward", "ftp_reduce_wgrad", "ftp_sgd_step"):
         getattr(lib, f).restype = ctypes.c_int
     return lib
 
@@ -89,7 +91,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ("ftp_profile", "ftp_profile_read", "ftp_set_overlap", "ftp_plan", "ftp_plan_destroy", "ftp_plan_buffer", "ftp_plan_rect", "ftp_plan_map_shape", "ftp_plan_sizes", "ftp_plan_work",
-           "ftp_forward", "ftp_backward", "ftp_reduce_wgrad", "ftp_sgd_step", "ftp_strerror", "ftp_last_hip_error")
+           "ftp_forward", "ftp_forward_static", "ftp_backward", "ftp_reduce_wgrad", "ftp_sgd_step", "ftp_strerror", "ftp_last_hip_error")
 
 
 def _check(rc, where):
@@ -169,6 +171,11 @@ def ftp_plan_buffer(plan, boundary, which):
 def ftp_forward(plan, x, weights, biases, workspace, y, stream=0):
     n = len(weights)
     _check(_lib.ftp_forward(plan, x, _ptr_array(weights, n), _ptr_array(biases, n), workspace, y, stream), "ftp_forward")
+
+
+def ftp_forward_static(plan, x, weights, biases, y, stream=0):
+    n = len(weights)
+    _check(_lib.ftp_forward_static(plan, x, _ptr_array(weights, n), _ptr_array(biases, n), y, stream), "ftp_forward_static")
 
 
 def ftp_backward(plan, dy, x, weights, workspace, dx, wgrad_partials, stream=0):

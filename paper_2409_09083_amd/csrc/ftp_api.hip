@@ -5,10 +5,19 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 using namespace ftp;
 
+// Workspace of ftp_forward_static.  On the host this name is only a handle for hipGetSymbolAddress: the device
+// address, one per GPU, is looked up once per device and kept in g_static_ws.
+static __device__ __align__(256) unsigned char scratch[FTP_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_static_ws[kMaxDevices] = {};
+std::mutex g_static_ws_lock;
 
 thread_local int g_last_hip = 0;
 
@@ -294,6 +303,28 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
     return FTP_OK;
 }
 
+int ftp_forward_static(const ftp_plan_t* plan, const void* x, const void* const* weights, const void* const* biases,
+                       void* y, void* stream)
+{
+    if (!plan) return FTP_EINVAL;
+    if (plan->p.workspace_bytes > (size_t)FTP_STATIC_WORKSPACE_BYTES) return FTP_ETOOLARGE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { g_last_hip = (int)hipGetLastError(); return FTP_EHIP; }
+    if (dev < 0 || dev >= kMaxDevices) return FTP_EINVAL;
+    void* ws = nullptr;
+    {
+        std::lock_guard<std::mutex> hold(g_static_ws_lock);
+        if (!g_static_ws[dev]) {
+            void* p = nullptr;
+            const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));       // this device's copy of the array
+            if (e != hipSuccess || !p) { g_last_hip = (int)e; (void)hipGetLastError(); return FTP_EHIP; }
+            g_static_ws[dev] = p;
+        }
+        ws = g_static_ws[dev];
+    }
+    return ftp_forward(plan, x, weights, biases, ws, y, stream);
+}
+
 int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const void* const* weights,
                  void* workspace, void* dx, float* wgrad_partials, void* stream)
 {
@@ -510,6 +541,7 @@ const char* ftp_strerror(int code)
         case FTP_ENOMEM: return "host allocation failed";
         case FTP_EHIP: return "HIP call failed";
         case FTP_ECHANNELS: return "channel counts of consecutive layers do not match";
+        case FTP_ETOOLARGE: return "the plan's workspace exceeds the fixed array of ftp_forward_static (FTP_STATIC_WORKSPACE_BYTES)";
         default: return "unknown error";
     }
 }
