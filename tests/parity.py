@@ -19,10 +19,12 @@ TOL_ACT_F32 = 1e-5     # activations, fp32
 TOL_GRAD_F32 = 1e-4    # dX and dW, fp32
 TOL_BF16 = 2e-2        # everything, bf16 storage
 # Chain check with flipped decisions (see check_case): relative L2 bounds and the largest share of decisions
-# that may flip, each twice the largest value measured on the MI355X over the whole test suite.
-CHAIN_L2_F32 = 2e-2
-CHAIN_L2_BF16 = 5e-1
-CHAIN_MAX_FLIP_SHARE = {False: 1e-4, True: 4e-2}
+# that may flip, each about twice the largest value measured on the MI355X over the whole test suite:
+#   fp32  at most 9.9e-7 of the decisions flip, error at most 5.3e-3 (config 4);
+#   bf16  at most 2.4e-4 of the decisions flip (config 5: 9567 of 39.9 million), error at most 0.142 in dx, 0.075 in dW.
+CHAIN_L2_F32 = 1.1e-2
+CHAIN_L2_BF16 = 3e-1
+CHAIN_MAX_FLIP_SHARE = {False: 2e-6, True: 5e-4}
 
 
 def rel_inf(a, b):
@@ -268,7 +270,7 @@ def check_case(oracle, cfg, seed=C.rng.MASTER_SEED, has_bias=False, strict_chain
         bound = CHAIN_L2_BF16 if bf else CHAIN_L2_F32
         print("chain %s: %d of %d decisions flipped (%.3g %%), rel L2 error dx %.3g dW %.3g (bound %.3g)"
               % (cfg.name, flipped, total, 100.0 * flipped / max(total, 1), e_dx, e_w, bound))
-        assert flipped <= CHAIN_MAX_FLIP_SHARE[bf] * total, ("flipped decisions", flipped, total)
+        assert flipped <= max(4, CHAIN_MAX_FLIP_SHARE[bf] * total), ("flipped decisions", flipped, total)   # (a handful in a small net)
         assert e_dx <= bound, ("chain dx", e_dx)
         assert e_w <= bound, ("chain dW", e_w)
     assert np.allclose(chain_p.astype(np.float64).sum(axis=0), chain_w, rtol=1e-5, atol=1e-6 * np.abs(ref).max())
