@@ -109,7 +109,7 @@ ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void*
     a.slope = ly.leaky_slope;
     a.N = p.N; a.M = p.M; a.batch = p.batch;
     a.bf16 = p.dtype == FTP_BF16;
-    a.wgrad_shares = u.wgrad_shares; a.wgrad_shares_thin = u.wgrad_shares_thin;
+    a.wgrad_shares = u.wgrad_shares; a.wgrad_shares_thin = u.wgrad_shares_thin; a.wgrad_shares16 = u.wgrad_shares16;
     return a;
 }
 
@@ -391,6 +391,8 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             if (overlap && gradient_in_flight && (rc = order(aux, s)) != FTP_OK) return rc;
             if (use_mfma() && thin_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { thin_wgrad(a, scratch, aux); });
+            } else if (use_mfma() && plain_geometry(a) && wgrad16_eligible(a)) {
+                rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { wgrad16(a, scratch, aux); });
             } else if (use_mfma() && mfma_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { mfma_wgrad(a, scratch, aux); });
             } else {

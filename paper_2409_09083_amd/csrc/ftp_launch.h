@@ -43,6 +43,7 @@ struct ConvArgs {
     int N = 1, M = 1, batch = 1;
     int bf16 = 0;
     int wgrad_shares = 1, wgrad_shares_thin = 1;   // shares of the matrix-core filter-gradient kernels (from the plan, which sized the scratch)
+    int wgrad_shares16 = 1;
 };
 
 struct PoolArgs {
@@ -106,6 +107,9 @@ struct MfmaWgradArgs {
 };
 
 bool mfma_wgrad_eligible(const ConvArgs& a);
+// bfloat 3x3 stride-1 filter gradient with packed staging (ftp_wgrad16.hip)
+bool wgrad16_eligible(const ConvArgs& a);
+void wgrad16(const ConvArgs& c, float* scratch, hipStream_t s);
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s);
 
 bool thin_conv_fwd_eligible(const ConvArgs& a);

@@ -225,6 +225,9 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
                     a.slot_h = max_len(gr, FTP_RECT_FWD, b, 1, N);
                     d.slot_w = max_len(gr, FTP_RECT_BWD, b, 0, M);
                     d.slot_h = max_len(gr, FTP_RECT_BWD, b, 1, N);
+                    // 16-bit maps: an even row length keeps every row of a slot on a 4-byte boundary (pairs of elements
+                    // are loaded as one dword)
+                    if (dtype == FTP_BF16) { a.slot_w = (a.slot_w + 1) & ~1; d.slot_w = (d.slot_w + 1) & ~1; }
                     a.kind = BUF_WS; a.bytes = stacks * batch * p.C[b] * a.slot_w * a.slot_h * p.esize; a.offset = alloc(a.bytes);
                     d.kind = BUF_WS; d.bytes = stacks * batch * p.C[b] * d.slot_w * d.slot_h * p.esize;
                     d.offset = (size_t)(ordinal & 1);       // ping-pong index, resolved below
@@ -293,7 +296,16 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
                     tchunks = std::max(tchunks, thin_wgrad_chunks(sx.b - sx.a + 1, sy.b - sy.a + 1, batch, PK, u.pooled).total);
                 }
             u.wgrad_shares_thin = wgrad_shares_thin(ly.cout, N * M, tchunks);
-            const int shares = std::max(u.wgrad_shares, u.wgrad_shares_thin);
+            if (dtype == FTP_BF16 && ly.k == 3 && ly.stride == 1) {
+                int c16 = 1;
+                for (int i = 0; i < N; ++i)
+                    for (int j = 0; j < M; ++j) {
+                        const Seg sx = gr.at(FTP_RECT_OWN, u.layer + 1, 0, j), sy = gr.at(FTP_RECT_OWN, u.layer + 1, 1, i);
+                        c16 = std::max(c16, wgrad16_chunks(sx.b - sx.a + 1, sy.b - sy.a + 1, batch, w16_patch_elems(w16_waves_ci(ly.cin))).total);
+                    }
+                u.wgrad_shares16 = wgrad16_shares(ly.cout, ly.cin, N * M, c16);
+            }
+            const int shares = std::max(std::max(u.wgrad_shares, u.wgrad_shares_thin), u.wgrad_shares16);
             if (shares > 1) scratch = std::max(scratch, stacks * shares * (size_t)ly.cout * ly.cin * ly.k * ly.k * sizeof(float));
         }
         p.wgrad_scratch_offset = alloc(scratch);

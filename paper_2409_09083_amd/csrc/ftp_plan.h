@@ -57,6 +57,7 @@ struct Unit {
     size_t bias_offset = 0;
     size_t wt_fwd_offset = 0, wt_bwd_offset = 0;   // relaid filter copies in the workspace (bytes)
     int wgrad_shares = 1, wgrad_shares_thin = 1;   // shares of the two matrix-core filter-gradient kernels (the scratch is sized for them)
+    int wgrad_shares16 = 1;                        // ... and of the bfloat 3x3 kernel
 };
 
 struct Plan {
@@ -136,6 +137,58 @@ inline int wgrad_shares(int cout, int cin, int k, int stacks, int chunks)
     int best = 1; double best_t = 0;
     for (int s = 1; s <= smax; ++s) {
         const double rounds = (double)(long long)((blocks * s + slots - 1) / slots);
+        const double t = rounds * 2.0 * ((chunks + s - 1) / s) * unit_us + (s > 1 ? s * share_us : 0.0);
+        if (s == 1 || t < best_t) { best = s; best_t = t; }
+    }
+    return best;
+}
+
+// Chunks of the bfloat 3x3 filter-gradient kernel (ftp_wgrad16.hip): pixels are taken in groups of 8 consecutive
+// pixels of one row of the owned rectangle (a row of TC pixels has G groups, the last one padded with zero deltas),
+// 16 groups to a chunk: RB rows of one image, or, where a whole rectangle has fewer groups, TI whole images.  The
+// patch of a chunk (rows + 2 halo rows per image, PWp elements each, PWp a multiple of 8 so that every row starts on
+// a 16-byte boundary) has to fit the LDS row of a channel: an odd multiple of 16 bytes (lanes of consecutive channels
+// then read 16 bytes each without bank conflicts), twice as long where a workgroup holds 32 input channels only.
+constexpr int kW16Groups = 16;
+FTP_HD constexpr int w16_row_bytes(int waves_ci) { return waves_ci == 1 ? 976 : 496; }
+FTP_HD constexpr int w16_patch_elems(int waves_ci) { return w16_row_bytes(waves_ci) / 2 - 16; }      // (reads run up to 8 elements past the patch)
+FTP_HD constexpr int w16_waves_ci(int cin) { return cin > 32 ? 2 : 1; }
+struct Wgrad16Chunks { int col_blocks, TC, G, PWp, RB, TI, row_blocks, img_blocks, total; };
+FTP_HD inline Wgrad16Chunks wgrad16_chunks(int rw, int rh, int batch, int patch_elems)
+{
+    Wgrad16Chunks c;
+    c.col_blocks = (rw + 63) / 64;
+    c.TC = c.col_blocks == 1 ? rw : (((rw + c.col_blocks - 1) / c.col_blocks + 7) & ~7);   // (blocks start at even columns)
+    c.col_blocks = (rw + c.TC - 1) / c.TC;
+    c.G = (c.TC + 7) / 8;
+    c.PWp = (c.TC + 3 + 7) & ~7;                             // TC + 2 halo columns + 1 for an odd start
+    c.RB = kW16Groups / c.G; if (c.RB > rh) c.RB = rh;
+    while (c.RB > 1 && (c.RB + 2) * c.PWp > patch_elems) --c.RB;
+    c.TI = 1;
+    if (c.RB == rh && c.col_blocks == 1) {
+        c.TI = kW16Groups / (c.G * rh);
+        const int by_patch = patch_elems / ((rh + 2) * c.PWp);
+        if (c.TI > by_patch) c.TI = by_patch;
+        if (c.TI > batch) c.TI = batch;
+        if (c.TI < 1) c.TI = 1;
+    }
+    c.row_blocks = (rh + c.RB - 1) / c.RB;
+    c.img_blocks = (batch + c.TI - 1) / c.TI;
+    c.total = c.img_blocks * c.row_blocks * c.col_blocks;
+    return c;
+}
+// Shares of one stack's chunk list for that kernel: blocks x shares should fill whole rounds of 512 workgroup slots
+// (two workgroups per CU) while a share keeps at least a few chunks; one more share costs a write and a read of the
+// layer's partial gradients.
+inline int wgrad16_shares(int cout, int cin, int stacks, int chunks)
+{
+    const double blocks = (double)((cout + 63) / 64) * ((cin + 63) / 64) * stacks;
+    const double unit_us = 1.6;                                                        // one chunk of one block
+    const double share_us = (double)stacks * cout * cin * 9 * 8.0 / 3.0e6;
+    const int smax = chunks / 2 < 64 ? (chunks / 2 < 1 ? 1 : chunks / 2) : 64;
+    int best = 1; double best_t = 0;
+    for (int s = 1; s <= smax; ++s) {
+        const double rounds = (double)(long long)((blocks * s + 511.0) / 512.0);
         const double t = rounds * 2.0 * ((chunks + s - 1) / s) * unit_us + (s > 1 ? s * share_us : 0.0);
         if (s == 1 || t < best_t) { best = s; best_t = t; }
     }

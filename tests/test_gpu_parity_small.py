@@ -69,6 +69,22 @@ def test_general_geometry_bf16_and_bias(oracle, net):
     P.check_case(oracle, _mk(net, (3, 2), "whole"), has_bias=True)
 
 
+# 16-bit storage, 3x3 filters wide enough for the packed filter-gradient kernel: rectangles wider than one column
+# block, odd widths and odd first columns, tiles narrower than one group of 8 pixels, several images per chunk,
+# channel counts that are no multiple of the workgroup's block, with and without the fused pool
+_NETS.update({
+    "w16plain": ((conv(4, 16), conv(16, 48), conv(48, 80), conv(80, 32)), 70, 54),
+    "w16pools": ((conv(4, 32), pool(32), conv(32, 64), pool(64), conv(64, 96), conv(96, 40)), 120, 88),
+})
+
+
+@pytest.mark.parametrize("net", ["w16plain", "w16pools"])
+@pytest.mark.parametrize("grouping", ["whole", "each"])
+@pytest.mark.parametrize("grid", [(1, 1), (3, 5), (7, 4)])
+def test_bf16_filter_gradient_shapes(oracle, net, grouping, grid):
+    P.check_case(oracle, _mk(net, grid, grouping, "bf16", batch=3))
+
+
 @pytest.mark.parametrize("grid", [(1, 1), (2, 3)])
 @pytest.mark.parametrize("grouping", ["whole", "split"])
 def test_deep_net_f32(oracle, grid, grouping):
