@@ -391,7 +391,8 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             if (overlap && gradient_in_flight && (rc = order(aux, s)) != FTP_OK) return rc;
             if (use_mfma() && thin_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { thin_wgrad(a, scratch, aux); });
-            } else if (use_mfma() && plain_geometry(a) && wgrad16_eligible(a)) {
+            } else if (use_mfma() && plain_geometry(a) && u.in_act.kind == BUF_WS && u.in_delta.kind == BUF_WS && wgrad16_eligible(a)) {
+                // (its wide loads round addresses down and may run a few bytes past a map: only inside the workspace, which has margins)
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { wgrad16(a, scratch, aux); });
             } else if (use_mfma() && mfma_wgrad_eligible(a)) {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { mfma_wgrad(a, scratch, aux); });

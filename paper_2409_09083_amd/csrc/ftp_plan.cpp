@@ -175,7 +175,7 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
     is_group_edge[0] = true;
     for (const GroupRects& g : p.groups) is_group_edge[g.e] = true;
 
-    size_t ws = 0;
+    size_t ws = 256;                           // (a margin in front: the 16-bit kernels round addresses down to whole dwords)
     auto alloc = [&](size_t bytes) { const size_t off = ws; ws = align256(ws + bytes); return off; };
 
     std::vector<BufRef>& act = p.act; std::vector<BufRef>& mask = p.mask; std::vector<BufRef>& delta = p.delta;
@@ -301,7 +301,7 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
                 for (int i = 0; i < N; ++i)
                     for (int j = 0; j < M; ++j) {
                         const Seg sx = gr.at(FTP_RECT_OWN, u.layer + 1, 0, j), sy = gr.at(FTP_RECT_OWN, u.layer + 1, 1, i);
-                        c16 = std::max(c16, wgrad16_chunks(sx.b - sx.a + 1, sy.b - sy.a + 1, batch, w16_patch_elems(w16_waves_ci(ly.cin))).total);
+                        c16 = std::max(c16, wgrad16_chunks(sx.b - sx.a + 1, sy.b - sy.a + 1, batch, w16_patch_elems(w16_waves_ci(ly.cin)), 1).total);
                     }
                 u.wgrad_shares16 = wgrad16_shares(ly.cout, ly.cin, N * M, c16);
             }
@@ -310,7 +310,8 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
         }
         p.wgrad_scratch_offset = alloc(scratch);
     }
-    p.workspace_bytes = std::max<size_t>(ws, 256);
+    // (a margin at the end: wide loads of the 16-bit kernels may run a few bytes past the last map)
+    p.workspace_bytes = std::max<size_t>(ws, 256) + 256;
 
     size_t poff = 0;
     for (Unit& u : p.units) {

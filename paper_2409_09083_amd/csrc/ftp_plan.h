@@ -143,25 +143,26 @@ inline int wgrad_shares(int cout, int cin, int k, int stacks, int chunks)
     return best;
 }
 
-// Chunks of the bfloat 3x3 filter-gradient kernel (ftp_wgrad16.hip): pixels are taken in groups of 8 consecutive
-// pixels of one row of the owned rectangle (a row of TC pixels has G groups, the last one padded with zero deltas),
-// 16 groups to a chunk: RB rows of one image, or, where a whole rectangle has fewer groups, TI whole images.  The
-// patch of a chunk (rows + 2 halo rows per image, PWp elements each, PWp a multiple of 8 so that every row starts on
-// a 16-byte boundary) has to fit the LDS row of a channel: an odd multiple of 16 bytes (lanes of consecutive channels
-// then read 16 bytes each without bank conflicts), twice as long where a workgroup holds 32 input channels only.
+// Chunks of the bfloat 3x3 filter-gradient kernel (ftp_wgrad16.hip).  The reduction runs over the elements of a patch
+// row of the input map, in groups of 8 that start on a 16-byte boundary of the patch; the patch starts `xs` elements
+// (0 or 1) before column x0 - 1, where the dword grid of the map falls.  A row of TC pixels reads TC + 2 + xs
+// elements: G = ceil((TC + 2 + xs) / 8) groups, PWp = 8 G elements per patch row.  16 groups to a chunk: RB rows of
+// one image, or, where a whole rectangle has fewer groups, TI whole images.  The patch of a chunk (rows + 2 halo rows
+// per image) has to fit the LDS row of a channel: an odd multiple of 16 bytes (lanes of consecutive channels then read
+// 16 bytes each without bank conflicts), twice as long where a workgroup holds 32 input channels only.
 constexpr int kW16Groups = 16;
-FTP_HD constexpr int w16_row_bytes(int waves_ci) { return waves_ci == 1 ? 976 : 496; }
-FTP_HD constexpr int w16_patch_elems(int waves_ci) { return w16_row_bytes(waves_ci) / 2 - 16; }      // (reads run up to 8 elements past the patch)
+FTP_HD constexpr int w16_row_bytes(int waves_ci) { return waves_ci == 1 ? 944 : 464; }
+FTP_HD constexpr int w16_patch_elems(int waves_ci) { return w16_row_bytes(waves_ci) / 2; }
 FTP_HD constexpr int w16_waves_ci(int cin) { return cin > 32 ? 2 : 1; }
 struct Wgrad16Chunks { int col_blocks, TC, G, PWp, RB, TI, row_blocks, img_blocks, total; };
-FTP_HD inline Wgrad16Chunks wgrad16_chunks(int rw, int rh, int batch, int patch_elems)
+FTP_HD inline Wgrad16Chunks wgrad16_chunks(int rw, int rh, int batch, int patch_elems, int xs)
 {
     Wgrad16Chunks c;
     c.col_blocks = (rw + 63) / 64;
     c.TC = c.col_blocks == 1 ? rw : (((rw + c.col_blocks - 1) / c.col_blocks + 7) & ~7);   // (blocks start at even columns)
     c.col_blocks = (rw + c.TC - 1) / c.TC;
-    c.G = (c.TC + 7) / 8;
-    c.PWp = (c.TC + 3 + 7) & ~7;                             // TC + 2 halo columns + 1 for an odd start
+    c.G = (c.TC + 2 + xs + 7) / 8;
+    c.PWp = 8 * c.G;
     c.RB = kW16Groups / c.G; if (c.RB > rh) c.RB = rh;
     while (c.RB > 1 && (c.RB + 2) * c.PWp > patch_elems) --c.RB;
     c.TI = 1;

@@ -1,20 +1,25 @@
 // Per-stack filter gradient of 3x3 stride-1 convolutions over 16-bit (bfloat) maps on the matrix cores of gfx950
 // (Sec. 4.1: the filter gradient of a tile is the correlation of its input map with the delta map of its output, summed
 // over the batch and over the pixels the tile owns):
-//   dW[co][ci][tap] = sum over images and owned output pixels q of dZ[co][q] * X[ci][q + tap - 1]
+//   dW[co][ci][ky][kx] = sum over images and owned output pixels (y, c) of dZ[co][y][c] * X[ci][y + ky - 1][c + kx - 1]
 // is a GEMM with M = co, N = ci and the pixels as reduction dimension, one accumulator tile per tap.
 //
 // v_mfma_f32_32x32x16_bf16 takes, per lane, 8 consecutive reduction elements of one row of A and one column of B
-// (A[m = lane%32][k = 8*(lane/32) + j], B[k = 8*(lane/32) + j][n = lane%32], j < 8).  With the pixels as reduction
-// dimension and maps stored pixel-contiguous per channel, those 8 elements are 8 consecutive pixels of one row of the
-// owned rectangle: 16 contiguous bytes of dZ, and for tap (ky, kx) 16 bytes of X that start kx elements further.
-// So the maps stay packed (two bfloats to a dword) and channel-major in LDS, as they are in HBM:
-//   X   HBM -> LDS with buffer_load ... lds, one dword (two neighbouring pixels) per lane, no registers in between;
-//       dwords outside the map (zero padding) come from out-of-range offsets, which read as zero; where the map ends in
-//       the middle of a dword the loading wavefront clears that one element afterwards.  The three taps of a filter
-//       row are cut out of 6 loaded dwords, the odd ones with v_alignbit.
-//   dZ  through registers (it needs per-pixel treatment: the rectangle's ragged end, and behind a pool the routing of
-//       each pooled delta to its window's winner), written to LDS as [group of 8 pixels][co][16 bytes].
+// (A[m = lane%32][k = 8*(lane/32) + j], B[k = 8*(lane/32) + j][n = lane%32], j < 8).  The maps are pixel-contiguous
+// per channel in HBM, so 8 consecutive reduction elements are 16 contiguous bytes if the reduction index is the
+// position e in a row of the input patch:
+//   dW[..][ky][kx] = sum over rows y and patch positions e of dZrow[y][e - kx] * Xpatch[y + ky][e]
+// where Xpatch row positions count from the patch's first element and dZrow is the row of deltas moved to where its
+// first pixel reads tap kx = 0, zero outside the owned pixels.  So:
+//   X   stays packed (two bfloats to a dword) and channel-major in LDS, as in HBM, and goes HBM -> LDS with
+//       buffer_load_dwordx4 ... lds, 16 bytes per lane, no registers in between.  The patch starts on the dword grid of
+//       the map (one element before column x0 - 1 where that is odd).  Units outside the map come from out-of-range
+//       offsets, which read as zero; elements a unit brings along beyond the needed columns are cleared afterwards by
+//       the wavefront that loaded it.  One aligned 16-byte LDS read serves the three taps of a filter row.
+//   dZ  goes through registers (it needs per-pixel treatment: the ends of a row, and behind a pool the routing of each
+//       pooled delta to its window's winner) and is written to LDS as [group of 8 positions][co][16 bytes]; the tap
+//       kx = 1, 2 operands are that group shifted by one and two elements, cut from it and the last dword of the group
+//       before it in the row (kept in a small table of its own, so that every LDS read is free of bank conflicts).
 // Two patch buffers alternate, so the loads of chunk i+1 are in flight while the matrix cores work on chunk i.
 #include "ftp_device.h"
 #include "ftp_launch.h"
@@ -38,6 +43,7 @@ struct Wgrad16Args {
 constexpr unsigned kOob16 = 0x80000000u;            // beyond the records of every buffer resource below: reads as zero
 constexpr unsigned kRecords16 = 0x7FFFFFFFu;
 
+
 __device__ __forceinline__ uint32_t alignhalf(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
 
 // HALF: 0 = deltas at the resolution of the owned rectangle; 1 = a 2x2 pool follows the convolution: the deltas sit
@@ -51,12 +57,13 @@ k_wgrad_mfma16(Wgrad16Args a)
     constexpr int NG = kW16Groups;
     constexpr int XSB = w16_row_bytes(WAVES_CI);
     constexpr int XBUF = BCI * XSB;
-    constexpr int ZBYTES = NG * BCO * 16;
+    constexpr int ZBYTES = NG * BCO * 16, PBYTES = NG * BCO * 4;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds16[];
     unsigned char* const Xl0 = lds16;
     unsigned char* const Xl1 = lds16 + XBUF;
     unsigned char* const Zl = lds16 + 2 * XBUF;           // [group][co (rotated by the group index)][8 bfloats]
-    int* const gtab = (int*)(Zl + ZBYTES);                // [group] -> byte offset of its pixels' tap (0, 0) in a patch row (even floor)
+    uint32_t* const Zp = (uint32_t*)(Zl + ZBYTES);        // [group][co]: last dword of the group before it in the row (or 0)
+    int* const gtab = (int*)(Zl + ZBYTES + PBYTES);       // [group] -> byte offset of its 8 positions in a patch row (ky = 0)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -69,12 +76,23 @@ k_wgrad_mfma16(Wgrad16Args a)
     const int co0 = (blockIdx.x / tiles_ci) * BCO, ci0 = (blockIdx.x % tiles_ci) * BCI;
     const int split = blockIdx.y;
 
-    const Wgrad16Chunks wc = wgrad16_chunks(rw, rh, a.batch, w16_patch_elems(WAVES_CI));
-    const int G = wc.G, PWp = wc.PWp, HW = wc.PWp >> 1;
+    // what the per-chunk code needs of the argument block, once
+    const int Hc = a.Hc, Wc = a.Wc, Cin = a.Cin, Cout = a.Cout, batch = a.batch;
+    const int in_x0 = a.in.x0[tj], in_y0 = a.in.y0[ti], in_pitch = a.in.pitch, in_cs = (int)a.in.cs, in_ns = (int)a.in.ns;
+    const int d_x0 = a.din.x0[tj], d_y0 = a.din.y0[ti], d_pitch = a.din.pitch, d_cs = (int)a.din.cs, d_ns = (int)a.din.ns;
+    const int m_x0 = a.mask.x0[tj], m_y0 = a.mask.y0[ti], m_pitch = a.mask.pitch, m_cs = (int)a.mask.cs, m_ns = (int)a.mask.ns;
+    // Parity of the patch's first column (x0 - 1) in the input view: the patch starts one element earlier where it is
+    // odd (strides of the view are even, column blocks a multiple of 8 wide: the same for every row, channel and chunk
+    // of the stack).  Patch position e is map column xb - 1 - xs + e; pixel c of a row reads positions c + xs + kx.
+    // Group gi holds the deltas of pixels 8 gi - xs .. 8 gi - xs + 7 (the pixels whose tap kx = 0 sits at positions
+    // 8 gi .. 8 gi + 7), zero where there is no such pixel.
+    const int xs = (x0 - 1 - in_x0) & 1;
+    const Wgrad16Chunks wc = wgrad16_chunks(rw, rh, batch, w16_patch_elems(WAVES_CI), xs);
+    const int G = wc.G, PWp = wc.PWp;
     const int id0 = (int)((long long)split * wc.total / a.splits), id1 = (int)((long long)(split + 1) * wc.total / a.splits);
 
-    // LDS starts as zeros: patch elements no load ever writes are multiplied with zero deltas only, and must be finite
-    for (int i = tid; i < (2 * XBUF + ZBYTES + NG * 4) / 4; i += 256) ((uint32_t*)lds16)[i] = 0u;
+    // LDS starts as zeros (everything a multiply reads is written first, except patch rows beyond a short chunk's)
+    for (int i = tid; i < (2 * XBUF + ZBYTES + PBYTES + NG * 4) / 4; i += 256) ((uint32_t*)lds16)[i] = 0u;
 
     v16f acc[9];
 #pragma unroll
@@ -82,196 +100,256 @@ k_wgrad_mfma16(Wgrad16Args a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
 
+    // Chunks: (image block, row block, column block), column block fastest.  Either a chunk is RB rows of one image
+    // (TI == 1), or TI whole images of rh rows: in both cases a patch position or a group index splits into (image, row,
+    // column part) the same way in every chunk of the stack, so each lane does that once.
     struct Chunk { int n0, ni, yb, nr, xb, nc; };
-    auto chunk_at = [&](int id) {
-        const int per_img = wc.row_blocks * wc.col_blocks;
-        const int ib = id / per_img, rem = id - ib * per_img;
-        const int rb = rem / wc.col_blocks, cb = rem - rb * wc.col_blocks;
+    const int RB = wc.RB, TI = wc.TI, TC = wc.TC, row_blocks = wc.row_blocks, col_blocks = wc.col_blocks;
+    auto chunk_of = [&](int ib, int rb, int cb) {
         Chunk c;
-        c.n0 = ib * wc.TI; c.ni = (a.batch - c.n0) < wc.TI ? (a.batch - c.n0) : wc.TI;
-        c.yb = y0 + rb * wc.RB; c.nr = (y1 - c.yb + 1) < wc.RB ? (y1 - c.yb + 1) : wc.RB;
-        c.xb = x0 + cb * wc.TC; c.nc = (x1 - c.xb + 1) < wc.TC ? (x1 - c.xb + 1) : wc.TC;
+        c.n0 = ib * TI; c.ni = (batch - c.n0) < TI ? (batch - c.n0) : TI;
+        c.yb = y0 + rb * RB; c.nr = (y1 - c.yb + 1) < RB ? (y1 - c.yb + 1) : RB;
+        c.xb = x0 + cb * TC; c.nc = (x1 - c.xb + 1) < TC ? (x1 - c.xb + 1) : TC;
         return c;
     };
-    // parity of the patch's first column in the input view: the even element of every loaded dword is the element
-    // just before it when the start is odd (strides of the view are even, so this holds for every row and channel)
-    auto patch_shift = [&](const Chunk& c) { return (c.xb - 1 - a.in.x0[tj]) & 1; };
+    const int prh_full = (TI > 1 ? rh : RB) + 2;                   // patch rows per image (TI > 1: always whole images)
+    // lane -> 16-byte unit of the patch: (image, row of its patch, unit of the row; G units to a row); a chunk with fewer
+    // rows (TI == 1: one image) has the same split, only fewer positions
+    const int x_pr = lane / G, x_u = lane - x_pr * G;
+    const int x_il = TI > 1 ? x_pr / prh_full : 0, x_lr = TI > 1 ? x_pr - x_il * prh_full : x_pr;
+    // thread -> group of the chunk: (row of the chunk, group of the row); row -> (image, row of the image)
+    const int zg = tid & 15, zco = tid >> 4;
+    const int z_fr = zg / G, z_gi = zg - z_fr * G;
+    const int z_il = TI > 1 ? z_fr / rh : 0, z_r = TI > 1 ? z_fr - z_il * rh : z_fr;
 
     // ---- X: HBM -> LDS ------------------------------------------------------------------------------------------
-    const bf16_t* const xstack = (const bf16_t*)a.in.p + (long long)stack * a.in.ss;
+    // One lane moves 16 bytes (8 elements, a "unit"; the memory pipeline handles four lanes a clock whatever their width,
+    // so dword loads would take four times as many instructions).  A unit is loaded if its row lies in the map and it
+    // overlaps the needed columns [xb - 1, xb + nc] cut to the map.  Its address is a multiple of 4 bytes, possibly
+    // 4 bytes before the view (the buffer resource starts 4 bytes early).
+    const bf16_t* const xstack = (const bf16_t*)a.in.p + (long long)stack * a.in.ss - 2;
     auto issue_x = [&](unsigned char* Xb, const Chunk& c) {
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(xstack + (long long)c.n0 * a.in.ns), (short)0, (int)kRecords16, 0x00020000);
-        const int xs = patch_shift(c);
-        const int prh = c.nr + 2, pdw = c.ni * prh * HW;
-        const int na = c.xb - 1 > 0 ? c.xb - 1 : 0, nb = c.xb + c.nc < a.Wc ? c.xb + c.nc : a.Wc - 1;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(xstack + (long long)c.n0 * in_ns), (short)0, (int)kRecords16, 0x00020000);
+        const int pu = c.ni * (c.nr + 2) * G;                      // units of the patch: at most 64
+        const int na = c.xb - 1 > 0 ? c.xb - 1 : 0, nb = c.xb + c.nc < Wc ? c.xb + c.nc : Wc - 1;
+        if (lane < pu) {                                            // (lanes beyond the patch must not write into the next channel's row)
+            const int y = c.yb - 1 + x_lr, mx = c.xb - 1 - xs + 8 * x_u;
+            unsigned vo = kOob16;
+            if (y >= 0 && y < Hc && mx + 7 >= na && mx <= nb)
+                vo = 4u + 2u * (unsigned)(x_il * in_ns + (y - in_y0) * in_pitch + (mx - in_x0));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (j * 64 < pdw) {
-                const int p = j * 64 + lane;
-                if (p < pdw) {                      // (lanes beyond the patch must not write into the next channel's row)
-                    const int pr = p / HW, d = p - pr * HW;
-                    const int il = pr / prh, lr = pr - il * prh;
-                    const int y = c.yb - 1 + lr, mx = c.xb - 1 - xs + 2 * d;
-                    unsigned vo = kOob16;
-                    if (y >= 0 && y < a.Hc && mx + 1 >= na && mx <= nb)
-                        vo = 2u * (unsigned)(il * (int)a.in.ns + (y - a.in.y0[ti]) * a.in.pitch + (mx - a.in.x0[tj]));
-#pragma unroll
-                    for (int k = 0; k < BCI / 4; ++k) {
-                        const int ci = wave + 4 * k;
-                        const unsigned v = ci0 + ci < a.Cin ? vo : kOob16;
-                        const unsigned so = 2u * (unsigned)((ci0 + ci) * (int)a.in.cs);
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FTP_LDS_PTR(Xb + ci * XSB + j * 256), 4, v, so, 0, 0);
-                    }
-                }
+            for (int k = 0; k < BCI / 4; ++k) {
+                const int ci = wave + 4 * k;
+                const unsigned v = ci0 + ci < Cin ? vo : kOob16;
+                const unsigned so = 2u * (unsigned)((ci0 + ci) * in_cs);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FTP_LDS_PTR(Xb + ci * XSB), 16, v, so, 0, 0);
             }
         }
     };
-    // Where the needed columns end on the even element of a dword, the odd element came along: it is the zero padding
-    // beyond the map's last column, or lies beyond everything a valid pixel reads.  The wavefront that loaded a channel
-    // clears it (after its loads have landed).
+    // The first and the last loaded unit of a row bring elements outside the needed columns along: zero padding beyond
+    // the map's first / last column (read by real pixels), or columns that only meet zero deltas (other stacks' data,
+    // another buffer, or memory nobody wrote: it has to be finite at least).  The wavefront that loaded a channel clears
+    // them once its loads have landed: lane = patch row, a few zero stores per channel.
     auto fixup_x = [&](unsigned char* Xb, const Chunk& c) {
-        const int xs = patch_shift(c);
-        const int nb = c.xb + c.nc < a.Wc ? c.xb + c.nc : a.Wc - 1;
-        const int eb = nb - (c.xb - 1) + xs;                       // patch element of the last needed column
-        if (eb & 1) return;
-        const int prows = c.ni * (c.nr + 2), items = (BCI / 4) * prows;
-        for (int it = lane; it < items; it += 64) {
-            const int k = it / prows, pr = it - k * prows;
-            *(uint16_t*)(Xb + (wave + 4 * k) * XSB + (pr * PWp + eb + 1) * 2) = (uint16_t)0;
+        const int na = c.xb - 1 > 0 ? c.xb - 1 : 0, nb = c.xb + c.nc < Wc ? c.xb + c.nc : Wc - 1;
+        const int e_first = na - (c.xb - 1) + xs, e_last = nb - (c.xb - 1) + xs;      // first / last needed position (e_first <= 2)
+        int z = e_last + 1;
+        const int zend = (e_last | 7) + 1;                         // positions [e_last + 1, zend) of the last unit are cleared
+        const bool w16 = (z & 1) != 0; z += z & 1;
+        const bool w32 = (z & 2) && z < zend; const int z32 = z; z += w32 ? 2 : 0;
+        const bool w64 = (z & 4) && z < zend; const int z64 = z;
+        if (lane < c.ni * (c.nr + 2)) {
+            unsigned char* row = Xb + wave * XSB + lane * PWp * 2;
+            if (e_first == 1) {
+#pragma unroll
+                for (int k = 0; k < BCI / 4; ++k) *(uint16_t*)(row + 4 * k * XSB) = (uint16_t)0;
+            }
+            if (e_first == 2) {
+#pragma unroll
+                for (int k = 0; k < BCI / 4; ++k) *(uint32_t*)(row + 4 * k * XSB) = 0u;
+            }
+            if (w16) {
+#pragma unroll
+                for (int k = 0; k < BCI / 4; ++k) *(uint16_t*)(row + 4 * k * XSB + 2 * (e_last + 1)) = (uint16_t)0;
+            }
+            if (w32) {
+#pragma unroll
+                for (int k = 0; k < BCI / 4; ++k) *(uint32_t*)(row + 4 * k * XSB + 2 * z32) = 0u;
+            }
+            if (w64) {
+#pragma unroll
+                for (int k = 0; k < BCI / 4; ++k) *(uint2*)(row + 4 * k * XSB + 2 * z64) = make_uint2(0u, 0u);
+            }
         }
     };
 
     // ---- dZ: HBM -> registers -> LDS ----------------------------------------------------------------------------
-    // thread -> group g = tid % 16 of the chunk and output channels tid / 16 + 16 * it
-    const int zg = tid & 15, zco = tid >> 4;
+    // thread -> group g = tid % 16 of the chunk and output channels tid / 16 + 16 * it.  A group's 8 pixels are 16
+    // contiguous bytes in HBM that start on a 2-byte boundary: 4 dwords from the even element at or before them, and a
+    // fifth when the start is odd.  Behind a pool: the 5 pooled deltas (3 dwords) and 5 code bytes (2 dwords) of the
+    // windows the group touches.  Pixels outside the row are masked; the loads may start 4 bytes before a map and run a
+    // few bytes past it (the workspace has margins for that): the buffer resources start 4 bytes early.
     uint32_t zr[4][5];
-    int zvalid = 0, zsh = 0, zwant = 0, zgoff = 0;
-    const bf16_t* const zstack = (const bf16_t*)a.din.p + (long long)stack * a.din.ss;
-    const uint8_t* const mstack = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss;
+    int zlo = 0, zhi = 0, zsh = 0, zwant = 0, zgoff = 0, zbo0 = 0;
+    bool zfrom_next = false;
+    const bf16_t* const zstack = (const bf16_t*)a.din.p + (long long)stack * a.din.ss - 2;
+    const uint8_t* const mstack = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss - 4;
     auto load_z = [&](const Chunk& c) {
         const int ngroups = c.ni * c.nr * G;
-        const int fr = zg / G, gi = zg - fr * G;
-        const int il = fr / c.nr, r = fr - il * c.nr;
-        const int c0 = 8 * gi;
-        int valid = c.nc - c0; valid = valid > 8 ? 8 : valid;
-        const bool exists = zg < ngroups && valid > 0;
-        zvalid = exists ? valid : 0;
-        zgoff = exists ? 2 * ((il * (c.nr + 2) + r) * PWp + c0) : 0;
-        const __amdgpu_buffer_rsrc_t zrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(zstack + (long long)c.n0 * a.din.ns), (short)0, (int)kRecords16, 0x00020000);
+        const int gi = z_gi, il = z_il, r = z_r;
+        const int cs0 = 8 * gi - xs;                               // first pixel of the group, relative to the row
+        int lo = cs0 < 0 ? -cs0 : 0, hi_ = c.nc - cs0; hi_ = hi_ > 8 ? 8 : hi_;
+        const bool inrow = zg < ngroups, exists = inrow && hi_ > lo;
+        zlo = exists ? lo : 0; zhi = exists ? hi_ : 0;
+        zgoff = inrow ? 2 * ((il * (c.nr + 2) + r) * PWp + 8 * gi) : 0;
+        const __amdgpu_buffer_rsrc_t zrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(zstack + (long long)c.n0 * d_ns), (short)0, (int)kRecords16, 0x00020000);
+        typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+        typedef uint32_t v3u __attribute__((ext_vector_type(3)));
+        typedef uint32_t v2u __attribute__((ext_vector_type(2)));
         if (HALF == 0) {
-            const int eo = il * (int)a.din.ns + (c.yb + r - a.din.y0[ti]) * a.din.pitch + (c.xb + c0 - a.din.x0[tj]);
-            const int odd = eo & 1, nd = (odd + zvalid + 1) >> 1;
+            const int eo = il * d_ns + (c.yb + r - d_y0) * d_pitch + (c.xb + cs0 - d_x0);       // (-1 at the very first pixel of a view)
+            const int odd = eo & 1;
             zsh = odd * 16;
+            // the fifth dword is the first dword of the next group of the row, which the next lane loads (same channel);
+            // only where the row's pixels end with this group it takes a load of its own
+            const bool fifth = odd && zhi == 8;
+            zfrom_next = fifth && c.nc - cs0 > 8;
+            const bool extra = fifth && !zfrom_next;
+            const bool any_extra = __builtin_amdgcn_ballot_w64(extra) != 0ull;
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 const int gco = co0 + zco + 16 * it;
-                const bool ok = exists && gco < a.Cout;
-                const unsigned base = 2u * (unsigned)((eo & ~1) + gco * (int)a.din.cs);
-#pragma unroll
-                for (int i = 0; i < 5; ++i) {
-                    const int ii = i < nd ? i : nd - 1;
-                    zr[it][i] = __builtin_amdgcn_raw_buffer_load_b32(zrsrc, ok ? base + 4u * (unsigned)ii : kOob16, 0, 0);
-                }
+                const bool ok = exists && gco < Cout;
+                const unsigned base = 4u + 2u * (unsigned)((eo & ~1) + gco * d_cs);
+                const v4u q = __builtin_amdgcn_raw_buffer_load_b128(zrsrc, ok ? base : kOob16, 0, 0);
+                zr[it][0] = q[0]; zr[it][1] = q[1]; zr[it][2] = q[2]; zr[it][3] = q[3];
+                zr[it][4] = 0u;
+                if (any_extra) zr[it][4] = __builtin_amdgcn_raw_buffer_load_b32(zrsrc, ok && extra ? base + 16u : kOob16, 0, 0);
             }
         } else {
-            const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(mstack + (long long)c.n0 * a.mask.ns), (short)0, (int)kRecords16, 0x00020000);
-            const int py = (c.yb + r) >> 1, pc = (c.xb + c0) >> 1, nwin = (zvalid + 1) >> 1;
+            const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(mstack + (long long)c.n0 * m_ns), (short)0, (int)kRecords16, 0x00020000);
+            // first window the group touches (the rectangle starts at an even column: windows are whole inside it)
+            const int py = (c.yb + r) >> 1, pw = (c.xb >> 1) + 4 * gi - xs;
             zwant = 2 * ((c.yb + r) & 1);
-            const int eo = il * (int)a.din.ns + (py - a.din.y0[ti]) * a.din.pitch + (pc - a.din.x0[tj]);
-            const int odd = eo & 1, nd = (odd + nwin + 1) >> 1;
-            zsh = odd * 16;
-            const int bo0 = il * (int)a.mask.ns + (py - a.mask.y0[ti]) * a.mask.pitch + (pc - a.mask.x0[tj]);
+            const int eo = il * d_ns + (py - d_y0) * d_pitch + (pw - d_x0);
+            zsh = (eo & 1) * 16;
+            zbo0 = il * m_ns + (py - m_y0) * m_pitch + (pw - m_x0);
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 const int gco = co0 + zco + 16 * it;
-                const bool ok = exists && gco < a.Cout;
-                const unsigned base = 2u * (unsigned)((eo & ~1) + gco * (int)a.din.cs);
-#pragma unroll
-                for (int i = 0; i < 3; ++i) {
-                    const int ii = i < nd ? i : nd - 1;
-                    zr[it][i] = __builtin_amdgcn_raw_buffer_load_b32(zrsrc, ok ? base + 4u * (unsigned)ii : kOob16, 0, 0);
-                }
-                const int bo = bo0 + gco * (int)a.mask.cs;
-                const int ncd = ((bo & 3) + nwin + 3) >> 2;
-                zr[it][3] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, ok ? (unsigned)(bo & ~3) : kOob16, 0, 0);
-                zr[it][4] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, ok ? (unsigned)(bo & ~3) + (ncd > 1 ? 4u : 0u) : kOob16, 0, 0);
+                const bool ok = exists && gco < Cout;
+                const unsigned base = 4u + 2u * (unsigned)((eo & ~1) + gco * d_cs);
+                const v3u q = __builtin_amdgcn_raw_buffer_load_b96(zrsrc, ok ? base : kOob16, 0, 0);
+                zr[it][0] = q[0]; zr[it][1] = q[1]; zr[it][2] = q[2];
+                const int bo = zbo0 + gco * m_cs;
+                const v2u k2 = __builtin_amdgcn_raw_buffer_load_b64(mrsrc, ok ? 4u + (unsigned)(bo & ~3) : kOob16, 0, 0);
+                zr[it][3] = k2[0]; zr[it][4] = k2[1];
             }
         }
     };
-    // element mask of output dword i of a group with `n` valid pixels
-    auto keep = [](int n, int i) -> uint32_t { return n >= 2 * i + 2 ? 0xFFFFFFFFu : n == 2 * i + 1 ? 0x0000FFFFu : 0u; };
-    auto store_z = [&](const Chunk& c) {
+    // which elements of output dword i (elements 2i, 2i+1) lie in [lo, hi)
+    auto keep = [](int lo, int hi_, int i) -> uint32_t {
+        return ((2 * i >= lo && 2 * i < hi_) ? 0x0000FFFFu : 0u) | ((2 * i + 1 >= lo && 2 * i + 1 < hi_) ? 0xFFFF0000u : 0u);
+    };
+    auto store_z = [&]() {
         if (tid < NG) gtab[zg] = zgoff;
-        int bo0 = 0;
-        if (HALF == 1) {
-            const int fr = zg / G, gi = zg - fr * G;
-            const int il = fr / c.nr, r = fr - il * c.nr;
-            const int py = (c.yb + r) >> 1, pc = (c.xb + 8 * gi) >> 1;
-            bo0 = il * (int)a.mask.ns + (py - a.mask.y0[ti]) * a.mask.pitch + (pc - a.mask.x0[tj]);
-        }
+        const uint32_t k0 = keep(zlo, zhi, 0), k1 = keep(zlo, zhi, 1), k2 = keep(zlo, zhi, 2), k3 = keep(zlo, zhi, 3);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int co = zco + 16 * it;
             uint32_t o[4];
             if (HALF == 0) {
+                const uint32_t nxt = (uint32_t)__shfl_down((int)zr[it][0], 1, 16);      // first dword of the next lane's group
+                const uint32_t q4 = zfrom_next ? nxt : zr[it][4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = __builtin_amdgcn_alignbit(zr[it][i + 1], zr[it][i], (uint32_t)zsh) & keep(zvalid, i);
+                for (int i = 0; i < 4; ++i) o[i] = __builtin_amdgcn_alignbit(i < 3 ? zr[it][i + 1] : q4, zr[it][i], (uint32_t)zsh);
             } else {
-                // 4 pooled deltas and their 4 winner codes; window j feeds pixels 2j and 2j+1 of this row
+                // 5 pooled deltas and their winner codes; element j of the group is pixel 8 gi - xs + j: window
+                // ((j - xs) >> 1) + xs of the 5, left or right pixel by the parity of j + xs
                 const uint32_t d01 = __builtin_amdgcn_alignbit(zr[it][1], zr[it][0], (uint32_t)zsh);
                 const uint32_t d23 = __builtin_amdgcn_alignbit(zr[it][2], zr[it][1], (uint32_t)zsh);
-                const int bo = bo0 + (co0 + co) * (int)a.mask.cs;
-                const uint32_t cw = __builtin_amdgcn_alignbyte(zr[it][4], zr[it][3], (uint32_t)(bo & 3));
+                const uint32_t d4 = zr[it][2] >> zsh;
+                const int bo = zbo0 + (co0 + co) * m_cs;
+                const unsigned long long kk = (((unsigned long long)zr[it][4] << 32) | zr[it][3]) >> (8 * (bo & 3));
+                uint32_t dv[5], wn[5];
+                dv[0] = d01 & 0xFFFFu; dv[1] = d01 >> 16; dv[2] = d23 & 0xFFFFu; dv[3] = d23 >> 16; dv[4] = d4 & 0xFFFFu;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t dj = ((j & 2) ? d23 : d01) >> ((j & 1) * 16) & 0xFFFFu;
-                    const uint32_t win = (cw >> (8 * j + 1)) & 3u;
+                for (int w = 0; w < 5; ++w) wn[w] = (uint32_t)(kk >> (8 * w + 1)) & 3u;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
                     uint32_t v = 0;
-                    if (win == (uint32_t)zwant) v = dj;
-                    if (win == (uint32_t)zwant + 1u) v = dj << 16;
-                    o[j] = v & keep(zvalid, j);
+                    if (xs == 0) {
+                        // elements 2i, 2i+1 are the left and right pixel of window i
+                        if (wn[i] == (uint32_t)zwant) v = dv[i];
+                        if (wn[i] == (uint32_t)zwant + 1u) v = dv[i] << 16;
+                    } else {
+                        // element 2i is the right pixel of window i, element 2i+1 the left pixel of window i+1
+                        if (wn[i] == (uint32_t)zwant + 1u) v = dv[i];
+                        if (wn[i + 1] == (uint32_t)zwant) v |= dv[i + 1] << 16;
+                    }
+                    o[i] = v;
                 }
             }
+            o[0] &= k0; o[1] &= k1; o[2] &= k2; o[3] &= k3;
             *(uint4*)(Zl + (zg * BCO + ((co + zg) & (BCO - 1))) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+            // the next group of the row finds this group's last dword in the table; the first group of a row finds zero
+            if (z_gi + 1 < G && zg + 1 < NG) Zp[(zg + 1) * BCO + co] = o[3];
+            if (z_gi == 0) Zp[zg * BCO + co] = 0u;
         }
     };
 
     // ---- multiply ---------------------------------------------------------------------------------------------
+    // A step multiplies two groups (lanes 0-31 one, lanes 32-63 the next).  Per group: the deltas at the group's 8
+    // positions for tap kx = 0 (a0), and the same row of deltas one and two elements earlier for kx = 1, 2 (a1, a2), against
+    // the three patch rows ky = 0, 1, 2 at those positions.  The operands of the next filter row are read from LDS
+    // before the matrix-core instructions of the current one are issued.
     const int co_l = wave_co * 32 + l32, ci_l = wave_ci * 32 + l32;
-    auto multiply = [&](const unsigned char* Xb, const Chunk& c) {
-        const int nsteps = (c.ni * c.nr * G + 1) >> 1;
-        const int xs = patch_shift(c);
+    constexpr int NSTEP = NG / 2 / WAVES_K;              // steps of one wavefront per chunk, at most
+    auto multiply = [&](const unsigned char* Xb, int ngroups) {
+        const int nsteps = (ngroups + 1) >> 1;
+        if (wave_k >= nsteps) return;
         const unsigned char* xrow = Xb + ci_l * XSB;
-        for (int s = wave_k; s < nsteps; s += WAVES_K) {
-            const int g = 2 * s + hi;
-            const int goff = gtab[g];
-            const uint4 av = *(const uint4*)(Zl + (g * BCO + ((co_l + g) & (BCO - 1))) * 16);
-            const v8bf A = __builtin_bit_cast(v8bf, av);
+        auto read_row = [&](int goff, int ky) { return *(const uint4*)(xrow + goff + ky * PWp * 2); };
+        auto read_a = [&](int i) {
+            const int g = 2 * (wave_k + WAVES_K * i) + hi;
+            return *(const uint4*)(Zl + (g * BCO + ((co_l + g) & (BCO - 1))) * 16);
+        };
+        auto read_p = [&](int i) { return Zp[(2 * (wave_k + WAVES_K * i) + hi) * BCO + co_l]; };
+        int gcur = gtab[2 * wave_k + hi];
+        uint4 a_cur = read_a(0);
+        uint32_t p_cur = read_p(0);
+        uint4 r_cur = read_row(gcur, 0);
+        for (int s = wave_k, i = 0; s < nsteps; s += WAVES_K, ++i) {
+            // (the step after the last one reads a group slot that exists in LDS, and is not used)
+            const int inext = i + 1 < NSTEP ? i + 1 : i;
+            const int gnext = gtab[2 * (wave_k + WAVES_K * inext) + hi];
+            const uint4 a1 = make_uint4(alignhalf(a_cur.x, p_cur), alignhalf(a_cur.y, a_cur.x), alignhalf(a_cur.z, a_cur.y), alignhalf(a_cur.w, a_cur.z));
+            const uint4 a2 = make_uint4(p_cur, a_cur.x, a_cur.y, a_cur.z);
+            const v8bf A0 = __builtin_bit_cast(v8bf, a_cur), A1 = __builtin_bit_cast(v8bf, a1), A2 = __builtin_bit_cast(v8bf, a2);
+            uint4 a_next = a_cur;
+            uint32_t p_next = p_cur;
 #pragma unroll
             for (int ky = 0; ky < 3; ++ky) {
-                const unsigned char* rp = xrow + goff + ky * PWp * 2;
-                const uint4 d = *(const uint4*)rp;
-                const uint2 e = *(const uint2*)(rp + 16);
-                uint4 t0, t1, t2;
-                if (xs == 0) {
-                    t0 = d;
-                    t1 = make_uint4(alignhalf(d.y, d.x), alignhalf(d.z, d.y), alignhalf(d.w, d.z), alignhalf(e.x, d.w));
-                    t2 = make_uint4(d.y, d.z, d.w, e.x);
-                } else {
-                    t0 = make_uint4(alignhalf(d.y, d.x), alignhalf(d.z, d.y), alignhalf(d.w, d.z), alignhalf(e.x, d.w));
-                    t1 = make_uint4(d.y, d.z, d.w, e.x);
-                    t2 = make_uint4(alignhalf(d.z, d.y), alignhalf(d.w, d.z), alignhalf(e.x, d.w), alignhalf(e.y, e.x));
-                }
-                acc[3 * ky + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(v8bf, t0), acc[3 * ky + 0], 0, 0, 0);
-                acc[3 * ky + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(v8bf, t1), acc[3 * ky + 1], 0, 0, 0);
-                acc[3 * ky + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(v8bf, t2), acc[3 * ky + 2], 0, 0, 0);
+                uint4 r_next;
+                if (ky < 2) r_next = read_row(gcur, ky + 1);
+                else { r_next = read_row(gnext, 0); a_next = read_a(inext); p_next = read_p(inext); }
+                __builtin_amdgcn_sched_barrier(0);     // keep these reads ahead of the matrix-core instructions below
+                const v8bf B = __builtin_bit_cast(v8bf, r_cur);
+                acc[3 * ky + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0, B, acc[3 * ky + 0], 0, 0, 0);
+                acc[3 * ky + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, B, acc[3 * ky + 1], 0, 0, 0);
+                acc[3 * ky + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, B, acc[3 * ky + 2], 0, 0, 0);
+                r_cur = r_next;
             }
+            a_cur = a_next; p_cur = p_next;
+            gcur = gnext;
         }
     };
 
     __syncthreads();                                    // the cleared LDS is visible
     if (id0 < id1) {
-        Chunk cur = chunk_at(id0);
+        const int per_img = row_blocks * col_blocks;
+        int ib = id0 / per_img, rb = (id0 - ib * per_img) / col_blocks, cb = id0 - ib * per_img - rb * col_blocks;
+        Chunk cur = chunk_of(ib, rb, cb);
         issue_x(Xl0, cur);
         load_z(cur);
         int buf = 0;
@@ -279,12 +357,17 @@ k_wgrad_mfma16(Wgrad16Args a)
             unsigned char* Xb = buf ? Xl1 : Xl0;
             __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wavefront's patch loads and delta registers have landed
             fixup_x(Xb, cur);
-            store_z(cur);
+            store_z();
             __syncthreads();                            // chunk `id` is complete in LDS
             const bool more = id + 1 < id1;
             Chunk nxt = cur;
-            if (more) { nxt = chunk_at(id + 1); issue_x(buf ? Xl0 : Xl1, nxt); load_z(nxt); }
-            multiply(Xb, cur);
+            if (more) {
+                if (++cb == col_blocks) { cb = 0; if (++rb == row_blocks) { rb = 0; ++ib; } }
+                nxt = chunk_of(ib, rb, cb);
+                issue_x(buf ? Xl0 : Xl1, nxt);
+                load_z(nxt);
+            }
+            multiply(Xb, cur.ni * cur.nr * G);
             if (!more) break;
             __syncthreads();                            // everybody is done with the deltas and the table of chunk `id`
             cur = nxt; buf ^= 1;
@@ -328,7 +411,7 @@ k_wgrad_mfma16(Wgrad16Args a)
 // Sum of the shares of one layer's partial gradient, in share order.
 __global__ void __launch_bounds__(256)
 k_wgrad_mfma16_share_sum(const float* __restrict__ scratch, float* __restrict__ partial, long long layer_params, long long n_params,
-                    long long w_off, int splits)
+                         long long w_off, int splits)
 {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int stack = blockIdx.y;
@@ -338,6 +421,7 @@ k_wgrad_mfma16_share_sum(const float* __restrict__ scratch, float* __restrict__ 
     for (int s = 1; s < splits; ++s) v += src[(long long)s * layer_params];
     partial[(long long)stack * n_params + w_off + i] = v;
 }
+
 
 namespace {
 
@@ -372,7 +456,7 @@ void wgrad16(const ConvArgs& c, float* scratch, hipStream_t s)
     a.splits = c.wgrad_shares16;
     const int waves_ci = w16_waves_ci(c.Cin);
     const int BCI = 32 * waves_ci;
-    const size_t lds = (size_t)2 * BCI * w16_row_bytes(waves_ci) + (size_t)kW16Groups * 64 * 16 + (size_t)kW16Groups * 4;
+    const size_t lds = (size_t)2 * BCI * w16_row_bytes(waves_ci) + (size_t)kW16Groups * 64 * 20 + (size_t)kW16Groups * 4;
     const int tiles = ((c.Cout + 63) / 64) * ((c.Cin + BCI - 1) / BCI);
     dim3 grid(tiles, a.splits, c.N * c.M), block(256);
 #define FTP_W16(WCI, HF) do { \
