@@ -25,6 +25,9 @@
  * gradient sum and the filter update do nothing.
  *
  * All functions return 0 on success or a negative ftp_status; nothing throws or aborts.
+ *
+ * A plan carries mutable host state (the event pool of the per-kernel timing, the second stream of the two-stream
+ * backward pass): use one plan from one host thread at a time.  Different plans are independent.
  */
 #ifndef FTP_H_
 #define FTP_H_
@@ -181,8 +184,9 @@ int ftp_sgd_step(const ftp_plan_t* plan, const float* wgrad_partials, void* cons
 
 /* Backward pass on two streams (Sec. 4.1: the delta back-propagation and the filter gradients of a layer both start
  * from the same delta map and do not depend on each other).  When enabled, ftp_backward runs each unit's filter
- * gradient on a second HIP stream of its own (default priority; a host object created on first use and owned by the
- * plan) beside the unit's delta back-propagation on the caller's stream, ordered with events so that no kernel
+ * gradient on a second HIP stream of its own (default priority; the stream and the events of one pass are host
+ * objects created by this call and owned by the plan, so that ftp_backward creates nothing and can be captured into a
+ * HIP graph with the switch on; if no device is usable yet, they are created by the first ftp_backward instead) beside the unit's delta back-propagation on the caller's stream, ordered with events so that no kernel
  * overwrites a map another one still reads; before ftp_backward returns, the caller's stream has been made to wait for
  * the second one, so the caller sees one stream as before.  Results are bit-identical either way.  Off by default
  * (on if the environment variable FTP_OVERLAP is 1 when the plan is created).  Kernels that run side by side share the

@@ -5,7 +5,9 @@ The paper describes the trade-off and leaves the search to a technical report th
 module does the search empirically on the GPU: the cost of a group (s, e) does not depend on how the other layers
 are grouped (groups meet at whole maps), so every contiguous group up to a maximum length is timed on its own as
 a one-group network, and a dynamic programme picks the partition of the layer list with the smallest total time.
-The result is then checked by timing the whole network with the chosen profile next to the uniform ones.
+That sum is a model (launch tails and cache state of neighbouring groups are not in it), so the partition it proposes
+is then timed as a whole network next to the uniform profiles and the configured one, and the search returns the
+fastest profile it has measured, never one it has only predicted.
 
     python -m paper_2409_09083_amd.autotune --config cfg4 [--max-group 8] [--steps 3]
 
@@ -55,22 +57,31 @@ def time_network(layers, batch, in_c, in_h, in_w, grid, group_ends, dtype, steps
     return ms
 
 
-def boundary_shapes(layers, in_c, in_h, in_w):
-    out = [(in_c, in_h, in_w)]
-    c, h, w = in_c, in_h, in_w
-    for ly in layers:
-        if ly.kind == 0:
-            c = ly.cout
-        else:
-            h, w = h // 2, w // 2
-        out.append((c, h, w))
+def boundary_shapes(cfg):
+    """(C, H, W) of every boundary 0..L, as the library's planner computes them (any stride, odd maps)."""
+    plan = B.ftp_plan(list(cfg.layers), cfg.batch, cfg.in_c, cfg.in_h, cfg.in_w, cfg.grid[0], cfg.grid[1],
+                      list(cfg.group_ends), B.FTP_BF16 if cfg.dtype == "bf16" else B.FTP_F32)
+    try:
+        return [B.ftp_plan_map_shape(plan, b) for b in range(len(cfg.layers) + 1)]
+    finally:
+        B.ftp_plan_destroy(plan)
+
+
+def candidate_profiles(L, searched, configured):
+    """Profiles that are timed as whole networks: the dynamic programme's, the configured one, the uniform ones."""
+    out = {"searched": tuple(searched), "as configured": tuple(configured)}
+    for g in sorted({1, 2, 4, 8, 16, L}):
+        if g <= L:
+            out["uniform %d" % g] = tuple(list(range(g, L, g)) + [L])
     return out
 
 
 def search(cfg, max_group=8, steps=3, log=None):
+    """Returns (group ends, ms per step, details): the fastest profile among those timed on the whole network.
+    details = {"predicted_ms", "group_cost", "profiles": {name: {"group_ends", "ms_per_step" | "error"}}, "chosen"}."""
     layers = list(cfg.layers)
     L = len(layers)
-    shapes = boundary_shapes(layers, cfg.in_c, cfg.in_h, cfg.in_w)
+    shapes = boundary_shapes(cfg)
     cost = {}
     for s0 in range(L):
         for e0 in range(s0 + 1, min(L, s0 + max_group) + 1):
@@ -81,8 +92,21 @@ def search(cfg, max_group=8, steps=3, log=None):
                 continue                 # e.g. a tile would own no pixel of this group's output
             if log:
                 log("group (%d, %d): %.3f ms" % (s0, e0, cost[(s0, e0)]))
-    ends, total = best_partition(cost, L, max_group)
-    return ends, total, cost
+    ends, predicted = best_partition(cost, L, max_group)
+    measured = {}
+    for name, pe in candidate_profiles(L, ends, cfg.group_ends).items():
+        try:
+            measured[name] = {"group_ends": list(pe),
+                              "ms_per_step": time_network(layers, cfg.batch, cfg.in_c, cfg.in_h, cfg.in_w, cfg.grid, pe,
+                                                          cfg.dtype, max(steps, 5), 2)}
+        except B.FtpError as e:
+            measured[name] = {"group_ends": list(pe), "error": str(e)}
+        if log:
+            log("profile %s %s: %s" % (name, list(pe), measured[name].get("ms_per_step", measured[name].get("error"))))
+    timed = {k: v for k, v in measured.items() if "ms_per_step" in v}
+    chosen = min(timed, key=lambda k: timed[k]["ms_per_step"])
+    details = {"predicted_ms": predicted, "group_cost": {"%d-%d" % k: v for k, v in cost.items()}, "profiles": measured, "chosen": chosen}
+    return tuple(timed[chosen]["group_ends"]), timed[chosen]["ms_per_step"], details
 
 
 def best_partition(cost, L, max_group):
@@ -113,22 +137,10 @@ def main():
     args = ap.parse_args()
     cfg = C.ALL[args.config]
     cfg = cfg() if callable(cfg) else cfg
-    L = len(cfg.layers)
-    ends, predicted, cost = search(cfg, args.max_group, args.steps, log=lambda m: print(m, file=sys.stderr, flush=True))
-    profiles = {"searched": ends, "as configured": tuple(cfg.group_ends)}
-    for g in (1, 2, 4, 8, 16):
-        if g <= L:
-            profiles["uniform %d" % g] = tuple(list(range(g, L, g)) + [L])
-    measured = {}
-    for name, pe in profiles.items():
-        try:
-            measured[name] = {"group_ends": list(pe),
-                              "ms_per_step": time_network(cfg.layers, cfg.batch, cfg.in_c, cfg.in_h, cfg.in_w, cfg.grid, pe,
-                                                          cfg.dtype, max(args.steps, 5), 2)}
-        except B.FtpError as e:
-            measured[name] = {"group_ends": list(pe), "error": str(e)}
+    ends, ms, details = search(cfg, args.max_group, args.steps, log=lambda m: print(m, file=sys.stderr, flush=True))
     print(json.dumps({"workload": cfg.name, "batch": cfg.batch, "grid": list(cfg.grid), "max_group": args.max_group,
-                      "predicted_ms": predicted, "profiles": measured}))
+                      "group_ends": list(ends), "ms_per_step": ms, "chosen": details["chosen"],
+                      "predicted_ms": details["predicted_ms"], "profiles": details["profiles"]}))
 
 
 if __name__ == "__main__":

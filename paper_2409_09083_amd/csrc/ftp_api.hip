@@ -188,14 +188,31 @@ int ftp_plan(const ftp_layer* layers, int32_t n_layers, int32_t batch, int32_t i
              ftp_dtype dtype, ftp_plan_t** out_plan)
 {
     const int rc = build_plan(layers, n_layers, batch, in_c, in_h, in_w, grid_rows, grid_cols, group_ends, n_groups, dtype, out_plan);
-    if (rc == FTP_OK) (*out_plan)->overlap.on = overlap_default();
+    if (rc == FTP_OK && overlap_default()) (void)ftp_set_overlap(*out_plan, 1);
     return rc;
 }
 
 int ftp_set_overlap(ftp_plan_t* plan, int32_t enable)
 {
     if (!plan) return FTP_EINVAL;
-    plan->overlap.on = enable != 0;
+    Overlap& ov = plan->overlap;
+    ov.on = enable != 0;
+    if (ov.on && !ov.aux) {
+        // The second stream and the events of one backward pass are created here, so that ftp_backward creates no
+        // object (it may run under stream capture).  Without a usable device (a host that only plans) this is put
+        // off to the first ftp_backward.
+        hipStream_t st = nullptr;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) == hipSuccess) {
+            ov.aux = st;
+            const size_t want = 3 * plan->p.units.size() + 4;
+            while (ov.events.size() < want) {
+                hipEvent_t e = nullptr;
+                if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) break;
+                ov.events.push_back(e);
+            }
+        }
+        (void)hipGetLastError();
+    }
     return FTP_OK;
 }
 

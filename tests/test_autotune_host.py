@@ -3,7 +3,8 @@ import itertools
 
 import pytest
 
-from paper_2409_09083_amd.autotune import best_partition, boundary_shapes
+from paper_2409_09083_amd.autotune import best_partition, boundary_shapes, candidate_profiles
+from ftp_synth.configs import Config
 from ftp_synth.configs import conv, pool
 
 
@@ -51,6 +52,14 @@ def test_additive_costs_prefer_the_cheaper_side():
         best_partition({(0, 1): 1.0}, 2, 2)
 
 
-def test_boundary_shapes():
-    layers = (conv(3, 8), pool(8), conv(8, 16, 1))
-    assert boundary_shapes(layers, 3, 32, 48) == [(3, 32, 48), (8, 32, 48), (8, 16, 24), (16, 16, 24)]
+def test_boundary_shapes_come_from_the_planner():
+    # strides, 5x5 / 7x7 kernels and a pool on an odd map: the shapes are the library's, not a re-derivation
+    layers = (conv(3, 8, 7, stride=2), pool(8), conv(8, 16, 1), conv(16, 8, 3, stride=2), pool(8))
+    cfg = Config("shapes", 1, 3, 75, 62, layers, (1, 2), (5,))
+    assert boundary_shapes(cfg) == [(3, 75, 62), (8, 38, 31), (8, 19, 15), (16, 19, 15), (8, 10, 8), (8, 5, 4)]
+
+
+def test_candidates_include_every_uniform_profile():
+    c = candidate_profiles(6, (2, 6), (3, 6))
+    assert c["searched"] == (2, 6) and c["as configured"] == (3, 6)
+    assert c["uniform 1"] == (1, 2, 3, 4, 5, 6) and c["uniform 4"] == (4, 6) and c["uniform 6"] == (6,)

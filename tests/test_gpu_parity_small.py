@@ -132,14 +132,18 @@ def test_deterministic_bitwise(oracle):
     b["session"].close()
 
 
-def test_step_under_graph_capture(oracle):
+@pytest.mark.parametrize("overlap", [False, True])
+def test_step_under_graph_capture(oracle, overlap):
     """The three device calls allocate nothing and use no host synchronisation, so a step can be captured in a HIP
-    graph: every replay (with eager work and synchronisations in between) reproduces the eager results bit for bit."""
+    graph: every replay (with eager work and synchronisations in between) reproduces the eager results bit for bit.
+    With the two-stream backward pass switched on the second stream joins the capture through its events (the stream
+    and the events exist before the capture starts: ftp_set_overlap creates them)."""
     import torch
     cfg = _mk("pools", (3, 2), "split")
     x, ws, bs, dy = C.make_tensors(cfg)
     s = P.make_session(cfg, x.shape[0])
     s.load(x=x, weights=ws, dy=dy)
+    s.set_overlap(overlap)
     s.step()
     torch.cuda.synchronize()
     ref = [s.y.clone(), s.dx.clone(), s.wgrad.clone()]
