@@ -41,6 +41,21 @@ __device__ __forceinline__ T* at(const View& v, int stack, int ti, int tj, int n
            (long long)(y - v.y0[ti]) * v.pitch + (x - v.x0[tj]);
 }
 
+// The dispatcher hands the workgroups of a launch to the 8 XCDs round-robin by linear index, and every XCD has an L2 of
+// its own.  Kernels in which a group of `gx` workgroups reads the same maps launch a 1-D grid of
+// 8 * gx * ceil(groups / 8) workgroups and number them so that a group's workgroups run on one XCD, one after the
+// other, while consecutive groups go to different XCDs (so uneven groups still spread over the chip):
+// XCD x = index % 8 works through the groups x, x + 8, x + 16, ...  Returns false for the padding (group >= groups).
+__device__ __forceinline__ bool xcd_order(int groups, int gx, int& group, int& block)
+{
+    const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3;
+    const int round = slot / gx;
+    block = slot - round * gx;
+    group = xcd + 8 * round;
+    return group < groups;
+}
+inline unsigned xcd_grid(int groups, int gx) { return (unsigned)(8 * gx * ((groups + 7) / 8)); }
+
 __device__ __forceinline__ float leaky(float z, float slope) { return z > 0.0f ? z : slope * z; }
 
 // Packed activation signs of a boundary (whole map): bit c % 32 of the 32-bit word [image][c / 32][y][x] is set

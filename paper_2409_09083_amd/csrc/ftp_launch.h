@@ -101,6 +101,7 @@ struct MfmaWgradArgs {
     long long n_params, w_off;
     int Cin, Cout, Hc, Wc;
     int splits;                                     // batch shares per stack
+    int gx, stacks;                                 // blocks per (stack, share); stacks (the grid is 1-D, see xcd_order)
     int PK;                                         // pixels staged per step
     float slope;
     int M, batch;

@@ -11,6 +11,10 @@
 // only if it is the window's winner; 2 = stride-2 convolution: the rectangle is the stack's owned part of the
 // *input* map and pixel (y, x) carries delta (y/2, x/2) if both are even, else zero (the filter gradient of a strided
 // convolution is the stride-1 one of the deltas with zeros in between; three quarters of the products are zero).
+// fp32 maps: the patch of X does not pass through registers.  It goes HBM -> LDS with buffer_load_dword ... lds, one
+// element per lane, channel-major ([ci][patch position], odd channel stride), positions outside the map from
+// out-of-range offsets (= 0); the deltas still go through registers (masking, pool routing), loaded during the
+// previous chunk's multiply.
 // 16-bit (bfloat) maps multiply with v_mfma_f32_32x32x8_bf16_1k: 8 pixels per instruction (lanes 0-31 the first 4,
 // lanes 32-63 the next 4), counted through the chunk's pixel list; a small table in LDS gives each pixel's patch
 // position.  The staged values are widened bfloats, so taking their upper halves back is exact.
@@ -32,26 +36,31 @@ k_wgrad_mfma(MfmaWgradArgs a)
 {
     constexpr bool POOL = HALF == 1;
     constexpr bool BF = sizeof(T) == 2;
+    constexpr bool DL = !BF;                           // fp32: the patch is loaded straight into LDS
     constexpr int WAVES_K = 4 / (WAVES_CO * WAVES_CI);
     constexpr int KK = K * K, P = K / 2, NTAP = TROWS * K;
     constexpr int BCO = 32 * WAVES_CO, BCI = 32 * WAVES_CI;
     constexpr int ZP = BCO + 1, XP = BCI + 1;          // odd strides: conflict-free transposing writes
     constexpr int NZ = BCO / 4, NX = BCI / 4;          // channels each wavefront stages
     constexpr int ZPOS = kWgradZPos, XPOS = wgrad_xpos(P), XPASS = XPOS / 64;
+    constexpr int XS = XPOS + 1;                       // DL: dwords between the patch rows of two channels
 
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: keeps the loop control scalar
     const int wave_co = wave % WAVES_CO, wave_ci = (wave / WAVES_CO) % WAVES_CI, wave_k = wave / (WAVES_CO * WAVES_CI);
     const int hi = lane >> 5, l32 = lane & 31;
-    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
+    // (block, share, stack), block fastest, in XCD order: the blocks of one stack and share read the same maps
+    int vgroup, bx;
+    if (!xcd_order(a.splits * a.stacks, a.gx, vgroup, bx)) return;
+    const int split = vgroup % a.splits;
+    const int stack = vgroup / a.splits, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.own.x0[tj], x1 = a.own.x1[tj], y0 = a.own.y0[ti], y1 = a.own.y1[ti];
     const int rw = x1 - x0 + 1, rh = y1 - y0 + 1;
     const int tiles_ci = (a.Cin + BCI - 1) / BCI, tiles = tiles_ci * ((a.Cout + BCO - 1) / BCO);
-    const int tile = TROWS == K ? blockIdx.x : blockIdx.x % tiles;
-    const int trow0 = TROWS == K ? 0 : (blockIdx.x / tiles) * TROWS;       // first filter row of this workgroup
+    const int tile = TROWS == K ? bx : bx % tiles;
+    const int trow0 = TROWS == K ? 0 : (bx / tiles) * TROWS;       // first filter row of this workgroup
     const int co0 = (tile / tiles_ci) * BCO, ci0 = (tile % tiles_ci) * BCI;
-    const int split = blockIdx.y;
 
     // Chunk geometry of this stack: TI images x TR rows x TC columns of the owned rectangle, at most ZPOS
     // pixels (rows padded to an even length TCp) and at most XPOS patch positions.  The stack's chunk list
@@ -60,7 +69,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
     const int col_blocks = wc.col_blocks, TC = wc.TC, TCp = wc.TCp, PW = wc.PW, TR = wc.TR, row_blocks = wc.row_blocks, TI = wc.TI;
     const int id0 = (int)((long long)split * wc.total / a.splits), id1 = (int)((long long)(split + 1) * wc.total / a.splits);
     float* Zl = lds;                                   // [pixel][ZP]
-    float* Xl = lds + ZPOS * ZP;                       // [patch position][XP]
+    float* Xl = lds + ZPOS * ZP;                       // [patch position][XP]; DL: [ci][XS]
     int* posl = (int*)(Xl + XPOS * XP);                // bfloat path: [pixel] -> XP * patch position of its tap (0, 0)
 
     v16f acc[NTAP];
@@ -87,7 +96,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
     // window.  xinfo: per pass bit 0 position exists, bit 1 inside the map.
     // zinfo bit 4: the position lies in the pixel list rounded up to a multiple of 8 (bfloat path; zero if it does not
     // exist); zpos: XP * patch position of the pixel.
-    uint32_t zm[NZ]; float zg[NZ]; float xg[XPASS][NX];
+    uint32_t zm[NZ]; float zg[NZ]; float xg[DL ? 1 : XPASS][DL ? 1 : NX];
     int zinfo = 0, xinfo = 0, zpos = 0;
 
     auto load = [&](const Chunk& c) {
@@ -111,7 +120,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
                 zg[k] = ld(gp + (long long)co * a.din.cs);
             }
         }
-        {
+        if constexpr (!DL) {
             const int nph = c.nr + 2 * P;
             const int npos = c.ni * nph * PW;
             xinfo = 0;
@@ -139,7 +148,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
     };
 
     auto store = [&]() {
-        __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): every load of the chunk has landed
+        if (!DL) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): every load of the chunk has landed
         if (zinfo & (BF ? 16 : 1)) {
             float* zdst = Zl + lane * ZP;
             const int code = (zinfo >> 2) & 3;
@@ -154,6 +163,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
             }
             if (BF && wave == 0) posl[lane] = zpos;
         }
+        if constexpr (!DL)
 #pragma unroll
         for (int pass = 0; pass < XPASS; ++pass) {
             const int f = xinfo >> (2 * pass);
@@ -165,6 +175,49 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     xdst[ch] = ((f & 2) && ci0 + ch < a.Cin) ? xg[pass][k] : 0.0f;
                 }
             }
+        }
+    };
+
+    // DL: one chunk's patch, HBM -> LDS.  Lane -> patch position (64 to an instruction), wavefront -> every fourth
+    // channel.  Returns the number of load instructions this wavefront issued.
+    auto issue_x = [&](const Chunk& c) -> int {
+        int issued = 0;
+        if constexpr (DL) {
+            const int nph = c.nr + 2 * P, npos = c.ni * nph * PW;
+            const T* base = (const T*)a.in.p + (long long)stack * a.in.ss + (long long)c.n0 * a.in.ns;
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, (short)0, 0x7FFFFFFF, 0x00020000);
+#pragma unroll
+            for (int pass = 0; pass < XPASS; ++pass) {
+                if (pass * 64 < npos) {
+                    const int p = lane + 64 * pass;
+                    const int prow = p / PW, xc = p - prow * PW;
+                    const int il = prow / nph, r = prow - il * nph;
+                    const int gy = c.yb - P + r, gx = c.xb - P + xc;
+                    const bool inside = p < npos && xc < c.nc + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
+                    const unsigned vo = inside ? 4u * (unsigned)(il * (int)a.in.ns + (gy - a.in.y0[ti]) * a.in.pitch + (gx - a.in.x0[tj])) : 0x80000000u;
+#pragma unroll
+                    for (int k = 0; k < NX; ++k) {
+                        const int ch = wave + 4 * k;
+                        const unsigned v = ci0 + ch < a.Cin ? vo : 0x80000000u;
+                        const unsigned so = 4u * (unsigned)((ci0 + ch) * (int)a.in.cs);
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(Xl + ch * XS + pass * 64), 4, v, so, 0, 0);
+                    }
+                    issued += NX;
+                }
+            }
+        }
+        return issued;
+    };
+    // waits until at most `n` of this wavefront's loads are outstanding (loads return in order)
+    auto wait_vm = [&](int n) {
+        switch (n) {
+            case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+            case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+            case 16: __builtin_amdgcn_s_waitcnt(0x4F70); break;
+            case 24: __builtin_amdgcn_s_waitcnt(0x4F78); break;
+            case 32: __builtin_amdgcn_s_waitcnt(0x8F70); break;
+            case 48: __builtin_amdgcn_s_waitcnt(0xCF70); break;
+            default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
         }
     };
 
@@ -196,14 +249,14 @@ k_wgrad_mfma(MfmaWgradArgs a)
         for (int rr = 0; rr < nrows; ++rr) {
             const int il = rr / c.nr, r = rr - il * c.nr;
             const float* zrow = Zl + (rr * TCp + hi) * ZP + co_l;
-            const float* xrow = Xl + ((il * nph + r) * PW + hi) * XP + ci_l;
+            const float* xrow = DL ? Xl + ci_l * XS + (il * nph + r) * PW + hi : Xl + ((il * nph + r) * PW + hi) * XP + ci_l;
             // wavefronts that share a (co, ci) tile take alternate pixel pairs of every row
             for (int xp = 2 * wave_k; xp < ncp; xp += 2 * WAVES_K) {
                 const float av = zrow[xp * ZP];
 #pragma unroll
                 for (int t = 0; t < NTAP; ++t) {
                     if (TROWS != K && trow0 + t / K >= K) break;           // (the last part of a split filter may be short)
-                    const float bv = xrow[((trow0 + t / K) * PW + xp + (t % K)) * XP];
+                    const float bv = xrow[((trow0 + t / K) * PW + xp + (t % K)) * (DL ? 1 : XP)];
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t], 0, 0, 0);
                 }
             }
@@ -219,7 +272,15 @@ k_wgrad_mfma(MfmaWgradArgs a)
         load(cur);
         for (;;) {
             __syncthreads();                            // the previous chunk has been consumed
-            store();
+            if constexpr (DL) {
+                // the patch loads start first; the deltas (loaded during the previous multiply) are stored while they fly
+                const int nx = issue_x(cur);
+                wait_vm(nx);
+                store();
+                __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): this wavefront's part of the patch has landed
+            } else {
+                store();
+            }
             __syncthreads();
             if (++cb == col_blocks) { cb = 0; if (++rb == row_blocks) { rb = 0; ++ib; } }
             const bool more = ++id < id1;
@@ -287,6 +348,8 @@ bool mfma_wgrad_eligible(const ConvArgs& c)
 {
     if (c.pooled && (c.S != 1 || c.K > 3)) return false;
     if (c.S == 2 && c.K > 3) return false;
+    // (the fp32 patch loads address one stack's images with 32-bit byte offsets; a chunk spans at most 64 images)
+    if (!c.bf16 && 4.0 * (64.0 * (double)c.in.ns + (double)c.Cin * (double)c.in.cs) >= 2.0e9) return false;
     return !c.has_bias && c.Cout >= 32 && c.Cin >= 16;
 }
 
@@ -306,10 +369,13 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     const int waves_co = (c.Cout <= 32 && c.K == 3 && waves_ci == 1) ? 1 : 2;
     const int BCO = 32 * waves_co, BCI = 32 * waves_ci;
     // (+ the bfloat path's table of patch positions)
-    const size_t lds = ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1) + kWgradZPos) * sizeof(float);
+    // (the fp32 patch layout is [ci][positions + 1], the bfloat one [position][ci + 1] + the table of patch positions)
+    const size_t lds = c.bf16 ? ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1) + kWgradZPos) * sizeof(float)
+                              : ((size_t)kWgradZPos * (BCO + 1) + (size_t)BCI * (wgrad_xpos(c.K / 2) + 1)) * sizeof(float);
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
     const int parts = c.K == 5 ? 3 : c.K == 7 ? 7 : 1;                 // filter rows 2 + 2 + 1, or one at a time
-    dim3 grid(tiles * parts, a.splits, c.N * c.M), block(256);
+    a.gx = tiles * parts; a.stacks = c.N * c.M;
+    dim3 grid(xcd_grid(a.splits * a.stacks, a.gx)), block(256);
     // more than 64 KB of dynamic LDS has to be granted per kernel, once
 #define FTP_WG1(TT, TN, KK, WCO, WCI, HF, TR) do { \
         static bool granted = false; \

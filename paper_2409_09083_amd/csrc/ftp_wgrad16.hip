@@ -37,6 +37,7 @@ struct Wgrad16Args {
     long long n_params, w_off;
     int Cin, Cout, Hc, Wc;                          // map extent at the convolution (stride 1: input = output)
     int splits, M, batch;
+    int gx, stacks;                                 // blocks per (stack, share); stacks (the grid is 1-D, see xcd_order)
 };
 
 #define FTP_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -69,12 +70,15 @@ k_wgrad_mfma16(Wgrad16Args a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_co = wave % WAVES_CO, wave_ci = (wave / WAVES_CO) % WAVES_CI, wave_k = wave / (WAVES_CO * WAVES_CI);
     const int hi = lane >> 5, l32 = lane & 31;
-    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
+    // (block, share, stack), block fastest, in XCD order: the blocks of one stack and share read the same maps
+    int vgroup, bx;
+    if (!xcd_order(a.splits * a.stacks, a.gx, vgroup, bx)) return;
+    const int split = vgroup % a.splits;
+    const int stack = vgroup / a.splits, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.own.x0[tj], x1 = a.own.x1[tj], y0 = a.own.y0[ti], y1 = a.own.y1[ti];
     const int rw = x1 - x0 + 1, rh = y1 - y0 + 1;
     const int tiles_ci = (a.Cin + BCI - 1) / BCI;
-    const int co0 = (blockIdx.x / tiles_ci) * BCO, ci0 = (blockIdx.x % tiles_ci) * BCI;
-    const int split = blockIdx.y;
+    const int co0 = (bx / tiles_ci) * BCO, ci0 = (bx % tiles_ci) * BCI;
 
     // what the per-chunk code needs of the argument block, once
     const int Hc = a.Hc, Wc = a.Wc, Cin = a.Cin, Cout = a.Cout, batch = a.batch;
@@ -458,7 +462,8 @@ void wgrad16(const ConvArgs& c, float* scratch, hipStream_t s)
     const int BCI = 32 * waves_ci;
     const size_t lds = (size_t)2 * BCI * w16_row_bytes(waves_ci) + (size_t)kW16Groups * 64 * 20 + (size_t)kW16Groups * 4;
     const int tiles = ((c.Cout + 63) / 64) * ((c.Cin + BCI - 1) / BCI);
-    dim3 grid(tiles, a.splits, c.N * c.M), block(256);
+    a.gx = tiles; a.stacks = c.N * c.M;
+    dim3 grid(xcd_grid(a.splits * a.stacks, a.gx)), block(256);
 #define FTP_W16(WCI, HF) do { \
         static bool granted = false; \
         if (!granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_mfma16<WCI, HF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); granted = true; } \
