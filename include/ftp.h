@@ -199,7 +199,7 @@ int ftp_set_overlap(ftp_plan_t* plan, int32_t enable);
  * ftp_profile(plan, 0) stops.  ftp_profile_read waits for the recorded events and returns one
  * record per (pass, layer): number of launches, their summed duration, and the algorithmic
  * work of one launch - the FLOPs and HBM bytes of the untiled layer (each map read or written
- * once, recomputed halos not credited).  `count` receives the number of records available;
+ * once, recomputed halos not credited) - and, beside it, the FLOPs the launch really executed.  `count` receives the number of records available;
  * at most `capacity` are written to `out` (host). */
 typedef enum {
     FTP_PASS_CONV_FWD = 0, FTP_PASS_CONV_BWD_DATA = 1, FTP_PASS_WGRAD = 2, FTP_PASS_REDUCE = 3,
@@ -211,6 +211,9 @@ typedef struct {
     int32_t pass, layer, launches, reserved;   /* layer = primitive layer index, -1 for the reduction */
     double total_ms, flops_per_launch, bytes_per_launch;
     char kernel[96];                           /* name of the kernel the launches ran */
+    double executed_flops_per_launch;          /* the same FLOPs over the rectangles the stacks really evaluate: forward
+                                                  and delta passes recompute the halo inside a group (Sec. 4.2), the
+                                                  filter gradient runs over owned pixels only (equal to flops_per_launch) */
 } ftp_kernel_time;
 int ftp_profile(ftp_plan_t* plan, int32_t enable);
 int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, int32_t* count);

@@ -27,7 +27,8 @@ class ftp_layer(ctypes.Structure):
 class ftp_kernel_time(ctypes.Structure):
     _fields_ = [("pass_", ctypes.c_int32), ("layer", ctypes.c_int32), ("launches", ctypes.c_int32),
                 ("reserved", ctypes.c_int32), ("total_ms", ctypes.c_double), ("flops_per_launch", ctypes.c_double),
-                ("bytes_per_launch", ctypes.c_double), ("kernel", ctypes.c_char * 96)]
+                ("bytes_per_launch", ctypes.c_double), ("kernel", ctypes.c_char * 96),
+                ("executed_flops_per_launch", ctypes.c_double)]
 
 
 PASS_NAMES = {0: "conv_fwd", 1: "conv_bwd_data", 2: "wgrad", 3: "reduce", 4: "pool_fwd", 5: "pool_bwd", 6: "scale_dy", 7: "update"}
@@ -206,7 +207,7 @@ def ftp_profile_read(plan, capacity=256):
     _check(_lib.ftp_profile_read(plan, out, capacity, ctypes.byref(n)), "ftp_profile_read")
     return [{"pass": PASS_NAMES[r.pass_], "layer": r.layer, "launches": r.launches, "total_ms": r.total_ms,
              "flops_per_launch": r.flops_per_launch, "bytes_per_launch": r.bytes_per_launch,
-             "kernel": r.kernel.decode()}
+             "kernel": r.kernel.decode(), "executed_flops_per_launch": r.executed_flops_per_launch}
             for r in out[:min(n.value, capacity)]]
 
 

@@ -515,7 +515,7 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
         const Profiler::Agg& g = pr.agg[i];
         ftp_kernel_time t;
         t.pass = g.pass; t.layer = g.layer; t.launches = g.launches; t.reserved = 0; t.total_ms = g.ms;
-        t.flops_per_launch = 0; t.bytes_per_launch = 0;
+        t.flops_per_launch = 0; t.bytes_per_launch = 0; t.executed_flops_per_launch = 0;
         std::memset(t.kernel, 0, sizeof(t.kernel));
         if (g.kernel) std::strncpy(t.kernel, g.kernel, sizeof(t.kernel) - 1);
         if (g.pass == FTP_PASS_REDUCE) {
@@ -538,6 +538,16 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
             } else if (u->kind == UNIT_CONV) {
                 const double wel = (double)ly.cout * ly.cin * ly.k * ly.k;
                 t.flops_per_launch = 2.0 * wel * B * p.H[g.layer + 1] * p.W[g.layer + 1];
+                {
+                    // rectangles the stacks evaluate: forward F at the convolution output, delta B at its input
+                    const GroupRects& gr = p.groups[u->group];
+                    const int kind = g.pass == FTP_PASS_CONV_FWD ? FTP_RECT_FWD : g.pass == FTP_PASS_CONV_BWD_DATA ? FTP_RECT_BWD : FTP_RECT_OWN;
+                    const int lb = g.pass == FTP_PASS_CONV_BWD_DATA ? g.layer : g.layer + 1;
+                    double sx = 0, sy = 0;
+                    for (int t2 = 0; t2 < p.M; ++t2) sx += seg_len(gr.at(kind, lb, 0, t2));
+                    for (int t2 = 0; t2 < p.N; ++t2) sy += seg_len(gr.at(kind, lb, 1, t2));
+                    t.executed_flops_per_launch = 2.0 * wel * B * sx * sy;
+                }
                 if (g.pass == FTP_PASS_CONV_FWD) t.bytes_per_launch = (in_el + out_el + wel) * es + out_el * has_arg;
                 else if (g.pass == FTP_PASS_CONV_BWD_DATA) t.bytes_per_launch = (in_el + 2.0 * out_el + wel) * es + out_el * has_arg;
                 else t.bytes_per_launch = (in_el + 2.0 * out_el) * es + out_el * has_arg + stacks * wel * 4.0;

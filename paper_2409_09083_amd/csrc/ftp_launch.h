@@ -75,6 +75,7 @@ struct MfmaConvArgs {
     int C, Mtot;                                    // reduction channels, output channels
     int Hc, Wc;                                     // map extent at the convolution
     int TC, tiles_x, tiles_r;                       // column block (when tiles_x > 1), column / row-run tile counts
+    int mblocks, stacks, xcd_groups;                // output-channel blocks; stacks; 1: workgroups in XCD order (the grid is 1-D, see xcd_order)
     int cap;                                        // pixels (pool windows) per tile
     int cs;                                         // LDS channel stride of the patch = largest patch of any stack
     float slope;

@@ -282,11 +282,22 @@ k_conv_mfma_dl(MfmaConvArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
     const int hi = lane >> 5, l32 = lane & 31;
-    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
+    // (tile, channel block, stack), tile fastest.  Where the launch says so the workgroups are renumbered in XCD order:
+    // the tiles of one stack and channel block then run on one XCD, and as the channel-block count divides 8, an XCD
+    // only ever meets one channel block's slice of the filter (with all blocks on every XCD the filters of the
+    // 256 -> 512 layers do not stay in a 4 MB L2).
+    int vgroup, vtile;
+    const int ntiles = a.tiles_x * a.tiles_r;
+    if (a.xcd_groups) {
+        if (!xcd_order(a.mblocks * a.stacks, ntiles, vgroup, vtile)) return;
+    } else {
+        vgroup = (int)blockIdx.x / ntiles; vtile = (int)blockIdx.x - vgroup * ntiles;
+    }
+    const int stack = vgroup / a.mblocks, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.rect.x0[tj], x1 = a.rect.x1[tj], y0 = a.rect.y0[ti], y1 = a.rect.y1[ti];
-    const TileGeom g = tile_geom<S, P>(a, x0, x1, y0, y1, blockIdx.x);
+    const TileGeom g = tile_geom<S, P>(a, x0, x1, y0, y1, vtile);
     if (g.empty) return;
-    const int m0 = blockIdx.y * BM;
+    const int m0 = (vgroup % a.mblocks) * BM;
     const int PW = g.PW, CS = a.cs;                    // CS: whole 64-position blocks cover every patch
 
     int baseB[NT];
@@ -630,7 +641,13 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     if (POOL_IN && DELTA_IN && (double)td.max_img * (double)a.mask.ns >= 5.0e8) return 1;
     if (!offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img, K)) return 1;
     a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = (td.cs + 63) & ~63;
-    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN, STRIDE>(a, sh, dim3(a.tiles_x * a.tiles_r, (a.Mtot + sh.BM - 1) / sh.BM, c.N * c.M), s);
+    a.mblocks = (a.Mtot + sh.BM - 1) / sh.BM; a.stacks = c.N * c.M;
+    // XCD order pays where several channel blocks compete for the L2 and the groups spread evenly over the 8 XCDs;
+    // with one channel block the plain order (neighbouring tiles on different XCDs) balances better
+    const int groups = a.mblocks * a.stacks, ntiles = a.tiles_x * a.tiles_r;
+    a.xcd_groups = (a.mblocks >= 2 && 8 % a.mblocks == 0 && groups % 8 == 0) ? 1 : 0;
+    const unsigned nwg = a.xcd_groups ? xcd_grid(groups, ntiles) : (unsigned)(groups * ntiles);
+    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN, STRIDE>(a, sh, dim3(nwg), s);
     return 0;
 }
 
