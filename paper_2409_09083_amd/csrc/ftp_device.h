@@ -56,6 +56,15 @@ __device__ __forceinline__ bool xcd_order(int groups, int gx, int& group, int& b
 }
 inline unsigned xcd_grid(int groups, int gx) { return (unsigned)(8 * gx * ((groups + 7) / 8)); }
 
+// Value of lane (lane ^ X) for X = 1, 2, 3: an exchange inside a quad of lanes, done by the vector ALU's data-parallel
+// primitives (quad_perm), not by a round trip through the LDS crossbar.
+template <int X>
+__device__ __forceinline__ float quad_xor(float v)
+{
+    constexpr int ctrl = X == 1 ? 0xB1 : X == 2 ? 0x4E : 0x1B;          // quad_perm [1,0,3,2] / [2,3,0,1] / [3,2,1,0]
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), ctrl, 0xF, 0xF, true));
+}
+
 __device__ __forceinline__ float leaky(float z, float slope) { return z > 0.0f ? z : slope * z; }
 
 // Packed activation signs of a boundary (whole map): bit c % 32 of the 32-bit word [image][c / 32][y][x] is set
