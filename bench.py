@@ -224,6 +224,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (batch-size sweeps; 0 = as configured)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="leave out the config-5 grouping sweep (cfg5_sweep)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the legs that follow the timed region (two-stream backward, forward only): profiler "
+                         "runs then see the timed region's launches only")
     ap.add_argument("--with-update", action="store_true",
                     help="close every step with the fused gradient sum + filter update (lr 0) instead of the plain gradient sum")
     ap.add_argument("--overlap", action="store_true",
@@ -250,7 +253,7 @@ def main():
         probe[1].copy_(probe[0])            # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del probe
-    r = run_workload(cfg, args.steps, args.warmup, args.with_update, args.overlap, args.per_kernel)
+    r = run_workload(cfg, args.steps, args.warmup, args.with_update, args.overlap, args.per_kernel, extras=not args.no_extras)
     out = {
         "metric": "train images/sec (fwd+bwd, fused-tile early layers)",
         "value": r.pop("value"), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
