@@ -546,7 +546,9 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
                     double sx = 0, sy = 0;
                     for (int t2 = 0; t2 < p.M; ++t2) sx += seg_len(gr.at(kind, lb, 0, t2));
                     for (int t2 = 0; t2 < p.N; ++t2) sy += seg_len(gr.at(kind, lb, 1, t2));
-                    t.executed_flops_per_launch = 2.0 * wel * B * sx * sy;
+                    // (delta pass of a strided convolution: a pixel of the input rectangle meets 1 / S^2 of the taps)
+                    const double per_px = g.pass == FTP_PASS_CONV_BWD_DATA ? 1.0 / ((double)ly.stride * ly.stride) : 1.0;
+                    t.executed_flops_per_launch = 2.0 * wel * B * sx * sy * per_px;
                 }
                 if (g.pass == FTP_PASS_CONV_FWD) t.bytes_per_launch = (in_el + out_el + wel) * es + out_el * has_arg;
                 else if (g.pass == FTP_PASS_CONV_BWD_DATA) t.bytes_per_launch = (in_el + 2.0 * out_el + wel) * es + out_el * has_arg;
