@@ -10,9 +10,10 @@
 // and the filter slice of a few channels x K*K taps sit in LDS; v_mfma_f32_32x32x2_f32 reads both from there.
 // MFMA lane layout (64 lanes): A[m = lane%32][k = lane/32], B[k = lane/32][n = lane%32],
 // D[m = 8*(i/4) + 4*(lane/32) + i%4][n = lane%32] for accumulator register i of 16.
-// With 16-bit (bfloat) maps and filters the stride-1 1x1 / 3x3 layers multiply with v_mfma_f32_32x32x8_bf16_1k
-// instead (A[m][k = 4*(lane/32) + j], B[k = 4*(lane/32) + j][n], j < 4, same D): products of two bfloats are exact in
-// fp32 and the sums are accumulated in fp32, so this is the same arithmetic at eight times the rate.
+// With 16-bit (bfloat) maps and filters the stride-1 1x1 / 3x3 layers multiply with v_mfma_f32_32x32x16_bf16
+// instead (A[m][k = 8*(lane/32) + j], B[k = 8*(lane/32) + j][n], j < 8, same D): products of two bfloats are exact in
+// fp32 and the sums are accumulated in fp32, so this is the same arithmetic at sixteen times the rate (the older
+// 32x32x8 form runs at half of that on this chip).
 #include "ftp_device.h"
 #include "ftp_launch.h"
 #include <algorithm>
@@ -23,6 +24,7 @@
 namespace ftp {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 
 // Filter relayout: OIHW -> [tap][reduction channel][output channel], so that a stage's slice is a set of
@@ -42,32 +44,32 @@ k_prep_filter(const T* __restrict__ w, float* __restrict__ wt_fwd, float* __rest
     if (wt_bwd) wt_bwd[((long long)(KK - 1 - t) * Cout + co) * Cin + ci] = v;
 }
 
-// Filter relayout for the bfloat matrix-core path: [tap][quad of 4 reduction channels][output channel][4 bfloats],
-// taps padded to an even count with zeros (one instruction multiplies 4 channels of two taps, or 8 channels of
-// one), reduction channels padded to whole quads with zeros.  fwd: reduction = ci, output = co; bwd: reduction = co,
+// Filter relayout for the bfloat matrix-core path: [tap][group of 8 reduction channels][output channel][8 bfloats],
+// taps padded to an even count with zeros (one instruction multiplies 8 channels of two taps, or 16 channels of
+// one), reduction channels padded to whole groups with zeros.  fwd: reduction = ci, output = co; bwd: reduction = co,
 // output = ci, taps rotated by 180 degrees.
 __global__ void __launch_bounds__(256)
 k_prep_filter16(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt_fwd, bf16_t* __restrict__ wt_bwd, int Cout, int Cin, int KK, int taps)
 {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int j = (int)(i & 3);
+    const int j = (int)(i & 7);
     if (wt_fwd) {
-        const int C4 = (Cin + 3) / 4;
-        const long long n = (long long)taps * C4 * Cout;
-        if ((i >> 2) < n) {
-            const long long e = i >> 2;
-            const int co = (int)(e % Cout), q = (int)((e / Cout) % C4), t = (int)(e / ((long long)Cout * C4));
-            const int ci = 4 * q + j;
+        const int C8 = (Cin + 7) / 8;
+        const long long n = (long long)taps * C8 * Cout;
+        if ((i >> 3) < n) {
+            const long long e = i >> 3;
+            const int co = (int)(e % Cout), q = (int)((e / Cout) % C8), t = (int)(e / ((long long)Cout * C8));
+            const int ci = 8 * q + j;
             wt_fwd[i] = (t < KK && ci < Cin) ? w[((long long)co * Cin + ci) * KK + t] : (bf16_t)0;
         }
     }
     if (wt_bwd) {
-        const int C4 = (Cout + 3) / 4;
-        const long long n = (long long)taps * C4 * Cin;
-        if ((i >> 2) < n) {
-            const long long e = i >> 2;
-            const int ci = (int)(e % Cin), q = (int)((e / Cin) % C4), t = (int)(e / ((long long)Cin * C4));
-            const int co = 4 * q + j;
+        const int C8 = (Cout + 7) / 8;
+        const long long n = (long long)taps * C8 * Cin;
+        if ((i >> 3) < n) {
+            const long long e = i >> 3;
+            const int ci = (int)(e % Cin), q = (int)((e / Cin) % C8), t = (int)(e / ((long long)Cin * C8));
+            const int co = 8 * q + j;
             wt_bwd[i] = (t < KK && co < Cout) ? w[((long long)co * Cin + ci) * KK + (KK - 1 - t)] : (bf16_t)0;
         }
     }
@@ -238,7 +240,8 @@ constexpr unsigned kBufRecords = 0x7FFFFFFFu;
 // bit of the result, does not depend on which shape the launch heuristics pick (they look at the batch size).
 // (5x5 and 7x7 filters take 2 channels per stage so that a slice of all taps still fits; a strided forward pass
 // reads a patch four times the size of its tile.)
-__host__ __device__ constexpr int conv_dl_stage_channels(int K, bool strided_fwd) { return K >= 5 ? 2 : (K == 1 && !strided_fwd) ? 16 : 4; }
+// (the bfloat matrix-core path takes 8 channels of a 3x3 filter per stage: one instruction multiplies 8 of them)
+__host__ __device__ constexpr int conv_dl_stage_channels(int K, bool strided_fwd, bool bf_mfma) { return K >= 5 ? 2 : (K == 1 && !strided_fwd) ? 16 : bf_mfma ? 8 : 4; }
 __host__ __device__ constexpr int conv_dl_max_positions(int K, int BN, bool strided_fwd)          // patch positions in LDS
 {
     return strided_fwd ? 768 : K >= 5 ? (BN == 256 ? 768 : 512) : K == 1 ? 256 : (BN == 256 ? 512 : 256);
@@ -262,16 +265,16 @@ k_conv_mfma_dl(MfmaConvArgs a)
     constexpr int WAVES_N = 4 / WAVES_M;
     constexpr int NT = BN / 32 / WAVES_N;
     constexpr int BM = 32 * MT * WAVES_M;
-    constexpr int kCK = conv_dl_stage_channels(K, STRIDED_FWD);
+    constexpr bool BF = sizeof(T) == 2 && K <= 3 && STRIDE == 1;
+    constexpr int kCK = conv_dl_stage_channels(K, STRIDED_FWD, BF);
     constexpr int KK = K * K, P = K / 2;
     constexpr int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
     constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD);
     constexpr int MAXPOS = XMAX / 256;
-    // bfloat matrix-core path: the filter slice is ROWS rows of [BM][4 bfloats]; a row is (tap, the stage's 4
-    // channels) for 3x3 (9 taps + 1 row of zeros) and (channels 4r .. 4r+3) for 1x1; step s multiplies rows 2s, 2s+1
-    constexpr bool BF = sizeof(T) == 2 && K <= 3 && STRIDE == 1;
-    constexpr int ROWS = K == 3 ? 10 : kCK / 4;
-    constexpr int WF = BF ? ROWS * BM * 2 : KK * kCK * BM;   // dwords of one filter slice (fp32: [tap][channel][BM])
+    // bfloat matrix-core path: the filter slice is ROWS rows of [BM][8 bfloats]; a row is (tap, the stage's 8
+    // channels) for 3x3 (9 taps + 1 row of zeros) and (channels 8r .. 8r+7) for 1x1; step s multiplies rows 2s, 2s+1
+    constexpr int ROWS = K == 3 ? 10 : kCK / 8;
+    constexpr int WF = BF ? ROWS * BM * 4 : KK * kCK * BM;   // dwords of one filter slice (fp32: [tap][channel][BM])
     constexpr int WPIECES = WF / 64;                   // 64-dword pieces of the slice, dealt round-robin to the 4 wavefronts
     constexpr int WINSTR = (WPIECES + 3) / 4;
     static_assert(WF % 64 == 0, "the filter slice is loaded in 64-float pieces");
@@ -354,8 +357,7 @@ k_conv_mfma_dl(MfmaConvArgs a)
     };
     // filter: a load instruction covers 64 consecutive floats of the slice; with BM >= 64 that is (part of) one
     // row, with BM = 32 two rows (two consecutive reduction channels)
-    // (bfloat path: a piece is 32 output channels x 4 bfloats; a wavefront always gets the same part of a row)
-    const unsigned woff16 = m0 + (wave % (BM / 32)) * 32 + (lane >> 1) < a.Mtot ? 4u * (unsigned)lane : kOobOffset;
+    // (bfloat path: one 16-byte load per lane = the 8 bfloats of one output channel; 64 channels to an instruction)
     unsigned woff;
     {
         const int col = BM >= 64 ? (wave % (BM / 64 > 0 ? BM / 64 : 1)) * 64 + lane : (lane & 31);
@@ -375,19 +377,30 @@ k_conv_mfma_dl(MfmaConvArgs a)
     auto issue = [&](float* buf, int c0) {
         float* Wl = buf;
         float* Xl = buf + WF;
+        if constexpr (BF) {
+            // rows x parts of 64 output channels, dealt round-robin to the 4 wavefronts
+            constexpr int PARTS = (BM + 63) / 64, NLOAD = ROWS * PARTS;
+            const int C8 = (a.C + 7) >> 3;
+#pragma unroll
+            for (int u = 0; u < (NLOAD + 3) / 4; ++u) {
+                const int idx = wave + 4 * u;
+                if (idx < NLOAD) {
+                    const int r = idx / PARTS, part = idx - r * PARTS;
+                    const int tap = K == 3 ? r : 0, oct = (c0 >> 3) + (K == 3 ? 0 : r);
+                    const int col = part * 64 + lane;
+                    if (col < BM) {
+                        const unsigned so = 16u * (unsigned)((tap * C8 + oct) * a.Mtot + m0);
+                        const unsigned vo = (oct < C8 && m0 + col < a.Mtot) ? 16u * (unsigned)col : kOobOffset;
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_LDS_PTR(Wl + (r * BM + part * 64) * 4), 16, vo, so, 0, 0);
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int u = 0; u < WINSTR; ++u) {
             const int idx = wave + 4 * u;                              // 64-dword piece of the slice
             if (idx >= WPIECES) break;
-            if constexpr (BF) {
-                const int r = idx / (BM / 32), part = idx - r * (BM / 32);
-                const int C4 = (a.C + 3) >> 2;
-                const int tap = K == 3 ? r : 0, quad = (c0 >> 2) + (K == 3 ? 0 : r);
-                const unsigned so = 4u * (unsigned)((((tap * C4 + quad) * a.Mtot + m0) << 1) + part * 64);
-                const unsigned vo = quad < C4 ? woff16 : kOobOffset;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_LDS_PTR(Wl + idx * 64), 4, vo, so, 0, 0);
-                continue;
-            }
+            if constexpr (BF) continue;
             const int row = BM >= 64 ? idx / (BM / 64 > 0 ? BM / 64 : 1) : 2 * idx;
             const int tap = row / kCK, k = row - tap * kCK;
             const unsigned so = 4u * (unsigned)((tap * a.C + c0 + k) * a.Mtot + m0);
@@ -419,24 +432,24 @@ k_conv_mfma_dl(MfmaConvArgs a)
         const float* Wl = buf;
         const float* Xl = buf + WF;
         if constexpr (BF) {
-            // one step = rows 2s and 2s+1 of the slice: lanes 0-31 feed row 2s, lanes 32-63 row 2s+1 (4 reduction
-            // elements each); the 4 patch values of a lane are zero-extended bfloats and are packed two to a dword
-            typedef short v4s __attribute__((ext_vector_type(4)));
+            // one step = rows 2s and 2s+1 of the slice: lanes 0-31 feed row 2s, lanes 32-63 row 2s+1 (8 reduction
+            // elements each); the 8 patch values of a lane are zero-extended bfloats and are packed two to a dword
             constexpr int NSTEP16 = ROWS / 2;
-            uint2 av[2][MT], bv[2][NT];
+            uint4 av[2][MT], bv[2][NT];
             auto load_step = [&](int s2, int b) {
                 const int r = 2 * s2 + hi;
                 int boff;
                 if (K == 3) { const int tap = r < KK ? r : 0; boff = (tap / 3) * PW + (tap - (tap / 3) * 3); }
-                else        boff = 4 * r * CS;
+                else        boff = 8 * r * CS;
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) av[b][mt] = *(const uint2*)(Wl + ((r * BM + baseA + 32 * mt) << 1));
+                for (int mt = 0; mt < MT; ++mt) av[b][mt] = *(const uint4*)(Wl + ((r * BM + baseA + 32 * mt) << 2));
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
                     const float* xp = Xl + baseB[t] + boff;
-                    const uint32_t x0 = __float_as_uint(xp[0]), x1 = __float_as_uint(xp[CS]);
-                    const uint32_t x2 = __float_as_uint(xp[2 * CS]), x3 = __float_as_uint(xp[3 * CS]);
-                    bv[b][t] = make_uint2(x0 | (x1 << 16), x2 | (x3 << 16));
+                    uint32_t x[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) x[k] = __float_as_uint(xp[k * CS]);
+                    bv[b][t] = make_uint4(x[0] | (x[1] << 16), x[2] | (x[3] << 16), x[4] | (x[5] << 16), x[6] | (x[7] << 16));
                 }
             };
             load_step(0, 0);
@@ -448,8 +461,8 @@ k_conv_mfma_dl(MfmaConvArgs a)
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
-                        acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(v4s, av[j & 1][mt]),
-                                                                             __builtin_bit_cast(v4s, bv[j & 1][t]), acc[mt][t], 0, 0, 0);
+                        acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av[j & 1][mt]),
+                                                                            __builtin_bit_cast(v8bf, bv[j & 1][t]), acc[mt][t], 0, 0, 0);
             }
             return;
         }
@@ -560,7 +573,8 @@ void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 #define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE>), grid, dim3(256), 0, s, a)
     if (sh.BN == 256) {
         if constexpr (!STRIDED_FWD) {
-            if (sh.BM == 128) { if constexpr (conv_dl_max_bm(K) >= 128) FTP_DL(2, 2, 256); }
+            // (the 3x3 bfloat path never takes 128 channels x 256 pixels: its 8-channel stages would not fit 64 KB of LDS)
+            if (sh.BM == 128) { if constexpr (conv_dl_max_bm(K) >= 128 && !(sizeof(T) == 2 && K == 3 && STRIDE == 1)) FTP_DL(2, 2, 256); }
             else if (sh.BM == 64) FTP_DL(1, 2, 256); else FTP_DL(1, 1, 256);
         }
     } else {
@@ -682,10 +696,10 @@ bool mfma_conv_packs_bf16(const ConvArgs& a) { return a.bf16 && a.K <= 3 && a.S 
 void prep_filter(const void* w, int bf16, int packed16, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s)
 {
     if (packed16) {
-        // (fits the fp32 areas: at most 10 taps x (C + 3) x M x 2 bytes against K*K x C x M x 4)
+        // (fits the fp32 areas: at most 10 taps x (C + 7) x M x 2 bytes against K*K x C x M x 4, C >= 8)
         const int taps = K == 3 ? 10 : 1;
-        const long long cmax = (long long)taps * (((wt_fwd ? Cin : Cout) + 3) / 4) * (wt_fwd ? Cout : Cin) * 4;
-        const long long cboth = (long long)taps * ((std::max(Cin, Cout) + 3) / 4) * std::max(Cin, Cout) * 4;
+        const long long cmax = (long long)taps * (((wt_fwd ? Cin : Cout) + 7) / 8) * (wt_fwd ? Cout : Cin) * 8;
+        const long long cboth = (long long)taps * ((std::max(Cin, Cout) + 7) / 8) * std::max(Cin, Cout) * 8;
         const long long n16 = wt_fwd && wt_bwd ? cboth : cmax;
         hipLaunchKernelGGL(k_prep_filter16, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (const bf16_t*)w, (bf16_t*)wt_fwd, (bf16_t*)wt_bwd,
                            Cout, Cin, K * K, taps);
