@@ -566,6 +566,37 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
 
+    // Behind a pool a chunk of up to 256 pixels is at most 64 windows: one (delta, winner) pair per lane and channel.
+    // They are loaded one chunk ahead, during the previous chunk's multiply, so that their latency is hidden.
+    const bool ahead = POOL && a.PK <= 256;
+    uint8_t pm[8]; float pg[8];
+    int p_il = 0, p_wr = 0, p_wx = 0;
+    bool p_ok = false;
+    auto load_ahead = [&](int id) {
+        const int ib = id / row_blocks, rb = id - ib * row_blocks;
+        const int n0 = ib * TI;
+        const int ni = (a.batch - n0) < TI ? (a.batch - n0) : TI;
+        const int yb = y0 + rb * TR;
+        const int nr = (y1 - yb + 1) < TR ? (y1 - yb + 1) : TR;
+        const int wpr = TCp >> 1, wrows = nr >> 1;
+        const int nwin = ni * wrows * wpr;
+        p_ok = lane < nwin;
+        const int wi = p_ok ? lane : 0;
+        const int wrow = wi / wpr;
+        p_wx = wi - wrow * wpr;
+        p_il = wrow / wrows; p_wr = wrow - p_il * wrows;
+        const int sy = (yb >> 1) + p_wr, sx = (x0 >> 1) + p_wx;
+        const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, n0 + p_il, 0, sy, sx);
+        const T* gp = at<T>(a.din, stack, ti, tj, n0 + p_il, 0, sy, sx);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int co = co0 + wave + 4 * k < a.Cout ? co0 + wave + 4 * k : a.Cout - 1;
+            pm[k] = mp[(long long)co * a.mask.cs];
+            pg[k] = ld(gp + (long long)co * a.din.cs);
+        }
+    };
+    if (ahead && id0 < id1) load_ahead(id0);
+
     for (int id = id0; id < id1; ++id) {
         {
             const int ib = id / row_blocks, rb = id - ib * row_blocks;
@@ -576,7 +607,17 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
             __syncthreads();
             // dZ, pixel-major [pixel][co]: wavefront w takes channels w, w+4, ... (8 of them).  All loads of a pass
             // are unconditional (clamped) and issued together; what must be zero is zeroed at the LDS write.
-            if (POOL) {
+            if (ahead) {
+                if (p_ok) {
+#pragma unroll
+                    for (int pos = 0; pos < 4; ++pos) {
+                        float* zdst = Zl + ((p_il * nr + 2 * p_wr + (pos >> 1)) * TCp + 2 * p_wx + (pos & 1)) * ZP + wave;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k)
+                            zdst[4 * k] = (((pm[k] >> 1) & 3) == pos && co0 + wave + 4 * k < a.Cout) ? pg[k] : 0.0f;
+                    }
+                }
+            } else if (POOL) {
                 // behind a pool one (delta, winner) pair per window and channel serves the window's 4 pixels;
                 // owned rectangles of a pooled convolution start and end on window borders
                 const int wpr = TCp >> 1, wrows = nr >> 1;
@@ -656,6 +697,7 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
                 }
             }
             __syncthreads();
+            if (ahead && id + 1 < id1) load_ahead(id + 1);       // in flight during the multiply below
             // the 4 wavefronts take alternate pixel pairs of every row
             const int nrows = ni * nr;
             for (int rr = 0; rr < nrows; ++rr) {
