@@ -10,7 +10,9 @@
 // rectangle is at the convolution output, the deltas at pooled resolution, and a pixel receives its window's delta
 // only if it is the window's winner; 2 = stride-2 convolution: the rectangle is the stack's owned part of the
 // *input* map and pixel (y, x) carries delta (y/2, x/2) if both are even, else zero (the filter gradient of a strided
-// convolution is the stride-1 one of the deltas with zeros in between; three quarters of the products are zero).
+// convolution is the stride-1 one of the deltas with zeros in between; three quarters of the products are zero; kept for
+// 16-bit maps); 3 = stride-2 convolution run over the stack's owned *output* pixels (fp32): pixel (y, x) reads the
+// patch of the input map at (2y + ky, 2x + kx), no zeros are multiplied, the patch of a chunk is four times as large.
 // fp32 maps: the patch of X does not pass through registers.  It goes HBM -> LDS with buffer_load_dword ... lds, one
 // element per lane, channel-major ([ci][patch position], odd channel stride), positions outside the map from
 // out-of-range offsets (= 0); the deltas still go through registers (masking, pool routing), loaded during the
@@ -37,12 +39,15 @@ k_wgrad_mfma(MfmaWgradArgs a)
     constexpr bool POOL = HALF == 1;
     constexpr bool BF = sizeof(T) == 2;
     constexpr bool DL = !BF;                           // fp32: the patch is loaded straight into LDS
+    constexpr int S = HALF == 3 ? 2 : 1;               // patch positions per chunk pixel and dimension
+    constexpr bool HALF_RES = HALF == 1 || HALF == 2;  // the deltas sit at half the resolution of the rectangle
+    static_assert(HALF != 3 || DL, "the output-pixel form of stride 2 is written for the direct-load path");
     constexpr int WAVES_K = 4 / (WAVES_CO * WAVES_CI);
     constexpr int KK = K * K, P = K / 2, NTAP = TROWS * K;
     constexpr int BCO = 32 * WAVES_CO, BCI = 32 * WAVES_CI;
     constexpr int ZP = BCO + 1, XP = BCI + 1;          // odd strides: conflict-free transposing writes
     constexpr int NZ = BCO / 4, NX = BCI / 4;          // channels each wavefront stages
-    constexpr int ZPOS = kWgradZPos, XPOS = wgrad_xpos(P), XPASS = XPOS / 64;
+    constexpr int ZPOS = kWgradZPos, XPOS = wgrad_xpos(P, S), XPASS = XPOS / 64;
     constexpr int XS = XPOS + 1;                       // DL: dwords between the patch rows of two channels
 
     extern __shared__ float lds[];
@@ -65,7 +70,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
     // Chunk geometry of this stack: TI images x TR rows x TC columns of the owned rectangle, at most ZPOS
     // pixels (rows padded to an even length TCp) and at most XPOS patch positions.  The stack's chunk list
     // (image block, row block, column block) is cut into a.splits contiguous shares.
-    const WgradChunks wc = wgrad_chunks(rw, rh, a.batch, P);
+    const WgradChunks wc = wgrad_chunks(rw, rh, a.batch, P, S);
     const int col_blocks = wc.col_blocks, TC = wc.TC, TCp = wc.TCp, PW = wc.PW, TR = wc.TR, row_blocks = wc.row_blocks, TI = wc.TI;
     const int id0 = (int)((long long)split * wc.total / a.splits), id1 = (int)((long long)(split + 1) * wc.total / a.splits);
     float* Zl = lds;                                   // [pixel][ZP]
@@ -107,7 +112,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
             const int row = p / TCp, zc = p - row * TCp;
             const int il = row / c.nr, r = row - il * c.nr;
             const int qy = c.yb + r, qx = c.xb + (zc < c.nc ? zc : c.nc - 1);
-            const int sy = HALF ? (qy >> 1) : qy, sx = HALF ? (qx >> 1) : qx;
+            const int sy = HALF_RES ? (qy >> 1) : qy, sx = HALF_RES ? (qx >> 1) : qx;
             zinfo = (ok ? 1 : 0) | (zc >= c.nc ? 2 : 0) | ((((qy & 1) << 1) | (qx & 1)) << 2) | (lane < ((npos + 7) & ~7) ? 16 : 0);
             zpos = ok ? ((il * (c.nr + 2 * P) + r) * PW + zc) * XP : 0;
             const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, c.n0 + il, 0, sy, sx);
@@ -183,7 +188,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
     auto issue_x = [&](const Chunk& c) -> int {
         int issued = 0;
         if constexpr (DL) {
-            const int nph = c.nr + 2 * P, npos = c.ni * nph * PW;
+            const int nph = S * c.nr + 2 * P, npos = c.ni * nph * PW;
             const T* base = (const T*)a.in.p + (long long)stack * a.in.ss + (long long)c.n0 * a.in.ns;
             const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, (short)0, 0x7FFFFFFF, 0x00020000);
 #pragma unroll
@@ -192,8 +197,8 @@ k_wgrad_mfma(MfmaWgradArgs a)
                     const int p = lane + 64 * pass;
                     const int prow = p / PW, xc = p - prow * PW;
                     const int il = prow / nph, r = prow - il * nph;
-                    const int gy = c.yb - P + r, gx = c.xb - P + xc;
-                    const bool inside = p < npos && xc < c.nc + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
+                    const int gy = S * c.yb - P + r, gx = S * c.xb - P + xc;
+                    const bool inside = p < npos && xc < S * c.nc + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
                     const unsigned vo = inside ? 4u * (unsigned)(il * (int)a.in.ns + (gy - a.in.y0[ti]) * a.in.pitch + (gx - a.in.x0[tj])) : 0x80000000u;
 #pragma unroll
                     for (int k = 0; k < NX; ++k) {
@@ -216,6 +221,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
             case 16: __builtin_amdgcn_s_waitcnt(0x4F70); break;
             case 24: __builtin_amdgcn_s_waitcnt(0x4F78); break;
             case 32: __builtin_amdgcn_s_waitcnt(0x8F70); break;
+            case 40: __builtin_amdgcn_s_waitcnt(0x8F78); break;
             case 48: __builtin_amdgcn_s_waitcnt(0xCF70); break;
             default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
         }
@@ -245,18 +251,18 @@ k_wgrad_mfma(MfmaWgradArgs a)
             }
             return;
         }
-        const int nrows = c.ni * c.nr, nph = c.nr + 2 * P, ncp = (c.nc + 1) & ~1;
+        const int nrows = c.ni * c.nr, nph = S * c.nr + 2 * P, ncp = (c.nc + 1) & ~1;
         for (int rr = 0; rr < nrows; ++rr) {
             const int il = rr / c.nr, r = rr - il * c.nr;
             const float* zrow = Zl + (rr * TCp + hi) * ZP + co_l;
-            const float* xrow = DL ? Xl + ci_l * XS + (il * nph + r) * PW + hi : Xl + ((il * nph + r) * PW + hi) * XP + ci_l;
+            const float* xrow = DL ? Xl + ci_l * XS + (il * nph + S * r) * PW + S * hi : Xl + ((il * nph + r) * PW + hi) * XP + ci_l;
             // wavefronts that share a (co, ci) tile take alternate pixel pairs of every row
             for (int xp = 2 * wave_k; xp < ncp; xp += 2 * WAVES_K) {
                 const float av = zrow[xp * ZP];
 #pragma unroll
                 for (int t = 0; t < NTAP; ++t) {
                     if (TROWS != K && trow0 + t / K >= K) break;           // (the last part of a split filter may be short)
-                    const float bv = xrow[((trow0 + t / K) * PW + xp + (t % K)) * (DL ? 1 : XP)];
+                    const float bv = xrow[((trow0 + t / K) * PW + S * xp + (t % K)) * (DL ? 1 : XP)];
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t], 0, 0, 0);
                 }
             }
@@ -358,20 +364,23 @@ bool mfma_wgrad_eligible(const ConvArgs& c)
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
 {
     MfmaWgradArgs a;
-    a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.S == 2 ? c.own : c.rect;
+    // (stride 2: fp32 runs over the owned output pixels, 16-bit maps over the owned input pixels with zero-inserted deltas)
+    const int half = c.pooled ? 1 : c.S == 2 ? (c.bf16 ? 2 : 3) : 0;
+    a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = half == 2 ? c.own : c.rect;
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
     a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hi; a.Wc = c.Wi; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
     a.splits = c.wgrad_shares;
     a.PK = kWgradZPos;
     // (64 input channels per workgroup where the patch of a 5x5 / 7x7 filter would not leave LDS for two workgroups)
-    const int waves_ci = (c.Cin >= 64 && c.K <= 3) ? 2 : 1;
+    // (... or of the fourfold patch of the output-pixel form of stride 2)
+    const int waves_ci = (c.Cin >= 64 && c.K <= 3 && half != 3) ? 2 : 1;
     // (32 output channels per workgroup for the 3x3 layers that have no more: all four wavefronts then split the pixels)
     const int waves_co = (c.Cout <= 32 && c.K == 3 && waves_ci == 1) ? 1 : 2;
     const int BCO = 32 * waves_co, BCI = 32 * waves_ci;
     // (+ the bfloat path's table of patch positions)
     // (the fp32 patch layout is [ci][positions + 1], the bfloat one [position][ci + 1] + the table of patch positions)
     const size_t lds = c.bf16 ? ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1) + kWgradZPos) * sizeof(float)
-                              : ((size_t)kWgradZPos * (BCO + 1) + (size_t)BCI * (wgrad_xpos(c.K / 2) + 1)) * sizeof(float);
+                              : ((size_t)kWgradZPos * (BCO + 1) + (size_t)BCI * (wgrad_xpos(c.K / 2, half == 3 ? 2 : 1) + 1)) * sizeof(float);
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
     const int parts = c.K == 5 ? 3 : c.K == 7 ? 7 : 1;                 // filter rows 2 + 2 + 1, or one at a time
     a.gx = tiles * parts; a.stacks = c.N * c.M;
@@ -383,15 +392,16 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
         g_kernel_label = "k_wgrad_mfma<" TN ", " #KK ", " #WCO ", " #WCI ", " #HF ", " #TR ">"; \
         hipLaunchKernelGGL((k_wgrad_mfma<TT, KK, WCO, WCI, HF, TR>), grid, block, lds, s, a); } while (0)
 #define FTP_WG(KK, WCO, WCI, HF, TR) do { if (c.bf16) FTP_WG1(bf16_t, "unsigned short", KK, WCO, WCI, HF, TR); else FTP_WG1(float, "float", KK, WCO, WCI, HF, TR); } while (0)
-    const int half = c.pooled ? 1 : c.S == 2 ? 2 : 0;
     if (c.K == 7) FTP_WG(7, 2, 1, 0, 1);
     else if (c.K == 5) FTP_WG(5, 2, 1, 0, 2);
     else if (c.K == 3) {
-        if (waves_co == 1)      { if (half == 1) FTP_WG(3, 1, 1, 1, 3); else if (half == 2) FTP_WG(3, 1, 1, 2, 3); else FTP_WG(3, 1, 1, 0, 3); }
+        if (half == 3)          { if (waves_co == 1) FTP_WG1(float, "float", 3, 1, 1, 3, 3); else FTP_WG1(float, "float", 3, 2, 1, 3, 3); }
+        else if (waves_co == 1) { if (half == 1) FTP_WG(3, 1, 1, 1, 3); else if (half == 2) FTP_WG(3, 1, 1, 2, 3); else FTP_WG(3, 1, 1, 0, 3); }
         else if (waves_ci == 2) { if (half == 1) FTP_WG(3, 2, 2, 1, 3); else if (half == 2) FTP_WG(3, 2, 2, 2, 3); else FTP_WG(3, 2, 2, 0, 3); }
         else                    { if (half == 1) FTP_WG(3, 2, 1, 1, 3); else if (half == 2) FTP_WG(3, 2, 1, 2, 3); else FTP_WG(3, 2, 1, 0, 3); }
     } else {
-        if (waves_ci == 2) { if (half == 1) FTP_WG(1, 2, 2, 1, 1); else if (half == 2) FTP_WG(1, 2, 2, 2, 1); else FTP_WG(1, 2, 2, 0, 1); }
+        if (half == 3)     FTP_WG1(float, "float", 1, 2, 1, 3, 1);
+        else if (waves_ci == 2) { if (half == 1) FTP_WG(1, 2, 2, 1, 1); else if (half == 2) FTP_WG(1, 2, 2, 2, 1); else FTP_WG(1, 2, 2, 0, 1); }
         else               { if (half == 1) FTP_WG(1, 2, 1, 1, 1); else if (half == 2) FTP_WG(1, 2, 1, 2, 1); else FTP_WG(1, 2, 1, 0, 1); }
     }
 #undef FTP_WG

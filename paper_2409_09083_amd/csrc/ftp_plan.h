@@ -95,24 +95,26 @@ struct Plan {
 // host (share count), so both see the same numbers.
 // (Patch positions: a 1x1 filter reads exactly the chunk's 64 pixels; 192 for 3x3 filters, 256 for 5x5 and 7x7.
 // The smaller the patch, the more workgroups share a CU's LDS.)
-FTP_HD constexpr int wgrad_xpos(int P) { return P == 0 ? 64 : P == 1 ? 192 : 256; }
+FTP_HD constexpr int wgrad_xpos(int P, int S = 1) { return S == 2 ? (P == 0 ? 256 : 384) : P == 0 ? 64 : P == 1 ? 192 : 256; }
 struct WgradChunks { int col_blocks, TC, TCp, PW, TR, row_blocks, TI, img_blocks, total; };
-FTP_HD inline WgradChunks wgrad_chunks(int rw, int rh, int batch, int P)
+// S = 2: a stride-2 convolution run over its owned *output* pixels (K = 1, 3): pixel (r, c) of a chunk reads the patch
+// at (2 r + ky, 2 c + kx), so the patch of a chunk is about four times the chunk.
+FTP_HD inline WgradChunks wgrad_chunks(int rw, int rh, int batch, int P, int S = 1)
 {
-    const int ZPOS = 64, XPOS = wgrad_xpos(P);
-    int MAXC = (XPOS / (1 + 2 * P) - 2 * P) & ~1;            // widest column block: one row of pixels and its halo rows fit XPOS
+    const int ZPOS = 64, XPOS = wgrad_xpos(P, S);
+    int MAXC = ((XPOS / (S + 2 * P) - 2 * P) / S) & ~1;      // widest column block: one row of pixels and its halo rows fit XPOS
     if (MAXC > 64 - 2 * P) MAXC = 64 - 2 * P;
     WgradChunks c;
     c.col_blocks = (rw + MAXC - 1) / MAXC;
     c.TC = (rw + c.col_blocks - 1) / c.col_blocks;
-    c.TCp = (c.TC + 1) & ~1; c.PW = c.TCp + 2 * P;
+    c.TCp = (c.TC + 1) & ~1; c.PW = S * c.TCp + 2 * P;
     c.TR = ZPOS / c.TCp; if (c.TR > rh) c.TR = rh;
-    while (c.TR > 1 && (c.TR + 2 * P) * c.PW > XPOS) --c.TR;
+    while (c.TR > 1 && (S * c.TR + 2 * P) * c.PW > XPOS) --c.TR;
     c.row_blocks = (rh + c.TR - 1) / c.TR;
     c.TI = 1;
     if (c.TR == rh && c.col_blocks == 1) {
         c.TI = ZPOS / (c.TCp * rh);
-        const int by_patch = XPOS / ((rh + 2 * P) * c.PW);
+        const int by_patch = XPOS / ((S * rh + 2 * P) * c.PW);
         if (c.TI > by_patch) c.TI = by_patch;
         if (c.TI < 1) c.TI = 1;
     }
