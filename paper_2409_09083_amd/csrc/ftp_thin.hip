@@ -250,7 +250,7 @@ k_conv_bwd_data_thin4(View din, View mask, View dout, View isign, int scale_out,
                       const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch,
                       int ntx, int nty, int tiles_x)
 {
-    constexpr int COC = kThin4Coc, CH = kThin4Patch, WR = 9 * CI;
+    constexpr int COC = kThin4Coc, CH = kThin4Patch, WR = (9 * CI + 3) & ~3;        // (filter rows on 16-byte boundaries: read four weights at a time)
     __shared__ __attribute__((aligned(16))) float dz[COC * CH];
     __shared__ __attribute__((aligned(16))) float wl[COC * WR];
     const int tid = threadIdx.x;
