@@ -219,11 +219,13 @@ FTP_HD inline ThinChunks thin_wgrad_chunks(int rw, int rh, int batch, int PK, bo
     c.total = c.img_blocks * c.row_blocks;
     return c;
 }
-// Shares of its chunk list (blocks of 32 output channels x stacks x shares should reach about 1024 workgroups).
+// Shares of its chunk list: blocks of 32 output channels x stacks x shares should come close to 1024 workgroups, the
+// number that runs at a time (four to a CU), without exceeding it - a few workgroups over would start a second round
+// as long as the first (36 stacks x 29 shares = 1044 took nearly twice as long as 36 x 28).
 inline int wgrad_shares_thin(int cout, int stacks, int chunks)
 {
     const int blocks = ((cout + 31) / 32) * stacks;
-    int shares = (1024 + blocks - 1) / blocks;
+    int shares = 1024 / blocks;
     if (shares > chunks) shares = chunks;
     if (shares > 256) shares = 256;
     return shares < 1 ? 1 : shares;
