@@ -115,14 +115,31 @@ k_wgrad_mfma(MfmaWgradArgs a)
             const int sy = HALF_RES ? (qy >> 1) : qy, sx = HALF_RES ? (qx >> 1) : qx;
             zinfo = (ok ? 1 : 0) | (zc >= c.nc ? 2 : 0) | ((((qy & 1) << 1) | (qx & 1)) << 2) | (lane < ((npos + 7) & ~7) ? 16 : 0);
             zpos = ok ? ((il * (c.nr + 2 * P) + r) * PW + zc) * XP : 0;
-            const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, c.n0 + il, 0, sy, sx);
-            const T* gp = at<T>(a.din, stack, ti, tj, c.n0 + il, 0, sy, sx);
+            if constexpr (DL) {
+                // fp32: buffer loads - one 32-bit offset per lane, the channel as a scalar offset
+                const T* gbase = (const T*)a.din.p + (long long)stack * a.din.ss + (long long)c.n0 * a.din.ns;
+                const __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc((void*)gbase, (short)0, 0x7FFFFFFF, 0x00020000);
+                const unsigned gvo = 4u * (unsigned)(il * (int)a.din.ns + (sy - a.din.y0[ti]) * a.din.pitch + (sx - a.din.x0[tj]));
+                const uint8_t* mbase = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)c.n0 * a.mask.ns;
+                const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)mbase, (short)0, 0x7FFFFFFF, 0x00020000);
+                const unsigned mvo = POOL ? (unsigned)(il * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj])) : 0u;
 #pragma unroll
-            for (int k = 0; k < NZ; ++k) {
-                const int ch = wave + 4 * k;
-                const int co = co0 + ch < a.Cout ? co0 + ch : a.Cout - 1;
-                zm[k] = POOL ? (uint32_t)mp[(long long)co * a.mask.cs] : 0u;      // only the pool winner is needed
-                zg[k] = ld(gp + (long long)co * a.din.cs);
+                for (int k = 0; k < NZ; ++k) {
+                    const int ch = wave + 4 * k;
+                    const int co = co0 + ch < a.Cout ? co0 + ch : a.Cout - 1;
+                    zm[k] = POOL ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(mrsrc, mvo, (unsigned)(co * (int)a.mask.cs), 0) : 0u;      // only the pool winner is needed
+                    zg[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(grsrc, gvo, 4u * (unsigned)(co * (int)a.din.cs), 0));
+                }
+            } else {
+                const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, c.n0 + il, 0, sy, sx);
+                const T* gp = at<T>(a.din, stack, ti, tj, c.n0 + il, 0, sy, sx);
+#pragma unroll
+                for (int k = 0; k < NZ; ++k) {
+                    const int ch = wave + 4 * k;
+                    const int co = co0 + ch < a.Cout ? co0 + ch : a.Cout - 1;
+                    zm[k] = POOL ? (uint32_t)mp[(long long)co * a.mask.cs] : 0u;      // only the pool winner is needed
+                    zg[k] = ld(gp + (long long)co * a.din.cs);
+                }
             }
         }
         if constexpr (!DL) {
@@ -356,6 +373,8 @@ bool mfma_wgrad_eligible(const ConvArgs& c)
     if (c.S == 2 && c.K > 3) return false;
     // (the fp32 patch loads address one stack's images with 32-bit byte offsets; a chunk spans at most 64 images)
     if (!c.bf16 && 4.0 * (64.0 * (double)c.in.ns + (double)c.Cin * (double)c.in.cs) >= 2.0e9) return false;
+    if (!c.bf16 && 4.0 * (64.0 * (double)c.din.ns + (double)c.Cout * (double)c.din.cs) >= 2.0e9) return false;
+    if (!c.bf16 && c.pooled && 64.0 * (double)c.mask.ns + (double)c.Cout * (double)c.mask.cs >= 2.0e9) return false;
     return !c.has_bias && c.Cout >= 32 && c.Cin >= 16;
 }
 
