@@ -630,7 +630,24 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc
         return wgs;
     };
     long long widest_wgs = 0;
-    for (int BN = (STRIDED_FWD || small_wg) ? 128 : 256; BN >= 128; BN /= 2) {
+    int bn_first = (STRIDED_FWD || small_wg) ? 128 : 256;
+    if (small_wg && POOL_OUT) {
+        // ... unless 128-pixel tiles (32 pool windows) fit the rows of the rectangles badly: a row of 19 windows leaves
+        // 13 of 32 slots empty, while three such rows fill 57 of 64 (config 5, the 32 -> 64 layer: 0.68 -> 0.58 ms)
+        long long units = 0, slots = 0;
+        const TileChoice t128 = choose_tile(a.rect, c.N, c.M, c.batch, 32, S, K / 2, conv_dl_max_positions(K, 128, STRIDED_FWD));
+        for (int i = 0; i < c.N; ++i)
+            for (int j = 0; j < c.M; ++j) {
+                const int rw = a.rect.x1[j] - a.rect.x0[j] + 1, rh = a.rect.y1[i] - a.rect.y0[i] + 1;
+                const int tcw = t128.tiles_x == 1 ? rw : t128.TC;
+                int trf = t128.cap / tcw; if (trf < 1) trf = 1;
+                const long long rtot = (long long)c.batch * rh;
+                units += rtot * rw;
+                slots += ((rtot + trf - 1) / trf) * ((rw + tcw - 1) / tcw) * t128.cap;
+            }
+        if (slots > 0 && (double)units < 0.7 * (double)slots) bn_first = 256;
+    }
+    for (int BN = bn_first; BN >= (bn_first == 256 && small_wg ? 256 : 128); BN /= 2) {
         const long long w = consider(BM, BN);
         if (w > widest_wgs) widest_wgs = w;
     }
