@@ -563,7 +563,7 @@ constexpr int conv_dl_max_bm(int K) { return K >= 7 ? 64 : 128; }
 template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE>
 void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 {
-    static char label[6][96];
+    static char label[6][96];                    // (every write of an entry stores the same text: entries depend on the template and the shape only)
     const int v = (sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1);
     std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%s, %d, %d, %d, %d, %s, %s, %s, %d>", sizeof(T) == 4 ? "float" : "unsigned short",
                   K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN, POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false",

@@ -406,7 +406,7 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     dim3 grid(xcd_grid(a.splits * a.stacks, a.gx)), block(256);
     // more than 64 KB of dynamic LDS has to be granted per kernel, once
 #define FTP_WG1(TT, TN, KK, WCO, WCI, HF, TR) do { \
-        static bool granted = false; \
+        static thread_local bool granted = false; \
         if (!granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_mfma<TT, KK, WCO, WCI, HF, TR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); granted = true; } \
         g_kernel_label = "k_wgrad_mfma<" TN ", " #KK ", " #WCO ", " #WCI ", " #HF ", " #TR ">"; \
         hipLaunchKernelGGL((k_wgrad_mfma<TT, KK, WCO, WCI, HF, TR>), grid, block, lds, s, a); } while (0)

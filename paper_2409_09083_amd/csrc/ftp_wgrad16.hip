@@ -465,7 +465,7 @@ void wgrad16(const ConvArgs& c, float* scratch, hipStream_t s)
     a.gx = tiles; a.stacks = c.N * c.M;
     dim3 grid(xcd_grid(a.splits * a.stacks, a.gx)), block(256);
 #define FTP_W16(WCI, HF) do { \
-        static bool granted = false; \
+        static thread_local bool granted = false; \
         if (!granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_mfma16<WCI, HF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); granted = true; } \
         g_kernel_label = "k_wgrad_mfma16<" #WCI ", " #HF ">"; \
         hipLaunchKernelGGL((k_wgrad_mfma16<WCI, HF>), grid, block, lds, s, a); } while (0)
