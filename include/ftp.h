@@ -205,7 +205,8 @@ typedef enum {
     FTP_PASS_CONV_FWD = 0, FTP_PASS_CONV_BWD_DATA = 1, FTP_PASS_WGRAD = 2, FTP_PASS_REDUCE = 3,
     FTP_PASS_POOL_FWD = 4, FTP_PASS_POOL_BWD = 5,
     FTP_PASS_SCALE_DY = 6,         /* dy times the last activation's derivative; layer = last convolution */
-    FTP_PASS_UPDATE = 7            /* ftp_sgd_step; layer = the convolution updated */
+    FTP_PASS_UPDATE = 7,           /* ftp_sgd_step; layer = the convolution updated */
+    FTP_PASS_WGRAD_SUM = 8         /* sum of the batch shares of a layer's per-stack filter gradient (inside ftp_backward) */
 } ftp_pass;
 typedef struct {
     int32_t pass, layer, launches, reserved;   /* layer = primitive layer index, -1 for the reduction */

@@ -31,7 +31,7 @@ class ftp_kernel_time(ctypes.Structure):
                 ("executed_flops_per_launch", ctypes.c_double)]
 
 
-PASS_NAMES = {0: "conv_fwd", 1: "conv_bwd_data", 2: "wgrad", 3: "reduce", 4: "pool_fwd", 5: "pool_bwd", 6: "scale_dy", 7: "update"}
+PASS_NAMES = {0: "conv_fwd", 1: "conv_bwd_data", 2: "wgrad", 3: "reduce", 4: "pool_fwd", 5: "pool_bwd", 6: "scale_dy", 7: "update", 8: "wgrad_sum"}
 
 
 class FtpError(RuntimeError):

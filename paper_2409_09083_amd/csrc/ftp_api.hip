@@ -3,6 +3,7 @@
 #include "ftp_plan.h"
 #include "ftp_launch.h"
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -406,16 +407,22 @@ int ftp_backward(const ftp_plan_t* plan, const void* dy, const void* x, const vo
             // (the previous gradient is still reading the region this unit's delta step will overwrite; gradients
             // are serial among themselves on `aux`, they share the scratch)
             if (overlap && gradient_in_flight && (rc = order(aux, s)) != FTP_OK) return rc;
+            int shares = 1;
             if (use_mfma() && thin_wgrad_eligible(a)) {
+                shares = a.wgrad_shares_thin;
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { thin_wgrad(a, scratch, aux); });
             } else if (use_mfma() && plain_geometry(a) && u.in_act.kind == BUF_WS && u.in_delta.kind == BUF_WS && wgrad16_eligible(a)) {
                 // (its wide loads round addresses down and may run a few bytes past a map: only inside the workspace, which has margins)
+                shares = a.wgrad_shares16;
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { wgrad16(a, scratch, aux); });
             } else if (use_mfma() && mfma_wgrad_eligible(a)) {
+                shares = a.wgrad_shares;
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { mfma_wgrad(a, scratch, aux); });
             } else {
                 rc = timed(plan, FTP_PASS_WGRAD, u.layer, aux, [&] { direct_wgrad(a, aux); });
             }
+            if (rc == FTP_OK && shares > 1)
+                rc = timed(plan, FTP_PASS_WGRAD_SUM, u.layer, aux, [&] { wgrad_share_sum(a, scratch, shares, aux); });
             if (rc != FTP_OK) return rc;
             gradient_in_flight = overlap;
             a.rect = make_rect(p, u.group, FTP_RECT_BWD, u.bi);
@@ -532,6 +539,11 @@ int ftp_profile_read(ftp_plan_t* plan, ftp_kernel_time* out, int32_t capacity, i
                 const double wel = (double)ly.cout * ly.cin * ly.k * ly.k + (ly.has_bias ? ly.cout : 0);
                 t.flops_per_launch = (stacks + 1.0) * wel;
                 t.bytes_per_launch = stacks * wel * 4.0 + 2.0 * wel * es;
+            } else if (g.pass == FTP_PASS_WGRAD_SUM) {
+                const double wel = (double)ly.cout * ly.cin * ly.k * ly.k;
+                const double sh = g.kernel == nullptr ? 1.0 : (double)std::max(std::max(u->wgrad_shares, u->wgrad_shares_thin), u->wgrad_shares16);
+                t.flops_per_launch = stacks * wel * (sh - 1.0);
+                t.bytes_per_launch = stacks * wel * 4.0 * (sh + 1.0);              // (upper bound: the largest share count of the layer)
             } else if (g.pass == FTP_PASS_SCALE_DY) {
                 t.flops_per_launch = out_el;
                 t.bytes_per_launch = out_el * (2.0 * es + 1.0);

@@ -113,6 +113,9 @@ bool mfma_wgrad_eligible(const ConvArgs& a);
 bool wgrad16_eligible(const ConvArgs& a);
 void wgrad16(const ConvArgs& c, float* scratch, hipStream_t s);
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s);
+// The three matrix-core filter-gradient kernels leave `shares` > 1 partial results per stack in the scratch area;
+// this sums them into the per-stack gradient vectors (a launch, and a timing record, of its own).
+void wgrad_share_sum(const ConvArgs& c, const float* scratch, int shares, hipStream_t s);
 
 bool thin_conv_fwd_eligible(const ConvArgs& a);
 void thin_conv_fwd(const ConvArgs& a, hipStream_t s);

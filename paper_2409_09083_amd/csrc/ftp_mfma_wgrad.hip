@@ -425,11 +425,16 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     }
 #undef FTP_WG
 #undef FTP_WG1
-    if (a.splits > 1) {
-        const long long lp = (long long)c.Cout * c.Cin * c.K * c.K;
-        dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);
-        hipLaunchKernelGGL(k_wgrad_splitk_reduce, g2, dim3(256), 0, s, scratch, c.partial, lp, c.n_params, c.w_off, a.splits);
-    }
+}
+
+// Sums the `shares` partial results one of the filter-gradient kernels left in the scratch area into the layer's place
+// in the per-stack gradient vectors, in share order.
+void wgrad_share_sum(const ConvArgs& c, const float* scratch, int shares, hipStream_t s)
+{
+    const long long lp = (long long)c.Cout * c.Cin * c.K * c.K;
+    dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);
+    g_kernel_label = "k_wgrad_splitk_reduce";
+    hipLaunchKernelGGL(k_wgrad_splitk_reduce, g2, dim3(256), 0, s, scratch, c.partial, lp, c.n_params, c.w_off, shares);
 }
 
 }  // namespace ftp

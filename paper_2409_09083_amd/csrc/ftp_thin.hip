@@ -739,19 +739,6 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
     }
 }
 
-__global__ void __launch_bounds__(256)
-k_thin_splitk_reduce(const float* __restrict__ scratch, float* __restrict__ partial, long long layer_params, long long n_params,
-                     long long w_off, int splits)
-{
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int stack = blockIdx.y;
-    if (i >= layer_params) return;
-    const float* src = scratch + (long long)stack * splits * layer_params + i;
-    float v = src[0];
-    for (int s = 1; s < splits; ++s) v += src[(long long)s * layer_params];
-    partial[(long long)stack * n_params + w_off + i] = v;
-}
-
 namespace {
 
 struct ThinGeom { int PK; size_t lds; };
@@ -814,11 +801,6 @@ void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
 #undef FTP_TWK
 #undef FTP_TWS
 #undef FTP_TW
-    if (a.splits > 1) {
-        const long long lp = (long long)c.Cout * c.Cin * c.K * c.K;
-        dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);
-        hipLaunchKernelGGL(k_thin_splitk_reduce, g2, dim3(256), 0, s, scratch, c.partial, lp, c.n_params, c.w_off, a.splits);
-    }
 }
 
 }  // namespace ftp

@@ -412,20 +412,6 @@ k_wgrad_mfma16(Wgrad16Args a)
     }
 }
 
-// Sum of the shares of one layer's partial gradient, in share order.
-__global__ void __launch_bounds__(256)
-k_wgrad_mfma16_share_sum(const float* __restrict__ scratch, float* __restrict__ partial, long long layer_params, long long n_params,
-                         long long w_off, int splits)
-{
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int stack = blockIdx.y;
-    if (i >= layer_params) return;
-    const float* src = scratch + (long long)stack * splits * layer_params + i;
-    float v = src[0];
-    for (int s = 1; s < splits; ++s) v += src[(long long)s * layer_params];
-    partial[(long long)stack * n_params + w_off + i] = v;
-}
-
 
 namespace {
 
@@ -472,11 +458,6 @@ void wgrad16(const ConvArgs& c, float* scratch, hipStream_t s)
     if (waves_ci == 2) { if (c.pooled) FTP_W16(2, 1); else FTP_W16(2, 0); }
     else               { if (c.pooled) FTP_W16(1, 1); else FTP_W16(1, 0); }
 #undef FTP_W16
-    if (a.splits > 1) {
-        const long long lp = (long long)c.Cout * c.Cin * 9;
-        dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);
-        hipLaunchKernelGGL(k_wgrad_mfma16_share_sum, g2, dim3(256), 0, s, scratch, c.partial, lp, c.n_params, c.w_off, a.splits);
-    }
 }
 
 }  // namespace ftp
