@@ -111,6 +111,7 @@ ConvArgs conv_args(const Plan& p, const Unit& u, const UserBufs& ub, const void*
     a.N = p.N; a.M = p.M; a.batch = p.batch;
     a.bf16 = p.dtype == FTP_BF16;
     a.wgrad_shares = u.wgrad_shares; a.wgrad_shares_thin = u.wgrad_shares_thin; a.wgrad_shares16 = u.wgrad_shares16;
+    a.in_ws = u.in_act.kind == BUF_WS ? 1 : 0; a.din_ws = u.in_delta.kind == BUF_WS ? 1 : 0;
     return a;
 }
 

@@ -44,6 +44,7 @@ struct ConvArgs {
     int bf16 = 0;
     int wgrad_shares = 1, wgrad_shares_thin = 1;   // shares of the matrix-core filter-gradient kernels (from the plan, which sized the scratch)
     int wgrad_shares16 = 1;
+    int in_ws = 0, din_ws = 0;      // the activation at the input / the delta at the output lie inside the workspace (which has margins)
 };
 
 struct PoolArgs {

@@ -87,7 +87,8 @@ struct TileGeom {
     bool empty;
 };
 
-template <int S, int P>
+// Q: the patch is loaded four positions to a lane, so a patch row is padded to whole quads.
+template <int S, int P, bool Q>
 __device__ __forceinline__ TileGeom tile_geom(const MfmaConvArgs& a, int x0, int x1, int y0, int y1, int bx)
 {
     TileGeom g;
@@ -103,6 +104,7 @@ __device__ __forceinline__ TileGeom tile_geom(const MfmaConvArgs& a, int x0, int
     g.n_a = g.R0 / g.rh; g.y_a = g.R0 - g.n_a * g.rh;
     const int n_l = (g.R0 + g.nrows - 1) / g.rh;
     g.PW = g.TC * S + 2 * P;
+    if (Q) g.PW = (g.PW + 3) & ~3;
     const int first_rows = g.rh - g.y_a < g.nrows ? g.rh - g.y_a : g.nrows;
     g.first_cnt = S * first_rows + 2 * P;
     g.per_cnt = S * g.rh + 2 * P;
@@ -129,16 +131,34 @@ __device__ __forceinline__ TilePix tile_pix(const TileGeom& g, int wq, int x1)
 // Epilogue shared by the convolution kernels: bias, leaky ReLU, the fused 2x2 max-pool, the decision codes and
 // the stores.  A lane holds, per 32x32 tile, 16 channels (8*(i/4) + 4*hi + i%4) of one pixel.  `bias_lds` is LDS
 // no wavefront reads any more once all of them have arrived here (BM floats are used).
+// Every map store is a buffer store: the lane's 32-bit byte offset carries the pixel (and the lane half's 4 channels),
+// the channel travels as a scalar offset, and a lane that has nothing to store uses an offset beyond the buffer's
+// records, which the hardware drops - no address arithmetic in 64 bits, no branch and no scalar reload per element.
+__device__ __forceinline__ void store_elem(__amdgpu_buffer_rsrc_t r, unsigned vo, unsigned so, float v, const float*)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, vo, so, 0);
+}
+__device__ __forceinline__ void store_elem(__amdgpu_buffer_rsrc_t r, unsigned vo, unsigned so, float v, const bf16_t*)
+{
+    __builtin_amdgcn_raw_buffer_store_b16((uint16_t)bf16_bits(v), r, vo, so, 0);
+}
+
 template <typename T, int K, int S, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, int NT>
 __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileGeom& g, v16f (&acc)[MT][NT], float* bias_lds,
                                               int m0, int x0, int x1, int y0, int stack, int ti, int tj)
 {
     constexpr int BM = 32 * MT * WAVES_M;
     constexpr int P = K / 2;                           // S: patch positions per tile pixel and dimension (pool or stride)
+    constexpr unsigned ES = sizeof(T);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
     const int hi = lane >> 5, l32 = lane & 31;
+    const View& ov = DELTA_IN ? a.dout : a.out;
+    // the tile's images start at image n_a of the stack; offsets from there fit 32 bits (checked by the launcher)
+    const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc((void*)((T*)ov.p + (long long)stack * ov.ss + (long long)g.n_a * ov.ns),
+                                                                            (short)0, (int)0x7FFFFFFF, 0x00020000);
+    const unsigned ocs = ES * (unsigned)ov.cs;         // bytes between channels
     // The bias goes through LDS: a global load between the stores below would make every store wait for all
     // earlier ones (loads and stores share one counter).
     if (!DELTA_IN) {
@@ -150,16 +170,16 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
         // Deltas are stored as dLoss/dZ: where the boundary written to carries an activation, its derivative is
         // applied now.  A lane's 16 channels of a 32-channel block share one sign word; all words are loaded
         // before the first store, so that no load has to wait for stores.
-        const View& ov = a.dout;
-        T* optr[NT]; bool pv[NT];
+        unsigned vo[NT];
         uint32_t sw[NT][MT];
+        float in_slope = a.in_slope;
+        asm volatile("" : "+v"(in_slope));             // (kept in a register: not re-read from the argument block per element)
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int q = (wave_n * NT + t) * 32 + l32;
             const TilePix tp = tile_pix<S, P>(g, q, x1);
-            pv[t] = tp.valid;
-            const int pn = pv[t] ? tp.n : 0, py = pv[t] ? y0 + tp.y : y0, pxx = pv[t] ? g.ox0 + tp.xl : x0;
-            optr[t] = at<T>(ov, stack, ti, tj, pn, 0, py, pxx);
+            const int pn = tp.valid ? tp.n : 0, py = tp.valid ? y0 + tp.y : y0, pxx = tp.valid ? g.ox0 + tp.xl : x0;
+            vo[t] = tp.valid ? ES * (unsigned)((pn - g.n_a) * (int)ov.ns + (py - ov.y0[ti]) * ov.pitch + (pxx - ov.x0[tj])) + 4u * hi * ocs : 0x80000000u;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int mb = m0 + (wave_m * MT + mt) * 32;            // first channel of the block
@@ -169,17 +189,29 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt) {
+                const int mb = m0 + (wave_m * MT + mt) * 32;
+                const uint32_t w = sw[t][mt] >> (4 * hi);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int bit = 8 * (i >> 2) + 4 * hi + (i & 3);
-                    const int m = m0 + (wave_m * MT + mt) * 32 + bit;
-                    float v = acc[mt][t][i];
-                    if (a.scale_out) v = scaled_delta<T>(v, (sw[t][mt] >> bit) & 1u, a.in_slope);
-                    if (pv[t] && m < a.Mtot) st(optr[t] + (long long)m * ov.cs, v);
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    // (the channel count is a multiple of 4: a group of 4 channels exists as a whole or not at all)
+                    const unsigned vg = mb + 8 * g4 + 4 * hi < a.Mtot ? vo[t] : 0x80000000u;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = 4 * g4 + e;
+                        float v = acc[mt][t][i];
+                        if (a.scale_out) v = scaled_delta<T>(v, (w >> (8 * g4 + e)) & 1u, in_slope);
+                        store_elem(orsrc, vg, (unsigned)(mb + 8 * g4 + e) * ocs, v, (const T*)nullptr);
+                    }
                 }
+            }
         return;
     }
+    float slope = a.slope;
+    asm volatile("" : "+v"(slope));
+    const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        POOL_OUT ? (void*)((uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)g.n_a * a.mask.ns) : (void*)ov.p, (short)0, (int)0x7FFFFFFF, 0x00020000);
+    const unsigned mcs = (unsigned)a.mask.cs;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int q = (wave_n * NT + t) * 32 + l32;
@@ -188,35 +220,41 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
         bool pvalid = tp.valid;
         if (POOL_OUT) pvalid = pvalid && (lane & 3) == 0;       // the window's first lane stores
         const bool powned = pvalid && py >= a.own.y0[ti] && py <= a.own.y1[ti] && pxx >= a.own.x0[tj] && pxx <= a.own.x1[tj];
-        T* __restrict__ optr = at<T>(a.out, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0);
-        // (code bytes exist only behind a pool)
-        uint8_t* __restrict__ mptr = POOL_OUT ? at<uint8_t>(a.mask, stack, ti, tj, pvalid ? pn : 0, 0, pvalid ? py : y0, pvalid ? pxx : x0) : nullptr;
+        const unsigned vo = pvalid ? ES * (unsigned)((pn - g.n_a) * (int)ov.ns + (py - ov.y0[ti]) * ov.pitch + (pxx - ov.x0[tj])) + 4u * hi * ocs : 0x80000000u;
+        // (code bytes exist only behind a pool, and only for owned pixels)
+        const unsigned mvo = (POOL_OUT && powned) ? (unsigned)((pn - g.n_a) * (int)a.mask.ns + (py - a.mask.y0[ti]) * a.mask.pitch + (pxx - a.mask.x0[tj])) + 4u * hi * mcs
+                                                  : 0x80000000u;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
+            const int mb = m0 + (wave_m * MT + mt) * 32;
             uint32_t signs = 0;                                 // this lane's 16 channels of the block's sign word
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int ml = (wave_m * MT + mt) * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
-                const int m = m0 + ml;
-                // compared and recorded as the map will hold it (rounded to the storage type)
-                float v = stored(leaky(acc[mt][t][i] + bias_lds[ml], a.slope), (const T*)nullptr);
-                int bi = 0;
-                if (POOL_OUT) {
-                    // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
-                    const float o1 = __shfl_xor(v, 1, 64), o2 = __shfl_xor(v, 2, 64), o3 = __shfl_xor(v, 3, 64);
-                    if (o1 > v) { v = o1; bi = 1; }
-                    if (o2 > v) { v = o2; bi = 2; }
-                    if (o3 > v) { v = o3; bi = 3; }
-                }
-                if (pvalid && m < a.Mtot) {
-                    st(optr + (long long)m * a.out.cs, v);
-                    if (POOL_OUT && powned) mptr[(long long)m * a.mask.cs] = (uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0));
-                    signs |= (v > 0.0f ? 1u : 0u) << (8 * (i >> 2) + 4 * hi + (i & 3));
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const bool gok = mb + 8 * g4 + 4 * hi < a.Mtot;
+                const unsigned vg = gok ? vo : 0x80000000u, mvg = gok ? mvo : 0x80000000u;
+                const float4 b4 = *(const float4*)(bias_lds + (wave_m * MT + mt) * 32 + 8 * g4 + 4 * hi);
+                const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = 4 * g4 + e;
+                    // compared and recorded as the map will hold it (rounded to the storage type)
+                    float v = stored(leaky(acc[mt][t][i] + bb[e], slope), (const T*)nullptr);
+                    int bi = 0;
+                    if (POOL_OUT) {
+                        // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
+                        const float o1 = quad_xor<1>(v), o2 = quad_xor<2>(v), o3 = quad_xor<3>(v);
+                        if (o1 > v) { v = o1; bi = 1; }
+                        if (o2 > v) { v = o2; bi = 2; }
+                        if (o3 > v) { v = o3; bi = 3; }
+                    }
+                    const unsigned so = (unsigned)(mb + 8 * g4 + e);
+                    store_elem(orsrc, vg, so * ocs, v, (const T*)nullptr);
+                    if (POOL_OUT) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0)), mrsrc, mvg, so * mcs, 0);
+                    if (gok && pvalid) signs |= (v > 0.0f ? 1u : 0u) << (8 * g4 + 4 * hi + e);
                 }
             }
             // the other half of the block's channels sits 32 lanes away (same pixel)
             signs |= (uint32_t)__shfl_xor((int)signs, 32, 64);
-            const int mb = m0 + (wave_m * MT + mt) * 32;
             if (powned && hi == 0 && mb < a.Mtot)
                 *at<uint32_t>(a.osign, stack, ti, tj, pn, mb >> 5, py, pxx) = signs;
         }
@@ -242,9 +280,12 @@ constexpr unsigned kBufRecords = 0x7FFFFFFFu;
 // reads a patch four times the size of its tile.)
 // (the bfloat matrix-core path takes 8 channels of a 3x3 filter per stage: one instruction multiplies 8 of them)
 __host__ __device__ constexpr int conv_dl_stage_channels(int K, bool strided_fwd, bool bf_mfma) { return K >= 5 ? 2 : (K == 1 && !strided_fwd) ? 16 : bf_mfma ? 8 : 4; }
-__host__ __device__ constexpr int conv_dl_max_positions(int K, int BN, bool strided_fwd)          // patch positions in LDS
+__host__ __device__ constexpr bool conv_dl_quads(size_t elem, bool pool_in, bool up_in) { return elem == 4 && !pool_in && !up_in; }
+// (a multiple of 256; quads pad every patch row to a multiple of 4 positions, which costs the narrow rectangles of deep
+// layers up to a fifth more positions: their 128-pixel tiles get the room of the 256-pixel ones)
+__host__ __device__ constexpr int conv_dl_max_positions(int K, int BN, bool strided_fwd, bool quad)          // patch positions in LDS
 {
-    return strided_fwd ? 768 : K >= 5 ? (BN == 256 ? 768 : 512) : K == 1 ? 256 : (BN == 256 ? 512 : 256);
+    return strided_fwd ? 768 : K >= 5 ? (BN == 256 ? 768 : 512) : K == 1 ? 256 : (BN == 256 || quad ? 512 : 256);
 }
 
 // POOL_IN (delta back-propagation through a fused pool): the patch lives at the convolution output, the delta at
@@ -269,8 +310,15 @@ k_conv_mfma_dl(MfmaConvArgs a)
     constexpr int kCK = conv_dl_stage_channels(K, STRIDED_FWD, BF);
     constexpr int KK = K * K, P = K / 2;
     constexpr int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
-    constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD);
+    constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD, conv_dl_quads(sizeof(T), POOL_IN, UP_IN));
     constexpr int MAXPOS = XMAX / 256;
+    // fp32 patches (not those gathered element by element through pool winners or between inserted zeros) travel 16
+    // bytes a lane: a quad of consecutive positions of one patch row (rows are padded to whole quads), 64 quads = 256
+    // positions to an instruction, NQB such blocks per channel; the wavefronts take (block, channel) pairs in turn.
+    constexpr bool XQ = conv_dl_quads(sizeof(T), POOL_IN, UP_IN);
+    constexpr int NQB = XMAX / 256, NXI = (NQB * kCK + 3) / 4;
+    constexpr bool ONEBLK = 4 % NQB == 0;              // a wavefront always meets the same block
+    constexpr int NXB = ONEBLK ? 1 : NXI;
     // bfloat matrix-core path: the filter slice is ROWS rows of [BM][8 bfloats]; a row is (tap, the stage's 8
     // channels) for 3x3 (9 taps + 1 row of zeros) and (channels 8r .. 8r+7) for 1x1; step s multiplies rows 2s, 2s+1
     constexpr int ROWS = K == 3 ? 10 : kCK / 8;
@@ -298,7 +346,7 @@ k_conv_mfma_dl(MfmaConvArgs a)
     }
     const int stack = vgroup / a.mblocks, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.rect.x0[tj], x1 = a.rect.x1[tj], y0 = a.rect.y0[ti], y1 = a.rect.y1[ti];
-    const TileGeom g = tile_geom<S, P>(a, x0, x1, y0, y1, vtile);
+    const TileGeom g = tile_geom<S, P, XQ>(a, x0, x1, y0, y1, vtile);
     if (g.empty) return;
     const int m0 = (vgroup % a.mblocks) * BM;
     const int PW = g.PW, CS = a.cs;                    // CS: whole 64-position blocks cover every patch
@@ -317,11 +365,40 @@ k_conv_mfma_dl(MfmaConvArgs a)
     const int npos = g.npos;
     const View& sv = DELTA_IN ? a.din : a.in;
     const T* src = (const T*)sv.p + (long long)stack * sv.ss + (long long)g.n_a * sv.ns;
-    unsigned xoff[MAXPOS];
+    unsigned xoff[XQ ? NXB : MAXPOS];
     int moff[MAXPOS];               // POOL_IN: element offset in the code map (channel 0), this position's place in its window in the top bits
+    unsigned xfix[NXB];             // XQ: elements of the lane's quad that lie beside the map (zero padding): cleared once the quad has landed
     const uint8_t* __restrict__ msk = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)g.n_a * a.mask.ns;
+    if constexpr (XQ) {
+        // The buffer starts 4 elements in front of the images' first element, so that a quad that begins beside the map's
+        // left border still has a non-negative offset (the maps lie inside the workspace, which has margins).
+        src -= 4;
 #pragma unroll
-    for (int j = 0; j < MAXPOS; ++j) {
+        for (int ub = 0; ub < NXB; ++ub) {
+            const int blk = ONEBLK ? wave % NQB : (wave + 4 * ub) % NQB;
+            const int s = 4 * (blk * 64 + lane);
+            xoff[ub] = kOobOffset; xfix[ub] = 0;
+            if (s < npos) {
+                const int pr = s / PW, c = s - pr * PW;
+                int k = 0, lr = pr, ybase = g.y_a * S;
+                if (pr >= g.first_cnt) {
+                    const int t = pr - g.first_cnt;
+                    k = 1 + t / g.per_cnt; lr = t - (k - 1) * g.per_cnt; ybase = 0;
+                }
+                const int gy = y0 * S + ybase + lr - P, gx = g.ox0 * S - P + c;
+                // rows no valid output pixel of this stack reads may lie outside the view; columns beside the needed ones
+                // just bring along what lies there (never multiplied into a valid pixel)
+                if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gy >= a.iy0[ti] && gy <= a.iy1[ti] && gx + 3 >= 0 && gx < a.Wc) {
+                    xoff[ub] = ES * (unsigned)(4 + k * (int)sv.ns + (gy - sv.y0[ti]) * sv.pitch + (gx - sv.x0[tj]));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (gx + e < 0 || gx + e >= a.Wc) xfix[ub] |= 1u << e;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < (XQ ? 0 : MAXPOS); ++j) {
         const int s = tid + j * 256;
         xoff[j] = kOobOffset; moff[j] = 0;
         if (s < npos) {
@@ -358,8 +435,15 @@ k_conv_mfma_dl(MfmaConvArgs a)
     // filter: a load instruction covers 64 consecutive floats of the slice; with BM >= 64 that is (part of) one
     // row, with BM = 32 two rows (two consecutive reduction channels)
     // (bfloat path: one 16-byte load per lane = the 8 bfloats of one output channel; 64 channels to an instruction)
+    // (fp32 slices whose 1 KB pieces hold rows of one tap only: 16 bytes per lane, lane -> (row of the piece, 4 channels))
+    constexpr bool W16 = !BF && kCK % (256 / BM) == 0 && WF % 256 == 0;
     unsigned woff;
-    {
+    int wrow = 0;
+    if constexpr (W16) {
+        const int col = 4 * (lane % (BM / 4));
+        wrow = lane / (BM / 4);
+        woff = m0 + col < a.Mtot ? 4u * (unsigned)(wrow * a.Mtot + col) : kOobOffset;
+    } else {
         const int col = BM >= 64 ? (wave % (BM / 64 > 0 ? BM / 64 : 1)) * 64 + lane : (lane & 31);
         woff = m0 + col < a.Mtot ? 4u * (unsigned)((BM >= 64 ? 0 : (lane >> 5) * a.Mtot) + col) : kOobOffset;
     }
@@ -396,11 +480,24 @@ k_conv_mfma_dl(MfmaConvArgs a)
                 }
             }
         }
+        if constexpr (W16) {
+            // a load instruction covers 256 consecutive floats of the slice: 16 bytes per lane, RPP rows of one tap
+            constexpr int RPP = 256 / BM, WP4 = WF / 256;
+#pragma unroll
+            for (int u = 0; u < (WP4 + 3) / 4; ++u) {
+                const int idx = wave + 4 * u;
+                if (idx >= WP4) break;
+                const int row0 = idx * RPP, tap = row0 / kCK, k0 = row0 - tap * kCK;
+                const unsigned so = 4u * (unsigned)((tap * a.C + c0 + k0) * a.Mtot + m0);
+                const unsigned vo = c0 + k0 + wrow < a.C ? woff : kOobOffset;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_LDS_PTR(Wl + idx * 256), 16, vo, so, 0, 0);
+            }
+        }
 #pragma unroll
         for (int u = 0; u < WINSTR; ++u) {
             const int idx = wave + 4 * u;                              // 64-dword piece of the slice
             if (idx >= WPIECES) break;
-            if constexpr (BF) continue;
+            if constexpr (BF || W16) continue;
             const int row = BM >= 64 ? idx / (BM / 64 > 0 ? BM / 64 : 1) : 2 * idx;
             const int tap = row / kCK, k = row - tap * kCK;
             const unsigned so = 4u * (unsigned)((tap * a.C + c0 + k) * a.Mtot + m0);
@@ -409,8 +506,20 @@ k_conv_mfma_dl(MfmaConvArgs a)
             else          vo = c0 + k + (lane >> 5) < a.C ? woff : kOobOffset;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_LDS_PTR(Wl + idx * 64), 4, vo, so, 0, 0);
         }
+        if constexpr (XQ) {
 #pragma unroll
-        for (int j = 0; j < MAXPOS; ++j) {
+            for (int u = 0; u < NXI; ++u) {
+                const int id = wave + 4 * u;
+                const int blk = id % NQB, k = id / NQB;
+                if (id < NQB * kCK && blk * 256 < npos) {
+                    const unsigned vo = c0 + k < a.C ? xoff[ONEBLK ? 0 : u] : kOobOffset;
+                    const unsigned so = ES * (unsigned)((c0 + k) * (int)sv.cs);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_LDS_PTR(Xl + k * CS + blk * 256), 16, vo, so, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < (XQ ? 0 : MAXPOS); ++j) {
             const int blk = wave + 4 * j;
             if (blk * 64 < npos) {
 #pragma unroll
@@ -489,17 +598,37 @@ k_conv_mfma_dl(MfmaConvArgs a)
         }
     };
 
+    // XQ: once this wavefront's quads of a stage have landed, the elements beside the map become the zero padding
+    auto fixup = [&](float* buf) {
+        if constexpr (XQ) {
+            float* Xl = buf + WF;
+#pragma unroll
+            for (int u = 0; u < NXI; ++u) {
+                const int id = wave + 4 * u;
+                const int blk = id % NQB, k = id / NQB;
+                const unsigned f = xfix[ONEBLK ? 0 : u];
+                if (id < NQB * kCK && f) {
+                    float* q = Xl + k * CS + blk * 256 + 4 * lane;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if ((f >> e) & 1u) q[e] = 0.0f;
+                }
+            }
+        }
+    };
     const int nst = (a.C + kCK - 1) / kCK;
     load_codes(0);
     issue(bufA, 0);                                     // (waits for the codes it selects by)
     load_codes(kCK);
     for (int st = 0; st < nst; st += 2) {
         __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's share of the stage has landed
+        fixup(bufA);
         __syncthreads();                               // ... and everybody's; the other buffer is free again
         if (st + 1 < nst) { issue(bufB, (st + 1) * kCK); load_codes((st + 2) * kCK); }
         multiply(bufA);
         if (st + 1 < nst) {
             __builtin_amdgcn_s_waitcnt(0x0F70);
+            fixup(bufB);
             __syncthreads();
             if (st + 2 < nst) { issue(bufA, (st + 2) * kCK); load_codes((st + 3) * kCK); }
             multiply(bufB);
@@ -514,7 +643,8 @@ namespace {
 struct TileChoice { int TC, tiles_x, tiles_r, cap, cs, max_img; };
 
 // Tile capacity (pixels or pool windows), column blocking and the worst-case patch size over all stacks.
-TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int S, int P, int max_pos)
+// quad: patch rows are padded to a multiple of 4 positions (the kernel loads them 4 positions to a lane).
+TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int S, int P, int max_pos, bool quad)
 {
     TileChoice c;
     int mw = 0;
@@ -560,7 +690,8 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
                 int nimg = (trf + rh - 2) / rh + 1; if (nimg > batch) nimg = batch;
                 if (nimg > c.max_img) c.max_img = nimg;
                 const int rows = trf < rtot ? trf : rtot;
-                const int npos = (S * rows + 2 * P * nimg) * (tc * S + 2 * P);
+                const int pw = quad ? (tc * S + 2 * P + 3) & ~3 : tc * S + 2 * P;
+                const int npos = (S * rows + 2 * P * nimg) * pw;
                 if (npos > c.cs) c.cs = npos;
                 if (npos > max_pos && trf > 1) fits = false;
             }
@@ -612,7 +743,7 @@ void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 // filled round of a launch leaves CUs idle: few large workgroups waste most there, many small ones least, while
 // larger ones re-read less.  cost = (full rounds + the last round's depth per CU) x work of one workgroup.
 template <int K, bool POOL_OUT, bool STRIDED_FWD>
-DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc_out)
+DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, bool quad, TileChoice* tc_out)
 {
     const int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
     DlShape best = {0, 0, 0}; double best_cost = 0;
@@ -628,8 +759,8 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc
     // does best with the most workgroups per CU: 64 channels x 128 pixels; config 5: 14.6 -> 14.4 ms per step)
     const bool small_wg = c.bf16 && K == 3 && !STRIDED_FWD && c.S == 1 && BM == 64;
     auto consider = [&](int bm, int BN) -> long long {
-        const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD);
-        const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos);
+        const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD, quad);
+        const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos, quad);
         if (tc.cs > max_pos) return -1;
         // tiles that exist: every stack has its own count, the grid is sized for the largest
         long long wgs = 0;
@@ -658,7 +789,7 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, TileChoice* tc
         // ... unless 128-pixel tiles (32 pool windows) fit the rows of the rectangles badly: a row of 19 windows leaves
         // 13 of 32 slots empty, while three such rows fill 57 of 64 (config 5, the 32 -> 64 layer: 0.68 -> 0.58 ms)
         long long units = 0, slots = 0;
-        const TileChoice t128 = choose_tile(a.rect, c.N, c.M, c.batch, 32, S, K / 2, conv_dl_max_positions(K, 128, STRIDED_FWD));
+        const TileChoice t128 = choose_tile(a.rect, c.N, c.M, c.batch, 32, S, K / 2, conv_dl_max_positions(K, 128, STRIDED_FWD, quad), quad);
         for (int i = 0; i < c.N; ++i)
             for (int j = 0; j < c.M; ++j) {
                 const int rw = a.rect.x1[j] - a.rect.x0[j] + 1, rh = a.rect.y1[i] - a.rect.y0[i] + 1;
@@ -689,12 +820,21 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
 {
     constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN;
     TileChoice td;
-    const DlShape sh = choose_dl_shape<K, POOL_OUT, STRIDED_FWD>(a, c, &td);
+    // fp32 patches are loaded 16 bytes a lane, a few bytes beyond the ends of map rows: only inside the workspace
+    constexpr bool quad = conv_dl_quads(sizeof(T), POOL_IN && DELTA_IN, STRIDE == 2 && DELTA_IN);
+    if (quad && !(DELTA_IN ? c.din_ws : c.in_ws)) return 1;
+    const DlShape sh = choose_dl_shape<K, POOL_OUT, STRIDED_FWD>(a, c, quad, &td);
     if (!sh.BM) return 1;
     // (the kernel keeps code-map offsets in 29 bits)
     if (POOL_IN && DELTA_IN && (double)td.max_img * (double)a.mask.ns >= 5.0e8) return 1;
     if (!offsets_fit_32bit(a, DELTA_IN ? a.din : a.in, td.max_img, K)) return 1;
-    a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = (td.cs + 63) & ~63;
+    // (the epilogue's buffer stores: the images a tile spans plus all output channels, maps and code bytes alike)
+    {
+        const View& ov = DELTA_IN ? a.dout : a.out;
+        if (4.0 * ((double)td.max_img * (double)ov.ns + ((double)a.Mtot + 8.0) * (double)ov.cs) >= 2.0e9) return 1;
+        if (POOL_OUT && !DELTA_IN && (double)td.max_img * (double)a.mask.ns + ((double)a.Mtot + 8.0) * (double)a.mask.cs >= 2.0e9) return 1;
+    }
+    a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = quad ? (td.cs + 255) & ~255 : (td.cs + 63) & ~63;
     a.mblocks = (a.Mtot + sh.BM - 1) / sh.BM; a.stacks = c.N * c.M;
     // XCD order pays where several channel blocks compete for the L2 and the groups spread evenly over the 8 XCDs;
     // with one channel block the plain order (neighbouring tiles on different XCDs) balances better
