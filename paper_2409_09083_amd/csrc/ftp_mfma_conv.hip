@@ -143,6 +143,16 @@ __device__ __forceinline__ void store_elem(__amdgpu_buffer_rsrc_t r, unsigned vo
     __builtin_amdgcn_raw_buffer_store_b16((uint16_t)bf16_bits(v), r, vo, so, 0);
 }
 
+// ... of a value that already is what the map holds (a bfloat widened to fp32: its upper half is stored)
+__device__ __forceinline__ void store_rounded(__amdgpu_buffer_rsrc_t r, unsigned vo, unsigned so, float v, const float*)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, vo, so, 0);
+}
+__device__ __forceinline__ void store_rounded(__amdgpu_buffer_rsrc_t r, unsigned vo, unsigned so, float v, const bf16_t*)
+{
+    __builtin_amdgcn_raw_buffer_store_b16((uint16_t)(__float_as_uint(v) >> 16), r, vo, so, 0);
+}
+
 template <typename T, int K, int S, int WAVES_M, int MT, bool POOL_OUT, bool DELTA_IN, int NT>
 __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileGeom& g, v16f (&acc)[MT][NT], float* bias_lds,
                                               int m0, int x0, int x1, int y0, int stack, int ti, int tj)
@@ -207,11 +217,38 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
             }
         return;
     }
+    // While another workgroup's wavefront keeps the matrix cores of this SIMD busy, every vector-ALU instruction issued
+    // here waits for a gap between its instructions, so the loop below is written for few of them: the bias is added in a
+    // pass of its own that layers without bias skip, the sign bits are collected with constant masks and brought into
+    // place once per word, scalar offsets carry the channel.
     float slope = a.slope;
     asm volatile("" : "+v"(slope));
+    if (a.bias) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const float4 b4 = *(const float4*)(bias_lds + (wave_m * MT + mt) * 32 + 8 * g4 + 4 * hi);
+                const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[mt][t][4 * g4 + e] += bb[e];
+            }
+    }
     const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc(
         POOL_OUT ? (void*)((uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)g.n_a * a.mask.ns) : (void*)ov.p, (short)0, (int)0x7FFFFFFF, 0x00020000);
     const unsigned mcs = (unsigned)a.mask.cs;
+    // which of the lane's 4 groups of 4 channels exist, as a mask over its 16 sign bits (before they are shifted by 4 * hi)
+    uint32_t gmask[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int mb = m0 + (wave_m * MT + mt) * 32;
+        gmask[mt] = 0;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+            if (mb + 8 * g4 + 4 * hi < a.Mtot) gmask[mt] |= 0xFu << (8 * g4);
+    }
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int q = (wave_n * NT + t) * 32 + l32;
@@ -227,32 +264,41 @@ __device__ __forceinline__ void conv_epilogue(const MfmaConvArgs& a, const TileG
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int mb = m0 + (wave_m * MT + mt) * 32;
-            uint32_t signs = 0;                                 // this lane's 16 channels of the block's sign word
+            uint32_t signs = 0;                                 // this lane's 16 channels of the block's sign word, bits 8 * g4 + e
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                const bool gok = mb + 8 * g4 + 4 * hi < a.Mtot;
+                const bool gok = (gmask[mt] >> (8 * g4)) & 1u;
                 const unsigned vg = gok ? vo : 0x80000000u, mvg = gok ? mvo : 0x80000000u;
-                const float4 b4 = *(const float4*)(bias_lds + (wave_m * MT + mt) * 32 + 8 * g4 + 4 * hi);
-                const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int i = 4 * g4 + e;
                     // compared and recorded as the map will hold it (rounded to the storage type)
-                    float v = stored(leaky(acc[mt][t][i] + bb[e], slope), (const T*)nullptr);
+                    float v;
+                    bool pos;
                     int bi = 0;
-                    if (POOL_OUT) {
-                        // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
-                        const float o1 = quad_xor<1>(v), o2 = quad_xor<2>(v), o3 = quad_xor<3>(v);
-                        if (o1 > v) { v = o1; bi = 1; }
-                        if (o2 > v) { v = o2; bi = 2; }
-                        if (o3 > v) { v = o3; bi = 3; }
+                    if constexpr (sizeof(T) == 4 && !POOL_OUT) {
+                        // (slopes are >= 0, so the activation is positive exactly where the convolution's result is)
+                        const float z = acc[mt][t][i];
+                        pos = z > 0.0f;
+                        v = pos ? z : slope * z;
+                    } else {
+                        v = stored(leaky(acc[mt][t][i], slope), (const T*)nullptr);
+                        if (POOL_OUT) {
+                            // the 4 pixels of a window sit in 4 adjacent lanes, in window order; the first lane decides
+                            const float o1 = quad_xor<1>(v), o2 = quad_xor<2>(v), o3 = quad_xor<3>(v);
+                            if (o1 > v) { v = o1; bi = 1; }
+                            if (o2 > v) { v = o2; bi = 2; }
+                            if (o3 > v) { v = o3; bi = 3; }
+                        }
+                        pos = v > 0.0f;
                     }
                     const unsigned so = (unsigned)(mb + 8 * g4 + e);
-                    store_elem(orsrc, vg, so * ocs, v, (const T*)nullptr);
-                    if (POOL_OUT) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)((bi << 1) | (v > 0.0f ? 1 : 0)), mrsrc, mvg, so * mcs, 0);
-                    if (gok && pvalid) signs |= (v > 0.0f ? 1u : 0u) << (8 * g4 + 4 * hi + e);
+                    store_rounded(orsrc, vg, so * ocs, v, (const T*)nullptr);
+                    if (POOL_OUT) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)((bi << 1) | (pos ? 1 : 0)), mrsrc, mvg, so * mcs, 0);
+                    signs |= (pos ? 1u : 0u) << (8 * g4 + e);
                 }
             }
+            signs = (pvalid ? signs & gmask[mt] : 0u) << (4 * hi);
             // the other half of the block's channels sits 32 lanes away (same pixel)
             signs |= (uint32_t)__shfl_xor((int)signs, 32, 64);
             if (powned && hi == 0 && mb < a.Mtot)
