@@ -24,6 +24,7 @@
 // so larger filters are split over blockIdx.x, each part staging the same chunks.
 #include "ftp_device.h"
 #include "ftp_launch.h"
+#include <type_traits>
 
 namespace ftp {
 
@@ -95,17 +96,66 @@ k_wgrad_mfma(MfmaWgradArgs a)
     };
 
     // Registers that carry one chunk from HBM to LDS.  Lane -> position (pixel of dZ, patch position of X,
-    // both row-major over the chunk), wavefront -> every fourth channel; all loads are unconditional (clamped
-    // addresses) and independent, so they are in flight together, and what must be zero is zeroed at the
-    // LDS write.  zinfo: bit 0 position exists, bit 1 padding column, bits 2-3 the pixel's place in its pool
+    // both row-major over the chunk), wavefront -> every fourth channel; all loads are independent, so they are in flight
+    // together.  16-bit maps: the loads are unconditional (clamped addresses) and what must be zero is zeroed at the LDS
+    // write; fp32 maps: a lane that has nothing to stage loads from beyond the buffer's records (= 0).  zinfo: bit 0 position exists, bit 1 padding column, bits 2-3 the pixel's place in its pool
     // window.  xinfo: per pass bit 0 position exists, bit 1 inside the map.
     // zinfo bit 4: the position lies in the pixel list rounded up to a multiple of 8 (bfloat path; zero if it does not
     // exist); zpos: XP * patch position of the pixel.
     uint32_t zm[NZ]; float zg[NZ]; float xg[DL ? 1 : XPASS][DL ? 1 : NX];
     int zinfo = 0, xinfo = 0, zpos = 0;
 
+    // fp32 path: which (image, row, column) of a chunk a lane stages never changes from chunk to chunk - chunks of
+    // several images hold whole rectangles, all others one image - so the divisions are done once, here.  (While the
+    // other workgroup's wavefront keeps this SIMD's matrix cores busy, every vector-ALU instruction of the staging code
+    // waits for a gap between its instructions: the per-chunk part is kept to a few of them.)
+    int z_il = 0, z_r = 0, z_c = 0;
+    int x_il[DL ? XPASS : 1], x_r[DL ? XPASS : 1], x_c[DL ? XPASS : 1];
+    if constexpr (DL) {
+        const int zrow = lane / TCp;
+        z_c = lane - zrow * TCp;
+        if (TI > 1) { z_il = zrow / rh; z_r = zrow - z_il * rh; } else { z_r = zrow; }
+        const int nph_all = S * rh + 2 * P;
+#pragma unroll
+        for (int pass = 0; pass < XPASS; ++pass) {
+            const int pp = lane + 64 * pass;
+            const int prow = pp / PW;
+            x_c[pass] = pp - prow * PW;
+            if (TI > 1) { x_il[pass] = prow / nph_all; x_r[pass] = prow - x_il[pass] * nph_all; } else { x_il[pass] = 0; x_r[pass] = prow; }
+        }
+    }
+    // whole blocks of channels (every layer of the paper's networks): no per-channel range checks in the staging code
+    const bool co_full = co0 + BCO <= a.Cout, ci_full = ci0 + BCI <= a.Cin;
+
+    // fp32: buffer loads - one 32-bit offset per lane, the channel as a scalar offset; a lane without a pixel (beyond
+    // the chunk, padding column) loads from beyond the buffer's records and receives the zero it has to stage
+    auto load_dl = [&](const Chunk& c, auto full) {
+        if constexpr (DL) {
+            const bool ok = z_il < c.ni && z_r < c.nr && z_c < c.nc;
+            const int qy = c.yb + z_r, qx = c.xb + z_c;
+            const int sy = HALF_RES ? (qy >> 1) : qy, sx = HALF_RES ? (qx >> 1) : qx;
+            zinfo = (((qy & 1) << 1) | (qx & 1)) << 2;
+            const T* gbase = (const T*)a.din.p + (long long)stack * a.din.ss + (long long)c.n0 * a.din.ns;
+            const __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc((void*)gbase, (short)0, 0x7FFFFFFF, 0x00020000);
+            const unsigned gvo = ok ? 4u * (unsigned)(z_il * (int)a.din.ns + (sy - a.din.y0[ti]) * a.din.pitch + (sx - a.din.x0[tj])) : 0x80000000u;
+            const uint8_t* mbase = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)c.n0 * a.mask.ns;
+            const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)mbase, (short)0, 0x7FFFFFFF, 0x00020000);
+            const unsigned mvo = (POOL && ok) ? (unsigned)(z_il * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj])) : 0x80000000u;
+#pragma unroll
+            for (int k = 0; k < NZ; ++k) {
+                const int ch = wave + 4 * k;
+                unsigned gv = gvo, mv = mvo;
+                if constexpr (!decltype(full)::value)
+                    if (co0 + ch >= a.Cout) { gv = 0x80000000u; mv = 0x80000000u; }
+                zm[k] = POOL ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(mrsrc, mv, (unsigned)((co0 + ch) * (int)a.mask.cs), 0) : 0u;      // only the pool winner is needed
+                zg[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(grsrc, gv, 4u * (unsigned)((co0 + ch) * (int)a.din.cs), 0));
+            }
+        }
+    };
     auto load = [&](const Chunk& c) {
-        {
+        if constexpr (DL) {
+            if (co_full) load_dl(c, std::true_type{}); else load_dl(c, std::false_type{});
+        } else {
             const int npos = c.ni * c.nr * TCp;
             const bool ok = lane < npos;
             const int p = ok ? lane : 0;
@@ -115,22 +165,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
             const int sy = HALF_RES ? (qy >> 1) : qy, sx = HALF_RES ? (qx >> 1) : qx;
             zinfo = (ok ? 1 : 0) | (zc >= c.nc ? 2 : 0) | ((((qy & 1) << 1) | (qx & 1)) << 2) | (lane < ((npos + 7) & ~7) ? 16 : 0);
             zpos = ok ? ((il * (c.nr + 2 * P) + r) * PW + zc) * XP : 0;
-            if constexpr (DL) {
-                // fp32: buffer loads - one 32-bit offset per lane, the channel as a scalar offset
-                const T* gbase = (const T*)a.din.p + (long long)stack * a.din.ss + (long long)c.n0 * a.din.ns;
-                const __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc((void*)gbase, (short)0, 0x7FFFFFFF, 0x00020000);
-                const unsigned gvo = 4u * (unsigned)(il * (int)a.din.ns + (sy - a.din.y0[ti]) * a.din.pitch + (sx - a.din.x0[tj]));
-                const uint8_t* mbase = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)c.n0 * a.mask.ns;
-                const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)mbase, (short)0, 0x7FFFFFFF, 0x00020000);
-                const unsigned mvo = POOL ? (unsigned)(il * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj])) : 0u;
-#pragma unroll
-                for (int k = 0; k < NZ; ++k) {
-                    const int ch = wave + 4 * k;
-                    const int co = co0 + ch < a.Cout ? co0 + ch : a.Cout - 1;
-                    zm[k] = POOL ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(mrsrc, mvo, (unsigned)(co * (int)a.mask.cs), 0) : 0u;      // only the pool winner is needed
-                    zg[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(grsrc, gvo, 4u * (unsigned)(co * (int)a.din.cs), 0));
-                }
-            } else {
+            {
                 const uint8_t* mp = at<uint8_t>(a.mask, stack, ti, tj, c.n0 + il, 0, sy, sx);
                 const T* gp = at<T>(a.din, stack, ti, tj, c.n0 + il, 0, sy, sx);
 #pragma unroll
@@ -170,6 +205,18 @@ k_wgrad_mfma(MfmaWgradArgs a)
     };
 
     auto store = [&]() {
+        if constexpr (DL) {
+            // (lanes without a pixel received zeros; those beyond the chunk write them where nothing is read)
+            float* zdst = Zl + lane * ZP;
+            const uint32_t code = (uint32_t)(zinfo >> 2) & 3u;
+#pragma unroll
+            for (int k = 0; k < NZ; ++k) {
+                float v = zg[k];                                       // the delta maps hold dLoss/dZ
+                if (POOL && ((zm[k] >> 1) & 3u) != code) v = 0.0f;
+                zdst[wave + 4 * k] = v;
+            }
+            return;
+        }
         if (!DL) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): every load of the chunk has landed
         if (zinfo & (BF ? 16 : 1)) {
             float* zdst = Zl + lane * ZP;
@@ -202,25 +249,25 @@ k_wgrad_mfma(MfmaWgradArgs a)
 
     // DL: one chunk's patch, HBM -> LDS.  Lane -> patch position (64 to an instruction), wavefront -> every fourth
     // channel.  Returns the number of load instructions this wavefront issued.
-    auto issue_x = [&](const Chunk& c) -> int {
+    auto issue_x_dl = [&](const Chunk& c, auto full) -> int {
         int issued = 0;
         if constexpr (DL) {
-            const int nph = S * c.nr + 2 * P, npos = c.ni * nph * PW;
+            const int nph = S * c.nr + 2 * P, npos = c.ni * nph * PW, ncn = S * c.nc + 2 * P;
             const T* base = (const T*)a.in.p + (long long)stack * a.in.ss + (long long)c.n0 * a.in.ns;
             const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, (short)0, 0x7FFFFFFF, 0x00020000);
+            const int gy0 = S * c.yb - P, gx0 = S * c.xb - P;
 #pragma unroll
             for (int pass = 0; pass < XPASS; ++pass) {
                 if (pass * 64 < npos) {
-                    const int p = lane + 64 * pass;
-                    const int prow = p / PW, xc = p - prow * PW;
-                    const int il = prow / nph, r = prow - il * nph;
-                    const int gy = S * c.yb - P + r, gx = S * c.xb - P + xc;
-                    const bool inside = p < npos && xc < S * c.nc + 2 * P && gy >= 0 && gy < a.Hc && gx >= 0 && gx < a.Wc;
-                    const unsigned vo = inside ? 4u * (unsigned)(il * (int)a.in.ns + (gy - a.in.y0[ti]) * a.in.pitch + (gx - a.in.x0[tj])) : 0x80000000u;
+                    const int gy = gy0 + x_r[pass], gx = gx0 + x_c[pass];
+                    const bool inside = x_il[pass] < c.ni && x_r[pass] < nph && x_c[pass] < ncn && (unsigned)gy < (unsigned)a.Hc && (unsigned)gx < (unsigned)a.Wc;
+                    const unsigned vo = inside ? 4u * (unsigned)(x_il[pass] * (int)a.in.ns + (gy - a.in.y0[ti]) * a.in.pitch + (gx - a.in.x0[tj])) : 0x80000000u;
 #pragma unroll
                     for (int k = 0; k < NX; ++k) {
                         const int ch = wave + 4 * k;
-                        const unsigned v = ci0 + ch < a.Cin ? vo : 0x80000000u;
+                        unsigned v = vo;
+                        if constexpr (!decltype(full)::value)
+                            if (ci0 + ch >= a.Cin) v = 0x80000000u;
                         const unsigned so = 4u * (unsigned)((ci0 + ch) * (int)a.in.cs);
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(Xl + ch * XS + pass * 64), 4, v, so, 0, 0);
                     }
@@ -229,6 +276,10 @@ k_wgrad_mfma(MfmaWgradArgs a)
             }
         }
         return issued;
+    };
+    auto issue_x = [&](const Chunk& c) -> int {
+        if constexpr (DL) return ci_full ? issue_x_dl(c, std::true_type{}) : issue_x_dl(c, std::false_type{});
+        return 0;
     };
     // waits until at most `n` of this wavefront's loads are outstanding (loads return in order)
     auto wait_vm = [&](int n) {
