@@ -87,8 +87,9 @@ struct TileGeom {
     bool empty;
 };
 
-// Q: the patch is loaded four positions to a lane, so a patch row is padded to whole quads.
-template <int S, int P, bool Q>
+// Q: positions of a patch row a lane loads at once (0: one; 4: fp32 quads; 8: packed bfloats, whose rows start up to one
+// position early, on the dword grid of the map): patch rows are padded to whole units.
+template <int S, int P, int Q>
 __device__ __forceinline__ TileGeom tile_geom(const MfmaConvArgs& a, int x0, int x1, int y0, int y1, int bx)
 {
     TileGeom g;
@@ -104,7 +105,8 @@ __device__ __forceinline__ TileGeom tile_geom(const MfmaConvArgs& a, int x0, int
     g.n_a = g.R0 / g.rh; g.y_a = g.R0 - g.n_a * g.rh;
     const int n_l = (g.R0 + g.nrows - 1) / g.rh;
     g.PW = g.TC * S + 2 * P;
-    if (Q) g.PW = (g.PW + 3) & ~3;
+    if (Q == 4) g.PW = (g.PW + 3) & ~3;
+    if (Q == 8) g.PW = (g.PW + 1 + 7) & ~7;
     const int first_rows = g.rh - g.y_a < g.nrows ? g.rh - g.y_a : g.nrows;
     g.first_cnt = S * first_rows + 2 * P;
     g.per_cnt = S * g.rh + 2 * P;
@@ -327,11 +329,16 @@ constexpr unsigned kBufRecords = 0x7FFFFFFFu;
 // (the bfloat matrix-core path takes 8 channels of a 3x3 filter per stage: one instruction multiplies 8 of them)
 __host__ __device__ constexpr int conv_dl_stage_channels(int K, bool strided_fwd, bool bf_mfma) { return K >= 5 ? 2 : (K == 1 && !strided_fwd) ? 16 : bf_mfma ? 8 : 4; }
 __host__ __device__ constexpr bool conv_dl_quads(size_t elem, bool pool_in, bool up_in) { return elem == 4 && !pool_in && !up_in; }
+// 16-bit maps on the bfloat matrix-core path (stride-1 1x1 / 3x3), patch not gathered through pool winners: the patch may
+// stay packed in LDS, two bytes a position, loaded 8 positions (16 bytes) a lane
+__host__ __device__ constexpr bool conv_dl_packable(size_t elem, int K, int stride, bool pool_in) { return elem == 2 && K <= 3 && stride == 1 && !pool_in; }
 // (a multiple of 256; quads pad every patch row to a multiple of 4 positions, which costs the narrow rectangles of deep
 // layers up to a fifth more positions: their 128-pixel tiles get the room of the 256-pixel ones)
-__host__ __device__ constexpr int conv_dl_max_positions(int K, int BN, bool strided_fwd, bool quad)          // patch positions in LDS
+// (packed bfloats: twice the positions in the same bytes, in blocks of 512)
+__host__ __device__ constexpr int conv_dl_max_positions(int K, int BN, bool strided_fwd, bool quad, bool packed = false)          // patch positions in LDS
 {
-    return strided_fwd ? 768 : K >= 5 ? (BN == 256 ? 768 : 512) : K == 1 ? 256 : (BN == 256 || quad ? 512 : 256);
+    return packed ? (K == 3 && BN == 256 ? 1024 : 512)
+                  : strided_fwd ? 768 : K >= 5 ? (BN == 256 ? 768 : 512) : K == 1 ? 256 : (BN == 256 || quad ? 512 : 256);
 }
 
 // POOL_IN (delta back-propagation through a fused pool): the patch lives at the convolution output, the delta at
@@ -342,10 +349,11 @@ __host__ __device__ constexpr int conv_dl_max_positions(int K, int BN, bool stri
 // STRIDE = 2, delta back-propagation: the adjoint of a strided convolution is the stride-1 one applied to the
 // deltas with zeros inserted between them; a patch position at even coordinates loads delta (y/2, x/2), every
 // other one loads from an out-of-range offset (three quarters of the matrix-core work multiply zeros).
-template <typename T, int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE>
+template <typename T, int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE, bool PACK>
 __global__ void __launch_bounds__(256, 2)
 k_conv_mfma_dl(MfmaConvArgs a)
 {
+    static_assert(!PACK || conv_dl_packable(sizeof(T), K, STRIDE, POOL_IN), "packed patches: bfloat matrix-core path only");
     static_assert(STRIDE == 1 || !(POOL_OUT || POOL_IN), "strided convolutions with a fused pool take the direct kernels");
     constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN, UP_IN = STRIDE == 2 && DELTA_IN, HALF_IN = POOL_IN || UP_IN;
     constexpr unsigned ES = sizeof(T);                 // bytes per map element
@@ -356,13 +364,18 @@ k_conv_mfma_dl(MfmaConvArgs a)
     constexpr int kCK = conv_dl_stage_channels(K, STRIDED_FWD, BF);
     constexpr int KK = K * K, P = K / 2;
     constexpr int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
-    constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD, conv_dl_quads(sizeof(T), POOL_IN, UP_IN));
+    constexpr bool XH = PACK;                          // the patch stays packed: [channel][position] bfloats
+    constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD, conv_dl_quads(sizeof(T), POOL_IN, UP_IN), XH);
     constexpr int MAXPOS = XMAX / 256;
     // fp32 patches (not those gathered element by element through pool winners or between inserted zeros) travel 16
     // bytes a lane: a quad of consecutive positions of one patch row (rows are padded to whole quads), 64 quads = 256
     // positions to an instruction, NQB such blocks per channel; the wavefronts take (block, channel) pairs in turn.
+    // Packed bfloat patches travel the same way, 8 positions (16 bytes) a lane, 512 positions to an instruction; their rows
+    // begin on the dword grid of the map (up to one position before the first column the tile needs).
     constexpr bool XQ = conv_dl_quads(sizeof(T), POOL_IN, UP_IN);
-    constexpr int NQB = XMAX / 256, NXI = (NQB * kCK + 3) / 4;
+    constexpr bool XW = XQ || XH;                      // wide loads
+    constexpr int NPL = XH ? 8 : 4;                    // positions per lane
+    constexpr int NQB = XMAX / (64 * NPL), NXI = (NQB * kCK + 3) / 4;
     constexpr bool ONEBLK = 4 % NQB == 0;              // a wavefront always meets the same block
     constexpr int NXB = ONEBLK ? 1 : NXI;
     // bfloat matrix-core path: the filter slice is ROWS rows of [BM][8 bfloats]; a row is (tap, the stage's 8
@@ -372,8 +385,9 @@ k_conv_mfma_dl(MfmaConvArgs a)
     constexpr int WPIECES = WF / 64;                   // 64-dword pieces of the slice, dealt round-robin to the 4 wavefronts
     constexpr int WINSTR = (WPIECES + 3) / 4;
     static_assert(WF % 64 == 0, "the filter slice is loaded in 64-float pieces");
-    __shared__ __attribute__((aligned(16))) float bufA[WF + kCK * XMAX];
-    __shared__ __attribute__((aligned(16))) float bufB[WF + kCK * XMAX];
+    constexpr int XDW = XH ? kCK * XMAX / 2 : kCK * XMAX;      // dwords of one stage's patch
+    __shared__ __attribute__((aligned(16))) float bufA[WF + XDW];
+    __shared__ __attribute__((aligned(16))) float bufB[WF + XDW];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -392,18 +406,20 @@ k_conv_mfma_dl(MfmaConvArgs a)
     }
     const int stack = vgroup / a.mblocks, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.rect.x0[tj], x1 = a.rect.x1[tj], y0 = a.rect.y0[ti], y1 = a.rect.y1[ti];
-    const TileGeom g = tile_geom<S, P, XQ>(a, x0, x1, y0, y1, vtile);
+    const TileGeom g = tile_geom<S, P, XH ? 8 : XQ ? 4 : 0>(a, x0, x1, y0, y1, vtile);
     if (g.empty) return;
     const int m0 = (vgroup % a.mblocks) * BM;
     const int PW = g.PW, CS = a.cs;                    // CS: whole 64-position blocks cover every patch
 
+    // packed patches: a row starts `sh` (0 or 1) positions before the tile's first patch column, where the map's dword grid falls
+    const int sh = XH ? ((g.ox0 * S - P - (DELTA_IN ? a.din : a.in).x0[tj]) & 1) : 0;
     int baseB[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int q = (wave_n * NT + t) * 32 + l32;
         const TilePix tp = tile_pix<S, P>(g, POOL_OUT ? (q >> 2) : q, x1);
         const int pos = POOL_OUT ? (q & 3) : 0;
-        baseB[t] = (tp.valid ? (tp.prow + (pos >> 1)) * PW + tp.xl * S + (pos & 1) : 0) + (BF ? 0 : hi * CS);
+        baseB[t] = (tp.valid ? (tp.prow + (pos >> 1)) * PW + tp.xl * S + (pos & 1) + sh : 0) + (BF ? 0 : hi * CS);
     }
     const int baseA = (BF ? 0 : hi * BM) + wave_m * (32 * MT) + l32;
 
@@ -411,18 +427,18 @@ k_conv_mfma_dl(MfmaConvArgs a)
     const int npos = g.npos;
     const View& sv = DELTA_IN ? a.din : a.in;
     const T* src = (const T*)sv.p + (long long)stack * sv.ss + (long long)g.n_a * sv.ns;
-    unsigned xoff[XQ ? NXB : MAXPOS];
+    unsigned xoff[XW ? NXB : MAXPOS];
     int moff[MAXPOS];               // POOL_IN: element offset in the code map (channel 0), this position's place in its window in the top bits
-    unsigned xfix[NXB];             // XQ: elements of the lane's quad that lie beside the map (zero padding): cleared once the quad has landed
+    unsigned xfix[NXB];             // wide loads: elements of the lane's unit that lie beside the map (zero padding): cleared once the unit has landed
     const uint8_t* __restrict__ msk = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)g.n_a * a.mask.ns;
-    if constexpr (XQ) {
-        // The buffer starts 4 elements in front of the images' first element, so that a quad that begins beside the map's
+    if constexpr (XW) {
+        // The buffer starts one unit in front of the images' first element, so that a unit that begins beside the map's
         // left border still has a non-negative offset (the maps lie inside the workspace, which has margins).
-        src -= 4;
+        src -= NPL;
 #pragma unroll
         for (int ub = 0; ub < NXB; ++ub) {
             const int blk = ONEBLK ? wave % NQB : (wave + 4 * ub) % NQB;
-            const int s = 4 * (blk * 64 + lane);
+            const int s = NPL * (blk * 64 + lane);
             xoff[ub] = kOobOffset; xfix[ub] = 0;
             if (s < npos) {
                 const int pr = s / PW, c = s - pr * PW;
@@ -431,20 +447,20 @@ k_conv_mfma_dl(MfmaConvArgs a)
                     const int t = pr - g.first_cnt;
                     k = 1 + t / g.per_cnt; lr = t - (k - 1) * g.per_cnt; ybase = 0;
                 }
-                const int gy = y0 * S + ybase + lr - P, gx = g.ox0 * S - P + c;
+                const int gy = y0 * S + ybase + lr - P, gx = g.ox0 * S - P - sh + c;
                 // rows no valid output pixel of this stack reads may lie outside the view; columns beside the needed ones
                 // just bring along what lies there (never multiplied into a valid pixel)
-                if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gy >= a.iy0[ti] && gy <= a.iy1[ti] && gx + 3 >= 0 && gx < a.Wc) {
-                    xoff[ub] = ES * (unsigned)(4 + k * (int)sv.ns + (gy - sv.y0[ti]) * sv.pitch + (gx - sv.x0[tj]));
+                if (g.n_a + k < a.batch && gy >= 0 && gy < a.Hc && gy >= a.iy0[ti] && gy <= a.iy1[ti] && gx + NPL - 1 >= 0 && gx < a.Wc) {
+                    xoff[ub] = ES * (unsigned)(NPL + k * (int)sv.ns + (gy - sv.y0[ti]) * sv.pitch + (gx - sv.x0[tj]));
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
+                    for (int e = 0; e < NPL; ++e)
                         if (gx + e < 0 || gx + e >= a.Wc) xfix[ub] |= 1u << e;
                 }
             }
         }
     }
 #pragma unroll
-    for (int j = 0; j < (XQ ? 0 : MAXPOS); ++j) {
+    for (int j = 0; j < (XW ? 0 : MAXPOS); ++j) {
         const int s = tid + j * 256;
         xoff[j] = kOobOffset; moff[j] = 0;
         if (s < npos) {
@@ -552,20 +568,20 @@ k_conv_mfma_dl(MfmaConvArgs a)
             else          vo = c0 + k + (lane >> 5) < a.C ? woff : kOobOffset;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_LDS_PTR(Wl + idx * 64), 4, vo, so, 0, 0);
         }
-        if constexpr (XQ) {
+        if constexpr (XW) {
 #pragma unroll
             for (int u = 0; u < NXI; ++u) {
                 const int id = wave + 4 * u;
                 const int blk = id % NQB, k = id / NQB;
-                if (id < NQB * kCK && blk * 256 < npos) {
+                if (id < NQB * kCK && blk * (64 * NPL) < npos) {
                     const unsigned vo = c0 + k < a.C ? xoff[ONEBLK ? 0 : u] : kOobOffset;
                     const unsigned so = ES * (unsigned)((c0 + k) * (int)sv.cs);
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_LDS_PTR(Xl + k * CS + blk * 256), 16, vo, so, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_LDS_PTR((char*)Xl + (int)ES * (k * CS + blk * (64 * NPL))), 16, vo, so, 0, 0);
                 }
             }
         }
 #pragma unroll
-        for (int j = 0; j < (XQ ? 0 : MAXPOS); ++j) {
+        for (int j = 0; j < (XW ? 0 : MAXPOS); ++j) {
             const int blk = wave + 4 * j;
             if (blk * 64 < npos) {
 #pragma unroll
@@ -600,10 +616,16 @@ k_conv_mfma_dl(MfmaConvArgs a)
                 for (int mt = 0; mt < MT; ++mt) av[b][mt] = *(const uint4*)(Wl + ((r * BM + baseA + 32 * mt) << 2));
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    const float* xp = Xl + baseB[t] + boff;
                     uint32_t x[8];
+                    if constexpr (XH) {
+                        const bf16_t* xp = (const bf16_t*)Xl + baseB[t] + boff;
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) x[k] = __float_as_uint(xp[k * CS]);
+                        for (int k = 0; k < 8; ++k) x[k] = xp[k * CS];
+                    } else {
+                        const float* xp = Xl + baseB[t] + boff;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) x[k] = __float_as_uint(xp[k * CS]);
+                    }
                     bv[b][t] = make_uint4(x[0] | (x[1] << 16), x[2] | (x[3] << 16), x[4] | (x[5] << 16), x[6] | (x[7] << 16));
                 }
             };
@@ -644,20 +666,20 @@ k_conv_mfma_dl(MfmaConvArgs a)
         }
     };
 
-    // XQ: once this wavefront's quads of a stage have landed, the elements beside the map become the zero padding
+    // wide loads: once this wavefront's units of a stage have landed, the elements beside the map become the zero padding
     auto fixup = [&](float* buf) {
-        if constexpr (XQ) {
-            float* Xl = buf + WF;
+        if constexpr (XW) {
+            T* Xl = (T*)(buf + WF);                    // (elements as the maps hold them)
 #pragma unroll
             for (int u = 0; u < NXI; ++u) {
                 const int id = wave + 4 * u;
                 const int blk = id % NQB, k = id / NQB;
                 const unsigned f = xfix[ONEBLK ? 0 : u];
                 if (id < NQB * kCK && f) {
-                    float* q = Xl + k * CS + blk * 256 + 4 * lane;
+                    T* q = Xl + k * CS + blk * (64 * NPL) + NPL * lane;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if ((f >> e) & 1u) q[e] = 0.0f;
+                    for (int e = 0; e < NPL; ++e)
+                        if ((f >> e) & 1u) q[e] = (T)0;
                 }
             }
         }
@@ -689,8 +711,8 @@ namespace {
 struct TileChoice { int TC, tiles_x, tiles_r, cap, cs, max_img; };
 
 // Tile capacity (pixels or pool windows), column blocking and the worst-case patch size over all stacks.
-// quad: patch rows are padded to a multiple of 4 positions (the kernel loads them 4 positions to a lane).
-TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int S, int P, int max_pos, bool quad)
+// npl: positions of a patch row the kernel loads per lane (0, 4 or 8): rows are padded as tile_geom pads them.
+TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int S, int P, int max_pos, int npl)
 {
     TileChoice c;
     int mw = 0;
@@ -736,7 +758,7 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
                 int nimg = (trf + rh - 2) / rh + 1; if (nimg > batch) nimg = batch;
                 if (nimg > c.max_img) c.max_img = nimg;
                 const int rows = trf < rtot ? trf : rtot;
-                const int pw = quad ? (tc * S + 2 * P + 3) & ~3 : tc * S + 2 * P;
+                const int pw = npl == 8 ? (tc * S + 2 * P + 1 + 7) & ~7 : npl == 4 ? (tc * S + 2 * P + 3) & ~3 : tc * S + 2 * P;
                 const int npos = (S * rows + 2 * P * nimg) * pw;
                 if (npos > c.cs) c.cs = npos;
                 if (npos > max_pos && trf > 1) fits = false;
@@ -761,16 +783,19 @@ struct DlShape { int BM, BN, per_cu; };
 constexpr int conv_dl_max_bm(int K) { return K >= 7 ? 64 : 128; }
 
 template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE>
-void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
+void launch_dl(const MfmaConvArgs& a, DlShape sh, bool pack, dim3 grid, hipStream_t s)
 {
-    static char label[6][96];                    // (every write of an entry stores the same text: entries depend on the template and the shape only)
-    const int v = (sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1);
-    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%s, %d, %d, %d, %d, %s, %s, %s, %d>", sizeof(T) == 4 ? "float" : "unsigned short",
+    static char label[12][104];                  // (every write of an entry stores the same text: entries depend on the template and the shape only)
+    const int v = ((sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1)) * 2 + (pack ? 1 : 0);
+    std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%s, %d, %d, %d, %d, %s, %s, %s, %d, %s>", sizeof(T) == 4 ? "float" : "unsigned short",
                   K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN, POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false",
-                  POOL_IN ? "true" : "false", STRIDE);
+                  POOL_IN ? "true" : "false", STRIDE, pack ? "true" : "false");
     g_kernel_label = label[v];
     constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN;
-#define FTP_DL(WM, MT, BN) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE>), grid, dim3(256), 0, s, a)
+    constexpr bool PACKABLE = conv_dl_packable(sizeof(T), K, STRIDE, POOL_IN);
+#define FTP_DL(WM, MT, BN) do { \
+        if (pack) { if constexpr (PACKABLE) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE, true>), grid, dim3(256), 0, s, a); } \
+        else hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE, false>), grid, dim3(256), 0, s, a); } while (0)
     if (sh.BN == 256) {
         if constexpr (!STRIDED_FWD) {
             // (the 3x3 bfloat path never takes 128 channels x 256 pixels: its 8-channel stages would not fit 64 KB of LDS)
@@ -789,7 +814,7 @@ void launch_dl(const MfmaConvArgs& a, DlShape sh, dim3 grid, hipStream_t s)
 // filled round of a launch leaves CUs idle: few large workgroups waste most there, many small ones least, while
 // larger ones re-read less.  cost = (full rounds + the last round's depth per CU) x work of one workgroup.
 template <int K, bool POOL_OUT, bool STRIDED_FWD>
-DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, bool quad, TileChoice* tc_out)
+DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, int npl, TileChoice* tc_out)
 {
     const int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
     DlShape best = {0, 0, 0}; double best_cost = 0;
@@ -805,8 +830,8 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, bool quad, Til
     // does best with the most workgroups per CU: 64 channels x 128 pixels; config 5: 14.6 -> 14.4 ms per step)
     const bool small_wg = c.bf16 && K == 3 && !STRIDED_FWD && c.S == 1 && BM == 64;
     auto consider = [&](int bm, int BN) -> long long {
-        const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD, quad);
-        const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos, quad);
+        const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD, npl == 4, npl == 8);
+        const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos, npl);
         if (tc.cs > max_pos) return -1;
         // tiles that exist: every stack has its own count, the grid is sized for the largest
         long long wgs = 0;
@@ -835,7 +860,7 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, bool quad, Til
         // ... unless 128-pixel tiles (32 pool windows) fit the rows of the rectangles badly: a row of 19 windows leaves
         // 13 of 32 slots empty, while three such rows fill 57 of 64 (config 5, the 32 -> 64 layer: 0.68 -> 0.58 ms)
         long long units = 0, slots = 0;
-        const TileChoice t128 = choose_tile(a.rect, c.N, c.M, c.batch, 32, S, K / 2, conv_dl_max_positions(K, 128, STRIDED_FWD, quad), quad);
+        const TileChoice t128 = choose_tile(a.rect, c.N, c.M, c.batch, 32, S, K / 2, conv_dl_max_positions(K, 128, STRIDED_FWD, npl == 4, npl == 8), npl);
         for (int i = 0; i < c.N; ++i)
             for (int j = 0; j < c.M; ++j) {
                 const int rw = a.rect.x1[j] - a.rect.x0[j] + 1, rh = a.rect.y1[i] - a.rect.y0[i] + 1;
@@ -869,7 +894,15 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     // fp32 patches are loaded 16 bytes a lane, a few bytes beyond the ends of map rows: only inside the workspace
     constexpr bool quad = conv_dl_quads(sizeof(T), POOL_IN && DELTA_IN, STRIDE == 2 && DELTA_IN);
     if (quad && !(DELTA_IN ? c.din_ws : c.in_ws)) return 1;
-    const DlShape sh = choose_dl_shape<K, POOL_OUT, STRIDED_FWD>(a, c, quad, &td);
+    // 16-bit maps on the bfloat matrix-core path: the patch stays packed in LDS and travels 16 bytes a lane where every row
+    // of the view starts on a 4-byte boundary (even strides) inside the workspace; otherwise element by element
+    bool pack = false;
+    if constexpr (conv_dl_packable(sizeof(T), K, STRIDE, POOL_IN && DELTA_IN)) {
+        const View& iv = DELTA_IN ? a.din : a.in;
+        pack = (DELTA_IN ? c.din_ws : c.in_ws) && ((uintptr_t)iv.p & 3) == 0 && !(iv.pitch & 1) && !(iv.cs & 1) && !(iv.ns & 1) && !(iv.ss & 1);
+    }
+    const int npl = quad ? 4 : pack ? 8 : 0;
+    const DlShape sh = choose_dl_shape<K, POOL_OUT, STRIDED_FWD>(a, c, npl, &td);
     if (!sh.BM) return 1;
     // (the kernel keeps code-map offsets in 29 bits)
     if (POOL_IN && DELTA_IN && (double)td.max_img * (double)a.mask.ns >= 5.0e8) return 1;
@@ -880,14 +913,14 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
         if (4.0 * ((double)td.max_img * (double)ov.ns + ((double)a.Mtot + 8.0) * (double)ov.cs) >= 2.0e9) return 1;
         if (POOL_OUT && !DELTA_IN && (double)td.max_img * (double)a.mask.ns + ((double)a.Mtot + 8.0) * (double)a.mask.cs >= 2.0e9) return 1;
     }
-    a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = quad ? (td.cs + 255) & ~255 : (td.cs + 63) & ~63;
+    a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = pack ? (td.cs + 511) & ~511 : quad ? (td.cs + 255) & ~255 : (td.cs + 63) & ~63;
     a.mblocks = (a.Mtot + sh.BM - 1) / sh.BM; a.stacks = c.N * c.M;
     // XCD order pays where several channel blocks compete for the L2 and the groups spread evenly over the 8 XCDs;
     // with one channel block the plain order (neighbouring tiles on different XCDs) balances better
     const int groups = a.mblocks * a.stacks, ntiles = a.tiles_x * a.tiles_r;
     a.xcd_groups = (a.mblocks >= 2 && 8 % a.mblocks == 0 && groups % 8 == 0) ? 1 : 0;
     const unsigned nwg = a.xcd_groups ? xcd_grid(groups, ntiles) : (unsigned)(groups * ntiles);
-    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN, STRIDE>(a, sh, dim3(nwg), s);
+    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN, STRIDE>(a, sh, pack, dim3(nwg), s);
     return 0;
 }
 
