@@ -78,6 +78,7 @@ struct MfmaConvArgs {
     int TC, tiles_x, tiles_r;                       // column block (when tiles_x > 1), column / row-run tile counts
     int mblocks, stacks, xcd_groups;                // output-channel blocks; stacks; 1: workgroups in XCD order (the grid is 1-D, see xcd_order)
     int cap;                                        // pixels (pool windows) per tile
+    int flat;                                       // 1: tiles are runs of cap pixels of the rectangle's pixel list, not runs of whole rows
     int cs;                                         // LDS channel stride of the patch = largest patch of any stack
     float slope;
     int M, batch;

@@ -75,11 +75,15 @@ k_prep_filter16(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt_fwd, bf16_
     }
 }
 
-// Geometry of one tile: rows R0 .. R0+nrows-1 of the batch-flattened row index, columns ox0 .. ox0+TC-1.
+// Geometry of one tile.  A rectangle is cut into column blocks of TC columns and runs of whole rows (c0 = 0), or, where
+// the launch says so (a rectangle of one column block whose rows fill a tile badly), into runs of `cap` consecutive pixels
+// of its row-major pixel list, counted through the batch: a tile then starts at column c0 of flattened row R0 and need not
+// end at a row end, so every tile but a stack's last is full.  The patch covers the rows R0 .. R0+nrows-1 in full.
 struct TileGeom {
     int rw, rh;            // the stack's rectangle
     int TC, ox0;           // column block
     int R0, nrows;         // flattened rows
+    int c0, npx;           // first pixel's column in row R0; pixels (pool windows) of the tile
     int n_a, y_a;          // first image and its first row
     int PW;                // patch row length
     int first_cnt, per_cnt;// patch rows of the first image / of every further image
@@ -97,11 +101,20 @@ __device__ __forceinline__ TileGeom tile_geom(const MfmaConvArgs& a, int x0, int
     const int tx = bx % a.tiles_x, tb = bx / a.tiles_x;
     g.TC = a.tiles_x == 1 ? g.rw : a.TC;
     g.ox0 = x0 + tx * g.TC;
-    int trf = a.cap / g.TC; if (trf < 1) trf = 1;
     const int rtot = a.batch * g.rh;
-    g.R0 = tb * trf;
-    g.empty = g.ox0 > x1 || g.R0 >= rtot;
-    g.nrows = rtot - g.R0 < trf ? rtot - g.R0 : trf;
+    if (a.flat) {
+        const int p0 = tb * a.cap, total = rtot * g.rw;
+        g.empty = p0 >= total;
+        g.R0 = p0 / g.rw; g.c0 = p0 - g.R0 * g.rw;
+        g.npx = total - p0 < a.cap ? total - p0 : a.cap;
+        g.nrows = (g.c0 + g.npx + g.rw - 1) / g.rw;
+    } else {
+        int trf = a.cap / g.TC; if (trf < 1) trf = 1;
+        g.R0 = tb * trf; g.c0 = 0;
+        g.empty = g.ox0 > x1 || g.R0 >= rtot;
+        g.nrows = rtot - g.R0 < trf ? rtot - g.R0 : trf;
+        g.npx = g.nrows * g.TC;
+    }
     g.n_a = g.R0 / g.rh; g.y_a = g.R0 - g.n_a * g.rh;
     const int n_l = (g.R0 + g.nrows - 1) / g.rh;
     g.PW = g.TC * S + 2 * P;
@@ -120,13 +133,14 @@ template <int S, int P>
 __device__ __forceinline__ TilePix tile_pix(const TileGeom& g, int wq, int x1)
 {
     TilePix t;
-    const int fr = wq / g.TC;
-    t.xl = wq - fr * g.TC;
+    const int lin = g.c0 + wq;
+    const int fr = lin / g.TC;
+    t.xl = lin - fr * g.TC;
     const int R = g.R0 + fr;
     t.n = R / g.rh;
     t.y = R - t.n * g.rh;
     t.prow = S * fr + 2 * P * (t.n - g.n_a);
-    t.valid = fr < g.nrows && g.ox0 + t.xl <= x1;
+    t.valid = wq < g.npx && fr < g.nrows && g.ox0 + t.xl <= x1;
     return t;
 }
 
@@ -349,8 +363,19 @@ __host__ __device__ constexpr int conv_dl_max_positions(int K, int BN, bool stri
 // STRIDE = 2, delta back-propagation: the adjoint of a strided convolution is the stride-1 one applied to the
 // deltas with zeros inserted between them; a patch position at even coordinates loads delta (y/2, x/2), every
 // other one loads from an out-of-range offset (three quarters of the matrix-core work multiply zeros).
+// Wavefronts per SIMD the register allocation aims at: two as a rule (the fp32 tiles have 128 accumulator registers; the
+// small tiles of the bfloat path then come out at about 160 registers, three wavefronts per SIMD); four for the pooled
+// forward kernels of the bfloat path (32 accumulator registers; their epilogue is what needs the registers), which wait for
+// loads more than they multiply and are as fast as the number of workgroups a CU holds (LDS holds four): config 5,
+// forward of the three pooled layers 0.45 / 0.28 / 0.22 -> 0.44 / 0.26 / 0.21 ms; the same target made the unpooled and the
+// delta kernels of the deep layers slower (more workgroups competing for the L2) and is not used there.
+__host__ __device__ constexpr int conv_dl_waves(size_t elem, int K, int stride, int MT, int BN, int WAVES_M, bool pool_out)
+{
+    return (elem == 2 && K <= 3 && stride == 1 && pool_out && BN == 128 && MT * (BN / 32 / (4 / WAVES_M)) <= 2) ? 4 : 2;
+}
+
 template <typename T, int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE, bool PACK>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, conv_dl_waves(sizeof(T), K, STRIDE, MT, BN, WAVES_M, POOL_OUT))
 k_conv_mfma_dl(MfmaConvArgs a)
 {
     static_assert(!PACK || conv_dl_packable(sizeof(T), K, STRIDE, POOL_IN), "packed patches: bfloat matrix-core path only");
@@ -708,21 +733,69 @@ k_conv_mfma_dl(MfmaConvArgs a)
 // ---- host side ------------------------------------------------------------------------------------------------
 namespace {
 
-struct TileChoice { int TC, tiles_x, tiles_r, cap, cs, max_img; };
+struct TileChoice { int TC, tiles_x, tiles_r, cap, cs, max_img, flat; };
 
 // Tile capacity (pixels or pool windows), column blocking and the worst-case patch size over all stacks.
 // npl: positions of a patch row the kernel loads per lane (0, 4 or 8): rows are padded as tile_geom pads them.
-TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int S, int P, int max_pos, int npl)
+// gather: every further patch position is expensive (the patch is collected element by element - through pool winners,
+// between inserted zeros - or the kernel is bound by the latency of its patch loads).
+TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int S, int P, int max_pos, int npl, bool gather)
 {
-    TileChoice c;
     int mw = 0;
     for (int t = 0; t < M; ++t) mw = mw > rt.x1[t] - rt.x0[t] + 1 ? mw : rt.x1[t] - rt.x0[t] + 1;
     const int max_tc = 64 / S;                         // widest column block of a tile
-    c.tiles_x = (mw + max_tc - 1) / max_tc;
-    // A tile is whole rows of a column block: narrower blocks can fill its `cap0` slots better (rows of 25 pool
-    // windows put 50 into 64 slots, blocks of 9 + 9 + 7 put 63 + 63 + 49 into 192).  Up to three more column blocks are
-    // tried; the split is taken if it saves more than 12 % of the slots (a block more costs a filter halo more).
+    // One way of cutting: `tx` column blocks and runs of whole rows, or (flat) runs of pixels.  The tile capacity is cut
+    // down until the largest patch fits LDS; `tiles` = workgroups of one channel block, each of which costs the same
+    // matrix-core work however many of its slots are filled.
+    auto eval = [&](int tx, bool flat, double* tiles_out) -> TileChoice {
+        TileChoice c;
+        c.tiles_x = tx; c.flat = flat ? 1 : 0;
+        c.TC = (mw + tx - 1) / tx;
+        c.cap = cap0;
+        for (;;) {
+            c.tiles_r = 1; c.cs = 1; c.max_img = 1;
+            bool fits = true;
+            double tiles_all = 0;
+            for (int i = 0; i < N; ++i)
+                for (int j = 0; j < M; ++j) {
+                    const int rw = rt.x1[j] - rt.x0[j] + 1, rh = rt.y1[i] - rt.y0[i] + 1;
+                    const int rtot = batch * rh;
+                    const int tc = tx == 1 ? rw : c.TC;
+                    int tiles, rows;                       // tiles of this stack (per column block); most rows one of them touches
+                    if (flat) {
+                        tiles = (int)(((long long)rtot * rw + c.cap - 1) / c.cap);
+                        rows = (c.cap + 2 * tc - 2) / tc;          // a run of cap pixels that starts at the last column of a row
+                    } else {
+                        int trf = c.cap / tc; if (trf < 1) trf = 1;
+                        tiles = (rtot + trf - 1) / trf;
+                        rows = trf;
+                    }
+                    if (rows > rtot) rows = rtot;
+                    if (tiles > c.tiles_r) c.tiles_r = tiles;
+                    tiles_all += (double)tiles * ((rw + tc - 1) / tc);
+                    int nimg = (rows + rh - 2) / rh + 1; if (nimg > batch) nimg = batch;
+                    if (nimg > c.max_img) c.max_img = nimg;
+                    const int pw = npl == 8 ? (tc * S + 2 * P + 1 + 7) & ~7 : npl == 4 ? (tc * S + 2 * P + 3) & ~3 : tc * S + 2 * P;
+                    const int npos = (S * rows + 2 * P * nimg) * pw;
+                    if (npos > c.cs) c.cs = npos;
+                    if (npos > max_pos && rows > 1) fits = false;
+                }
+            *tiles_out = tiles_all;
+            if (fits || c.cap <= 8) break;
+            c.cap -= c.cap / 8;
+        }
+        return c;
+    };
+    // Whole rows of the fewest column blocks are the reference.  Narrower blocks can fill the slots of a tile better (rows
+    // of 25 pool windows put 50 into 64 slots, blocks of 9 + 9 + 7 put 63 + 63 + 49 into 192): up to three more blocks are
+    // tried and taken if they save more than 12 % of the tiles (a block more costs a filter halo more).  A rectangle of one
+    // column block can be cut into runs of pixels, which leaves no slot empty but makes a tile touch one or two rows more (a
+    // larger patch): taken if it saves tiles at all, but not where patch positions are expensive (config 4, delta pass
+    // through the first pool: 16 % fewer tiles, a third more patch positions, 13 % slower).
+    const int base = (mw + max_tc - 1) / max_tc;
+    int tx_rows = base;
     {
+        // (slots of the uncut capacity: what the split is judged by)
         auto slots_for = [&](int tx) -> double {
             const int TCt = (mw + tx - 1) / tx;
             double slots = 0;
@@ -735,38 +808,30 @@ TileChoice choose_tile(const RectTab& rt, int N, int M, int batch, int cap0, int
                 }
             return slots;
         };
-        const int base = c.tiles_x;
-        double best = slots_for(base);
+        double best_slots = slots_for(base);
         for (int tx = base + 1; tx <= base + 3 && (mw + tx - 1) / tx >= 4; ++tx) {
             const double sl = slots_for(tx);
-            if (sl < 0.88 * best) { best = sl; c.tiles_x = tx; }
+            if (sl < 0.88 * best_slots) { best_slots = sl; tx_rows = tx; }
         }
     }
-    c.TC = (mw + c.tiles_x - 1) / c.tiles_x;
-    c.cap = cap0;
-    for (;;) {
-        c.tiles_r = 1; c.cs = 1; c.max_img = 1;
-        bool fits = true;
-        for (int i = 0; i < N; ++i)
-            for (int j = 0; j < M; ++j) {
-                const int rw = rt.x1[j] - rt.x0[j] + 1, rh = rt.y1[i] - rt.y0[i] + 1;
-                const int tc = c.tiles_x == 1 ? rw : c.TC;
-                int trf = c.cap / tc; if (trf < 1) trf = 1;
-                const int rtot = batch * rh;
-                const int tiles = (rtot + trf - 1) / trf;
-                if (tiles > c.tiles_r) c.tiles_r = tiles;
-                int nimg = (trf + rh - 2) / rh + 1; if (nimg > batch) nimg = batch;
-                if (nimg > c.max_img) c.max_img = nimg;
-                const int rows = trf < rtot ? trf : rtot;
-                const int pw = npl == 8 ? (tc * S + 2 * P + 1 + 7) & ~7 : npl == 4 ? (tc * S + 2 * P + 3) & ~3 : tc * S + 2 * P;
-                const int npos = (S * rows + 2 * P * nimg) * pw;
-                if (npos > c.cs) c.cs = npos;
-                if (npos > max_pos && trf > 1) fits = false;
-            }
-        if (fits || c.cap <= 8) break;
-        c.cap -= c.cap / 8;
+    double best_tiles = 0;
+    TileChoice best = eval(tx_rows, false, &best_tiles);
+    if (base == 1 && !gather) {
+        double t = 0;
+        const TileChoice c = eval(1, true, &t);
+        if (t < 0.99 * best_tiles) { best = c; best_tiles = t; }
     }
-    return c;
+    return best;
+}
+
+// Tiles one stack's rectangle is cut into (what tile_geom() enumerates).
+long long tile_slots(const TileChoice& tc, int rw, int rh, int batch)
+{
+    const long long rtot = (long long)batch * rh;
+    if (tc.flat) return (rtot * rw + tc.cap - 1) / tc.cap;
+    const int tcw = tc.tiles_x == 1 ? rw : tc.TC;
+    int trf = tc.cap / tcw; if (trf < 1) trf = 1;
+    return ((rtot + trf - 1) / trf) * ((rw + tcw - 1) / tcw);
 }
 
 // Largest byte offset a workgroup forms from its base pointer: the images a tile can span plus all channels.
@@ -814,7 +879,7 @@ void launch_dl(const MfmaConvArgs& a, DlShape sh, bool pack, dim3 grid, hipStrea
 // filled round of a launch leaves CUs idle: few large workgroups waste most there, many small ones least, while
 // larger ones re-read less.  cost = (full rounds + the last round's depth per CU) x work of one workgroup.
 template <int K, bool POOL_OUT, bool STRIDED_FWD>
-DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, int npl, TileChoice* tc_out)
+DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, int npl, bool gather, TileChoice* tc_out)
 {
     const int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
     DlShape best = {0, 0, 0}; double best_cost = 0;
@@ -831,17 +896,14 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, int npl, TileC
     const bool small_wg = c.bf16 && K == 3 && !STRIDED_FWD && c.S == 1 && BM == 64;
     auto consider = [&](int bm, int BN) -> long long {
         const int max_pos = conv_dl_max_positions(K, BN, STRIDED_FWD, npl == 4, npl == 8);
-        const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos, npl);
+        const TileChoice tc = choose_tile(a.rect, c.N, c.M, c.batch, POOL_OUT ? BN / 4 : BN, S, K / 2, max_pos, npl, gather);
         if (tc.cs > max_pos) return -1;
         // tiles that exist: every stack has its own count, the grid is sized for the largest
         long long wgs = 0;
         for (int i = 0; i < c.N; ++i)
             for (int j = 0; j < c.M; ++j) {
                 const int rw = a.rect.x1[j] - a.rect.x0[j] + 1, rh = a.rect.y1[i] - a.rect.y0[i] + 1;
-                const int tcw = tc.tiles_x == 1 ? rw : tc.TC;
-                int trf = tc.cap / tcw; if (trf < 1) trf = 1;
-                const long long rtot = (long long)c.batch * rh;
-                wgs += ((rtot + trf - 1) / trf) * ((rw + tcw - 1) / tcw);
+                wgs += tile_slots(tc, rw, rh, c.batch);
             }
         const int mblocks = (a.Mtot + bm - 1) / bm;
         wgs *= mblocks;
@@ -860,15 +922,12 @@ DlShape choose_dl_shape(const MfmaConvArgs& a, const ConvArgs& c, int npl, TileC
         // ... unless 128-pixel tiles (32 pool windows) fit the rows of the rectangles badly: a row of 19 windows leaves
         // 13 of 32 slots empty, while three such rows fill 57 of 64 (config 5, the 32 -> 64 layer: 0.68 -> 0.58 ms)
         long long units = 0, slots = 0;
-        const TileChoice t128 = choose_tile(a.rect, c.N, c.M, c.batch, 32, S, K / 2, conv_dl_max_positions(K, 128, STRIDED_FWD, npl == 4, npl == 8), npl);
+        const TileChoice t128 = choose_tile(a.rect, c.N, c.M, c.batch, 32, S, K / 2, conv_dl_max_positions(K, 128, STRIDED_FWD, npl == 4, npl == 8), npl, gather);
         for (int i = 0; i < c.N; ++i)
             for (int j = 0; j < c.M; ++j) {
                 const int rw = a.rect.x1[j] - a.rect.x0[j] + 1, rh = a.rect.y1[i] - a.rect.y0[i] + 1;
-                const int tcw = t128.tiles_x == 1 ? rw : t128.TC;
-                int trf = t128.cap / tcw; if (trf < 1) trf = 1;
-                const long long rtot = (long long)c.batch * rh;
-                units += rtot * rw;
-                slots += ((rtot + trf - 1) / trf) * ((rw + tcw - 1) / tcw) * t128.cap;
+                units += (long long)c.batch * rh * rw;
+                slots += tile_slots(t128, rw, rh, c.batch) * t128.cap;
             }
         if (slots > 0 && (double)units < 0.7 * (double)slots) bn_first = 256;
     }
@@ -902,7 +961,10 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
         pack = (DELTA_IN ? c.din_ws : c.in_ws) && ((uintptr_t)iv.p & 3) == 0 && !(iv.pitch & 1) && !(iv.cs & 1) && !(iv.ns & 1) && !(iv.ss & 1);
     }
     const int npl = quad ? 4 : pack ? 8 : 0;
-    const DlShape sh = choose_dl_shape<K, POOL_OUT, STRIDED_FWD>(a, c, npl, &td);
+    // (16-bit maps through a fused pool: the kernel waits for its patch more than it multiplies, and runs of pixels, which
+    // touch more patch rows, were measured slower: config 5 forward of the pooled layers 0.45 / 0.28 / 0.22 -> 0.50 / 0.33 / 0.24 ms)
+    const bool costly_patch = ((POOL_IN || STRIDE == 2) && DELTA_IN) || (sizeof(T) == 2 && POOL_OUT && !DELTA_IN);
+    const DlShape sh = choose_dl_shape<K, POOL_OUT, STRIDED_FWD>(a, c, npl, costly_patch, &td);
     if (!sh.BM) return 1;
     // (the kernel keeps code-map offsets in 29 bits)
     if (POOL_IN && DELTA_IN && (double)td.max_img * (double)a.mask.ns >= 5.0e8) return 1;
@@ -913,7 +975,7 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
         if (4.0 * ((double)td.max_img * (double)ov.ns + ((double)a.Mtot + 8.0) * (double)ov.cs) >= 2.0e9) return 1;
         if (POOL_OUT && !DELTA_IN && (double)td.max_img * (double)a.mask.ns + ((double)a.Mtot + 8.0) * (double)a.mask.cs >= 2.0e9) return 1;
     }
-    a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.cs = pack ? (td.cs + 511) & ~511 : quad ? (td.cs + 255) & ~255 : (td.cs + 63) & ~63;
+    a.TC = td.TC; a.tiles_x = td.tiles_x; a.tiles_r = td.tiles_r; a.cap = td.cap; a.flat = td.flat; a.cs = pack ? (td.cs + 511) & ~511 : quad ? (td.cs + 255) & ~255 : (td.cs + 63) & ~63;
     a.mblocks = (a.Mtot + sh.BM - 1) / sh.BM; a.stacks = c.N * c.M;
     // XCD order pays where several channel blocks compete for the L2 and the groups spread evenly over the 8 XCDs;
     // with one channel block the plain order (neighbouring tiles on different XCDs) balances better
