@@ -302,11 +302,13 @@ __host__ __device__ constexpr int conv_dl_waves(size_t elem, int K, int stride, 
     return (elem == 2 && K <= 3 && stride == 1 && pool_out && BN == 128 && MT * (BN / 32 / (4 / WAVES_M)) <= 2) ? 4 : 2;
 }
 
-template <typename T, int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE, bool PACK>
+template <typename T, int K, int WAVES_M, int MT, int BN, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE, bool WIDE>
 __global__ void __launch_bounds__(256, conv_dl_waves(sizeof(T), K, STRIDE, MT, BN, WAVES_M, POOL_OUT))
 k_conv_mfma_dl(MfmaConvArgs a)
 {
-    static_assert(!PACK || conv_dl_packable(sizeof(T), K, STRIDE, POOL_IN), "packed patches: bfloat matrix-core path only");
+    // WIDE: the patch travels 16 bytes a lane (fp32: quads of positions; bfloat matrix-core path: packed, 8 positions)
+    static_assert(!WIDE || conv_dl_packable(sizeof(T), K, STRIDE, POOL_IN) || conv_dl_quads(sizeof(T), POOL_IN, STRIDE == 2 && DELTA_IN),
+                  "wide patch loads: fp32 patches that are not gathered element by element, and the bfloat matrix-core path");
     static_assert(STRIDE == 1 || !(POOL_OUT || POOL_IN), "strided convolutions with a fused pool take the direct kernels");
     constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN, UP_IN = STRIDE == 2 && DELTA_IN, HALF_IN = POOL_IN || UP_IN;
     constexpr unsigned ES = sizeof(T);                 // bytes per map element
@@ -317,15 +319,15 @@ k_conv_mfma_dl(MfmaConvArgs a)
     constexpr int kCK = conv_dl_stage_channels(K, STRIDED_FWD, BF);
     constexpr int KK = K * K, P = K / 2;
     constexpr int S = (POOL_OUT || STRIDED_FWD) ? 2 : 1;
-    constexpr bool XH = PACK;                          // the patch stays packed: [channel][position] bfloats
-    constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD, conv_dl_quads(sizeof(T), POOL_IN, UP_IN), XH);
+    constexpr bool XH = WIDE && sizeof(T) == 2;        // the patch stays packed: [channel][position] bfloats
+    constexpr bool XQ = WIDE && sizeof(T) == 4;        // fp32 quads
+    constexpr int XMAX = conv_dl_max_positions(K, BN, STRIDED_FWD, XQ, XH);
     constexpr int MAXPOS = XMAX / 256;
     // fp32 patches (not those gathered element by element through pool winners or between inserted zeros) travel 16
     // bytes a lane: a quad of consecutive positions of one patch row (rows are padded to whole quads), 64 quads = 256
     // positions to an instruction, NQB such blocks per channel; the wavefronts take (block, channel) pairs in turn.
     // Packed bfloat patches travel the same way, 8 positions (16 bytes) a lane, 512 positions to an instruction; their rows
     // begin on the dword grid of the map (up to one position before the first column the tile needs).
-    constexpr bool XQ = conv_dl_quads(sizeof(T), POOL_IN, UP_IN);
     constexpr bool XW = XQ || XH;                      // wide loads
     constexpr int NPL = XH ? 8 : 4;                    // positions per lane
     constexpr int NQB = XMAX / (64 * NPL), NXI = (NQB * kCK + 3) / 4;
@@ -675,19 +677,22 @@ struct DlShape { int BM, BN, per_cu; };
 constexpr int conv_dl_max_bm(int K) { return K >= 7 ? 64 : 128; }
 
 template <typename T, int K, bool POOL_OUT, bool DELTA_IN, bool POOL_IN, int STRIDE>
-void launch_dl(const MfmaConvArgs& a, DlShape sh, bool pack, dim3 grid, hipStream_t s)
+void launch_dl(const MfmaConvArgs& a, DlShape sh, bool wide, dim3 grid, hipStream_t s)
 {
     static char label[12][104];                  // (every write of an entry stores the same text: entries depend on the template and the shape only)
-    const int v = ((sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1)) * 2 + (pack ? 1 : 0);
+    const int v = ((sh.BM == 128 ? 0 : sh.BM == 64 ? 1 : 2) * 2 + (sh.BN == 256 ? 0 : 1)) * 2 + (wide ? 1 : 0);
     std::snprintf(label[v], sizeof(label[v]), "k_conv_mfma_dl<%s, %d, %d, %d, %d, %s, %s, %s, %d, %s>", sizeof(T) == 4 ? "float" : "unsigned short",
                   K, sh.BM == 128 ? 2 : 1, sh.BM == 32 ? 1 : 2, sh.BN, POOL_OUT ? "true" : "false", DELTA_IN ? "true" : "false",
-                  POOL_IN ? "true" : "false", STRIDE, pack ? "true" : "false");
+                  POOL_IN ? "true" : "false", STRIDE, wide ? "true" : "false");
     g_kernel_label = label[v];
     constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN;
-    constexpr bool PACKABLE = conv_dl_packable(sizeof(T), K, STRIDE, POOL_IN);
+    // (which forms exist: the delta maps always lie inside the workspace, so an fp32 delta pass that can load wide always does)
+    constexpr bool QUADABLE = conv_dl_quads(sizeof(T), POOL_IN, STRIDE == 2 && DELTA_IN);
+    constexpr bool WIDEABLE = QUADABLE || conv_dl_packable(sizeof(T), K, STRIDE, POOL_IN);
+    constexpr bool NARROWABLE = !(QUADABLE && DELTA_IN);
 #define FTP_DL(WM, MT, BN) do { \
-        if (pack) { if constexpr (PACKABLE) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE, true>), grid, dim3(256), 0, s, a); } \
-        else hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE, false>), grid, dim3(256), 0, s, a); } while (0)
+        if (wide) { if constexpr (WIDEABLE) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE, true>), grid, dim3(256), 0, s, a); } \
+        else { if constexpr (NARROWABLE) hipLaunchKernelGGL((k_conv_mfma_dl<T, K, WM, MT, BN, POOL_OUT, DELTA_IN, POOL_IN, STRIDE, false>), grid, dim3(256), 0, s, a); } } while (0)
     if (sh.BN == 256) {
         if constexpr (!STRIDED_FWD) {
             // (the 3x3 bfloat path never takes 128 channels x 256 pixels: its 8-channel stages would not fit 64 KB of LDS)
@@ -780,9 +785,11 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
 {
     constexpr bool STRIDED_FWD = STRIDE == 2 && !DELTA_IN;
     TileChoice td;
-    // fp32 patches are loaded 16 bytes a lane, a few bytes beyond the ends of map rows: only inside the workspace
-    constexpr bool quad = conv_dl_quads(sizeof(T), POOL_IN && DELTA_IN, STRIDE == 2 && DELTA_IN);
-    if (quad && !(DELTA_IN ? c.din_ws : c.in_ws)) return 1;
+    // fp32 patches are loaded 16 bytes a lane, a few bytes beyond the ends of map rows: only inside the workspace (the
+    // caller's input, which a wide first layer reads, is loaded element by element)
+    constexpr bool quadable = conv_dl_quads(sizeof(T), POOL_IN && DELTA_IN, STRIDE == 2 && DELTA_IN);
+    const bool quad = quadable && (DELTA_IN ? c.din_ws : c.in_ws);
+    if (quadable && DELTA_IN && !quad) return 1;
     // 16-bit maps on the bfloat matrix-core path: the patch stays packed in LDS and travels 16 bytes a lane where every row
     // of the view starts on a 4-byte boundary (even strides) inside the workspace; otherwise element by element
     bool pack = false;
@@ -812,7 +819,7 @@ int launch_t(MfmaConvArgs& a, const ConvArgs& c, hipStream_t s)
     const int groups = a.mblocks * a.stacks, ntiles = a.tiles_x * a.tiles_r;
     a.xcd_groups = (a.mblocks >= 2 && 8 % a.mblocks == 0 && groups % 8 == 0) ? 1 : 0;
     const unsigned nwg = a.xcd_groups ? xcd_grid(groups, ntiles) : (unsigned)(groups * ntiles);
-    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN, STRIDE>(a, sh, pack, dim3(nwg), s);
+    launch_dl<T, K, POOL_OUT && !DELTA_IN, DELTA_IN, POOL_IN && DELTA_IN, STRIDE>(a, sh, quad || pack, dim3(nwg), s);
     return 0;
 }
 
