@@ -403,18 +403,34 @@ k_wgrad_mfma(MfmaWgradArgs a)
     }
 }
 
-// Sum of the batch shares of one layer's partial gradient, in share order.
+// Sum of the batch shares of one layer's partial gradient, in share order.  V = 4: four consecutive parameters per thread,
+// the shares' 16-byte loads four at a time in flight (layers whose parameter count is a multiple of 4); V = 1 otherwise.
+template <int V>
 __global__ void __launch_bounds__(256)
 k_wgrad_splitk_reduce(const float* __restrict__ scratch, float* __restrict__ partial, long long layer_params, long long n_params,
                       long long w_off, int splits)
 {
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * V;
     const int stack = blockIdx.y;
     if (i >= layer_params) return;
     const float* src = scratch + (long long)stack * splits * layer_params + i;
-    float v = src[0];
-    for (int s = 1; s < splits; ++s) v += src[(long long)s * layer_params];
-    partial[(long long)stack * n_params + w_off + i] = v;
+    float* dst = partial + (long long)stack * n_params + w_off + i;
+    if constexpr (V == 4) {
+        auto ld4 = [&](int sh) { return *(const float4*)(src + (long long)sh * layer_params); };
+        auto add = [](float4& v, const float4& b) { v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w; };
+        float4 v = ld4(0);
+        int sh = 1;
+        for (; sh + 3 < splits; sh += 4) {
+            const float4 b0 = ld4(sh), b1 = ld4(sh + 1), b2 = ld4(sh + 2), b3 = ld4(sh + 3);
+            add(v, b0); add(v, b1); add(v, b2); add(v, b3);
+        }
+        for (; sh < splits; ++sh) add(v, ld4(sh));
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;     // (the layer's place in the parameter vector need not be 16-byte aligned)
+    } else {
+        float v = src[0];
+        for (int sh = 1; sh < splits; ++sh) v += src[(long long)sh * layer_params];
+        dst[0] = v;
+    }
 }
 
 // Geometry: stride 1 with K = 1, 3 (with or without the fused pool), K = 5, 7 without; stride 2 with K = 1, 3.
@@ -483,9 +499,15 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
 void wgrad_share_sum(const ConvArgs& c, const float* scratch, int shares, hipStream_t s)
 {
     const long long lp = (long long)c.Cout * c.Cin * c.K * c.K;
-    dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);
     g_kernel_label = "k_wgrad_splitk_reduce";
-    hipLaunchKernelGGL(k_wgrad_splitk_reduce, g2, dim3(256), 0, s, scratch, c.partial, lp, c.n_params, c.w_off, shares);
+    // (the share scratch is 256-byte aligned, so with a parameter count that is a multiple of 4 every share's slice is too)
+    if (lp % 4 == 0 && ((uintptr_t)scratch & 15) == 0) {
+        dim3 g2((unsigned)((lp / 4 + 255) / 256), c.N * c.M);
+        hipLaunchKernelGGL(k_wgrad_splitk_reduce<4>, g2, dim3(256), 0, s, scratch, c.partial, lp, c.n_params, c.w_off, shares);
+    } else {
+        dim3 g2((unsigned)((lp + 255) / 256), c.N * c.M);
+        hipLaunchKernelGGL(k_wgrad_splitk_reduce<1>, g2, dim3(256), 0, s, scratch, c.partial, lp, c.n_params, c.w_off, shares);
+    }
 }
 
 }  // namespace ftp
