@@ -106,6 +106,7 @@ struct MfmaWgradArgs {
     int splits;                                     // batch shares per stack
     int gx, stacks;                                 // blocks per (stack, share); stacks (the grid is 1-D, see xcd_order)
     int PK;                                         // pixels staged per step
+    int zs = 0, stage_words = 0;                    // streamed thin-layer kernel: dwords between the dZ rows of two channels; dwords of a stage
     float slope;
     int M, batch;
 };

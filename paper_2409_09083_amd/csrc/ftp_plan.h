@@ -219,13 +219,44 @@ FTP_HD inline ThinChunks thin_wgrad_chunks(int rw, int rh, int batch, int PK, bo
     c.total = c.img_blocks * c.row_blocks;
     return c;
 }
-// Shares of its chunk list: blocks of 32 output channels x stacks x shares should come close to 1024 workgroups, the
-// number that runs at a time (four to a CU), without exceeding it - a few workgroups over would start a second round
-// as long as the first (36 stacks x 29 shares = 1044 took nearly twice as long as 36 x 28).
-inline int wgrad_shares_thin(int cout, int stacks, int chunks)
+// The streamed form of that kernel keeps two chunks in LDS (dZ as [32 channels][zs positions], at the pooled resolution
+// behind a pool, where the winner codes follow in the same layout; then the patch), one dword a position.
+FTP_HD constexpr int kThinZPass(bool pooled) { return pooled ? 2 : 4; }      // dZ positions of a chunk, in blocks of 64
+struct ThinStream { int PK, zs, stage_words, wgs_per_cu; size_t lds; bool fits; };
+inline ThinStream thin_stream_geom(const int* rws, const int* rhs, int N, int M, int batch, int cin, int K, int S, bool pooled)
+{
+    ThinStream g;
+    const int P = K / 2;
+    int wmax = 0;
+    for (int j = 0; j < M; ++j) { const int w = (rws[j] + 1) & ~1; if (w > wmax) wmax = w; }
+    // behind a pool a chunk is 64 windows or one row of windows; else 128 pixels or one row
+    g.PK = pooled ? (2 * wmax > 256 ? 2 * wmax : 256) : (wmax > 128 ? wmax : 128);
+    int nzp = 1, xmax = 1;
+    for (int i = 0; i < N; ++i)
+        for (int j = 0; j < M; ++j) {
+            const ThinChunks tc = thin_wgrad_chunks(rws[j], rhs[i], batch, g.PK, pooled);
+            const int z = pooled ? tc.TI * (tc.TR >> 1) * (tc.TCp >> 1) : tc.TI * tc.TR * tc.TCp;
+            const int x = cin * tc.TI * (S * tc.TR + 2 * P) * (S * tc.TCp + 2 * P);
+            if (z > nzp) nzp = z;
+            if (x > xmax) xmax = x;
+        }
+    g.zs = ((nzp + 63) & ~63) + 2;
+    g.stage_words = 32 * g.zs * (pooled ? 2 : 1) + xmax + 4;
+    size_t words = 2 * (size_t)g.stage_words;
+    if (words < 3 * 16 * 64) words = 3 * 16 * 64;                              // final sum of the wavefronts
+    g.lds = words * sizeof(float);
+    g.fits = nzp <= 64 * kThinZPass(pooled) && g.lds <= 64 * 1024;
+    const int per_cu = (int)((160 * 1024) / g.lds);
+    g.wgs_per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
+    return g;
+}
+// Shares of its chunk list: blocks of 32 output channels x stacks x shares should come close to `slots` workgroups, the
+// number that runs at a time (1024: four to a CU), without exceeding it - a few workgroups over would start a second
+// round as long as the first (36 stacks x 29 shares = 1044 took nearly twice as long as 36 x 28).
+inline int wgrad_shares_thin(int cout, int stacks, int chunks, int slots = 1024)
 {
     const int blocks = ((cout + 31) / 32) * stacks;
-    int shares = 1024 / blocks;
+    int shares = slots / blocks;
     if (shares > chunks) shares = chunks;
     if (shares > 256) shares = 256;
     return shares < 1 ? 1 : shares;

@@ -739,6 +739,279 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
     }
 }
 
+// ---- the same gradient, its chunks streamed into LDS by the load unit ------------------------------------------
+// Two stages of LDS: while the matrix cores work on one chunk, the next one travels HBM -> LDS without passing through
+// registers (one barrier a chunk).  A stage holds dZ as [32 channels][zs positions] - at the pooled resolution behind a
+// pool, followed by the winner codes in the same layout - and the patch [ci][image][row][column] in natural order; 16-bit
+// maps occupy one dword a position (the bits in the lower half).  zs = 2 mod 64 keeps the A-operand reads (32 channels
+// x 2 neighbouring pixels) on 64 different banks.
+// Five wavefronts: the fifth only issues the loads (lane -> position of a row, one instruction per channel / patch row)
+// and waits for them, so that the address arithmetic never sits between the matrix instructions of the four that
+// multiply; these split the pixel pairs of every row among themselves as in the kernel above.
+#define FTP_THIN_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+template <typename T, int K, int S, int NB, bool POOL>
+__global__ void __launch_bounds__(320)
+k_wgrad_thin_dl(MfmaWgradArgs a)
+{
+    constexpr int KK = K * K, P = K / 2, ES = sizeof(T);
+    constexpr int ZPASS = kThinZPass(POOL);
+    constexpr unsigned OOB = 0x80000000u;              // beyond the records of the buffer resources below: reads as zero
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hi = lane >> 5, l32 = lane & 31;
+    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
+    const int x0 = a.own.x0[tj], x1 = a.own.x1[tj], y0 = a.own.y0[ti], y1 = a.own.y1[ti];
+    const int rw = x1 - x0 + 1, rh = y1 - y0 + 1;
+    const int co0 = blockIdx.x * 32;
+    const int split = blockIdx.y;
+
+    const ThinChunks tc = thin_wgrad_chunks(rw, rh, a.batch, a.PK, POOL);
+    const int TCp = tc.TCp, TR = tc.TR, TI = tc.TI, row_blocks = tc.row_blocks;
+    const int id0 = (int)((long long)split * tc.total / a.splits), id1 = (int)((long long)(split + 1) * tc.total / a.splits);
+    const int PW = S * TCp + 2 * P, PH = S * TR + 2 * P;
+    const int XCS = TI * PH * PW;                      // channel stride of the patch
+    const int zs = a.zs;
+    const int zwords = 32 * zs * (POOL ? 2 : 1);
+    const int wpr = TCp >> 1, wrT = TR >> 1;           // POOL: windows per row, window rows of a full chunk
+    const int nzp = POOL ? TI * wrT * wpr : TI * TR * TCp;     // dZ positions of a full chunk
+
+    int lane_off[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int nn = nb * 32 + l32 < a.Cin * KK ? nb * 32 + l32 : 0;
+        lane_off[nb] = (nn / KK) * XCS + ((nn % KK) / K) * PW + (nn % KK) % K + S * hi;
+    }
+    v16f acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
+
+    // which (image, row, column) of a chunk a lane stages is the same for every chunk (chunks of several images hold
+    // whole rectangles): divided once.  z_r: pixel row inside the chunk.
+    int z_il[ZPASS], z_r[ZPASS]; unsigned z_vo[ZPASS], z_mo[ZPASS];
+#pragma unroll
+    for (int p = 0; p < ZPASS; ++p) {
+        const int zi = lane + 64 * p;
+        const int row = zi / (POOL ? wpr : TCp), c = zi - row * (POOL ? wpr : TCp);
+        const int rows_img = POOL ? wrT : TR;
+        const int il = TI > 1 ? row / rows_img : 0;
+        const int r = row - il * rows_img;
+        z_r[p] = POOL ? 2 * r : r;
+        const bool ok = zi < nzp && (POOL || c < rw);
+        z_il[p] = ok ? il : a.batch;                   // (a.batch: never inside a chunk)
+        z_vo[p] = ok ? (unsigned)ES * (unsigned)(il * (int)a.din.ns + r * a.din.pitch + c) : 0u;
+        z_mo[p] = POOL && ok ? (unsigned)(il * (int)a.mask.ns + r * a.mask.pitch + c) : 0u;
+    }
+
+    struct Chunk { int n0, ni, yb, nr, rb; };
+    auto chunk_at = [&](int id) {
+        Chunk c;
+        const int ib = id / row_blocks;
+        c.rb = id - ib * row_blocks;
+        c.n0 = ib * TI; c.ni = (a.batch - c.n0) < TI ? (a.batch - c.n0) : TI;
+        c.yb = y0 + c.rb * TR; c.nr = (y1 - c.yb + 1) < TR ? (y1 - c.yb + 1) : TR;
+        return c;
+    };
+
+    // Per load instruction only a scalar offset changes: the channel's (a channel beyond the layer's last loads the last
+    // one again - its row of the product is never stored); a chunk's own origin goes into the base address of the
+    // buffer resource.
+    const int z_cs = (int)a.din.cs, m_cs = POOL ? (int)a.mask.cs : 0, co_last = a.Cout - 1 - co0;
+    const T* const zstack = (const T*)a.din.p + (long long)stack * a.din.ss
+                            + ((POOL ? (y0 >> 1) : y0) - a.din.y0[ti]) * a.din.pitch + ((POOL ? (x0 >> 1) : x0) - a.din.x0[tj]);
+    const uint8_t* const mstack = POOL ? (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss
+                                         + ((y0 >> 1) - a.mask.y0[ti]) * a.mask.pitch + ((x0 >> 1) - a.mask.x0[tj]) : nullptr;
+    const long long z_ns = a.din.ns, m_ns = a.mask.ns, x_ns = a.in.ns;
+    const int z_rowstep = (POOL ? TR >> 1 : TR) * a.din.pitch, m_rowstep = POOL ? (TR >> 1) * a.mask.pitch : 0;
+    // the patch: column offsets of this lane (the same for every chunk), rows relative to the map row S * y0 - P
+    const T* const xstack = (const T*)a.in.p + (long long)stack * a.in.ss - (long long)a.in.y0[ti] * a.in.pitch - a.in.x0[tj];
+    const int x_pitch = a.in.pitch, x_cs = (int)a.in.cs;
+    const int gx0 = S * x0 - P, ncol = S * rw + 2 * P;
+    const int Hc = a.Hc, Cin = a.Cin;
+
+    auto issue = [&](const Chunk& c, int rb, float* st) {
+        // dZ (and the winner codes): lanes without a pixel receive zeros
+        {
+            const T* gbase = zstack + c.n0 * z_ns + rb * z_rowstep;
+            const __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc((void*)gbase, (short)0, 0x7FFFFFFF, 0x00020000);
+            const uint8_t* mbase = POOL ? mstack + c.n0 * m_ns + rb * m_rowstep : nullptr;
+            const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)mbase, (short)0, 0x7FFFFFFF, 0x00020000);
+#pragma unroll
+            for (int p = 0; p < ZPASS; ++p) {
+                if (64 * p < nzp) {
+                    const bool ok = z_il[p] < c.ni && z_r[p] < c.nr;
+                    const unsigned gv = ok ? z_vo[p] : OOB, mv = ok ? z_mo[p] : OOB;
+#pragma unroll 8
+                    for (int ch = 0; ch < 32; ++ch) {
+                        const int co = co0 + (ch < co_last ? ch : co_last);
+                        float* zd = st + ch * zs + 64 * p;
+                        if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_ptr_buffer_load_lds(grsrc, FTP_THIN_LDS(zd), 4, gv, (unsigned)ES * (unsigned)(co * z_cs), 0, 0);
+                        else                          __builtin_amdgcn_raw_ptr_buffer_load_lds(grsrc, FTP_THIN_LDS(zd), 2, gv, (unsigned)ES * (unsigned)(co * z_cs), 0, 0);
+                        if constexpr (POOL)
+                            __builtin_amdgcn_raw_ptr_buffer_load_lds(mrsrc, FTP_THIN_LDS(zd + 32 * zs), 1, mv, (unsigned)(co * m_cs), 0, 0);
+                    }
+                }
+            }
+        }
+        // the patch, 64 columns of a row to an instruction; rows and columns outside the map are filled with zeros
+        {
+            const int nph = S * c.nr + 2 * P;
+            const int gy0 = S * c.yb - P;
+            const T* base = xstack + c.n0 * x_ns + (long long)gy0 * x_pitch;       // (row gy0 may lie above the map: never read)
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, (short)0, 0x7FFFFFFF, 0x00020000);
+            float* xs = st + zwords;
+            for (int cb = 0; cb < PW; cb += 64) {
+                const int col = cb + lane, gx = gx0 + col;
+                const unsigned vo = (col < ncol && gx >= 0 && gx < a.Wc) ? (unsigned)ES * (unsigned)gx : OOB;
+                if (col < PW) {
+                    for (int ci = 0; ci < Cin; ++ci)
+                        for (int il = 0; il < c.ni; ++il) {
+                            int so = ES * (ci * x_cs + il * (int)x_ns);
+                            float* xd = xs + ci * XCS + il * PH * PW + cb;
+                            for (int r = 0; r < nph; ++r, so += ES * x_pitch, xd += PW) {
+                                const bool rok = (unsigned)(gy0 + r) < (unsigned)Hc;   // (uniform)
+                                if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FTP_THIN_LDS(xd), 4, rok ? vo : OOB, rok ? (unsigned)so : 0u, 0, 0);
+                                else                          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, FTP_THIN_LDS(xd), 2, rok ? vo : OOB, rok ? (unsigned)so : 0u, 0, 0);
+                            }
+                        }
+                }
+            }
+        }
+    };
+
+    auto widen = [](float v) -> float { return ES == 4 ? v : __uint_as_float(__float_as_uint(v) << 16); };
+
+    // (the LDS reads of the next pixel pair are issued before the matrix instructions of the current one)
+    auto multiply = [&](const Chunk& c, const float* st) {
+        const float* xs = st + zwords;
+        if constexpr (POOL) {
+            const int wrows = c.nr >> 1;
+            for (int il = 0; il < c.ni; ++il)
+                for (int wr = 0; wr < wrows; ++wr) {
+                    const float* zrow = st + l32 * zs + (il * wrT + wr) * wpr;
+                    const float* xrow = xs + (il * PH + 2 * wr) * PW;
+                    // this wavefront's windows wave, wave + 4, ...: two to a turn of the loop, the LDS reads of each issued
+                    // before the matrix instructions of the one before
+                    const int n = (wpr - wave + 3) >> 2;
+                    if (n <= 0) continue;
+                    const float* pz = zrow + wave;
+                    const float* px[NB];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) px[nb] = xrow + lane_off[nb] + 2 * wave;
+                    float zA, cA, x0A[NB], x1A[NB], zB, cB, x0B[NB], x1B[NB];
+                    auto ldw = [&](int i, float& z, float& cw, float (&x0v)[NB], float (&x1v)[NB]) {
+                        z = pz[4 * i]; cw = pz[32 * zs + 4 * i];
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) { x0v[nb] = px[nb][8 * i]; x1v[nb] = px[nb][PW + 8 * i]; }
+                    };
+                    auto mm = [&](float z, float cw, const float (&x0v)[NB], const float (&x1v)[NB]) {
+                        const float zv = widen(z);
+                        const uint32_t cd = (__float_as_uint(cw) >> 1) & 3u;
+                        const float a0 = cd == (uint32_t)hi ? zv : 0.0f, a1 = cd == (uint32_t)(2 + hi) ? zv : 0.0f;
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, widen(x0v[nb]), acc[nb], 0, 0, 0);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, widen(x1v[nb]), acc[nb], 0, 0, 0);
+                    };
+                    ldw(0, zA, cA, x0A, x1A);
+                    int i = 0;
+                    for (; i + 2 < n; i += 2) {
+                        ldw(i + 1, zB, cB, x0B, x1B);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mm(zA, cA, x0A, x1A);
+                        __builtin_amdgcn_sched_barrier(0);
+                        ldw(i + 2, zA, cA, x0A, x1A);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mm(zB, cB, x0B, x1B);
+                        __builtin_amdgcn_sched_barrier(0);
+                        asm volatile("" : "+v"(zA), "+v"(cA));         // (a value of this turn, not a read of the next)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(x0A[nb]), "+v"(x1A[nb]));
+                    }
+                    if (i + 1 < n) {
+                        ldw(i + 1, zB, cB, x0B, x1B);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mm(zA, cA, x0A, x1A);
+                        mm(zB, cB, x0B, x1B);
+                    } else {
+                        mm(zA, cA, x0A, x1A);
+                    }
+                }
+        } else {
+            for (int il = 0; il < c.ni; ++il)
+                for (int r = 0; r < c.nr; ++r) {
+                    const float* zrow = st + l32 * zs + (il * TR + r) * TCp + hi;
+                    const float* xrow = xs + (il * PH + S * r) * PW;
+                    if (2 * wave >= TCp) continue;
+                    float zc = zrow[2 * wave], xc[NB];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) xc[nb] = xrow[lane_off[nb] + S * 2 * wave];
+                    for (int xp = 2 * wave; xp < TCp; xp += 8) {
+                        const int xn = xp + 8 < TCp ? xp + 8 : xp;
+                        const float zn = zrow[xn];
+                        float xnv[NB];
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) xnv[nb] = xrow[lane_off[nb] + S * xn];
+                        __builtin_amdgcn_sched_barrier(0);
+                        const float av = widen(zc);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, widen(xc[nb]), acc[nb], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        zc = zn;
+                        asm volatile("" : "+v"(zc));
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) { xc[nb] = xnv[nb]; asm volatile("" : "+v"(xc[nb])); }
+                    }
+                }
+        }
+    };
+
+    if (wave == 4) {
+        // the loader: chunk id + 1 is on its way while the others multiply chunk id
+        if (id0 < id1) issue(chunk_at(id0), chunk_at(id0).rb, lds);
+        for (int id = id0; id < id1; ++id) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): chunk id has landed
+            __syncthreads();                           // ... and the stage of chunk id - 1 has been consumed
+            if (id + 1 < id1) { const Chunk nxt = chunk_at(id + 1); issue(nxt, nxt.rb, lds + ((id + 1 - id0) & 1) * a.stage_words); }
+        }
+    } else {
+        for (int id = id0; id < id1; ++id) {
+            __syncthreads();
+            multiply(chunk_at(id), lds + ((id - id0) & 1) * a.stage_words);
+        }
+    }
+
+    // sum the 4 wavefronts in order, then wavefront 0 stores D[co][(ci, tap)]
+    float* red = lds;                                  // [3][16][64]
+    const long long layer_params = (long long)a.Cout * a.Cin * KK;
+    float* dst = a.splits > 1 ? a.scratch + ((long long)stack * a.splits + split) * layer_params
+                              : a.partial + (long long)stack * a.n_params + a.w_off;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        __syncthreads();
+        if (wave > 0 && wave < 4) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red[((wave - 1) * 16 + i) * 64 + lane] = acc[nb][i];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const int n = nb * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float v = ((acc[nb][i] + red[(0 * 16 + i) * 64 + lane]) + red[(1 * 16 + i) * 64 + lane]) + red[(2 * 16 + i) * 64 + lane];
+                const int co = co0 + 8 * (i >> 2) + 4 * hi + (i & 3);
+                if (co < a.Cout && n < a.Cin * KK) dst[(long long)co * a.Cin * KK + n] = v;
+            }
+        }
+    }
+}
+#undef FTP_THIN_LDS
+
 namespace {
 
 struct ThinGeom { int PK; size_t lds; };
@@ -764,6 +1037,26 @@ ThinGeom thin_geom(const ConvArgs& c)
 
 }  // namespace
 
+namespace {
+
+ThinStream stream_geom(const ConvArgs& c)
+{
+    int rws[kTabGrid], rhs[kTabGrid];
+    for (int j = 0; j < c.M; ++j) rws[j] = c.rect.x1[j] - c.rect.x0[j] + 1;
+    for (int i = 0; i < c.N; ++i) rhs[i] = c.rect.y1[i] - c.rect.y0[i] + 1;
+    ThinStream g = thin_stream_geom(rws, rhs, c.N, c.M, c.batch, c.Cin, c.K, c.S, c.pooled != 0);
+    // the kernel addresses one chunk's images with 32-bit byte offsets
+    int ti_max = 1;
+    for (int i = 0; i < c.N; ++i)
+        for (int j = 0; j < c.M; ++j) ti_max = std::max(ti_max, thin_wgrad_chunks(rws[j], rhs[i], c.batch, g.PK, c.pooled != 0).TI);
+    const long long es = c.bf16 ? 2 : 4, lim = 0x7FFFFFFFll;
+    if ((ti_max * c.in.ns + (long long)c.Cin * c.in.cs) * es > lim || (ti_max * c.din.ns + (long long)c.Cout * c.din.cs) * es > lim) g.fits = false;
+    if (c.pooled && ti_max * c.mask.ns + (long long)c.Cout * c.mask.cs > lim) g.fits = false;
+    return g;
+}
+
+}  // namespace
+
 // c.rect must hold the owned rectangles.
 bool thin_wgrad_eligible(const ConvArgs& c)
 {
@@ -774,6 +1067,7 @@ bool thin_wgrad_eligible(const ConvArgs& c)
         for (int t = 0; t < c.M; ++t) if ((c.rect.x0[t] & 1) || !((c.rect.x1[t] - c.rect.x0[t]) & 1)) return false;
         for (int t = 0; t < c.N; ++t) if ((c.rect.y0[t] & 1) || !((c.rect.y1[t] - c.rect.y0[t]) & 1)) return false;
     }
+    if (c.Cin <= 4 && stream_geom(c).fits) return true;
     return thin_geom(c).lds <= 64 * 1024;
 }
 
@@ -784,20 +1078,31 @@ void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
     a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hi; a.Wc = c.Wi; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
     a.splits = c.wgrad_shares_thin;
-    const ThinGeom g = thin_geom(c);
-    a.PK = g.PK;
-    dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
-    g_kernel_label = "k_wgrad_mfma_thin";
     const int nb = (c.Cin * c.K * c.K + 31) / 32;      // 1 (up to 3x3), 2 or 4 (5x5), 4 to 7 (7x7: 5 for 3 channels)
-#define FTP_TW(T, KK, SS, NB, PL) hipLaunchKernelGGL((k_wgrad_mfma_thin<T, KK, SS, NB, PL>), grid, block, g.lds, s, a)
-#define FTP_TWS(T, KK, NB) do { if (c.S == 2) FTP_TW(T, KK, 2, NB, false); else FTP_TW(T, KK, 1, NB, false); } while (0)
-#define FTP_TWK(T) do { \
-        if (c.K == 7)      { if (nb <= 4) FTP_TWS(T, 7, 4); else FTP_TWS(T, 7, 5); } \
-        else if (c.K == 5) { if (nb <= 2) FTP_TWS(T, 5, 2); else FTP_TWS(T, 5, 4); } \
-        else if (c.K == 3) { if (nb <= 1) { if (c.pooled) FTP_TW(T, 3, 1, 1, true); else FTP_TWS(T, 3, 1); } \
-                             else         { if (c.pooled) FTP_TW(T, 3, 1, 2, true); else FTP_TWS(T, 3, 2); } } \
-        else               { if (c.pooled) FTP_TW(T, 1, 1, 1, true); else FTP_TWS(T, 1, 1); } } while (0)
-    if (c.bf16) FTP_TWK(bf16_t); else FTP_TWK(float);
+    dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
+    const ThinStream ts = c.Cin <= 4 ? stream_geom(c) : ThinStream{0, 0, 0, 1, 0, false};
+    const bool stream = ts.fits;
+    const ThinGeom g = stream ? ThinGeom{ts.PK, ts.lds} : thin_geom(c);
+    a.PK = g.PK; a.zs = ts.zs; a.stage_words = ts.stage_words;
+    // more than 64 KB of dynamic LDS has to be granted per kernel, once
+#define FTP_TW(T, TN, KK, SS, NB, PL) do { \
+        if (stream) { \
+            static thread_local size_t granted = 64 * 1024; \
+            if (g.lds > granted) { (void)hipFuncSetAttribute((const void*)k_wgrad_thin_dl<T, KK, SS, NB, PL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds); granted = g.lds; } \
+            g_kernel_label = "k_wgrad_thin_dl<" TN ", " #KK ", " #SS ", " #NB ", " #PL ">"; \
+            hipLaunchKernelGGL((k_wgrad_thin_dl<T, KK, SS, NB, PL>), grid, dim3(320), g.lds, s, a); \
+        } else { \
+            g_kernel_label = "k_wgrad_mfma_thin"; \
+            hipLaunchKernelGGL((k_wgrad_mfma_thin<T, KK, SS, NB, PL>), grid, block, g.lds, s, a); \
+        } } while (0)
+#define FTP_TWS(T, TN, KK, NB) do { if (c.S == 2) FTP_TW(T, TN, KK, 2, NB, false); else FTP_TW(T, TN, KK, 1, NB, false); } while (0)
+#define FTP_TWK(T, TN) do { \
+        if (c.K == 7)      { if (nb <= 4) FTP_TWS(T, TN, 7, 4); else FTP_TWS(T, TN, 7, 5); } \
+        else if (c.K == 5) { if (nb <= 2) FTP_TWS(T, TN, 5, 2); else FTP_TWS(T, TN, 5, 4); } \
+        else if (c.K == 3) { if (nb <= 1) { if (c.pooled) FTP_TW(T, TN, 3, 1, 1, true); else FTP_TWS(T, TN, 3, 1); } \
+                             else         { if (c.pooled) FTP_TW(T, TN, 3, 1, 2, true); else FTP_TWS(T, TN, 3, 2); } } \
+        else               { if (c.pooled) FTP_TW(T, TN, 1, 1, 1, true); else FTP_TWS(T, TN, 1, 1); } } while (0)
+    if (c.bf16) FTP_TWK(bf16_t, "unsigned short"); else FTP_TWK(float, "float");
 #undef FTP_TWK
 #undef FTP_TWS
 #undef FTP_TW
