@@ -143,7 +143,8 @@ inline TileChoice choose_tile(const int* rws, const int* rhs, int N, int M, int 
     };
     // Whole rows of the fewest column blocks are the reference.  Narrower blocks can fill the slots of a tile better (rows
     // of 25 pool windows put 50 into 64 slots, blocks of 9 + 9 + 7 put 63 + 63 + 49 into 192): up to three more blocks are
-    // tried and taken if they save more than 12 % of the tiles (a block more costs a filter halo more).  A rectangle of one
+    // tried and taken if they save more than 9 % of the tiles (a block more costs a filter halo more; config 4, delta through
+    // the first pool: rows of 54 pixels fill 216 of 256 slots, blocks of 18 fill 252, 2.39 -> 2.16 ms).  A rectangle of one
     // column block can be cut into runs of pixels, which leaves no slot empty but makes a tile touch one or two rows more (a
     // larger patch): taken if it saves tiles at all, but not where patch positions are expensive (config 4, delta pass
     // through the first pool: 16 % fewer tiles, a third more patch positions, 13 % slower).
@@ -166,7 +167,7 @@ inline TileChoice choose_tile(const int* rws, const int* rhs, int N, int M, int 
         double best_slots = slots_for(base);
         for (int tx = base + 1; tx <= base + 3 && (mw + tx - 1) / tx >= 4; ++tx) {
             const double sl = slots_for(tx);
-            if (sl < 0.88 * best_slots) { best_slots = sl; tx_rows = tx; }
+            if (sl < 0.91 * best_slots) { best_slots = sl; tx_rows = tx; }
         }
     }
     double best_tiles = 0;
