@@ -273,3 +273,26 @@ def _random_wide_net(seed):
 def test_random_wide_networks(oracle, seed):
     cfg, has_bias = _random_wide_net(seed)
     P.check_case(oracle, cfg, has_bias=has_bias, partial_check=False)
+
+
+_THIN = {
+    # rows of 120 pool windows (two blocks of 64 positions per channel), 40 output channels (a partial block of 32)
+    "wide_rows": ((conv(2, 40), pool(40), conv(40, 8)), 2, 2, 40, 480, (1, 2), "f32"),
+    # rectangles of a few pixels: a chunk holds several images; 5x5 filter on 3 channels (75 columns: three blocks of 32)
+    "small_rects_5x5": ((conv(3, 24, 5), conv(24, 8)), 7, 3, 26, 22, (3, 3), "f32"),
+    # the same behind a pool, 4 input channels (36 columns), bfloat maps
+    "small_rects_pool": ((conv(4, 16), pool(16), conv(16, 8)), 9, 4, 24, 24, (3, 3), "bf16"),
+    # strided 7x7 stem on one channel, odd map, 33 output channels
+    "stem_7x7": ((conv(1, 33, 7, stride=2), conv(33, 8)), 3, 1, 75, 61, (2, 2), "f32"),
+    # odd rectangle widths (rows padded to an even length) and a 1x1 filter on 3 channels
+    "odd_1x1": ((conv(3, 20, 1), conv(20, 8)), 2, 3, 45, 39, (3, 3), "bf16"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(_THIN))
+def test_thin_first_layer_shapes(oracle, name):
+    """First layers with 1 to 4 input channels: the kernels written for them (forward, delta, filter gradient streamed
+    through LDS) on chunk shapes the networks above do not reach."""
+    layers, batch, cin, h, w, grid, dtype = _THIN[name]
+    L = len(layers)
+    P.check_case(oracle, Config("thin_%s" % name, batch, cin, h, w, layers, grid, (L,), dtype), partial_check=False)
