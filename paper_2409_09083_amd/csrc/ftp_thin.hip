@@ -238,14 +238,15 @@ k_conv_bwd_data_thin(View din, View mask, View dout, View isign, int scale_out, 
 
 // ---- the same for K = 3, register-tiled: every thread produces 4 neighbouring pixels of all CI input channels ----
 // Workgroup = TW x TH pixels of one (stack, image), TW = 4 * ntx <= 64, TH = nty <= 64, ntx * nty <= 256, chosen
-// on the host from the largest rectangle so that its tiles leave no ragged last column.  Per 8 output channels the
+// on the host from the largest rectangle so that its tiles leave no ragged last column.  Per 4 output channels the
 // routed dZ patch (tile + filter halo) is staged in LDS - behind a pool one (delta, winner) pair per window
 // serves its 4 pixels - next to the filter slice [co][ci][tap].  A thread reads 3 x 6 patch values and 9 * CI
-// weights per output channel for 36 * CI multiply-adds.
-constexpr int kThin4Coc = 8, kThin4Patch = 1344;     // channels per stage, floats of one channel's patch
+// weights per output channel for 36 * CI multiply-adds.  Four channels per stage (22 KB of LDS) and at most 80 registers:
+// six workgroups share a CU and cover each other's staging (8 channels, three workgroups: config 4 1.16 instead of 0.90 ms).
+constexpr int kThin4Coc = 4, kThin4Patch = 1344;     // channels per stage, floats of one channel's patch
 
 template <typename T, bool POOL, int CI>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 6)              // (six wavefronts a SIMD: the kernel waits for LDS and memory, not for registers)
 k_conv_bwd_data_thin4(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt,
                       const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch,
                       int ntx, int nty, int tiles_x)
@@ -368,7 +369,7 @@ k_conv_bwd_data_thin4(View din, View mask, View dout, View isign, int scale_out,
 // Input pixel (2j + a, 2i + b) receives W[ky][kx] dZ[qy][qx] from the taps with ky = a + P, kx = b + P (mod 2), at
 // qy = j + (a + P - ky) / 2, qx likewise: the four pixels of a cell (j, i) together use every tap exactly once and
 // read the deltas of the cells [j + QLO, j + QHI] x [i + QLO, i + QHI] (4 x 4 for a 7x7 filter).
-// Workgroup = 16 x 16 cells (32 x 32 pixels) of one (stack, image), one cell per thread.  Per 16 output channels the
+// Workgroup = 16 x 16 cells (32 x 32 pixels) of one (stack, image), one cell per thread.  Per 8 output channels the
 // delta patch (tile + that halo; zero outside the stack's delta rectangle) and the filter slice [co][tap][ci padded
 // to 4] (fp32) are staged in LDS; a thread reads its NQ x NQ deltas and one 16-byte filter vector per tap for
 // K * K * CI multiply-adds per output channel.
@@ -376,10 +377,10 @@ template <int K> struct StridedTaps {
     static constexpr int P = K / 2;
     static constexpr int QLO = -((K - 1 - P) / 2), QHI = (1 + P) / 2, NQ = QHI - QLO + 1;
 };
-constexpr int kThinS2Coc = 16, kThinS2Cells = 16;
+constexpr int kThinS2Coc = 8, kThinS2Cells = 16;      // (8 channels a stage, 18 KB of LDS: five workgroups a CU; 16 channels, four workgroups: 3.37 instead of 2.85 ms on the 7x7 stem)
 
 template <typename T, int K, int CI>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 5)
 k_conv_bwd_data_thin_s2(View din, View dout, View isign, int scale_out, float in_slope, RectTab rt, RectTab ext,
                         const T* __restrict__ w, int Cin, int Cout, int M, int batch, int tiles_x)
 {
