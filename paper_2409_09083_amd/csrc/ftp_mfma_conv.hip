@@ -299,6 +299,9 @@ __host__ __device__ constexpr int conv_dl_stage_channels(int K, bool strided_fwd
 // delta kernels of the deep layers slower (more workgroups competing for the L2) and is not used there.
 __host__ __device__ constexpr int conv_dl_waves(size_t elem, int K, int stride, int MT, int BN, int WAVES_M, bool pool_out)
 {
+    // (fp32 3x3, 256 pixels, at most 64 accumulator registers: these came out at 131-134 registers, one too many for a
+    // fourth workgroup on the CU, which LDS would hold: config 4, forward of the 32 -> 64 layer 2.34 -> 2.22 ms)
+    if (elem == 4 && K == 3 && stride == 1 && BN == 256 && MT * (BN / 32 / (4 / WAVES_M)) <= 4) return 4;
     return (elem == 2 && K <= 3 && stride == 1 && pool_out && BN == 128 && MT * (BN / 32 / (4 / WAVES_M)) <= 2) ? 4 : 2;
 }
 
