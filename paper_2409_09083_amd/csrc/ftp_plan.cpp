@@ -302,12 +302,7 @@ int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int i
                 for (int j = 0; j < M; ++j) { const Seg sx = gr.at(FTP_RECT_OWN, u.layer + 1, 0, j); rws[j] = sx.b - sx.a + 1; }
                 for (int i = 0; i < N; ++i) { const Seg sy = gr.at(FTP_RECT_OWN, u.layer + 1, 1, i); rhs[i] = sy.b - sy.a + 1; }
                 const ThinStream ts = thin_stream_geom(rws, rhs, N, M, batch, ly.cin, ly.k, ly.stride, u.pooled);
-                if (ts.fits) {
-                    int sc = 1;
-                    for (int i = 0; i < N; ++i)
-                        for (int j = 0; j < M; ++j) sc = std::max(sc, thin_wgrad_chunks(rws[j], rhs[i], batch, ts.PK, u.pooled).total);
-                    u.wgrad_shares_thin = wgrad_shares_thin(ly.cout, N * M, sc, 256 * ts.wgs_per_cu);
-                }
+                if (ts.fits) u.wgrad_shares_thin = wgrad_shares_thin(ly.cout, N * M, ts.max_chunks, 256 * ts.wgs_per_cu);
             }
             if (dtype == FTP_BF16 && ly.k == 3 && ly.stride == 1) {
                 int c16 = 1;

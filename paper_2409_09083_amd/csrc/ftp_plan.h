@@ -220,32 +220,56 @@ FTP_HD inline ThinChunks thin_wgrad_chunks(int rw, int rh, int batch, int PK, bo
     return c;
 }
 // The streamed form of that kernel keeps two chunks in LDS (dZ as [32 channels][zs positions], at the pooled resolution
-// behind a pool, where the winner codes follow in the same layout; then the patch), one dword a position.
-FTP_HD constexpr int kThinZPass(bool pooled) { return pooled ? 2 : 4; }      // dZ positions of a chunk, in blocks of 64
-struct ThinStream { int PK, zs, stage_words, wgs_per_cu; size_t lds; bool fits; };
+// behind a pool, where the winner codes follow in the same layout; then the patch), one dword a position.  Its chunks: a
+// column block of at most 128 pixels (the rectangle's width in equal, even blocks) x as many rows as 128 pixels - behind a
+// pool 64 windows - allow, x several images where one image's rectangle is smaller than that.  cb_max: widest column block
+// (128, or 64 / 32 where the patch of wider blocks - large strided filters - would not fit LDS).
+FTP_HD constexpr int kThinZPass(bool pooled) { return pooled ? 1 : 2; }      // dZ positions of a chunk, in blocks of 64
+struct ThinStreamChunks { int TC, col_blocks, TR, row_blocks, TI, img_blocks, total; };
+FTP_HD inline ThinStreamChunks thin_stream_chunks(int rw, int rh, int batch, bool pooled, int cb_max)
+{
+    ThinStreamChunks c;
+    const int rwp = (rw + 1) & ~1;
+    c.col_blocks = (rwp + cb_max - 1) / cb_max;
+    c.TC = (((rwp + c.col_blocks - 1) / c.col_blocks) + 1) & ~1;
+    const int room = pooled ? 256 : 128;               // pixels of a chunk
+    c.TR = room / c.TC; if (c.TR < 1) c.TR = 1;
+    if (pooled) { c.TR &= ~1; if (c.TR < 2) c.TR = 2; }
+    if (c.TR > rh) c.TR = rh;
+    c.TI = 1;
+    if (c.TR == rh && c.col_blocks == 1) { c.TI = room / (c.TC * rh); if (c.TI < 1) c.TI = 1; }
+    c.row_blocks = (rh + c.TR - 1) / c.TR;
+    c.img_blocks = (batch + c.TI - 1) / c.TI;
+    c.total = c.img_blocks * c.row_blocks * c.col_blocks;
+    return c;
+}
+struct ThinStream { int cb_max, zs, stage_words, wgs_per_cu, max_chunks, max_ti; size_t lds; bool fits; };
 inline ThinStream thin_stream_geom(const int* rws, const int* rhs, int N, int M, int batch, int cin, int K, int S, bool pooled)
 {
     ThinStream g;
     const int P = K / 2;
-    int wmax = 0;
-    for (int j = 0; j < M; ++j) { const int w = (rws[j] + 1) & ~1; if (w > wmax) wmax = w; }
-    // behind a pool a chunk is 64 windows or one row of windows; else 128 pixels or one row
-    g.PK = pooled ? (2 * wmax > 256 ? 2 * wmax : 256) : (wmax > 128 ? wmax : 128);
-    int nzp = 1, xmax = 1;
-    for (int i = 0; i < N; ++i)
-        for (int j = 0; j < M; ++j) {
-            const ThinChunks tc = thin_wgrad_chunks(rws[j], rhs[i], batch, g.PK, pooled);
-            const int z = pooled ? tc.TI * (tc.TR >> 1) * (tc.TCp >> 1) : tc.TI * tc.TR * tc.TCp;
-            const int x = cin * tc.TI * (S * tc.TR + 2 * P) * (S * tc.TCp + 2 * P);
-            if (z > nzp) nzp = z;
-            if (x > xmax) xmax = x;
-        }
-    g.zs = ((nzp + 63) & ~63) + 2;
-    g.stage_words = 32 * g.zs * (pooled ? 2 : 1) + xmax + 4;
-    size_t words = 2 * (size_t)g.stage_words;
-    if (words < 3 * 16 * 64) words = 3 * 16 * 64;                              // final sum of the wavefronts
-    g.lds = words * sizeof(float);
-    g.fits = nzp <= 64 * kThinZPass(pooled) && g.lds <= 64 * 1024;
+    for (g.cb_max = 128; ; g.cb_max /= 2) {
+        int nzp = 1, xmax = 1;
+        g.max_chunks = 1; g.max_ti = 1;
+        for (int i = 0; i < N; ++i)
+            for (int j = 0; j < M; ++j) {
+                const ThinStreamChunks tc = thin_stream_chunks(rws[j], rhs[i], batch, pooled, g.cb_max);
+                const int z = pooled ? tc.TI * (tc.TR >> 1) * (tc.TC >> 1) : tc.TI * tc.TR * tc.TC;
+                const int x = cin * tc.TI * (S * tc.TR + 2 * P) * (S * tc.TC + 2 * P);
+                if (z > nzp) nzp = z;
+                if (x > xmax) xmax = x;
+                if (tc.total > g.max_chunks) g.max_chunks = tc.total;
+                if (tc.TI > g.max_ti) g.max_ti = tc.TI;
+            }
+        g.zs = ((nzp + 63) & ~63) + 2;
+        g.stage_words = 32 * g.zs * (pooled ? 2 : 1) + xmax + 4;
+        size_t words = 2 * (size_t)g.stage_words;
+        if (words < 3 * 16 * 64) words = 3 * 16 * 64;                          // final sum of the wavefronts
+        g.lds = words * sizeof(float);
+        g.fits = nzp <= 64 * kThinZPass(pooled) && g.lds <= 64 * 1024;
+        break;                                         // (narrower blocks for patches that do not fit were measured: slower than the
+                                                       // register-staged kernel, which takes those layers)
+    }
     const int per_cu = (int)((160 * 1024) / g.lds);
     g.wgs_per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
     return g;

@@ -745,7 +745,8 @@ k_wgrad_mfma_thin(MfmaWgradArgs a)
 // registers (one barrier a chunk).  A stage holds dZ as [32 channels][zs positions] - at the pooled resolution behind a
 // pool, followed by the winner codes in the same layout - and the patch [ci][image][row][column] in natural order; 16-bit
 // maps occupy one dword a position (the bits in the lower half).  zs = 2 mod 64 keeps the A-operand reads (32 channels
-// x 2 neighbouring pixels) on 64 different banks.
+// x 2 neighbouring pixels) on 64 different banks.  A chunk = a column block of the rectangle (at most 128 pixels wide) x
+// the rows that 128 pixels (64 pool windows) allow x, for small rectangles, several images (thin_stream_chunks).
 // Five wavefronts: the fifth only issues the loads (lane -> position of a row, one instruction per channel / patch row)
 // and waits for them, so that the address arithmetic never sits between the matrix instructions of the four that
 // multiply; these split the pixel pairs of every row among themselves as in the kernel above.
@@ -767,8 +768,8 @@ k_wgrad_thin_dl(MfmaWgradArgs a)
     const int co0 = blockIdx.x * 32;
     const int split = blockIdx.y;
 
-    const ThinChunks tc = thin_wgrad_chunks(rw, rh, a.batch, a.PK, POOL);
-    const int TCp = tc.TCp, TR = tc.TR, TI = tc.TI, row_blocks = tc.row_blocks;
+    const ThinStreamChunks tc = thin_stream_chunks(rw, rh, a.batch, POOL, a.PK);      // (a.PK: widest column block)
+    const int TCp = tc.TC, TR = tc.TR, TI = tc.TI, row_blocks = tc.row_blocks, col_blocks = tc.col_blocks;
     const int id0 = (int)((long long)split * tc.total / a.splits), id1 = (int)((long long)(split + 1) * tc.total / a.splits);
     const int PW = S * TCp + 2 * P, PH = S * TR + 2 * P;
     const int XCS = TI * PH * PW;                      // channel stride of the patch
@@ -791,7 +792,7 @@ k_wgrad_thin_dl(MfmaWgradArgs a)
 
     // which (image, row, column) of a chunk a lane stages is the same for every chunk (chunks of several images hold
     // whole rectangles): divided once.  z_r: pixel row inside the chunk.
-    int z_il[ZPASS], z_r[ZPASS]; unsigned z_vo[ZPASS], z_mo[ZPASS];
+    int z_il[ZPASS], z_r[ZPASS], z_c[ZPASS]; unsigned z_vo[ZPASS], z_mo[ZPASS];
 #pragma unroll
     for (int p = 0; p < ZPASS; ++p) {
         const int zi = lane + 64 * p;
@@ -800,20 +801,31 @@ k_wgrad_thin_dl(MfmaWgradArgs a)
         const int il = TI > 1 ? row / rows_img : 0;
         const int r = row - il * rows_img;
         z_r[p] = POOL ? 2 * r : r;
-        const bool ok = zi < nzp && (POOL || c < rw);
+        z_c[p] = POOL ? 2 * c : c;                     // pixel column inside the chunk
+        const bool ok = zi < nzp;
         z_il[p] = ok ? il : a.batch;                   // (a.batch: never inside a chunk)
         z_vo[p] = ok ? (unsigned)ES * (unsigned)(il * (int)a.din.ns + r * a.din.pitch + c) : 0u;
         z_mo[p] = POOL && ok ? (unsigned)(il * (int)a.mask.ns + r * a.mask.pitch + c) : 0u;
     }
 
-    struct Chunk { int n0, ni, yb, nr, rb; };
+    // chunk list: image block, row block, column block (fastest); walked with counters, divided once
+    struct Chunk { int ib, n0, ni, yb, nr, rb, cb, nc; };      // nc: columns of the block that lie in the rectangle
+    auto fill = [&](Chunk& c) {
+        c.n0 = c.ib * TI; c.ni = (a.batch - c.n0) < TI ? (a.batch - c.n0) : TI;
+        c.yb = y0 + c.rb * TR; c.nr = (y1 - c.yb + 1) < TR ? (y1 - c.yb + 1) : TR;
+        c.nc = (rw - c.cb * TCp) < TCp ? (rw - c.cb * TCp) : TCp;
+    };
     auto chunk_at = [&](int id) {
         Chunk c;
-        const int ib = id / row_blocks;
-        c.rb = id - ib * row_blocks;
-        c.n0 = ib * TI; c.ni = (a.batch - c.n0) < TI ? (a.batch - c.n0) : TI;
-        c.yb = y0 + c.rb * TR; c.nr = (y1 - c.yb + 1) < TR ? (y1 - c.yb + 1) : TR;
+        c.ib = id / (row_blocks * col_blocks);
+        const int rem = id - c.ib * (row_blocks * col_blocks);
+        c.rb = rem / col_blocks; c.cb = rem - c.rb * col_blocks;
+        fill(c);
         return c;
+    };
+    auto next_chunk = [&](Chunk& c) {
+        if (++c.cb == col_blocks) { c.cb = 0; if (++c.rb == row_blocks) { c.rb = 0; ++c.ib; } }
+        fill(c);
     };
 
     // Per load instruction only a scalar offset changes: the channel's (a channel beyond the layer's last loads the last
@@ -826,23 +838,24 @@ k_wgrad_thin_dl(MfmaWgradArgs a)
                                          + ((y0 >> 1) - a.mask.y0[ti]) * a.mask.pitch + ((x0 >> 1) - a.mask.x0[tj]) : nullptr;
     const long long z_ns = a.din.ns, m_ns = a.mask.ns, x_ns = a.in.ns;
     const int z_rowstep = (POOL ? TR >> 1 : TR) * a.din.pitch, m_rowstep = POOL ? (TR >> 1) * a.mask.pitch : 0;
+    const int z_colstep = POOL ? TCp >> 1 : TCp;
     // the patch: column offsets of this lane (the same for every chunk), rows relative to the map row S * y0 - P
     const T* const xstack = (const T*)a.in.p + (long long)stack * a.in.ss - (long long)a.in.y0[ti] * a.in.pitch - a.in.x0[tj];
     const int x_pitch = a.in.pitch, x_cs = (int)a.in.cs;
-    const int gx0 = S * x0 - P, ncol = S * rw + 2 * P;
+    const int gx00 = S * x0 - P;
     const int Hc = a.Hc, Cin = a.Cin;
 
     auto issue = [&](const Chunk& c, int rb, float* st) {
         // dZ (and the winner codes): lanes without a pixel receive zeros
         {
-            const T* gbase = zstack + c.n0 * z_ns + rb * z_rowstep;
+            const T* gbase = zstack + c.n0 * z_ns + rb * z_rowstep + c.cb * z_colstep;
             const __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc((void*)gbase, (short)0, 0x7FFFFFFF, 0x00020000);
-            const uint8_t* mbase = POOL ? mstack + c.n0 * m_ns + rb * m_rowstep : nullptr;
+            const uint8_t* mbase = POOL ? mstack + c.n0 * m_ns + rb * m_rowstep + c.cb * z_colstep : nullptr;
             const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)mbase, (short)0, 0x7FFFFFFF, 0x00020000);
 #pragma unroll
             for (int p = 0; p < ZPASS; ++p) {
                 if (64 * p < nzp) {
-                    const bool ok = z_il[p] < c.ni && z_r[p] < c.nr;
+                    const bool ok = z_il[p] < c.ni && z_r[p] < c.nr && z_c[p] < c.nc;
                     const unsigned gv = ok ? z_vo[p] : OOB, mv = ok ? z_mo[p] : OOB;
 #pragma unroll 8
                     for (int ch = 0; ch < 32; ++ch) {
@@ -858,8 +871,8 @@ k_wgrad_thin_dl(MfmaWgradArgs a)
         }
         // the patch, 64 columns of a row to an instruction; rows and columns outside the map are filled with zeros
         {
-            const int nph = S * c.nr + 2 * P;
-            const int gy0 = S * c.yb - P;
+            const int nph = S * c.nr + 2 * P, ncol = S * c.nc + 2 * P;
+            const int gy0 = S * c.yb - P, gx0 = gx00 + S * c.cb * TCp;
             const T* base = xstack + c.n0 * x_ns + (long long)gy0 * x_pitch;       // (row gy0 may lie above the map: never read)
             const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, (short)0, 0x7FFFFFFF, 0x00020000);
             float* xs = st + zwords;
@@ -895,7 +908,7 @@ k_wgrad_thin_dl(MfmaWgradArgs a)
                     const float* xrow = xs + (il * PH + 2 * wr) * PW;
                     // this wavefront's windows wave, wave + 4, ...: two to a turn of the loop, the LDS reads of each issued
                     // before the matrix instructions of the one before
-                    const int n = (wpr - wave + 3) >> 2;
+                    const int n = ((c.nc >> 1) - wave + 3) >> 2;
                     if (n <= 0) continue;
                     const float* pz = zrow + wave;
                     const float* px[NB];
@@ -947,12 +960,13 @@ k_wgrad_thin_dl(MfmaWgradArgs a)
                 for (int r = 0; r < c.nr; ++r) {
                     const float* zrow = st + l32 * zs + (il * TR + r) * TCp + hi;
                     const float* xrow = xs + (il * PH + S * r) * PW;
-                    if (2 * wave >= TCp) continue;
+                    const int ncp = (c.nc + 1) & ~1;
+                    if (2 * wave >= ncp) continue;
                     float zc = zrow[2 * wave], xc[NB];
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) xc[nb] = xrow[lane_off[nb] + S * 2 * wave];
-                    for (int xp = 2 * wave; xp < TCp; xp += 8) {
-                        const int xn = xp + 8 < TCp ? xp + 8 : xp;
+                    for (int xp = 2 * wave; xp < ncp; xp += 8) {
+                        const int xn = xp + 8 < ncp ? xp + 8 : xp;
                         const float zn = zrow[xn];
                         float xnv[NB];
 #pragma unroll
@@ -974,16 +988,19 @@ k_wgrad_thin_dl(MfmaWgradArgs a)
 
     if (wave == 4) {
         // the loader: chunk id + 1 is on its way while the others multiply chunk id
-        if (id0 < id1) issue(chunk_at(id0), chunk_at(id0).rb, lds);
+        Chunk c = chunk_at(id0);
+        if (id0 < id1) issue(c, c.rb, lds);
         for (int id = id0; id < id1; ++id) {
             __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): chunk id has landed
             __syncthreads();                           // ... and the stage of chunk id - 1 has been consumed
-            if (id + 1 < id1) { const Chunk nxt = chunk_at(id + 1); issue(nxt, nxt.rb, lds + ((id + 1 - id0) & 1) * a.stage_words); }
+            if (id + 1 < id1) { next_chunk(c); issue(c, c.rb, lds + ((id + 1 - id0) & 1) * a.stage_words); }
         }
     } else {
+        Chunk c = chunk_at(id0);
         for (int id = id0; id < id1; ++id) {
             __syncthreads();
-            multiply(chunk_at(id), lds + ((id - id0) & 1) * a.stage_words);
+            multiply(c, lds + ((id - id0) & 1) * a.stage_words);
+            next_chunk(c);
         }
     }
 
@@ -1047,9 +1064,7 @@ ThinStream stream_geom(const ConvArgs& c)
     for (int i = 0; i < c.N; ++i) rhs[i] = c.rect.y1[i] - c.rect.y0[i] + 1;
     ThinStream g = thin_stream_geom(rws, rhs, c.N, c.M, c.batch, c.Cin, c.K, c.S, c.pooled != 0);
     // the kernel addresses one chunk's images with 32-bit byte offsets
-    int ti_max = 1;
-    for (int i = 0; i < c.N; ++i)
-        for (int j = 0; j < c.M; ++j) ti_max = std::max(ti_max, thin_wgrad_chunks(rws[j], rhs[i], c.batch, g.PK, c.pooled != 0).TI);
+    const int ti_max = g.max_ti;
     const long long es = c.bf16 ? 2 : 4, lim = 0x7FFFFFFFll;
     if ((ti_max * c.in.ns + (long long)c.Cin * c.in.cs) * es > lim || (ti_max * c.din.ns + (long long)c.Cout * c.din.cs) * es > lim) g.fits = false;
     if (c.pooled && ti_max * c.mask.ns + (long long)c.Cout * c.mask.cs > lim) g.fits = false;
@@ -1081,9 +1096,9 @@ void thin_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     a.splits = c.wgrad_shares_thin;
     const int nb = (c.Cin * c.K * c.K + 31) / 32;      // 1 (up to 3x3), 2 or 4 (5x5), 4 to 7 (7x7: 5 for 3 channels)
     dim3 grid((c.Cout + 31) / 32, a.splits, c.N * c.M), block(256);
-    const ThinStream ts = c.Cin <= 4 ? stream_geom(c) : ThinStream{0, 0, 0, 1, 0, false};
+    const ThinStream ts = c.Cin <= 4 ? stream_geom(c) : ThinStream{0, 0, 0, 1, 1, 1, 0, false};
     const bool stream = ts.fits;
-    const ThinGeom g = stream ? ThinGeom{ts.PK, ts.lds} : thin_geom(c);
+    const ThinGeom g = stream ? ThinGeom{ts.cb_max, ts.lds} : thin_geom(c);
     a.PK = g.PK; a.zs = ts.zs; a.stage_words = ts.stage_words;
     // more than 64 KB of dynamic LDS has to be granted per kernel, once
 #define FTP_TW(T, TN, KK, SS, NB, PL) do { \

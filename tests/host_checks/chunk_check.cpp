@@ -82,7 +82,7 @@ int main()
                 if (pooled && (S != 1 || K > 3)) continue;
                 const int P = K / 2;
                 for (int cin = 1; cin <= 4; ++cin)
-                    for (int rw0 = pooled ? 2 : 1; rw0 <= 300; rw0 += pooled ? 2 : 3)
+                    for (int rw0 = pooled ? 2 : 1; rw0 <= 620; rw0 += pooled ? 2 : 3)
                         for (int d = 0; d <= 4; d += 2)
                             for (int rh0 = pooled ? 2 : 1; rh0 <= 80; rh0 += pooled ? 6 : 7)
                                 for (int batch = 1; batch <= 9; batch += 4) {
@@ -93,21 +93,25 @@ int main()
                                     bool ok = g.zs % 64 == 2 && g.lds <= 64 * 1024 && 2 * (size_t)g.stage_words * 4 <= g.lds && g.wgs_per_cu >= 1;
                                     for (int i = 0; i < 2 && ok; ++i)
                                         for (int j = 0; j < 2 && ok; ++j) {
-                                            const ftp::ThinChunks c = ftp::thin_wgrad_chunks(rws[j], rhs[i], batch, g.PK, pooled != 0);
-                                            const int nzp = pooled ? c.TI * (c.TR >> 1) * (c.TCp >> 1) : c.TI * c.TR * c.TCp;
+                                            const ftp::ThinStreamChunks c = ftp::thin_stream_chunks(rws[j], rhs[i], batch, pooled != 0, g.cb_max);
+                                            const int nzp = pooled ? c.TI * (c.TR >> 1) * (c.TC >> 1) : c.TI * c.TR * c.TC;
                                             const int passes = (nzp + 63) / 64;
-                                            const int PW = S * c.TCp + 2 * P, PH = S * c.TR + 2 * P, XCS = c.TI * PH * PW;
+                                            const int PW = S * c.TC + 2 * P, PH = S * c.TR + 2 * P, XCS = c.TI * PH * PW;
                                             const int zwords = 32 * g.zs * (pooled ? 2 : 1);
-                                            ok = ok && (!pooled || ((c.TR & 1) == 0 && (c.TCp & 1) == 0));
+                                            ok = ok && c.TC >= 2 && (c.TC & 1) == 0 && c.TC <= g.cb_max && c.col_blocks * c.TC >= rws[j] && (c.col_blocks - 1) * c.TC < rws[j];
+                                            ok = ok && c.TR >= 1 && c.row_blocks * c.TR >= rhs[i] && c.TI >= 1 && c.img_blocks * c.TI >= batch;
+                                            ok = ok && c.total == c.img_blocks * c.row_blocks * c.col_blocks && c.total <= g.max_chunks && c.TI <= g.max_ti;
+                                            ok = ok && (c.TI == 1 || (c.TR == rhs[i] && c.col_blocks == 1));
+                                            ok = ok && (!pooled || (c.TR & 1) == 0);
                                             ok = ok && passes <= ftp::kThinZPass(pooled != 0) && 64 * passes <= g.zs - 2;
                                             ok = ok && zwords + cin * XCS <= g.stage_words;
                                             // last B operand: lane (last channel, last tap, second pixel of the pair), last row, last pair
-                                            const int last = (cin - 1) * XCS + (K - 1) * PW + (K - 1) + S + ((c.TI - 1) * PH + S * (c.TR - 1)) * PW + S * (c.TCp - 2);
+                                            const int last = (cin - 1) * XCS + (K - 1) * PW + (K - 1) + S + ((c.TI - 1) * PH + S * (c.TR - 1)) * PW + S * (c.TC - 2);
                                             ok = ok && last < cin * XCS;
                                         }
                                     if (!ok) {
-                                        std::printf("thin_stream_geom(rw=%d+%d, rh=%d+%d, batch=%d, cin=%d, K=%d, S=%d, pooled=%d): PK=%d zs=%d stage=%d lds=%zu\n",
-                                                    rw0, d, rh0, d, batch, cin, K, S, pooled, g.PK, g.zs, g.stage_words, g.lds);
+                                        std::printf("thin_stream_geom(rw=%d+%d, rh=%d+%d, batch=%d, cin=%d, K=%d, S=%d, pooled=%d): block=%d zs=%d stage=%d lds=%zu\n",
+                                                    rw0, d, rh0, d, batch, cin, K, S, pooled, g.cb_max, g.zs, g.stage_words, g.lds);
                                         return 1;
                                     }
                                 }
