@@ -284,6 +284,8 @@ _THIN = {
     "small_rects_pool": ((conv(4, 16), pool(16), conv(16, 8)), 9, 4, 24, 24, (3, 3), "bf16"),
     # strided 7x7 stem on one channel, odd map, 33 output channels
     "stem_7x7": ((conv(1, 33, 7, stride=2), conv(33, 8)), 3, 1, 75, 61, (2, 2), "f32"),
+    # three column blocks, the last one of odd width; no pool
+    "wide_odd": ((conv(3, 16), conv(16, 8)), 2, 3, 9, 301, (1, 1), "f32"),
     # odd rectangle widths (rows padded to an even length) and a 1x1 filter on 3 channels
     "odd_1x1": ((conv(3, 20, 1), conv(20, 8)), 2, 3, 45, 39, (3, 3), "bf16"),
 }
