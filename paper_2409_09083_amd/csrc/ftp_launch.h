@@ -94,6 +94,8 @@ bool mfma_conv_packs_bf16(const ConvArgs& a);
 void prep_filter(const void* w, int bf16, int packed16, float* wt_fwd, float* wt_bwd, int Cout, int Cin, int K, hipStream_t s);
 int mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);       // non-zero: does not fit
 int mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
+// delta through a 3x3 stride-2 convolution by parity classes (ftp_delta_s2.hip); non-zero: does not fit
+int delta_s2_mfma(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s);
 
 // Kernel argument block of the matrix-core filter gradient.
 struct MfmaWgradArgs {
