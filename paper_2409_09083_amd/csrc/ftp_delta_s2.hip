@@ -2,11 +2,12 @@
 // Eq. (2) with S_l = 2: input pixel (2j + a, 2i + b) receives W[ky][kx]^T dZ[qy][qx] only from the taps with
 // ky = a + 1 (mod 2), kx = b + 1 (mod 2), at qy = j + (a + 1 - ky) / 2, qx likewise.  The four pixels of a cell (j, i)
 // form four parity classes with 1, 2, 2 and 4 taps: together they use each of the 9 taps once, on the 2 x 2
-// neighbourhood dZ[j .. j+1][i .. i+1].  A workgroup takes a tile of 8 x 16 cells of one (stack, image) and 32 * MT
-// input channels; each of its four multiplying wavefronts owns two cell rows (32 cells = the N side of a
-// 32x32x2 MFMA) and keeps one accumulator tile per class and channel block, so every MFMA multiplies deltas that exist.
+// neighbourhood dZ[j .. j+1][i .. i+1].  A stack's cells are cut into blocks of 32 (1 x 32, 2 x 16 or 4 x 8, whichever gives
+// the fewest blocks; listed over image, row group, column group); a workgroup takes four consecutive blocks and 32 * MT
+// input channels; each of its four multiplying wavefronts owns one block (32 cells = the N side of a 32x32x2 MFMA)
+// and keeps one accumulator tile per class and channel block, so every MFMA multiplies deltas that exist.
 // The reduction runs over the output channels in stages of 8: filter slice [tap][8][channels] and delta patch
-// [8][9 x 17 positions] travel HBM -> LDS with buffer_load ... lds, issued by a fifth wavefront one stage ahead (two LDS
+// [block][8][(rows + 1) x (columns + 1) positions] travel HBM -> LDS with buffer_load ... lds, issued by a fifth wavefront one stage ahead (two LDS
 // stages, one barrier a stage).  Positions outside the map (zero padding) or outside the stack's delta view (never
 // needed by a valid pixel) are loaded from beyond the buffer's records and read as zero.
 #include "ftp_device.h"
@@ -25,49 +26,72 @@ struct DeltaS2Args {
     int C, Mtot;                                    // reduction (output) channels, produced (input) channels
     int Hd, Wd;                                     // extent of the delta map at the output side
     int scale_out; float in_slope;
-    int M, batch, tiles_x;
+    int M, batch;
 };
 
-constexpr int kS2Rows = 8, kS2Cols = 16, kS2PW = kS2Cols + 1, kS2PH = kS2Rows + 1, kS2Pos = kS2PW * kS2PH;
-constexpr int kS2XCS = 161;                         // dwords between two channels of the patch
+constexpr int kS2XCS = 67;                          // dwords between two channels of a block's patch (at most 2 x 33 positions)
 constexpr int kS2CK = 8;                            // reduction channels per stage
 #define FTP_S2_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 
-template <typename T, int MT>
+// Blocks of 32 cells (32 / NC rows x NC columns) of one stack: image, row group, column group (fastest).
+struct S2Blocks { int gc, gr, total; };
+__host__ __device__ inline S2Blocks s2_blocks(int x0, int x1, int y0, int y1, int batch, int NC)
+{
+    S2Blocks b;
+    const int cw = (x1 >> 1) - (x0 >> 1) + 1, ch = (y1 >> 1) - (y0 >> 1) + 1, NR = 32 / NC;
+    b.gc = (cw + NC - 1) / NC; b.gr = (ch + NR - 1) / NR;
+    b.total = batch * b.gr * b.gc;
+    return b;
+}
+
+template <typename T, int MT, int NC>
 __global__ void __launch_bounds__(320)
 k_delta_s2_mfma(DeltaS2Args a)
 {
-    constexpr int BM = 32 * MT, ES = sizeof(T);
+    constexpr int BM = 32 * MT, ES = sizeof(T), NR = 32 / NC;
+    constexpr int PW = NC + 1, NPOS = (NR + 1) * PW, XPASS = (NPOS + 63) / 64;
     constexpr int WF = 9 * kS2CK * BM;                 // dwords of a filter slice
-    constexpr int STAGE = WF + kS2CK * kS2XCS;
+    constexpr int XB = kS2CK * kS2XCS;                 // dwords of one block's patch
+    constexpr int STAGE = WF + 4 * XB;
     constexpr unsigned OOB = 0x80000000u;
+    static_assert(NPOS <= kS2XCS, "a block's patch fits its channel stride");
     __shared__ __attribute__((aligned(16))) float lds[2 * STAGE];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hi = lane >> 5, l32 = lane & 31;
-    const int stack = blockIdx.z / a.batch, n = blockIdx.z - stack * a.batch;
-    const int ti = stack / a.M, tj = stack % a.M;
+    const int stack = blockIdx.z, ti = stack / a.M, tj = stack % a.M;
     const int x0 = a.rect.x0[tj], x1 = a.rect.x1[tj], y0 = a.rect.y0[ti], y1 = a.rect.y1[ti];
-    const int bx = blockIdx.x % a.tiles_x, by = blockIdx.x / a.tiles_x;
-    const int J0 = (y0 >> 1) + kS2Rows * by, I0 = (x0 >> 1) + kS2Cols * bx;      // first cell of the tile
-    if (2 * J0 > y1 || 2 * I0 > x1) return;
+    const S2Blocks sb = s2_blocks(x0, x1, y0, y1, a.batch, NC);
+    if (4 * (int)blockIdx.x >= sb.total) return;
     const int m0 = blockIdx.y * BM;
     const int nst = (a.C + kS2CK - 1) / kS2CK;
+    // block q of the stack -> image and first cell
+    auto block_at = [&](int q, int& img, int& J0, int& I0) {
+        img = q / (sb.gr * sb.gc);
+        const int rem = q - img * (sb.gr * sb.gc), rg = rem / sb.gc;
+        J0 = (y0 >> 1) + NR * rg; I0 = (x0 >> 1) + NC * (rem - rg * sb.gc);
+    };
 
     if (wave == 4) {
         // ---- the loader ------------------------------------------------------------------------------------------
-        const T* src = (const T*)a.din.p + (long long)stack * a.din.ss + (long long)n * a.din.ns;
+        const T* src = (const T*)a.din.p + (long long)stack * a.din.ss;
         const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)src, (short)0, 0x7FFFFFFF, 0x00020000);
         const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.wt, (short)0, 0x7FFFFFFF, 0x00020000);
-        unsigned xvo[3];
+        unsigned xvo[4][XPASS];
 #pragma unroll
-        for (int u = 0; u < 3; ++u) {
-            const int p = lane + 64 * u;
-            const int prow = p / kS2PW, pcol = p - prow * kS2PW;
-            const int qy = J0 + prow, qx = I0 + pcol;
-            const bool ok = p < kS2Pos && qy >= 0 && qy < a.Hd && qx >= 0 && qx < a.Wd &&
-                            qy >= a.iy0[ti] && qy <= a.iy1[ti] && qx >= a.ix0[tj] && qx <= a.ix1[tj];
-            xvo[u] = ok ? (unsigned)ES * (unsigned)((qy - a.din.y0[ti]) * a.din.pitch + (qx - a.din.x0[tj])) : OOB;
+        for (int w = 0; w < 4; ++w) {
+            const int q = 4 * blockIdx.x + w;
+            int img, J0, I0;
+            block_at(q < sb.total ? q : 0, img, J0, I0);
+#pragma unroll
+            for (int u = 0; u < XPASS; ++u) {
+                const int p = lane + 64 * u;
+                const int prow = p / PW, pcol = p - prow * PW;
+                const int qy = J0 + prow, qx = I0 + pcol;
+                const bool ok = q < sb.total && p < NPOS && qy >= 0 && qy < a.Hd && qx >= 0 && qx < a.Wd &&
+                                qy >= a.iy0[ti] && qy <= a.iy1[ti] && qx >= a.ix0[tj] && qx <= a.ix1[tj];
+                xvo[w][u] = ok ? (unsigned)ES * (unsigned)(img * (int)a.din.ns + (qy - a.din.y0[ti]) * a.din.pitch + (qx - a.din.x0[tj])) : OOB;
+            }
         }
         constexpr int RPP = 256 / BM, WINSTR = (WF + 255) / 256;     // filter rows per load instruction; instructions per slice
         const int wrow = lane / (BM / 4), wcol = 4 * (lane % (BM / 4));
@@ -76,22 +100,25 @@ k_delta_s2_mfma(DeltaS2Args a)
 #pragma unroll
             for (int idx = 0; idx < WINSTR; ++idx) {
                 const int row = idx * RPP + wrow, tap = row / kS2CK, k = row - tap * kS2CK;
-                if (row < 9 * kS2CK) {                                               // (the last instruction of a 32-channel slice is half empty)
+                if (row < 9 * kS2CK) {                                               // (the last instruction of a slice may be half empty)
                     const bool ok = c0 + k < a.C && m0 + wcol < a.Mtot;
                     const unsigned vo = ok ? 4u * (unsigned)(((8 - tap) * a.C + c0 + k) * a.Mtot + m0 + wcol) : OOB;
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_S2_LDS(buf + idx * 256), 16, vo, 0u, 0, 0);
                 }
             }
-            float* xs = buf + WF;
 #pragma unroll
-            for (int u = 0; u < 3; ++u) {
-                if (lane + 64 * u < kS2Pos) {
+            for (int w = 0; w < 4; ++w) {
+                float* xs = buf + WF + w * XB;
 #pragma unroll
-                    for (int k = 0; k < kS2CK; ++k) {
-                        const bool chok = c0 + k < a.C;                                   // (uniform)
-                        const unsigned so = (unsigned)ES * (unsigned)((c0 + k) * (int)a.din.cs);
-                        if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_S2_LDS(xs + k * kS2XCS + 64 * u), 4, chok ? xvo[u] : OOB, chok ? so : 0u, 0, 0);
-                        else                          __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_S2_LDS(xs + k * kS2XCS + 64 * u), 2, chok ? xvo[u] : OOB, chok ? so : 0u, 0, 0);
+                for (int u = 0; u < XPASS; ++u) {
+                    if (lane + 64 * u < NPOS) {
+#pragma unroll
+                        for (int k = 0; k < kS2CK; ++k) {
+                            const bool chok = c0 + k < a.C;                               // (uniform)
+                            const unsigned so = (unsigned)ES * (unsigned)((c0 + k) * (int)a.din.cs);
+                            if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_S2_LDS(xs + k * kS2XCS + 64 * u), 4, chok ? xvo[w][u] : OOB, chok ? so : 0u, 0, 0);
+                            else                          __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, FTP_S2_LDS(xs + k * kS2XCS + 64 * u), 2, chok ? xvo[w][u] : OOB, chok ? so : 0u, 0, 0);
+                        }
                     }
                 }
             }
@@ -105,7 +132,7 @@ k_delta_s2_mfma(DeltaS2Args a)
         return;
     }
 
-    // ---- the four multiplying wavefronts: cell rows 2 * wave and 2 * wave + 1 of the tile ----------------------------------
+    // ---- the four multiplying wavefronts, one block of 32 cells each ----------------------------------------------------------
     v16f_s2 acc[4][MT];
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -113,8 +140,8 @@ k_delta_s2_mfma(DeltaS2Args a)
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[c][mt][i] = 0.0f;
-    const int cr = 2 * wave + (l32 >> 4), cc = l32 & 15;      // this lane's cell inside the tile
-    const int pb = cr * kS2PW + cc + hi * kS2XCS;
+    const int cr = l32 / NC, cc = l32 - cr * NC;       // this lane's cell inside the block
+    const int pb = wave * XB + cr * PW + cc + hi * kS2XCS;
     auto widen = [](float v) -> float { return ES == 4 ? v : __uint_as_float(__float_as_uint(v) << 16); };
 
     for (int sg = 0; sg < nst; ++sg) {
@@ -130,7 +157,7 @@ k_delta_s2_mfma(DeltaS2Args a)
                 const int cls = 2 * pa + pbx, tap = ky * 3 + kx;
 #pragma unroll
                 for (int i = 0; i < kS2CK / 2; ++i) {
-                    const float bv = widen(Xl[2 * i * kS2XCS + pb + dj * kS2PW + di]);
+                    const float bv = widen(Xl[2 * i * kS2XCS + pb + dj * PW + di]);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
                         const float av = Wl[(tap * kS2CK + 2 * i + hi) * BM + 32 * mt + l32];
@@ -142,6 +169,10 @@ k_delta_s2_mfma(DeltaS2Args a)
 
     // ---- store: accumulator row 8 * (i / 4) + 4 * hi + i % 4 = channel, column l32 = cell ----------------------------------
     // (the 32 channels of a block share one word of the sign map; their addresses differ by multiples of the channel stride)
+    const int q = 4 * blockIdx.x + wave;
+    if (q >= sb.total) return;
+    int n, J0, I0;
+    block_at(q, n, J0, I0);
     const int j = J0 + cr, ic = I0 + cc;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -174,29 +205,39 @@ int delta_s2_mfma(const ConvArgs& c, const RectTab& inrect, const float* wt, hip
 {
     if (c.K != 3 || c.S != 2 || c.pooled || c.Cin % 4 != 0 || c.Cin < 16) return 1;
     const double es = c.bf16 ? 2.0 : 4.0;
-    if (es * ((double)c.Cout * (double)c.din.cs + (double)c.din.ns) >= 2.0e9) return 1;       // 32-bit byte offsets inside one image
+    if (es * ((double)c.Cout * (double)c.din.cs + (double)c.batch * (double)c.din.ns) >= 2.0e9) return 1;   // 32-bit byte offsets inside one stack's maps
     if (4.0 * 9.0 * (double)c.Cout * (double)c.Cin >= 2.0e9) return 1;
     DeltaS2Args a;
     a.din = c.din; a.dout = c.dout; a.isign = c.isign; a.rect = c.rect;
     for (int t = 0; t < kTabGrid; ++t) { a.ix0[t] = inrect.x0[t]; a.ix1[t] = inrect.x1[t]; a.iy0[t] = inrect.y0[t]; a.iy1[t] = inrect.y1[t]; }
     a.wt = wt; a.C = c.Cout; a.Mtot = c.Cin; a.Hd = c.Hc; a.Wd = c.Wc;
     a.scale_out = c.scale_out; a.in_slope = c.in_slope; a.M = c.M; a.batch = c.batch;
-    int mw = 0, mh = 0;                                // cells per dimension of the largest rectangle
-    for (int t = 0; t < c.M; ++t) mw = std::max(mw, (c.rect.x1[t] >> 1) - (c.rect.x0[t] >> 1) + 1);
-    for (int t = 0; t < c.N; ++t) mh = std::max(mh, (c.rect.y1[t] >> 1) - (c.rect.y0[t] >> 1) + 1);
-    a.tiles_x = (mw + kS2Cols - 1) / kS2Cols;
-    const int tiles_y = (mh + kS2Rows - 1) / kS2Rows;
-    const long long images = (long long)c.N * c.M * c.batch;
-    if (images > 65535) return 1;
-    if (c.Cin > 32) {
-        dim3 grid(a.tiles_x * tiles_y, (c.Cin + 63) / 64, (unsigned)images);
-        if (c.bf16) { g_kernel_label = "k_delta_s2_mfma<unsigned short, 2>"; hipLaunchKernelGGL((k_delta_s2_mfma<bf16_t, 2>), grid, dim3(320), 0, s, a); }
-        else        { g_kernel_label = "k_delta_s2_mfma<float, 2>";          hipLaunchKernelGGL((k_delta_s2_mfma<float, 2>), grid, dim3(320), 0, s, a); }
-    } else {
-        dim3 grid(a.tiles_x * tiles_y, 1, (unsigned)images);
-        if (c.bf16) { g_kernel_label = "k_delta_s2_mfma<unsigned short, 1>"; hipLaunchKernelGGL((k_delta_s2_mfma<bf16_t, 1>), grid, dim3(320), 0, s, a); }
-        else        { g_kernel_label = "k_delta_s2_mfma<float, 1>";          hipLaunchKernelGGL((k_delta_s2_mfma<float, 1>), grid, dim3(320), 0, s, a); }
+    // block shape: the one that cuts the stacks' cell rectangles into the cheapest set of blocks of 32 cells
+    int best_nc = 16; long long best_blocks = -1; int max_total = 1;
+    for (int nc = 8; nc <= 32; nc *= 2) {
+        long long blocks = 0; int mx = 1;
+        for (int i = 0; i < c.N; ++i)
+            for (int j = 0; j < c.M; ++j) {
+                const S2Blocks b = s2_blocks(c.rect.x0[j], c.rect.x1[j], c.rect.y0[i], c.rect.y1[i], c.batch, nc);
+                blocks += b.total; mx = std::max(mx, b.total);
+            }
+        blocks *= 160 + (32 / nc + 1) * (nc + 1);      // (a block costs its matrix work plus the loads of its patch: flat blocks have the larger halo)
+        if (best_blocks < 0 || blocks < best_blocks) { best_blocks = blocks; best_nc = nc; max_total = mx; }
     }
+    const int mt = c.Cin > 32 ? 2 : 1;
+    dim3 grid((max_total + 3) / 4, (c.Cin + 32 * mt - 1) / (32 * mt), c.N * c.M);
+    static const char* const labels[2][2][3] = {
+        {{"k_delta_s2_mfma<float, 1, 8>", "k_delta_s2_mfma<float, 1, 16>", "k_delta_s2_mfma<float, 1, 32>"},
+         {"k_delta_s2_mfma<float, 2, 8>", "k_delta_s2_mfma<float, 2, 16>", "k_delta_s2_mfma<float, 2, 32>"}},
+        {{"k_delta_s2_mfma<unsigned short, 1, 8>", "k_delta_s2_mfma<unsigned short, 1, 16>", "k_delta_s2_mfma<unsigned short, 1, 32>"},
+         {"k_delta_s2_mfma<unsigned short, 2, 8>", "k_delta_s2_mfma<unsigned short, 2, 16>", "k_delta_s2_mfma<unsigned short, 2, 32>"}}};
+    g_kernel_label = labels[c.bf16 ? 1 : 0][mt - 1][best_nc == 8 ? 0 : best_nc == 16 ? 1 : 2];
+#define FTP_S2L(T, MTv, NCv) hipLaunchKernelGGL((k_delta_s2_mfma<T, MTv, NCv>), grid, dim3(320), 0, s, a)
+#define FTP_S2N(T, MTv) do { if (best_nc == 8) FTP_S2L(T, MTv, 8); else if (best_nc == 16) FTP_S2L(T, MTv, 16); else FTP_S2L(T, MTv, 32); } while (0)
+    if (c.bf16) { if (mt == 2) FTP_S2N(bf16_t, 2); else FTP_S2N(bf16_t, 1); }
+    else        { if (mt == 2) FTP_S2N(float, 2); else FTP_S2N(float, 1); }
+#undef FTP_S2N
+#undef FTP_S2L
     return 0;
 }
 
