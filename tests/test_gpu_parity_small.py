@@ -298,3 +298,13 @@ def test_thin_first_layer_shapes(oracle, name):
     layers, batch, cin, h, w, grid, dtype = _THIN[name]
     L = len(layers)
     P.check_case(oracle, Config("thin_%s" % name, batch, cin, h, w, layers, grid, (L,), dtype), partial_check=False)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("grid,grouping", [((1, 1), (4,)), ((4, 3), (4,)), ((2, 5), (1, 2, 3, 4))])
+def test_strided_delta_parity_classes(oracle, dtype, grid, grouping):
+    """3x3 stride-2 layers whose delta pass splits the input pixels into their four parity classes: odd maps (rectangles
+    that start at odd pixels), 20 and 48 produced channels (partial blocks of 32), rectangles of a few cells (a workgroup's
+    blocks then span several images), both storage types."""
+    layers = (conv(16, 20), conv(20, 48, 3, stride=2), conv(48, 40, 3, stride=2), conv(40, 8, 3, stride=2))
+    P.check_case(oracle, Config("s2_classes_%s" % dtype, 3, 16, 61, 75, layers, grid, grouping, dtype), partial_check=False)
