@@ -224,7 +224,9 @@ int delta_s2_mfma(const ConvArgs& c, const RectTab& inrect, const float* wt, hip
         blocks *= 160 + (32 / nc + 1) * (nc + 1);      // (a block costs its matrix work plus the loads of its patch: flat blocks have the larger halo)
         if (best_blocks < 0 || blocks < best_blocks) { best_blocks = blocks; best_nc = nc; max_total = mx; }
     }
-    const int mt = c.Cin > 32 ? 2 : 1;
+    // 32 produced channels per workgroup: 64 (two accumulator tiles per class) need 151 registers and leave room for two
+    // workgroups a CU instead of four - measured slower (gen_stem: 0.46 / 0.21 ms against 0.44 / 0.14 ms)
+    const int mt = 1;
     dim3 grid((max_total + 3) / 4, (c.Cin + 32 * mt - 1) / (32 * mt), c.N * c.M);
     static const char* const labels[2][2][3] = {
         {{"k_delta_s2_mfma<float, 1, 8>", "k_delta_s2_mfma<float, 1, 16>", "k_delta_s2_mfma<float, 1, 32>"},
@@ -234,8 +236,7 @@ int delta_s2_mfma(const ConvArgs& c, const RectTab& inrect, const float* wt, hip
     g_kernel_label = labels[c.bf16 ? 1 : 0][mt - 1][best_nc == 8 ? 0 : best_nc == 16 ? 1 : 2];
 #define FTP_S2L(T, MTv, NCv) hipLaunchKernelGGL((k_delta_s2_mfma<T, MTv, NCv>), grid, dim3(320), 0, s, a)
 #define FTP_S2N(T, MTv) do { if (best_nc == 8) FTP_S2L(T, MTv, 8); else if (best_nc == 16) FTP_S2L(T, MTv, 16); else FTP_S2L(T, MTv, 32); } while (0)
-    if (c.bf16) { if (mt == 2) FTP_S2N(bf16_t, 2); else FTP_S2N(bf16_t, 1); }
-    else        { if (mt == 2) FTP_S2N(float, 2); else FTP_S2N(float, 1); }
+    if (c.bf16) FTP_S2N(bf16_t, 1); else FTP_S2N(float, 1);
 #undef FTP_S2N
 #undef FTP_S2L
     return 0;
