@@ -1,4 +1,4 @@
-// Delta back-propagation through a 3x3 stride-2 convolution on the matrix cores without multiplying zeros, gfx950.
+// Delta back-propagation through a 3x3 (or 1x1) stride-2 convolution on the matrix cores without multiplying zeros, gfx950.
 // Eq. (2) with S_l = 2: input pixel (2j + a, 2i + b) receives W[ky][kx]^T dZ[qy][qx] only from the taps with
 // ky = a + 1 (mod 2), kx = b + 1 (mod 2), at qy = j + (a + 1 - ky) / 2, qx likewise.  The four pixels of a cell (j, i)
 // form four parity classes with 1, 2, 2 and 4 taps: together they use each of the 9 taps once, on the 2 x 2
@@ -22,7 +22,7 @@ struct DeltaS2Args {
     View din, dout, isign;
     RectTab rect;                                   // pixels of the delta each stack has to produce (input side)
     int ix0[kTabGrid], ix1[kTabGrid], iy0[kTabGrid], iy1[kTabGrid];   // extent of the delta view at the output side
-    const float* wt;                                // [8 - tap][C][Mtot]: the relaid filter of the backward pass
+    const float* wt;                                // [K * K - 1 - tap][C][Mtot]: the relaid filter of the backward pass
     int C, Mtot;                                    // reduction (output) channels, produced (input) channels
     int Hd, Wd;                                     // extent of the delta map at the output side
     int scale_out; float in_slope;
@@ -44,13 +44,14 @@ __host__ __device__ inline S2Blocks s2_blocks(int x0, int x1, int y0, int y1, in
     return b;
 }
 
-template <typename T, int MT, int NC>
+template <typename T, int K, int MT, int NC>
 __global__ void __launch_bounds__(320)
 k_delta_s2_mfma(DeltaS2Args a)
 {
-    constexpr int BM = 32 * MT, ES = sizeof(T), NR = 32 / NC;
-    constexpr int PW = NC + 1, NPOS = (NR + 1) * PW, XPASS = (NPOS + 63) / 64;
-    constexpr int WF = 9 * kS2CK * BM;                 // dwords of a filter slice
+    static_assert(K == 1 || K == 3, "1x1 and 3x3 filters");
+    constexpr int BM = 32 * MT, ES = sizeof(T), NR = 32 / NC, KK = K * K, P = K / 2;
+    constexpr int PW = NC + P, NPOS = (NR + P) * PW, XPASS = (NPOS + 63) / 64;     // (a 1x1 filter reads no neighbour: only the pixels (2j, 2i) receive a delta)
+    constexpr int WF = KK * kS2CK * BM;                // dwords of a filter slice
     constexpr int XB = kS2CK * kS2XCS;                 // dwords of one block's patch
     constexpr int STAGE = WF + 4 * XB;
     constexpr unsigned OOB = 0x80000000u;
@@ -100,9 +101,9 @@ k_delta_s2_mfma(DeltaS2Args a)
 #pragma unroll
             for (int idx = 0; idx < WINSTR; ++idx) {
                 const int row = idx * RPP + wrow, tap = row / kS2CK, k = row - tap * kS2CK;
-                if (row < 9 * kS2CK) {                                               // (the last instruction of a slice may be half empty)
+                if (row < KK * kS2CK) {                                              // (the last instruction of a slice may be half empty)
                     const bool ok = c0 + k < a.C && m0 + wcol < a.Mtot;
-                    const unsigned vo = ok ? 4u * (unsigned)(((8 - tap) * a.C + c0 + k) * a.Mtot + m0 + wcol) : OOB;
+                    const unsigned vo = ok ? 4u * (unsigned)(((KK - 1 - tap) * a.C + c0 + k) * a.Mtot + m0 + wcol) : OOB;
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, FTP_S2_LDS(buf + idx * 256), 16, vo, 0u, 0, 0);
                 }
             }
@@ -149,12 +150,12 @@ k_delta_s2_mfma(DeltaS2Args a)
         const float* Wl = lds + (sg & 1) * STAGE;
         const float* Xl = Wl + WF;
 #pragma unroll
-        for (int ky = 0; ky < 3; ++ky)
+        for (int ky = 0; ky < K; ++ky)
 #pragma unroll
-            for (int kx = 0; kx < 3; ++kx) {
-                const int pa = (ky + 1) & 1, pbx = (kx + 1) & 1;                 // parity class of the pixels this tap reaches
-                const int dj = (pa + 1 - ky) / 2, di = (pbx + 1 - kx) / 2;       // ... and where in the 2 x 2 neighbourhood
-                const int cls = 2 * pa + pbx, tap = ky * 3 + kx;
+            for (int kx = 0; kx < K; ++kx) {
+                const int pa = (ky + P) & 1, pbx = (kx + P) & 1;                 // parity class of the pixels this tap reaches
+                const int dj = (pa + P - ky) / 2, di = (pbx + P - kx) / 2;       // ... and where in the 2 x 2 neighbourhood
+                const int cls = 2 * pa + pbx, tap = ky * K + kx;
 #pragma unroll
                 for (int i = 0; i < kS2CK / 2; ++i) {
                     const float bv = widen(Xl[2 * i * kS2XCS + pb + dj * PW + di]);
@@ -203,7 +204,7 @@ k_delta_s2_mfma(DeltaS2Args a)
 // pass's relaid filter.  Returns non-zero where the layer does not fit (the caller then takes the general kernel).
 int delta_s2_mfma(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
 {
-    if (c.K != 3 || c.S != 2 || c.pooled || c.Cin % 4 != 0 || c.Cin < 16) return 1;
+    if ((c.K != 3 && c.K != 1) || c.S != 2 || c.pooled || c.Cin % 4 != 0 || c.Cin < 16) return 1;
     const double es = c.bf16 ? 2.0 : 4.0;
     if (es * ((double)c.Cout * (double)c.din.cs + (double)c.batch * (double)c.din.ns) >= 2.0e9) return 1;   // 32-bit byte offsets inside one stack's maps
     if (4.0 * 9.0 * (double)c.Cout * (double)c.Cin >= 2.0e9) return 1;
@@ -221,7 +222,7 @@ int delta_s2_mfma(const ConvArgs& c, const RectTab& inrect, const float* wt, hip
                 const S2Blocks b = s2_blocks(c.rect.x0[j], c.rect.x1[j], c.rect.y0[i], c.rect.y1[i], c.batch, nc);
                 blocks += b.total; mx = std::max(mx, b.total);
             }
-        blocks *= 160 + (32 / nc + 1) * (nc + 1);      // (a block costs its matrix work plus the loads of its patch: flat blocks have the larger halo)
+        blocks *= 160 + (32 / nc + c.K / 2) * (nc + c.K / 2);      // (a block costs its matrix work plus the loads of its patch: flat blocks have the larger halo)
         if (best_blocks < 0 || blocks < best_blocks) { best_blocks = blocks; best_nc = nc; max_total = mx; }
     }
     // 32 produced channels per workgroup: 64 (two accumulator tiles per class) need 151 registers and leave room for two
@@ -229,12 +230,13 @@ int delta_s2_mfma(const ConvArgs& c, const RectTab& inrect, const float* wt, hip
     const int mt = 1;
     dim3 grid((max_total + 3) / 4, (c.Cin + 32 * mt - 1) / (32 * mt), c.N * c.M);
     static const char* const labels[2][2][3] = {
-        {{"k_delta_s2_mfma<float, 1, 8>", "k_delta_s2_mfma<float, 1, 16>", "k_delta_s2_mfma<float, 1, 32>"},
-         {"k_delta_s2_mfma<float, 2, 8>", "k_delta_s2_mfma<float, 2, 16>", "k_delta_s2_mfma<float, 2, 32>"}},
-        {{"k_delta_s2_mfma<unsigned short, 1, 8>", "k_delta_s2_mfma<unsigned short, 1, 16>", "k_delta_s2_mfma<unsigned short, 1, 32>"},
-         {"k_delta_s2_mfma<unsigned short, 2, 8>", "k_delta_s2_mfma<unsigned short, 2, 16>", "k_delta_s2_mfma<unsigned short, 2, 32>"}}};
-    g_kernel_label = labels[c.bf16 ? 1 : 0][mt - 1][best_nc == 8 ? 0 : best_nc == 16 ? 1 : 2];
-#define FTP_S2L(T, MTv, NCv) hipLaunchKernelGGL((k_delta_s2_mfma<T, MTv, NCv>), grid, dim3(320), 0, s, a)
+        {{"k_delta_s2_mfma<float, 1, 1, 8>", "k_delta_s2_mfma<float, 1, 1, 16>", "k_delta_s2_mfma<float, 1, 1, 32>"},
+         {"k_delta_s2_mfma<float, 3, 1, 8>", "k_delta_s2_mfma<float, 3, 1, 16>", "k_delta_s2_mfma<float, 3, 1, 32>"}},
+        {{"k_delta_s2_mfma<unsigned short, 1, 1, 8>", "k_delta_s2_mfma<unsigned short, 1, 1, 16>", "k_delta_s2_mfma<unsigned short, 1, 1, 32>"},
+         {"k_delta_s2_mfma<unsigned short, 3, 1, 8>", "k_delta_s2_mfma<unsigned short, 3, 1, 16>", "k_delta_s2_mfma<unsigned short, 3, 1, 32>"}}};
+    g_kernel_label = labels[c.bf16 ? 1 : 0][c.K == 3 ? 1 : 0][best_nc == 8 ? 0 : best_nc == 16 ? 1 : 2];
+#define FTP_S2L(T, MTv, NCv) do { if (c.K == 3) hipLaunchKernelGGL((k_delta_s2_mfma<T, 3, MTv, NCv>), grid, dim3(320), 0, s, a); \
+                                   else          hipLaunchKernelGGL((k_delta_s2_mfma<T, 1, MTv, NCv>), grid, dim3(320), 0, s, a); } while (0)
 #define FTP_S2N(T, MTv) do { if (best_nc == 8) FTP_S2L(T, MTv, 8); else if (best_nc == 16) FTP_S2L(T, MTv, 16); else FTP_S2L(T, MTv, 32); } while (0)
     if (c.bf16) FTP_S2N(bf16_t, 1); else FTP_S2N(float, 1);
 #undef FTP_S2N

@@ -892,8 +892,8 @@ int mfma_conv_fwd(const ConvArgs& c, const RectTab& inrect, const float* wt, hip
 // (at the unit's output boundary, pooled coordinates if the unit has a pool).
 int mfma_conv_bwd_data(const ConvArgs& c, const RectTab& inrect, const float* wt, hipStream_t s)
 {
-    // (3x3 stride 2: the kernel that splits the pixels into their four parity classes multiplies no inserted zeros)
-    if (c.S == 2 && c.K == 3 && delta_s2_mfma(c, inrect, wt, s) == 0) return 0;
+    // (stride 2: the kernel that splits the pixels into their four parity classes multiplies no inserted zeros)
+    if (c.S == 2 && (c.K == 3 || c.K == 1) && delta_s2_mfma(c, inrect, wt, s) == 0) return 0;
     MfmaConvArgs a;
     fill_common(a, c, inrect);
     a.wt = wt; a.bias = nullptr;
