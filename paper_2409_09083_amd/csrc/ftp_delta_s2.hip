@@ -29,20 +29,8 @@ struct DeltaS2Args {
     int M, batch;
 };
 
-constexpr int kS2XCS = 67;                          // dwords between two channels of a block's patch (at most 2 x 33 positions)
 constexpr int kS2CK = 8;                            // reduction channels per stage
 #define FTP_S2_LDS(p) ((__attribute__((address_space(3))) void*)(p))
-
-// Blocks of 32 cells (32 / NC rows x NC columns) of one stack: image, row group, column group (fastest).
-struct S2Blocks { int gc, gr, total; };
-__host__ __device__ inline S2Blocks s2_blocks(int x0, int x1, int y0, int y1, int batch, int NC)
-{
-    S2Blocks b;
-    const int cw = (x1 >> 1) - (x0 >> 1) + 1, ch = (y1 >> 1) - (y0 >> 1) + 1, NR = 32 / NC;
-    b.gc = (cw + NC - 1) / NC; b.gr = (ch + NR - 1) / NR;
-    b.total = batch * b.gr * b.gc;
-    return b;
-}
 
 template <typename T, int K, int MT, int NC>
 __global__ void __launch_bounds__(320)

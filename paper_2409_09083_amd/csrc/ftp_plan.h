@@ -286,6 +286,19 @@ inline int wgrad_shares_thin(int cout, int stacks, int chunks, int slots = 1024)
     return shares < 1 ? 1 : shares;
 }
 
+// The parity-class delta kernel of stride-2 layers (ftp_delta_s2.hip) cuts the cells (2 x 2 input pixels) that cover a
+// stack's rectangle into blocks of 32: 32 / NC rows x NC columns, listed over image, row group, column group (fastest).
+constexpr int kS2XCS = 67;                          // dwords between two channels of a block's patch (at most 2 x 33 positions)
+struct S2Blocks { int gc, gr, total; };
+FTP_HD inline S2Blocks s2_blocks(int x0, int x1, int y0, int y1, int batch, int NC)
+{
+    S2Blocks b;
+    const int cw = (x1 >> 1) - (x0 >> 1) + 1, ch = (y1 >> 1) - (y0 >> 1) + 1, NR = 32 / NC;
+    b.gc = (cw + NC - 1) / NC; b.gr = (ch + NR - 1) / NR;
+    b.total = batch * b.gr * b.gc;
+    return b;
+}
+
 int build_plan(const ftp_layer* layers, int n_layers, int batch, int in_c, int in_h, int in_w,
                int N, int M, const int32_t* group_ends, int n_groups, ftp_dtype dtype, ftp_plan_s** out);
 

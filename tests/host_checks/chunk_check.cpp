@@ -116,6 +116,36 @@ int main()
                                     }
                                 }
             }
+    // parity-class delta kernel: the blocks of 32 cells cover every pixel of the rectangle exactly once (pixel = cell +
+    // class), a block's patch fits its LDS stride, the last operand read lies inside the patch
+    for (int nc = 8; nc <= 32; nc *= 2)
+        for (int K = 1; K <= 3; K += 2)
+            for (int x0 = 0; x0 <= 3; ++x0)
+                for (int w = 1; w <= 70; w += (w < 12 ? 1 : 7))
+                    for (int y0 = 0; y0 <= 3; ++y0)
+                        for (int h = 1; h <= 23; h += (h < 8 ? 1 : 5)) {
+                            const int x1 = x0 + w - 1, y1 = y0 + h - 1, batch = 3, NR = 32 / nc, P = K / 2;
+                            const ftp::S2Blocks b = ftp::s2_blocks(x0, x1, y0, y1, batch, nc);
+                            ++checked;
+                            long long covered = 0;
+                            bool ok = (NR + P) * (nc + P) <= ftp::kS2XCS;
+                            for (int q = 0; q < b.total && ok; ++q) {
+                                const int img = q / (b.gr * b.gc), rem = q - img * (b.gr * b.gc), rg = rem / b.gc;
+                                const int J0 = (y0 >> 1) + NR * rg, I0 = (x0 >> 1) + nc * (rem - rg * b.gc);
+                                ok = ok && img < batch;
+                                for (int l = 0; l < 32; ++l) {
+                                    const int cr = l / nc, cc = l - cr * nc;
+                                    // last operand read of the lane: second channel of a pair, neighbour (P, P)
+                                    ok = ok && (cr + P) * (nc + P) + cc + P < (NR + P) * (nc + P);
+                                    for (int c = 0; c < 4; ++c) {
+                                        const int y = 2 * (J0 + cr) + (c >> 1), x = 2 * (I0 + cc) + (c & 1);
+                                        if (y >= y0 && y <= y1 && x >= x0 && x <= x1) ++covered;
+                                    }
+                                }
+                            }
+                            ok = ok && covered == (long long)batch * w * h;
+                            if (!ok) { std::printf("s2_blocks(x0=%d, w=%d, y0=%d, h=%d, NC=%d, K=%d): gc=%d gr=%d total=%d covered=%lld\n", x0, w, y0, h, nc, K, b.gc, b.gr, b.total, covered); return 1; }
+                        }
     std::printf("ok %ld\n", checked);
     return 0;
 }
