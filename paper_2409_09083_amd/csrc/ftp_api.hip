@@ -308,6 +308,8 @@ int ftp_forward(const ftp_plan_t* plan, const void* x, const void* const* weight
                 });
             } else if (fast && thin_conv_fwd_eligible(a)) {
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { thin_conv_fwd(a, s); });
+            } else if (use_mfma() && thin_conv_fwd_gen_eligible(a)) {
+                rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { thin_conv_fwd_gen(a, s); });
             } else {
                 rc = timed(plan, FTP_PASS_CONV_FWD, u.layer, s, [&] { direct_conv_fwd(a, s); });
             }

@@ -124,6 +124,9 @@ void wgrad_share_sum(const ConvArgs& c, const float* scratch, int shares, hipStr
 
 bool thin_conv_fwd_eligible(const ConvArgs& a);
 void thin_conv_fwd(const ConvArgs& a, hipStream_t s);
+// ... with a 5x5 / 7x7 filter or stride 2 (no fused pool)
+bool thin_conv_fwd_gen_eligible(const ConvArgs& a);
+void thin_conv_fwd_gen(const ConvArgs& a, hipStream_t s);
 bool thin_bwd_data_strided_eligible(const ConvArgs& a);
 void thin_conv_bwd_data_strided(const ConvArgs& a, const RectTab& ext, hipStream_t s);   // ext: extent of the delta view per stack
 bool thin_bwd_data_eligible(const ConvArgs& a);

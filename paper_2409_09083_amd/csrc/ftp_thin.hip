@@ -158,6 +158,115 @@ void thin_conv_fwd(const ConvArgs& a, hipStream_t s)
 #undef FTP_TF
 }
 
+// ---- forward of the other thin first layers: 5x5 / 7x7 filters, stride 2 (no fused pool) ------------------------------
+// Workgroup = 16 x 16 output pixels of one (stack, image), one pixel per thread.  The input patch of the tile (all
+// input channels, zero outside the map) is staged in LDS once; a thread copies its own K x K x CI patch into registers
+// and then walks the output channels, 16 at a time: their filters (+ bias) are staged in LDS as rows of whole float4s
+// and read as broadcast vectors, K * K * CI multiply-adds per channel.  A thread sees all channels of its pixel, so
+// it writes the sign words itself.
+constexpr int kThinGenTile = 16, kThinGenCoc = 16;
+
+template <typename T, int K, int S, int CI>
+__global__ void __launch_bounds__(256)
+k_conv_fwd_thin_gen(View in, View out, View osign, RectTab rt, RectTab own, const T* __restrict__ w,
+                    const T* __restrict__ bias, int Cin, int Cout, int Hi, int Wi, float slope, int M, int batch, int tiles_x)
+{
+    constexpr int P = K / 2, KK = K * K, TS = kThinGenTile, COC = kThinGenCoc;
+    constexpr int PD = S * (TS - 1) + K, PP = PD | 1;               // patch extent, odd pitch
+    constexpr int WR = CI * KK, WRP = (WR + 1 + 3) & ~3;            // weights of a channel (+ bias), padded to float4s
+    __shared__ __attribute__((aligned(16))) float xp[CI * PD * PP];
+    __shared__ __attribute__((aligned(16))) float wl[COC * WRP];
+    const int tid = threadIdx.x;
+    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    const int ti = stack / M, tj = stack % M;
+    const int bx = blockIdx.x % tiles_x, by = blockIdx.x / tiles_x;
+    const int ox0 = rt.x0[tj] + bx * TS, oy0 = rt.y0[ti] + by * TS;
+    if (ox0 > rt.x1[tj] || oy0 > rt.y1[ti]) return;
+    const int ix0 = S * ox0 - P, iy0 = S * oy0 - P;
+    // positions only pixels beyond the rectangle would read may lie outside the input view
+    const int ylim = S * rt.y1[ti] + P, xlim = S * rt.x1[tj] + P;
+    for (int i = tid; i < CI * PD * PD; i += 256) {
+        const int ci = i / (PD * PD), rem = i - ci * (PD * PD), r = rem / PD, q = rem - r * PD;
+        const int y = iy0 + r, x = ix0 + q;
+        const bool okp = ci < Cin && y >= 0 && y < Hi && x >= 0 && x < Wi && y <= ylim && x <= xlim;
+        xp[(ci * PD + r) * PP + q] = okp ? ld(at<T>(in, stack, ti, tj, n, ci, y, x)) : 0.0f;
+    }
+    __syncthreads();
+    const int tx = tid % TS, ty = tid / TS;
+    const int oy = oy0 + ty, ox = ox0 + tx;
+    float p[WR];
+#pragma unroll
+    for (int ci = 0; ci < CI; ++ci)
+#pragma unroll
+        for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < K; ++kx) p[ci * KK + ky * K + kx] = xp[(ci * PD + S * ty + ky) * PP + S * tx + kx];
+    const bool v0 = oy <= rt.y1[ti] && ox <= rt.x1[tj];
+    const bool o0 = v0 && in_rect_thin(own, ti, tj, oy, ox);
+    uint32_t s0 = 0;
+    for (int c0 = 0; c0 < Cout; c0 += COC) {
+        __syncthreads();                               // the previous block's filters have been consumed
+        for (int i = tid; i < COC * WRP; i += 256) {
+            const int c = i / WRP, r = i - c * WRP;
+            float v = 0.0f;
+            if (c0 + c < Cout) {
+                if (r < WR) { const int ci = r / KK, t = r - ci * KK; if (ci < Cin) v = ld(w + ((size_t)(c0 + c) * Cin + ci) * KK + t); }
+                else if (r == WR && bias) v = ld(bias + c0 + c);
+            }
+            wl[i] = v;
+        }
+        __syncthreads();
+        for (int c = 0; c < COC; ++c) {
+            const int co = c0 + c;
+            if (co >= Cout) break;
+            const float4* w4 = (const float4*)(wl + c * WRP);
+            float acc = 0.0f;
+#pragma unroll
+            for (int q = 0; q < WRP / 4; ++q) {
+                const float4 wv = w4[q];
+                if (4 * q + 0 < WR) acc = fmaf(wv.x, p[4 * q + 0 < WR ? 4 * q + 0 : 0], acc);
+                if (4 * q + 1 < WR) acc = fmaf(wv.y, p[4 * q + 1 < WR ? 4 * q + 1 : 0], acc);
+                if (4 * q + 2 < WR) acc = fmaf(wv.z, p[4 * q + 2 < WR ? 4 * q + 2 : 0], acc);
+                if (4 * q + 3 < WR) acc = fmaf(wv.w, p[4 * q + 3 < WR ? 4 * q + 3 : 0], acc);
+            }
+            const float bv = wl[c * WRP + WR];
+            const float a0 = stored(leaky(acc + bv, slope), (const T*)nullptr);
+            if (v0) st(at<T>(out, stack, ti, tj, n, co, oy, ox), a0);
+            s0 |= (a0 > 0.0f ? 1u : 0u) << (co & 31);
+            if ((co & 31) == 31 || co == Cout - 1) {
+                if (o0) *at<uint32_t>(osign, stack, ti, tj, n, co >> 5, oy, ox) = s0;
+                s0 = 0;
+            }
+        }
+    }
+}
+
+bool thin_conv_fwd_gen_eligible(const ConvArgs& a)
+{
+    return a.Cin <= 4 && !a.pooled && (a.K == 5 || a.K == 7 || (a.S == 2 && (a.K == 1 || a.K == 3))) && (a.S == 1 || a.S == 2);
+}
+
+void thin_conv_fwd_gen(const ConvArgs& a, hipStream_t s)
+{
+    int mw = 0, mh = 0;
+    for (int t = 0; t < a.M; ++t) mw = std::max(mw, a.rect.x1[t] - a.rect.x0[t] + 1);
+    for (int t = 0; t < a.N; ++t) mh = std::max(mh, a.rect.y1[t] - a.rect.y0[t] + 1);
+    const int tiles_x = (mw + kThinGenTile - 1) / kThinGenTile, tiles_y = (mh + kThinGenTile - 1) / kThinGenTile;
+    dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
+    g_kernel_label = "k_conv_fwd_thin_gen";
+#define FTP_TG(T, KK, SS, CI) hipLaunchKernelGGL((k_conv_fwd_thin_gen<T, KK, SS, CI>), grid, block, 0, s, a.in, a.out, a.osign, a.rect, a.own, (const T*)a.w, (const T*)a.bias, a.Cin, a.Cout, a.Hi, a.Wi, a.slope, a.M, a.batch, tiles_x)
+#define FTP_TGC(T, KK, SS) do { if (a.Cin <= 3) FTP_TG(T, KK, SS, 3); else FTP_TG(T, KK, SS, 4); } while (0)
+#define FTP_TGK(T) do { \
+        if (a.K == 7)      { if (a.S == 2) FTP_TGC(T, 7, 2); else FTP_TGC(T, 7, 1); } \
+        else if (a.K == 5) { if (a.S == 2) FTP_TGC(T, 5, 2); else FTP_TGC(T, 5, 1); } \
+        else if (a.K == 3) FTP_TGC(T, 3, 2); \
+        else               FTP_TGC(T, 1, 2); } while (0)
+    if (a.bf16) FTP_TGK(bf16_t); else FTP_TGK(float);
+#undef FTP_TGK
+#undef FTP_TGC
+#undef FTP_TG
+}
+
 // ---- delta at the input of a convolution with at most CIT input channels ------------------------------------
 // Workgroup = 64 x 4 pixels of one (stack, image): wide tiles keep the reads of the (pooled) delta rows long.
 // LDS = dZ patch of COC channels with the filter halo.
