@@ -38,11 +38,12 @@ __global__ void __launch_bounds__(256, 2)
 k_wgrad_mfma(MfmaWgradArgs a)
 {
     constexpr bool POOL = HALF == 1;
-    constexpr bool BF = sizeof(T) == 2;
-    constexpr bool DL = !BF;                           // fp32: the patch is loaded straight into LDS
+    constexpr bool BF = sizeof(T) == 2 && HALF != 3;   // 16-bit maps on the bfloat matrix cores, staged through registers
+    constexpr bool DL = !BF;                           // fp32 arithmetic: the patch is loaded straight into LDS (16-bit maps: the
+                                                       // output-pixel form of stride 2 only, an element a dword, widened at the read)
+    constexpr unsigned ES = sizeof(T);
     constexpr int S = HALF == 3 ? 2 : 1;               // patch positions per chunk pixel and dimension
     constexpr bool HALF_RES = HALF == 1 || HALF == 2;  // the deltas sit at half the resolution of the rectangle
-    static_assert(HALF != 3 || DL, "the output-pixel form of stride 2 is written for the direct-load path");
     constexpr int WAVES_K = 4 / (WAVES_CO * WAVES_CI);
     constexpr int KK = K * K, P = K / 2, NTAP = TROWS * K;
     constexpr int BCO = 32 * WAVES_CO, BCI = 32 * WAVES_CI;
@@ -137,7 +138,7 @@ k_wgrad_mfma(MfmaWgradArgs a)
             zinfo = (((qy & 1) << 1) | (qx & 1)) << 2;
             const T* gbase = (const T*)a.din.p + (long long)stack * a.din.ss + (long long)c.n0 * a.din.ns;
             const __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc((void*)gbase, (short)0, 0x7FFFFFFF, 0x00020000);
-            const unsigned gvo = ok ? 4u * (unsigned)(z_il * (int)a.din.ns + (sy - a.din.y0[ti]) * a.din.pitch + (sx - a.din.x0[tj])) : 0x80000000u;
+            const unsigned gvo = ok ? ES * (unsigned)(z_il * (int)a.din.ns + (sy - a.din.y0[ti]) * a.din.pitch + (sx - a.din.x0[tj])) : 0x80000000u;
             const uint8_t* mbase = (const uint8_t*)a.mask.p + (long long)stack * a.mask.ss + (long long)c.n0 * a.mask.ns;
             const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)mbase, (short)0, 0x7FFFFFFF, 0x00020000);
             const unsigned mvo = (POOL && ok) ? (unsigned)(z_il * (int)a.mask.ns + (sy - a.mask.y0[ti]) * a.mask.pitch + (sx - a.mask.x0[tj])) : 0x80000000u;
@@ -148,7 +149,8 @@ k_wgrad_mfma(MfmaWgradArgs a)
                 if constexpr (!decltype(full)::value)
                     if (co0 + ch >= a.Cout) { gv = 0x80000000u; mv = 0x80000000u; }
                 zm[k] = POOL ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(mrsrc, mv, (unsigned)((co0 + ch) * (int)a.mask.cs), 0) : 0u;      // only the pool winner is needed
-                zg[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(grsrc, gv, 4u * (unsigned)((co0 + ch) * (int)a.din.cs), 0));
+                if constexpr (sizeof(T) == 4) zg[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(grsrc, gv, 4u * (unsigned)((co0 + ch) * (int)a.din.cs), 0));
+                else                          zg[k] = __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(grsrc, gv, 2u * (unsigned)((co0 + ch) * (int)a.din.cs), 0) << 16);
             }
         }
     };
@@ -261,15 +263,16 @@ k_wgrad_mfma(MfmaWgradArgs a)
                 if (pass * 64 < npos) {
                     const int gy = gy0 + x_r[pass], gx = gx0 + x_c[pass];
                     const bool inside = x_il[pass] < c.ni && x_r[pass] < nph && x_c[pass] < ncn && (unsigned)gy < (unsigned)a.Hc && (unsigned)gx < (unsigned)a.Wc;
-                    const unsigned vo = inside ? 4u * (unsigned)(x_il[pass] * (int)a.in.ns + (gy - a.in.y0[ti]) * a.in.pitch + (gx - a.in.x0[tj])) : 0x80000000u;
+                    const unsigned vo = inside ? ES * (unsigned)(x_il[pass] * (int)a.in.ns + (gy - a.in.y0[ti]) * a.in.pitch + (gx - a.in.x0[tj])) : 0x80000000u;
 #pragma unroll
                     for (int k = 0; k < NX; ++k) {
                         const int ch = wave + 4 * k;
                         unsigned v = vo;
                         if constexpr (!decltype(full)::value)
                             if (ci0 + ch >= a.Cin) v = 0x80000000u;
-                        const unsigned so = 4u * (unsigned)((ci0 + ch) * (int)a.in.cs);
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(Xl + ch * XS + pass * 64), 4, v, so, 0, 0);
+                        const unsigned so = ES * (unsigned)((ci0 + ch) * (int)a.in.cs);
+                        if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(Xl + ch * XS + pass * 64), 4, v, so, 0, 0);
+                        else                          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(Xl + ch * XS + pass * 64), 2, v, so, 0, 0);
                     }
                     issued += NX;
                 }
@@ -330,7 +333,8 @@ k_wgrad_mfma(MfmaWgradArgs a)
 #pragma unroll
                 for (int t = 0; t < NTAP; ++t) {
                     if (TROWS != K && trow0 + t / K >= K) break;           // (the last part of a split filter may be short)
-                    const float bv = xrow[((trow0 + t / K) * PW + S * xp + (t % K)) * (DL ? 1 : XP)];
+                    float bv = xrow[((trow0 + t / K) * PW + S * xp + (t % K)) * (DL ? 1 : XP)];
+                    if constexpr (DL && sizeof(T) == 2) bv = __uint_as_float(__float_as_uint(bv) << 16);      // (a 16-bit element in the lower half of its dword)
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t], 0, 0, 0);
                 }
             }
@@ -439,8 +443,9 @@ bool mfma_wgrad_eligible(const ConvArgs& c)
     if (c.pooled && (c.S != 1 || c.K > 3)) return false;
     if (c.S == 2 && c.K > 3) return false;
     // (the fp32 patch loads address one stack's images with 32-bit byte offsets; a chunk spans at most 64 images)
-    if (!c.bf16 && 4.0 * (64.0 * (double)c.in.ns + (double)c.Cin * (double)c.in.cs) >= 2.0e9) return false;
-    if (!c.bf16 && 4.0 * (64.0 * (double)c.din.ns + (double)c.Cout * (double)c.din.cs) >= 2.0e9) return false;
+    const bool direct = !c.bf16 || c.S == 2;           // (the patch goes straight into LDS)
+    if (direct && 4.0 * (64.0 * (double)c.in.ns + (double)c.Cin * (double)c.in.cs) >= 2.0e9) return false;
+    if (direct && 4.0 * (64.0 * (double)c.din.ns + (double)c.Cout * (double)c.din.cs) >= 2.0e9) return false;
     if (!c.bf16 && c.pooled && 64.0 * (double)c.mask.ns + (double)c.Cout * (double)c.mask.cs >= 2.0e9) return false;
     return !c.has_bias && c.Cout >= 32 && c.Cin >= 16;
 }
@@ -450,9 +455,9 @@ bool mfma_wgrad_eligible(const ConvArgs& c)
 void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
 {
     MfmaWgradArgs a;
-    // (stride 2: fp32 runs over the owned output pixels, 16-bit maps over the owned input pixels with zero-inserted deltas)
-    const int half = c.pooled ? 1 : c.S == 2 ? (c.bf16 ? 2 : 3) : 0;
-    a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = half == 2 ? c.own : c.rect;
+    // (stride 2: the gradient runs over the owned output pixels, pixel (y, x) reading the patch at (2y + ky, 2x + kx))
+    const int half = c.pooled ? 1 : c.S == 2 ? 3 : 0;
+    a.in = c.in; a.din = c.din; a.mask = c.mask; a.own = c.rect;
     a.partial = c.partial; a.scratch = scratch; a.n_params = c.n_params; a.w_off = c.w_off;
     a.Cin = c.Cin; a.Cout = c.Cout; a.Hc = c.Hi; a.Wc = c.Wi; a.slope = c.slope; a.M = c.M; a.batch = c.batch;
     a.splits = c.wgrad_shares;
@@ -465,7 +470,7 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     const int BCO = 32 * waves_co, BCI = 32 * waves_ci;
     // (+ the bfloat path's table of patch positions)
     // (the fp32 patch layout is [ci][positions + 1], the bfloat one [position][ci + 1] + the table of patch positions)
-    const size_t lds = c.bf16 ? ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1) + kWgradZPos) * sizeof(float)
+    const size_t lds = (c.bf16 && half != 3) ? ((size_t)kWgradZPos * (BCO + 1) + (size_t)wgrad_xpos(c.K / 2) * (BCI + 1) + kWgradZPos) * sizeof(float)
                               : ((size_t)kWgradZPos * (BCO + 1) + (size_t)BCI * (wgrad_xpos(c.K / 2, half == 3 ? 2 : 1) + 1)) * sizeof(float);
     const int tiles = ((c.Cout + BCO - 1) / BCO) * ((c.Cin + BCI - 1) / BCI);
     const int parts = c.K == 5 ? 3 : c.K == 7 ? 7 : 1;                 // filter rows 2 + 2 + 1, or one at a time
@@ -481,14 +486,14 @@ void mfma_wgrad(const ConvArgs& c, float* scratch, hipStream_t s)
     if (c.K == 7) FTP_WG(7, 2, 1, 0, 1);
     else if (c.K == 5) FTP_WG(5, 2, 1, 0, 2);
     else if (c.K == 3) {
-        if (half == 3)          { if (waves_co == 1) FTP_WG1(float, "float", 3, 1, 1, 3, 3); else FTP_WG1(float, "float", 3, 2, 1, 3, 3); }
-        else if (waves_co == 1) { if (half == 1) FTP_WG(3, 1, 1, 1, 3); else if (half == 2) FTP_WG(3, 1, 1, 2, 3); else FTP_WG(3, 1, 1, 0, 3); }
-        else if (waves_ci == 2) { if (half == 1) FTP_WG(3, 2, 2, 1, 3); else if (half == 2) FTP_WG(3, 2, 2, 2, 3); else FTP_WG(3, 2, 2, 0, 3); }
-        else                    { if (half == 1) FTP_WG(3, 2, 1, 1, 3); else if (half == 2) FTP_WG(3, 2, 1, 2, 3); else FTP_WG(3, 2, 1, 0, 3); }
+        if (half == 3)          { if (waves_co == 1) FTP_WG(3, 1, 1, 3, 3); else FTP_WG(3, 2, 1, 3, 3); }
+        else if (waves_co == 1) { if (half == 1) FTP_WG(3, 1, 1, 1, 3); else FTP_WG(3, 1, 1, 0, 3); }
+        else if (waves_ci == 2) { if (half == 1) FTP_WG(3, 2, 2, 1, 3); else FTP_WG(3, 2, 2, 0, 3); }
+        else                    { if (half == 1) FTP_WG(3, 2, 1, 1, 3); else FTP_WG(3, 2, 1, 0, 3); }
     } else {
-        if (half == 3)     FTP_WG1(float, "float", 1, 2, 1, 3, 1);
-        else if (waves_ci == 2) { if (half == 1) FTP_WG(1, 2, 2, 1, 1); else if (half == 2) FTP_WG(1, 2, 2, 2, 1); else FTP_WG(1, 2, 2, 0, 1); }
-        else               { if (half == 1) FTP_WG(1, 2, 1, 1, 1); else if (half == 2) FTP_WG(1, 2, 1, 2, 1); else FTP_WG(1, 2, 1, 0, 1); }
+        if (half == 3)     FTP_WG(1, 2, 1, 3, 1);
+        else if (waves_ci == 2) { if (half == 1) FTP_WG(1, 2, 2, 1, 1); else FTP_WG(1, 2, 2, 0, 1); }
+        else               { if (half == 1) FTP_WG(1, 2, 1, 1, 1); else FTP_WG(1, 2, 1, 0, 1); }
     }
 #undef FTP_WG
 #undef FTP_WG1
