@@ -10,9 +10,10 @@
 // rectangle is at the convolution output, the deltas at pooled resolution, and a pixel receives its window's delta
 // only if it is the window's winner; 2 = stride-2 convolution: the rectangle is the stack's owned part of the
 // *input* map and pixel (y, x) carries delta (y/2, x/2) if both are even, else zero (the filter gradient of a strided
-// convolution is the stride-1 one of the deltas with zeros in between; three quarters of the products are zero; kept for
-// 16-bit maps); 3 = stride-2 convolution run over the stack's owned *output* pixels (fp32): pixel (y, x) reads the
-// patch of the input map at (2y + ky, 2x + kx), no zeros are multiplied, the patch of a chunk is four times as large.
+// convolution is the stride-1 one of the deltas with zeros in between; three quarters of the products are zero; no
+// longer launched); 3 = stride-2 convolution run over the stack's owned *output* pixels: pixel (y, x) reads the
+// patch of the input map at (2y + ky, 2x + kx), no zeros are multiplied, the patch of a chunk is four times as large
+// (fp32 arithmetic for both storage types: 16-bit maps arrive one element per dword and are widened at the read).
 // fp32 maps: the patch of X does not pass through registers.  It goes HBM -> LDS with buffer_load_dword ... lds, one
 // element per lane, channel-major ([ci][patch position], odd channel stride), positions outside the map from
 // out-of-range offsets (= 0); the deltas still go through registers (masking, pool routing), loaded during the
