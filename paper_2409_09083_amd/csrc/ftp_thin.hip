@@ -478,7 +478,7 @@ k_conv_bwd_data_thin4(View din, View mask, View dout, View isign, int scale_out,
 // Input pixel (2j + a, 2i + b) receives W[ky][kx] dZ[qy][qx] from the taps with ky = a + P, kx = b + P (mod 2), at
 // qy = j + (a + P - ky) / 2, qx likewise: the four pixels of a cell (j, i) together use every tap exactly once and
 // read the deltas of the cells [j + QLO, j + QHI] x [i + QLO, i + QHI] (4 x 4 for a 7x7 filter).
-// Workgroup = 16 x 16 cells (32 x 32 pixels) of one (stack, image), one cell per thread.  Per 8 output channels the
+// Workgroup = 16 x 32 cells (32 x 64 pixels) of one (stack, image), two neighbouring cells per thread.  Per 8 output channels the
 // delta patch (tile + that halo; zero outside the stack's delta rectangle) and the filter slice [co][tap][ci padded
 // to 4] (fp32) are staged in LDS; a thread reads its NQ x NQ deltas and one 16-byte filter vector per tap for
 // K * K * CI multiply-adds per output channel.
@@ -486,6 +486,7 @@ template <int K> struct StridedTaps {
     static constexpr int P = K / 2;
     static constexpr int QLO = -((K - 1 - P) / 2), QHI = (1 + P) / 2, NQ = QHI - QLO + 1;
 };
+constexpr int kThinS2PerThread = 2;                   // cells per thread along a row: they share 3 of 4 delta columns and every weight read (1: 2.87 ms on the 7x7 stem, 2: 2.09, 4: 2.27)
 constexpr int kThinS2Coc = 8, kThinS2Cells = 16;      // (8 channels a stage, 18 KB of LDS: five workgroups a CU; 16 channels, four workgroups: 3.37 instead of 2.85 ms on the 7x7 stem)
 
 template <typename T, int K, int CI>
@@ -495,35 +496,38 @@ k_conv_bwd_data_thin_s2(View din, View dout, View isign, int scale_out, float in
 {
     typedef StridedTaps<K> G;
     constexpr int P = G::P, QLO = G::QLO, NQ = G::NQ, KK = K * K;
-    constexpr int COC = kThinS2Coc, TC = kThinS2Cells, PD = TC + NQ - 1, PDP = PD + 1;     // patch extent, padded pitch
-    __shared__ __attribute__((aligned(16))) float dzl[COC * PD * PDP];
+    constexpr int COC = kThinS2Coc, TC = kThinS2Cells, NCX = kThinS2PerThread;
+    constexpr int TCX = NCX * TC, PDY = TC + NQ - 1, PDX = TCX + NQ - 1, PDP = PDX + 1;     // tile, patch extent, padded pitch
+    __shared__ __attribute__((aligned(16))) float dzl[COC * PDY * PDP];
     __shared__ __attribute__((aligned(16))) float wl[COC * KK * 4];
     const int tid = threadIdx.x;
     const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
     const int ti = stack / M, tj = stack % M;
     const int bx = blockIdx.x % tiles_x, by = blockIdx.x / tiles_x;
-    const int J0 = (rt.y0[ti] >> 1) + by * TC, I0 = (rt.x0[tj] >> 1) + bx * TC;      // first cell of the tile
+    const int J0 = (rt.y0[ti] >> 1) + by * TC, I0 = (rt.x0[tj] >> 1) + bx * TCX;     // first cell of the tile
     if (2 * J0 > rt.y1[ti] || 2 * I0 > rt.x1[tj]) return;
-    const int cy = tid / TC, cx = tid % TC;
-    float acc[2][2][CI];
+    const int cy = tid / TC, cx = NCX * (tid % TC);     // this thread's cells: (cy, cx) .. (cy, cx + NCX - 1)
+    float acc[NCX][2][2][CI];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int u = 0; u < NCX; ++u)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int c = 0; c < CI; ++c) acc[a][b][c] = 0.0f;
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int c = 0; c < CI; ++c) acc[u][a][b][c] = 0.0f;
 
     for (int c0 = 0; c0 < Cout; c0 += COC) {
         __syncthreads();                               // the previous slice has been consumed
         // delta patch: rows QLO .. of the tile's cells, COC channels; lanes run along a patch row
-        for (int e = tid; e < COC * PD * PD; e += 256) {
-            const int c = e / (PD * PD), r = e - c * (PD * PD);
-            const int py = r / PD, px = r - py * PD;
+        for (int e = tid; e < COC * PDY * PDX; e += 256) {
+            const int c = e / (PDY * PDX), r = e - c * (PDY * PDX);
+            const int py = r / PDX, px = r - py * PDX;
             const int qy = J0 + QLO + py, qx = I0 + QLO + px;
             float v = 0.0f;
             if (c0 + c < Cout && qy >= ext.y0[ti] && qy <= ext.y1[ti] && qx >= ext.x0[tj] && qx <= ext.x1[tj])
                 v = ld(at<T>(din, stack, ti, tj, n, c0 + c, qy, qx));
-            dzl[(c * PD + py) * PDP + px] = v;
+            dzl[(c * PDY + py) * PDP + px] = v;
         }
         // filter slice as fp32, [co][tap][ci (4)]
         for (int e = tid; e < COC * KK * 4; e += 256) {
@@ -534,11 +538,12 @@ k_conv_bwd_data_thin_s2(View din, View dout, View isign, int scale_out, float in
         __syncthreads();
         for (int c = 0; c < COC; ++c) {
             if (c0 + c >= Cout) break;
-            float dv[NQ][NQ];
+            // neighbouring cells share all but one column of their deltas, and every weight
+            float dv[NQ][NQ + NCX - 1];
 #pragma unroll
             for (int y = 0; y < NQ; ++y)
 #pragma unroll
-                for (int x = 0; x < NQ; ++x) dv[y][x] = dzl[(c * PD + cy + y) * PDP + cx + x];
+                for (int x = 0; x < NQ + NCX - 1; ++x) dv[y][x] = dzl[(c * PDY + cy + y) * PDP + cx + x];
             const float4* wc = (const float4*)(wl + c * KK * 4);
 #pragma unroll
             for (int ky = 0; ky < K; ++ky)
@@ -547,28 +552,33 @@ k_conv_bwd_data_thin_s2(View din, View dout, View isign, int scale_out, float in
                     const int a = (ky + P) & 1, b = (kx + P) & 1;
                     const int dy = (a + P - ky) / 2 - QLO, dx = (b + P - kx) / 2 - QLO;     // compile-time after unrolling
                     const float4 wv = wc[ky * K + kx];
-                    const float d = dv[dy][dx];
-                    acc[a][b][0] = fmaf(wv.x, d, acc[a][b][0]);
-                    if (CI > 1) acc[a][b][1] = fmaf(wv.y, d, acc[a][b][1]);
-                    if (CI > 2) acc[a][b][2] = fmaf(wv.z, d, acc[a][b][2]);
-                    if (CI > 3) acc[a][b][3] = fmaf(wv.w, d, acc[a][b][3]);
+#pragma unroll
+                    for (int u = 0; u < NCX; ++u) {
+                        const float d = dv[dy][dx + u];
+                        acc[u][a][b][0] = fmaf(wv.x, d, acc[u][a][b][0]);
+                        if (CI > 1) acc[u][a][b][1] = fmaf(wv.y, d, acc[u][a][b][1]);
+                        if (CI > 2) acc[u][a][b][2] = fmaf(wv.z, d, acc[u][a][b][2]);
+                        if (CI > 3) acc[u][a][b][3] = fmaf(wv.w, d, acc[u][a][b][3]);
+                    }
                 }
         }
     }
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int u = 0; u < NCX; ++u)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int iy = 2 * (J0 + cy) + a, ix = 2 * (I0 + cx) + b;
-            if (iy < rt.y0[ti] || iy > rt.y1[ti] || ix < rt.x0[tj] || ix > rt.x1[tj]) continue;
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int c = 0; c < CI; ++c)
-                if (c < Cin) {
-                    float v = acc[a][b][c];
-                    if (scale_out) v = scaled_delta<T>(v, sign_bit(isign, stack, ti, tj, n, c, iy, ix), in_slope);
-                    st(at<T>(dout, stack, ti, tj, n, c, iy, ix), v);
-                }
-        }
+            for (int b = 0; b < 2; ++b) {
+                const int iy = 2 * (J0 + cy) + a, ix = 2 * (I0 + cx + u) + b;
+                if (iy < rt.y0[ti] || iy > rt.y1[ti] || ix < rt.x0[tj] || ix > rt.x1[tj]) continue;
+#pragma unroll
+                for (int c = 0; c < CI; ++c)
+                    if (c < Cin) {
+                        float v = acc[u][a][b][c];
+                        if (scale_out) v = scaled_delta<T>(v, sign_bit(isign, stack, ti, tj, n, c, iy, ix), in_slope);
+                        st(at<T>(dout, stack, ti, tj, n, c, iy, ix), v);
+                    }
+            }
 }
 
 bool thin_bwd_data_strided_eligible(const ConvArgs& a) { return a.S == 2 && a.Cin <= 4 && !a.pooled && a.K >= 3; }
@@ -579,7 +589,8 @@ void thin_conv_bwd_data_strided(const ConvArgs& a, const RectTab& ext, hipStream
     int mw = 0, mh = 0;                                // cells per dimension of the largest rectangle
     for (int t = 0; t < a.M; ++t) mw = std::max(mw, (a.rect.x1[t] >> 1) - (a.rect.x0[t] >> 1) + 1);
     for (int t = 0; t < a.N; ++t) mh = std::max(mh, (a.rect.y1[t] >> 1) - (a.rect.y0[t] >> 1) + 1);
-    const int tiles_x = (mw + kThinS2Cells - 1) / kThinS2Cells, tiles_y = (mh + kThinS2Cells - 1) / kThinS2Cells;
+    const int tcx = kThinS2PerThread * kThinS2Cells;
+    const int tiles_x = (mw + tcx - 1) / tcx, tiles_y = (mh + kThinS2Cells - 1) / kThinS2Cells;
     dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
     g_kernel_label = "k_conv_bwd_data_thin_s2";
 #define FTP_S2(T, KK, CI) hipLaunchKernelGGL((k_conv_bwd_data_thin_s2<T, KK, CI>), grid, block, 0, s, a.din, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, ext, (const T*)a.w, a.Cin, a.Cout, a.M, a.batch, tiles_x)
