@@ -358,16 +358,19 @@ template <typename T, bool POOL, int CI>
 __global__ void __launch_bounds__(256, 6)              // (six wavefronts a SIMD: the kernel waits for LDS and memory, not for registers)
 k_conv_bwd_data_thin4(View din, View mask, View dout, View isign, int scale_out, float in_slope, RectTab rt,
                       const T* __restrict__ w, int Cin, int Cout, int Hc, int Wc, int M, int batch,
-                      int ntx, int nty, int tiles_x)
+                      int ntx, int nty, int tiles_x, int tiles, int images)
 {
     constexpr int COC = kThin4Coc, CH = kThin4Patch, WR = (9 * CI + 3) & ~3;        // (filter rows on 16-byte boundaries: read four weights at a time)
     __shared__ __attribute__((aligned(16))) float dz[COC * CH];
     __shared__ __attribute__((aligned(16))) float wl[COC * WR];
     const int tid = threadIdx.x;
-    const int stack = blockIdx.z / batch, n = blockIdx.z % batch;
+    // 1-D grid in XCD order: the tiles of one (stack, image), whose patches overlap, run on one XCD and share its L2
+    int image, tile;
+    if (!xcd_order(images, tiles, image, tile)) return;
+    const int stack = image / batch, n = image % batch;
     const int ti = stack / M, tj = stack % M;
     const int TW = 4 * ntx, TH = nty, PP = (TW + 2 + 3) & ~3;
-    const int bx = blockIdx.x % tiles_x, by = blockIdx.x / tiles_x;
+    const int bx = tile % tiles_x, by = tile / tiles_x;
     const int ox0 = rt.x0[tj] + bx * TW, oy0 = rt.y0[ti] + by * TH;
     if (ox0 > rt.x1[tj] || oy0 > rt.y1[ti]) return;
     const int tx = tid % ntx, ty = tid / ntx;
@@ -619,9 +622,10 @@ void thin_conv_bwd_data(const ConvArgs& a, hipStream_t s)
         const int nty = (mh + tiles_y - 1) / tiles_y;
         const int PP = (4 * ntx + 2 + 3) & ~3;
         if ((nty + 2) * PP <= kThin4Patch) {
-            dim3 grid(tiles_x * tiles_y, 1, a.N * a.M * a.batch), block(256);
+            const int tiles = tiles_x * tiles_y, images = a.N * a.M * a.batch;
+            dim3 grid(xcd_grid(images, tiles)), block(256);
             g_kernel_label = "k_conv_bwd_data_thin4";
-#define FTP_T4(T, PL, CI) hipLaunchKernelGGL((k_conv_bwd_data_thin4<T, PL, CI>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, (const T*)a.w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch, ntx, nty, tiles_x)
+#define FTP_T4(T, PL, CI) hipLaunchKernelGGL((k_conv_bwd_data_thin4<T, PL, CI>), grid, block, 0, s, a.din, a.mask, a.dout, a.isign, a.scale_out, a.in_slope, a.rect, (const T*)a.w, a.Cin, a.Cout, a.Hc, a.Wc, a.M, a.batch, ntx, nty, tiles_x, tiles, images)
 #define FTP_T4C(T, PL) do { if (a.Cin <= 3) FTP_T4(T, PL, 3); else FTP_T4(T, PL, 4); } while (0)
             if (a.bf16) { if (a.pooled) FTP_T4C(bf16_t, true); else FTP_T4C(bf16_t, false); }
             else        { if (a.pooled) FTP_T4C(float, true); else FTP_T4C(float, false); }
